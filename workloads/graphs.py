@@ -1,0 +1,215 @@
+"""Subgraph descriptors for the synthetic memory-intensive workloads.
+
+A descriptor is *data*: named tensors, an ordered list of ops (opcode, operand
+names, attributes) and the tensors the subgraph hands back.  It carries no
+arithmetic; the CPU oracle interprets it one op at a time in float64 and the
+GPU binding replays it through the C ABI.  It plays the role of the paper's
+"fusion pattern" P_i = (V_i, E_i), a subgraph of memory-intensive ops
+(Section 5.1), which is the input of the code generator (Section 4).
+
+Shape conventions
+-----------------
+* Binary ops broadcast numpy-style: ranks are right-aligned and a dimension of
+  extent 1 stretches.
+* Reductions keep the reduced axis with extent 1.
+* Every op result is a float32 tensor unless the op is ``convert``.
+* ``outputs`` lists (tensor name, storage dtype).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Sequence, Tuple
+
+DTYPES = ("f32", "f16", "bf16", "i32")
+DTYPE_BYTES = {"f32": 4, "f16": 2, "bf16": 2, "i32": 4}
+
+# opcode -> number of tensor operands
+OPCODES = {
+    "add": 2, "sub": 2, "mul": 2, "div": 2, "max": 2,
+    "scale": 1, "add_scalar": 1,
+    "square": 1, "exp": 1, "rsqrt": 1, "tanh": 1,
+    "gelu_tanh": 1, "gelu_tanh_grad": 1,
+    "broadcast": 1,
+    "reduce_sum": 1, "reduce_max": 1, "reduce_mean": 1,
+    "transpose": 1, "convert": 1,
+}
+
+
+@dataclass(frozen=True)
+class TensorSpec:
+    name: str
+    dtype: str
+    dims: Tuple[int, ...]
+
+
+@dataclass(frozen=True)
+class OpSpec:
+    out: str
+    opcode: str
+    inputs: Tuple[str, ...]
+    attr: Dict = field(default_factory=dict)
+
+
+@dataclass
+class GraphSpec:
+    name: str
+    inputs: List[TensorSpec]
+    ops: List[OpSpec]
+    outputs: List[Tuple[str, str]]
+
+    def input_names(self) -> List[str]:
+        return [t.name for t in self.inputs]
+
+
+def _op(out: str, opcode: str, *inputs: str, **attr) -> OpSpec:
+    assert opcode in OPCODES and len(inputs) == OPCODES[opcode], (opcode, inputs)
+    return OpSpec(out, opcode, tuple(inputs), dict(attr))
+
+
+def _softmax_ops(src: str, axis: int, prefix: str = "") -> List[OpSpec]:
+    p = prefix
+    return [
+        _op(p + "m", "reduce_max", src, axis=axis),
+        _op(p + "s", "sub", src, p + "m"),
+        _op(p + "e", "exp", p + "s"),
+        _op(p + "z", "reduce_sum", p + "e", axis=axis),
+        _op(p + "y", "div", p + "e", p + "z"),
+    ]
+
+
+def softmax_graph(rows: int, cols: int, dtype: str = "f32") -> GraphSpec:
+    """Row softmax: row max, subtract, exp, row sum, divide (5 ops)."""
+    return GraphSpec(
+        name=f"softmax_{dtype}_{rows}x{cols}",
+        inputs=[TensorSpec("x", dtype, (rows, cols))],
+        ops=_softmax_ops("x", 1),
+        outputs=[("y", dtype)],
+    )
+
+
+def add_bias_layernorm_graph(rows: int, cols: int, eps: float = 1e-5,
+                             in_dtype: str = "f32", out_dtype: str = "bf16") -> GraphSpec:
+    """Residual add + bias + LayerNorm (12 ops, the last one the storage convert).
+
+    Population variance, two-pass (mean of squared deviations), eps inside the
+    square root; two row reductions and one expensive op on the [rows,1] tensor.
+    """
+    ops = [
+        _op("h0", "add", "x", "res"),
+        _op("h", "add", "h0", "bias"),
+        _op("mu", "reduce_mean", "h", axis=1),
+        _op("c", "sub", "h", "mu"),
+        _op("q", "square", "c"),
+        _op("v", "reduce_mean", "q", axis=1),
+        _op("ve", "add_scalar", "v", value=float(eps)),
+        _op("r", "rsqrt", "ve"),
+        _op("n", "mul", "c", "r"),
+        _op("g", "mul", "n", "gamma"),
+        _op("o", "add", "g", "beta"),
+        _op("out", "convert", "o", dtype=out_dtype),
+    ]
+    return GraphSpec(
+        name=f"add_bias_layernorm_{in_dtype}_{rows}x{cols}",
+        inputs=[
+            TensorSpec("x", in_dtype, (rows, cols)),
+            TensorSpec("res", in_dtype, (rows, cols)),
+            TensorSpec("bias", in_dtype, (cols,)),
+            TensorSpec("gamma", in_dtype, (cols,)),
+            TensorSpec("beta", in_dtype, (cols,)),
+        ],
+        ops=ops,
+        outputs=[("out", out_dtype)],
+    )
+
+
+def attention_scores_graph(batch: int, heads: int, q_len: int, k_len: int,
+                           scale: float = 0.125, dtype: str = "f16") -> GraphSpec:
+    """Scale, additive key mask [batch,1,1,k_len], softmax over the last axis (7 ops)."""
+    ops = [
+        _op("t", "scale", "scores", value=float(scale)),
+        _op("a", "add", "t", "mask"),
+    ] + _softmax_ops("a", 3)
+    return GraphSpec(
+        name=f"attention_scores_{dtype}_{batch}x{heads}x{q_len}x{k_len}",
+        inputs=[
+            TensorSpec("scores", dtype, (batch, heads, q_len, k_len)),
+            TensorSpec("mask", dtype, (batch, 1, 1, k_len)),
+        ],
+        ops=ops,
+        outputs=[("y", dtype)],
+    )
+
+
+def bias_gelu_dbias_graph(rows: int, cols: int, dtype: str = "bf16") -> GraphSpec:
+    """Bias + tanh-GELU forward packed with the bias-gradient column sum (5 ops)."""
+    ops = [
+        _op("z", "add", "x", "bias"),
+        _op("y", "gelu_tanh", "z"),
+        _op("d", "gelu_tanh_grad", "z"),
+        _op("p", "mul", "grad", "d"),
+        _op("dbias", "reduce_sum", "p", axis=0),
+    ]
+    return GraphSpec(
+        name=f"bias_gelu_dbias_{dtype}_{rows}x{cols}",
+        inputs=[
+            TensorSpec("x", dtype, (rows, cols)),
+            TensorSpec("bias", dtype, (cols,)),
+            TensorSpec("grad", dtype, (rows, cols)),
+        ],
+        ops=ops,
+        outputs=[("y", dtype), ("dbias", "f32")],
+    )
+
+
+def transpose_chain_graph(batch: int, seq: int, heads: int, dim: int,
+                          eps: float = 1e-6, dtype: str = "f32") -> GraphSpec:
+    """[B,S,H,D] -> [B,H,S,D], per-head scale, L2-normalise the last axis (7 ops)."""
+    ops = [
+        _op("t", "transpose", "x", perm=(0, 2, 1, 3)),
+        _op("u", "mul", "t", "scale"),
+        _op("q", "square", "u"),
+        _op("ss", "reduce_sum", "q", axis=3),
+        _op("e", "add_scalar", "ss", value=float(eps)),
+        _op("r", "rsqrt", "e"),
+        _op("out", "mul", "u", "r"),
+    ]
+    return GraphSpec(
+        name=f"transpose_chain_{dtype}_{batch}x{seq}x{heads}x{dim}",
+        inputs=[
+            TensorSpec("x", dtype, (batch, seq, heads, dim)),
+            TensorSpec("scale", dtype, (heads, 1, 1)),
+        ],
+        ops=ops,
+        outputs=[("out", dtype)],
+    )
+
+
+def transpose_graph(dims: Sequence[int], perm: Sequence[int], dtype: str = "f32") -> GraphSpec:
+    """A single transpose op (moves raw bits; used for the bit-exact checks)."""
+    return GraphSpec(
+        name=f"transpose_{dtype}_{'x'.join(map(str, dims))}_p{''.join(map(str, perm))}",
+        inputs=[TensorSpec("x", dtype, tuple(int(d) for d in dims))],
+        ops=[_op("t", "transpose", "x", perm=tuple(int(p) for p in perm))],
+        outputs=[("t", dtype)],
+    )
+
+
+def bias_gelu_graph(rows: int, cols: int, dtype: str = "bf16") -> GraphSpec:
+    """Bias + tanh-GELU only: a pure elementwise chain (thread composition)."""
+    return GraphSpec(
+        name=f"bias_gelu_{dtype}_{rows}x{cols}",
+        inputs=[TensorSpec("x", dtype, (rows, cols)), TensorSpec("bias", dtype, (cols,))],
+        ops=[_op("z", "add", "x", "bias"), _op("y", "gelu_tanh", "z")],
+        outputs=[("y", dtype)],
+    )
+
+
+# The five configurations the build is measured on, at their full sizes, and a
+# small sibling of each that still spans several tiles and a ragged tail.
+FULL_CONFIGS = {
+    "C1": lambda: softmax_graph(64, 128, "f32"),
+    "C2": lambda: add_bias_layernorm_graph(8192, 768),
+    "C3": lambda: attention_scores_graph(32, 12, 128, 128),
+    "C4": lambda: bias_gelu_dbias_graph(16384, 3072),
+    "C5": lambda: transpose_chain_graph(64, 512, 12, 64),
+}
