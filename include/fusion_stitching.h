@@ -1,0 +1,201 @@
+/*
+ * fusion_stitching.h -- C ABI of the MI355X (gfx950) stitched-subgraph library.
+ *
+ * The library executes one *fusion pattern* -- a subgraph of memory-intensive
+ * ops (element-wise, broadcast, reduction, transpose; paper Section 2.1 and
+ * Section 5.1, "fusion pattern P_i = (V_i, E_i)") -- either as one stitched GPU
+ * kernel in which intermediates stay on chip, or as the per-op baseline of one
+ * kernel per op.  The calls mirror the paper's code-generation problem
+ * statement (Section 4: a fusion pattern goes in, a kernel with a chosen
+ * schedule and launch dimension comes out, Section 4.2), with hand-written
+ * kernels selected by pattern matching instead of JIT emission.
+ *
+ * Conventions
+ *   - All handles are opaque and owned by the library; destroy with the
+ *     matching *_destroy.  Every pointer passed to fs_execute / fs_stream_copy
+ *     is DEVICE memory owned by the caller; every other pointer is HOST memory.
+ *   - No call throws or aborts.  Calls returning fs_status give FS_OK (0) or a
+ *     negative error; calls returning fs_tensor give an id >= 0 or a negative
+ *     error.  fs_last_error() gives the text of the calling thread's last error.
+ *   - Tensors are dense, row-major, rank 1..FS_MAX_RANK, fewer than 2^31 elements.
+ *   - Arithmetic is float32 whatever the storage dtype; conversion to a
+ *     16-bit storage dtype rounds to nearest-even at the final store.
+ */
+#ifndef FUSION_STITCHING_H
+#define FUSION_STITCHING_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FS_MAX_RANK 4
+
+typedef struct fs_graph fs_graph;
+typedef struct fs_plan fs_plan;
+typedef int32_t fs_status;
+typedef int32_t fs_tensor;
+
+enum fs_error {
+  FS_OK = 0,
+  FS_ERR_INVALID_ARG = -1,         /* null pointer, bad enum value, bad id, graph not finalized, ...  */
+  FS_ERR_SHAPE = -2,               /* operand shapes do not broadcast / bad axis / bad perm / too large */
+  FS_ERR_DTYPE = -3,               /* dtype not accepted by the op                                    */
+  FS_ERR_CYCLE = -4,               /* an operand id does not precede the op (graphs are built in
+                                      topological order, so a cycle can only show up this way;
+                                      Section 5.2 discards cyclic patterns)                            */
+  FS_ERR_UNSUPPORTED_PATTERN = -5, /* a stitched scheme was asked for and no stitched kernel matches
+                                      (Section 5.2: only patterns the code generator can process)      */
+  FS_ERR_LOCALITY = -6,            /* forced scheme / shape breaks the reuse-scope locality rule
+                                      (Section 4.2: schedules violating data locality are discarded)   */
+  FS_ERR_WORKSPACE = -7,           /* workspace null or smaller than fs_plan_info.workspace_bytes      */
+  FS_ERR_ALIGN = -8,               /* a device pointer is not 16-byte aligned                          */
+  FS_ERR_HIP = -9                  /* a HIP call failed; text carries hipGetErrorString                */
+};
+
+enum fs_dtype { FS_F32 = 0, FS_F16 = 1, FS_BF16 = 2, FS_I32 = 3 };
+
+/* Memory-intensive op vocabulary (Section 4: light element-wise, expensive
+ * element-wise, reduction; Section 3.1: broadcast; plus transpose and convert).
+ * Binary ops broadcast numpy-style (ranks right-aligned, extent 1 stretches).
+ * Reductions keep the reduced axis with extent 1.  Results are FS_F32 except
+ * FS_TRANSPOSE (keeps its operand's dtype, moves raw bits) and FS_CONVERT.     */
+enum fs_opcode {
+  FS_ADD = 0, FS_SUB = 1, FS_MUL = 2, FS_DIV = 3, FS_MAX = 4, /* 2 operands, attr: none            */
+  FS_SCALE = 5,          /* x * value                      attr: fs_attr_scalar                    */
+  FS_ADD_SCALAR = 6,     /* x + value                      attr: fs_attr_scalar                    */
+  FS_SQUARE = 7, FS_EXP = 8, FS_RSQRT = 9, FS_TANH = 10,      /* 1 operand, attr: none             */
+  FS_GELU_TANH = 11,     /* z/2 (1 + tanh(sqrt(2/pi)(z + 0.044715 z^3)))                           */
+  FS_GELU_TANH_GRAD = 12,/* d/dz of FS_GELU_TANH                                                   */
+  FS_BROADCAST = 13,     /* stretch to attr dims           attr: fs_attr_dims                      */
+  FS_REDUCE_SUM = 14, FS_REDUCE_MAX = 15, FS_REDUCE_MEAN = 16, /* attr: fs_attr_axis               */
+  FS_TRANSPOSE = 17,     /* out.dims[i] = in.dims[perm[i]] attr: fs_attr_perm                      */
+  FS_CONVERT = 18,       /* round to dtype                 attr: fs_attr_dtype                     */
+  FS_OPCODE_COUNT = 19
+};
+
+typedef struct fs_attr_scalar { double value; } fs_attr_scalar;
+typedef struct fs_attr_axis { int32_t axis; } fs_attr_axis;               /* 0 <= axis < rank        */
+typedef struct fs_attr_perm { int32_t perm[FS_MAX_RANK]; } fs_attr_perm;   /* first `rank` entries    */
+typedef struct fs_attr_dims { int32_t rank; int64_t dims[FS_MAX_RANK]; } fs_attr_dims;
+typedef struct fs_attr_dtype { int32_t dtype; } fs_attr_dtype;
+
+/* Composition schemes (Section 4.1).  LOCAL = kernel packing + thread composition
+ * (values stay in the lane that made them); WAVE = warp composition on a 64-wide
+ * wavefront (cross-lane DPP / permute); LDS = block composition (reduced values
+ * and tiles go through LDS); GLOBAL = one hand-off through device memory between
+ * workgroups, which the paper leaves out (Section 4.1, last paragraph) and which
+ * the column-reduction pattern needs; UNFUSED = one kernel per op; AUTO = the
+ * cost model chooses among the stitched candidates and falls back to UNFUSED
+ * when no stitched kernel matches.                                              */
+enum fs_scheme {
+  FS_SCHEME_AUTO = 0, FS_SCHEME_UNFUSED = 1, FS_SCHEME_LOCAL = 2,
+  FS_SCHEME_WAVE = 3, FS_SCHEME_LDS = 4, FS_SCHEME_GLOBAL = 5
+};
+
+/* Optional constraints on the launch shape; a zero / negative field means "any".
+ * The cost model picks the cheapest candidate that satisfies all given fields;
+ * if none does, fs_plan_create returns FS_ERR_LOCALITY.                          */
+typedef struct fs_plan_opts {
+  int32_t candidate;      /* >= 0: take exactly this entry of the candidate list; -1: choose   */
+  int32_t block_threads;  /* threads per workgroup                                             */
+  int32_t lanes_per_row;  /* lanes that share one reduction row (WAVE) / threads per row (LDS) */
+  int32_t vecs_per_lane;  /* 128-bit vectors each lane keeps in registers                      */
+} fs_plan_opts;
+
+/* What a plan will do (Section 4.3: latency is estimated from launch dimension,
+ * shared-memory use and register use; here registers and LDS are the compiled
+ * kernel's own figures).                                                         */
+typedef struct fs_plan_info {
+  int32_t scheme;            /* enum fs_scheme actually used                                   */
+  int32_t n_kernels;         /* launches per fs_execute                                        */
+  int32_t block[3];          /* workgroup shape of the dominant kernel                         */
+  int32_t grid[3];           /* workgroups of the dominant kernel                              */
+  int32_t lanes_per_row;
+  int32_t vecs_per_lane;
+  int32_t rows_per_block;
+  int32_t lds_bytes;         /* LDS per workgroup                                              */
+  int32_t vgprs;             /* vector registers per lane (compiled figure, or an estimate
+                                when no device is present)                                     */
+  int32_t waves_per_simd;    /* occupancy the model derived from vgprs / lds / block shape     */
+  int32_t n_candidates;      /* size of the enumerated candidate list                          */
+  int32_t candidate;         /* index of the chosen one                                        */
+  int64_t workspace_bytes;   /* device scratch fs_execute needs (may be 0)                     */
+  int64_t bytes_min;         /* each subgraph input read once + each output written once       */
+  int64_t bytes_moved_model; /* bytes the plan's kernels move according to the model           */
+  double predicted_us;       /* cost-model estimate for one fs_execute                         */
+  char pattern[32];          /* matched stitched pattern, or "unfused"                         */
+  char kernel[64];           /* name of the dominant kernel variant                            */
+} fs_plan_info;
+
+/* ---- graph descriptor (Section 5.1: a fusion pattern is a subgraph) ---------- */
+
+/* New empty graph.  *out receives the handle.  Errors: FS_ERR_INVALID_ARG.      */
+fs_status fs_graph_create(fs_graph **out);
+/* Frees the graph (null is accepted).  Plans made from it stay valid.           */
+void fs_graph_destroy(fs_graph *g);
+/* Declares a subgraph input of `rank` extents dims[0..rank) (host array, copied).
+ * fs_execute's `inputs` follow the order of these calls.
+ * Errors: FS_ERR_INVALID_ARG (null, bad dtype, finalized graph), FS_ERR_SHAPE.   */
+fs_tensor fs_graph_input(fs_graph *g, int32_t dtype, int32_t rank, const int64_t *dims);
+/* Appends op `opcode` over operands in[0..n_in) (host array of earlier ids) with
+ * the attribute struct named beside the opcode (host, copied; null when the op
+ * has none).  Returns the id of its result tensor.
+ * Errors: FS_ERR_INVALID_ARG, FS_ERR_CYCLE, FS_ERR_SHAPE, FS_ERR_DTYPE.          */
+fs_tensor fs_graph_op(fs_graph *g, int32_t opcode, int32_t n_in, const fs_tensor *in,
+                      const void *attr, size_t attr_bytes);
+/* Marks tensor t as a subgraph output stored as `store_as`.  fs_execute's
+ * `outputs` follow the order of these calls.  A tensor can be marked once.
+ * Errors: FS_ERR_INVALID_ARG, FS_ERR_DTYPE (I32 tensors only store as I32).      */
+fs_status fs_graph_output(fs_graph *g, fs_tensor t, int32_t store_as);
+/* Freezes the graph: at least one output, every op reaches an output.
+ * Errors: FS_ERR_INVALID_ARG.                                                    */
+fs_status fs_graph_finalize(fs_graph *g);
+
+/* ---- plan (Section 4.2: enumerate schedules and launch dimensions, discard
+ *      those that break locality, keep the cheapest by the evaluator) ----------- */
+
+/* Builds a plan for a finalized graph.  `opts` may be null.  *out receives the
+ * handle.  Needs no GPU (register figures fall back to estimates without one).
+ * Errors: FS_ERR_INVALID_ARG, FS_ERR_UNSUPPORTED_PATTERN, FS_ERR_LOCALITY.        */
+fs_status fs_plan_create(const fs_graph *g, int32_t scheme, const fs_plan_opts *opts, fs_plan **out);
+void fs_plan_destroy(fs_plan *p);
+/* Fills *out (host) with the chosen candidate's figures.                         */
+fs_status fs_plan_query(const fs_plan *p, fs_plan_info *out);
+/* Fills *out with the figures of entry `index` (0 <= index < n_candidates) of the
+ * list the plan was chosen from, in enumeration order.                           */
+fs_status fs_plan_candidate(const fs_plan *p, int32_t index, fs_plan_info *out);
+
+/* ---- execution (the run-time hot path) --------------------------------------- */
+
+/* Enqueues the plan's kernel(s) on `hip_stream` (a hipStream_t; null = the
+ * default stream) and returns without waiting.  inputs[i] / outputs[j] are
+ * DEVICE pointers in declaration order, each 16-byte aligned and sized for its
+ * tensor; inputs are never written.  `workspace` is DEVICE scratch of at least
+ * fs_plan_info.workspace_bytes (may be null when that is 0); the library leaves
+ * it reusable for the next call of the same plan on the same stream (its
+ * arrival counters are reset by the kernel that used them) but its first use
+ * must see zeros in the first 256 bytes * (number of counters); the simplest
+ * rule: zero-fill it once after allocating.  Allocates nothing, never
+ * synchronizes.  Two calls that share a workspace must be ordered on one stream.
+ * Errors: FS_ERR_INVALID_ARG, FS_ERR_WORKSPACE, FS_ERR_ALIGN, FS_ERR_HIP.         */
+fs_status fs_execute(const fs_plan *p, const void *const *inputs, void *const *outputs,
+                     void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Plain streaming copy of `bytes` (multiple of 16) from src to dst, both DEVICE
+ * and 16-byte aligned: the measured HBM ceiling every result is reported beside
+ * (Section 2.3 names off-chip traffic as the dominant cost).                     */
+fs_status fs_stream_copy(void *dst, const void *src, size_t bytes, void *hip_stream);
+
+/* Text of the calling thread's most recent error ("" if none); valid until the
+ * thread's next library call.                                                    */
+const char *fs_last_error(void);
+/* Library version string (static storage).                                       */
+const char *fs_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FUSION_STITCHING_H */

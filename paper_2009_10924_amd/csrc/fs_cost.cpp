@@ -1,0 +1,59 @@
+#include "fs_cost.hpp"
+
+#include <algorithm>
+#include <cmath>
+
+namespace fs {
+
+const DeviceModel& device() {
+  static const DeviceModel d;
+  return d;
+}
+
+CostResult evaluate(const KernelCost& k, int32_t vgprs_compiled) {
+  const DeviceModel& d = device();
+  CostResult r;
+  r.vgprs = vgprs_compiled > 0 ? vgprs_compiled : k.vgpr_estimate;
+
+  // Occupancy from registers, LDS and workgroup shape (Section 4.3).
+  const uint32_t vg = std::max<uint32_t>(d.vgpr_granule, (r.vgprs + d.vgpr_granule - 1) / d.vgpr_granule * d.vgpr_granule);
+  uint32_t occ = std::min<uint32_t>(d.max_waves_per_simd, d.vgpr_per_simd_lane / vg);
+  const uint32_t wpb = std::max(1, k.waves_per_block);
+  uint32_t blocks_per_cu = occ * d.simd_per_cu / wpb;
+  if (k.lds_bytes_per_block > 0) blocks_per_cu = std::min<uint32_t>(blocks_per_cu, d.lds_per_cu / (uint32_t)k.lds_bytes_per_block);
+  blocks_per_cu = std::max<uint32_t>(1, blocks_per_cu);
+  const double waves_per_cu = std::min<double>(occ * d.simd_per_cu, (double)blocks_per_cu * wpb);
+  r.waves_per_simd = (int32_t)std::max(1.0, std::floor(waves_per_cu / d.simd_per_cu));
+
+  // N_wave: rounds of resident wavefronts.
+  const double capacity = waves_per_cu * d.n_cu;
+  const double resident = std::min(k.waves, capacity);
+  const double rounds = std::max(1.0, std::ceil(k.waves / capacity));
+
+  // L_warp: one trip of a wave = dependent memory phases + its instruction stream while
+  // sharing the SIMD with the other resident waves.
+  const double elems_per_wave_trip = k.elems / std::max(1.0, k.waves * k.rows_per_wave_loop);
+  const double wave_instr = elems_per_wave_trip / 64.0 / std::max(0.05, k.lane_utilisation);
+  const double cycles = wave_instr * (k.valu_per_elem * d.cycles_valu + k.trans_per_elem * d.cycles_trans) +
+                        k.xlane_steps * d.cycles_xlane;
+  const double simd_share = std::max(1.0, resident / (d.n_cu * d.simd_per_cu));
+  const double t_issue = cycles * simd_share / d.clock_hz;
+  const double t_trip = k.dep_phases * d.mem_latency_s + k.barriers * d.barrier_s + t_issue;
+  const double t_latency = rounds * k.rows_per_wave_loop * t_trip;
+
+  // Streaming floors: HBM (with Little's law on the bytes in flight), caches, LDS.
+  const double in_flight = resident * 64.0 * k.bytes_in_flight_per_lane * k.lane_utilisation;
+  double bw = std::min(d.hbm_peak_Bps * d.stream_fraction, in_flight / d.mem_latency_s);
+  if (k.store_run_bytes > 0 && k.store_run_bytes < 512) bw *= 0.9;   // short store runs cost a little write efficiency
+  const double t_hbm = k.hbm_bytes / bw * (rounds * capacity >= k.waves && k.waves > capacity ? rounds * capacity / k.waves : 1.0);
+  const double t_cache = k.cache_bytes / d.l2_Bps;
+  const double t_lds = k.lds_traffic_bytes / d.lds_Bps;
+  const double t_alu = k.elems / std::max(0.05, k.lane_utilisation) / 64.0 *
+                       (k.valu_per_elem * d.cycles_valu + k.trans_per_elem * d.cycles_trans) /
+                       (d.n_cu * d.simd_per_cu) / d.clock_hz;
+
+  r.seconds = d.launch_s + std::max({t_latency, t_hbm + t_cache + t_lds, t_alu}) + k.serial_tail_s;
+  return r;
+}
+
+}  // namespace fs

@@ -1,0 +1,105 @@
+// Internal host-side structures shared by the graph, matcher, cost model and executor.
+#pragma once
+#include <cstdarg>
+#include <cstdint>
+#include <cstdio>
+#include <string>
+#include <vector>
+
+#include "../../include/fusion_stitching.h"
+#include "fs_cost.hpp"
+#include "kernels/launch.hpp"
+
+namespace fs {
+
+struct Tensor {
+  int32_t dtype = FS_F32;
+  int32_t rank = 0;
+  int64_t dims[FS_MAX_RANK] = {1, 1, 1, 1};
+  int32_t producer = -1;      // op index, -1 for a graph input
+  int32_t input_slot = -1;    // position in fs_execute's inputs, -1 if not an input
+  int32_t output_slot = -1;   // position in fs_execute's outputs, -1 if not an output
+  int32_t store_as = FS_F32;  // storage dtype when it is an output
+  std::vector<int32_t> consumers;
+  int64_t numel() const {
+    int64_t n = 1;
+    for (int i = 0; i < rank; ++i) n *= dims[i];
+    return n;
+  }
+};
+
+struct Op {
+  int32_t opcode = 0;
+  int32_t n_in = 0;
+  int32_t in[2] = {-1, -1};
+  int32_t out = -1;
+  double scalar = 0.0;                     // FS_SCALE / FS_ADD_SCALAR
+  int32_t axis = 0;                        // reductions
+  int32_t perm[FS_MAX_RANK] = {0, 1, 2, 3};
+  int32_t to_dtype = FS_F32;               // FS_CONVERT
+};
+
+int dtype_bytes(int32_t dt);
+const char* dtype_name(int32_t dt);
+const char* opcode_name(int32_t op);
+const char* scheme_name(int32_t s);
+
+// status + thread-local message
+fs_status fail(fs_status code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+
+}  // namespace fs
+
+struct fs_graph {
+  std::vector<fs::Tensor> tensors;
+  std::vector<fs::Op> ops;
+  std::vector<int32_t> inputs;   // tensor ids in declaration order
+  std::vector<int32_t> outputs;  // tensor ids in declaration order
+  bool finalized = false;
+};
+
+namespace fs {
+
+// ---- plan ------------------------------------------------------------------
+
+// One kernel launch of a plan.  `args` is a POD blob the launcher understands;
+// pointer fields inside it are filled at execute time from `bind`.
+enum BufKind : int32_t { BUF_NONE = 0, BUF_INPUT = 1, BUF_OUTPUT = 2, BUF_WORKSPACE = 3 };
+struct BufRef {
+  int32_t kind = BUF_NONE;
+  int32_t slot = 0;     // input/output slot
+  int64_t offset = 0;   // byte offset (workspace)
+};
+
+struct Launch {
+  int32_t kernel = 0;            // KernelId
+  KernelArgs args;               // shapes, flags; pointers patched per execute
+  BufRef ptr[kMaxPtrs];          // which buffer each pointer slot takes
+  LaunchShape shape;
+};
+
+struct Candidate {
+  fs_plan_info info;
+  std::vector<Launch> launches;
+  KernelCost cost;               // description of the (single) stitched kernel; unused for unfused plans
+};
+
+}  // namespace fs
+
+struct fs_plan {
+  std::vector<fs::Candidate> candidates;
+  int32_t chosen = 0;
+  int32_t n_inputs = 0, n_outputs = 0;
+  std::vector<int64_t> input_bytes, output_bytes;
+};
+
+namespace fs {
+
+// matcher + candidate enumeration (fs_match.cpp / fs_cost.cpp)
+fs_status build_unfused(const fs_graph& g, Candidate* out);
+// Appends every stitched candidate that fits `g`; returns the pattern name or "" if none matches.
+std::string build_stitched(const fs_graph& g, std::vector<Candidate>* out);
+int64_t graph_bytes_min(const fs_graph& g);
+void predict(Candidate* c);  // fills info.predicted_us, waves_per_simd, vgprs, lds
+
+}  // namespace fs

@@ -1,0 +1,187 @@
+// Plan creation (choose scheme + launch shape by the evaluator) and execution
+// (patch device pointers, enqueue the launches).  fs_execute is the only place where
+// control crosses from host to device.
+#include <algorithm>
+#include <cstring>
+
+#include "fs_internal.hpp"
+
+namespace fs {
+
+void predict(Candidate* c) {
+  if (c->info.scheme == FS_SCHEME_UNFUSED) {
+    // per-op plan: every launch streams its own operands and results
+    const DeviceModel& d = device();
+    double t = 0;
+    for (const Launch& l : c->launches) {
+      (void)l;
+      t += d.launch_s;
+    }
+    t += (double)c->info.bytes_moved_model / (d.hbm_peak_Bps * d.stream_fraction);
+    c->info.predicted_us = t * 1e6;
+    c->info.waves_per_simd = (int32_t)d.max_waves_per_simd;
+    c->info.vgprs = 0;
+    return;
+  }
+  const Launch& l = c->launches.front();
+  const KernelResources res = kernel_resources(l.kernel, l.args);
+  const CostResult r = evaluate(c->cost, res.from_device ? res.vgprs : 0);
+  c->info.predicted_us = r.seconds * 1e6;
+  c->info.waves_per_simd = r.waves_per_simd;
+  c->info.vgprs = r.vgprs;
+  if (res.from_device && res.static_lds > c->info.lds_bytes) c->info.lds_bytes = res.static_lds;
+}
+
+static bool satisfies(const fs_plan_info& i, const fs_plan_opts& o) {
+  if (o.block_threads > 0 && i.block[0] != o.block_threads) return false;
+  if (o.lanes_per_row > 0 && i.lanes_per_row != o.lanes_per_row) return false;
+  if (o.vecs_per_lane > 0 && i.vecs_per_lane != o.vecs_per_lane) return false;
+  return true;
+}
+
+}  // namespace fs
+
+using namespace fs;
+
+extern "C" {
+
+fs_status fs_plan_create(const fs_graph* g, int32_t scheme, const fs_plan_opts* opts, fs_plan** out) {
+  clear_error();
+  if (!g || !out) return fail(FS_ERR_INVALID_ARG, "fs_plan_create: null argument");
+  if (!g->finalized) return fail(FS_ERR_INVALID_ARG, "fs_plan_create: graph is not finalized");
+  if (scheme < FS_SCHEME_AUTO || scheme > FS_SCHEME_GLOBAL) return fail(FS_ERR_INVALID_ARG, "fs_plan_create: bad scheme %d", scheme);
+  fs_plan_opts o = {-1, 0, 0, 0};
+  if (opts) o = *opts;
+
+  std::vector<Candidate> all;
+  std::string pattern;
+  if (scheme != FS_SCHEME_UNFUSED) {
+    pattern = build_stitched(*g, &all);
+    for (Candidate& c : all) predict(&c);
+  }
+  if (scheme == FS_SCHEME_UNFUSED || (scheme == FS_SCHEME_AUTO && all.empty())) {
+    Candidate u;
+    const fs_status s = build_unfused(*g, &u);
+    if (s != FS_OK) return s;
+    predict(&u);
+    all.clear();
+    all.push_back(u);
+  } else if (all.empty()) {
+    if (pattern.empty())
+      return fail(FS_ERR_UNSUPPORTED_PATTERN, "fs_plan_create: no stitched kernel matches this graph (scheme %s)", scheme_name(scheme));
+    return fail(FS_ERR_UNSUPPORTED_PATTERN,
+                "fs_plan_create: pattern '%s' recognised, but its shapes / dtypes fit no stitched kernel", pattern.c_str());
+  }
+
+  // keep the candidates of the requested scheme; AUTO keeps all of them
+  std::vector<Candidate> kept;
+  for (const Candidate& c : all)
+    if (scheme == FS_SCHEME_AUTO || scheme == FS_SCHEME_UNFUSED || c.info.scheme == scheme) kept.push_back(c);
+  if (kept.empty())
+    return fail(FS_ERR_LOCALITY,
+                "fs_plan_create: pattern '%s' has no %s schedule that keeps its reduction rows inside the reuse scope",
+                pattern.c_str(), scheme_name(scheme));
+
+  int best = -1;
+  if (o.candidate >= 0) {
+    if (o.candidate >= (int32_t)kept.size())
+      return fail(FS_ERR_INVALID_ARG, "fs_plan_create: candidate %d outside 0..%zu", o.candidate, kept.size() - 1);
+    best = o.candidate;
+  } else {
+    for (int i = 0; i < (int)kept.size(); ++i) {
+      if (!satisfies(kept[i].info, o)) continue;
+      if (best < 0 || kept[i].info.predicted_us < kept[best].info.predicted_us) best = i;
+    }
+    if (best < 0)
+      return fail(FS_ERR_LOCALITY, "fs_plan_create: no %s candidate of pattern '%s' has the requested launch shape",
+                  scheme_name(scheme), pattern.c_str());
+  }
+
+  fs_plan* p = new (std::nothrow) fs_plan();
+  if (!p) return fail(FS_ERR_INVALID_ARG, "fs_plan_create: out of host memory");
+  p->candidates = kept;
+  p->chosen = best;
+  for (size_t i = 0; i < p->candidates.size(); ++i) {
+    p->candidates[i].info.n_candidates = (int32_t)p->candidates.size();
+    p->candidates[i].info.candidate = (int32_t)i;
+  }
+  p->n_inputs = (int32_t)g->inputs.size();
+  p->n_outputs = (int32_t)g->outputs.size();
+  for (int t : g->inputs) p->input_bytes.push_back(g->tensors[t].numel() * dtype_bytes(g->tensors[t].dtype));
+  for (int t : g->outputs) p->output_bytes.push_back(g->tensors[t].numel() * dtype_bytes(g->tensors[t].store_as));
+  *out = p;
+  return FS_OK;
+}
+
+void fs_plan_destroy(fs_plan* p) { delete p; }
+
+fs_status fs_plan_query(const fs_plan* p, fs_plan_info* out) {
+  clear_error();
+  if (!p || !out) return fail(FS_ERR_INVALID_ARG, "fs_plan_query: null argument");
+  *out = p->candidates[p->chosen].info;
+  return FS_OK;
+}
+
+fs_status fs_plan_candidate(const fs_plan* p, int32_t index, fs_plan_info* out) {
+  clear_error();
+  if (!p || !out) return fail(FS_ERR_INVALID_ARG, "fs_plan_candidate: null argument");
+  if (index < 0 || index >= (int32_t)p->candidates.size())
+    return fail(FS_ERR_INVALID_ARG, "fs_plan_candidate: index %d outside 0..%zu", index, p->candidates.size() - 1);
+  *out = p->candidates[index].info;
+  return FS_OK;
+}
+
+fs_status fs_execute(const fs_plan* p, const void* const* inputs, void* const* outputs, void* workspace,
+                     size_t workspace_bytes, void* hip_stream) {
+  clear_error();
+  if (!p || !inputs || !outputs) return fail(FS_ERR_INVALID_ARG, "fs_execute: null argument");
+  const Candidate& c = p->candidates[p->chosen];
+  for (int i = 0; i < p->n_inputs; ++i) {
+    if (!inputs[i]) return fail(FS_ERR_INVALID_ARG, "fs_execute: input %d is null", i);
+    if ((uintptr_t)inputs[i] & 15u) return fail(FS_ERR_ALIGN, "fs_execute: input %d is not 16-byte aligned", i);
+  }
+  for (int i = 0; i < p->n_outputs; ++i) {
+    if (!outputs[i]) return fail(FS_ERR_INVALID_ARG, "fs_execute: output %d is null", i);
+    if ((uintptr_t)outputs[i] & 15u) return fail(FS_ERR_ALIGN, "fs_execute: output %d is not 16-byte aligned", i);
+  }
+  if (c.info.workspace_bytes > 0) {
+    if (!workspace || workspace_bytes < (size_t)c.info.workspace_bytes)
+      return fail(FS_ERR_WORKSPACE, "fs_execute: workspace of %lld bytes needed, %zu given", (long long)c.info.workspace_bytes, workspace_bytes);
+    if ((uintptr_t)workspace & 15u) return fail(FS_ERR_ALIGN, "fs_execute: workspace is not 16-byte aligned");
+  }
+  for (const Launch& l : c.launches) {
+    KernelArgs a = l.args;
+    for (int k = 0; k < kMaxPtrs; ++k) {
+      switch (l.ptr[k].kind) {
+        case BUF_INPUT: a.p[k] = const_cast<void*>(inputs[l.ptr[k].slot]); break;
+        case BUF_OUTPUT: a.p[k] = outputs[l.ptr[k].slot]; break;
+        case BUF_WORKSPACE: a.p[k] = static_cast<char*>(workspace) + l.ptr[k].offset; break;
+        default: a.p[k] = nullptr; break;
+      }
+    }
+    const int err = launch_kernel(l.kernel, a, l.shape, hip_stream);
+    if (err != 0) return fail(FS_ERR_HIP, "fs_execute: launching %s failed: %s", kernel_name(l.kernel), hip_error_text(err));
+  }
+  return FS_OK;
+}
+
+fs_status fs_stream_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
+  clear_error();
+  if (!dst || !src) return fail(FS_ERR_INVALID_ARG, "fs_stream_copy: null pointer");
+  if (((uintptr_t)dst | (uintptr_t)src | bytes) & 15u) return fail(FS_ERR_ALIGN, "fs_stream_copy: pointers and size must be multiples of 16");
+  if (bytes == 0) return FS_OK;
+  if (bytes / 16 >= (size_t(1) << 32)) return fail(FS_ERR_SHAPE, "fs_stream_copy: too large");
+  KernelArgs a;
+  a.p[0] = const_cast<void*>(src);
+  a.p[1] = dst;
+  a.u.unary = UnaryP{};
+  a.u.unary.n = (uint32_t)(bytes / 16);
+  LaunchShape s;
+  s.block[0] = 256;
+  s.grid[0] = (uint32_t)((bytes / 16 + 1023) / 1024);
+  const int err = launch_kernel(K_COPY, a, s, hip_stream);
+  if (err != 0) return fail(FS_ERR_HIP, "fs_stream_copy: %s", hip_error_text(err));
+  return FS_OK;
+}
+
+}  // extern "C"

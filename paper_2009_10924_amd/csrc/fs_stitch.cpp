@@ -1,0 +1,653 @@
+// Stitched plans: recognise the fusion pattern, enumerate the legal schedules and
+// launch dimensions for it (paper Section 4.2), and describe each one so the
+// evaluator (fs_cost.cpp) can rank them.  Schedules that cannot keep a reduction row
+// inside the reuse scope they rely on (one wavefront's registers, one workgroup)
+// are simply not generated -- the paper's locality filter.
+#include <algorithm>
+#include <cstring>
+
+#include "fs_cost.hpp"
+#include "fs_internal.hpp"
+#include "fs_match.hpp"
+
+namespace fs {
+
+namespace {
+
+uint32_t pow2_at_least(uint32_t v) {
+  uint32_t p = 1;
+  while (p < v) p <<= 1;
+  return p;
+}
+int vec_of(int32_t dt) { return 16 / dtype_bytes(dt); }
+
+bool is_input(const fs_graph& g, int32_t t) { return t >= 0 && g.tensors[t].producer < 0; }
+bool same_dims(const Tensor& a, const Tensor& b) {
+  if (a.rank != b.rank) return false;
+  for (int k = 0; k < a.rank; ++k)
+    if (a.dims[k] != b.dims[k]) return false;
+  return true;
+}
+// [C] or [1,..,1,C]
+bool is_row_vector(const Tensor& v, int64_t cols) {
+  if (v.dims[v.rank - 1] != cols) return false;
+  for (int k = 0; k < v.rank - 1; ++k)
+    if (v.dims[k] != 1) return false;
+  return true;
+}
+bool covers_all(const fs_graph& g, const MatchState& st) { return st.covered.size() == g.ops.size(); }
+
+BufRef in_ref(const fs_graph& g, int32_t t) {
+  BufRef r;
+  r.kind = BUF_INPUT;
+  r.slot = g.tensors[t].input_slot;
+  return r;
+}
+BufRef out_ref(int slot) {
+  BufRef r;
+  r.kind = BUF_OUTPUT;
+  r.slot = slot;
+  return r;
+}
+BufRef ws_ref(int64_t off) {
+  BufRef r;
+  r.kind = BUF_WORKSPACE;
+  r.offset = off;
+  return r;
+}
+
+Candidate make_candidate(const fs_graph& g, const char* pattern, int32_t scheme, int32_t kernel) {
+  Candidate c;
+  memset(&c.info, 0, sizeof c.info);
+  c.info.scheme = scheme;
+  c.info.n_kernels = 1;
+  c.info.bytes_min = graph_bytes_min(g);
+  c.info.bytes_moved_model = c.info.bytes_min;
+  snprintf(c.info.pattern, sizeof c.info.pattern, "%s", pattern);
+  c.launches.emplace_back();
+  c.launches.back().kernel = kernel;
+  return c;
+}
+
+void finish_candidate(Candidate* c, const char* variant, const KernelCost& cost) {
+  Launch& l = c->launches.front();
+  for (int k = 0; k < 3; ++k) { c->info.block[k] = (int32_t)l.shape.block[k]; c->info.grid[k] = (int32_t)l.shape.grid[k]; }
+  snprintf(c->info.kernel, sizeof c->info.kernel, "%s%s", kernel_name(l.kernel), variant);
+  c->cost = cost;
+}
+
+// ------------------------------------------------------------------ softmax family
+const char* kSoftmaxTail = "div(exp(sub(@,rmax[-1](@))),rsum[-1](exp(sub(@,rmax[-1](@)))))";
+std::string subst(const std::string& text, const std::string& a) {
+  std::string r;
+  for (char ch : text) {
+    if (ch == '@') r += a;
+    else r += ch;
+  }
+  return r;
+}
+
+bool build_softmax(const fs_graph& g, std::vector<Candidate>* out) {
+  if (g.outputs.size() != 1) return false;
+  static const char* pre[] = {"add(scale[#0]($X),$M)", "add($X,$M)", "scale[#0]($X)", "$X"};
+  MatchState st;
+  bool found = false;
+  for (const char* a : pre) {
+    Pattern pat(subst(kSoftmaxTail, a));
+    MatchState trial;
+    if (pat.match(g, g.outputs[0], &trial) && covers_all(g, trial) && is_input(g, trial.tensors["X"]) &&
+        (!trial.tensors.count("M") || is_input(g, trial.tensors["M"]))) {
+      st = trial;
+      found = true;
+      break;
+    }
+  }
+  if (!found) return false;
+
+  const Tensor& x = g.tensors[st.tensors["X"]];
+  const Tensor& y = g.tensors[g.outputs[0]];
+  const bool has_mask = st.tensors.count("M") != 0;
+  SoftmaxP p{};
+  p.in_dt = x.dtype;
+  p.out_dt = y.store_as;
+  p.cols = (uint32_t)x.dims[x.rank - 1];
+  p.rows = (uint32_t)(x.numel() / p.cols);
+  p.scale = st.scalars.count(0) ? (float)st.scalars[0] : 1.0f;
+  p.has_mask = has_mask;
+  p.od[0] = p.od[1] = p.od[2] = 1;
+  p.ms[0] = p.ms[1] = p.ms[2] = 0;
+  for (int k = 0; k < x.rank - 1; ++k) p.od[3 - (x.rank - 1) + k] = (uint32_t)x.dims[k];
+  bool dtype_ok = p.in_dt == p.out_dt;
+  if (has_mask) {
+    const Tensor& m = g.tensors[st.tensors["M"]];
+    p.mask_dt = m.dtype;
+    dtype_ok = dtype_ok && m.dtype == x.dtype;
+    // the mask may stretch along x but must not stretch x itself
+    if (!same_dims(y, x)) return true;
+    int64_t acc = 1;
+    for (int k = x.rank - 1; k >= 0; --k) {
+      const int km = k - (x.rank - m.rank);
+      const int64_t d = km >= 0 ? m.dims[km] : 1;
+      const int64_t stride = d == 1 ? 0 : acc;
+      acc *= d;
+      if (k == x.rank - 1) p.mask_inner = d == 1 ? 0 : 1;
+      else p.ms[3 - (x.rank - 1) + k] = (uint32_t)stride;
+    }
+  }
+  if (!dtype_ok) return true;
+
+  const int VEC = vec_of(p.in_dt);
+  const int esz = dtype_bytes(p.in_dt);
+  const int64_t mask_bytes = has_mask ? g.tensors[st.tensors["M"]].numel() * esz : 0;
+  auto base_cost = [&](KernelCost* kc) {
+    kc->hbm_bytes = 2.0 * p.rows * (double)p.cols * esz + mask_bytes;
+    kc->elems = (double)p.rows * p.cols;
+    kc->valu_per_elem = 6.0 + (esz == 2 ? 2.0 : 0.0);
+    kc->trans_per_elem = 1.0;
+    kc->dep_phases = 1;
+  };
+  const bool vector_ok = p.cols % VEC == 0;
+  const uint32_t nvec = vector_ok ? p.cols / VEC : 0;
+
+  if (vector_ok) {
+    for (int K : {1, 2, 4, 8}) {
+      const uint32_t L = pow2_at_least((nvec + K - 1) / K);
+      if (L > 64) continue;
+      if (K > 1 && (uint64_t)L * K >= 2ull * nvec) continue;   // half the register slots would idle
+      Candidate c = make_candidate(g, "softmax", L == 1 ? FS_SCHEME_LOCAL : FS_SCHEME_WAVE, K_SOFTMAX_WAVE);
+      Launch& l = c.launches.front();
+      SoftmaxP q = p;
+      q.lanes_per_row = (int32_t)L;
+      q.vecs_per_lane = K;
+      l.args.u.softmax = q;
+      l.ptr[0] = in_ref(g, st.tensors["X"]);
+      if (has_mask) l.ptr[1] = in_ref(g, st.tensors["M"]);
+      l.ptr[2] = out_ref(0);
+      l.shape.block[0] = 256;
+      const uint32_t rows_per_block = 256 / L;
+      l.shape.grid[0] = (p.rows + rows_per_block - 1) / rows_per_block;
+      c.info.lanes_per_row = (int32_t)L;
+      c.info.vecs_per_lane = K;
+      c.info.rows_per_block = (int32_t)rows_per_block;
+      KernelCost kc;
+      base_cost(&kc);
+      kc.waves = (double)l.shape.grid[0] * 4;
+      kc.waves_per_block = 4;
+      kc.bytes_in_flight_per_lane = 16.0 * K * (has_mask && p.mask_inner ? 2 : 1);
+      kc.vgpr_estimate = 16 + K * VEC * 1 + (has_mask ? VEC : 0);
+      int steps = 0;
+      for (uint32_t s = 1; s < L; s <<= 1) ++steps;
+      kc.xlane_steps = 2 * steps;
+      kc.lane_utilisation = (double)nvec / ((double)L * K);
+      char var[32];
+      snprintf(var, sizeof var, "<%s,K%d,L%u>", dtype_name(p.in_dt), K, L);
+      finish_candidate(&c, var, kc);
+      out->push_back(c);
+    }
+    for (int K : {1, 2, 4, 8}) {
+      const uint32_t need = (nvec + K - 1) / K;
+      const uint32_t T = (need + 63) / 64 * 64;
+      if (T > 256) continue;
+      if (K > 1 && (uint64_t)T * K >= 2ull * nvec && T > 64) continue;
+      if (K > 1 && T == 64 && (nvec + K / 2 - 1) / (K / 2) <= 64) continue;   // a smaller K already gives one wave
+      Candidate c = make_candidate(g, "softmax", FS_SCHEME_LDS, K_SOFTMAX_BLOCK);
+      Launch& l = c.launches.front();
+      SoftmaxP q = p;
+      q.lanes_per_row = (int32_t)T;
+      q.vecs_per_lane = K;
+      l.args.u.softmax = q;
+      l.ptr[0] = in_ref(g, st.tensors["X"]);
+      if (has_mask) l.ptr[1] = in_ref(g, st.tensors["M"]);
+      l.ptr[2] = out_ref(0);
+      l.shape.block[0] = T;
+      l.shape.grid[0] = p.rows;
+      c.info.lanes_per_row = (int32_t)T;
+      c.info.vecs_per_lane = K;
+      c.info.rows_per_block = 1;
+      c.info.lds_bytes = 32;
+      KernelCost kc;
+      base_cost(&kc);
+      kc.waves_per_block = T / 64;
+      kc.waves = (double)p.rows * kc.waves_per_block;
+      kc.bytes_in_flight_per_lane = 16.0 * K * (has_mask && p.mask_inner ? 2 : 1);
+      kc.vgpr_estimate = 16 + K * VEC + (has_mask ? VEC : 0);
+      kc.xlane_steps = 12;
+      kc.barriers = 2;
+      kc.lds_bytes_per_block = 32;
+      kc.lane_utilisation = (double)nvec / ((double)T * K);
+      char var[32];
+      snprintf(var, sizeof var, "<%s,K%d,T%u>", dtype_name(p.in_dt), K, T);
+      finish_candidate(&c, var, kc);
+      out->push_back(c);
+    }
+  }
+  if (out->empty()) {
+    // ragged or very long rows: block per row, three passes, reduced values via LDS
+    Candidate c = make_candidate(g, "softmax", FS_SCHEME_LDS, K_SOFTMAX_BLOCK);
+    Launch& l = c.launches.front();
+    SoftmaxP q = p;
+    q.lanes_per_row = 256;
+    q.vecs_per_lane = 0;
+    l.args.u.softmax = q;
+    l.ptr[0] = in_ref(g, st.tensors["X"]);
+    if (has_mask) l.ptr[1] = in_ref(g, st.tensors["M"]);
+    l.ptr[2] = out_ref(0);
+    l.shape.block[0] = 256;
+    l.shape.grid[0] = p.rows;
+    c.info.lanes_per_row = 256;
+    c.info.rows_per_block = 1;
+    c.info.lds_bytes = 32;
+    KernelCost kc;
+    base_cost(&kc);
+    kc.hbm_bytes += 2.0 * p.rows * (double)p.cols * esz * 0.25;   // re-reads mostly hit L2
+    kc.valu_per_elem *= 3;
+    kc.trans_per_elem = 2;
+    kc.dep_phases = 3;
+    kc.waves_per_block = 4;
+    kc.waves = (double)p.rows * 4;
+    kc.bytes_in_flight_per_lane = esz;
+    kc.vgpr_estimate = 24;
+    kc.xlane_steps = 12;
+    kc.barriers = 2;
+    kc.lds_bytes_per_block = 32;
+    finish_candidate(&c, "<generic>", kc);
+    out->push_back(c);
+  }
+  return true;
+}
+
+// ------------------------------------------------------------------ layernorm family
+bool build_layernorm(const fs_graph& g, std::vector<Candidate>* out) {
+  if (g.outputs.size() != 1) return false;
+  static const char* hs[] = {"add(add($X,$R),$B)", "add($X,$R)", "$X"};
+  const std::string c_txt = "sub(@,rmean[-1](@))";
+  const std::string norm_txt = "mul(%,rsqrt(addc[#0](rmean[-1](square(%)))))";
+  MatchState st;
+  bool found = false, affine = false;
+  for (const char* h : hs) {
+    const std::string c = subst(c_txt, h);
+    std::string norm;
+    for (char ch : norm_txt) {
+      if (ch == '%') norm += c;
+      else norm += ch;
+    }
+    for (int variant = 0; variant < 4 && !found; ++variant) {
+      std::string top = (variant & 1) ? norm : "add(mul(" + norm + ",$G),$Bt)";
+      if (variant & 2) top = "cvt(" + top + ")";
+      Pattern pat(top);
+      MatchState trial;
+      if (pat.match(g, g.outputs[0], &trial) && covers_all(g, trial)) {
+        bool inputs_ok = true;
+        for (auto& kv : trial.tensors) inputs_ok = inputs_ok && is_input(g, kv.second);
+        if (inputs_ok) {
+          st = trial;
+          found = true;
+          affine = !(variant & 1);
+        }
+      }
+    }
+    if (found) break;
+  }
+  if (!found) return false;
+
+  int32_t tx = st.tensors["X"], tr = st.tensors.count("R") ? st.tensors["R"] : -1, tb = st.tensors.count("B") ? st.tensors["B"] : -1;
+  // put the full-shaped tensor in X; a lone second operand is a residual or a bias by its shape
+  auto full = [&](int32_t a, int32_t b) { return g.tensors[a].numel() >= g.tensors[b].numel(); };
+  if (tr >= 0 && !full(tx, tr)) std::swap(tx, tr);
+  const Tensor& x = g.tensors[tx];
+  LayerNormP p{};
+  p.cols = (uint32_t)x.dims[x.rank - 1];
+  p.rows = (uint32_t)(x.numel() / p.cols);
+  if (tr >= 0 && tb < 0 && !same_dims(g.tensors[tr], x)) { tb = tr; tr = -1; }
+  if (tr >= 0 && !same_dims(g.tensors[tr], x)) return true;
+  if (tb >= 0 && !is_row_vector(g.tensors[tb], p.cols)) return true;
+  const int32_t tg = affine ? st.tensors["G"] : -1, tbt = affine ? st.tensors["Bt"] : -1;
+  if (affine && (!is_row_vector(g.tensors[tg], p.cols) || !is_row_vector(g.tensors[tbt], p.cols))) return true;
+  p.in_dt = x.dtype;
+  p.par_dt = x.dtype;
+  p.out_dt = g.tensors[g.outputs[0]].store_as;
+  for (int32_t t : {tr, tb, tg, tbt})
+    if (t >= 0 && g.tensors[t].dtype != x.dtype) return true;
+  if (!(p.in_dt == FS_F32 || p.out_dt == p.in_dt)) return true;   // compiled dtype pairs
+  p.has_res = tr >= 0;
+  p.has_bias = tb >= 0;
+  p.has_affine = affine;
+  p.eps = (float)st.scalars[0];
+
+  const int VEC = vec_of(p.in_dt);
+  if (p.cols % VEC != 0) return true;
+  const uint32_t nvec = p.cols / VEC;
+  const int in_b = dtype_bytes(p.in_dt), out_b = dtype_bytes(p.out_dt);
+  const double n = (double)p.rows * p.cols;
+  const int n_vec_inputs = (p.has_bias ? 1 : 0) + (affine ? 2 : 0);
+  auto base_cost = [&](KernelCost* kc) {
+    kc->hbm_bytes = n * in_b * (1 + p.has_res) + n * out_b + (double)n_vec_inputs * p.cols * in_b;
+    kc->elems = n;
+    kc->valu_per_elem = 8.0 + (in_b == 2 ? 1.0 : 0.0) + (out_b == 2 ? 1.0 : 0.0);
+    kc->trans_per_elem = 0.0;
+    kc->dep_phases = 1;
+  };
+  auto fill_ptrs = [&](Launch& l) {
+    l.ptr[0] = in_ref(g, tx);
+    if (tr >= 0) l.ptr[1] = in_ref(g, tr);
+    if (tb >= 0) l.ptr[2] = in_ref(g, tb);
+    if (affine) { l.ptr[3] = in_ref(g, tg); l.ptr[4] = in_ref(g, tbt); }
+    l.ptr[5] = out_ref(0);
+  };
+
+  for (int K : {1, 2, 3, 4, 6, 8}) {
+    const uint32_t L = pow2_at_least((nvec + K - 1) / K);
+    if (L > 64) continue;
+    if (K > 1 && (uint64_t)L * K >= 2ull * nvec) continue;
+    Candidate c = make_candidate(g, "layernorm", L == 1 ? FS_SCHEME_LOCAL : FS_SCHEME_WAVE, K_LAYERNORM_WAVE);
+    Launch& l = c.launches.front();
+    LayerNormP q = p;
+    q.lanes_per_row = (int32_t)L;
+    q.vecs_per_lane = K;
+    q.rows_per_block = (int32_t)(256 / L);
+    l.args.u.layernorm = q;
+    fill_ptrs(l);
+    l.shape.block[0] = 256;
+    l.shape.grid[0] = (p.rows + q.rows_per_block - 1) / q.rows_per_block;
+    c.info.lanes_per_row = (int32_t)L;
+    c.info.vecs_per_lane = K;
+    c.info.rows_per_block = q.rows_per_block;
+    KernelCost kc;
+    base_cost(&kc);
+    kc.waves = (double)l.shape.grid[0] * 4;
+    kc.waves_per_block = 4;
+    kc.bytes_in_flight_per_lane = 16.0 * K * (1 + p.has_res);
+    kc.vgpr_estimate = 20 + K * VEC * 2;
+    int steps = 0;
+    for (uint32_t s = 1; s < L; s <<= 1) ++steps;
+    kc.xlane_steps = 2 * steps;
+    kc.cache_bytes = n / p.cols * (double)n_vec_inputs * p.cols * in_b;   // bias/gamma/beta re-read per row from L1/L2
+    kc.lane_utilisation = (double)nvec / ((double)L * K);
+    char var[40];
+    snprintf(var, sizeof var, "<%s,%s,K%d,L%u>", dtype_name(p.in_dt), dtype_name(p.out_dt), K, L);
+    finish_candidate(&c, var, kc);
+    out->push_back(c);
+  }
+  for (int K : {1, 2, 3, 4, 6, 8}) {
+    const uint32_t need = (nvec + K - 1) / K;
+    const uint32_t T = (need + 63) / 64 * 64;
+    if (T > 256 || T < 128) continue;   // a single wave per row is the wave variant's job
+    if ((uint64_t)T * K >= 2ull * nvec) continue;
+    Candidate c = make_candidate(g, "layernorm", FS_SCHEME_LDS, K_LAYERNORM_BLOCK);
+    Launch& l = c.launches.front();
+    LayerNormP q = p;
+    q.lanes_per_row = (int32_t)T;
+    q.vecs_per_lane = K;
+    q.rows_per_block = 1;
+    l.args.u.layernorm = q;
+    fill_ptrs(l);
+    l.shape.block[0] = T;
+    const uint32_t blocks_per_cu = std::max<uint32_t>(1, 2048 / T / 2);   // fill about half the wave slots per CU with one pass
+    l.shape.grid[0] = std::min<uint32_t>(p.rows, device().n_cu * blocks_per_cu);
+    c.info.lanes_per_row = (int32_t)T;
+    c.info.vecs_per_lane = K;
+    c.info.rows_per_block = 1;
+    c.info.lds_bytes = 64;
+    KernelCost kc;
+    base_cost(&kc);
+    kc.waves_per_block = T / 64;
+    kc.waves = (double)l.shape.grid[0] * kc.waves_per_block;
+    kc.rows_per_wave_loop = (double)p.rows / l.shape.grid[0];
+    kc.bytes_in_flight_per_lane = 16.0 * K * (1 + p.has_res);
+    kc.vgpr_estimate = 20 + K * VEC * 2;
+    kc.xlane_steps = 12;
+    kc.barriers = 2;
+    kc.lds_bytes_per_block = 64;
+    kc.cache_bytes = n / p.cols * (double)n_vec_inputs * p.cols * in_b;
+    kc.lane_utilisation = (double)nvec / ((double)T * K);
+    char var[40];
+    snprintf(var, sizeof var, "<%s,%s,K%d,T%u>", dtype_name(p.in_dt), dtype_name(p.out_dt), K, T);
+    finish_candidate(&c, var, kc);
+    out->push_back(c);
+  }
+  return true;
+}
+
+// ------------------------------------------------------------------ bias-GELU family
+bool build_gelu(const fs_graph& g, std::vector<Candidate>* out) {
+  MatchState st;
+  bool with_dbias = false;
+  if (g.outputs.size() == 2) {
+    Pattern py("gelu(add($X,$B))"), pd("rsum[-2](mul($G,gelugrad(add($X,$B))))");
+    int32_t ty = g.outputs[0], td = g.outputs[1];
+    MatchState trial;
+    if (!(py.match(g, ty, &trial) && pd.match(g, td, &trial))) {
+      trial = MatchState();
+      std::swap(ty, td);
+      if (!(py.match(g, ty, &trial) && pd.match(g, td, &trial))) return false;
+    }
+    if (!covers_all(g, trial)) return false;
+    st = trial;
+    st.tensors["__y"] = ty;
+    st.tensors["__d"] = td;
+    with_dbias = true;
+  } else if (g.outputs.size() == 1) {
+    Pattern py("gelu(add($X,$B))");
+    if (!py.match(g, g.outputs[0], &st) || !covers_all(g, st)) return false;
+    st.tensors["__y"] = g.outputs[0];
+  } else {
+    return false;
+  }
+  int32_t tx = st.tensors["X"], tb = st.tensors["B"];
+  if (!is_input(g, tx) || !is_input(g, tb)) return false;
+  if (g.tensors[tx].numel() < g.tensors[tb].numel()) std::swap(tx, tb);
+  const Tensor& x = g.tensors[tx];
+  if (x.rank != 2 && with_dbias) return true;
+  GeluP p{};
+  p.cols = (uint32_t)x.dims[x.rank - 1];
+  p.rows = (uint32_t)(x.numel() / p.cols);
+  p.dt = x.dtype;
+  p.bias_dt = g.tensors[tb].dtype;
+  const Tensor& y = g.tensors[st.tensors["__y"]];
+  if (!is_row_vector(g.tensors[tb], p.cols) || p.bias_dt != p.dt || y.store_as != p.dt) return true;
+  const int VEC = vec_of(p.dt);
+  if (p.cols % VEC != 0) return true;
+  const int esz = dtype_bytes(p.dt);
+  const double n = (double)p.rows * p.cols;
+
+  if (!with_dbias) {
+    Candidate c = make_candidate(g, "bias_gelu", FS_SCHEME_LOCAL, K_BIAS_GELU);
+    Launch& l = c.launches.front();
+    l.args.u.gelu = p;
+    l.ptr[0] = in_ref(g, tx);
+    l.ptr[1] = in_ref(g, tb);
+    l.ptr[2] = out_ref(0);
+    l.shape.block[0] = 256;
+    l.shape.grid[0] = (uint32_t)((n / VEC + 255) / 256);
+    c.info.vecs_per_lane = 1;
+    KernelCost kc;
+    kc.hbm_bytes = 2 * n * esz + p.cols * esz;
+    kc.elems = n;
+    kc.valu_per_elem = 10 + (esz == 2 ? 2 : 0);
+    kc.trans_per_elem = 2;
+    kc.waves = (double)l.shape.grid[0] * 4;
+    kc.waves_per_block = 4;
+    kc.bytes_in_flight_per_lane = 16;
+    kc.vgpr_estimate = 24;
+    char var[24];
+    snprintf(var, sizeof var, "<%s>", dtype_name(p.dt));
+    finish_candidate(&c, var, kc);
+    out->push_back(c);
+    return true;
+  }
+
+  const int32_t tg = st.tensors["G"];
+  const Tensor& d = g.tensors[st.tensors["__d"]];
+  if (!is_input(g, tg) || !same_dims(g.tensors[tg], x) || g.tensors[tg].dtype != p.dt || d.store_as != FS_F32) return true;
+  const uint32_t tile_cols = 64 * VEC;
+  const uint32_t n_col_tiles = (p.cols + tile_cols - 1) / tile_cols;
+  const int64_t counter_bytes = ((int64_t)n_col_tiles * 4 + 255) / 256 * 256;
+  for (uint32_t rpb : {32u, 64u, 128u, 256u, 512u}) {
+    if (rpb > 32 && rpb >= 2 * p.rows) continue;
+    Candidate c = make_candidate(g, "bias_gelu_dbias", FS_SCHEME_GLOBAL, K_BIAS_GELU_DBIAS);
+    Launch& l = c.launches.front();
+    GeluP q = p;
+    q.rows_per_block = rpb;
+    q.n_row_tiles = (p.rows + rpb - 1) / rpb;
+    q.col_tile = tile_cols;
+    l.args.u.gelu = q;
+    l.ptr[0] = in_ref(g, tx);
+    l.ptr[1] = in_ref(g, tb);
+    l.ptr[2] = in_ref(g, tg);
+    l.ptr[3] = out_ref(y.output_slot);
+    l.ptr[4] = out_ref(d.output_slot);
+    l.ptr[5] = ws_ref(counter_bytes);
+    l.ptr[6] = ws_ref(0);
+    l.shape.block[0] = 512;
+    l.shape.grid[0] = q.n_row_tiles * n_col_tiles;
+    c.info.workspace_bytes = counter_bytes + (int64_t)q.n_row_tiles * p.cols * 4;
+    c.info.rows_per_block = (int32_t)rpb;
+    c.info.vecs_per_lane = 1;
+    c.info.lanes_per_row = 64;
+    c.info.lds_bytes = 8 * (int32_t)tile_cols * 4 + 4;
+    c.info.bytes_moved_model = c.info.bytes_min + 2ll * q.n_row_tiles * p.cols * 4;
+    KernelCost kc;
+    kc.hbm_bytes = 3 * n * esz + 2.0 * q.n_row_tiles * p.cols * 4;
+    kc.elems = n;
+    kc.valu_per_elem = 16 + (esz == 2 ? 3 : 0);
+    kc.trans_per_elem = 2;
+    kc.waves_per_block = 8;
+    kc.waves = (double)l.shape.grid[0] * 8;
+    kc.bytes_in_flight_per_lane = 64;
+    kc.vgpr_estimate = 64;
+    kc.barriers = 3;
+    kc.lds_bytes_per_block = c.info.lds_bytes;
+    kc.serial_tail_s = (double)q.n_row_tiles / 8.0 * device().mem_latency_s * 0.5;   // last workgroup folds the partials
+    kc.rows_per_wave_loop = (double)rpb / 8.0;
+    char var[32];
+    snprintf(var, sizeof var, "<%s,R%u>", dtype_name(p.dt), rpb);
+    finish_candidate(&c, var, kc);
+    out->push_back(c);
+  }
+  return true;
+}
+
+// ------------------------------------------------------------------ transpose chain family
+bool build_tchain(const fs_graph& g, std::vector<Candidate>* out) {
+  if (g.outputs.size() != 1) return false;
+  const std::string u = "mul(tr[0213]($X),$S)";
+  Pattern pat("mul(" + u + ",rsqrt(addc[#0](rsum[-1](square(" + u + ")))))");
+  MatchState st;
+  if (!pat.match(g, g.outputs[0], &st) || !covers_all(g, st)) return false;
+  int32_t tx = st.tensors["X"], ts = st.tensors["S"];
+  if (!is_input(g, tx) || !is_input(g, ts)) return false;
+  const Tensor& x = g.tensors[tx];
+  const Tensor& s = g.tensors[ts];
+  if (x.rank != 4) return true;
+  TChainP p{};
+  p.B = (uint32_t)x.dims[0]; p.S = (uint32_t)x.dims[1]; p.H = (uint32_t)x.dims[2]; p.D = (uint32_t)x.dims[3];
+  // scale must be one value per head: [H,1,1] (or [1,H,1,1])
+  if (s.numel() != (int64_t)p.H || s.rank < 3 || s.dims[s.rank - 3] != (int64_t)p.H) return true;
+  p.dt = x.dtype;
+  p.scale_dt = s.dtype;
+  p.eps = (float)st.scalars[0];
+  if (s.dtype != x.dtype || g.tensors[g.outputs[0]].store_as != x.dtype) return true;
+  const int VEC = vec_of(p.dt);
+  if (p.D % VEC != 0) return true;
+  const uint32_t nvec = p.D / VEC;
+  const int esz = dtype_bytes(p.dt);
+  const double n = (double)x.numel();
+
+  for (int lds = 0; lds < 2; ++lds) {
+    for (int K : {1, 2, 4}) {
+      const uint32_t L = pow2_at_least((nvec + K - 1) / K);
+      if (L > 64) continue;
+      if (K > 1 && (uint64_t)L * K >= 2ull * nvec) continue;
+      for (uint32_t s_tile : {4u, 8u, 16u}) {
+        if (s_tile > 4 && s_tile >= 2 * p.S) continue;
+        const int64_t lds_bytes = lds ? (int64_t)s_tile * p.H * (p.D + 4) * 4 : 0;
+        if (lds_bytes > 64 * 1024) continue;
+        Candidate c = make_candidate(g, "transpose_chain", lds ? FS_SCHEME_LDS : (L == 1 ? FS_SCHEME_LOCAL : FS_SCHEME_WAVE),
+                                     lds ? K_TCHAIN_LDS : K_TCHAIN_WAVE);
+        Launch& l = c.launches.front();
+        TChainP q = p;
+        q.lanes_per_row = (int32_t)L;
+        q.vecs_per_lane = K;
+        q.s_tile = (int32_t)s_tile;
+        l.args.u.tchain = q;
+        l.ptr[0] = in_ref(g, tx);
+        l.ptr[1] = in_ref(g, ts);
+        l.ptr[2] = out_ref(0);
+        l.shape.block[0] = 256;
+        l.shape.grid[0] = p.B * ((p.S + s_tile - 1) / s_tile);
+        l.shape.lds_bytes = (uint32_t)lds_bytes;
+        c.info.lanes_per_row = (int32_t)L;
+        c.info.vecs_per_lane = K;
+        c.info.rows_per_block = (int32_t)(s_tile * p.H);
+        c.info.lds_bytes = (int32_t)lds_bytes;
+        KernelCost kc;
+        kc.hbm_bytes = 2 * n * esz;
+        kc.elems = n;
+        kc.valu_per_elem = 5 + (esz == 2 ? 2 : 0) + (lds ? 2 : 0);
+        kc.trans_per_elem = 0;
+        kc.waves_per_block = 4;
+        kc.waves = (double)l.shape.grid[0] * 4;
+        const double passes = std::max(1.0, (double)s_tile * p.H / (256.0 / L));
+        kc.rows_per_wave_loop = passes;
+        kc.bytes_in_flight_per_lane = 16.0 * K;
+        kc.vgpr_estimate = 24 + K * VEC;
+        int steps = 0;
+        for (uint32_t t = 1; t < L; t <<= 1) ++steps;
+        kc.xlane_steps = steps;
+        kc.barriers = lds ? 1 : 0;
+        kc.lds_bytes_per_block = (int32_t)lds_bytes;
+        kc.lds_traffic_bytes = lds ? 2 * n * 4 : 0;
+        kc.store_run_bytes = lds ? (double)s_tile * p.D * esz : (double)p.D * esz;
+        kc.lane_utilisation = (double)nvec / ((double)L * K);
+        char var[40];
+        snprintf(var, sizeof var, "<%s,K%d,L%u,S%u>", dtype_name(p.dt), K, L, s_tile);
+        finish_candidate(&c, var, kc);
+        out->push_back(c);
+      }
+    }
+  }
+  return true;
+}
+
+// ------------------------------------------------------------------ lone transpose
+bool build_transpose(const fs_graph& g, std::vector<Candidate>* out) {
+  if (g.ops.size() != 1 || g.ops[0].opcode != FS_TRANSPOSE || g.outputs.size() != 1) return false;
+  Candidate u;
+  if (build_unfused(g, &u) != FS_OK) return true;
+  const Launch& l = u.launches.front();
+  const bool tile = l.kernel == K_TRANSPOSE_TILE;
+  u.info.scheme = tile ? FS_SCHEME_LDS : FS_SCHEME_LOCAL;
+  snprintf(u.info.pattern, sizeof u.info.pattern, "transpose");
+  u.info.lds_bytes = tile ? 32 * 33 * l.args.u.transpose.elem_bytes : 0;
+  KernelCost kc;
+  kc.hbm_bytes = (double)u.info.bytes_min;
+  kc.elems = (double)l.args.u.transpose.n;
+  kc.valu_per_elem = tile ? 12 : 4;
+  kc.waves_per_block = 4;
+  kc.waves = (double)l.shape.grid[0] * 4;
+  kc.bytes_in_flight_per_lane = tile ? 4.0 * l.args.u.transpose.elem_bytes : (double)l.args.u.transpose.vec * l.args.u.transpose.elem_bytes;
+  kc.vgpr_estimate = 24;
+  kc.barriers = tile ? 1 : 0;
+  kc.lds_bytes_per_block = u.info.lds_bytes;
+  u.cost = kc;
+  out->push_back(u);
+  return true;
+}
+
+}  // namespace
+
+std::string build_stitched(const fs_graph& g, std::vector<Candidate>* out) {
+  struct Family { const char* name; bool (*build)(const fs_graph&, std::vector<Candidate>*); };
+  static const Family families[] = {
+      {"softmax", build_softmax}, {"layernorm", build_layernorm}, {"bias_gelu", build_gelu},
+      {"transpose_chain", build_tchain}, {"transpose", build_transpose},
+  };
+  for (const Family& f : families) {
+    out->clear();
+    if (f.build(g, out)) return f.name;
+  }
+  out->clear();
+  return "";
+}
+
+}  // namespace fs

@@ -1,0 +1,169 @@
+// Device-side helpers for gfx950: 128-bit typed loads/stores that widen to float32,
+// round-to-nearest-even narrowing, and wave64 cross-lane reductions.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace fsk {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+struct bf16_t { uint16_t bits; };   // storage tag types; arithmetic is always float32
+typedef _Float16 f16_t;
+
+constexpr int kWave = 64;
+
+// ---- element traits: VEC = elements in one 128-bit access --------------------
+template <typename T> struct Elem;
+template <> struct Elem<float> { static constexpr int VEC = 4; };
+template <> struct Elem<f16_t> { static constexpr int VEC = 8; };
+template <> struct Elem<bf16_t> { static constexpr int VEC = 8; };
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __builtin_bit_cast(float, b << 16); }
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  bf16x2 r = __builtin_convertvector(v, bf16x2);   // v_cvt_pk_bf16_f32: round to nearest even
+  return __builtin_bit_cast(uint32_t, r);
+}
+__device__ __forceinline__ uint32_t pack_f16(float lo, float hi) {
+  f16x2 r = {(_Float16)lo, (_Float16)hi};          // v_cvt_f16_f32: round to nearest even
+  return __builtin_bit_cast(uint32_t, r);
+}
+__device__ __forceinline__ void unpack_f16(uint32_t w, float& lo, float& hi) {
+  f16x2 h = __builtin_bit_cast(f16x2, w);
+  lo = (float)h.x;
+  hi = (float)h.y;
+}
+
+// ---- scalar element access ---------------------------------------------------
+__device__ __forceinline__ float load1(const float* p) { return *p; }
+__device__ __forceinline__ float load1(const f16_t* p) { return (float)*p; }
+__device__ __forceinline__ float load1(const bf16_t* p) { return bf16_bits_to_f32(p->bits); }
+__device__ __forceinline__ void store1(float* p, float v) { *p = v; }
+__device__ __forceinline__ void store1(f16_t* p, float v) { *p = (_Float16)v; }
+__device__ __forceinline__ void store1(bf16_t* p, float v) {
+  p->bits = __builtin_bit_cast(uint16_t, (__bf16)v);
+}
+
+// ---- 128-bit vector access: VEC elements <-> float[VEC] -----------------------
+__device__ __forceinline__ void load_vec(const float* p, float (&v)[4]) {
+  f32x4 t = *reinterpret_cast<const f32x4*>(p);
+  v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+}
+__device__ __forceinline__ void load_vec(const bf16_t* p, float (&v)[8]) {
+  u32x4 t = *reinterpret_cast<const u32x4*>(p);
+  v[0] = __builtin_bit_cast(float, t.x << 16); v[1] = __builtin_bit_cast(float, t.x & 0xFFFF0000u);
+  v[2] = __builtin_bit_cast(float, t.y << 16); v[3] = __builtin_bit_cast(float, t.y & 0xFFFF0000u);
+  v[4] = __builtin_bit_cast(float, t.z << 16); v[5] = __builtin_bit_cast(float, t.z & 0xFFFF0000u);
+  v[6] = __builtin_bit_cast(float, t.w << 16); v[7] = __builtin_bit_cast(float, t.w & 0xFFFF0000u);
+}
+__device__ __forceinline__ void load_vec(const f16_t* p, float (&v)[8]) {
+  u32x4 t = *reinterpret_cast<const u32x4*>(p);
+  unpack_f16(t.x, v[0], v[1]); unpack_f16(t.y, v[2], v[3]);
+  unpack_f16(t.z, v[4], v[5]); unpack_f16(t.w, v[6], v[7]);
+}
+__device__ __forceinline__ void store_vec(float* p, const float (&v)[4]) {
+  f32x4 t = {v[0], v[1], v[2], v[3]};
+  *reinterpret_cast<f32x4*>(p) = t;
+}
+__device__ __forceinline__ void store_vec(bf16_t* p, const float (&v)[8]) {
+  u32x4 t = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7])};
+  *reinterpret_cast<u32x4*>(p) = t;
+}
+__device__ __forceinline__ void store_vec(f16_t* p, const float (&v)[8]) {
+  u32x4 t = {pack_f16(v[0], v[1]), pack_f16(v[2], v[3]), pack_f16(v[4], v[5]), pack_f16(v[6], v[7])};
+  *reinterpret_cast<u32x4*>(p) = t;
+}
+// 4-element (64-bit) access for 16-bit types, used when a float32 vector of 4 pairs with them.
+__device__ __forceinline__ void load_vec4(const float* p, float (&v)[4]) { load_vec(p, v); }
+__device__ __forceinline__ void load_vec4(const bf16_t* p, float (&v)[4]) {
+  u32x2 t = *reinterpret_cast<const u32x2*>(p);
+  v[0] = __builtin_bit_cast(float, t.x << 16); v[1] = __builtin_bit_cast(float, t.x & 0xFFFF0000u);
+  v[2] = __builtin_bit_cast(float, t.y << 16); v[3] = __builtin_bit_cast(float, t.y & 0xFFFF0000u);
+}
+__device__ __forceinline__ void load_vec4(const f16_t* p, float (&v)[4]) {
+  u32x2 t = *reinterpret_cast<const u32x2*>(p);
+  unpack_f16(t.x, v[0], v[1]); unpack_f16(t.y, v[2], v[3]);
+}
+__device__ __forceinline__ void store_vec4(float* p, const float (&v)[4]) { store_vec(p, v); }
+__device__ __forceinline__ void store_vec4(bf16_t* p, const float (&v)[4]) {
+  u32x2 t = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+  *reinterpret_cast<u32x2*>(p) = t;
+}
+__device__ __forceinline__ void store_vec4(f16_t* p, const float (&v)[4]) {
+  u32x2 t = {pack_f16(v[0], v[1]), pack_f16(v[2], v[3])};
+  *reinterpret_cast<u32x2*>(p) = t;
+}
+
+// ---- math ---------------------------------------------------------------------
+constexpr float kLog2e = 1.4426950408889634f;
+__device__ __forceinline__ float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * kLog2e); }
+__device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
+__device__ __forceinline__ float fast_rsqrt(float x) { return __builtin_amdgcn_rsqf(x); }
+
+// tanh-GELU through the logistic form: gelu(z) = z * s, s = 1/(1+exp(-2u)),
+// u = sqrt(2/pi) (z + 0.044715 z^3).  Same function as z/2 (1+tanh u) in exact
+// arithmetic, without the cancellation of 1+tanh(u) for z << 0.
+__device__ __forceinline__ void gelu_parts(float z, float& s, float& dcoef) {
+  constexpr float k2c = 2.0f * 0.7978845608028654f;          // 2 sqrt(2/pi)
+  const float z2 = z * z;
+  const float w = k2c * z * __builtin_fmaf(0.044715f, z2, 1.0f);   // 2u
+  s = fast_rcp(1.0f + __builtin_amdgcn_exp2f(-kLog2e * w));
+  dcoef = k2c * __builtin_fmaf(3.0f * 0.044715f, z2, 1.0f);        // d(2u)/dz
+}
+__device__ __forceinline__ float gelu_fwd(float z) {
+  float s, d;
+  gelu_parts(z, s, d);
+  return z * s;
+}
+__device__ __forceinline__ float gelu_grad(float z) {
+  float s, d;
+  gelu_parts(z, s, d);
+  return __builtin_fmaf(z * s * (1.0f - s), d, s);
+}
+
+// ---- wave64 cross-lane all-reduce over aligned groups of L lanes (L power of two) ----
+// Steps inside a 16-lane DPP row use DPP operand modifiers (no LDS traffic); the
+// 32- and 64-lane steps use ds_bpermute.  Every lane of the group ends with the
+// same bits: each step combines two values that both sides hold, with a
+// commutative op.
+struct OpSum { __device__ __forceinline__ static float apply(float a, float b) { return a + b; } };
+struct OpMax { __device__ __forceinline__ static float apply(float a, float b) { return fmaxf(a, b); } };
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+
+template <typename OP>
+__device__ __forceinline__ float group_allreduce(float v, int lanes) {
+  if (lanes > 1) v = OP::apply(v, dpp_move<0xB1>(v));    // quad_perm [1,0,3,2]  : lane ^ 1
+  if (lanes > 2) v = OP::apply(v, dpp_move<0x4E>(v));    // quad_perm [2,3,0,1]  : lane ^ 2
+  if (lanes > 4) v = OP::apply(v, dpp_move<0x141>(v));   // row_half_mirror      : other quad of the 8
+  if (lanes > 8) v = OP::apply(v, dpp_move<0x140>(v));   // row_mirror           : other half of the 16
+  if (lanes > 16) v = OP::apply(v, __shfl_xor(v, 16));
+  if (lanes > 32) v = OP::apply(v, __shfl_xor(v, 32));
+  return v;
+}
+
+// Workgroup all-reduce through LDS (block composition): each wave reduces, lane 0
+// of each wave parks its value, after the barrier every thread folds the parked
+// values in wave order.  `slot` must hold blockDim.x/64 floats; the caller owns
+// reuse of `slot` (a barrier separates two uses).
+template <typename OP>
+__device__ __forceinline__ float block_allreduce(float v, float* slot, int n_waves) {
+  v = group_allreduce<OP>(v, kWave);
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x >> 6;
+  if (lane == 0) slot[wave] = v;
+  __syncthreads();
+  float r = slot[0];
+  for (int w = 1; w < n_waves; ++w) r = OP::apply(r, slot[w]);
+  return r;
+}
+
+}  // namespace fsk

@@ -1,0 +1,132 @@
+// Host-visible description of every kernel the library can launch: ids, parameter
+// blocks (plain data, passed by value), launch shapes.  No HIP types here so the
+// host-only translation units can include it.
+#pragma once
+#include <cstdint>
+
+namespace fs {
+
+constexpr int kMaxPtrs = 8;
+
+// storage dtypes, numbered like the public fs_dtype
+enum DType : int32_t { DT_F32 = 0, DT_F16 = 1, DT_BF16 = 2, DT_I32 = 3 };
+
+enum KernelId : int32_t {
+  // per-op baseline
+  K_UNARY = 0,         // p0 in, p1 out
+  K_BINARY,            // p0 a, p1 b, p2 out
+  K_REDUCE_ROW,        // p0 in [rows, cols], p1 out [rows]
+  K_REDUCE_MID,        // p0 in [outer, red, inner], p1 out [outer, nchunk, inner]
+  K_TRANSPOSE_ROWS,    // p0 in, p1 out : permutation keeps the innermost axis
+  K_TRANSPOSE_TILE,    // p0 in, p1 out : innermost axis moves, staged through an LDS tile
+  K_COPY,              // p0 src, p1 dst
+  // stitched
+  K_SOFTMAX_WAVE,      // p0 x, p1 mask (or null), p2 out
+  K_SOFTMAX_BLOCK,     // same operands, one workgroup per row, reduced values through LDS
+  K_LAYERNORM_WAVE,    // p0 x, p1 res, p2 bias, p3 gamma, p4 beta, p5 out
+  K_LAYERNORM_BLOCK,
+  K_BIAS_GELU,         // p0 x, p1 bias, p2 y
+  K_BIAS_GELU_DBIAS,   // p0 x, p1 bias, p2 grad, p3 y, p4 dbias, p5 partials, p6 counters
+  K_TCHAIN_WAVE,       // p0 x, p1 scale, p2 out
+  K_TCHAIN_LDS,
+  K_COUNT
+};
+
+struct LaunchShape {
+  uint32_t grid[3] = {1, 1, 1};
+  uint32_t block[3] = {1, 1, 1};
+  uint32_t lds_bytes = 0;   // dynamic LDS
+};
+
+// ---- per-op baseline ----------------------------------------------------------
+enum UnaryOp : int32_t { U_COPY = 0, U_SCALE, U_ADD_SCALAR, U_SQUARE, U_EXP, U_RSQRT, U_TANH, U_GELU, U_GELU_GRAD };
+struct UnaryP {
+  int32_t op, in_dt, out_dt, vec;   // vec: elements per lane per step (8, 4 or 1)
+  uint32_t n;
+  float value;
+};
+enum BinaryOp : int32_t { B_ADD = 0, B_SUB, B_MUL, B_DIV, B_MAX, B_FIRST };
+struct BinaryP {
+  int32_t op, a_dt, b_dt, out_dt, vec, rank;
+  uint32_t n;            // output elements
+  uint32_t dims[4];      // collapsed output extents, dims[rank-1] innermost
+  uint32_t sa[4], sb[4]; // operand strides in elements (0 = broadcast)
+};
+enum ReduceOp : int32_t { R_SUM = 0, R_MAX, R_MEAN };
+struct ReduceP {
+  int32_t op, in_dt, out_dt, vec;
+  uint32_t outer, red, inner;   // input viewed as [outer, red, inner]
+  uint32_t chunk, nchunk;       // K_REDUCE_MID: rows of `red` per workgroup, chunks per column
+  uint32_t lanes_per_row;       // K_REDUCE_ROW
+  float post_scale;             // 1/red for mean on the final pass, else 1
+};
+struct TransposeP {
+  int32_t elem_bytes, vec;      // vec: elements per 128-bit (or narrower) access along the inner axis
+  uint32_t out_dims[4];         // output extents padded to rank 4 (leading 1s)
+  uint32_t in_stride[4];        // input stride (elements) of the axis that feeds each output axis
+  uint32_t n;
+  // K_TRANSPOSE_TILE: the two axes of the tile
+  uint32_t tile_in_axis_out_pos;  // output position of the input's innermost axis
+  uint32_t out_stride[4];
+};
+
+// ---- stitched -----------------------------------------------------------------
+struct SoftmaxP {
+  int32_t in_dt, out_dt, mask_dt;
+  int32_t has_mask, mask_inner;     // mask_inner: 1 if the mask varies along the row, 0 if one value per row
+  uint32_t rows, cols;
+  uint32_t od[3];                   // outer extents of the row index (od[2] fastest), product = rows
+  uint32_t ms[3];                   // mask element stride for each outer coordinate
+  float scale;
+  int32_t lanes_per_row, vecs_per_lane;
+};
+struct LayerNormP {
+  int32_t in_dt, out_dt, par_dt;    // x/res dtype, output dtype, bias/gamma/beta dtype
+  int32_t has_res, has_bias, has_affine;
+  uint32_t rows, cols;
+  float eps;
+  int32_t lanes_per_row, vecs_per_lane, rows_per_block;
+};
+struct GeluP {
+  int32_t dt, bias_dt;              // x / grad / y share dt
+  uint32_t rows, cols;
+  uint32_t rows_per_block;          // rows of one workgroup's tile
+  uint32_t n_row_tiles;
+  uint32_t col_tile;                // columns per workgroup
+};
+struct TChainP {
+  int32_t dt, scale_dt;
+  uint32_t B, S, H, D;              // input [B,S,H,D] -> output [B,H,S,D]
+  float eps;
+  int32_t lanes_per_row, vecs_per_lane, s_tile;
+};
+
+struct KernelArgs {
+  void* p[kMaxPtrs] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  union {
+    UnaryP unary;
+    BinaryP binary;
+    ReduceP reduce;
+    TransposeP transpose;
+    SoftmaxP softmax;
+    LayerNormP layernorm;
+    GeluP gelu;
+    TChainP tchain;
+  } u;
+  KernelArgs() { u.binary = BinaryP{}; }
+};
+
+struct KernelResources {
+  int32_t vgprs = 0;       // architected vector registers per lane
+  int32_t static_lds = 0;  // bytes
+  bool from_device = false;
+};
+
+// Implemented in kernels/*.hip.  Returns hipError_t as int (0 = success).
+int launch_kernel(int32_t kernel, const KernelArgs& args, const LaunchShape& shape, void* stream);
+// Register / LDS figures of the variant `launch_kernel` would pick for these args.
+KernelResources kernel_resources(int32_t kernel, const KernelArgs& args);
+const char* kernel_name(int32_t kernel);
+const char* hip_error_text(int err);
+
+}  // namespace fs

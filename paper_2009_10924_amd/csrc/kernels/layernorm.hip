@@ -1,0 +1,188 @@
+// Stitched residual-add + bias + LayerNorm:
+//     h = x (+ res) (+ bias);  mu = mean(h);  c = h - mu;  v = mean(c^2);
+//     out = c * rsqrt(v + eps) (* gamma + beta)          -- one kernel, 12 ops
+// This is the pattern of the paper's Figure 1 / Section 7.3: two row reductions and
+// one expensive op on the per-row tensor, with every intermediate kept on chip.
+//   * wave variant  (warp composition): an aligned group of L lanes of one wavefront
+//     owns a row in registers; mean and variance are cross-lane all-reduces.
+//   * block variant (block composition): a workgroup owns a row; per-wave partial
+//     sums meet in LDS, the reduced values are read back from LDS by every thread.
+// Two-pass variance on the register-resident row (no E[h^2] - mu^2 cancellation).
+#include <hip/hip_runtime.h>
+
+#include "device_utils.hpp"
+#include "kernel_table.hpp"
+
+namespace fsk {
+using namespace fs;
+
+// TI: dtype of x / res / bias / gamma / beta.  TO: dtype of out.  Both move VEC(TI)
+// elements per lane per step, so the lane->column mapping is the same on both sides.
+template <typename TO, int N> struct StoreN;
+template <typename TO> struct StoreN<TO, 4> {
+  __device__ __forceinline__ static void run(TO* p, const float (&v)[4]) { store_vec4(p, v); }
+};
+template <> struct StoreN<float, 8> {
+  __device__ __forceinline__ static void run(float* p, const float (&v)[8]) {
+    float a[4] = {v[0], v[1], v[2], v[3]}, b[4] = {v[4], v[5], v[6], v[7]};
+    store_vec(p, a);
+    store_vec(p + 4, b);
+  }
+};
+template <> struct StoreN<f16_t, 8> {
+  __device__ __forceinline__ static void run(f16_t* p, const float (&v)[8]) { store_vec(p, v); }
+};
+template <> struct StoreN<bf16_t, 8> {
+  __device__ __forceinline__ static void run(bf16_t* p, const float (&v)[8]) { store_vec(p, v); }
+};
+
+template <typename TI, typename TO, int K>
+struct LnRow {
+  static constexpr int VEC = Elem<TI>::VEC;
+  float h[K][VEC];
+
+  __device__ __forceinline__ float load(const TI* __restrict__ x, const TI* __restrict__ res,
+                                        const TI* __restrict__ bias, const LayerNormP& p, uint32_t row,
+                                        bool row_ok, uint32_t lane, uint32_t stride) {
+    const uint32_t nvec = p.cols / VEC;
+    const size_t base = (size_t)row * p.cols;
+    float sum = 0.0f;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      const uint32_t j = lane + k * stride;
+      if (row_ok && j < nvec) {
+        load_vec(x + base + j * VEC, h[k]);
+        if (p.has_res) {
+          float r[VEC];
+          load_vec(res + base + j * VEC, r);
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) h[k][e] += r[e];
+        }
+        if (p.has_bias) {
+          float b[VEC];
+          load_vec(bias + j * VEC, b);
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) h[k][e] += b[e];
+        }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) sum += h[k][e];
+      } else {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) h[k][e] = 0.0f;
+      }
+    }
+    return sum;
+  }
+
+  __device__ __forceinline__ float center(const LayerNormP& p, float mean, bool row_ok, uint32_t lane, uint32_t stride) {
+    const uint32_t nvec = p.cols / VEC;
+    float sq = 0.0f;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      const uint32_t j = lane + k * stride;
+      if (row_ok && j < nvec) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          h[k][e] -= mean;
+          sq = __builtin_fmaf(h[k][e], h[k][e], sq);
+        }
+      }
+    }
+    return sq;
+  }
+
+  __device__ __forceinline__ void finish(TO* __restrict__ out, const TI* __restrict__ gamma,
+                                         const TI* __restrict__ beta, const LayerNormP& p, uint32_t row,
+                                         bool row_ok, uint32_t lane, uint32_t stride, float rstd) {
+    const uint32_t nvec = p.cols / VEC;
+    const size_t base = (size_t)row * p.cols;
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      const uint32_t j = lane + k * stride;
+      if (row_ok && j < nvec) {
+        if (p.has_affine) {
+          float g[VEC], b[VEC];
+          load_vec(gamma + j * VEC, g);
+          load_vec(beta + j * VEC, b);
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) h[k][e] = __builtin_fmaf(h[k][e] * rstd, g[e], b[e]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) h[k][e] *= rstd;
+        }
+        StoreN<TO, VEC>::run(out + base + j * VEC, h[k]);
+      }
+    }
+  }
+};
+
+template <typename TI, typename TO, int K>
+__global__ void __launch_bounds__(256) k_layernorm_wave(const TI* __restrict__ x, const TI* __restrict__ res,
+                                                        const TI* __restrict__ bias, const TI* __restrict__ gamma,
+                                                        const TI* __restrict__ beta, TO* __restrict__ out,
+                                                        LayerNormP p) {
+  const uint32_t L = p.lanes_per_row;
+  const uint32_t group = threadIdx.x / L;
+  const uint32_t lane = threadIdx.x & (L - 1);
+  const uint32_t row = blockIdx.x * (256u / L) + group;
+  const bool row_ok = row < p.rows;
+  const float inv_n = 1.0f / (float)p.cols;
+  LnRow<TI, TO, K> r;
+  const float mean = group_allreduce<OpSum>(r.load(x, res, bias, p, row, row_ok, lane, L), L) * inv_n;
+  const float var = group_allreduce<OpSum>(r.center(p, mean, row_ok, lane, L), L) * inv_n;
+  r.finish(out, gamma, beta, p, row, row_ok, lane, L, fast_rsqrt(var + p.eps));
+}
+
+template <typename TI, typename TO, int K>
+__global__ void __launch_bounds__(256) k_layernorm_block(const TI* __restrict__ x, const TI* __restrict__ res,
+                                                         const TI* __restrict__ bias, const TI* __restrict__ gamma,
+                                                         const TI* __restrict__ beta, TO* __restrict__ out,
+                                                         LayerNormP p) {
+  __shared__ float slot_sum[2][4], slot_sq[2][4];
+  const uint32_t n_waves = blockDim.x >> 6;
+  const float inv_n = 1.0f / (float)p.cols;
+  uint32_t it = 0;
+  for (uint32_t row = blockIdx.x; row < p.rows; row += gridDim.x, ++it) {
+    LnRow<TI, TO, K> r;
+    // two slot sets alternate between rows: a wave may start row i+1 while a slower
+    // one still reads the slots of row i.
+    const float mean = block_allreduce<OpSum>(r.load(x, res, bias, p, row, true, threadIdx.x, blockDim.x),
+                                              slot_sum[it & 1], n_waves) * inv_n;
+    const float var = block_allreduce<OpSum>(r.center(p, mean, true, threadIdx.x, blockDim.x),
+                                             slot_sq[it & 1], n_waves) * inv_n;
+    r.finish(out, gamma, beta, p, row, true, threadIdx.x, blockDim.x, fast_rsqrt(var + p.eps));
+  }
+}
+
+}  // namespace fsk
+
+namespace fs {
+using namespace fsk;
+
+namespace {
+template <typename TI, typename TO>
+const void* ln_sym(int32_t kernel, int K) {
+#define FS_LN_CASE(KK)                                                             \
+  case KK:                                                                         \
+    return kernel == K_LAYERNORM_WAVE ? (const void*)k_layernorm_wave<TI, TO, KK>  \
+                                      : (const void*)k_layernorm_block<TI, TO, KK>;
+  switch (K) {
+    FS_LN_CASE(1) FS_LN_CASE(2) FS_LN_CASE(3) FS_LN_CASE(4) FS_LN_CASE(6) FS_LN_CASE(8)
+    default: return nullptr;
+  }
+#undef FS_LN_CASE
+}
+}  // namespace
+
+const void* layernorm_kernel_symbol(int32_t kernel, const KernelArgs& a) {
+  const LayerNormP& p = a.u.layernorm;
+  const int K = p.vecs_per_lane;
+  if (p.in_dt == DT_F32 && p.out_dt == DT_F32) return ln_sym<float, float>(kernel, K);
+  if (p.in_dt == DT_F32 && p.out_dt == DT_BF16) return ln_sym<float, bf16_t>(kernel, K);
+  if (p.in_dt == DT_F32 && p.out_dt == DT_F16) return ln_sym<float, f16_t>(kernel, K);
+  if (p.in_dt == DT_BF16 && p.out_dt == DT_BF16) return ln_sym<bf16_t, bf16_t>(kernel, K);
+  if (p.in_dt == DT_F16 && p.out_dt == DT_F16) return ln_sym<f16_t, f16_t>(kernel, K);
+  return nullptr;
+}
+
+}  // namespace fs

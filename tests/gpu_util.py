@@ -1,0 +1,56 @@
+"""Shared plumbing of the GPU parity tests: run a workload descriptor through the C ABI
+and hand back float64 host arrays for comparison with the oracle."""
+from __future__ import annotations
+
+import sys
+
+import numpy as np
+
+from oracle import oracle as O
+from paper_2009_10924_amd import binding as B
+
+# Comparison bars (max relative error vs the float64 oracle):
+#   float32 outputs 1e-5, 16-bit outputs 1e-2; transposes bit-exact.
+# `floor` = 0 means strict |got-ref|/|ref| with 0/0 := 0.  Outputs formed by cancelling
+# sums (LayerNorm output, the bias-gradient column sums) are judged against
+# max(|ref|, rms(ref)): float32 arithmetic carries an absolute error of about 1e-7 of
+# the operands, which no kernel can turn into 1e-5 of an output that happens to be ~0.
+TOL = {"f32": 1e-5, "f16": 1e-2, "bf16": 1e-2}
+
+
+def note(msg: str) -> None:
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def run_spec(spec, inputs_np, scheme="auto", repeat=1, **opts):
+    """Builds graph + plan, uploads inputs, executes `repeat` times, returns ({name: f64 array}, info)."""
+    import torch
+    g = B.Graph.from_spec(spec)
+    plan = B.Plan(g, scheme, **opts)
+    dev_in = [B.to_device(inputs_np[t.name], t.dtype) for t in spec.inputs]
+    dev_out = B.alloc_outputs(spec)
+    for t in dev_out:
+        if t.dtype in (torch.float32, torch.float16, torch.bfloat16):
+            t.fill_(float("nan"))
+        else:
+            t.fill_(-1)
+    ws = plan.make_workspace()
+    results = []
+    for _ in range(repeat):
+        plan.execute(dev_in, dev_out, ws)
+        torch.cuda.synchronize()
+        results.append({name: B.to_host(t, dt).copy() for (name, dt), t in zip(spec.outputs, dev_out)})
+    for r in results[1:]:
+        for name in r:
+            assert np.array_equal(r[name].view(np.uint8), results[0][name].view(np.uint8)), f"{name}: not run-to-run identical"
+    out = {name: O.to_f64(results[0][name], dt) for name, dt in spec.outputs}
+    raw = results[0]
+    return out, raw, plan.info, plan
+
+
+def check(got, ref, dtype, floor=0.0, what=""):
+    err = O.max_rel_err(got, ref, floor)
+    assert np.isfinite(got).all(), f"{what}: non-finite values in the GPU result"
+    assert err <= TOL[dtype], f"{what}: max rel err {err:.3e} > {TOL[dtype]:.0e}"
+    return err

@@ -1,0 +1,202 @@
+"""GPU parity: every scheme and every enumerated launch shape of every pattern, plus the
+per-op baseline, against the float64 oracle on the same seeded inputs.  Sizes span
+several tiles and end in ragged tails.  All calls go through the C ABI."""
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+from paper_2009_10924_amd import binding as B
+from tests.gpu_util import TOL, check, note, run_spec
+from workloads import (add_bias_layernorm_graph, attention_scores_graph, bias_gelu_dbias_graph, bias_gelu_graph,
+                       make_inputs, softmax_graph, transpose_chain_graph, transpose_graph)
+from workloads.graphs import GraphSpec, OpSpec, TensorSpec
+
+pytestmark = pytest.mark.gpu
+
+
+def all_candidates(spec, inputs, ref, floors, repeat=1):
+    """Runs the per-op plan and every stitched candidate; returns the worst error per output."""
+    worst = {}
+    g = B.Graph.from_spec(spec)
+    n = B.Plan(g, "auto").info["n_candidates"]
+    runs = [("unfused", {})] + [("auto", {"candidate": i}) for i in range(n)]
+    for scheme, opts in runs:
+        note(f"  case {spec.name} scheme={scheme} opts={opts}")
+        got, _, info, _ = run_spec(spec, inputs, scheme, repeat=repeat, **opts)
+        for name, dt in spec.outputs:
+            e = check(got[name], ref[name], dt, floors.get(name, 0.0), f"{spec.name}/{info['kernel']}/{name}")
+            worst[name] = max(worst.get(name, 0.0), e)
+    return worst
+
+
+# ------------------------------------------------------------------ C1 softmax
+@pytest.mark.parametrize("rows,cols,dtype", [
+    (64, 128, "f32"),        # the configuration itself
+    (301, 128, "f32"),       # ragged row count across workgroups
+    (37, 4, "f32"),          # one vector per row: a lane owns a row (thread composition)
+    (19, 1000, "f32"),       # 250 vectors: partly filled lanes
+    (7, 2048, "f32"),        # 512 vectors: fills 64 lanes x 8 vectors
+    (5, 4096, "f32"),        # too long for a wavefront: workgroup per row
+    (33, 37, "f32"),         # row not a multiple of 4: generic kernel
+    (29, 264, "f16"), (29, 264, "bf16"),
+])
+def test_softmax(rows, cols, dtype):
+    spec = softmax_graph(rows, cols, dtype)
+    inp = make_inputs(spec, seed=0)
+    ref = O.evaluate(spec, inp)
+    worst = all_candidates(spec, inp, ref, {}, repeat=2)
+    note(f"softmax {rows}x{cols} {dtype}: worst rel err {worst}")
+
+
+# ------------------------------------------------------------------ C3 attention scores
+@pytest.mark.parametrize("B_,H,S,T,dtype", [(3, 2, 9, 128, "f16"), (2, 3, 5, 64, "f16"), (2, 2, 7, 40, "bf16"),
+                                           (2, 2, 3, 128, "f32"), (2, 1, 4, 36, "f16")])
+def test_attention_scores(B_, H, S, T, dtype):
+    spec = attention_scores_graph(B_, H, S, T, dtype=dtype)
+    inp = make_inputs(spec, seed=0)
+    ref = O.evaluate(spec, inp)
+    all_candidates(spec, inp, ref, {})
+    # masked keys come out as exact zeros
+    got, _, _, _ = run_spec(spec, inp, "auto")
+    assert ((got["y"] == 0) == (ref["y"] == 0)).all()
+
+
+# ------------------------------------------------------------------ C2 add + bias + LayerNorm
+@pytest.mark.parametrize("rows,cols,in_dt,out_dt", [
+    (67, 768, "f32", "bf16"), (130, 768, "f32", "f32"), (9, 1024, "f32", "bf16"), (11, 100, "f32", "f32"),
+    (5, 4, "f32", "f32"), (13, 2048, "f32", "f16"), (17, 768, "bf16", "bf16"), (17, 512, "f16", "f16"),
+])
+def test_add_bias_layernorm(rows, cols, in_dt, out_dt):
+    spec = add_bias_layernorm_graph(rows, cols, in_dtype=in_dt, out_dtype=out_dt)
+    inp = make_inputs(spec, seed=0)
+    ref = O.evaluate(spec, inp)
+    floors = {"out": O.rms(ref["out"])}
+    worst = all_candidates(spec, inp, ref, floors, repeat=2)
+    note(f"layernorm {rows}x{cols} {in_dt}->{out_dt}: worst rel err (floor rms) {worst}")
+
+
+def test_layernorm_variants_without_residual_or_affine():
+    # plain LayerNorm (no residual, no bias), and normalisation without gamma / beta
+    base = add_bias_layernorm_graph(21, 256, out_dtype="f32")
+    inp = make_inputs(base, seed=0)
+    plain_ops = [OpSpec("mu", "reduce_mean", ("x",), {"axis": 1}), OpSpec("c", "sub", ("x", "mu"))] + list(base.ops[4:10]) + \
+                [OpSpec("o", "add", ("g", "beta"))]
+    plain = GraphSpec("add_bias_layernorm_plain", [base.inputs[0], base.inputs[3], base.inputs[4]], plain_ops, [("o", "f32")])
+    ref = O.evaluate(plain, inp)
+    got, _, info, _ = run_spec(plain, inp, "auto")
+    assert info["pattern"] == "layernorm"
+    check(got["o"], ref["o"], "f32", O.rms(ref["o"]), "plain layernorm")
+    noaff = GraphSpec("add_bias_layernorm_noaffine", base.inputs[:2], [base.ops[0]] +
+                      [OpSpec("mu", "reduce_mean", ("h0",), {"axis": 1}), OpSpec("c", "sub", ("h0", "mu"))] + list(base.ops[4:9]),
+                      [("n", "f32")])
+    ref = O.evaluate(noaff, inp)
+    got, _, info, _ = run_spec(noaff, inp, "auto")
+    assert info["pattern"] == "layernorm"
+    check(got["n"], ref["n"], "f32", O.rms(ref["n"]), "layernorm without affine")
+
+
+# ------------------------------------------------------------------ C4 bias GELU + bias gradient
+@pytest.mark.parametrize("rows,cols,dtype", [(300, 1032, "bf16"), (70, 512, "bf16"), (33, 264, "f16"), (129, 260, "f32"),
+                                             (1, 8, "bf16")])
+def test_bias_gelu_dbias(rows, cols, dtype):
+    spec = bias_gelu_dbias_graph(rows, cols, dtype)
+    inp = make_inputs(spec, seed=0)
+    ref = O.evaluate(spec, inp)
+    floors = {"dbias": O.rms(ref["dbias"])}
+    worst = all_candidates(spec, inp, ref, floors, repeat=3)   # repeat: the arrival counters must reset themselves
+    note(f"bias_gelu_dbias {rows}x{cols} {dtype}: worst {worst}")
+
+
+def test_bias_gelu_negative_tail():
+    # z far below zero: the textbook 1+tanh(u) form cancels in float32, the kernel's form must not
+    spec = bias_gelu_graph(4, 64, "f32")
+    x = np.linspace(-5.0, -2.0, 256, dtype=np.float32).reshape(4, 64)
+    inp = {"x": x, "bias": np.zeros(64, np.float32)}
+    ref = O.evaluate(spec, inp)
+    for scheme in ("unfused", "auto"):
+        got, _, _, _ = run_spec(spec, inp, scheme)
+        # float32 outputs carry the 1e-5 bar wherever the result is a normal float32
+        normal = np.abs(ref["y"]) > 1e-30
+        assert O.max_rel_err(got["y"][normal], ref["y"][normal]) <= 1e-5
+
+
+def test_bias_gelu_only():
+    for dtype in ("bf16", "f16", "f32"):
+        spec = bias_gelu_graph(37, 520, dtype)
+        inp = make_inputs(spec, seed=0)
+        ref = O.evaluate(spec, inp)
+        all_candidates(spec, inp, ref, {})
+
+
+# ------------------------------------------------------------------ C5 transpose chain
+@pytest.mark.parametrize("B_,S,H,D,dtype", [(2, 37, 12, 64, "f32"), (1, 5, 3, 128, "f32"), (3, 18, 5, 32, "f32"),
+                                           (2, 9, 4, 256, "f32"), (2, 11, 12, 64, "bf16"), (1, 70, 2, 8, "f32")])
+def test_transpose_chain(B_, S, H, D, dtype):
+    spec = transpose_chain_graph(B_, S, H, D, dtype=dtype)
+    inp = make_inputs(spec, seed=0)
+    ref = O.evaluate(spec, inp)
+    worst = all_candidates(spec, inp, ref, {})
+    note(f"transpose_chain {B_}x{S}x{H}x{D} {dtype}: worst {worst}")
+
+
+# ------------------------------------------------------------------ transpose: bit-exact
+@pytest.mark.parametrize("dims,perm,dtype", [
+    ((4, 37, 12, 64), (0, 2, 1, 3), "f32"), ((3, 5, 7, 6), (0, 2, 1, 3), "i32"), ((2, 33, 5, 8), (2, 0, 1, 3), "bf16"),
+    ((2, 9, 50, 70), (0, 1, 3, 2), "f32"), ((5, 40, 70), (2, 0, 1), "f16"), ((3, 4, 35, 33), (3, 1, 0, 2), "i32"),
+    ((67, 129), (1, 0), "f32"), ((2, 3, 4, 5), (3, 2, 1, 0), "f32"), ((6, 10), (0, 1), "f32"),
+])
+def test_transpose_bit_exact(dims, perm, dtype):
+    spec = transpose_graph(dims, perm, dtype)
+    inp = make_inputs(spec)                     # element i carries the bit pattern of i
+    want = np.ascontiguousarray(np.transpose(inp["x"], perm))
+    for scheme in ("unfused", "auto"):
+        note(f"  case {spec.name} scheme={scheme}")
+        _, raw, info, _ = run_spec(spec, inp, scheme)
+        assert raw["t"].shape == want.shape
+        assert np.array_equal(raw["t"].view(np.uint8), want.view(np.uint8)), f"{spec.name} {info['kernel']}"
+    # transpose o transpose = identity when the permutation is an involution
+    if tuple(np.argsort(perm)) == tuple(perm):
+        spec2 = transpose_graph(want.shape, perm, dtype)
+        _, raw2, _, _ = run_spec(spec2, {"x": want}, "auto")
+        assert np.array_equal(raw2["t"].view(np.uint8), inp["x"].view(np.uint8))
+
+
+# ------------------------------------------------------------------ per-op plan on graphs no stitched kernel covers
+def test_unfused_generic_graph():
+    rng = np.random.default_rng(3)
+    spec = GraphSpec("custom", [TensorSpec("a", "f32", (3, 5, 8)), TensorSpec("b", "f16", (5, 1)), TensorSpec("c", "bf16", (3, 1, 8))], [
+        OpSpec("t0", "mul", ("a", "b")), OpSpec("t1", "max", ("t0", "c")), OpSpec("t2", "tanh", ("t1",)),
+        OpSpec("t3", "reduce_max", ("t2",), {"axis": 1}), OpSpec("t4", "broadcast", ("t3",), {"dims": (3, 5, 8)}),
+        OpSpec("t5", "div", ("t2", "t4")), OpSpec("t6", "reduce_mean", ("t5",), {"axis": 0}),
+        OpSpec("t7", "convert", ("t5",), {"dtype": "f16"}), OpSpec("t8", "scale", ("t7",), {"value": 3.0}),
+        OpSpec("t9", "transpose", ("t8",), {"perm": (2, 0, 1)}), OpSpec("t10", "add_scalar", ("t9",), {"value": -1.5}),
+    ], [("t6", "f32"), ("t10", "f32"), ("t5", "bf16")])
+    from workloads import quantise
+    inp = {"a": quantise(rng.standard_normal((3, 5, 8)), "f32"), "b": quantise(rng.uniform(0.5, 2, (5, 1)), "f16"),
+           "c": quantise(rng.standard_normal((3, 1, 8)), "bf16")}
+    ref = O.evaluate(spec, inp)
+    got, _, info, _ = run_spec(spec, inp, "auto")
+    assert info["scheme"] == "unfused"
+    check(got["t6"], ref["t6"], "f32", O.rms(ref["t6"]), "t6")
+    check(got["t10"], ref["t10"], "f16", 0.0, "t10")       # passed through an explicit f16 rounding
+    check(got["t5"], ref["t5"], "bf16", 0.0, "t5")
+
+
+def test_execute_argument_errors():
+    import torch
+    spec = bias_gelu_dbias_graph(40, 64)
+    inp = make_inputs(spec)
+    g = B.Graph.from_spec(spec)
+    plan = B.Plan(g, "global")
+    dev_in = [B.to_device(inp[t.name], t.dtype) for t in spec.inputs]
+    dev_out = B.alloc_outputs(spec)
+    with pytest.raises(B.FsError) as e:
+        plan.execute(dev_in, dev_out, None)
+    assert e.value.code == -7                                 # FS_ERR_WORKSPACE
+    ws = plan.make_workspace()
+    with pytest.raises(B.FsError) as e:
+        plan.execute_ptrs([t.data_ptr() for t in dev_in], [dev_out[0].data_ptr() + 2, dev_out[1].data_ptr()],
+                          ws.data_ptr(), ws.numel(), torch.cuda.current_stream().cuda_stream)
+    assert e.value.code == -8                                 # FS_ERR_ALIGN
+    plan.execute(dev_in, dev_out, ws)                         # still works afterwards
+    torch.cuda.synchronize()
