@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Benchmark of the stitched hot path on one MI355X.
+
+Headline workload (benchmark configs[1]): residual add + bias + LayerNorm,
+x,res fp32 [8192,768] -> bf16, one stitched kernel per step.  A step is one pass of the
+whole subgraph over one batch.  Inputs are resident in HBM before the timed region;
+the step rotates through enough independent buffer sets that no set is still in the
+256 MB Infinity Cache when its turn comes again (cold-HBM rule).
+
+Prints ONE JSON line: metric/value = achieved GB/s on the subgraph's minimum traffic
+(each input read once + each output written once), plus `roofline`, `cpu_baseline`
+(the float64 per-op oracle timed on this machine's host) and, for context, the other four
+configurations, the per-op GPU baseline and a plain streaming copy.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+CACHE_BYTES = 256 << 20         # Infinity Cache; rotation footprint must be >= 2x this
+
+
+def _sets_needed(footprint: int) -> int:
+    return max(2, -(-2 * (CACHE_BYTES + (32 << 20)) // max(1, footprint)))
+
+
+class Runner:
+    """One plan + rotating device buffer sets."""
+
+    def __init__(self, spec, scheme="auto", seed=0, n_sets=None, host_inputs=None, **opts):
+        import torch
+        from paper_2009_10924_amd import binding as B
+        from workloads import make_inputs
+        self.torch, self.B, self.spec = torch, B, spec
+        self.graph = B.Graph.from_spec(spec)
+        self.plan = B.Plan(self.graph, scheme, **opts)
+        self.info = self.plan.info
+        self.host_inputs = host_inputs if host_inputs is not None else make_inputs(spec, seed)
+        first = [B.to_device(self.host_inputs[t.name], t.dtype) for t in spec.inputs]
+        footprint = self.info["bytes_min"] + self.info["workspace_bytes"]
+        self.n_sets = n_sets or min(_sets_needed(footprint), 4096)
+        self.inputs = [first] + [[t.clone() for t in first] for _ in range(self.n_sets - 1)]
+        self.outputs = [B.alloc_outputs(spec) for _ in range(self.n_sets)]
+        self.workspaces = [self.plan.make_workspace() for _ in range(self.n_sets)]
+        self.stream = torch.cuda.current_stream().cuda_stream
+        self._ptrs = [([t.data_ptr() for t in i], [t.data_ptr() for t in o],
+                       w.data_ptr() if w is not None else 0, w.numel() if w is not None else 0)
+                      for i, o, w in zip(self.inputs, self.outputs, self.workspaces)]
+        self.step_no = 0
+
+    def step(self):
+        i, o, w, wb = self._ptrs[self.step_no % self.n_sets]
+        self.plan.execute_ptrs(i, o, w, wb, self.stream)
+        self.step_no += 1
+
+    def time_region(self, steps, warmup):
+        """(wall seconds, event seconds) for `steps` back-to-back executes after `warmup` untimed ones."""
+        torch = self.torch
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        e0.record()
+        for _ in range(steps):
+            self.step()
+        e1.record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        return wall, e0.elapsed_time(e1) * 1e-3
+
+    def per_launch_events(self, steps):
+        """Average over `steps` of an event pair around each single execute (includes the pair's own overhead)."""
+        torch = self.torch
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+        for a, b in pairs:
+            a.record()
+            self.step()
+            b.record()
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) * 1e-3 for a, b in pairs)
+        return sum(ts) / len(ts), ts[len(ts) // 2], ts[0]
+
+
+def copy_ceiling(steps=50, nbytes=1 << 30):
+    """GB/s (read+write) of the library's plain streaming copy over buffers far larger than the caches."""
+    import torch
+    from paper_2009_10924_amd import binding as B
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    dst = torch.empty_like(src)
+    src.fill_(1)
+    for _ in range(3):
+        B.stream_copy(dst, src)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        B.stream_copy(dst, src)
+    e1.record()
+    torch.cuda.synchronize()
+    sec = e0.elapsed_time(e1) * 1e-3 / steps
+    return 2 * nbytes / sec / 1e9
+
+
+def time_oracle(spec, host_inputs, min_seconds=10.0, max_repeats=50):
+    """Wall-clock of the float64 per-op oracle on this host (single-threaded numpy kernels)."""
+    from oracle import oracle as O
+    O.evaluate(spec, host_inputs)                 # untimed warm pass
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        O.evaluate(spec, host_inputs)
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt >= min_seconds or reps >= max_repeats:
+            return dt / reps, reps
+
+
+def measure_config(name, spec, steps, warmup, with_unfused=True):
+    r = Runner(spec, "auto")
+    wall, ev = r.time_region(steps, warmup)
+    sec = ev / steps
+    out = {
+        "workload": spec.name, "pattern": r.info["pattern"], "scheme": r.info["scheme"], "kernel": r.info["kernel"],
+        "n_kernels": r.info["n_kernels"], "bytes_min": r.info["bytes_min"], "us": sec * 1e6,
+        "GBps": r.info["bytes_min"] / sec / 1e9, "frac_of_peak": r.info["bytes_min"] / sec / 1e9 / HBM_PEAK_GBPS,
+        "predicted_us": r.info["predicted_us"], "buffer_sets": r.n_sets,
+    }
+    if with_unfused:
+        host = r.host_inputs
+        del r
+        u = Runner(spec, "unfused", host_inputs=host, n_sets=2)
+        _, evu = u.time_region(max(10, steps // 4), max(3, warmup // 4))
+        secu = evu / max(10, steps // 4)
+        out.update({"unfused_us": secu * 1e6, "unfused_kernels": u.info["n_kernels"],
+                    "unfused_bytes_model": u.info["bytes_moved_model"], "speedup_vs_unfused": secu / sec})
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=400)
+    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--no-context", action="store_true", help="skip the other configurations, copy ceiling and oracle timing")
+    ap.add_argument("--oracle-seconds", type=float, default=10.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (rows shard with no exchange; see the design document); use --gpus 1")
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the hot path has no CPU fallback")
+    torch.cuda.set_device(0)
+    from workloads import FULL_CONFIGS
+
+    spec = FULL_CONFIGS["C2"]()
+    r = Runner(spec, "auto")
+    bytes_min = r.info["bytes_min"]
+    wall, ev = r.time_region(args.steps, args.warmup)
+    sec_step = ev / args.steps
+    # one more pass with an event pair around every launch (upper bound of the kernel's own duration)
+    avg_pair, med_pair, min_pair = r.per_launch_events(min(args.steps, 200))
+    achieved = bytes_min / sec_step / 1e9
+
+    result = {
+        "metric": "achieved HBM GB/s (% of peak) per fused subgraph; speedup vs unfused per-op",
+        "value": achieved, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": sec_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "C2 residual add + bias + LayerNorm, x,res fp32 [8192,768] -> bf16, eps 1e-5, seed 0",
+                   "pattern": r.info["pattern"], "scheme": r.info["scheme"], "kernel": r.info["kernel"],
+                   "block": r.info["block"], "grid": r.info["grid"], "vgprs": r.info["vgprs"],
+                   "buffer_sets": r.n_sets, "cold_hbm_rotation_bytes": r.n_sets * bytes_min},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "algorithmic_bytes_per_launch": bytes_min, "us_per_launch_region": sec_step * 1e6,
+                     "us_per_launch_event_pair": {"avg": avg_pair * 1e6, "median": med_pair * 1e6, "min": min_pair * 1e6}},
+        "wall_ms_per_step": wall / args.steps * 1e3,
+    }
+    host_c2 = r.host_inputs
+    del r
+    torch.cuda.empty_cache()
+
+    if not args.no_context:
+        u = Runner(spec, "unfused", host_inputs=host_c2, n_sets=3)
+        _, evu = u.time_region(max(20, args.steps // 8), 5)
+        secu = evu / max(20, args.steps // 8)
+        result["unfused"] = {"us": secu * 1e6, "n_kernels": u.info["n_kernels"], "bytes_model": u.info["bytes_moved_model"],
+                             "speedup_stitched": secu / sec_step}
+        del u
+        torch.cuda.empty_cache()
+        result["copy_ceiling_GBps"] = copy_ceiling()
+        torch.cuda.empty_cache()
+        sec_o, reps = time_oracle(spec, host_c2, args.oracle_seconds)
+        threads = 1
+        result["cpu_baseline"] = {"value": bytes_min / sec_o / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+                                  "sample": f"full C2 batch [8192,768], {reps} repeats after one warm pass, {sec_o:.3f} s each",
+                                  "seconds_per_subgraph": sec_o, "host_cpus": os.cpu_count(),
+                                  "affinity": len(os.sched_getaffinity(0))}
+        others = {}
+        for name in ("C1", "C3", "C4", "C5"):
+            others[name] = measure_config(name, FULL_CONFIGS[name](), max(50, args.steps // 4), max(10, args.warmup // 2))
+            torch.cuda.empty_cache()
+        result["other_configs"] = others
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

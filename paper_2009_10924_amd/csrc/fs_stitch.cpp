@@ -4,6 +4,7 @@
 // inside the reuse scope they rely on (one wavefront's registers, one workgroup)
 // are simply not generated -- the paper's locality filter.
 #include <algorithm>
+#include <cmath>
 #include <cstring>
 
 #include "fs_cost.hpp"
@@ -20,6 +21,22 @@ uint32_t pow2_at_least(uint32_t v) {
   return p;
 }
 int vec_of(int32_t dt) { return 16 / dtype_bytes(dt); }
+
+// Magic numbers for n / d, n < 2^31; checked on the spot against plain division.
+FastDiv make_fastdiv(uint32_t d) {
+  FastDiv f = {d == 0 ? 1u : d, 0u, 0u};
+  if (d <= 1) return f;
+  uint32_t l = 0;
+  while ((1ull << l) < d) ++l;
+  f.s = l - 1;
+  f.m = (uint32_t)(((1ull << (31 + l)) / d) + 1);
+  const uint32_t probes[] = {0u, 1u, d - 1, d, d + 1, 2 * d - 1, 2 * d, 0x7FFFFFFFu / d * d - 1, 0x7FFFFFFFu / d * d, 0x7FFFFFFFu};
+  for (uint32_t n : probes) {
+    const uint32_t q = (uint32_t)(((uint64_t)n * f.m) >> 32) >> f.s;
+    if (q != n / d) { f.m = 0; f.s = 0; f.d = 0; break; }   // d == 0 marks "unusable"; callers then offer no candidate
+  }
+  return f;
+}
 
 bool is_input(const fs_graph& g, int32_t t) { return t >= 0 && g.tensors[t].producer < 0; }
 bool same_dims(const Tensor& a, const Tensor& b) {
@@ -114,9 +131,9 @@ bool build_softmax(const fs_graph& g, std::vector<Candidate>* out) {
   p.rows = (uint32_t)(x.numel() / p.cols);
   p.scale = st.scalars.count(0) ? (float)st.scalars[0] : 1.0f;
   p.has_mask = has_mask;
-  p.od[0] = p.od[1] = p.od[2] = 1;
   p.ms[0] = p.ms[1] = p.ms[2] = 0;
-  for (int k = 0; k < x.rank - 1; ++k) p.od[3 - (x.rank - 1) + k] = (uint32_t)x.dims[k];
+  uint32_t od[3] = {1, 1, 1};
+  for (int k = 0; k < x.rank - 1; ++k) od[3 - (x.rank - 1) + k] = (uint32_t)x.dims[k];
   bool dtype_ok = p.in_dt == p.out_dt;
   if (has_mask) {
     const Tensor& m = g.tensors[st.tensors["M"]];
@@ -135,6 +152,32 @@ bool build_softmax(const fs_graph& g, std::vector<Candidate>* out) {
     }
   }
   if (!dtype_ok) return true;
+  // neighbouring outer axes over which the mask moves alike (both stretched, or both dense) merge,
+  // so the common [batch,1,1,keys] mask costs one division per row instead of two
+  {
+    uint32_t e[3], st[3];
+    int n = 0;
+    for (int k = 0; k < 3; ++k) {
+      if (od[k] == 1) continue;
+      if (n > 0 && ((st[n - 1] == 0 && p.ms[k] == 0) || (p.ms[k] != 0 && st[n - 1] == p.ms[k] * od[k]))) {
+        e[n - 1] *= od[k];
+        st[n - 1] = p.ms[k];
+      } else {
+        e[n] = od[k];
+        st[n] = p.ms[k];
+        ++n;
+      }
+    }
+    for (int k = 0; k < 3; ++k) {
+      const int src = k - (3 - n);
+      od[k] = src >= 0 ? e[src] : 1;
+      p.ms[k] = src >= 0 ? st[src] : 0;
+    }
+  }
+  for (int k = 0; k < 3; ++k) {
+    p.od[k] = make_fastdiv(od[k]);
+    if (p.od[k].d == 0) return true;
+  }
 
   const int VEC = vec_of(p.in_dt);
   const int esz = dtype_bytes(p.in_dt);
@@ -482,47 +525,80 @@ bool build_gelu(const fs_graph& g, std::vector<Candidate>* out) {
   const uint32_t tile_cols = 64 * VEC;
   const uint32_t n_col_tiles = (p.cols + tile_cols - 1) / tile_cols;
   const int64_t counter_bytes = ((int64_t)n_col_tiles * 4 + 255) / 256 * 256;
-  for (uint32_t rpb : {32u, 64u, 128u, 256u, 512u}) {
-    if (rpb > 32 && rpb >= 2 * p.rows) continue;
-    Candidate c = make_candidate(g, "bias_gelu_dbias", FS_SCHEME_GLOBAL, K_BIAS_GELU_DBIAS);
-    Launch& l = c.launches.front();
-    GeluP q = p;
-    q.rows_per_block = rpb;
-    q.n_row_tiles = (p.rows + rpb - 1) / rpb;
-    q.col_tile = tile_cols;
-    l.args.u.gelu = q;
-    l.ptr[0] = in_ref(g, tx);
-    l.ptr[1] = in_ref(g, tb);
-    l.ptr[2] = in_ref(g, tg);
-    l.ptr[3] = out_ref(y.output_slot);
-    l.ptr[4] = out_ref(d.output_slot);
-    l.ptr[5] = ws_ref(counter_bytes);
-    l.ptr[6] = ws_ref(0);
-    l.shape.block[0] = 512;
-    l.shape.grid[0] = q.n_row_tiles * n_col_tiles;
-    c.info.workspace_bytes = counter_bytes + (int64_t)q.n_row_tiles * p.cols * 4;
-    c.info.rows_per_block = (int32_t)rpb;
-    c.info.vecs_per_lane = 1;
-    c.info.lanes_per_row = 64;
-    c.info.lds_bytes = 8 * (int32_t)tile_cols * 4 + 4;
-    c.info.bytes_moved_model = c.info.bytes_min + 2ll * q.n_row_tiles * p.cols * 4;
-    KernelCost kc;
-    kc.hbm_bytes = 3 * n * esz + 2.0 * q.n_row_tiles * p.cols * 4;
-    kc.elems = n;
-    kc.valu_per_elem = 16 + (esz == 2 ? 3 : 0);
-    kc.trans_per_elem = 2;
-    kc.waves_per_block = 8;
-    kc.waves = (double)l.shape.grid[0] * 8;
-    kc.bytes_in_flight_per_lane = 64;
-    kc.vgpr_estimate = 64;
-    kc.barriers = 3;
-    kc.lds_bytes_per_block = c.info.lds_bytes;
-    kc.serial_tail_s = (double)q.n_row_tiles / 8.0 * device().mem_latency_s * 0.5;   // last workgroup folds the partials
-    kc.rows_per_wave_loop = (double)rpb / 8.0;
-    char var[32];
-    snprintf(var, sizeof var, "<%s,R%u>", dtype_name(p.dt), rpb);
-    finish_candidate(&c, var, kc);
-    out->push_back(c);
+  struct Shape { int waves, unroll; };
+  for (int ticket = 0; ticket < 2; ++ticket) {
+    for (Shape sh : {Shape{4, 4}, Shape{4, 8}, Shape{8, 4}}) {
+      const uint32_t tile_rows = sh.waves * sh.unroll;
+      const uint32_t max_rb = (p.rows + tile_rows - 1) / tile_rows;
+      uint32_t last_rb = 0;
+      for (uint32_t want : {64u, 128u, 256u}) {
+        // enough workgroups to fill the chip, few enough that the partials stay small
+        const uint32_t n_rb = std::min(max_rb, std::max<uint32_t>(1, want * 6 / n_col_tiles));
+        if (n_rb == last_rb) continue;
+        last_rb = n_rb;
+        Candidate c = make_candidate(g, "bias_gelu_dbias", FS_SCHEME_GLOBAL, K_BIAS_GELU_DBIAS);
+        GeluP q = p;
+        q.n_row_tiles = n_rb;
+        q.waves = sh.waves;
+        q.unroll = sh.unroll;
+        q.ticket = ticket;
+        {
+          Launch& l = c.launches.front();
+          l.args.u.gelu = q;
+          l.ptr[0] = in_ref(g, tx);
+          l.ptr[1] = in_ref(g, tb);
+          l.ptr[2] = in_ref(g, tg);
+          l.ptr[3] = out_ref(y.output_slot);
+          l.ptr[4] = out_ref(d.output_slot);
+          l.ptr[5] = ws_ref(counter_bytes);
+          l.ptr[6] = ws_ref(0);
+          l.shape.block[0] = sh.waves * 64;
+          l.shape.grid[0] = n_rb * n_col_tiles;
+        }
+        if (!ticket) {
+          c.launches.emplace_back();
+          Launch& f = c.launches.back();
+          f.kernel = K_COLFOLD;
+          f.args.u.gelu = q;
+          f.ptr[0] = ws_ref(counter_bytes);
+          f.ptr[1] = out_ref(d.output_slot);
+          f.shape.block[0] = 1024;
+          f.shape.grid[0] = (p.cols / 4 + 63) / 64;
+          c.info.n_kernels = 2;
+        }
+        c.info.workspace_bytes = counter_bytes + (int64_t)n_rb * p.cols * 4;
+        c.info.rows_per_block = (int32_t)tile_rows;
+        c.info.vecs_per_lane = sh.unroll;
+        c.info.lanes_per_row = 64;
+        c.info.lds_bytes = sh.waves * (int32_t)tile_cols * 4 + 4;
+        c.info.bytes_moved_model = c.info.bytes_min + 2ll * n_rb * p.cols * 4;
+        KernelCost kc;
+        kc.hbm_bytes = 3 * n * esz + 2.0 * n_rb * p.cols * 4;
+        kc.elems = n;
+        kc.valu_per_elem = 13 + (esz == 2 ? 1 : 0);
+        kc.trans_per_elem = 2;
+        kc.waves_per_block = sh.waves;
+        kc.waves = (double)n_rb * n_col_tiles * sh.waves;
+        kc.bytes_in_flight_per_lane = 32.0 * sh.unroll;
+        kc.vgpr_estimate = 40 + 8 * sh.unroll;
+        kc.barriers = ticket ? 5 : 1;
+        kc.lds_bytes_per_block = c.info.lds_bytes;
+        kc.rows_per_wave_loop = std::max(1.0, (double)p.rows / ((double)n_rb * tile_rows));
+        kc.dep_phases = 1;
+        // the fold: a second launch spread over the chip, or one workgroup per column tile
+        // reading n_rb partial rows with (threads / column quads) row groups in parallel
+        if (ticket) {
+          const double groups = std::max(1.0, sh.waves * 64.0 / (tile_cols / 4.0));
+          kc.serial_tail_s = device().mem_latency_s * (2.0 + std::ceil(n_rb / groups / 8.0));
+        } else {
+          kc.serial_tail_s = device().launch_s + device().mem_latency_s * (1.0 + std::ceil(n_rb / 16.0 / 8.0)) * 0.5;
+        }
+        char var[48];
+        snprintf(var, sizeof var, "<%s,W%d,U%d,RB%u,%s>", dtype_name(p.dt), sh.waves, sh.unroll, n_rb, ticket ? "ticket" : "fold");
+        finish_candidate(&c, var, kc);
+        out->push_back(c);
+      }
+    }
   }
   return true;
 }
@@ -558,9 +634,14 @@ bool build_tchain(const fs_graph& g, std::vector<Candidate>* out) {
       const uint32_t L = pow2_at_least((nvec + K - 1) / K);
       if (L > 64) continue;
       if (K > 1 && (uint64_t)L * K >= 2ull * nvec) continue;
-      for (uint32_t s_tile : {4u, 8u, 16u}) {
-        if (s_tile > 4 && s_tile >= 2 * p.S) continue;
-        const int64_t lds_bytes = lds ? (int64_t)s_tile * p.H * (p.D + 4) * 4 : 0;
+      const uint32_t groups = 256 / L;
+      for (uint32_t s_tile : {1u, 2u, 3u, 4u, 6u, 8u, 12u, 16u}) {
+        if (s_tile > 1 && s_tile >= 2 * p.S) continue;
+        const uint32_t tile_rows = s_tile * p.H;
+        const uint32_t passes = (tile_rows + groups - 1) / groups;
+        if (passes > 4 || passes * K > 8) continue;
+        if ((double)tile_rows / (passes * groups) < 0.7 && s_tile > 1) continue;   // too many idle lane groups
+        const int64_t lds_bytes = lds ? (int64_t)tile_rows * (p.D + 4) * 4 : 0;
         if (lds_bytes > 64 * 1024) continue;
         Candidate c = make_candidate(g, "transpose_chain", lds ? FS_SCHEME_LDS : (L == 1 ? FS_SCHEME_LOCAL : FS_SCHEME_WAVE),
                                      lds ? K_TCHAIN_LDS : K_TCHAIN_WAVE);
@@ -569,6 +650,7 @@ bool build_tchain(const fs_graph& g, std::vector<Candidate>* out) {
         q.lanes_per_row = (int32_t)L;
         q.vecs_per_lane = K;
         q.s_tile = (int32_t)s_tile;
+        q.passes = (int32_t)passes;
         l.args.u.tchain = q;
         l.ptr[0] = in_ref(g, tx);
         l.ptr[1] = in_ref(g, ts);
@@ -578,7 +660,7 @@ bool build_tchain(const fs_graph& g, std::vector<Candidate>* out) {
         l.shape.lds_bytes = (uint32_t)lds_bytes;
         c.info.lanes_per_row = (int32_t)L;
         c.info.vecs_per_lane = K;
-        c.info.rows_per_block = (int32_t)(s_tile * p.H);
+        c.info.rows_per_block = (int32_t)tile_rows;
         c.info.lds_bytes = (int32_t)lds_bytes;
         KernelCost kc;
         kc.hbm_bytes = 2 * n * esz;
@@ -587,20 +669,19 @@ bool build_tchain(const fs_graph& g, std::vector<Candidate>* out) {
         kc.trans_per_elem = 0;
         kc.waves_per_block = 4;
         kc.waves = (double)l.shape.grid[0] * 4;
-        const double passes = std::max(1.0, (double)s_tile * p.H / (256.0 / L));
-        kc.rows_per_wave_loop = passes;
-        kc.bytes_in_flight_per_lane = 16.0 * K;
-        kc.vgpr_estimate = 24 + K * VEC;
+        kc.rows_per_wave_loop = 1;
+        kc.bytes_in_flight_per_lane = 16.0 * K * passes;
+        kc.vgpr_estimate = 16 + K * VEC * (int)passes * 2;
         int steps = 0;
         for (uint32_t t = 1; t < L; t <<= 1) ++steps;
-        kc.xlane_steps = steps;
+        kc.xlane_steps = steps * (int)passes;
         kc.barriers = lds ? 1 : 0;
         kc.lds_bytes_per_block = (int32_t)lds_bytes;
         kc.lds_traffic_bytes = lds ? 2 * n * 4 : 0;
         kc.store_run_bytes = lds ? (double)s_tile * p.D * esz : (double)p.D * esz;
-        kc.lane_utilisation = (double)nvec / ((double)L * K);
-        char var[40];
-        snprintf(var, sizeof var, "<%s,K%d,L%u,S%u>", dtype_name(p.dt), K, L, s_tile);
+        kc.lane_utilisation = (double)nvec / ((double)L * K) * (double)tile_rows / (passes * groups);
+        char var[48];
+        snprintf(var, sizeof var, "<%s,K%d,L%u,S%u,P%u>", dtype_name(p.dt), K, L, s_tile, passes);
         finish_candidate(&c, var, kc);
         out->push_back(c);
       }

@@ -79,6 +79,57 @@ __device__ __forceinline__ void store_vec(f16_t* p, const float (&v)[8]) {
   u32x4 t = {pack_f16(v[0], v[1]), pack_f16(v[2], v[3]), pack_f16(v[4], v[5]), pack_f16(v[6], v[7])};
   *reinterpret_cast<u32x4*>(p) = t;
 }
+// ---- raw 128-bit access with a streaming (non-temporal) hint ------------------------
+// Inputs read once and outputs written once should not displace the small operands
+// (bias, gamma, mask) that every row re-reads from cache.  A kernel first issues all
+// its raw loads, then unpacks: the loads stay independent of any arithmetic and of
+// each other, so they are all in flight together.
+template <typename T>
+__device__ __forceinline__ u32x4 load_raw_nt(const T* p) {
+  return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+}
+template <typename T>
+__device__ __forceinline__ u32x4 load_raw(const T* p) {
+  return *reinterpret_cast<const u32x4*>(p);
+}
+__device__ __forceinline__ void unpack(u32x4 t, float (&v)[4], const float*) {
+  // the whole vector is re-typed first: bit-casting a single vector element (an lvalue
+  // like t.y) is miscompiled by this toolchain into a read of element 0
+  const f32x4 f = __builtin_bit_cast(f32x4, t);
+  v[0] = f.x; v[1] = f.y; v[2] = f.z; v[3] = f.w;
+}
+__device__ __forceinline__ void unpack(u32x4 t, float (&v)[8], const bf16_t*) {
+  v[0] = __builtin_bit_cast(float, t.x << 16); v[1] = __builtin_bit_cast(float, t.x & 0xFFFF0000u);
+  v[2] = __builtin_bit_cast(float, t.y << 16); v[3] = __builtin_bit_cast(float, t.y & 0xFFFF0000u);
+  v[4] = __builtin_bit_cast(float, t.z << 16); v[5] = __builtin_bit_cast(float, t.z & 0xFFFF0000u);
+  v[6] = __builtin_bit_cast(float, t.w << 16); v[7] = __builtin_bit_cast(float, t.w & 0xFFFF0000u);
+}
+__device__ __forceinline__ void unpack(u32x4 t, float (&v)[8], const f16_t*) {
+  unpack_f16(t.x, v[0], v[1]); unpack_f16(t.y, v[2], v[3]);
+  unpack_f16(t.z, v[4], v[5]); unpack_f16(t.w, v[6], v[7]);
+}
+__device__ __forceinline__ void store_vec_nt(float* p, const float (&v)[4]) {
+  f32x4 t = {v[0], v[1], v[2], v[3]};
+  __builtin_nontemporal_store(t, reinterpret_cast<f32x4*>(p));
+}
+__device__ __forceinline__ void store_vec_nt(bf16_t* p, const float (&v)[8]) {
+  u32x4 t = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7])};
+  __builtin_nontemporal_store(t, reinterpret_cast<u32x4*>(p));
+}
+__device__ __forceinline__ void store_vec_nt(f16_t* p, const float (&v)[8]) {
+  u32x4 t = {pack_f16(v[0], v[1]), pack_f16(v[2], v[3]), pack_f16(v[4], v[5]), pack_f16(v[6], v[7])};
+  __builtin_nontemporal_store(t, reinterpret_cast<u32x4*>(p));
+}
+__device__ __forceinline__ void store_vec4_nt(float* p, const float (&v)[4]) { store_vec_nt(p, v); }
+__device__ __forceinline__ void store_vec4_nt(bf16_t* p, const float (&v)[4]) {
+  u32x2 t = {pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3])};
+  __builtin_nontemporal_store(t, reinterpret_cast<u32x2*>(p));
+}
+__device__ __forceinline__ void store_vec4_nt(f16_t* p, const float (&v)[4]) {
+  u32x2 t = {pack_f16(v[0], v[1]), pack_f16(v[2], v[3])};
+  __builtin_nontemporal_store(t, reinterpret_cast<u32x2*>(p));
+}
+
 // 4-element (64-bit) access for 16-bit types, used when a float32 vector of 4 pairs with them.
 __device__ __forceinline__ void load_vec4(const float* p, float (&v)[4]) { load_vec(p, v); }
 __device__ __forceinline__ void load_vec4(const bf16_t* p, float (&v)[4]) {
@@ -98,6 +149,12 @@ __device__ __forceinline__ void store_vec4(bf16_t* p, const float (&v)[4]) {
 __device__ __forceinline__ void store_vec4(f16_t* p, const float (&v)[4]) {
   u32x2 t = {pack_f16(v[0], v[1]), pack_f16(v[2], v[3])};
   *reinterpret_cast<u32x2*>(p) = t;
+}
+
+// ---- division by a run-time constant (see fs::FastDiv) -------------------------------
+template <typename FD>
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, const FD& f) {
+  return f.d == 1 ? n : (__umulhi(n, f.m) >> f.s);
 }
 
 // ---- math ---------------------------------------------------------------------
@@ -140,14 +197,24 @@ __device__ __forceinline__ float dpp_move(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
 }
 
+__device__ __forceinline__ float read_lane(float v, int lane) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+
 template <typename OP>
 __device__ __forceinline__ float group_allreduce(float v, int lanes) {
   if (lanes > 1) v = OP::apply(v, dpp_move<0xB1>(v));    // quad_perm [1,0,3,2]  : lane ^ 1
   if (lanes > 2) v = OP::apply(v, dpp_move<0x4E>(v));    // quad_perm [2,3,0,1]  : lane ^ 2
   if (lanes > 4) v = OP::apply(v, dpp_move<0x141>(v));   // row_half_mirror      : other quad of the 8
   if (lanes > 8) v = OP::apply(v, dpp_move<0x140>(v));   // row_mirror           : other half of the 16
-  if (lanes > 16) v = OP::apply(v, __shfl_xor(v, 16));
-  if (lanes > 32) v = OP::apply(v, __shfl_xor(v, 32));
+  if (lanes > 16) {
+    // every 16-lane row now holds its own total in all lanes: combine rows through
+    // scalar registers (v_readlane), which costs no LDS-crossbar round trip.
+    const float lo = OP::apply(read_lane(v, 0), read_lane(v, 16));
+    const float hi = OP::apply(read_lane(v, 32), read_lane(v, 48));
+    if (lanes > 32) v = OP::apply(lo, hi);
+    else v = (threadIdx.x & 32u) ? hi : lo;
+  }
   return v;
 }
 

@@ -6,11 +6,12 @@
 //
 // The column reduction needs rows owned by other workgroups, which the paper's
 // schemes exclude (Section 4.1, last paragraph: no inter-block communication).  Here
-// it is one round trip through device memory: every workgroup writes its column
-// partials to a [n_row_tiles, cols] float32 workspace, takes a ticket from a per
-// column-tile counter, and the workgroup that draws the last ticket folds the
-// partials in row-tile order.  The fold order is fixed, so results are bit-identical
-// from run to run, and the counter is left at zero for the next launch.
+// it is one round trip through device memory: every workgroup leaves its column
+// partials in a [n_row_blocks, cols] float32 workspace, and the partials are folded in
+// row-block order (fixed order: results are bit-identical from run to run) either
+//   * by a second, tiny launch (k_colfold) -- the kernel boundary is the hand-off; or
+//   * inside the same launch by the workgroup that draws the last ticket of its
+//     column tile from a counter in the workspace (the counter is left at zero).
 #include <hip/hip_runtime.h>
 
 #include "device_utils.hpp"
@@ -29,81 +30,75 @@ __global__ void __launch_bounds__(256) k_bias_gelu(const T* __restrict__ x, cons
   const uint32_t vi = blockIdx.x * 256u + threadIdx.x;
   if (vi >= n_vec) return;
   const uint32_t cv = vi % vecs_per_row;
+  const u32x4 rx = load_raw_nt(x + (size_t)vi * VEC);
+  const u32x4 rb = load_raw(bias + cv * VEC);
   float v[VEC], b[VEC];
-  load_vec(x + (size_t)vi * VEC, v);
-  load_vec(bias + cv * VEC, b);
+  unpack(rx, v, (const T*)nullptr);
+  unpack(rb, b, (const T*)nullptr);
 #pragma unroll
   for (int e = 0; e < VEC; ++e) v[e] = gelu_fwd(v[e] + b[e]);
-  store_vec(y + (size_t)vi * VEC, v);
+  store_vec_nt(y + (size_t)vi * VEC, v);
 }
 
-// ---- bias + GELU forward + bias-gradient column sum --------------------------------
-// Workgroup = WAVES wavefronts over one tile of rows_per_block rows x (64*VEC) columns.
-// Lane l of every wave owns columns [l*VEC, l*VEC+VEC) of the tile; wave w walks rows
-// w, w+WAVES, ... of the tile, so each wave-wide access is 1 KB contiguous.
-template <typename T, int WAVES>
+// y = gelu(z) and acc += g * gelu'(z) with shared sub-expressions:
+//   t = -2c log2(e) (1 + a z^2);  e = 2^(z t) = exp(-2u);  s = 1/(1+e);  y = z s
+//   gelu' = s + z s (1-s) d(2u)/dz,   d(2u)/dz = 2c (1 + 3 a z^2)
+__device__ __forceinline__ float gelu_and_grad(float z, float g, float& acc) {
+  constexpr float c = 0.7978845608028654f, a = 0.044715f;
+  constexpr float k = -2.0f * c * kLog2e;
+  const float z2 = z * z;
+  const float t = __builtin_fmaf(k * a, z2, k);
+  const float s = fast_rcp(1.0f + __builtin_amdgcn_exp2f(z * t));
+  const float y = z * s;
+  const float dw = __builtin_fmaf(6.0f * c * a, z2, 2.0f * c);
+  acc = __builtin_fmaf(g, __builtin_fmaf(__builtin_fmaf(-y, s, y), dw, s), acc);
+  return y;
+}
+
+// ---- bias + GELU forward + bias-gradient column partials ------------------------------
+// Workgroup (ct, rb): column tile ct of 64*VEC columns, row tiles rb, rb + n_rb, ... of
+// WAVES*UNROLL rows each.  Lane l owns columns [l*VEC, l*VEC+VEC) of the tile, wave w
+// rows w, w+WAVES, ... of a row tile, so every wave-wide access is one contiguous
+// 1 KB piece, and at any moment the resident workgroups sweep one band of rows
+// (DRAM pages stay open) while each keeps its column sums in registers.
+template <typename T, int WAVES, int UNROLL, bool TICKET>
 __global__ void __launch_bounds__(WAVES * 64) k_bias_gelu_dbias(const T* __restrict__ x, const T* __restrict__ bias,
                                                                 const T* __restrict__ grad, T* __restrict__ y,
                                                                 float* __restrict__ dbias, float* __restrict__ partials,
                                                                 uint32_t* __restrict__ counters, GeluP p) {
   constexpr int VEC = Elem<T>::VEC;
-  constexpr int TILE_COLS = 64 * VEC;
+  constexpr int TILE_COLS = 64 * VEC, NT = WAVES * 64, TILE_ROWS = WAVES * UNROLL;
   __shared__ float red[WAVES][TILE_COLS];
-  __shared__ uint32_t ticket;
   const uint32_t n_col_tiles = (p.cols + TILE_COLS - 1) / TILE_COLS;
-  const uint32_t ct = blockIdx.x % n_col_tiles;
-  const uint32_t rt = blockIdx.x / n_col_tiles;
+  const uint32_t rb = blockIdx.x / n_col_tiles;
+  const uint32_t ct = blockIdx.x - rb * n_col_tiles;
   const uint32_t lane = threadIdx.x & 63u, wave = threadIdx.x >> 6;
-  const uint32_t col = ct * TILE_COLS + lane * VEC;
-  const bool col_ok = col < p.cols;              // cols is a multiple of VEC
-  const uint32_t r_begin = rt * p.rows_per_block;
-  const uint32_t r_end = min(r_begin + p.rows_per_block, p.rows);
+  const uint32_t col = min(ct * TILE_COLS + lane * VEC, p.cols - VEC);   // clamped lanes of a ragged tile redo valid columns
+  const bool col_ok = ct * TILE_COLS + lane * VEC < p.cols;
 
-  float acc[VEC];
+  float acc[VEC], b[VEC];
 #pragma unroll
   for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
-  if (col_ok) {
-    float b[VEC];
-    load_vec(bias + col, b);
-    constexpr uint32_t UNROLL = 2;
-    uint32_t r = r_begin + wave;
-    for (; r + (UNROLL - 1) * WAVES < r_end; r += UNROLL * WAVES) {
-      float xv[UNROLL][VEC], gv[UNROLL][VEC];
+  unpack(load_raw(bias + col), b, (const T*)nullptr);
+  for (uint32_t r0 = rb * TILE_ROWS; r0 < p.rows; r0 += p.n_row_tiles * TILE_ROWS) {
+    u32x4 rx[UNROLL], rg[UNROLL];
 #pragma unroll
-      for (uint32_t u = 0; u < UNROLL; ++u) {
-        const size_t off = (size_t)(r + u * WAVES) * p.cols + col;
-        load_vec(x + off, xv[u]);
-        load_vec(grad + off, gv[u]);
-      }
-#pragma unroll
-      for (uint32_t u = 0; u < UNROLL; ++u) {
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-          const float z = xv[u][e] + b[e];
-          float s, d;
-          gelu_parts(z, s, d);
-          const float zs = z * s;
-          xv[u][e] = zs;
-          acc[e] = __builtin_fmaf(gv[u][e], __builtin_fmaf(zs * (1.0f - s), d, s), acc[e]);
-        }
-        store_vec(y + (size_t)(r + u * WAVES) * p.cols + col, xv[u]);
-      }
+    for (int u = 0; u < UNROLL; ++u) {
+      const size_t off = (size_t)min(r0 + wave + u * WAVES, p.rows - 1) * p.cols + col;
+      rx[u] = load_raw_nt(x + off);
+      rg[u] = load_raw_nt(grad + off);
     }
-    for (; r < r_end; r += WAVES) {
-      float xv[VEC], gv[VEC];
-      const size_t off = (size_t)r * p.cols + col;
-      load_vec(x + off, xv);
-      load_vec(grad + off, gv);
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) {
-        const float z = xv[e] + b[e];
-        float s, d;
-        gelu_parts(z, s, d);
-        const float zs = z * s;
-        xv[e] = zs;
-        acc[e] = __builtin_fmaf(gv[e], __builtin_fmaf(zs * (1.0f - s), d, s), acc[e]);
+    for (int u = 0; u < UNROLL; ++u) {
+      const uint32_t r = r0 + wave + u * WAVES;
+      if (r < p.rows) {
+        float xv[VEC], gv[VEC];
+        unpack(rx[u], xv, (const T*)nullptr);
+        unpack(rg[u], gv, (const T*)nullptr);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) xv[e] = gelu_and_grad(xv[e] + b[e], gv[e], acc[e]);
+        if (col_ok) store_vec_nt(y + (size_t)r * p.cols + col, xv);
       }
-      store_vec(y + off, xv);
     }
   }
 
@@ -111,39 +106,79 @@ __global__ void __launch_bounds__(WAVES * 64) k_bias_gelu_dbias(const T* __restr
 #pragma unroll
   for (int e = 0; e < VEC; ++e) red[wave][lane * VEC + e] = acc[e];
   __syncthreads();
-  for (uint32_t c = threadIdx.x; c < TILE_COLS; c += WAVES * 64) {
+  for (uint32_t c = threadIdx.x; c < TILE_COLS; c += NT) {
     float s = red[0][c];
 #pragma unroll
     for (int w = 1; w < WAVES; ++w) s += red[w][c];
     const uint32_t gc = ct * TILE_COLS + c;
-    if (gc < p.cols) partials[(size_t)rt * p.cols + gc] = s;
-  }
-
-  // global step: publish, take a ticket, last workgroup of this column tile folds
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0)
-    ticket = __hip_atomic_fetch_add(&counters[ct], 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-  __syncthreads();
-  if (ticket != p.n_row_tiles - 1) return;
-  __threadfence();
-  for (uint32_t c = threadIdx.x; c < TILE_COLS; c += WAVES * 64) {
-    const uint32_t gc = ct * TILE_COLS + c;
-    if (gc >= p.cols) continue;
-    float s = 0.0f;
-    const float* src = partials + gc;
-    uint32_t t = 0;
-    for (; t + 8 <= p.n_row_tiles; t += 8) {
-      float q[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) q[u] = __builtin_nontemporal_load(src + (size_t)(t + u) * p.cols);
-#pragma unroll
-      for (int u = 0; u < 8; ++u) s += q[u];
+    if (gc < p.cols) {
+      float* dst = partials + (size_t)rb * p.cols + gc;
+      // TICKET: write through to device memory (agent-scope atomic store), so the
+      // folding workgroup, which may sit on another XCD with its own L2, can see it.
+      if (TICKET) __hip_atomic_store(dst, s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      else *dst = s;
     }
-    for (; t < p.n_row_tiles; ++t) s += __builtin_nontemporal_load(src + (size_t)t * p.cols);
-    dbias[gc] = s;
   }
-  if (threadIdx.x == 0) __hip_atomic_store(&counters[ct], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if constexpr (TICKET) {
+    // global step.  The barrier makes every lane's write-through store complete before
+    // lane 0 takes the ticket, so a full L2 write-back (what a release fence would cost
+    // on this multi-L2 part while the cache is full of freshly written y) is not needed.
+    __shared__ uint32_t ticket;
+    __syncthreads();
+    if (threadIdx.x == 0) ticket = __hip_atomic_fetch_add(&counters[ct], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    if (ticket != p.n_row_tiles - 1) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // drop stale cached lines before reading the partials
+    constexpr int NQ = TILE_COLS / 4, NG = NT / NQ;      // column quads x row groups; NG <= WAVES
+    const uint32_t quad = threadIdx.x % NQ, g = threadIdx.x / NQ;
+    const uint32_t qc = ct * TILE_COLS + quad * 4;
+    f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (qc < p.cols) {
+      const float* src = partials + qc;
+      for (uint32_t t = g; t < p.n_row_tiles; t += NG) s += *reinterpret_cast<const f32x4*>(src + (size_t)t * p.cols);
+    }
+    __syncthreads();
+    *reinterpret_cast<f32x4*>(&red[g][quad * 4]) = s;
+    __syncthreads();
+    for (uint32_t c = threadIdx.x; c < TILE_COLS; c += NT) {
+      float v = red[0][c];
+#pragma unroll
+      for (int k = 1; k < NG; ++k) v += red[k][c];
+      const uint32_t gc = ct * TILE_COLS + c;
+      if (gc < p.cols) dbias[gc] = v;
+    }
+    if (threadIdx.x == 0) __hip_atomic_store(&counters[ct], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
+
+// ---- fold of column partials: [n_rows, cols] float32 -> [cols] --------------------------
+// Workgroup = 64 column quads x 16 row groups; each thread sums its rows in order with
+// eight independent loads in flight, LDS folds the 16 groups in order.
+__global__ void __launch_bounds__(1024) k_colfold(const float* __restrict__ partials, float* __restrict__ out, GeluP p) {
+  __shared__ f32x4 sm[16][64];
+  const uint32_t q = threadIdx.x & 63u, g = threadIdx.x >> 6;
+  const uint32_t col = (blockIdx.x * 64u + q) * 4u;
+  const uint32_t n = p.n_row_tiles;
+  f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
+  if (col < p.cols) {
+    uint32_t t = g;
+    for (; t + 7 * 16 < n; t += 8 * 16) {
+      f32x4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x4*>(partials + (size_t)(t + u * 16) * p.cols + col);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; t < n; t += 16) s += *reinterpret_cast<const f32x4*>(partials + (size_t)t * p.cols + col);
+  }
+  sm[g][q] = s;
+  __syncthreads();
+  if (g == 0 && col < p.cols) {
+    f32x4 v = sm[0][q];
+#pragma unroll
+    for (int k = 1; k < 16; ++k) v += sm[k][q];
+    *reinterpret_cast<f32x4*>(out + col) = v;
+  }
 }
 
 }  // namespace fsk
@@ -151,19 +186,28 @@ __global__ void __launch_bounds__(WAVES * 64) k_bias_gelu_dbias(const T* __restr
 namespace fs {
 using namespace fsk;
 
+namespace {
+template <typename T, bool TICKET>
+const void* dbias_sym(int waves, int unroll) {
+  if (waves == 4 && unroll == 4) return (const void*)k_bias_gelu_dbias<T, 4, 4, TICKET>;
+  if (waves == 4 && unroll == 8) return (const void*)k_bias_gelu_dbias<T, 4, 8, TICKET>;
+  if (waves == 8 && unroll == 4) return (const void*)k_bias_gelu_dbias<T, 8, 4, TICKET>;
+  return nullptr;
+}
+template <typename T>
+const void* gelu_sym(int32_t kernel, const GeluP& p) {
+  if (kernel == K_BIAS_GELU) return (const void*)k_bias_gelu<T>;
+  return p.ticket ? dbias_sym<T, true>(p.waves, p.unroll) : dbias_sym<T, false>(p.waves, p.unroll);
+}
+}  // namespace
+
 const void* gelu_kernel_symbol(int32_t kernel, const KernelArgs& a) {
   const GeluP& p = a.u.gelu;
-  if (kernel == K_BIAS_GELU) {
-    switch (p.dt) {
-      case DT_F32: return (const void*)k_bias_gelu<float>;
-      case DT_F16: return (const void*)k_bias_gelu<f16_t>;
-      default: return (const void*)k_bias_gelu<bf16_t>;
-    }
-  }
+  if (kernel == K_COLFOLD) return (const void*)k_colfold;
   switch (p.dt) {
-    case DT_F32: return (const void*)k_bias_gelu_dbias<float, 8>;
-    case DT_F16: return (const void*)k_bias_gelu_dbias<f16_t, 8>;
-    default: return (const void*)k_bias_gelu_dbias<bf16_t, 8>;
+    case DT_F32: return gelu_sym<float>(kernel, p);
+    case DT_F16: return gelu_sym<f16_t>(kernel, p);
+    default: return gelu_sym<bf16_t>(kernel, p);
   }
 }
 

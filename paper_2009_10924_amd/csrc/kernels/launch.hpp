@@ -27,9 +27,16 @@ enum KernelId : int32_t {
   K_LAYERNORM_BLOCK,
   K_BIAS_GELU,         // p0 x, p1 bias, p2 y
   K_BIAS_GELU_DBIAS,   // p0 x, p1 bias, p2 grad, p3 y, p4 dbias, p5 partials, p6 counters
+  K_COLFOLD,           // p0 partials [n_row_tiles, cols] f32, p1 out [cols] f32
   K_TCHAIN_WAVE,       // p0 x, p1 scale, p2 out
   K_TCHAIN_LDS,
   K_COUNT
+};
+
+// Division of a 31-bit index by a run-time constant as multiply-high + shift:
+// q = n (d == 1), else q = mulhi(n, m) >> s with m = floor(2^(32+s) / d) + 1, s = ceil(log2 d) - 1.
+struct FastDiv {
+  uint32_t d, m, s;
 };
 
 struct LaunchShape {
@@ -75,7 +82,7 @@ struct SoftmaxP {
   int32_t in_dt, out_dt, mask_dt;
   int32_t has_mask, mask_inner;     // mask_inner: 1 if the mask varies along the row, 0 if one value per row
   uint32_t rows, cols;
-  uint32_t od[3];                   // outer extents of the row index (od[2] fastest), product = rows
+  FastDiv od[3];                    // outer extents of the row index (od[2] fastest), product = rows
   uint32_t ms[3];                   // mask element stride for each outer coordinate
   float scale;
   int32_t lanes_per_row, vecs_per_lane;
@@ -90,15 +97,16 @@ struct LayerNormP {
 struct GeluP {
   int32_t dt, bias_dt;              // x / grad / y share dt
   uint32_t rows, cols;
-  uint32_t rows_per_block;          // rows of one workgroup's tile
-  uint32_t n_row_tiles;
-  uint32_t col_tile;                // columns per workgroup
+  uint32_t n_row_tiles;             // row blocks = rows of the partials workspace
+  int32_t waves, unroll;            // workgroup = waves x 64 lanes; a row tile = waves * unroll rows
+  int32_t ticket;                   // 1: fold inside the launch (last ticket), 0: fold by K_COLFOLD
 };
 struct TChainP {
   int32_t dt, scale_dt;
   uint32_t B, S, H, D;              // input [B,S,H,D] -> output [B,H,S,D]
   float eps;
   int32_t lanes_per_row, vecs_per_lane, s_tile;
+  int32_t passes;                   // rows each lane group handles = ceil(s_tile * H / groups), 1..4
 };
 
 struct KernelArgs {

@@ -20,20 +20,20 @@ using namespace fs;
 // elements per lane per step, so the lane->column mapping is the same on both sides.
 template <typename TO, int N> struct StoreN;
 template <typename TO> struct StoreN<TO, 4> {
-  __device__ __forceinline__ static void run(TO* p, const float (&v)[4]) { store_vec4(p, v); }
+  __device__ __forceinline__ static void run(TO* p, const float (&v)[4]) { store_vec4_nt(p, v); }
 };
 template <> struct StoreN<float, 8> {
   __device__ __forceinline__ static void run(float* p, const float (&v)[8]) {
     float a[4] = {v[0], v[1], v[2], v[3]}, b[4] = {v[4], v[5], v[6], v[7]};
-    store_vec(p, a);
-    store_vec(p + 4, b);
+    store_vec_nt(p, a);
+    store_vec_nt(p + 4, b);
   }
 };
 template <> struct StoreN<f16_t, 8> {
-  __device__ __forceinline__ static void run(f16_t* p, const float (&v)[8]) { store_vec(p, v); }
+  __device__ __forceinline__ static void run(f16_t* p, const float (&v)[8]) { store_vec_nt(p, v); }
 };
 template <> struct StoreN<bf16_t, 8> {
-  __device__ __forceinline__ static void run(bf16_t* p, const float (&v)[8]) { store_vec(p, v); }
+  __device__ __forceinline__ static void run(bf16_t* p, const float (&v)[8]) { store_vec_nt(p, v); }
 };
 
 template <typename TI, typename TO, int K>
@@ -41,51 +41,60 @@ struct LnRow {
   static constexpr int VEC = Elem<TI>::VEC;
   float h[K][VEC];
 
+  // All loads are issued before any value is used; vectors past the row end and rows
+  // past the tensor end are clamped to a valid address and zeroed afterwards.
   __device__ __forceinline__ float load(const TI* __restrict__ x, const TI* __restrict__ res,
                                         const TI* __restrict__ bias, const LayerNormP& p, uint32_t row,
-                                        bool row_ok, uint32_t lane, uint32_t stride) {
+                                        uint32_t lane, uint32_t stride) {
     const uint32_t nvec = p.cols / VEC;
-    const size_t base = (size_t)row * p.cols;
+    const size_t base = (size_t)min(row, p.rows - 1) * p.cols;
+    u32x4 rx[K], rr[K], rb[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) rx[k] = load_raw_nt(x + base + min(lane + k * stride, nvec - 1) * VEC);
+    if (p.has_res) {
+#pragma unroll
+      for (int k = 0; k < K; ++k) rr[k] = load_raw_nt(res + base + min(lane + k * stride, nvec - 1) * VEC);
+    }
+    if (p.has_bias) {
+#pragma unroll
+      for (int k = 0; k < K; ++k) rb[k] = load_raw(bias + min(lane + k * stride, nvec - 1) * VEC);
+    }
     float sum = 0.0f;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      const uint32_t j = lane + k * stride;
-      if (row_ok && j < nvec) {
-        load_vec(x + base + j * VEC, h[k]);
-        if (p.has_res) {
-          float r[VEC];
-          load_vec(res + base + j * VEC, r);
+      unpack(rx[k], h[k], (const TI*)nullptr);
+      if (p.has_res) {
+        float r[VEC];
+        unpack(rr[k], r, (const TI*)nullptr);
 #pragma unroll
-          for (int e = 0; e < VEC; ++e) h[k][e] += r[e];
-        }
-        if (p.has_bias) {
-          float b[VEC];
-          load_vec(bias + j * VEC, b);
+        for (int e = 0; e < VEC; ++e) h[k][e] += r[e];
+      }
+      if (p.has_bias) {
+        float b[VEC];
+        unpack(rb[k], b, (const TI*)nullptr);
 #pragma unroll
-          for (int e = 0; e < VEC; ++e) h[k][e] += b[e];
-        }
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) sum += h[k][e];
-      } else {
+        for (int e = 0; e < VEC; ++e) h[k][e] += b[e];
+      }
+      if (lane + k * stride >= nvec) {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) h[k][e] = 0.0f;
       }
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) sum += h[k][e];
     }
     return sum;
   }
 
-  __device__ __forceinline__ float center(const LayerNormP& p, float mean, bool row_ok, uint32_t lane, uint32_t stride) {
+  __device__ __forceinline__ float center(const LayerNormP& p, float mean, uint32_t lane, uint32_t stride) {
     const uint32_t nvec = p.cols / VEC;
     float sq = 0.0f;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      const uint32_t j = lane + k * stride;
-      if (row_ok && j < nvec) {
+      const float m = (lane + k * stride < nvec) ? mean : 0.0f;   // padded slots stay exactly zero
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-          h[k][e] -= mean;
-          sq = __builtin_fmaf(h[k][e], h[k][e], sq);
-        }
+      for (int e = 0; e < VEC; ++e) {
+        h[k][e] -= m;
+        sq = __builtin_fmaf(h[k][e], h[k][e], sq);
       }
     }
     return sq;
@@ -96,22 +105,29 @@ struct LnRow {
                                          bool row_ok, uint32_t lane, uint32_t stride, float rstd) {
     const uint32_t nvec = p.cols / VEC;
     const size_t base = (size_t)row * p.cols;
+    u32x4 rg[K], rb[K];
+    if (p.has_affine) {
+#pragma unroll
+      for (int k = 0; k < K; ++k) {
+        const uint32_t j = min(lane + k * stride, nvec - 1);
+        rg[k] = load_raw(gamma + j * VEC);
+        rb[k] = load_raw(beta + j * VEC);
+      }
+    }
 #pragma unroll
     for (int k = 0; k < K; ++k) {
       const uint32_t j = lane + k * stride;
-      if (row_ok && j < nvec) {
-        if (p.has_affine) {
-          float g[VEC], b[VEC];
-          load_vec(gamma + j * VEC, g);
-          load_vec(beta + j * VEC, b);
+      if (p.has_affine) {
+        float g[VEC], b[VEC];
+        unpack(rg[k], g, (const TI*)nullptr);
+        unpack(rb[k], b, (const TI*)nullptr);
 #pragma unroll
-          for (int e = 0; e < VEC; ++e) h[k][e] = __builtin_fmaf(h[k][e] * rstd, g[e], b[e]);
-        } else {
+        for (int e = 0; e < VEC; ++e) h[k][e] = __builtin_fmaf(h[k][e] * rstd, g[e], b[e]);
+      } else {
 #pragma unroll
-          for (int e = 0; e < VEC; ++e) h[k][e] *= rstd;
-        }
-        StoreN<TO, VEC>::run(out + base + j * VEC, h[k]);
+        for (int e = 0; e < VEC; ++e) h[k][e] *= rstd;
       }
+      if (row_ok && j < nvec) StoreN<TO, VEC>::run(out + base + j * VEC, h[k]);
     }
   }
 };
@@ -128,8 +144,8 @@ __global__ void __launch_bounds__(256) k_layernorm_wave(const TI* __restrict__ x
   const bool row_ok = row < p.rows;
   const float inv_n = 1.0f / (float)p.cols;
   LnRow<TI, TO, K> r;
-  const float mean = group_allreduce<OpSum>(r.load(x, res, bias, p, row, row_ok, lane, L), L) * inv_n;
-  const float var = group_allreduce<OpSum>(r.center(p, mean, row_ok, lane, L), L) * inv_n;
+  const float mean = group_allreduce<OpSum>(r.load(x, res, bias, p, row, lane, L), L) * inv_n;
+  const float var = group_allreduce<OpSum>(r.center(p, mean, lane, L), L) * inv_n;
   r.finish(out, gamma, beta, p, row, row_ok, lane, L, fast_rsqrt(var + p.eps));
 }
 
@@ -146,9 +162,9 @@ __global__ void __launch_bounds__(256) k_layernorm_block(const TI* __restrict__ 
     LnRow<TI, TO, K> r;
     // two slot sets alternate between rows: a wave may start row i+1 while a slower
     // one still reads the slots of row i.
-    const float mean = block_allreduce<OpSum>(r.load(x, res, bias, p, row, true, threadIdx.x, blockDim.x),
+    const float mean = block_allreduce<OpSum>(r.load(x, res, bias, p, row, threadIdx.x, blockDim.x),
                                               slot_sum[it & 1], n_waves) * inv_n;
-    const float var = block_allreduce<OpSum>(r.center(p, mean, true, threadIdx.x, blockDim.x),
+    const float var = block_allreduce<OpSum>(r.center(p, mean, threadIdx.x, blockDim.x),
                                              slot_sq[it & 1], n_waves) * inv_n;
     r.finish(out, gamma, beta, p, row, true, threadIdx.x, blockDim.x, fast_rsqrt(var + p.eps));
   }

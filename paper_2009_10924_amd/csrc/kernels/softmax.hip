@@ -18,42 +18,52 @@
 namespace fsk {
 using namespace fs;
 
+// Loads the row segment of one lane.  Every load is issued before any value is used:
+// out-of-range vectors and rows are clamped to a valid address and blanked afterwards,
+// so no branch separates the loads and all of them are in flight together.
 template <typename T, int K, bool HAS_MASK>
 __device__ __forceinline__ void softmax_load(const T* __restrict__ x, const T* __restrict__ mask, const SoftmaxP& p,
-                                             uint32_t row, bool row_ok, uint32_t lane, uint32_t stride,
+                                             uint32_t row, uint32_t lane, uint32_t stride,
                                              float (&v)[K][Elem<T>::VEC]) {
   constexpr int VEC = Elem<T>::VEC;
   const uint32_t nvec = p.cols / VEC;
-  uint32_t moff = 0;
+  const uint32_t r = min(row, p.rows - 1);
+  const T* xr = x + (size_t)r * p.cols;
+  u32x4 raw[K], rawm[K];
+  float mscalar = 0.0f;
+#pragma unroll
+  for (int k = 0; k < K; ++k) raw[k] = load_raw_nt(xr + min(lane + k * stride, nvec - 1) * VEC);
   if constexpr (HAS_MASK) {
-    const uint32_t c2 = row % p.od[2];
-    const uint32_t r1 = row / p.od[2];
-    const uint32_t c1 = r1 % p.od[1];
-    const uint32_t c0 = r1 / p.od[1];
-    moff = c0 * p.ms[0] + c1 * p.ms[1] + c2 * p.ms[2];
+    const uint32_t r1 = fast_div(r, p.od[2]);
+    const uint32_t c2 = r - r1 * p.od[2].d;
+    const uint32_t c0 = fast_div(r1, p.od[1]);
+    const uint32_t c1 = r1 - c0 * p.od[1].d;
+    const T* mrow = mask + (c0 * p.ms[0] + c1 * p.ms[1] + c2 * p.ms[2]);
+    if (p.mask_inner) {
+#pragma unroll
+      for (int k = 0; k < K; ++k) rawm[k] = load_raw(mrow + min(lane + k * stride, nvec - 1) * VEC);
+    } else {
+      mscalar = load1(mrow);
+    }
   }
-  const T* xr = x + (size_t)row * p.cols;
 #pragma unroll
   for (int k = 0; k < K; ++k) {
-    const uint32_t j = lane + k * stride;
-    if (row_ok && j < nvec) {
-      load_vec(xr + j * VEC, v[k]);
-      if constexpr (HAS_MASK) {
-        float m[VEC];
-        if (p.mask_inner) {
-          load_vec(mask + moff + j * VEC, m);
-        } else {
-          const float s = load1(mask + moff);
-#pragma unroll
-          for (int e = 0; e < VEC; ++e) m[e] = s;
-        }
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) v[k][e] = v[k][e] * p.scale + m[e];
+    unpack(raw[k], v[k], (const T*)nullptr);
+    if constexpr (HAS_MASK) {
+      float m[VEC];
+      if (p.mask_inner) {
+        unpack(rawm[k], m, (const T*)nullptr);
       } else {
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) v[k][e] *= p.scale;
+        for (int e = 0; e < VEC; ++e) m[e] = mscalar;
       }
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) v[k][e] = v[k][e] * p.scale + m[e];
     } else {
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) v[k][e] *= p.scale;
+    }
+    if (lane + k * stride >= nvec) {
 #pragma unroll
       for (int e = 0; e < VEC; ++e) v[k][e] = -INFINITY;
     }
@@ -96,7 +106,7 @@ __device__ __forceinline__ void softmax_store(T* __restrict__ out, const Softmax
     if (row_ok && j < nvec) {
 #pragma unroll
       for (int e = 0; e < VEC; ++e) v[k][e] *= inv;
-      store_vec(orow + j * VEC, v[k]);
+      store_vec_nt(orow + j * VEC, v[k]);
     }
   }
 }
@@ -112,7 +122,7 @@ __global__ void __launch_bounds__(256) k_softmax_wave(const T* __restrict__ x, c
   const uint32_t row = blockIdx.x * (256u / L) + group;
   const bool row_ok = row < p.rows;
   float v[K][VEC];
-  softmax_load<T, K, HAS_MASK>(x, mask, p, row, row_ok, lane, L, v);
+  softmax_load<T, K, HAS_MASK>(x, mask, p, row, lane, L, v);
   const float m = group_allreduce<OpMax>(local_max<K, VEC>(v), L);
   const float s = group_allreduce<OpSum>(exp_and_sum<K, VEC>(v, m), L);
   softmax_store<T, K>(out, p, row, row_ok, lane, L, v, fast_rcp(s));
@@ -127,7 +137,7 @@ __global__ void __launch_bounds__(256) k_softmax_block(const T* __restrict__ x, 
   const uint32_t row = blockIdx.x;
   const uint32_t n_waves = blockDim.x >> 6;
   float v[K][VEC];
-  softmax_load<T, K, HAS_MASK>(x, mask, p, row, true, threadIdx.x, blockDim.x, v);
+  softmax_load<T, K, HAS_MASK>(x, mask, p, row, threadIdx.x, blockDim.x, v);
   const float m = block_allreduce<OpMax>(local_max<K, VEC>(v), slot_max, n_waves);
   const float s = block_allreduce<OpSum>(exp_and_sum<K, VEC>(v, m), slot_sum, n_waves);
   softmax_store<T, K>(out, p, row, true, threadIdx.x, blockDim.x, v, fast_rcp(s));
@@ -141,9 +151,9 @@ __global__ void __launch_bounds__(256) k_softmax_generic(const T* __restrict__ x
   const uint32_t row = blockIdx.x;
   uint32_t moff = 0;
   if (p.has_mask) {
-    const uint32_t c2 = row % p.od[2];
-    const uint32_t r1 = row / p.od[2];
-    moff = (r1 / p.od[1]) * p.ms[0] + (r1 % p.od[1]) * p.ms[1] + c2 * p.ms[2];
+    const uint32_t r1 = fast_div(row, p.od[2]);
+    const uint32_t c0 = fast_div(r1, p.od[1]);
+    moff = c0 * p.ms[0] + (r1 - c0 * p.od[1].d) * p.ms[1] + (row - r1 * p.od[2].d) * p.ms[2];
   }
   const T* xr = x + (size_t)row * p.cols;
   auto value = [&](uint32_t c) {

@@ -16,35 +16,59 @@
 namespace fsk {
 using namespace fs;
 
-template <typename T, int K>
-__device__ __forceinline__ void tchain_row(const T* __restrict__ xrow, float scale, float eps, uint32_t lane,
-                                           uint32_t L, uint32_t nvec, bool ok, float (&v)[K][Elem<T>::VEC]) {
-  constexpr int VEC = Elem<T>::VEC;
-  float ss = 0.0f;
+// One workgroup owns the [s_tile, H] slab of rows at (b, s0); lane group g handles rows
+// g, g + groups, ... (input order, so a wavefront reads consecutive rows).  PASSES rows
+// per lane group are loaded up front so that all loads are in flight together; rows
+// past the slab are clamped to its last row and dropped at the store.
+template <typename T, int K, int PASSES>
+struct TChainTile {
+  static constexpr int VEC = Elem<T>::VEC;
+  float v[PASSES][K][VEC];
+  uint32_t sl[PASSES], h[PASSES];
+  bool ok[PASSES];
+
+  __device__ __forceinline__ void run(const T* __restrict__ x, const T* __restrict__ scale, const TChainP& p,
+                                      uint32_t b, uint32_t s0, uint32_t n_rows, uint32_t group, uint32_t groups,
+                                      uint32_t lane, uint32_t L) {
+    const uint32_t nvec = p.D / VEC;
+    u32x4 raw[PASSES][K];
+    float sc[PASSES];
 #pragma unroll
-  for (int k = 0; k < K; ++k) {
-    const uint32_t j = lane + k * L;
-    if (ok && j < nvec) {
-      load_vec(xrow + j * VEC, v[k]);
+    for (int it = 0; it < PASSES; ++it) {
+      const uint32_t idx = it * groups + group;
+      ok[it] = idx < n_rows;
+      const uint32_t cidx = min(idx, n_rows - 1);
+      sl[it] = cidx / p.H;
+      h[it] = cidx - sl[it] * p.H;
+      const T* xrow = x + ((size_t)(b * p.S + s0 + sl[it]) * p.H + h[it]) * p.D;
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) {
-        v[k][e] *= scale;
-        ss = __builtin_fmaf(v[k][e], v[k][e], ss);
+      for (int k = 0; k < K; ++k) raw[it][k] = load_raw_nt(xrow + min(lane + k * L, nvec - 1) * VEC);
+      sc[it] = load1(scale + h[it]);
+    }
+#pragma unroll
+    for (int it = 0; it < PASSES; ++it) {
+      float ss = 0.0f;
+#pragma unroll
+      for (int k = 0; k < K; ++k) {
+        unpack(raw[it][k], v[it][k], (const T*)nullptr);
+        const float s = (lane + k * L < nvec) ? sc[it] : 0.0f;
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          v[it][k][e] *= s;
+          ss = __builtin_fmaf(v[it][k][e], v[it][k][e], ss);
+        }
       }
-    } else {
+      ss = group_allreduce<OpSum>(ss, L);
+      const float r = fast_rsqrt(ss + p.eps);
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) v[k][e] = 0.0f;
+      for (int k = 0; k < K; ++k)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) v[it][k][e] *= r;
     }
   }
-  ss = group_allreduce<OpSum>(ss, L);
-  const float r = fast_rsqrt(ss + eps);
-#pragma unroll
-  for (int k = 0; k < K; ++k)
-#pragma unroll
-    for (int e = 0; e < VEC; ++e) v[k][e] *= r;
-}
+};
 
-template <typename T, int K>
+template <typename T, int K, int PASSES>
 __global__ void __launch_bounds__(256) k_tchain_wave(const T* __restrict__ x, const T* __restrict__ scale,
                                                      T* __restrict__ out, TChainP p) {
   constexpr int VEC = Elem<T>::VEC;
@@ -54,32 +78,26 @@ __global__ void __launch_bounds__(256) k_tchain_wave(const T* __restrict__ x, co
   const uint32_t nvec = p.D / VEC;
   const uint32_t s_tiles = (p.S + p.s_tile - 1) / p.s_tile;
   const uint32_t b = blockIdx.x / s_tiles;
-  const uint32_t s0 = (blockIdx.x % s_tiles) * p.s_tile;
+  const uint32_t s0 = (blockIdx.x - b * s_tiles) * p.s_tile;
   const uint32_t s_cnt = min((uint32_t)p.s_tile, p.S - s0);
-  const uint32_t n_rows = s_cnt * p.H;                    // rows of this slab, input order (s, h)
-  const uint32_t passes = (p.s_tile * p.H + groups - 1) / groups;
-  for (uint32_t it = 0; it < passes; ++it) {
-    const uint32_t idx = it * groups + group;
-    const bool ok = idx < n_rows;
-    const uint32_t sl = idx / p.H, h = idx % p.H;
-    float v[K][VEC];
-    const T* xrow = x + ((size_t)(b * p.S + s0 + sl) * p.H + h) * p.D;
-    const float sc = ok ? load1(scale + h) : 0.0f;
-    tchain_row<T, K>(xrow, sc, p.eps, lane, L, nvec, ok, v);
-    T* orow = out + ((size_t)(b * p.H + h) * p.S + s0 + sl) * p.D;
+  TChainTile<T, K, PASSES> t;
+  t.run(x, scale, p, b, s0, s_cnt * p.H, group, groups, lane, L);
+#pragma unroll
+  for (int it = 0; it < PASSES; ++it) {
+    T* orow = out + ((size_t)(b * p.H + t.h[it]) * p.S + s0 + t.sl[it]) * p.D;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
       const uint32_t j = lane + k * L;
-      if (ok && j < nvec) store_vec(orow + j * VEC, v[k]);
+      if (t.ok[it] && j < nvec) store_vec_nt(orow + j * VEC, t.v[it][k]);
     }
   }
 }
 
-template <typename T, int K>
+template <typename T, int K, int PASSES>
 __global__ void __launch_bounds__(256) k_tchain_lds(const T* __restrict__ x, const T* __restrict__ scale,
                                                     T* __restrict__ out, TChainP p) {
   constexpr int VEC = Elem<T>::VEC;
-  extern __shared__ float slab[];                          // [s_tile * H][pitch] float32
+  extern __shared__ float slab[];                          // [H][s_tile][pitch] float32, output order
   const uint32_t L = p.lanes_per_row;
   const uint32_t groups = 256u / L;
   const uint32_t group = threadIdx.x / L, lane = threadIdx.x & (L - 1);
@@ -87,28 +105,22 @@ __global__ void __launch_bounds__(256) k_tchain_lds(const T* __restrict__ x, con
   const uint32_t pitch = p.D + 4;                          // skew rows across LDS banks
   const uint32_t s_tiles = (p.S + p.s_tile - 1) / p.s_tile;
   const uint32_t b = blockIdx.x / s_tiles;
-  const uint32_t s0 = (blockIdx.x % s_tiles) * p.s_tile;
+  const uint32_t s0 = (blockIdx.x - b * s_tiles) * p.s_tile;
   const uint32_t s_cnt = min((uint32_t)p.s_tile, p.S - s0);
-  const uint32_t n_rows = s_cnt * p.H;
-  const uint32_t passes = (p.s_tile * p.H + groups - 1) / groups;
-  for (uint32_t it = 0; it < passes; ++it) {
-    const uint32_t idx = it * groups + group;
-    const bool ok = idx < n_rows;
-    const uint32_t sl = idx / p.H, h = idx % p.H;
-    float v[K][VEC];
-    const T* xrow = x + ((size_t)(b * p.S + s0 + sl) * p.H + h) * p.D;
-    const float sc = ok ? load1(scale + h) : 0.0f;
-    tchain_row<T, K>(xrow, sc, p.eps, lane, L, nvec, ok, v);
-    if (ok) {
-      float* dst = slab + (h * p.s_tile + sl) * pitch;     // parked in output order (h, s)
+  {
+    TChainTile<T, K, PASSES> t;
+    t.run(x, scale, p, b, s0, s_cnt * p.H, group, groups, lane, L);
+#pragma unroll
+    for (int it = 0; it < PASSES; ++it) {
+      float* dst = slab + (t.h[it] * p.s_tile + t.sl[it]) * pitch;
 #pragma unroll
       for (int k = 0; k < K; ++k) {
         const uint32_t j = lane + k * L;
-        if (j < nvec) {
+        if (t.ok[it] && j < nvec) {
 #pragma unroll
           for (int e = 0; e < VEC; e += 4) {
-            f32x4 t = {v[k][e], v[k][e + 1], v[k][e + 2], v[k][e + 3]};
-            *reinterpret_cast<f32x4*>(dst + j * VEC + e) = t;
+            f32x4 q = {t.v[it][k][e], t.v[it][k][e + 1], t.v[it][k][e + 2], t.v[it][k][e + 3]};
+            *reinterpret_cast<f32x4*>(dst + j * VEC + e) = q;
           }
         }
       }
@@ -118,16 +130,16 @@ __global__ void __launch_bounds__(256) k_tchain_lds(const T* __restrict__ x, con
   // write phase: for each head the s_cnt rows are contiguous in the output
   const uint32_t vec_per_head = s_cnt * nvec;
   for (uint32_t i = threadIdx.x; i < p.H * vec_per_head; i += 256u) {
-    const uint32_t h = i / vec_per_head, rem = i % vec_per_head;
-    const uint32_t sl = rem / nvec, j = rem % nvec;
+    const uint32_t h = i / vec_per_head, rem = i - h * vec_per_head;
+    const uint32_t sl = rem / nvec, j = rem - sl * nvec;
     const float* src = slab + (h * p.s_tile + sl) * pitch + j * VEC;
     float v[VEC];
 #pragma unroll
     for (int e = 0; e < VEC; e += 4) {
-      f32x4 t = *reinterpret_cast<const f32x4*>(src + e);
-      v[e] = t.x; v[e + 1] = t.y; v[e + 2] = t.z; v[e + 3] = t.w;
+      f32x4 q = *reinterpret_cast<const f32x4*>(src + e);
+      v[e] = q.x; v[e + 1] = q.y; v[e + 2] = q.z; v[e + 3] = q.w;
     }
-    store_vec(out + ((size_t)(b * p.H + h) * p.S + s0 + sl) * p.D + j * VEC, v);
+    store_vec_nt(out + ((size_t)(b * p.H + h) * p.S + s0 + sl) * p.D + j * VEC, v);
   }
 }
 
@@ -137,24 +149,33 @@ namespace fs {
 using namespace fsk;
 
 namespace {
-template <typename T>
-const void* tc_sym(int32_t kernel, int K) {
-#define FS_TC_CASE(KK) \
-  case KK: return kernel == K_TCHAIN_WAVE ? (const void*)k_tchain_wave<T, KK> : (const void*)k_tchain_lds<T, KK>;
-  switch (K) {
-    FS_TC_CASE(1) FS_TC_CASE(2) FS_TC_CASE(4)
+template <typename T, int K>
+const void* tc_sym_kp(int32_t kernel, int passes) {
+#define FS_TC_CASE(PP) \
+  case PP: return kernel == K_TCHAIN_WAVE ? (const void*)k_tchain_wave<T, K, PP> : (const void*)k_tchain_lds<T, K, PP>;
+  switch (passes) {
+    FS_TC_CASE(1) FS_TC_CASE(2) FS_TC_CASE(3) FS_TC_CASE(4)
     default: return nullptr;
   }
 #undef FS_TC_CASE
+}
+template <typename T>
+const void* tc_sym(int32_t kernel, int K, int passes) {
+  switch (K) {
+    case 1: return tc_sym_kp<T, 1>(kernel, passes);
+    case 2: return tc_sym_kp<T, 2>(kernel, passes);
+    case 4: return tc_sym_kp<T, 4>(kernel, passes);
+    default: return nullptr;
+  }
 }
 }  // namespace
 
 const void* tchain_kernel_symbol(int32_t kernel, const KernelArgs& a) {
   const TChainP& p = a.u.tchain;
   switch (p.dt) {
-    case DT_F32: return tc_sym<float>(kernel, p.vecs_per_lane);
-    case DT_F16: return tc_sym<f16_t>(kernel, p.vecs_per_lane);
-    default: return tc_sym<bf16_t>(kernel, p.vecs_per_lane);
+    case DT_F32: return tc_sym<float>(kernel, p.vecs_per_lane, p.passes);
+    case DT_F16: return tc_sym<f16_t>(kernel, p.vecs_per_lane, p.passes);
+    default: return tc_sym<bf16_t>(kernel, p.vecs_per_lane, p.passes);
   }
 }
 

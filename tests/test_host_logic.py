@@ -64,7 +64,8 @@ def test_full_configs_match_a_stitched_pattern(cfg):
               "C4": ("bias_gelu_dbias", 302008320), "C5": ("transpose_chain", 201326640)}[cfg]
     assert info["pattern"] == expect[0]
     assert info["bytes_min"] == expect[1]          # each input read once + each output written once
-    assert info["n_kernels"] == 1
+    # one launch, or two when the column sums are folded by a second tiny launch
+    assert info["n_kernels"] == 1 or (cfg == "C4" and info["n_kernels"] == 2 and info["kernel"].endswith("fold>"))
     assert info["predicted_us"] > 0
     cands = plan.candidates()
     assert len(cands) == info["n_candidates"] >= 1
