@@ -51,14 +51,13 @@ class Runner:
         self.outputs = [B.alloc_outputs(spec) for _ in range(self.n_sets)]
         self.workspaces = [self.plan.make_workspace() for _ in range(self.n_sets)]
         self.stream = torch.cuda.current_stream().cuda_stream
-        self._ptrs = [([t.data_ptr() for t in i], [t.data_ptr() for t in o],
-                       w.data_ptr() if w is not None else 0, w.numel() if w is not None else 0)
-                      for i, o, w in zip(self.inputs, self.outputs, self.workspaces)]
+        self._calls = [self.plan.bind([t.data_ptr() for t in i], [t.data_ptr() for t in o],
+                                      w.data_ptr() if w is not None else 0, w.numel() if w is not None else 0, self.stream)
+                       for i, o, w in zip(self.inputs, self.outputs, self.workspaces)]
         self.step_no = 0
 
     def step(self):
-        i, o, w, wb = self._ptrs[self.step_no % self.n_sets]
-        self.plan.execute_ptrs(i, o, w, wb, self.stream)
+        self._calls[self.step_no % self.n_sets]()
         self.step_no += 1
 
     def time_region(self, steps, warmup):
@@ -147,8 +146,8 @@ def measure_config(name, spec, steps, warmup, with_unfused=True):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--no-context", action="store_true", help="skip the other configurations, copy ceiling and oracle timing")
     ap.add_argument("--oracle-seconds", type=float, default=10.0)
     args = ap.parse_args()

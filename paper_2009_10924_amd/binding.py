@@ -242,6 +242,19 @@ class Plan:
         outs = (C.c_void_p * max(1, len(outputs)))(*outputs)
         _check(self._lib.fs_execute(self.handle, ins, outs, C.c_void_p(workspace), workspace_bytes, C.c_void_p(stream)))
 
+    def bind(self, inputs: Sequence[int], outputs: Sequence[int], workspace: int, workspace_bytes: int, stream: int):
+        """Marshals the arguments once; the returned callable only crosses the C ABI (for tight launch loops)."""
+        ins = (C.c_void_p * max(1, len(inputs)))(*inputs)
+        outs = (C.c_void_p * max(1, len(outputs)))(*outputs)
+        ws, nb, st = C.c_void_p(workspace), C.c_size_t(workspace_bytes), C.c_void_p(stream)
+        fn, handle = self._lib.fs_execute, self.handle
+
+        def call(_keep=(ins, outs)):
+            code = fn(handle, ins, outs, ws, nb, st)
+            if code < 0:
+                _check(code)
+        return call
+
     def execute(self, inputs, outputs, workspace=None, stream: Optional[int] = None) -> None:
         """inputs / outputs: torch device tensors in declaration order; workspace: a zero-initialised uint8 tensor."""
         import torch

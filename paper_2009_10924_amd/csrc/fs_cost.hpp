@@ -19,9 +19,9 @@ struct DeviceModel {
   double clock_hz = 2.4e9;
   double hbm_peak_Bps = 8.0e12;
   // measured / calibrated on the box (see the calibration notes in the design document)
-  double stream_fraction = 0.62;     // plain copy kernel, fraction of hbm_peak
-  double mem_latency_s = 2.0e-6;     // loaded HBM round trip seen by a wave
-  double launch_s = 2.5e-6;          // fixed cost of one kernel: dispatch, ramp, drain
+  double stream_fraction = 0.78;     // plain copy kernel, fraction of hbm_peak
+  double mem_latency_s = 1.2e-6;     // loaded HBM round trip seen by a wave
+  double launch_s = 2.2e-6;          // fixed cost of one kernel: dispatch, first load round trip, drain
   double l2_Bps = 20.0e12;           // aggregate cache bandwidth for re-read operands
   double lds_Bps = 60.0e12;          // aggregate LDS bandwidth
   double barrier_s = 0.15e-6;        // one workgroup barrier incl. the LDS round trip
@@ -49,7 +49,9 @@ struct KernelCost {
   int32_t vgpr_estimate = 32;
   int32_t lds_bytes_per_block = 0;
   double lane_utilisation = 1.0;        // fraction of lanes holding data
+  double access_run_bytes = 0;          // contiguous bytes one row group touches per load (0 = long)
   double store_run_bytes = 0;           // contiguous run written by one store instruction group (0 = long)
+  double preamble_instr = 40;           // VALU instructions a wave runs before it can issue its first load
   double serial_tail_s = 0;             // work done by a single workgroup after the rest finished
 };
 

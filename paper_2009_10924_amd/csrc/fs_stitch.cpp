@@ -21,6 +21,11 @@ uint32_t pow2_at_least(uint32_t v) {
   return p;
 }
 int vec_of(int32_t dt) { return 16 / dtype_bytes(dt); }
+int log2_of(uint32_t pow2) {
+  int l = 0;
+  while ((1u << l) < pow2) ++l;
+  return l;
+}
 
 // Magic numbers for n / d, n < 2^31; checked on the spot against plain division.
 FastDiv make_fastdiv(uint32_t d) {
@@ -201,7 +206,9 @@ bool build_softmax(const fs_graph& g, std::vector<Candidate>* out) {
       Launch& l = c.launches.front();
       SoftmaxP q = p;
       q.lanes_per_row = (int32_t)L;
+      q.lanes_log2 = log2_of(L);
       q.vecs_per_lane = K;
+      q.fast = (uint64_t)L * K == nvec && p.rows % (256 / L) == 0 && (!has_mask || p.mask_inner);
       l.args.u.softmax = q;
       l.ptr[0] = in_ref(g, st.tensors["X"]);
       if (has_mask) l.ptr[1] = in_ref(g, st.tensors["M"]);
@@ -217,11 +224,12 @@ bool build_softmax(const fs_graph& g, std::vector<Candidate>* out) {
       kc.waves = (double)l.shape.grid[0] * 4;
       kc.waves_per_block = 4;
       kc.bytes_in_flight_per_lane = 16.0 * K * (has_mask && p.mask_inner ? 2 : 1);
-      kc.vgpr_estimate = 16 + K * VEC * 1 + (has_mask ? VEC : 0);
+      kc.vgpr_estimate = 12 + K * (VEC + 4) + (has_mask ? K * 4 : 0);
       int steps = 0;
       for (uint32_t s = 1; s < L; s <<= 1) ++steps;
       kc.xlane_steps = 2 * steps;
       kc.lane_utilisation = (double)nvec / ((double)L * K);
+      kc.access_run_bytes = std::min<double>(L, nvec) * 16.0;
       char var[32];
       snprintf(var, sizeof var, "<%s,K%d,L%u>", dtype_name(p.in_dt), K, L);
       finish_candidate(&c, var, kc);
@@ -238,6 +246,7 @@ bool build_softmax(const fs_graph& g, std::vector<Candidate>* out) {
       SoftmaxP q = p;
       q.lanes_per_row = (int32_t)T;
       q.vecs_per_lane = K;
+      q.fast = (uint64_t)T * K == nvec && (!has_mask || p.mask_inner);
       l.args.u.softmax = q;
       l.ptr[0] = in_ref(g, st.tensors["X"]);
       if (has_mask) l.ptr[1] = in_ref(g, st.tensors["M"]);
@@ -356,6 +365,7 @@ bool build_layernorm(const fs_graph& g, std::vector<Candidate>* out) {
   p.has_bias = tb >= 0;
   p.has_affine = affine;
   p.eps = (float)st.scalars[0];
+  p.inv_cols = (float)(1.0 / (double)p.cols);
 
   const int VEC = vec_of(p.in_dt);
   if (p.cols % VEC != 0) return true;
@@ -386,8 +396,10 @@ bool build_layernorm(const fs_graph& g, std::vector<Candidate>* out) {
     Launch& l = c.launches.front();
     LayerNormP q = p;
     q.lanes_per_row = (int32_t)L;
+    q.lanes_log2 = log2_of(L);
     q.vecs_per_lane = K;
     q.rows_per_block = (int32_t)(256 / L);
+    q.fast = p.has_res && p.has_bias && affine && (uint64_t)L * K == nvec && p.rows % (256 / L) == 0;
     l.args.u.layernorm = q;
     fill_ptrs(l);
     l.shape.block[0] = 256;
@@ -400,12 +412,13 @@ bool build_layernorm(const fs_graph& g, std::vector<Candidate>* out) {
     kc.waves = (double)l.shape.grid[0] * 4;
     kc.waves_per_block = 4;
     kc.bytes_in_flight_per_lane = 16.0 * K * (1 + p.has_res);
-    kc.vgpr_estimate = 20 + K * VEC * 2;
+    kc.vgpr_estimate = 16 + K * (VEC + 8 + (affine ? 0 : 0)) + (K > 3 ? K * 4 : 0);
     int steps = 0;
     for (uint32_t s = 1; s < L; s <<= 1) ++steps;
     kc.xlane_steps = 2 * steps;
     kc.cache_bytes = n / p.cols * (double)n_vec_inputs * p.cols * in_b;   // bias/gamma/beta re-read per row from L1/L2
     kc.lane_utilisation = (double)nvec / ((double)L * K);
+    kc.access_run_bytes = std::min<double>(L, nvec) * 16.0;
     char var[40];
     snprintf(var, sizeof var, "<%s,%s,K%d,L%u>", dtype_name(p.in_dt), dtype_name(p.out_dt), K, L);
     finish_candidate(&c, var, kc);
@@ -422,6 +435,7 @@ bool build_layernorm(const fs_graph& g, std::vector<Candidate>* out) {
     q.lanes_per_row = (int32_t)T;
     q.vecs_per_lane = K;
     q.rows_per_block = 1;
+    q.fast = p.has_res && p.has_bias && affine && (uint64_t)T * K == nvec;
     l.args.u.layernorm = q;
     fill_ptrs(l);
     l.shape.block[0] = T;
@@ -648,9 +662,13 @@ bool build_tchain(const fs_graph& g, std::vector<Candidate>* out) {
         Launch& l = c.launches.front();
         TChainP q = p;
         q.lanes_per_row = (int32_t)L;
+        q.lanes_log2 = log2_of(L);
         q.vecs_per_lane = K;
         q.s_tile = (int32_t)s_tile;
         q.passes = (int32_t)passes;
+        q.div_h = make_fastdiv(p.H);
+        q.div_s_tiles = make_fastdiv((p.S + s_tile - 1) / s_tile);
+        if (q.div_h.d == 0 || q.div_s_tiles.d == 0) continue;
         l.args.u.tchain = q;
         l.ptr[0] = in_ref(g, tx);
         l.ptr[1] = in_ref(g, ts);
@@ -680,6 +698,7 @@ bool build_tchain(const fs_graph& g, std::vector<Candidate>* out) {
         kc.lds_traffic_bytes = lds ? 2 * n * 4 : 0;
         kc.store_run_bytes = lds ? (double)s_tile * p.D * esz : (double)p.D * esz;
         kc.lane_utilisation = (double)nvec / ((double)L * K) * (double)tile_rows / (passes * groups);
+        kc.access_run_bytes = std::min<double>(L, nvec) * 16.0;
         char var[48];
         snprintf(var, sizeof var, "<%s,K%d,L%u,S%u,P%u>", dtype_name(p.dt), K, L, s_tile, passes);
         finish_candidate(&c, var, kc);

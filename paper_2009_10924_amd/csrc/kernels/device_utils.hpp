@@ -201,21 +201,24 @@ __device__ __forceinline__ float read_lane(float v, int lane) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
 }
 
+// Branch-free on purpose: `lanes` is wave-uniform, each step is computed and then kept
+// or dropped by a select.  Without branches a kernel's loads, reductions and stores
+// stay in one basic block, so the scheduler keeps early loads early instead of sinking
+// them next to their first use behind the reduction.
 template <typename OP>
 __device__ __forceinline__ float group_allreduce(float v, int lanes) {
-  if (lanes > 1) v = OP::apply(v, dpp_move<0xB1>(v));    // quad_perm [1,0,3,2]  : lane ^ 1
-  if (lanes > 2) v = OP::apply(v, dpp_move<0x4E>(v));    // quad_perm [2,3,0,1]  : lane ^ 2
-  if (lanes > 4) v = OP::apply(v, dpp_move<0x141>(v));   // row_half_mirror      : other quad of the 8
-  if (lanes > 8) v = OP::apply(v, dpp_move<0x140>(v));   // row_mirror           : other half of the 16
-  if (lanes > 16) {
-    // every 16-lane row now holds its own total in all lanes: combine rows through
-    // scalar registers (v_readlane), which costs no LDS-crossbar round trip.
-    const float lo = OP::apply(read_lane(v, 0), read_lane(v, 16));
-    const float hi = OP::apply(read_lane(v, 32), read_lane(v, 48));
-    if (lanes > 32) v = OP::apply(lo, hi);
-    else v = (threadIdx.x & 32u) ? hi : lo;
-  }
-  return v;
+  float t;
+  t = OP::apply(v, dpp_move<0xB1>(v));  v = lanes > 1 ? t : v;   // quad_perm [1,0,3,2] : lane ^ 1
+  t = OP::apply(v, dpp_move<0x4E>(v));  v = lanes > 2 ? t : v;   // quad_perm [2,3,0,1] : lane ^ 2
+  t = OP::apply(v, dpp_move<0x141>(v)); v = lanes > 4 ? t : v;   // row_half_mirror     : other quad of the 8
+  t = OP::apply(v, dpp_move<0x140>(v)); v = lanes > 8 ? t : v;   // row_mirror          : other half of the 16
+  // every 16-lane row now holds its own total in all lanes: rows are combined through
+  // scalar registers (v_readlane), which costs no LDS-crossbar round trip.
+  const float lo = OP::apply(read_lane(v, 0), read_lane(v, 16));
+  const float hi = OP::apply(read_lane(v, 32), read_lane(v, 48));
+  const float half = (threadIdx.x & 32u) ? hi : lo;
+  const float full = OP::apply(lo, hi);
+  return lanes > 32 ? full : (lanes > 16 ? half : v);
 }
 
 // Workgroup all-reduce through LDS (block composition): each wave reduces, lane 0

@@ -86,13 +86,17 @@ struct SoftmaxP {
   uint32_t ms[3];                   // mask element stride for each outer coordinate
   float scale;
   int32_t lanes_per_row, vecs_per_lane;
+  int32_t lanes_log2;               // log2(lanes_per_row) for the wave variant
+  int32_t fast;                     // 1: the row fills the lanes and the rows fill the workgroups exactly
 };
 struct LayerNormP {
   int32_t in_dt, out_dt, par_dt;    // x/res dtype, output dtype, bias/gamma/beta dtype
   int32_t has_res, has_bias, has_affine;
   uint32_t rows, cols;
-  float eps;
+  float eps, inv_cols;              // inv_cols = 1 / cols, rounded on the host
   int32_t lanes_per_row, vecs_per_lane, rows_per_block;
+  int32_t lanes_log2;
+  int32_t fast;                     // 1: all operands present, row and row count fill lanes / workgroups exactly
 };
 struct GeluP {
   int32_t dt, bias_dt;              // x / grad / y share dt
@@ -107,6 +111,8 @@ struct TChainP {
   float eps;
   int32_t lanes_per_row, vecs_per_lane, s_tile;
   int32_t passes;                   // rows each lane group handles = ceil(s_tile * H / groups), 1..4
+  int32_t lanes_log2;
+  FastDiv div_h, div_s_tiles;       // division by H and by the number of s tiles per batch entry
 };
 
 struct KernelArgs {

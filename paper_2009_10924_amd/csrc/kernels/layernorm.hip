@@ -36,51 +36,67 @@ template <> struct StoreN<bf16_t, 8> {
   __device__ __forceinline__ static void run(bf16_t* p, const float (&v)[8]) { store_vec_nt(p, v); }
 };
 
-template <typename TI, typename TO, int K>
+// FAST: residual, bias and affine all present, the row fills the lanes exactly and the
+// row count fills the workgroups exactly, so every flag test, clamp and padding mask
+// folds away at compile time (the shape of the benchmarked configuration).
+template <typename TI, typename TO, int K, bool FAST>
 struct LnRow {
   static constexpr int VEC = Elem<TI>::VEC;
   float h[K][VEC];
+  u32x4 raw_gamma[K], raw_beta[K];   // fetched with the row, consumed after both reductions
 
   // All loads are issued before any value is used; vectors past the row end and rows
   // past the tensor end are clamped to a valid address and zeroed afterwards.
   __device__ __forceinline__ float load(const TI* __restrict__ x, const TI* __restrict__ res,
-                                        const TI* __restrict__ bias, const LayerNormP& p, uint32_t row,
+                                        const TI* __restrict__ bias, const TI* __restrict__ gamma,
+                                        const TI* __restrict__ beta, const LayerNormP& p, uint32_t row,
                                         uint32_t lane, uint32_t stride) {
     const uint32_t nvec = p.cols / VEC;
-    const size_t base = (size_t)min(row, p.rows - 1) * p.cols;
+    const bool has_res = FAST || p.has_res, has_bias = FAST || p.has_bias, has_affine = FAST || p.has_affine;
+    const size_t base = (size_t)(FAST ? row : min(row, p.rows - 1)) * p.cols;
+    auto vec_at = [&](int k) { return FAST ? lane + k * stride : min(lane + k * stride, nvec - 1); };
     u32x4 rx[K], rr[K], rb[K];
 #pragma unroll
-    for (int k = 0; k < K; ++k) rx[k] = load_raw_nt(x + base + min(lane + k * stride, nvec - 1) * VEC);
-    if (p.has_res) {
+    for (int k = 0; k < K; ++k) rx[k] = load_raw_nt(x + base + vec_at(k) * VEC);
+    if (has_res) {
 #pragma unroll
-      for (int k = 0; k < K; ++k) rr[k] = load_raw_nt(res + base + min(lane + k * stride, nvec - 1) * VEC);
+      for (int k = 0; k < K; ++k) rr[k] = load_raw_nt(res + base + vec_at(k) * VEC);
     }
-    if (p.has_bias) {
+    if (has_bias) {
 #pragma unroll
-      for (int k = 0; k < K; ++k) rb[k] = load_raw(bias + min(lane + k * stride, nvec - 1) * VEC);
+      for (int k = 0; k < K; ++k) rb[k] = load_raw(bias + vec_at(k) * VEC);
     }
     float sum = 0.0f;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
       unpack(rx[k], h[k], (const TI*)nullptr);
-      if (p.has_res) {
+      if (has_res) {
         float r[VEC];
         unpack(rr[k], r, (const TI*)nullptr);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) h[k][e] += r[e];
       }
-      if (p.has_bias) {
+      if (has_bias) {
         float b[VEC];
         unpack(rb[k], b, (const TI*)nullptr);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) h[k][e] += b[e];
       }
-      if (lane + k * stride >= nvec) {
+      if (!FAST && lane + k * stride >= nvec) {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) h[k][e] = 0.0f;
       }
 #pragma unroll
       for (int e = 0; e < VEC; ++e) sum += h[k][e];
+    }
+    // gamma / beta are requested now, when the registers of the raw row are free again;
+    // they arrive from cache while the two reductions run.
+    if (has_affine) {
+#pragma unroll
+      for (int k = 0; k < K; ++k) {
+        raw_gamma[k] = load_raw(gamma + vec_at(k) * VEC);
+        raw_beta[k] = load_raw(beta + vec_at(k) * VEC);
+      }
     }
     return sum;
   }
@@ -90,7 +106,7 @@ struct LnRow {
     float sq = 0.0f;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      const float m = (lane + k * stride < nvec) ? mean : 0.0f;   // padded slots stay exactly zero
+      const float m = (FAST || lane + k * stride < nvec) ? mean : 0.0f;   // padded slots stay exactly zero
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
         h[k][e] -= m;
@@ -100,73 +116,63 @@ struct LnRow {
     return sq;
   }
 
-  __device__ __forceinline__ void finish(TO* __restrict__ out, const TI* __restrict__ gamma,
-                                         const TI* __restrict__ beta, const LayerNormP& p, uint32_t row,
+  __device__ __forceinline__ void finish(TO* __restrict__ out, const LayerNormP& p, uint32_t row,
                                          bool row_ok, uint32_t lane, uint32_t stride, float rstd) {
     const uint32_t nvec = p.cols / VEC;
     const size_t base = (size_t)row * p.cols;
-    u32x4 rg[K], rb[K];
-    if (p.has_affine) {
-#pragma unroll
-      for (int k = 0; k < K; ++k) {
-        const uint32_t j = min(lane + k * stride, nvec - 1);
-        rg[k] = load_raw(gamma + j * VEC);
-        rb[k] = load_raw(beta + j * VEC);
-      }
-    }
 #pragma unroll
     for (int k = 0; k < K; ++k) {
       const uint32_t j = lane + k * stride;
-      if (p.has_affine) {
+      if (FAST || p.has_affine) {
         float g[VEC], b[VEC];
-        unpack(rg[k], g, (const TI*)nullptr);
-        unpack(rb[k], b, (const TI*)nullptr);
+        unpack(raw_gamma[k], g, (const TI*)nullptr);
+        unpack(raw_beta[k], b, (const TI*)nullptr);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) h[k][e] = __builtin_fmaf(h[k][e] * rstd, g[e], b[e]);
       } else {
 #pragma unroll
         for (int e = 0; e < VEC; ++e) h[k][e] *= rstd;
       }
-      if (row_ok && j < nvec) StoreN<TO, VEC>::run(out + base + j * VEC, h[k]);
+      if (FAST || (row_ok && j < nvec)) StoreN<TO, VEC>::run(out + base + j * VEC, h[k]);
     }
   }
 };
 
-template <typename TI, typename TO, int K>
+template <typename TI, typename TO, int K, bool FAST>
 __global__ void __launch_bounds__(256) k_layernorm_wave(const TI* __restrict__ x, const TI* __restrict__ res,
                                                         const TI* __restrict__ bias, const TI* __restrict__ gamma,
                                                         const TI* __restrict__ beta, TO* __restrict__ out,
                                                         LayerNormP p) {
   const uint32_t L = p.lanes_per_row;
-  const uint32_t group = threadIdx.x / L;
+  const uint32_t group = threadIdx.x >> p.lanes_log2;
   const uint32_t lane = threadIdx.x & (L - 1);
-  const uint32_t row = blockIdx.x * (256u / L) + group;
+  const uint32_t row = blockIdx.x * (256u >> p.lanes_log2) + group;
   const bool row_ok = row < p.rows;
-  const float inv_n = 1.0f / (float)p.cols;
-  LnRow<TI, TO, K> r;
-  const float mean = group_allreduce<OpSum>(r.load(x, res, bias, p, row, lane, L), L) * inv_n;
+  const float inv_n = p.inv_cols;
+  LnRow<TI, TO, K, FAST> r;
+  const float mean = group_allreduce<OpSum>(r.load(x, res, bias, gamma, beta, p, row, lane, L), L) * inv_n;
   const float var = group_allreduce<OpSum>(r.center(p, mean, lane, L), L) * inv_n;
-  r.finish(out, gamma, beta, p, row, row_ok, lane, L, fast_rsqrt(var + p.eps));
+  r.finish(out, p, row, row_ok, lane, L, fast_rsqrt(var + p.eps));
 }
 
-template <typename TI, typename TO, int K>
+template <typename TI, typename TO, int K, bool FAST>
 __global__ void __launch_bounds__(256) k_layernorm_block(const TI* __restrict__ x, const TI* __restrict__ res,
                                                          const TI* __restrict__ bias, const TI* __restrict__ gamma,
                                                          const TI* __restrict__ beta, TO* __restrict__ out,
                                                          LayerNormP p) {
   __shared__ float slot_sum[2][4], slot_sq[2][4];
   const uint32_t n_waves = blockDim.x >> 6;
-  const float inv_n = 1.0f / (float)p.cols;
+  const float inv_n = p.inv_cols;
   uint32_t it = 0;
   for (uint32_t row = blockIdx.x; row < p.rows; row += gridDim.x, ++it) {
-    LnRow<TI, TO, K> r;
+    LnRow<TI, TO, K, FAST> r;
     // two slot sets alternate between rows: a wave may start row i+1 while a slower
     // one still reads the slots of row i.
-    const float mean = block_allreduce<OpSum>(r.load(x, res, bias, p, row, threadIdx.x, blockDim.x),
+    const float mean = block_allreduce<OpSum>(r.load(x, res, bias, gamma, beta, p, row, threadIdx.x, blockDim.x),
                                               slot_sum[it & 1], n_waves) * inv_n;
     const float var = block_allreduce<OpSum>(r.center(p, mean, threadIdx.x, blockDim.x),
                                              slot_sq[it & 1], n_waves) * inv_n;
-    r.finish(out, gamma, beta, p, row, true, threadIdx.x, blockDim.x, fast_rsqrt(var + p.eps));
+    r.finish(out, p, row, true, threadIdx.x, blockDim.x, fast_rsqrt(var + p.eps));
   }
 }
 
@@ -177,11 +183,14 @@ using namespace fsk;
 
 namespace {
 template <typename TI, typename TO>
-const void* ln_sym(int32_t kernel, int K) {
-#define FS_LN_CASE(KK)                                                             \
-  case KK:                                                                         \
-    return kernel == K_LAYERNORM_WAVE ? (const void*)k_layernorm_wave<TI, TO, KK>  \
-                                      : (const void*)k_layernorm_block<TI, TO, KK>;
+const void* ln_sym(int32_t kernel, int K, bool fast) {
+#define FS_LN_CASE(KK)                                                                                     \
+  case KK:                                                                                                 \
+    if (fast)                                                                                              \
+      return kernel == K_LAYERNORM_WAVE ? (const void*)k_layernorm_wave<TI, TO, KK, true>                  \
+                                        : (const void*)k_layernorm_block<TI, TO, KK, true>;                \
+    return kernel == K_LAYERNORM_WAVE ? (const void*)k_layernorm_wave<TI, TO, KK, false>                   \
+                                      : (const void*)k_layernorm_block<TI, TO, KK, false>;
   switch (K) {
     FS_LN_CASE(1) FS_LN_CASE(2) FS_LN_CASE(3) FS_LN_CASE(4) FS_LN_CASE(6) FS_LN_CASE(8)
     default: return nullptr;
@@ -193,11 +202,11 @@ const void* ln_sym(int32_t kernel, int K) {
 const void* layernorm_kernel_symbol(int32_t kernel, const KernelArgs& a) {
   const LayerNormP& p = a.u.layernorm;
   const int K = p.vecs_per_lane;
-  if (p.in_dt == DT_F32 && p.out_dt == DT_F32) return ln_sym<float, float>(kernel, K);
-  if (p.in_dt == DT_F32 && p.out_dt == DT_BF16) return ln_sym<float, bf16_t>(kernel, K);
-  if (p.in_dt == DT_F32 && p.out_dt == DT_F16) return ln_sym<float, f16_t>(kernel, K);
-  if (p.in_dt == DT_BF16 && p.out_dt == DT_BF16) return ln_sym<bf16_t, bf16_t>(kernel, K);
-  if (p.in_dt == DT_F16 && p.out_dt == DT_F16) return ln_sym<f16_t, f16_t>(kernel, K);
+  if (p.in_dt == DT_F32 && p.out_dt == DT_F32) return ln_sym<float, float>(kernel, K, p.fast != 0);
+  if (p.in_dt == DT_F32 && p.out_dt == DT_BF16) return ln_sym<float, bf16_t>(kernel, K, p.fast != 0);
+  if (p.in_dt == DT_F32 && p.out_dt == DT_F16) return ln_sym<float, f16_t>(kernel, K, p.fast != 0);
+  if (p.in_dt == DT_BF16 && p.out_dt == DT_BF16) return ln_sym<bf16_t, bf16_t>(kernel, K, p.fast != 0);
+  if (p.in_dt == DT_F16 && p.out_dt == DT_F16) return ln_sym<f16_t, f16_t>(kernel, K, p.fast != 0);
   return nullptr;
 }
 

@@ -21,27 +21,31 @@ using namespace fs;
 // Loads the row segment of one lane.  Every load is issued before any value is used:
 // out-of-range vectors and rows are clamped to a valid address and blanked afterwards,
 // so no branch separates the loads and all of them are in flight together.
-template <typename T, int K, bool HAS_MASK>
+// FAST: the row fills the lanes exactly, the rows fill the workgroups exactly and a mask,
+// if any, varies along the row: clamps, padding masks and flag tests fold away.
+template <typename T, int K, bool HAS_MASK, bool FAST>
 __device__ __forceinline__ void softmax_load(const T* __restrict__ x, const T* __restrict__ mask, const SoftmaxP& p,
                                              uint32_t row, uint32_t lane, uint32_t stride,
                                              float (&v)[K][Elem<T>::VEC]) {
   constexpr int VEC = Elem<T>::VEC;
   const uint32_t nvec = p.cols / VEC;
-  const uint32_t r = min(row, p.rows - 1);
+  const uint32_t r = FAST ? row : min(row, p.rows - 1);
   const T* xr = x + (size_t)r * p.cols;
+  auto vec_at = [&](int k) { return FAST ? lane + k * stride : min(lane + k * stride, nvec - 1); };
+  const bool mask_inner = FAST || p.mask_inner;
   u32x4 raw[K], rawm[K];
   float mscalar = 0.0f;
 #pragma unroll
-  for (int k = 0; k < K; ++k) raw[k] = load_raw_nt(xr + min(lane + k * stride, nvec - 1) * VEC);
+  for (int k = 0; k < K; ++k) raw[k] = load_raw_nt(xr + vec_at(k) * VEC);
   if constexpr (HAS_MASK) {
     const uint32_t r1 = fast_div(r, p.od[2]);
     const uint32_t c2 = r - r1 * p.od[2].d;
     const uint32_t c0 = fast_div(r1, p.od[1]);
     const uint32_t c1 = r1 - c0 * p.od[1].d;
     const T* mrow = mask + (c0 * p.ms[0] + c1 * p.ms[1] + c2 * p.ms[2]);
-    if (p.mask_inner) {
+    if (mask_inner) {
 #pragma unroll
-      for (int k = 0; k < K; ++k) rawm[k] = load_raw(mrow + min(lane + k * stride, nvec - 1) * VEC);
+      for (int k = 0; k < K; ++k) rawm[k] = load_raw(mrow + vec_at(k) * VEC);
     } else {
       mscalar = load1(mrow);
     }
@@ -51,7 +55,7 @@ __device__ __forceinline__ void softmax_load(const T* __restrict__ x, const T* _
     unpack(raw[k], v[k], (const T*)nullptr);
     if constexpr (HAS_MASK) {
       float m[VEC];
-      if (p.mask_inner) {
+      if (mask_inner) {
         unpack(rawm[k], m, (const T*)nullptr);
       } else {
 #pragma unroll
@@ -63,7 +67,7 @@ __device__ __forceinline__ void softmax_load(const T* __restrict__ x, const T* _
 #pragma unroll
       for (int e = 0; e < VEC; ++e) v[k][e] *= p.scale;
     }
-    if (lane + k * stride >= nvec) {
+    if (!FAST && lane + k * stride >= nvec) {
 #pragma unroll
       for (int e = 0; e < VEC; ++e) v[k][e] = -INFINITY;
     }
@@ -94,7 +98,7 @@ __device__ __forceinline__ float exp_and_sum(float (&v)[K][VEC], float m) {
   return s;
 }
 
-template <typename T, int K>
+template <typename T, int K, bool FAST>
 __device__ __forceinline__ void softmax_store(T* __restrict__ out, const SoftmaxP& p, uint32_t row, bool row_ok,
                                               uint32_t lane, uint32_t stride, float (&v)[K][Elem<T>::VEC], float inv) {
   constexpr int VEC = Elem<T>::VEC;
@@ -103,7 +107,7 @@ __device__ __forceinline__ void softmax_store(T* __restrict__ out, const Softmax
 #pragma unroll
   for (int k = 0; k < K; ++k) {
     const uint32_t j = lane + k * stride;
-    if (row_ok && j < nvec) {
+    if (FAST || (row_ok && j < nvec)) {
 #pragma unroll
       for (int e = 0; e < VEC; ++e) v[k][e] *= inv;
       store_vec_nt(orow + j * VEC, v[k]);
@@ -112,24 +116,24 @@ __device__ __forceinline__ void softmax_store(T* __restrict__ out, const Softmax
 }
 
 // ---- wave variant ------------------------------------------------------------------
-template <typename T, int K, bool HAS_MASK>
+template <typename T, int K, bool HAS_MASK, bool FAST>
 __global__ void __launch_bounds__(256) k_softmax_wave(const T* __restrict__ x, const T* __restrict__ mask,
                                                       T* __restrict__ out, SoftmaxP p) {
   constexpr int VEC = Elem<T>::VEC;
   const uint32_t L = p.lanes_per_row;            // power of two, <= 64
-  const uint32_t group = threadIdx.x / L;
+  const uint32_t group = threadIdx.x >> p.lanes_log2;
   const uint32_t lane = threadIdx.x & (L - 1);
-  const uint32_t row = blockIdx.x * (256u / L) + group;
+  const uint32_t row = blockIdx.x * (256u >> p.lanes_log2) + group;
   const bool row_ok = row < p.rows;
   float v[K][VEC];
-  softmax_load<T, K, HAS_MASK>(x, mask, p, row, lane, L, v);
+  softmax_load<T, K, HAS_MASK, FAST>(x, mask, p, row, lane, L, v);
   const float m = group_allreduce<OpMax>(local_max<K, VEC>(v), L);
   const float s = group_allreduce<OpSum>(exp_and_sum<K, VEC>(v, m), L);
-  softmax_store<T, K>(out, p, row, row_ok, lane, L, v, fast_rcp(s));
+  softmax_store<T, K, FAST>(out, p, row, row_ok, lane, L, v, fast_rcp(s));
 }
 
 // ---- block variant -----------------------------------------------------------------
-template <typename T, int K, bool HAS_MASK>
+template <typename T, int K, bool HAS_MASK, bool FAST>
 __global__ void __launch_bounds__(256) k_softmax_block(const T* __restrict__ x, const T* __restrict__ mask,
                                                        T* __restrict__ out, SoftmaxP p) {
   constexpr int VEC = Elem<T>::VEC;
@@ -137,10 +141,10 @@ __global__ void __launch_bounds__(256) k_softmax_block(const T* __restrict__ x, 
   const uint32_t row = blockIdx.x;
   const uint32_t n_waves = blockDim.x >> 6;
   float v[K][VEC];
-  softmax_load<T, K, HAS_MASK>(x, mask, p, row, threadIdx.x, blockDim.x, v);
+  softmax_load<T, K, HAS_MASK, FAST>(x, mask, p, row, threadIdx.x, blockDim.x, v);
   const float m = block_allreduce<OpMax>(local_max<K, VEC>(v), slot_max, n_waves);
   const float s = block_allreduce<OpSum>(exp_and_sum<K, VEC>(v, m), slot_sum, n_waves);
-  softmax_store<T, K>(out, p, row, true, threadIdx.x, blockDim.x, v, fast_rcp(s));
+  softmax_store<T, K, FAST>(out, p, row, true, threadIdx.x, blockDim.x, v, fast_rcp(s));
 }
 
 // ---- generic variant ---------------------------------------------------------------
@@ -178,29 +182,33 @@ namespace fs {
 using namespace fsk;
 
 namespace {
-template <typename T, bool M>
+template <typename T, bool M, bool F>
 const void* wave_sym(int K) {
   switch (K) {
-    case 1: return (const void*)k_softmax_wave<T, 1, M>;
-    case 2: return (const void*)k_softmax_wave<T, 2, M>;
-    case 4: return (const void*)k_softmax_wave<T, 4, M>;
-    default: return (const void*)k_softmax_wave<T, 8, M>;
+    case 1: return (const void*)k_softmax_wave<T, 1, M, F>;
+    case 2: return (const void*)k_softmax_wave<T, 2, M, F>;
+    case 4: return (const void*)k_softmax_wave<T, 4, M, F>;
+    default: return (const void*)k_softmax_wave<T, 8, M, F>;
+  }
+}
+template <typename T, bool M, bool F>
+const void* block_sym(int K) {
+  switch (K) {
+    case 1: return (const void*)k_softmax_block<T, 1, M, F>;
+    case 2: return (const void*)k_softmax_block<T, 2, M, F>;
+    case 4: return (const void*)k_softmax_block<T, 4, M, F>;
+    default: return (const void*)k_softmax_block<T, 8, M, F>;
   }
 }
 template <typename T, bool M>
-const void* block_sym(int K) {
-  switch (K) {
-    case 1: return (const void*)k_softmax_block<T, 1, M>;
-    case 2: return (const void*)k_softmax_block<T, 2, M>;
-    case 4: return (const void*)k_softmax_block<T, 4, M>;
-    default: return (const void*)k_softmax_block<T, 8, M>;
-  }
+const void* sym_mf(int32_t kernel, const SoftmaxP& p) {
+  if (kernel == K_SOFTMAX_WAVE) return p.fast ? wave_sym<T, M, true>(p.vecs_per_lane) : wave_sym<T, M, false>(p.vecs_per_lane);
+  return p.fast ? block_sym<T, M, true>(p.vecs_per_lane) : block_sym<T, M, false>(p.vecs_per_lane);
 }
 template <typename T>
 const void* sym_for(int32_t kernel, const SoftmaxP& p) {
   if (p.vecs_per_lane == 0) return (const void*)k_softmax_generic<T>;
-  if (kernel == K_SOFTMAX_WAVE) return p.has_mask ? wave_sym<T, true>(p.vecs_per_lane) : wave_sym<T, false>(p.vecs_per_lane);
-  return p.has_mask ? block_sym<T, true>(p.vecs_per_lane) : block_sym<T, false>(p.vecs_per_lane);
+  return p.has_mask ? sym_mf<T, true>(kernel, p) : sym_mf<T, false>(kernel, p);
 }
 }  // namespace
 

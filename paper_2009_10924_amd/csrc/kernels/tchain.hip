@@ -38,7 +38,7 @@ struct TChainTile {
       const uint32_t idx = it * groups + group;
       ok[it] = idx < n_rows;
       const uint32_t cidx = min(idx, n_rows - 1);
-      sl[it] = cidx / p.H;
+      sl[it] = fast_div(cidx, p.div_h);
       h[it] = cidx - sl[it] * p.H;
       const T* xrow = x + ((size_t)(b * p.S + s0 + sl[it]) * p.H + h[it]) * p.D;
 #pragma unroll
@@ -73,12 +73,11 @@ __global__ void __launch_bounds__(256) k_tchain_wave(const T* __restrict__ x, co
                                                      T* __restrict__ out, TChainP p) {
   constexpr int VEC = Elem<T>::VEC;
   const uint32_t L = p.lanes_per_row;
-  const uint32_t groups = 256u / L;
-  const uint32_t group = threadIdx.x / L, lane = threadIdx.x & (L - 1);
+  const uint32_t groups = 256u >> p.lanes_log2;
+  const uint32_t group = threadIdx.x >> p.lanes_log2, lane = threadIdx.x & (L - 1);
   const uint32_t nvec = p.D / VEC;
-  const uint32_t s_tiles = (p.S + p.s_tile - 1) / p.s_tile;
-  const uint32_t b = blockIdx.x / s_tiles;
-  const uint32_t s0 = (blockIdx.x - b * s_tiles) * p.s_tile;
+  const uint32_t b = fast_div(blockIdx.x, p.div_s_tiles);
+  const uint32_t s0 = (blockIdx.x - b * p.div_s_tiles.d) * p.s_tile;
   const uint32_t s_cnt = min((uint32_t)p.s_tile, p.S - s0);
   TChainTile<T, K, PASSES> t;
   t.run(x, scale, p, b, s0, s_cnt * p.H, group, groups, lane, L);
@@ -99,13 +98,12 @@ __global__ void __launch_bounds__(256) k_tchain_lds(const T* __restrict__ x, con
   constexpr int VEC = Elem<T>::VEC;
   extern __shared__ float slab[];                          // [H][s_tile][pitch] float32, output order
   const uint32_t L = p.lanes_per_row;
-  const uint32_t groups = 256u / L;
-  const uint32_t group = threadIdx.x / L, lane = threadIdx.x & (L - 1);
+  const uint32_t groups = 256u >> p.lanes_log2;
+  const uint32_t group = threadIdx.x >> p.lanes_log2, lane = threadIdx.x & (L - 1);
   const uint32_t nvec = p.D / VEC;
   const uint32_t pitch = p.D + 4;                          // skew rows across LDS banks
-  const uint32_t s_tiles = (p.S + p.s_tile - 1) / p.s_tile;
-  const uint32_t b = blockIdx.x / s_tiles;
-  const uint32_t s0 = (blockIdx.x - b * s_tiles) * p.s_tile;
+  const uint32_t b = fast_div(blockIdx.x, p.div_s_tiles);
+  const uint32_t s0 = (blockIdx.x - b * p.div_s_tiles.d) * p.s_tile;
   const uint32_t s_cnt = min((uint32_t)p.s_tile, p.S - s0);
   {
     TChainTile<T, K, PASSES> t;
