@@ -28,6 +28,20 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 CACHE_BYTES = 256 << 20         # Infinity Cache; rotation footprint must be >= 2x this
 
 
+def _profiled_traffic(tag: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of
+    known size); the figure is kept with the committed counter summary under profiles/."""
+    path = os.path.join(ROOT, "profiles", "stitched_kernels_hbm_traffic_pmc.md")
+    try:
+        for line in open(path):
+            parts = line.split()
+            if len(parts) == 4 and parts[0] == "TRAFFIC_BYTES_PER_LAUNCH" and parts[1] == tag:
+                return float(parts[3])
+    except OSError:
+        pass
+    return None
+
+
 def _sets_needed(footprint: int) -> int:
     return max(2, -(-2 * (CACHE_BYTES + (32 << 20)) // max(1, footprint)))
 
@@ -179,7 +193,7 @@ def main():
                    "block": r.info["block"], "grid": r.info["grid"], "vgprs": r.info["vgprs"],
                    "buffer_sets": r.n_sets, "cold_hbm_rotation_bytes": r.n_sets * bytes_min},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": _profiled_traffic("C2"),
                      "algorithmic_bytes_per_launch": bytes_min, "us_per_launch_region": sec_step * 1e6,
                      "us_per_launch_event_pair": {"avg": avg_pair * 1e6, "median": med_pair * 1e6, "min": min_pair * 1e6}},
         "wall_ms_per_step": wall / args.steps * 1e3,

@@ -1,0 +1,41 @@
+"""Full-size parity: the five benchmark configurations at their real shapes, in the launch
+configuration the benchmark times (scheme AUTO), against the float64 oracle on the same
+seeded inputs; plus the per-op plan at the same size as a second, independent GPU
+implementation."""
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+from tests.gpu_util import TOL, check, note, run_spec
+from workloads import FULL_CONFIGS, make_inputs
+
+pytestmark = pytest.mark.gpu
+
+# output name -> use the rms floor (outputs formed by cancelling sums)
+RMS_FLOOR = {"C2": {"out"}, "C4": {"dbias"}}
+
+
+@pytest.mark.parametrize("cfg", ["C1", "C2", "C3", "C4", "C5"])
+def test_full_size_config(cfg):
+    spec = FULL_CONFIGS[cfg]()
+    note(f"  full-size {cfg}: {spec.name}: generating inputs")
+    inp = make_inputs(spec, seed=0)
+    note("  oracle")
+    ref = O.evaluate(spec, inp)
+    for scheme in ("auto", "unfused"):
+        note(f"  gpu scheme={scheme}")
+        got, _, info, _ = run_spec(spec, inp, scheme, repeat=2)
+        for name, dt in spec.outputs:
+            floor = O.rms(ref[name]) if name in RMS_FLOOR.get(cfg, ()) else 0.0
+            err = check(got[name], ref[name], dt, floor, f"{cfg}/{info['kernel']}/{name}")
+            strict = O.max_rel_err(got[name], ref[name], 0.0)
+            over = int(np.sum(np.abs(got[name] - ref[name]) > TOL[dt] * np.abs(ref[name])))
+            note(f"    {cfg} {scheme:7s} {info['kernel']:48s} {name}: max rel err {err:.3e} "
+                 f"(strict {strict:.3e}, {over} of {ref[name].size} elements over the strict bar)")
+        if cfg == "C3":
+            assert ((got["y"] == 0) == (ref["y"] == 0)).all()      # masked keys are exact zeros
+        if cfg == "C5":
+            ss = np.sum(got["out"] ** 2, axis=-1)                   # rows are unit vectors up to eps
+            assert np.max(np.abs(ss - 1.0)) < 1e-4
+        if cfg in ("C1", "C3"):
+            assert np.max(np.abs(np.sum(got["y"], axis=-1) - 1.0)) < (1e-5 if cfg == "C1" else 2e-2)
