@@ -541,11 +541,11 @@ bool build_gelu(const fs_graph& g, std::vector<Candidate>* out) {
   const int64_t counter_bytes = ((int64_t)n_col_tiles * 4 + 255) / 256 * 256;
   struct Shape { int waves, unroll; };
   for (int ticket = 0; ticket < 2; ++ticket) {
-    for (Shape sh : {Shape{4, 4}, Shape{4, 8}, Shape{8, 4}}) {
+    for (Shape sh : {Shape{4, 2}, Shape{4, 4}, Shape{8, 2}, Shape{8, 4}}) {
       const uint32_t tile_rows = sh.waves * sh.unroll;
       const uint32_t max_rb = (p.rows + tile_rows - 1) / tile_rows;
       uint32_t last_rb = 0;
-      for (uint32_t want : {64u, 128u, 256u}) {
+      for (uint32_t want : {128u, 256u}) {
         // enough workgroups to fill the chip, few enough that the partials stay small
         const uint32_t n_rb = std::min(max_rb, std::max<uint32_t>(1, want * 6 / n_col_tiles));
         if (n_rb == last_rb) continue;
@@ -576,8 +576,8 @@ bool build_gelu(const fs_graph& g, std::vector<Candidate>* out) {
           f.args.u.gelu = q;
           f.ptr[0] = ws_ref(counter_bytes);
           f.ptr[1] = out_ref(d.output_slot);
-          f.shape.block[0] = 1024;
-          f.shape.grid[0] = (p.cols / 4 + 63) / 64;
+          f.shape.block[0] = 256;
+          f.shape.grid[0] = (p.cols / 4 + 15) / 16;
           c.info.n_kernels = 2;
         }
         c.info.workspace_bytes = counter_bytes + (int64_t)n_rb * p.cols * 4;
@@ -594,18 +594,18 @@ bool build_gelu(const fs_graph& g, std::vector<Candidate>* out) {
         kc.waves_per_block = sh.waves;
         kc.waves = (double)n_rb * n_col_tiles * sh.waves;
         kc.bytes_in_flight_per_lane = 32.0 * sh.unroll;
-        kc.vgpr_estimate = 40 + 8 * sh.unroll;
+        kc.vgpr_estimate = 40 + 16 * sh.unroll;
         kc.barriers = ticket ? 5 : 1;
         kc.lds_bytes_per_block = c.info.lds_bytes;
         kc.rows_per_wave_loop = std::max(1.0, (double)p.rows / ((double)n_rb * tile_rows));
-        kc.dep_phases = 1;
+        kc.dep_phases = 0;   // software pipelined: only the first tile's load latency is exposed (added below)
         // the fold: a second launch spread over the chip, or one workgroup per column tile
         // reading n_rb partial rows with (threads / column quads) row groups in parallel
         if (ticket) {
           const double groups = std::max(1.0, sh.waves * 64.0 / (tile_cols / 4.0));
-          kc.serial_tail_s = device().mem_latency_s * (2.0 + std::ceil(n_rb / groups / 8.0));
+          kc.serial_tail_s = device().mem_latency_s * (3.0 + std::ceil(n_rb / groups / 8.0));
         } else {
-          kc.serial_tail_s = device().launch_s + device().mem_latency_s * (1.0 + std::ceil(n_rb / 16.0 / 8.0)) * 0.5;
+          kc.serial_tail_s = device().mem_latency_s + 0.5 * device().launch_s + device().mem_latency_s * std::ceil(n_rb / 16.0 / 8.0) * 0.5;
         }
         char var[48];
         snprintf(var, sizeof var, "<%s,W%d,U%d,RB%u,%s>", dtype_name(p.dt), sh.waves, sh.unroll, n_rb, ticket ? "ticket" : "fold");

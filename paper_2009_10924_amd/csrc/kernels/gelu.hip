@@ -80,14 +80,26 @@ __global__ void __launch_bounds__(WAVES * 64) k_bias_gelu_dbias(const T* __restr
 #pragma unroll
   for (int e = 0; e < VEC; ++e) acc[e] = 0.0f;
   unpack(load_raw(bias + col), b, (const T*)nullptr);
-  for (uint32_t r0 = rb * TILE_ROWS; r0 < p.rows; r0 += p.n_row_tiles * TILE_ROWS) {
-    u32x4 rx[UNROLL], rg[UNROLL];
+  // software pipeline: the loads of the next row tile are in flight while this one is
+  // computed, so a wave overlaps its own ALU phase (two quarter-rate ops per element)
+  // with its own memory phase instead of relying on the other waves of the SIMD.
+  u32x4 nx[UNROLL], ng[UNROLL];
+  auto issue = [&](uint32_t r0) {
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
       const size_t off = (size_t)min(r0 + wave + u * WAVES, p.rows - 1) * p.cols + col;
-      rx[u] = load_raw_nt(x + off);
-      rg[u] = load_raw_nt(grad + off);
+      nx[u] = load_raw_nt(x + off);
+      ng[u] = load_raw_nt(grad + off);
     }
+  };
+  const uint32_t stride = p.n_row_tiles * TILE_ROWS;
+  uint32_t r0 = rb * TILE_ROWS;
+  if (r0 < p.rows) issue(r0);
+  for (; r0 < p.rows; r0 += stride) {
+    u32x4 rx[UNROLL], rg[UNROLL];
+#pragma unroll
+    for (int u = 0; u < UNROLL; ++u) { rx[u] = nx[u]; rg[u] = ng[u]; }
+    if (r0 + stride < p.rows) issue(r0 + stride);
 #pragma unroll
     for (int u = 0; u < UNROLL; ++u) {
       const uint32_t r = r0 + wave + u * WAVES;
@@ -152,12 +164,13 @@ __global__ void __launch_bounds__(WAVES * 64) k_bias_gelu_dbias(const T* __restr
 }
 
 // ---- fold of column partials: [n_rows, cols] float32 -> [cols] --------------------------
-// Workgroup = 64 column quads x 16 row groups; each thread sums its rows in order with
-// eight independent loads in flight, LDS folds the 16 groups in order.
-__global__ void __launch_bounds__(1024) k_colfold(const float* __restrict__ partials, float* __restrict__ out, GeluP p) {
-  __shared__ f32x4 sm[16][64];
-  const uint32_t q = threadIdx.x & 63u, g = threadIdx.x >> 6;
-  const uint32_t col = (blockIdx.x * 64u + q) * 4u;
+// Workgroup = 16 column quads x 16 row groups (256 threads), so even a 3072-column fold
+// spreads over 48 compute units; each thread sums its rows in order with eight
+// independent loads in flight, LDS folds the 16 groups in order.
+__global__ void __launch_bounds__(256) k_colfold(const float* __restrict__ partials, float* __restrict__ out, GeluP p) {
+  __shared__ f32x4 sm[16][16];
+  const uint32_t q = threadIdx.x & 15u, g = threadIdx.x >> 4;
+  const uint32_t col = (blockIdx.x * 16u + q) * 4u;
   const uint32_t n = p.n_row_tiles;
   f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
   if (col < p.cols) {
@@ -189,8 +202,9 @@ using namespace fsk;
 namespace {
 template <typename T, bool TICKET>
 const void* dbias_sym(int waves, int unroll) {
+  if (waves == 4 && unroll == 2) return (const void*)k_bias_gelu_dbias<T, 4, 2, TICKET>;
   if (waves == 4 && unroll == 4) return (const void*)k_bias_gelu_dbias<T, 4, 4, TICKET>;
-  if (waves == 4 && unroll == 8) return (const void*)k_bias_gelu_dbias<T, 4, 8, TICKET>;
+  if (waves == 8 && unroll == 2) return (const void*)k_bias_gelu_dbias<T, 8, 2, TICKET>;
   if (waves == 8 && unroll == 4) return (const void*)k_bias_gelu_dbias<T, 8, 4, TICKET>;
   return nullptr;
 }
