@@ -91,7 +91,8 @@ _LIB: Optional[C.CDLL] = None
 
 
 def lib_path() -> str:
-    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfusion_stitching.so")
+    """In-tree library; FUSION_STITCHING_LIB overrides it (e.g. a sanitizer build of the host code)."""
+    return os.environ.get("FUSION_STITCHING_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libfusion_stitching.so")
 
 
 def load() -> C.CDLL:
@@ -276,6 +277,18 @@ def stream_copy(dst, src, stream: Optional[int] = None) -> None:
         stream = torch.cuda.current_stream().cuda_stream
     nbytes = src.numel() * src.element_size()
     _check(load().fs_stream_copy(C.c_void_p(dst.data_ptr()), C.c_void_p(src.data_ptr()), nbytes, C.c_void_p(stream)))
+
+
+def bind_copy(dst_ptr: int, src_ptr: int, nbytes: int, stream: int):
+    """Pre-marshalled fs_stream_copy call (for tight timing loops)."""
+    fn = load().fs_stream_copy
+    d, s_, n, st = C.c_void_p(dst_ptr), C.c_void_p(src_ptr), C.c_size_t(nbytes), C.c_void_p(stream)
+
+    def call():
+        code = fn(d, s_, n, st)
+        if code < 0:
+            _check(code)
+    return call
 
 
 # ---- torch <-> storage helpers (memory plumbing, no arithmetic) --------------------
