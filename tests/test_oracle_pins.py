@@ -13,8 +13,8 @@ import pytest
 
 from oracle import oracle as O
 from workloads import (add_bias_layernorm_graph, attention_scores_graph, bias_gelu_dbias_graph,
-                       make_inputs, quantise, softmax_graph, transpose_chain_graph,
-                       transpose_graph, valid_lengths)
+                       layernorm_backward_graph, make_inputs, quantise, softmax_backward_graph, softmax_graph,
+                       transpose_chain_graph, transpose_graph, valid_lengths)
 
 
 def _read_rows(path):
@@ -311,6 +311,67 @@ def test_transpose_chain_invariants():
     inp2["scale"] = (2.0 * sc).astype(np.float32).reshape(H, 1, 1)
     out2 = O.evaluate(g, inp2)["out"]
     np.testing.assert_allclose(out2, out, rtol=1e-5)
+
+
+# ------------------------------------------------------------------ backward patterns
+def test_softmax_backward_is_the_gradient_of_softmax():
+    rng = np.random.default_rng(11)
+    R, C = 3, 6
+    x = rng.standard_normal((R, C))
+    dy = rng.standard_normal((R, C))
+    fwd = softmax_graph(R, C, "f32")
+    y = _eval_f64(fwd, {"x": x})["y"]
+    bwd = softmax_backward_graph(R, C, "f32")
+    dx = _eval_f64(bwd, {"y": y, "dy": dy})["dx"]
+    np.testing.assert_allclose(dx.sum(axis=1), 0.0, atol=1e-14)        # rows of dx sum to zero
+    h = 1e-6
+    for i in range(R):
+        for j in range(C):
+            xp, xm = x.copy(), x.copy()
+            xp[i, j] += h
+            xm[i, j] -= h
+            lp = float(np.sum(dy * _eval_f64(fwd, {"x": xp})["y"]))
+            lm = float(np.sum(dy * _eval_f64(fwd, {"x": xm})["y"]))
+            assert dx[i, j] == pytest.approx((lp - lm) / (2 * h), abs=1e-8)
+    # a row with a uniform upstream gradient gets exactly zero
+    dx0 = _eval_f64(bwd, {"y": y, "dy": np.full((R, C), 2.5)})["dx"]
+    np.testing.assert_allclose(dx0, 0.0, atol=1e-15)
+
+
+def test_layernorm_backward_is_the_gradient_of_layernorm():
+    rng = np.random.default_rng(12)
+    R, C, eps = 3, 5, 1e-5
+    hin = rng.standard_normal((R, C))
+    dy = rng.standard_normal((R, C))
+    gamma = 1.0 + 0.1 * rng.standard_normal(C)
+    fwd = add_bias_layernorm_graph(R, C, eps=eps, out_dtype="f32")
+    zeros_rc, zeros_c = np.zeros((R, C)), np.zeros(C)
+
+    def forward(hv, gv):
+        return _eval_f64(fwd, {"x": hv, "res": zeros_rc, "bias": zeros_c, "gamma": gv, "beta": zeros_c})["out"]
+
+    mu = hin.mean(axis=1, keepdims=True)
+    rstd = 1.0 / np.sqrt(((hin - mu) ** 2).mean(axis=1, keepdims=True) + eps)
+    bwd = layernorm_backward_graph(R, C, "f32")
+    out = _eval_f64(bwd, {"h": hin, "dy": dy, "gamma": gamma, "mu": mu, "rstd": rstd})
+    assert out["dx"].shape == (R, C) and out["dgamma"].shape == (1, C) and out["dbeta"].shape == (1, C)
+    h = 1e-6
+    for i in range(R):
+        for j in range(C):
+            hp, hm = hin.copy(), hin.copy()
+            hp[i, j] += h
+            hm[i, j] -= h
+            fd = (np.sum(dy * forward(hp, gamma)) - np.sum(dy * forward(hm, gamma))) / (2 * h)
+            assert out["dx"][i, j] == pytest.approx(fd, abs=2e-8)
+    for j in range(C):
+        gp, gm = gamma.copy(), gamma.copy()
+        gp[j] += h
+        gm[j] -= h
+        fd = (np.sum(dy * forward(hin, gp)) - np.sum(dy * forward(hin, gm))) / (2 * h)
+        assert out["dgamma"][0, j] == pytest.approx(fd, abs=2e-8)
+        assert out["dbeta"][0, j] == pytest.approx(math.fsum(dy[:, j]), abs=1e-14)
+    # dx is orthogonal to the constant vector and to x_hat in every row (up to the eps term)
+    np.testing.assert_allclose(out["dx"].sum(axis=1), 0.0, atol=1e-13)
 
 
 # ------------------------------------------------------------------ misc ops + metric

@@ -204,8 +204,60 @@ def bias_gelu_graph(rows: int, cols: int, dtype: str = "bf16") -> GraphSpec:
     )
 
 
+def softmax_backward_graph(rows: int, cols: int, dtype: str = "f32") -> GraphSpec:
+    """Row softmax backward: dx = y * (dy - sum_j y_j dy_j)  (4 ops, one row reduction)."""
+    ops = [
+        _op("p", "mul", "y", "dy"),
+        _op("s", "reduce_sum", "p", axis=1),
+        _op("d", "sub", "dy", "s"),
+        _op("dx", "mul", "y", "d"),
+    ]
+    return GraphSpec(
+        name=f"softmax_backward_{dtype}_{rows}x{cols}",
+        inputs=[TensorSpec("y", dtype, (rows, cols)), TensorSpec("dy", dtype, (rows, cols))],
+        ops=ops,
+        outputs=[("dx", dtype)],
+    )
+
+
+def layernorm_backward_graph(rows: int, cols: int, dtype: str = "f32") -> GraphSpec:
+    """LayerNorm backward from saved per-row mean and reciprocal standard deviation (13 ops):
+    two row reductions for dx, two column reductions for dgamma and dbeta."""
+    ops = [
+        _op("c", "sub", "h", "mu"),
+        _op("xh", "mul", "c", "rstd"),
+        _op("g", "mul", "dy", "gamma"),
+        _op("m1", "reduce_mean", "g", axis=1),
+        _op("gx", "mul", "g", "xh"),
+        _op("m2", "reduce_mean", "gx", axis=1),
+        _op("t1", "sub", "g", "m1"),
+        _op("t2", "mul", "xh", "m2"),
+        _op("t3", "sub", "t1", "t2"),
+        _op("dx", "mul", "t3", "rstd"),
+        _op("dyx", "mul", "dy", "xh"),
+        _op("dgamma", "reduce_sum", "dyx", axis=0),
+        _op("dbeta", "reduce_sum", "dy", axis=0),
+    ]
+    return GraphSpec(
+        name=f"layernorm_backward_{dtype}_{rows}x{cols}",
+        inputs=[
+            TensorSpec("h", dtype, (rows, cols)), TensorSpec("dy", dtype, (rows, cols)),
+            TensorSpec("gamma", dtype, (cols,)),
+            TensorSpec("mu", "f32", (rows, 1)), TensorSpec("rstd", "f32", (rows, 1)),
+        ],
+        ops=ops,
+        outputs=[("dx", dtype), ("dgamma", "f32"), ("dbeta", "f32")],
+    )
+
+
 # The five configurations the build is measured on, at their full sizes, and a
 # small sibling of each that still spans several tiles and a ragged tail.
+# Backward patterns measured next to them (same transformer-block shapes).
+NEXT_CONFIGS = {
+    "N1": lambda: softmax_backward_graph(32 * 12 * 128, 128, "f16"),
+    "N2": lambda: layernorm_backward_graph(8192, 768, "f32"),
+}
+
 FULL_CONFIGS = {
     "C1": lambda: softmax_graph(64, 128, "f32"),
     "C2": lambda: add_bias_layernorm_graph(8192, 768),
