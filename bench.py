@@ -272,6 +272,9 @@ def main():
         others["C1_rows_2pow20"] = measure_config("C1_large", softmax_graph(1 << 20, 128, "f32"), 30, 5, with_unfused=False)
         torch.cuda.empty_cache()
         result["other_configs"] = others
+        from workloads import NEXT_CONFIGS
+        result["backward_patterns"] = {name: measure_config(name, NEXT_CONFIGS[name](), max(50, args.steps // 4), 20)
+                                       for name in ("N1", "N2")}
     print(json.dumps(result))
 
 

@@ -54,6 +54,7 @@ CostResult evaluate(const KernelCost& k, int32_t vgprs_compiled) {
   if (k.store_run_bytes > 0 && k.store_run_bytes < 512) bw *= 0.97;
   bw /= 1.0 + 0.3 * (1.0 / util - 1.0);
   bw /= 1.0 + 0.25 * (rounds / rounds_exact - 1.0);
+  if (occ < 4) bw /= 1.0 + 0.04 * (4.0 - occ);   // few waves per SIMD: a wave's own stalls are not covered
   const double t_hbm = k.hbm_bytes / bw;
   const double t_cache = k.cache_bytes / d.l2_Bps;
   const double t_lds = k.lds_traffic_bytes / d.lds_Bps;

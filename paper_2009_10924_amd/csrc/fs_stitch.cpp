@@ -465,6 +465,20 @@ bool build_layernorm(const fs_graph& g, std::vector<Candidate>* out) {
   return true;
 }
 
+// Fold launch of [n_rows, width] float32 column partials (see k_colfold).
+void make_fold_launch(Launch* f, uint32_t n_rows, uint32_t width, uint32_t split) {
+  f->kernel = K_COLFOLD;
+  GeluP fp{};
+  fp.n_row_tiles = n_rows;
+  fp.cols = width;
+  fp.fold_cols = width;
+  fp.fold_split = split;
+  fp.fold_quads = n_rows > 128 ? 4 : 16;
+  f->args.u.gelu = fp;
+  f->shape.block[0] = 256;
+  f->shape.grid[0] = (width / 4 + fp.fold_quads - 1) / fp.fold_quads;
+}
+
 // ------------------------------------------------------------------ bias-GELU family
 bool build_gelu(const fs_graph& g, std::vector<Candidate>* out) {
   MatchState st;
@@ -572,12 +586,9 @@ bool build_gelu(const fs_graph& g, std::vector<Candidate>* out) {
         if (!ticket) {
           c.launches.emplace_back();
           Launch& f = c.launches.back();
-          f.kernel = K_COLFOLD;
-          f.args.u.gelu = q;
+          make_fold_launch(&f, n_rb, p.cols, p.cols);
           f.ptr[0] = ws_ref(counter_bytes);
           f.ptr[1] = out_ref(d.output_slot);
-          f.shape.block[0] = 256;
-          f.shape.grid[0] = (p.cols / 4 + 15) / 16;
           c.info.n_kernels = 2;
         }
         c.info.workspace_bytes = counter_bytes + (int64_t)n_rb * p.cols * 4;
@@ -709,6 +720,191 @@ bool build_tchain(const fs_graph& g, std::vector<Candidate>* out) {
   return true;
 }
 
+// ------------------------------------------------------------------ generic row patterns
+// dx = y * (dy - rowsum(y * dy))
+bool build_softmax_backward(const fs_graph& g, std::vector<Candidate>* out) {
+  if (g.outputs.size() != 1) return false;
+  Pattern pat("mul($Y,sub($DY,rsum[-1](mul($Y,$DY))))");
+  MatchState st;
+  if (!pat.match(g, g.outputs[0], &st) || !covers_all(g, st)) return false;
+  const int32_t ty = st.tensors["Y"], tdy = st.tensors["DY"];
+  if (!is_input(g, ty) || !is_input(g, tdy)) return false;
+  const Tensor& y = g.tensors[ty];
+  const Tensor& dy = g.tensors[tdy];
+  const Tensor& dx = g.tensors[g.outputs[0]];
+  if (!same_dims(y, dy) || y.dtype != dy.dtype || dx.store_as != y.dtype || y.dtype == FS_I32) return true;
+  RowP p{};
+  p.pattern = ROW_SOFTMAX_BWD;
+  p.dt = y.dtype;
+  p.cols = (uint32_t)y.dims[y.rank - 1];
+  p.rows = (uint32_t)(y.numel() / p.cols);
+  const int VEC = vec_of(p.dt);
+  if (p.cols % VEC != 0) return true;
+  const uint32_t nvec = p.cols / VEC;
+  const int esz = dtype_bytes(p.dt);
+  for (int K : {1, 2, 4, 8}) {
+    const uint32_t L = pow2_at_least((nvec + K - 1) / K);
+    if (L > 64) continue;
+    if (K > 1 && (uint64_t)L * K >= 2ull * nvec) continue;
+    if (K * 2 > 8) continue;   // two inputs: keep the raw row within 8 vectors per lane
+    Candidate c = make_candidate(g, "softmax_backward", L == 1 ? FS_SCHEME_LOCAL : FS_SCHEME_WAVE, K_ROW_WAVE);
+    Launch& l = c.launches.front();
+    RowP q = p;
+    q.lanes_per_row = (int32_t)L;
+    q.lanes_log2 = log2_of(L);
+    q.vecs_per_lane = K;
+    q.fast = (uint64_t)L * K == nvec && p.rows % (256 / L) == 0;
+    l.args.u.row = q;
+    l.ptr[0] = in_ref(g, ty);
+    l.ptr[1] = in_ref(g, tdy);
+    l.ptr[4] = out_ref(0);
+    l.shape.block[0] = 256;
+    const uint32_t rows_per_block = 256 / L;
+    l.shape.grid[0] = (p.rows + rows_per_block - 1) / rows_per_block;
+    c.info.lanes_per_row = (int32_t)L;
+    c.info.vecs_per_lane = K;
+    c.info.rows_per_block = (int32_t)rows_per_block;
+    KernelCost kc;
+    kc.hbm_bytes = 3.0 * p.rows * (double)p.cols * esz;
+    kc.elems = (double)p.rows * p.cols;
+    kc.valu_per_elem = 4.0 + (esz == 2 ? 2.5 : 0.0);
+    kc.waves = (double)l.shape.grid[0] * 4;
+    kc.waves_per_block = 4;
+    kc.bytes_in_flight_per_lane = 32.0 * K;
+    kc.vgpr_estimate = 12 + K * (2 * VEC + 8);
+    int steps = 0;
+    for (uint32_t s = 1; s < L; s <<= 1) ++steps;
+    kc.xlane_steps = steps;
+    kc.lane_utilisation = (double)nvec / ((double)L * K);
+    kc.access_run_bytes = std::min<double>(L, nvec) * 16.0;
+    char var[40];
+    snprintf(var, sizeof var, "<softmax_bwd,%s,K%d,L%u>", dtype_name(p.dt), K, L);
+    finish_candidate(&c, var, kc);
+    out->push_back(c);
+  }
+  return true;
+}
+
+// ------------------------------------------------------------------ layernorm backward
+bool build_layernorm_backward(const fs_graph& g, std::vector<Candidate>* out) {
+  if (g.outputs.size() != 3) return false;
+  const std::string xh = "mul(sub($H,$MU),$RS)", gg = "mul($DY,$G)";
+  Pattern p_dx("mul(sub(sub(" + gg + ",rmean[-1](" + gg + ")),mul(" + xh + ",rmean[-1](mul(" + gg + "," + xh + ")))),$RS)");
+  Pattern p_dg("rsum[-2](mul($DY," + xh + "))");
+  Pattern p_db("rsum[-2]($DY)");
+  MatchState st;
+  int32_t t_dx = -1, t_dg = -1, t_db = -1;
+  // dx binds every name; then the two column sums must agree with those bindings
+  for (int32_t t : g.outputs)
+    if (t_dx < 0 && p_dx.match(g, t, &st)) t_dx = t;
+  if (t_dx < 0) return false;
+  for (int32_t t : g.outputs) {
+    if (t == t_dx) continue;
+    if (t_dg < 0 && p_dg.match(g, t, &st)) { t_dg = t; continue; }
+    if (t_db < 0 && p_db.match(g, t, &st)) { t_db = t; continue; }
+  }
+  if (t_dg < 0 || t_db < 0 || !covers_all(g, st)) return false;
+  const int32_t th = st.tensors["H"], tdy = st.tensors["DY"], tg = st.tensors["G"], tmu = st.tensors["MU"], trs = st.tensors["RS"];
+  for (int32_t t : {th, tdy, tg, tmu, trs})
+    if (!is_input(g, t)) return false;
+  const Tensor& h = g.tensors[th];
+  if (h.rank != 2) return true;
+  LnBwdP p{};
+  p.rows = (uint32_t)h.dims[0];
+  p.cols = (uint32_t)h.dims[1];
+  p.dt = h.dtype;
+  p.inv_cols = (float)(1.0 / (double)p.cols);
+  const Tensor& mu = g.tensors[tmu];
+  const Tensor& rs = g.tensors[trs];
+  auto per_row = [&](const Tensor& t) { return t.rank == 2 && t.dims[0] == (int64_t)p.rows && t.dims[1] == 1 && t.dtype == FS_F32; };
+  if (!same_dims(g.tensors[tdy], h) || g.tensors[tdy].dtype != p.dt || !is_row_vector(g.tensors[tg], p.cols) ||
+      g.tensors[tg].dtype != p.dt || !per_row(mu) || !per_row(rs) || p.dt == FS_I32)
+    return true;
+  if (g.tensors[t_dx].store_as != p.dt || g.tensors[t_dg].store_as != FS_F32 || g.tensors[t_db].store_as != FS_F32) return true;
+  const int VEC = vec_of(p.dt);
+  if (p.cols % VEC != 0) return true;
+  const uint32_t nvec = p.cols / VEC;
+  const int esz = dtype_bytes(p.dt);
+  const double n = (double)p.rows * p.cols;
+  for (int K : {1, 2, 3, 4, 6}) {
+    const uint32_t L = pow2_at_least((nvec + K - 1) / K);
+    if (L > 64) continue;
+    if (K > 1 && (uint64_t)L * K >= 2ull * nvec) continue;
+    struct Shape { int waves, r; };
+    for (Shape sh : {Shape{4, 1}, Shape{4, 2}, Shape{4, 4}, Shape{8, 1}, Shape{8, 2}}) {
+      if (sh.r * K > 8) continue;                      // raw rows held in registers: at most 16 vectors
+      const uint32_t groups = sh.waves * 64 / L;
+      const int64_t lds_bytes = (int64_t)groups * 2 * p.cols * 4;
+      if (lds_bytes > 64 * 1024) continue;
+      const uint32_t tile_rows = groups * sh.r;
+      const uint32_t n_tiles = (p.rows + tile_rows - 1) / tile_rows;
+      uint32_t last = 0;
+      for (uint32_t want : {512u, 1024u, 2048u}) {
+        const uint32_t n_rb = std::min<uint32_t>(want, n_tiles);
+        if (n_rb == last) continue;
+        last = n_rb;
+        Candidate c = make_candidate(g, "layernorm_backward", FS_SCHEME_GLOBAL, K_LAYERNORM_BWD);
+        LnBwdP q = p;
+        q.lanes_per_row = (int32_t)L;
+        q.lanes_log2 = log2_of(L);
+        q.vecs_per_lane = K;
+        q.waves = sh.waves;
+        q.rows_per_group = sh.r;
+        {
+          Launch& l = c.launches.front();
+          l.args.u.lnbwd = q;
+          l.ptr[0] = in_ref(g, th);
+          l.ptr[1] = in_ref(g, tdy);
+          l.ptr[2] = in_ref(g, tg);
+          l.ptr[3] = in_ref(g, tmu);
+          l.ptr[4] = in_ref(g, trs);
+          l.ptr[5] = out_ref(g.tensors[t_dx].output_slot);
+          l.ptr[6] = ws_ref(0);
+          l.shape.block[0] = sh.waves * 64;
+          l.shape.grid[0] = n_rb;
+          l.shape.lds_bytes = (uint32_t)lds_bytes;
+        }
+        c.launches.emplace_back();
+        Launch& f = c.launches.back();
+        make_fold_launch(&f, n_rb, 2 * p.cols, p.cols);
+        f.ptr[0] = ws_ref(0);
+        f.ptr[1] = out_ref(g.tensors[t_dg].output_slot);
+        f.ptr[2] = out_ref(g.tensors[t_db].output_slot);
+        c.info.n_kernels = 2;
+        c.info.workspace_bytes = (int64_t)n_rb * 2 * p.cols * 4;
+        c.info.lanes_per_row = (int32_t)L;
+        c.info.vecs_per_lane = K;
+        c.info.rows_per_block = (int32_t)tile_rows;
+        c.info.lds_bytes = (int32_t)lds_bytes;
+        c.info.bytes_moved_model = c.info.bytes_min + 2 * c.info.workspace_bytes;
+        KernelCost kc;
+        kc.hbm_bytes = 3 * n * esz + 2.0 * (double)c.info.workspace_bytes;
+        kc.elems = n;
+        kc.valu_per_elem = 12 + (esz == 2 ? 3 : 0);
+        kc.waves_per_block = sh.waves;
+        kc.waves = (double)n_rb * sh.waves;
+        kc.bytes_in_flight_per_lane = 32.0 * K * sh.r;
+        kc.vgpr_estimate = 24 + K * (VEC * 5 + 8 * sh.r);
+        int steps = 0;
+        for (uint32_t s2 = 1; s2 < L; s2 <<= 1) ++steps;
+        kc.xlane_steps = 2 * steps * sh.r;
+        kc.barriers = 0;
+        kc.lds_bytes_per_block = (int32_t)lds_bytes;
+        kc.rows_per_wave_loop = std::max(1.0, (double)n_tiles / n_rb);
+        kc.dep_phases = 1;
+        kc.lane_utilisation = (double)nvec / ((double)L * K);
+        kc.access_run_bytes = std::min<double>(L, nvec) * 16.0;
+        kc.serial_tail_s = device().mem_latency_s + 0.5 * device().launch_s + device().mem_latency_s * std::ceil(n_rb / 16.0 / 8.0) * 0.5;
+        char var[56];
+        snprintf(var, sizeof var, "<%s,K%d,L%u,W%d,R%d,RB%u>", dtype_name(p.dt), K, L, sh.waves, sh.r, n_rb);
+        finish_candidate(&c, var, kc);
+        out->push_back(c);
+      }
+    }
+  }
+  return true;
+}
+
 // ------------------------------------------------------------------ lone transpose
 bool build_transpose(const fs_graph& g, std::vector<Candidate>* out) {
   if (g.ops.size() != 1 || g.ops[0].opcode != FS_TRANSPOSE || g.outputs.size() != 1) return false;
@@ -740,7 +936,8 @@ std::string build_stitched(const fs_graph& g, std::vector<Candidate>* out) {
   struct Family { const char* name; bool (*build)(const fs_graph&, std::vector<Candidate>*); };
   static const Family families[] = {
       {"softmax", build_softmax}, {"layernorm", build_layernorm}, {"bias_gelu", build_gelu},
-      {"transpose_chain", build_tchain}, {"transpose", build_transpose},
+      {"transpose_chain", build_tchain}, {"softmax_backward", build_softmax_backward},
+      {"layernorm_backward", build_layernorm_backward}, {"transpose", build_transpose},
   };
   for (const Family& f : families) {
     out->clear();

@@ -163,34 +163,38 @@ __global__ void __launch_bounds__(WAVES * 64) k_bias_gelu_dbias(const T* __restr
   }
 }
 
-// ---- fold of column partials: [n_rows, cols] float32 -> [cols] --------------------------
-// Workgroup = 16 column quads x 16 row groups (256 threads), so even a 3072-column fold
-// spreads over 48 compute units; each thread sums its rows in order with eight
-// independent loads in flight, LDS folds the 16 groups in order.
-__global__ void __launch_bounds__(256) k_colfold(const float* __restrict__ partials, float* __restrict__ out, GeluP p) {
-  __shared__ f32x4 sm[16][16];
-  const uint32_t q = threadIdx.x & 15u, g = threadIdx.x >> 4;
-  const uint32_t col = (blockIdx.x * 16u + q) * 4u;
-  const uint32_t n = p.n_row_tiles;
+// ---- fold of column partials: [n_rows, width] float32 -> [width] -------------------------
+// Workgroup = Q column quads x G row groups (256 threads).  Each thread sums its rows in
+// order with eight independent loads in flight, LDS folds the G groups in order.  Few
+// partial rows: (Q,G) = (16,16); many: (4,64), so a thread still needs one batch of loads.
+template <int Q, int G>
+__global__ void __launch_bounds__(256) k_colfold(const float* __restrict__ partials, float* __restrict__ out0,
+                                                 float* __restrict__ out1, GeluP p) {
+  __shared__ f32x4 sm[G][Q];
+  const uint32_t q = threadIdx.x % Q, g = threadIdx.x / Q;
+  const uint32_t col = (blockIdx.x * Q + q) * 4u;
+  const uint32_t n = p.n_row_tiles, width = p.fold_cols;
   f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
-  if (col < p.cols) {
+  if (col < width) {
     uint32_t t = g;
-    for (; t + 7 * 16 < n; t += 8 * 16) {
+    for (; t + 7 * G < n; t += 8 * G) {
       f32x4 v[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x4*>(partials + (size_t)(t + u * 16) * p.cols + col);
+      for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x4*>(partials + (size_t)(t + u * G) * width + col);
 #pragma unroll
       for (int u = 0; u < 8; ++u) s += v[u];
     }
-    for (; t < n; t += 16) s += *reinterpret_cast<const f32x4*>(partials + (size_t)t * p.cols + col);
+    for (; t < n; t += G) s += *reinterpret_cast<const f32x4*>(partials + (size_t)t * width + col);
   }
   sm[g][q] = s;
   __syncthreads();
-  if (g == 0 && col < p.cols) {
+  if (g == 0 && col < width) {
     f32x4 v = sm[0][q];
 #pragma unroll
-    for (int k = 1; k < 16; ++k) v += sm[k][q];
-    *reinterpret_cast<f32x4*>(out + col) = v;
+    for (int k = 1; k < G; ++k) v += sm[k][q];
+    // fold_split is a multiple of 4, so a quad never straddles the two outputs
+    float* dst = col < p.fold_split ? out0 + col : out1 + (col - p.fold_split);
+    *reinterpret_cast<f32x4*>(dst) = v;
   }
 }
 
@@ -217,7 +221,7 @@ const void* gelu_sym(int32_t kernel, const GeluP& p) {
 
 const void* gelu_kernel_symbol(int32_t kernel, const KernelArgs& a) {
   const GeluP& p = a.u.gelu;
-  if (kernel == K_COLFOLD) return (const void*)k_colfold;
+  if (kernel == K_COLFOLD) return p.fold_quads == 4 ? (const void*)k_colfold<4, 64> : (const void*)k_colfold<16, 16>;
   switch (p.dt) {
     case DT_F32: return gelu_sym<float>(kernel, p);
     case DT_F16: return gelu_sym<f16_t>(kernel, p);

@@ -8,4 +8,5 @@ const void* softmax_kernel_symbol(int32_t kernel, const KernelArgs& a);
 const void* layernorm_kernel_symbol(int32_t kernel, const KernelArgs& a);
 const void* gelu_kernel_symbol(int32_t kernel, const KernelArgs& a);
 const void* tchain_kernel_symbol(int32_t kernel, const KernelArgs& a);
+const void* rowops_kernel_symbol(int32_t kernel, const KernelArgs& a);
 }  // namespace fs

@@ -15,7 +15,8 @@ const KernelDesc kDesc[K_COUNT] = {
     {"unary", 2},          {"binary", 3},          {"reduce_row", 2},     {"reduce_mid", 2},
     {"transpose_rows", 2}, {"transpose_tile", 2},  {"copy", 2},           {"softmax_wave", 3},
     {"softmax_block", 3},  {"layernorm_wave", 6},  {"layernorm_block", 6}, {"bias_gelu", 3},
-    {"bias_gelu_dbias", 7}, {"colfold", 2},        {"tchain_wave", 3},    {"tchain_lds", 3},
+    {"bias_gelu_dbias", 7}, {"colfold", 3},        {"tchain_wave", 3},    {"tchain_lds", 3},
+    {"row_wave", 6},       {"layernorm_bwd", 7},
 };
 
 const void* symbol_for(int32_t kernel, const KernelArgs& a) {
@@ -25,12 +26,14 @@ const void* symbol_for(int32_t kernel, const KernelArgs& a) {
       return unfused_kernel_symbol(kernel, a);
     case K_SOFTMAX_WAVE: case K_SOFTMAX_BLOCK:
       return softmax_kernel_symbol(kernel, a);
-    case K_LAYERNORM_WAVE: case K_LAYERNORM_BLOCK:
+    case K_LAYERNORM_WAVE: case K_LAYERNORM_BLOCK: case K_LAYERNORM_BWD:
       return layernorm_kernel_symbol(kernel, a);
     case K_BIAS_GELU: case K_BIAS_GELU_DBIAS: case K_COLFOLD:
       return gelu_kernel_symbol(kernel, a);
     case K_TCHAIN_WAVE: case K_TCHAIN_LDS:
       return tchain_kernel_symbol(kernel, a);
+    case K_ROW_WAVE:
+      return rowops_kernel_symbol(kernel, a);
     default:
       return nullptr;
   }

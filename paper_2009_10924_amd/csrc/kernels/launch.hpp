@@ -27,9 +27,11 @@ enum KernelId : int32_t {
   K_LAYERNORM_BLOCK,
   K_BIAS_GELU,         // p0 x, p1 bias, p2 y
   K_BIAS_GELU_DBIAS,   // p0 x, p1 bias, p2 grad, p3 y, p4 dbias, p5 partials, p6 counters
-  K_COLFOLD,           // p0 partials [n_row_tiles, cols] f32, p1 out [cols] f32
+  K_COLFOLD,           // p0 partials [n_row_tiles, fold_cols] f32, p1 out0 (columns < fold_split), p2 out1 (the rest)
   K_TCHAIN_WAVE,       // p0 x, p1 scale, p2 out
   K_TCHAIN_LDS,
+  K_ROW_WAVE,          // p0..p3 row inputs, p4 out0, p5 out1 : generic row-stitched skeleton
+  K_LAYERNORM_BWD,     // p0 h, p1 dy, p2 gamma, p3 mu, p4 rstd, p5 dx, p6 partials [n_row_blocks, 2, cols]
   K_COUNT
 };
 
@@ -104,6 +106,8 @@ struct GeluP {
   uint32_t n_row_tiles;             // row blocks = rows of the partials workspace
   int32_t waves, unroll;            // workgroup = waves x 64 lanes; a row tile = waves * unroll rows
   int32_t ticket;                   // 1: fold inside the launch (last ticket), 0: fold by K_COLFOLD
+  uint32_t fold_cols, fold_split;   // K_COLFOLD: columns of the partials, first column that goes to the second output
+  uint32_t fold_quads;              // K_COLFOLD: column quads per workgroup (16 with 16 row groups, or 4 with 64)
 };
 struct TChainP {
   int32_t dt, scale_dt;
@@ -113,6 +117,21 @@ struct TChainP {
   int32_t passes;                   // rows each lane group handles = ceil(s_tile * H / groups), 1..4
   int32_t lanes_log2;
   FastDiv div_h, div_s_tiles;       // division by H and by the number of s tiles per batch entry
+};
+
+struct LnBwdP {
+  int32_t dt;                       // h / dy / gamma / dx share dt; mu, rstd, dgamma, dbeta are float32
+  uint32_t rows, cols;
+  float inv_cols;
+  int32_t lanes_per_row, lanes_log2, vecs_per_lane;
+  int32_t waves, rows_per_group;    // workgroup = waves x 64 lanes; rows each lane group loads up front
+};
+enum RowPattern : int32_t { ROW_SOFTMAX_BWD = 0 };
+struct RowP {
+  int32_t pattern, dt;              // all row inputs and outputs share dt
+  uint32_t rows, cols;
+  float f[4];                       // pattern scalars
+  int32_t lanes_per_row, lanes_log2, vecs_per_lane, fast;
 };
 
 struct KernelArgs {
@@ -126,6 +145,8 @@ struct KernelArgs {
     LayerNormP layernorm;
     GeluP gelu;
     TChainP tchain;
+    RowP row;
+    LnBwdP lnbwd;
   } u;
   KernelArgs() { u.binary = BinaryP{}; }
 };

@@ -176,12 +176,141 @@ __global__ void __launch_bounds__(256) k_layernorm_block(const TI* __restrict__ 
   }
 }
 
+// ---- LayerNorm backward ------------------------------------------------------------------
+//   xh = (h - mu) rstd;  g = dy gamma;  dx = (g - mean(g) - xh mean(g xh)) rstd
+//   dgamma = colsum(dy xh);  dbeta = colsum(dy)                      -- 13 ops, one launch + fold
+// Row part: warp composition as in the forward kernel (two row reductions, issued
+// together).  Column part: a lane keeps the column sums of the rows it has seen in
+// registers while its lane group walks rows g, g + G, ... (software pipelined); the
+// lane groups of a workgroup meet in LDS (regional step) and each workgroup leaves one
+// [2, cols] row of partials for the fold launch (global step).
+// A workgroup of WAVES wavefronts = G lane groups handles tiles of G*R consecutive rows
+// (lane group g takes rows g, g+G, ... of the tile); the R rows of a lane group are all
+// requested before the first is used.  With one tile per workgroup the whole problem
+// runs as a single round of resident wavefronts, like the forward kernel; with more
+// tiles than workgroups the column sums simply keep accumulating.
+template <typename T, int K, int R, int WAVES>
+__global__ void __launch_bounds__(WAVES * 64) k_layernorm_bwd(const T* __restrict__ h, const T* __restrict__ dy,
+                                                              const T* __restrict__ gamma, const float* __restrict__ mu,
+                                                              const float* __restrict__ rstd, T* __restrict__ dx,
+                                                              float* __restrict__ partials, LnBwdP p) {
+  constexpr int VEC = Elem<T>::VEC;
+  constexpr uint32_t NT = WAVES * 64;
+  extern __shared__ float lds[];                       // [groups][2][cols]
+  const uint32_t L = p.lanes_per_row;
+  const uint32_t groups = NT >> p.lanes_log2;
+  const uint32_t group = threadIdx.x >> p.lanes_log2, lane = threadIdx.x & (L - 1);
+  const uint32_t nvec = p.cols / VEC;
+  auto vec_at = [&](int k) { return min(lane + k * L, nvec - 1); };
+  auto valid = [&](int k) { return lane + k * L < nvec; };
+
+  float gam[K][VEC], dg[K][VEC], db[K][VEC];
+  {
+    u32x4 rg[K];
+#pragma unroll
+    for (int k = 0; k < K; ++k) rg[k] = load_raw(gamma + vec_at(k) * VEC);
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      unpack(rg[k], gam[k], (const T*)nullptr);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) { dg[k][e] = 0.0f; db[k][e] = 0.0f; }
+    }
+  }
+  const uint32_t tile_rows = groups * R;
+  const uint32_t n_tiles = (p.rows + tile_rows - 1) / tile_rows;
+  for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+    u32x4 rh[R][K], rd[R][K];
+    float rmu[R], rrs[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const uint32_t rc = min(tile * tile_rows + r * groups + group, p.rows - 1);
+      const size_t base = (size_t)rc * p.cols;
+#pragma unroll
+      for (int k = 0; k < K; ++k) {
+        rh[r][k] = load_raw_nt(h + base + vec_at(k) * VEC);
+        rd[r][k] = load_raw_nt(dy + base + vec_at(k) * VEC);
+      }
+      rmu[r] = mu[rc];
+      rrs[r] = rstd[rc];
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const uint32_t row = tile * tile_rows + r * groups + group;
+      const bool row_ok = row < p.rows;
+      float xh[K][VEC], g[K][VEC];
+      float s1 = 0.0f, s2 = 0.0f;
+#pragma unroll
+      for (int k = 0; k < K; ++k) {
+        float dv[VEC];
+        unpack(rh[r][k], xh[k], (const T*)nullptr);
+        unpack(rd[r][k], dv, (const T*)nullptr);
+        const bool ok = row_ok && valid(k);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+          const float d = ok ? dv[e] : 0.0f;             // padding and past-the-end rows contribute nothing
+          xh[k][e] = (xh[k][e] - rmu[r]) * rrs[r];
+          g[k][e] = d * gam[k][e];
+          s1 += g[k][e];
+          s2 = __builtin_fmaf(g[k][e], xh[k][e], s2);
+          dg[k][e] = __builtin_fmaf(d, xh[k][e], dg[k][e]);
+          db[k][e] += d;
+        }
+      }
+      const float m1 = group_allreduce<OpSum>(s1, (int)L) * p.inv_cols;
+      const float m2 = group_allreduce<OpSum>(s2, (int)L) * p.inv_cols;
+      const size_t base = (size_t)min(row, p.rows - 1) * p.cols;
+#pragma unroll
+      for (int k = 0; k < K; ++k) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) g[k][e] = (g[k][e] - m1 - xh[k][e] * m2) * rrs[r];
+        if (row_ok && valid(k)) store_vec_nt(dx + base + (lane + k * L) * VEC, g[k]);
+      }
+    }
+  }
+  // regional step: lane groups of the workgroup meet in LDS, folded in group order
+#pragma unroll
+  for (int k = 0; k < K; ++k) {
+    if (valid(k)) {
+      float* a = lds + (size_t)(group * 2) * p.cols + (lane + k * L) * VEC;
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) { a[e] = dg[k][e]; a[p.cols + e] = db[k][e]; }
+    }
+  }
+  __syncthreads();
+  float* prow = partials + (size_t)blockIdx.x * 2 * p.cols;
+  for (uint32_t c = threadIdx.x; c < 2 * p.cols; c += NT) {
+    float s = lds[c];
+    for (uint32_t gi = 1; gi < groups; ++gi) s += lds[(size_t)gi * 2 * p.cols + c];
+    prow[c] = s;
+  }
+}
+
 }  // namespace fsk
 
 namespace fs {
 using namespace fsk;
 
 namespace {
+template <typename T, int R, int WAVES>
+const void* ln_bwd_sym_k(int K) {
+  switch (K) {
+    case 1: return (const void*)k_layernorm_bwd<T, 1, R, WAVES>;
+    case 2: return (const void*)k_layernorm_bwd<T, 2, R, WAVES>;
+    case 3: return (const void*)k_layernorm_bwd<T, 3, R, WAVES>;
+    case 4: return (const void*)k_layernorm_bwd<T, 4, R, WAVES>;
+    case 6: return (const void*)k_layernorm_bwd<T, 6, R, WAVES>;
+    default: return nullptr;
+  }
+}
+template <typename T>
+const void* ln_bwd_sym(const LnBwdP& b) {
+  if (b.waves == 4 && b.rows_per_group == 1) return ln_bwd_sym_k<T, 1, 4>(b.vecs_per_lane);
+  if (b.waves == 4 && b.rows_per_group == 2) return ln_bwd_sym_k<T, 2, 4>(b.vecs_per_lane);
+  if (b.waves == 4 && b.rows_per_group == 4) return ln_bwd_sym_k<T, 4, 4>(b.vecs_per_lane);
+  if (b.waves == 8 && b.rows_per_group == 1) return ln_bwd_sym_k<T, 1, 8>(b.vecs_per_lane);
+  if (b.waves == 8 && b.rows_per_group == 2) return ln_bwd_sym_k<T, 2, 8>(b.vecs_per_lane);
+  return nullptr;
+}
 template <typename TI, typename TO>
 const void* ln_sym(int32_t kernel, int K, bool fast) {
 #define FS_LN_CASE(KK)                                                                                     \
@@ -200,6 +329,14 @@ const void* ln_sym(int32_t kernel, int K, bool fast) {
 }  // namespace
 
 const void* layernorm_kernel_symbol(int32_t kernel, const KernelArgs& a) {
+  if (kernel == K_LAYERNORM_BWD) {
+    const LnBwdP& b = a.u.lnbwd;
+    switch (b.dt) {
+      case DT_F32: return ln_bwd_sym<float>(b);
+      case DT_F16: return ln_bwd_sym<f16_t>(b);
+      default: return ln_bwd_sym<bf16_t>(b);
+    }
+  }
   const LayerNormP& p = a.u.layernorm;
   const int K = p.vecs_per_lane;
   if (p.in_dt == DT_F32 && p.out_dt == DT_F32) return ln_sym<float, float>(kernel, K, p.fast != 0);

@@ -7,17 +7,18 @@ import pytest
 
 from oracle import oracle as O
 from tests.gpu_util import TOL, check, note, run_spec
-from workloads import FULL_CONFIGS, make_inputs
+from workloads import FULL_CONFIGS, NEXT_CONFIGS, make_inputs
 
 pytestmark = pytest.mark.gpu
 
 # output name -> use the rms floor (outputs formed by cancelling sums)
-RMS_FLOOR = {"C2": {"out"}, "C4": {"dbias"}}
+RMS_FLOOR = {"C2": {"out"}, "C4": {"dbias"}, "N1": {"dx"}, "N2": {"dx", "dgamma", "dbeta"}}
+ALL = dict(FULL_CONFIGS, **NEXT_CONFIGS)
 
 
-@pytest.mark.parametrize("cfg", ["C1", "C2", "C3", "C4", "C5"])
+@pytest.mark.parametrize("cfg", ["C1", "C2", "C3", "C4", "C5", "N1", "N2"])
 def test_full_size_config(cfg):
-    spec = FULL_CONFIGS[cfg]()
+    spec = ALL[cfg]()
     note(f"  full-size {cfg}: {spec.name}: generating inputs")
     inp = make_inputs(spec, seed=0)
     note("  oracle")

@@ -8,7 +8,8 @@ from oracle import oracle as O
 from paper_2009_10924_amd import binding as B
 from tests.gpu_util import TOL, check, note, run_spec
 from workloads import (add_bias_layernorm_graph, attention_scores_graph, bias_gelu_dbias_graph, bias_gelu_graph,
-                       make_inputs, softmax_graph, transpose_chain_graph, transpose_graph)
+                       layernorm_backward_graph, make_inputs, softmax_backward_graph, softmax_graph,
+                       transpose_chain_graph, transpose_graph)
 from workloads.graphs import GraphSpec, OpSpec, TensorSpec
 
 pytestmark = pytest.mark.gpu
@@ -137,6 +138,30 @@ def test_transpose_chain(B_, S, H, D, dtype):
     ref = O.evaluate(spec, inp)
     worst = all_candidates(spec, inp, ref, {})
     note(f"transpose_chain {B_}x{S}x{H}x{D} {dtype}: worst {worst}")
+
+
+# ------------------------------------------------------------------ backward patterns
+# Their outputs are differences of nearly equal terms (dy - sum y dy; g - mean g - ...), so the
+# rms floor applies as for the LayerNorm output.
+@pytest.mark.parametrize("rows,cols,dtype", [(301, 128, "f32"), (64, 128, "f16"), (37, 4, "f32"), (19, 1000, "f32"),
+                                             (7, 1024, "bf16"), (33, 37, "f32"), (5, 4096, "f32")])
+def test_softmax_backward(rows, cols, dtype):
+    spec = softmax_backward_graph(rows, cols, dtype)
+    inp = make_inputs(spec, seed=0)
+    ref = O.evaluate(spec, inp)
+    worst = all_candidates(spec, inp, ref, {"dx": O.rms(ref["dx"])}, repeat=2)
+    note(f"softmax backward {rows}x{cols} {dtype}: {worst}")
+
+
+@pytest.mark.parametrize("rows,cols,dtype", [(67, 768, "f32"), (300, 256, "f32"), (9, 1024, "bf16"), (11, 100, "f32"),
+                                             (5, 4, "f32"), (130, 520, "f16"), (1, 8, "f32"), (1030, 64, "f32")])
+def test_layernorm_backward(rows, cols, dtype):
+    spec = layernorm_backward_graph(rows, cols, dtype)
+    inp = make_inputs(spec, seed=0)
+    ref = O.evaluate(spec, inp)
+    floors = {k: O.rms(ref[k]) for k in ("dx", "dgamma", "dbeta")}
+    worst = all_candidates(spec, inp, ref, floors, repeat=2)
+    note(f"layernorm backward {rows}x{cols} {dtype}: {worst}")
 
 
 # ------------------------------------------------------------------ transpose: bit-exact
