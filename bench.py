@@ -273,8 +273,9 @@ def main():
         torch.cuda.empty_cache()
         result["other_configs"] = others
         from workloads import NEXT_CONFIGS
-        result["backward_patterns"] = {name: measure_config(name, NEXT_CONFIGS[name](), max(50, args.steps // 4), 20)
-                                       for name in ("N1", "N2")}
+        # patterns beyond the five configurations: softmax / LayerNorm backward, innermost-axis-moving transposes
+        result["next_patterns"] = {name: measure_config(name, NEXT_CONFIGS[name](), max(50, args.steps // 4), 20)
+                                   for name in ("N1", "N2", "N3", "N4")}
     print(json.dumps(result))
 
 

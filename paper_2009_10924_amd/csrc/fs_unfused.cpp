@@ -225,11 +225,14 @@ fs_status build_unfused(const fs_graph& g, Candidate* out) {
         p.vec = vec;
         grid1d(l, n_out / vec);
       } else {
-        p.vec = 1;
         uint32_t q = 0;
         for (int k = 0; k < r.rank; ++k) if (op.perm[k] == a.rank - 1) q = (uint32_t)(pad + k);
         p.tile_in_axis_out_pos = q;
-        int64_t blocks = ((int64_t)p.out_dims[q] + 31) / 32 * (((int64_t)p.out_dims[3] + 31) / 32);
+        // both tile axes multiples of a 128-bit vector: 64x64 tile with vector accesses, else 32x32 scalar
+        const uint32_t v128 = 16 / p.elem_bytes;
+        p.vec = (p.out_dims[q] % v128 == 0 && p.out_dims[3] % v128 == 0) ? (int32_t)v128 : 1;
+        const int64_t tile = p.vec > 1 ? 64 : 32;
+        int64_t blocks = ((int64_t)p.out_dims[q] + tile - 1) / tile * (((int64_t)p.out_dims[3] + tile - 1) / tile);
         for (uint32_t k = 0; k < 3; ++k) if (k != q) blocks *= p.out_dims[k];
         if (blocks >= (int64_t(1) << 31)) return fail(FS_ERR_SHAPE, "transpose: too many tiles");
         l.shape.grid[0] = (uint32_t)blocks;

@@ -243,6 +243,59 @@ __global__ void __launch_bounds__(256) k_transpose_tile(const T* __restrict__ in
   }
 }
 
+// ---- transpose, innermost axis moves: 64x64 tile, 128-bit global accesses ----------------
+// Same tiling as above with both HBM sides moved as 128-bit vectors: a thread loads
+// VEC contiguous input elements, parks them in LDS un-transposed, and after the barrier
+// gathers VEC elements down a tile column for one 128-bit store along the output's
+// innermost axis.  Tile pitch 64+1 words (64+2 halfwords) keeps both LDS phases at the
+// two-lanes-per-bank minimum of a 64-lane wave.  Needs both tile axes to be multiples
+// of VEC; other shapes use the 32x32 scalar kernel.
+template <typename T>
+__global__ void __launch_bounds__(256) k_transpose_tile64(const T* __restrict__ in, T* __restrict__ out, TransposeP p) {
+  constexpr uint32_t VEC = 16 / sizeof(T), TILE = 64, PITCH = TILE + (sizeof(T) == 4 ? 1 : 2);
+  constexpr uint32_t LANES_PER_ROW = TILE / VEC, ROWS_PER_PASS = 256 / LANES_PER_ROW;
+  __shared__ T tile[TILE][PITCH];
+  const uint32_t q = p.tile_in_axis_out_pos;
+  const uint32_t nq = p.out_dims[q], n3 = p.out_dims[3];
+  const uint32_t tq = (nq + TILE - 1) / TILE, t3 = (n3 + TILE - 1) / TILE;
+  uint32_t bid = blockIdx.x;
+  const uint32_t b3 = bid % t3; bid /= t3;
+  const uint32_t bq = bid % tq; bid /= tq;
+  uint32_t ax[2], na = 0;
+  for (uint32_t k = 0; k < 3; ++k) if (k != q) ax[na++] = k;
+  const uint32_t cb1 = bid % p.out_dims[ax[1]];
+  const uint32_t cb0 = bid / p.out_dims[ax[1]];
+  const uint32_t in_base = cb0 * p.in_stride[ax[0]] + cb1 * p.in_stride[ax[1]];
+  const uint32_t out_base = cb0 * p.out_stride[ax[0]] + cb1 * p.out_stride[ax[1]];
+  const uint32_t lr = threadIdx.x % LANES_PER_ROW, rr = threadIdx.x / LANES_PER_ROW;
+  union Pack { u32x4 v; T e[VEC]; };
+  // read: 128-bit along the input's innermost axis (output axis q)
+  Pack buf[TILE / ROWS_PER_PASS];
+#pragma unroll
+  for (uint32_t s = 0; s < TILE / ROWS_PER_PASS; ++s) {
+    const uint32_t j = rr + s * ROWS_PER_PASS;
+    const uint32_t cq = min(bq * TILE + lr * VEC, nq - VEC), c3 = min(b3 * TILE + j, n3 - 1);
+    buf[s].v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(in + in_base + cq + c3 * p.in_stride[3]));
+  }
+#pragma unroll
+  for (uint32_t s = 0; s < TILE / ROWS_PER_PASS; ++s) {
+    const uint32_t j = rr + s * ROWS_PER_PASS;
+#pragma unroll
+    for (uint32_t e = 0; e < VEC; ++e) tile[j][lr * VEC + e] = buf[s].e[e];
+  }
+  __syncthreads();
+  // write: 128-bit along the output's innermost axis
+#pragma unroll
+  for (uint32_t s = 0; s < TILE / ROWS_PER_PASS; ++s) {
+    const uint32_t i = rr + s * ROWS_PER_PASS;
+    const uint32_t cq = bq * TILE + i, c3 = b3 * TILE + lr * VEC;
+    Pack o;
+#pragma unroll
+    for (uint32_t e = 0; e < VEC; ++e) o.e[e] = tile[lr * VEC + e][i];
+    if (cq < nq && c3 < n3) __builtin_nontemporal_store(o.v, reinterpret_cast<u32x4*>(out + out_base + cq * p.out_stride[q] + c3));
+  }
+}
+
 // ---- streaming copy (the measured HBM ceiling) ------------------------------------
 __global__ void __launch_bounds__(256) k_copy(const u32x4* __restrict__ src, u32x4* __restrict__ dst, UnaryP p) {
   const uint32_t n_vec = p.n;   // 128-bit vectors
@@ -276,6 +329,8 @@ const void* unfused_kernel_symbol(int32_t kernel, const KernelArgs& a) {
            : vb == 4 ? (const void*)k_transpose_rows<uint32_t> : (const void*)k_transpose_rows<uint16_t>;
     }
     case K_TRANSPOSE_TILE:
+      if (a.u.transpose.vec > 1)
+        return a.u.transpose.elem_bytes == 4 ? (const void*)k_transpose_tile64<uint32_t> : (const void*)k_transpose_tile64<uint16_t>;
       return a.u.transpose.elem_bytes == 4 ? (const void*)k_transpose_tile<uint32_t> : (const void*)k_transpose_tile<uint16_t>;
     case K_COPY:
       return (const void*)k_copy;

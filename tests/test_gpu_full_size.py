@@ -16,6 +16,17 @@ RMS_FLOOR = {"C2": {"out"}, "C4": {"dbias"}, "N1": {"dx"}, "N2": {"dx", "dgamma"
 ALL = dict(FULL_CONFIGS, **NEXT_CONFIGS)
 
 
+@pytest.mark.parametrize("cfg", ["N3", "N4"])
+def test_full_size_transpose_bit_exact(cfg):
+    spec = ALL[cfg]()
+    inp = make_inputs(spec)                                       # element i carries the bit pattern of i
+    want = np.ascontiguousarray(np.transpose(inp["x"], spec.ops[0].attr["perm"]))
+    for scheme in ("auto", "unfused"):
+        _, raw, info, _ = run_spec(spec, inp, scheme, repeat=2)
+        assert np.array_equal(raw["t"].view(np.uint8), want.view(np.uint8)), f"{cfg} {scheme} {info['kernel']}"
+        note(f"    {cfg} {scheme} {info['kernel']}: bit-exact over {want.size} elements")
+
+
 @pytest.mark.parametrize("cfg", ["C1", "C2", "C3", "C4", "C5", "N1", "N2"])
 def test_full_size_config(cfg):
     spec = ALL[cfg]()

@@ -169,6 +169,9 @@ def test_layernorm_backward(rows, cols, dtype):
     ((4, 37, 12, 64), (0, 2, 1, 3), "f32"), ((3, 5, 7, 6), (0, 2, 1, 3), "i32"), ((2, 33, 5, 8), (2, 0, 1, 3), "bf16"),
     ((2, 9, 50, 70), (0, 1, 3, 2), "f32"), ((5, 40, 70), (2, 0, 1), "f16"), ((3, 4, 35, 33), (3, 1, 0, 2), "i32"),
     ((67, 129), (1, 0), "f32"), ((2, 3, 4, 5), (3, 2, 1, 0), "f32"), ((6, 10), (0, 1), "f32"),
+    # both tile axes multiples of a 128-bit vector: the 64x64 vectorised LDS tile, with ragged tiles
+    ((4, 40, 12, 64), (0, 2, 3, 1), "f32"), ((3, 24, 5, 16), (0, 2, 3, 1), "bf16"), ((2, 3, 72, 200), (0, 1, 3, 2), "f16"),
+    ((132, 68), (1, 0), "i32"), ((2, 136, 3, 8), (3, 2, 0, 1), "f32"), ((64, 64), (1, 0), "bf16"),
 ])
 def test_transpose_bit_exact(dims, perm, dtype):
     spec = transpose_graph(dims, perm, dtype)

@@ -256,6 +256,8 @@ def layernorm_backward_graph(rows: int, cols: int, dtype: str = "f32") -> GraphS
 NEXT_CONFIGS = {
     "N1": lambda: softmax_backward_graph(32 * 12 * 128, 128, "f16"),
     "N2": lambda: layernorm_backward_graph(8192, 768, "f32"),
+    "N3": lambda: transpose_graph((64, 512, 12, 64), (0, 2, 3, 1), "f32"),   # innermost axis moves: [B,S,H,D] -> [B,H,D,S]
+    "N4": lambda: transpose_graph((64, 512, 12, 64), (0, 2, 3, 1), "bf16"),
 }
 
 FULL_CONFIGS = {
