@@ -275,7 +275,7 @@ def main():
         from workloads import NEXT_CONFIGS
         # patterns beyond the five configurations: softmax / LayerNorm backward, innermost-axis-moving transposes
         result["next_patterns"] = {name: measure_config(name, NEXT_CONFIGS[name](), max(50, args.steps // 4), 20)
-                                   for name in ("N1", "N2", "N3", "N4")}
+                                   for name in ("N1", "N2", "N3", "N4", "N5")}
     print(json.dumps(result))
 
 

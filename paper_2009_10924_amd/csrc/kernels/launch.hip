@@ -16,7 +16,7 @@ const KernelDesc kDesc[K_COUNT] = {
     {"transpose_rows", 2}, {"transpose_tile", 2},  {"copy", 2},           {"softmax_wave", 3},
     {"softmax_block", 3},  {"layernorm_wave", 6},  {"layernorm_block", 6}, {"bias_gelu", 3},
     {"bias_gelu_dbias", 7}, {"colfold", 3},        {"tchain_wave", 3},    {"tchain_lds", 3},
-    {"row_wave", 6},       {"layernorm_bwd", 7},
+    {"row_wave", 6},       {"row_block", 6},       {"layernorm_bwd", 7},
 };
 
 const void* symbol_for(int32_t kernel, const KernelArgs& a) {
@@ -32,7 +32,7 @@ const void* symbol_for(int32_t kernel, const KernelArgs& a) {
       return gelu_kernel_symbol(kernel, a);
     case K_TCHAIN_WAVE: case K_TCHAIN_LDS:
       return tchain_kernel_symbol(kernel, a);
-    case K_ROW_WAVE:
+    case K_ROW_WAVE: case K_ROW_BLOCK:
       return rowops_kernel_symbol(kernel, a);
     default:
       return nullptr;

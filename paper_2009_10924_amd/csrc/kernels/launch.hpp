@@ -30,7 +30,8 @@ enum KernelId : int32_t {
   K_COLFOLD,           // p0 partials [n_row_tiles, fold_cols] f32, p1 out0 (columns < fold_split), p2 out1 (the rest)
   K_TCHAIN_WAVE,       // p0 x, p1 scale, p2 out
   K_TCHAIN_LDS,
-  K_ROW_WAVE,          // p0..p3 row inputs, p4 out0, p5 out1 : generic row-stitched skeleton
+  K_ROW_WAVE,          // p0,p1 row inputs, p2,p3 column vectors, p4 out0, p5 out1 : generic row-stitched skeleton
+  K_ROW_BLOCK,         // same operands as K_ROW_WAVE, one workgroup per row, reduced values through LDS
   K_LAYERNORM_BWD,     // p0 h, p1 dy, p2 gamma, p3 mu, p4 rstd, p5 dx, p6 partials [n_row_blocks, 2, cols]
   K_COUNT
 };
@@ -126,7 +127,7 @@ struct LnBwdP {
   int32_t lanes_per_row, lanes_log2, vecs_per_lane;
   int32_t waves, rows_per_group;    // workgroup = waves x 64 lanes; rows each lane group loads up front
 };
-enum RowPattern : int32_t { ROW_SOFTMAX_BWD = 0 };
+enum RowPattern : int32_t { ROW_SOFTMAX_BWD = 0, ROW_RMSNORM = 1 };
 struct RowP {
   int32_t pattern, dt;              // all row inputs and outputs share dt
   uint32_t rows, cols;

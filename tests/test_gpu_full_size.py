@@ -27,7 +27,7 @@ def test_full_size_transpose_bit_exact(cfg):
         note(f"    {cfg} {scheme} {info['kernel']}: bit-exact over {want.size} elements")
 
 
-@pytest.mark.parametrize("cfg", ["C1", "C2", "C3", "C4", "C5", "N1", "N2"])
+@pytest.mark.parametrize("cfg", ["C1", "C2", "C3", "C4", "C5", "N1", "N2", "N5"])
 def test_full_size_config(cfg):
     spec = ALL[cfg]()
     note(f"  full-size {cfg}: {spec.name}: generating inputs")

@@ -8,7 +8,7 @@ from oracle import oracle as O
 from paper_2009_10924_amd import binding as B
 from tests.gpu_util import TOL, check, note, run_spec
 from workloads import (add_bias_layernorm_graph, attention_scores_graph, bias_gelu_dbias_graph, bias_gelu_graph,
-                       layernorm_backward_graph, make_inputs, softmax_backward_graph, softmax_graph,
+                       layernorm_backward_graph, make_inputs, rmsnorm_graph, softmax_backward_graph, softmax_graph,
                        transpose_chain_graph, transpose_graph)
 from workloads.graphs import GraphSpec, OpSpec, TensorSpec
 
@@ -151,6 +151,16 @@ def test_softmax_backward(rows, cols, dtype):
     ref = O.evaluate(spec, inp)
     worst = all_candidates(spec, inp, ref, {"dx": O.rms(ref["dx"])}, repeat=2)
     note(f"softmax backward {rows}x{cols} {dtype}: {worst}")
+
+
+@pytest.mark.parametrize("rows,cols,dtype", [(67, 4096, "bf16"), (130, 768, "f32"), (9, 1024, "f16"), (11, 100, "f32"),
+                                             (5, 4, "f32"), (3, 8192, "bf16"), (33, 37, "f32")])
+def test_rmsnorm(rows, cols, dtype):
+    spec = rmsnorm_graph(rows, cols, dtype=dtype)
+    inp = make_inputs(spec, seed=0)
+    ref = O.evaluate(spec, inp)
+    worst = all_candidates(spec, inp, ref, {}, repeat=2)       # no cancellation: strict relative error
+    note(f"rmsnorm {rows}x{cols} {dtype}: {worst}")
 
 
 @pytest.mark.parametrize("rows,cols,dtype", [(67, 768, "f32"), (300, 256, "f32"), (9, 1024, "bf16"), (11, 100, "f32"),

@@ -13,7 +13,7 @@ import pytest
 
 from oracle import oracle as O
 from workloads import (add_bias_layernorm_graph, attention_scores_graph, bias_gelu_dbias_graph,
-                       layernorm_backward_graph, make_inputs, quantise, softmax_backward_graph, softmax_graph,
+                       layernorm_backward_graph, make_inputs, quantise, rmsnorm_graph, softmax_backward_graph, softmax_graph,
                        transpose_chain_graph, transpose_graph, valid_lengths)
 
 
@@ -372,6 +372,24 @@ def test_layernorm_backward_is_the_gradient_of_layernorm():
         assert out["dbeta"][0, j] == pytest.approx(math.fsum(dy[:, j]), abs=1e-14)
     # dx is orthogonal to the constant vector and to x_hat in every row (up to the eps term)
     np.testing.assert_allclose(out["dx"].sum(axis=1), 0.0, atol=1e-13)
+
+
+def test_rmsnorm_closed_forms():
+    eps = 1e-6
+    g = rmsnorm_graph(3, 4, eps=eps, dtype="f32")
+    x = np.array([[3.0, -4.0, 0.0, 0.0], [1.0, 1.0, 1.0, 1.0], [2.0, -2.0, 2.0, -2.0]])
+    gamma = np.array([1.0, 2.0, 0.5, -1.0])
+    out = _eval_f64(g, {"x": x, "gamma": gamma})["out"]
+    # row 0: mean square = 25/4; row 1: 1; row 2: 4
+    for i, ms in enumerate((6.25, 1.0, 4.0)):
+        want = [float(x[i, j]) / math.sqrt(ms + eps) * float(gamma[j]) for j in range(4)]
+        np.testing.assert_allclose(out[i], want, rtol=1e-14)
+    # with gamma = 1 the output has mean square v / (v + eps); scaling x leaves it unchanged up to eps
+    ones = np.ones(4)
+    o1 = _eval_f64(g, {"x": x, "gamma": ones})["out"]
+    np.testing.assert_allclose((o1 ** 2).mean(axis=1), np.array([6.25, 1.0, 4.0]) / (np.array([6.25, 1.0, 4.0]) + eps), rtol=1e-13)
+    o2 = _eval_f64(g, {"x": 8.0 * x, "gamma": ones})["out"]
+    np.testing.assert_allclose(o2, o1, rtol=1e-6)
 
 
 # ------------------------------------------------------------------ misc ops + metric

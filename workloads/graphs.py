@@ -220,6 +220,24 @@ def softmax_backward_graph(rows: int, cols: int, dtype: str = "f32") -> GraphSpe
     )
 
 
+def rmsnorm_graph(rows: int, cols: int, eps: float = 1e-6, dtype: str = "bf16") -> GraphSpec:
+    """RMS normalisation: x * rsqrt(mean(x^2) + eps) * gamma  (6 ops, one row reduction)."""
+    ops = [
+        _op("q", "square", "x"),
+        _op("v", "reduce_mean", "q", axis=1),
+        _op("ve", "add_scalar", "v", value=float(eps)),
+        _op("r", "rsqrt", "ve"),
+        _op("n", "mul", "x", "r"),
+        _op("out", "mul", "n", "gamma"),
+    ]
+    return GraphSpec(
+        name=f"rmsnorm_{dtype}_{rows}x{cols}",
+        inputs=[TensorSpec("x", dtype, (rows, cols)), TensorSpec("gamma", dtype, (cols,))],
+        ops=ops,
+        outputs=[("out", dtype)],
+    )
+
+
 def layernorm_backward_graph(rows: int, cols: int, dtype: str = "f32") -> GraphSpec:
     """LayerNorm backward from saved per-row mean and reciprocal standard deviation (13 ops):
     two row reductions for dx, two column reductions for dgamma and dbeta."""
@@ -258,6 +276,7 @@ NEXT_CONFIGS = {
     "N2": lambda: layernorm_backward_graph(8192, 768, "f32"),
     "N3": lambda: transpose_graph((64, 512, 12, 64), (0, 2, 3, 1), "f32"),   # innermost axis moves: [B,S,H,D] -> [B,H,D,S]
     "N4": lambda: transpose_graph((64, 512, 12, 64), (0, 2, 3, 1), "bf16"),
+    "N5": lambda: rmsnorm_graph(8192, 4096, dtype="bf16"),
 }
 
 FULL_CONFIGS = {

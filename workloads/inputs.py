@@ -17,7 +17,7 @@ import numpy as np
 
 from .graphs import GraphSpec
 
-CONFIG_INDEX = {"softmax_backward": 8, "layernorm_backward": 9, "softmax": 1, "add_bias_layernorm": 2, "attention_scores": 3,
+CONFIG_INDEX = {"rmsnorm": 10, "softmax_backward": 8, "layernorm_backward": 9, "softmax": 1, "add_bias_layernorm": 2, "attention_scores": 3,
                 "bias_gelu_dbias": 4, "transpose_chain": 5, "transpose": 6, "bias_gelu": 7}
 
 
@@ -68,6 +68,7 @@ def make_inputs(graph: GraphSpec, seed: int = 0) -> Dict[str, np.ndarray]:
       transpose_chain    x ~ U(-1,1); scale ~ U(0.5,1.5)
       transpose          element i holds the bit pattern of the integer i (index encoding)
       softmax_backward   y ~ Dirichlet(1,..,1) per row (positive, rows sum to 1); dy ~ N(0,1)
+      rmsnorm            x ~ N(0,1); gamma ~ 1+N(0,0.02)
       layernorm_backward h, dy ~ N(0,1); gamma ~ 1+N(0,0.02); mu ~ N(0,0.05); rstd ~ U(0.8,1.2)
     """
     kind = _kind(graph)
@@ -95,6 +96,8 @@ def make_inputs(graph: GraphSpec, seed: int = 0) -> Dict[str, np.ndarray]:
                 a = a.reshape(t.dims)
         elif kind in ("bias_gelu_dbias", "bias_gelu"):
             a = g.standard_normal(t.dims) if n in ("x", "grad") else 0.02 * g.standard_normal(t.dims)
+        elif kind == "rmsnorm":
+            a = g.standard_normal(t.dims) if n == "x" else 1.0 + 0.02 * g.standard_normal(t.dims)
         elif kind == "softmax_backward":
             a = g.dirichlet(np.ones(t.dims[-1]), size=t.dims[:-1]) if n == "y" else g.standard_normal(t.dims)
         elif kind == "layernorm_backward":
