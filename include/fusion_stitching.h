@@ -35,6 +35,7 @@ extern "C" {
 
 typedef struct fs_graph fs_graph;
 typedef struct fs_plan fs_plan;
+typedef struct fs_pack fs_pack;
 typedef int32_t fs_status;
 typedef int32_t fs_tensor;
 
@@ -183,6 +184,45 @@ fs_status fs_plan_candidate(const fs_plan *p, int32_t index, fs_plan_info *out);
  * Errors: FS_ERR_INVALID_ARG, FS_ERR_WORKSPACE, FS_ERR_ALIGN, FS_ERR_HIP.         */
 fs_status fs_execute(const fs_plan *p, const void *const *inputs, void *const *outputs,
                      void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* ---- packed execution (Section 4.1, kernel packing: ops with no data dependence
+ *      share one kernel to cut launches; Section 5.3, remote fusion: patterns that
+ *      are not adjacent in the graph may still be packed) -------------------------- */
+
+#define FS_PACK_MAX_MEMBERS 256  /* members of one pack; every 32 of them share one launch */
+
+typedef struct fs_pack_info {
+  int32_t n_members;
+  int32_t n_kernels;            /* launches per fs_pack_execute = ceil(n_members / 32)          */
+  int32_t grid, block;          /* workgroups over all launches, threads per workgroup          */
+  int32_t vgprs;                /* registers per lane of the packed kernel (0 without a device) */
+  int32_t n_inputs, n_outputs;  /* lengths of fs_pack_execute's pointer arrays                  */
+  int32_t reserved;
+  int64_t bytes_min;            /* sum of the members' bytes_min                                */
+  double predicted_us;          /* model estimate for one fs_pack_execute                       */
+  double predicted_separate_us; /* sum of the members' own predicted_us (one launch each)       */
+} fs_pack_info;
+
+/* Packs plans[0..n) -- independent patterns, none reading another's output -- into
+ * one object whose execution runs all of them in ceil(n/32) launches.  A member must
+ * be a plan made with a scheme other than FS_SCHEME_UNFUSED whose pattern has a
+ * row-stitched packed form: softmax without mask, softmax backward, RMS norm,
+ * LayerNorm with affine output (alone, or with residual and bias), bias + GELU; input
+ * and output storage of the same dtype (LayerNorm also float32 -> bfloat16); rows of
+ * at most 1024 128-bit vectors.  The plans may be destroyed afterwards; the pack keeps
+ * what it needs.  `plans` is a HOST array.
+ * Errors: FS_ERR_INVALID_ARG, FS_ERR_UNSUPPORTED_PATTERN (names the member),
+ * FS_ERR_LOCALITY (a member's row is too long for one workgroup), FS_ERR_SHAPE.      */
+fs_status fs_pack_create(const fs_plan *const *plans, int32_t n, fs_pack **out);
+void fs_pack_destroy(fs_pack *p);
+fs_status fs_pack_query(const fs_pack *p, fs_pack_info *out);
+/* Enqueues the packed launch(es) on `hip_stream` and returns without waiting.
+ * `inputs` holds the members' inputs one member after the other (member 0's inputs in
+ * its graph's declaration order, then member 1's, ...), `outputs` likewise; HOST arrays
+ * of DEVICE pointers, each 16-byte aligned.  Members must not alias each other's
+ * outputs.  Needs no workspace, allocates nothing, never synchronizes.
+ * Errors: FS_ERR_INVALID_ARG, FS_ERR_ALIGN, FS_ERR_HIP.                              */
+fs_status fs_pack_execute(const fs_pack *p, const void *const *inputs, void *const *outputs, void *hip_stream);
 
 /* Plain streaming copy of `bytes` (multiple of 16) from src to dst, both DEVICE
  * and 16-byte aligned: the measured HBM ceiling every result is reported beside

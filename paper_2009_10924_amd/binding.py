@@ -29,7 +29,9 @@ EXPORTS = [
     "fs_graph_create", "fs_graph_destroy", "fs_graph_input", "fs_graph_op", "fs_graph_output",
     "fs_graph_finalize", "fs_plan_create", "fs_plan_destroy", "fs_plan_query", "fs_plan_candidate",
     "fs_execute", "fs_stream_copy", "fs_last_error", "fs_version",
+    "fs_pack_create", "fs_pack_destroy", "fs_pack_query", "fs_pack_execute",
 ]
+FS_PACK_MAX_MEMBERS = 256
 
 
 class FsError(RuntimeError):
@@ -87,6 +89,17 @@ class fs_plan_info(C.Structure):
         }
 
 
+class fs_pack_info(C.Structure):
+    _fields_ = [
+        ("n_members", C.c_int32), ("n_kernels", C.c_int32), ("grid", C.c_int32), ("block", C.c_int32),
+        ("vgprs", C.c_int32), ("n_inputs", C.c_int32), ("n_outputs", C.c_int32), ("reserved", C.c_int32),
+        ("bytes_min", C.c_int64), ("predicted_us", C.c_double), ("predicted_separate_us", C.c_double),
+    ]
+
+    def as_dict(self) -> Dict:
+        return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved"}
+
+
 _LIB: Optional[C.CDLL] = None
 
 
@@ -135,6 +148,14 @@ def load() -> C.CDLL:
     lib.fs_execute.restype = i32
     lib.fs_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
     lib.fs_stream_copy.restype = i32
+    lib.fs_pack_create.argtypes = [C.POINTER(vp), i32, C.POINTER(vp)]
+    lib.fs_pack_create.restype = i32
+    lib.fs_pack_destroy.argtypes = [vp]
+    lib.fs_pack_destroy.restype = None
+    lib.fs_pack_query.argtypes = [vp, C.POINTER(fs_pack_info)]
+    lib.fs_pack_query.restype = i32
+    lib.fs_pack_execute.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp]
+    lib.fs_pack_execute.restype = i32
     lib.fs_last_error.argtypes = []
     lib.fs_last_error.restype = C.c_char_p
     lib.fs_version.argtypes = []
@@ -269,6 +290,41 @@ class Plan:
         import torch
         n = int(self.info["workspace_bytes"])
         return torch.zeros(max(n, 16), dtype=torch.uint8, device=device) if n > 0 else None
+
+
+class Pack:
+    """Several independent plans executed as one packed launch per 32 members."""
+
+    def __init__(self, plans: Sequence[Plan]):
+        self._lib = load()
+        arr = (C.c_void_p * max(1, len(plans)))(*[p.handle for p in plans])
+        h = C.c_void_p()
+        _check(self._lib.fs_pack_create(arr, len(plans), C.byref(h)))
+        self.handle = h
+        info = fs_pack_info()
+        _check(self._lib.fs_pack_query(self.handle, C.byref(info)))
+        self.info = info.as_dict()
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            self._lib.fs_pack_destroy(self.handle)
+            self.handle = None
+
+    def bind(self, inputs: Sequence[int], outputs: Sequence[int], stream: int):
+        """inputs / outputs: device addresses, member after member; returns a pre-marshalled call."""
+        ins = (C.c_void_p * max(1, len(inputs)))(*inputs)
+        outs = (C.c_void_p * max(1, len(outputs)))(*outputs)
+        st = C.c_void_p(stream)
+        fn, handle = self._lib.fs_pack_execute, self.handle
+
+        def call(_keep=(ins, outs)):
+            code = fn(handle, ins, outs, st)
+            if code < 0:
+                _check(code)
+        return call
+
+    def execute_ptrs(self, inputs: Sequence[int], outputs: Sequence[int], stream: int) -> None:
+        self.bind(inputs, outputs, stream)()
 
 
 def stream_copy(dst, src, stream: Optional[int] = None) -> None:

@@ -18,7 +18,7 @@ struct DeviceModel {
   uint32_t lds_per_cu = 160 * 1024;
   double clock_hz = 2.4e9;
   double hbm_peak_Bps = 8.0e12;
-  // measured / calibrated on the box (see the calibration notes in the design document)
+  // measured / calibrated on one MI355X
   double stream_fraction = 0.78;     // plain copy kernel, fraction of hbm_peak
   double mem_latency_s = 1.2e-6;     // loaded HBM round trip seen by a wave
   double launch_s = 2.2e-6;          // fixed cost of one kernel: dispatch, first load round trip, drain

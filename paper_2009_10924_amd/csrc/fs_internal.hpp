@@ -78,6 +78,17 @@ struct Launch {
   LaunchShape shape;
 };
 
+// Form in which a matched pattern can join a packed launch (one kernel over many
+// independent patterns): one of the row-skeleton specs plus where its operands come from.
+struct PackForm {
+  int32_t spec = -1;              // PackSpec; -1: this pattern has no packed form
+  int32_t in_dt = 0, out_dt = 0;
+  uint32_t rows = 0, cols = 0;
+  float f[4] = {0, 0, 0, 0};
+  int32_t in_slot[2] = {-1, -1};      // fs_execute input slots of the row operands
+  int32_t vec_slot[3] = {-1, -1, -1}; // fs_execute input slots of the column vectors
+};
+
 struct Candidate {
   fs_plan_info info;
   std::vector<Launch> launches;
@@ -91,6 +102,8 @@ struct fs_plan {
   int32_t chosen = 0;
   int32_t n_inputs = 0, n_outputs = 0;
   std::vector<int64_t> input_bytes, output_bytes;
+  fs::PackForm pack;
+  int64_t bytes_min = 0;
 };
 
 namespace fs {
@@ -98,7 +111,8 @@ namespace fs {
 // matcher + candidate enumeration (fs_match.cpp / fs_cost.cpp)
 fs_status build_unfused(const fs_graph& g, Candidate* out);
 // Appends every stitched candidate that fits `g`; returns the pattern name or "" if none matches.
-std::string build_stitched(const fs_graph& g, std::vector<Candidate>* out);
+// `pack` (may be null) receives the pattern's packed form when it has one.
+std::string build_stitched(const fs_graph& g, std::vector<Candidate>* out, PackForm* pack);
 int64_t graph_bytes_min(const fs_graph& g);
 void predict(Candidate* c);  // fills info.predicted_us, waves_per_simd, vgprs, lds
 

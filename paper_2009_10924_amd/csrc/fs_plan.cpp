@@ -55,8 +55,9 @@ fs_status fs_plan_create(const fs_graph* g, int32_t scheme, const fs_plan_opts* 
 
   std::vector<Candidate> all;
   std::string pattern;
+  PackForm pack_form;
   if (scheme != FS_SCHEME_UNFUSED) {
-    pattern = build_stitched(*g, &all);
+    pattern = build_stitched(*g, &all, &pack_form);
     for (Candidate& c : all) predict(&c);
   }
   if (scheme == FS_SCHEME_UNFUSED || (scheme == FS_SCHEME_AUTO && all.empty())) {
@@ -105,6 +106,8 @@ fs_status fs_plan_create(const fs_graph* g, int32_t scheme, const fs_plan_opts* 
     p->candidates[i].info.n_candidates = (int32_t)p->candidates.size();
     p->candidates[i].info.candidate = (int32_t)i;
   }
+  p->pack = pack_form;
+  p->bytes_min = graph_bytes_min(*g);
   p->n_inputs = (int32_t)g->inputs.size();
   p->n_outputs = (int32_t)g->outputs.size();
   for (int t : g->inputs) p->input_bytes.push_back(g->tensors[t].numel() * dtype_bytes(g->tensors[t].dtype));

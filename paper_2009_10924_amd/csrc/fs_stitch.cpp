@@ -78,6 +78,8 @@ BufRef ws_ref(int64_t off) {
   return r;
 }
 
+int32_t slot_of(const fs_graph& g, int32_t t) { return t >= 0 ? g.tensors[t].input_slot : -1; }
+
 Candidate make_candidate(const fs_graph& g, const char* pattern, int32_t scheme, int32_t kernel) {
   Candidate c;
   memset(&c.info, 0, sizeof c.info);
@@ -109,7 +111,7 @@ std::string subst(const std::string& text, const std::string& a) {
   return r;
 }
 
-bool build_softmax(const fs_graph& g, std::vector<Candidate>* out) {
+bool build_softmax(const fs_graph& g, std::vector<Candidate>* out, PackForm* pack) {
   if (g.outputs.size() != 1) return false;
   static const char* pre[] = {"add(scale[#0]($X),$M)", "add($X,$M)", "scale[#0]($X)", "$X"};
   MatchState st;
@@ -196,6 +198,14 @@ bool build_softmax(const fs_graph& g, std::vector<Candidate>* out) {
   };
   const bool vector_ok = p.cols % VEC == 0;
   const uint32_t nvec = vector_ok ? p.cols / VEC : 0;
+  if (vector_ok && !has_mask) {
+    pack->spec = PACK_SOFTMAX;
+    pack->in_dt = pack->out_dt = p.in_dt;
+    pack->rows = p.rows;
+    pack->cols = p.cols;
+    pack->f[0] = p.scale;
+    pack->in_slot[0] = slot_of(g, st.tensors["X"]);
+  }
 
   if (vector_ok) {
     for (int K : {1, 2, 4, 8}) {
@@ -309,7 +319,7 @@ bool build_softmax(const fs_graph& g, std::vector<Candidate>* out) {
 }
 
 // ------------------------------------------------------------------ layernorm family
-bool build_layernorm(const fs_graph& g, std::vector<Candidate>* out) {
+bool build_layernorm(const fs_graph& g, std::vector<Candidate>* out, PackForm* pack) {
   if (g.outputs.size() != 1) return false;
   static const char* hs[] = {"add(add($X,$R),$B)", "add($X,$R)", "$X"};
   const std::string c_txt = "sub(@,rmean[-1](@))";
@@ -373,6 +383,25 @@ bool build_layernorm(const fs_graph& g, std::vector<Candidate>* out) {
   const int in_b = dtype_bytes(p.in_dt), out_b = dtype_bytes(p.out_dt);
   const double n = (double)p.rows * p.cols;
   const int n_vec_inputs = (p.has_bias ? 1 : 0) + (affine ? 2 : 0);
+  if (affine && p.has_res == p.has_bias && (p.out_dt == p.in_dt || p.out_dt == FS_BF16)) {
+    pack->spec = p.has_res ? PACK_LN_FULL : PACK_LN_PLAIN;
+    pack->in_dt = p.in_dt;
+    pack->out_dt = p.out_dt;
+    pack->rows = p.rows;
+    pack->cols = p.cols;
+    pack->f[0] = p.eps;
+    pack->f[1] = p.inv_cols;
+    pack->in_slot[0] = slot_of(g, tx);
+    if (p.has_res) {
+      pack->in_slot[1] = slot_of(g, tr);
+      pack->vec_slot[0] = slot_of(g, tb);
+      pack->vec_slot[1] = slot_of(g, tg);
+      pack->vec_slot[2] = slot_of(g, tbt);
+    } else {
+      pack->vec_slot[0] = slot_of(g, tg);
+      pack->vec_slot[1] = slot_of(g, tbt);
+    }
+  }
   auto base_cost = [&](KernelCost* kc) {
     kc->hbm_bytes = n * in_b * (1 + p.has_res) + n * out_b + (double)n_vec_inputs * p.cols * in_b;
     kc->elems = n;
@@ -480,7 +509,7 @@ void make_fold_launch(Launch* f, uint32_t n_rows, uint32_t width, uint32_t split
 }
 
 // ------------------------------------------------------------------ bias-GELU family
-bool build_gelu(const fs_graph& g, std::vector<Candidate>* out) {
+bool build_gelu(const fs_graph& g, std::vector<Candidate>* out, PackForm* pack) {
   MatchState st;
   bool with_dbias = false;
   if (g.outputs.size() == 2) {
@@ -522,6 +551,12 @@ bool build_gelu(const fs_graph& g, std::vector<Candidate>* out) {
   const double n = (double)p.rows * p.cols;
 
   if (!with_dbias) {
+    pack->spec = PACK_BIAS_GELU;
+    pack->in_dt = pack->out_dt = p.dt;
+    pack->rows = p.rows;
+    pack->cols = p.cols;
+    pack->in_slot[0] = slot_of(g, tx);
+    pack->vec_slot[0] = slot_of(g, tb);
     Candidate c = make_candidate(g, "bias_gelu", FS_SCHEME_LOCAL, K_BIAS_GELU);
     Launch& l = c.launches.front();
     l.args.u.gelu = p;
@@ -629,7 +664,7 @@ bool build_gelu(const fs_graph& g, std::vector<Candidate>* out) {
 }
 
 // ------------------------------------------------------------------ transpose chain family
-bool build_tchain(const fs_graph& g, std::vector<Candidate>* out) {
+bool build_tchain(const fs_graph& g, std::vector<Candidate>* out, PackForm* pack) {
   if (g.outputs.size() != 1) return false;
   const std::string u = "mul(tr[0213]($X),$S)";
   Pattern pat("mul(" + u + ",rsqrt(addc[#0](rsum[-1](square(" + u + ")))))");
@@ -731,7 +766,7 @@ struct RowMatch {
   double valu_per_elem;
 };
 
-void emit_row_candidates(const fs_graph& g, const RowMatch& m, std::vector<Candidate>* out) {
+void emit_row_candidates(const fs_graph& g, const RowMatch& m, std::vector<Candidate>* out, PackForm* pack) {
   const Tensor& x = g.tensors[m.row_in[0]];
   const Tensor& y = g.tensors[g.outputs[0]];
   int n_in = 0, n_vec = 0;
@@ -758,6 +793,15 @@ void emit_row_candidates(const fs_graph& g, const RowMatch& m, std::vector<Candi
   if (p.cols % VEC != 0) return;
   const uint32_t nvec = p.cols / VEC;
   const int esz = dtype_bytes(p.dt);
+  pack->spec = m.pattern == ROW_SOFTMAX_BWD ? PACK_SOFTMAX_BWD : PACK_RMSNORM;
+  pack->in_dt = pack->out_dt = p.dt;
+  pack->rows = p.rows;
+  pack->cols = p.cols;
+  for (int i = 0; i < 4; ++i) pack->f[i] = m.f[i];
+  for (int i = 0; i < 2; ++i) {
+    pack->in_slot[i] = slot_of(g, m.row_in[i]);
+    pack->vec_slot[i] = slot_of(g, m.vec_in[i]);
+  }
   for (int K : {1, 2, 4, 8}) {
     const uint32_t L = pow2_at_least((nvec + K - 1) / K);
     if (L > 64) continue;
@@ -846,19 +890,19 @@ void emit_row_candidates(const fs_graph& g, const RowMatch& m, std::vector<Candi
 }
 
 // dx = y * (dy - rowsum(y * dy))
-bool build_softmax_backward(const fs_graph& g, std::vector<Candidate>* out) {
+bool build_softmax_backward(const fs_graph& g, std::vector<Candidate>* out, PackForm* pack) {
   if (g.outputs.size() != 1) return false;
   Pattern pat("mul($Y,sub($DY,rsum[-1](mul($Y,$DY))))");
   MatchState st;
   if (!pat.match(g, g.outputs[0], &st) || !covers_all(g, st)) return false;
   const int32_t ty = st.tensors["Y"], tdy = st.tensors["DY"];
   if (!is_input(g, ty) || !is_input(g, tdy)) return false;
-  emit_row_candidates(g, RowMatch{"softmax_backward", ROW_SOFTMAX_BWD, {ty, tdy}, {-1, -1}, {0, 0, 0, 0}, 4.0}, out);
+  emit_row_candidates(g, RowMatch{"softmax_backward", ROW_SOFTMAX_BWD, {ty, tdy}, {-1, -1}, {0, 0, 0, 0}, 4.0}, out, pack);
   return true;
 }
 
 // out = x * rsqrt(mean(x^2) + eps) * gamma
-bool build_rmsnorm(const fs_graph& g, std::vector<Candidate>* out) {
+bool build_rmsnorm(const fs_graph& g, std::vector<Candidate>* out, PackForm* pack) {
   if (g.outputs.size() != 1) return false;
   Pattern pat("mul(mul($X,rsqrt(addc[#0](rmean[-1](square($X))))),$G)");
   MatchState st;
@@ -867,12 +911,12 @@ bool build_rmsnorm(const fs_graph& g, std::vector<Candidate>* out) {
   if (!is_input(g, tx) || !is_input(g, tg)) return false;
   const Tensor& x = g.tensors[tx];
   const float inv_cols = (float)(1.0 / (double)x.dims[x.rank - 1]);
-  emit_row_candidates(g, RowMatch{"rmsnorm", ROW_RMSNORM, {tx, -1}, {tg, -1}, {(float)st.scalars[0], inv_cols, 0, 0}, 5.0}, out);
+  emit_row_candidates(g, RowMatch{"rmsnorm", ROW_RMSNORM, {tx, -1}, {tg, -1}, {(float)st.scalars[0], inv_cols, 0, 0}, 5.0}, out, pack);
   return true;
 }
 
 // ------------------------------------------------------------------ layernorm backward
-bool build_layernorm_backward(const fs_graph& g, std::vector<Candidate>* out) {
+bool build_layernorm_backward(const fs_graph& g, std::vector<Candidate>* out, PackForm* pack) {
   if (g.outputs.size() != 3) return false;
   const std::string xh = "mul(sub($H,$MU),$RS)", gg = "mul($DY,$G)";
   Pattern p_dx("mul(sub(sub(" + gg + ",rmean[-1](" + gg + ")),mul(" + xh + ",rmean[-1](mul(" + gg + "," + xh + ")))),$RS)");
@@ -992,7 +1036,7 @@ bool build_layernorm_backward(const fs_graph& g, std::vector<Candidate>* out) {
 }
 
 // ------------------------------------------------------------------ lone transpose
-bool build_transpose(const fs_graph& g, std::vector<Candidate>* out) {
+bool build_transpose(const fs_graph& g, std::vector<Candidate>* out, PackForm* pack) {
   if (g.ops.size() != 1 || g.ops[0].opcode != FS_TRANSPOSE || g.outputs.size() != 1) return false;
   Candidate u;
   if (build_unfused(g, &u) != FS_OK) return true;
@@ -1019,8 +1063,10 @@ bool build_transpose(const fs_graph& g, std::vector<Candidate>* out) {
 
 }  // namespace
 
-std::string build_stitched(const fs_graph& g, std::vector<Candidate>* out) {
-  struct Family { const char* name; bool (*build)(const fs_graph&, std::vector<Candidate>*); };
+std::string build_stitched(const fs_graph& g, std::vector<Candidate>* out, PackForm* pack) {
+  PackForm scratch_form;
+  if (!pack) pack = &scratch_form;
+  struct Family { const char* name; bool (*build)(const fs_graph&, std::vector<Candidate>*, PackForm*); };
   static const Family families[] = {
       {"softmax", build_softmax}, {"layernorm", build_layernorm}, {"bias_gelu", build_gelu},
       {"transpose_chain", build_tchain}, {"softmax_backward", build_softmax_backward}, {"rmsnorm", build_rmsnorm},
@@ -1028,9 +1074,11 @@ std::string build_stitched(const fs_graph& g, std::vector<Candidate>* out) {
   };
   for (const Family& f : families) {
     out->clear();
-    if (f.build(g, out)) return f.name;
+    *pack = PackForm();
+    if (f.build(g, out, pack)) return f.name;
   }
   out->clear();
+  *pack = PackForm();
   return "";
 }
 

@@ -135,6 +135,32 @@ struct RowP {
   int32_t lanes_per_row, lanes_log2, vecs_per_lane, fast;
 };
 
+// ---- packed launch: many independent row patterns in one kernel -----------------------
+enum PackSpec : int32_t {
+  PACK_SOFTMAX = 0,      // in0 x;                                  f[0] = scale
+  PACK_SOFTMAX_BWD = 1,  // in0 y, in1 dy
+  PACK_RMSNORM = 2,      // in0 x, vec0 gamma;                      f[0] = eps, f[1] = 1/cols
+  PACK_LN_FULL = 3,      // in0 x, in1 res, vec0 bias, vec1 gamma, vec2 beta; f as above
+  PACK_LN_PLAIN = 4,     // in0 x, vec0 gamma, vec1 beta;           f as above
+  PACK_BIAS_GELU = 5,    // in0 x, vec0 bias
+  PACK_SPEC_COUNT = 6
+};
+// dtype pairs (storage of inputs -> storage of the output) the packed kernel is compiled for
+enum PackTypes : int32_t { PT_F32 = 0, PT_F16 = 1, PT_BF16 = 2, PT_F32_BF16 = 3, PT_COUNT = 4 };
+constexpr int kPackMaxMembers = 32;   // one launch; the table travels in the kernel arguments
+struct PackEntry {
+  const void* in[2];
+  const void* vec[3];
+  void* out;
+  RowP p;                // lanes_per_row > 64: one workgroup per row; p.pattern holds the PackSpec
+  int32_t variant;       // (spec * PT_COUNT + types) * 3 + log2(vecs_per_lane)
+  uint32_t first_block;  // first workgroup of the launch that serves this member
+};
+struct PackTable {
+  int32_t n;
+  uint32_t total_blocks;
+  PackEntry e[kPackMaxMembers];
+};
 struct KernelArgs {
   void* p[kMaxPtrs] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
   union {
@@ -162,6 +188,9 @@ struct KernelResources {
 int launch_kernel(int32_t kernel, const KernelArgs& args, const LaunchShape& shape, void* stream);
 // Register / LDS figures of the variant `launch_kernel` would pick for these args.
 KernelResources kernel_resources(int32_t kernel, const KernelArgs& args);
+// Packed launch (kernels/pack.hip): one kernel over table.total_blocks workgroups.
+int launch_pack(const PackTable& table, void* stream);
+KernelResources pack_kernel_resources();
 const char* kernel_name(int32_t kernel);
 const char* hip_error_text(int err);
 

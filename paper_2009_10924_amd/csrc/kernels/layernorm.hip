@@ -12,30 +12,13 @@
 
 #include "device_utils.hpp"
 #include "kernel_table.hpp"
+#include "row_skeleton.hpp"
 
 namespace fsk {
 using namespace fs;
 
 // TI: dtype of x / res / bias / gamma / beta.  TO: dtype of out.  Both move VEC(TI)
 // elements per lane per step, so the lane->column mapping is the same on both sides.
-template <typename TO, int N> struct StoreN;
-template <typename TO> struct StoreN<TO, 4> {
-  __device__ __forceinline__ static void run(TO* p, const float (&v)[4]) { store_vec4_nt(p, v); }
-};
-template <> struct StoreN<float, 8> {
-  __device__ __forceinline__ static void run(float* p, const float (&v)[8]) {
-    float a[4] = {v[0], v[1], v[2], v[3]}, b[4] = {v[4], v[5], v[6], v[7]};
-    store_vec_nt(p, a);
-    store_vec_nt(p + 4, b);
-  }
-};
-template <> struct StoreN<f16_t, 8> {
-  __device__ __forceinline__ static void run(f16_t* p, const float (&v)[8]) { store_vec_nt(p, v); }
-};
-template <> struct StoreN<bf16_t, 8> {
-  __device__ __forceinline__ static void run(bf16_t* p, const float (&v)[8]) { store_vec_nt(p, v); }
-};
-
 // FAST: residual, bias and affine all present, the row fills the lanes exactly and the
 // row count fills the workgroups exactly, so every flag test, clamp and padding mask
 // folds away at compile time (the shape of the benchmarked configuration).

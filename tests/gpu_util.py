@@ -54,3 +54,31 @@ def check(got, ref, dtype, floor=0.0, what=""):
     assert np.isfinite(got).all(), f"{what}: non-finite values in the GPU result"
     assert err <= TOL[dtype], f"{what}: max rel err {err:.3e} > {TOL[dtype]:.0e}"
     return err
+
+
+def run_pack(specs, inputs_list, repeat=1):
+    """Plans every spec (scheme AUTO), packs the plans, executes the pack; returns ([{name: f64 array}], pack info)."""
+    import torch
+    plans = [B.Plan(B.Graph.from_spec(s), "auto") for s in specs]
+    pack = B.Pack(plans)
+    dev_in, dev_out = [], []
+    for spec, inp in zip(specs, inputs_list):
+        dev_in.append([B.to_device(inp[t.name], t.dtype) for t in spec.inputs])
+        outs = B.alloc_outputs(spec)
+        for t in outs:
+            t.fill_(float("nan"))
+        dev_out.append(outs)
+    stream = torch.cuda.current_stream().cuda_stream
+    call = pack.bind([t.data_ptr() for m in dev_in for t in m], [t.data_ptr() for m in dev_out for t in m], stream)
+    results = []
+    for _ in range(repeat):
+        call()
+        torch.cuda.synchronize()
+        results.append([{name: B.to_host(t, dt).copy() for (name, dt), t in zip(spec.outputs, outs)}
+                        for spec, outs in zip(specs, dev_out)])
+    for r in results[1:]:
+        for a, b in zip(r, results[0]):
+            for name in a:
+                assert np.array_equal(a[name].view(np.uint8), b[name].view(np.uint8)), f"{name}: not run-to-run identical"
+    out = [{name: O.to_f64(res[name], dt) for name, dt in spec.outputs} for spec, res in zip(specs, results[0])]
+    return out, pack.info

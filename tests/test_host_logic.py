@@ -43,15 +43,17 @@ def test_header_is_plain_c_and_struct_layout_matches(tmp_path):
     src = tmp_path / "layout.c"
     src.write_text(
         '#include <stdio.h>\n#include <stddef.h>\n#include "fusion_stitching.h"\n'
-        'int main(void){printf("%zu %zu %zu %zu %zu %zu\\n", sizeof(fs_plan_info), offsetof(fs_plan_info, workspace_bytes),'
-        ' offsetof(fs_plan_info, predicted_us), offsetof(fs_plan_info, kernel), sizeof(fs_plan_opts), sizeof(fs_attr_dims));return 0;}\n')
+        'int main(void){printf("%zu %zu %zu %zu %zu %zu %zu %zu %zu\\n", sizeof(fs_plan_info), offsetof(fs_plan_info, workspace_bytes),'
+        ' offsetof(fs_plan_info, predicted_us), offsetof(fs_plan_info, kernel), sizeof(fs_plan_opts), sizeof(fs_attr_dims),'
+        ' sizeof(fs_pack_info), offsetof(fs_pack_info, bytes_min), offsetof(fs_pack_info, predicted_separate_us));return 0;}\n')
     exe = tmp_path / "layout"
     import subprocess
     subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
     got = [int(v) for v in subprocess.run([str(exe)], capture_output=True, text=True, check=True).stdout.split()]
     I = B.fs_plan_info
     assert got == [ctypes.sizeof(I), I.workspace_bytes.offset, I.predicted_us.offset, I.kernel.offset,
-                   ctypes.sizeof(B.fs_plan_opts), ctypes.sizeof(B.fs_attr_dims)]
+                   ctypes.sizeof(B.fs_plan_opts), ctypes.sizeof(B.fs_attr_dims),
+                   ctypes.sizeof(B.fs_pack_info), B.fs_pack_info.bytes_min.offset, B.fs_pack_info.predicted_separate_us.offset]
 
 
 @pytest.mark.parametrize("cfg", ["C1", "C2", "C3", "C4", "C5"])
@@ -195,3 +197,36 @@ def test_unfused_plan_shapes():
     assert info["pattern"] == "transpose_chain" and info["lds_bytes"] > 0
     info = B.Plan(B.Graph.from_spec(bias_gelu_dbias_graph(100, 520)), "global").info
     assert info["workspace_bytes"] > 0 and info["scheme"] == "global"
+
+
+def test_pack_creation_and_errors(lib):
+    from workloads.graphs import add_bias_layernorm_graph, rmsnorm_graph, softmax_backward_graph
+    specs = [softmax_graph(64, 128, "f32"), add_bias_layernorm_graph(100, 768), rmsnorm_graph(50, 4096),
+             softmax_backward_graph(77, 256, "f16"), bias_gelu_graph(33, 3072)]
+    plans = [B.Plan(B.Graph.from_spec(s), "auto") for s in specs]
+    info = B.Pack(plans).info
+    # 8 rows / workgroup, 4 rows / workgroup, then one workgroup per row (rows longer than 64 lanes x 4 vectors), 8 rows, per row
+    assert info["grid"] == 8 + 25 + 50 + 10 + 33 and info["block"] == 256
+    assert info["n_members"] == 5 and info["n_kernels"] == 1
+    assert info["n_inputs"] == 1 + 5 + 2 + 2 + 2 and info["n_outputs"] == 5
+    assert info["bytes_min"] == sum(p.info["bytes_min"] for p in plans)
+    assert info["predicted_us"] < info["predicted_separate_us"]
+    # 33 members need two launches
+    assert B.Pack([plans[0]] * 33).info["n_kernels"] == 2
+    with pytest.raises(B.FsError) as e:       # masked softmax has no packed form
+        B.Pack([plans[0], B.Plan(B.Graph.from_spec(attention_scores_graph(2, 2, 16, 16)), "auto")])
+    assert e.value.code == -5 and "plan 1" in e.value.text
+    with pytest.raises(B.FsError) as e:       # per-op plans carry no pattern
+        B.Pack([B.Plan(B.Graph.from_spec(softmax_graph(8, 64)), "unfused")])
+    assert e.value.code == -5
+    with pytest.raises(B.FsError) as e:       # row too long for one workgroup
+        B.Pack([B.Plan(B.Graph.from_spec(softmax_graph(4, 16384, "f32")), "auto")])
+    assert e.value.code == -6
+    with pytest.raises(B.FsError) as e:
+        B.Pack([])
+    assert e.value.code == -1
+    with pytest.raises(B.FsError):
+        B.Pack([plans[0]] * (B.FS_PACK_MAX_MEMBERS + 1))
+    assert lib.fs_pack_query(None, None) == -1
+    assert lib.fs_pack_execute(None, None, None, None) == -1
+    lib.fs_pack_destroy(None)
