@@ -185,6 +185,60 @@ def measure_config(name, spec, steps, warmup, with_unfused=True):
     return out
 
 
+def measure_pack(name, steps, warmup):
+    """Packed launch of many tiny independent subgraphs against one stitched launch each and against the
+    per-op plans; every member keeps its own seeded inputs and outputs (all of it cache-resident: the
+    regime is launch-bound, not bandwidth-bound)."""
+    import torch
+    from paper_2009_10924_amd import binding as B
+    from workloads import PACK_CONFIGS, make_inputs
+    specs = PACK_CONFIGS[name]()
+    stream = torch.cuda.current_stream().cuda_stream
+    plans = [B.Plan(B.Graph.from_spec(s), "auto") for s in specs]
+    unfused = [B.Plan(B.Graph.from_spec(s), "unfused") for s in specs]
+    pack = B.Pack(plans)
+    dev_in = [[B.to_device(make_inputs(s, seed=i)[t.name], t.dtype) for t in s.inputs] for i, s in enumerate(specs)]
+    dev_out = [B.alloc_outputs(s) for s in specs]
+    packed = pack.bind([t.data_ptr() for m in dev_in for t in m], [t.data_ptr() for m in dev_out for t in m], stream)
+    ws = [p.make_workspace() for p in unfused]
+    sep_calls = [p.bind([t.data_ptr() for t in i], [t.data_ptr() for t in o], 0, 0, stream) for p, i, o in zip(plans, dev_in, dev_out)]
+    unf_calls = [p.bind([t.data_ptr() for t in i], [t.data_ptr() for t in o], w.data_ptr() if w is not None else 0,
+                        w.numel() if w is not None else 0, stream) for p, i, o, w in zip(unfused, dev_in, dev_out, ws)]
+
+    def timed(fn, n):
+        for _ in range(warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(n):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / n
+
+    def all_separate():
+        for c in sep_calls:
+            c()
+
+    def all_unfused():
+        for c in unf_calls:
+            c()
+
+    t_pack = timed(packed, steps)
+    t_sep = timed(all_separate, max(10, steps // 8))
+    t_unf = timed(all_unfused, max(5, steps // 32))
+    return {"workload": f"{name}: {len(specs)} independent tiny subgraphs (8 softmax f32 [64,128], 8 add+bias+LayerNorm f32->bf16 "
+                        "[128,768], 8 softmax backward f16 [384,128], 4 RMSNorm bf16 [64,1024], 4 bias+GELU bf16 [64,3072])",
+            "members": len(specs), "bytes_min": pack.info["bytes_min"],
+            "packed_us": t_pack, "packed_launches": pack.info["n_kernels"], "packed_grid": pack.info["grid"], "packed_vgprs": pack.info["vgprs"],
+            "packed_GBps": pack.info["bytes_min"] / t_pack / 1e3,
+            "stitched_one_launch_each_us": t_sep, "stitched_launches": sum(p.info["n_kernels"] for p in plans),
+            "unfused_us": t_unf, "unfused_launches": sum(p.info["n_kernels"] for p in unfused),
+            "speedup_vs_one_launch_each": t_sep / t_pack, "speedup_vs_unfused": t_unf / t_pack,
+            "predicted_us": pack.info["predicted_us"], "predicted_separate_us": pack.info["predicted_separate_us"]}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -194,7 +248,7 @@ def main():
     ap.add_argument("--oracle-seconds", type=float, default=10.0)
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (rows shard with no exchange; see the design document); use --gpus 1")
+        sys.exit("bench.py: this build runs on one GPU only (rows would shard across GPUs with no exchange); use --gpus 1")
 
     import torch
     if not torch.cuda.is_available():
@@ -276,6 +330,8 @@ def main():
         # patterns beyond the five configurations: softmax / LayerNorm backward, innermost-axis-moving transposes
         result["next_patterns"] = {name: measure_config(name, NEXT_CONFIGS[name](), max(50, args.steps // 4), 20)
                                    for name in ("N1", "N2", "N3", "N4", "N5")}
+        torch.cuda.empty_cache()
+        result["packing"] = measure_pack("P1", max(200, args.steps // 2), 20)
     print(json.dumps(result))
 
 

@@ -84,7 +84,12 @@ fs_status fs_pack_create(const fs_plan* const* plans, int32_t n, fs_pack** out) 
   if (!pk) return fail(FS_ERR_INVALID_ARG, "fs_pack_create: out of host memory");
   double separate_us = 0, body_s = 0;
   int64_t bytes = 0;
-  PackTable cur{};
+  auto empty_table = [] {
+    PackTable t{};
+    for (uint32_t& fb : t.first_block) fb = 0xFFFFFFFFu;
+    return t;
+  };
+  PackTable cur = empty_table();
   uint64_t total_blocks = 0;
   const DeviceModel& d = device();
   for (int i = 0; i < n; ++i) {
@@ -104,10 +109,10 @@ fs_status fs_pack_create(const fs_plan* const* plans, int32_t n, fs_pack** out) 
     if (cur.n == kPackMaxMembers) {
       cur.total_blocks = (uint32_t)total_blocks;
       pk->tables.push_back(cur);
-      cur = PackTable{};
+      cur = empty_table();
       total_blocks = 0;
     }
-    e.first_block = (uint32_t)total_blocks;
+    cur.first_block[cur.n] = (uint32_t)total_blocks;
     total_blocks += blocks;
     if (total_blocks >= (1ull << 31)) { delete pk; return fail(FS_ERR_SHAPE, "fs_pack_create: too many workgroups"); }
     cur.e[cur.n++] = e;

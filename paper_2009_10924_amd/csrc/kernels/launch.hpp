@@ -154,9 +154,12 @@ struct PackEntry {
   void* out;
   RowP p;                // lanes_per_row > 64: one workgroup per row; p.pattern holds the PackSpec
   int32_t variant;       // (spec * PT_COUNT + types) * 3 + log2(vecs_per_lane)
-  uint32_t first_block;  // first workgroup of the launch that serves this member
+  int32_t reserved;
 };
 struct PackTable {
+  // first workgroup of the launch that serves member j, ascending; unused slots hold 0xFFFFFFFF.
+  // Kept together at the front so a workgroup finds its member from two wide scalar loads.
+  uint32_t first_block[kPackMaxMembers];
   int32_t n;
   uint32_t total_blocks;
   PackEntry e[kPackMaxMembers];

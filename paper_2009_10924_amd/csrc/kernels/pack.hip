@@ -57,13 +57,13 @@ __global__ void __launch_bounds__(256) k_pack(const PackTable table_in_kernarg) 
   __shared__ float slots[16];
   ConstTable tab = (ConstTable)__builtin_amdgcn_kernarg_segment_ptr();
   const uint32_t b = blockIdx.x;
-  const int n = tab->n;
-  int i = 0;
-  for (int j = 1; j < n; ++j) i = b >= tab->e[j].first_block ? j : i;   // first_block ascends
+  int i = -1;
+#pragma unroll
+  for (int j = 0; j < kPackMaxMembers; ++j) i += b >= tab->first_block[j] ? 1 : 0;   // first_block[0] = 0
   i = __builtin_amdgcn_readfirstlane(i);
   PackEntry e;
   __builtin_memcpy(&e, &tab->e[i], sizeof(PackEntry));
-  const uint32_t vblock = b - e.first_block;
+  const uint32_t vblock = b - tab->first_block[i];
   const int k_log2 = e.variant % 3, types = (e.variant / 3) % PT_COUNT, spec = e.variant / (3 * PT_COUNT);
   switch (spec) {
     case PACK_SOFTMAX: run_member_t<SoftmaxSpec, false>(e, slots, vblock, types, k_log2); break;

@@ -279,6 +279,20 @@ NEXT_CONFIGS = {
     "N5": lambda: rmsnorm_graph(8192, 4096, dtype="bf16"),
 }
 
+def pack_members_p1() -> List[GraphSpec]:
+    """P1: 32 independent tiny subgraphs (each a few microseconds or less on its own, so launch-bound when run
+    one kernel each): the many-small-kernels regime that kernel packing addresses."""
+    members: List[GraphSpec] = []
+    members += [softmax_graph(64, 128, "f32") for _ in range(8)]                # the C1 shape
+    members += [add_bias_layernorm_graph(128, 768) for _ in range(8)]
+    members += [softmax_backward_graph(384, 128, "f16") for _ in range(8)]
+    members += [rmsnorm_graph(64, 1024, dtype="bf16") for _ in range(4)]
+    members += [bias_gelu_graph(64, 3072, "bf16") for _ in range(4)]
+    return members
+
+
+PACK_CONFIGS = {"P1": pack_members_p1}
+
 FULL_CONFIGS = {
     "C1": lambda: softmax_graph(64, 128, "f32"),
     "C2": lambda: add_bias_layernorm_graph(8192, 768),
