@@ -169,6 +169,16 @@ fs_status fs_plan_query(const fs_plan *p, fs_plan_info *out);
  * list the plan was chosen from, in enumeration order.                           */
 fs_status fs_plan_candidate(const fs_plan *p, int32_t index, fs_plan_info *out);
 
+/* Writes a text listing of what the plan will run into `text` (HOST buffer of `capacity`
+ * bytes, always NUL-terminated when capacity > 0; truncated if too small) and returns
+ * the size needed for the whole listing including the NUL, or a negative error.  One
+ * line per launch (kernel, grid, block, dynamic LDS) and per buffer binding; for a
+ * pattern that runs as an interpreted row program (the generic path for patterns no
+ * hand-written kernel covers, Section 4.2) also its register files and one line per
+ * instruction: `instr <n> <op> a=<kind>:<index> b=<kind>:<index> dst=<index>
+ * flags=<v|s><k|-> aux=<dtype> imm=<value>`.  Errors: FS_ERR_INVALID_ARG.              */
+int64_t fs_plan_describe(const fs_plan *p, char *text, size_t capacity);
+
 /* ---- execution (the run-time hot path) --------------------------------------- */
 
 /* Enqueues the plan's kernel(s) on `hip_stream` (a hipStream_t; null = the

@@ -27,7 +27,7 @@ ERROR_NAME = {0: "FS_OK", -1: "FS_ERR_INVALID_ARG", -2: "FS_ERR_SHAPE", -3: "FS_
 
 EXPORTS = [
     "fs_graph_create", "fs_graph_destroy", "fs_graph_input", "fs_graph_op", "fs_graph_output",
-    "fs_graph_finalize", "fs_plan_create", "fs_plan_destroy", "fs_plan_query", "fs_plan_candidate",
+    "fs_graph_finalize", "fs_plan_create", "fs_plan_destroy", "fs_plan_query", "fs_plan_candidate", "fs_plan_describe",
     "fs_execute", "fs_stream_copy", "fs_last_error", "fs_version",
     "fs_pack_create", "fs_pack_destroy", "fs_pack_query", "fs_pack_execute",
 ]
@@ -144,6 +144,8 @@ def load() -> C.CDLL:
     lib.fs_plan_query.restype = i32
     lib.fs_plan_candidate.argtypes = [vp, i32, C.POINTER(fs_plan_info)]
     lib.fs_plan_candidate.restype = i32
+    lib.fs_plan_describe.argtypes = [vp, C.c_char_p, C.c_size_t]
+    lib.fs_plan_describe.restype = C.c_int64
     lib.fs_execute.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp, C.c_size_t, vp]
     lib.fs_execute.restype = i32
     lib.fs_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
@@ -249,6 +251,14 @@ class Plan:
         info = fs_plan_info()
         _check(self._lib.fs_plan_query(self.handle, C.byref(info)))
         return info.as_dict()
+
+    def describe(self) -> str:
+        need = self._lib.fs_plan_describe(self.handle, None, 0)
+        if need < 0:
+            _check(int(need))
+        buf = C.create_string_buffer(int(need))
+        self._lib.fs_plan_describe(self.handle, buf, int(need))
+        return buf.value.decode()
 
     def candidates(self) -> List[Dict]:
         out = []

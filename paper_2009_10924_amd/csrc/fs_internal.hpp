@@ -113,6 +113,9 @@ fs_status build_unfused(const fs_graph& g, Candidate* out);
 // Appends every stitched candidate that fits `g`; returns the pattern name or "" if none matches.
 // `pack` (may be null) receives the pattern's packed form when it has one.
 std::string build_stitched(const fs_graph& g, std::vector<Candidate>* out, PackForm* pack);
+// Candidates that run `g` as an interpreted row program (fs_rowprog.cpp); false if `g` is not a
+// pattern of element-wise ops and last-axis reductions over one row space.
+bool build_row_program(const fs_graph& g, std::vector<Candidate>* out);
 int64_t graph_bytes_min(const fs_graph& g);
 void predict(Candidate* c);  // fills info.predicted_us, waves_per_simd, vgprs, lds
 

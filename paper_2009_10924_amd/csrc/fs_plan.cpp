@@ -3,6 +3,7 @@
 // control crosses from host to device.
 #include <algorithm>
 #include <cstring>
+#include <string>
 
 #include "fs_internal.hpp"
 
@@ -132,6 +133,62 @@ fs_status fs_plan_candidate(const fs_plan* p, int32_t index, fs_plan_info* out) 
     return fail(FS_ERR_INVALID_ARG, "fs_plan_candidate: index %d outside 0..%zu", index, p->candidates.size() - 1);
   *out = p->candidates[index].info;
   return FS_OK;
+}
+
+int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) {
+  clear_error();
+  if (!p || (!text && capacity > 0)) return fail(FS_ERR_INVALID_ARG, "fs_plan_describe: null argument");
+  const Candidate& c = p->candidates[p->chosen];
+  std::string s;
+  char line[256];
+  auto buf_name = [&](const BufRef& r) {
+    char b[48];
+    if (r.kind == BUF_INPUT) snprintf(b, sizeof b, "in%d", r.slot);
+    else if (r.kind == BUF_OUTPUT) snprintf(b, sizeof b, "out%d", r.slot);
+    else if (r.kind == BUF_WORKSPACE) snprintf(b, sizeof b, "ws+%lld", (long long)r.offset);
+    else snprintf(b, sizeof b, "-");
+    return std::string(b);
+  };
+  snprintf(line, sizeof line, "plan pattern=%s scheme=%s launches=%zu\n", c.info.pattern, scheme_name(c.info.scheme), c.launches.size());
+  s += line;
+  for (const Launch& l : c.launches) {
+    snprintf(line, sizeof line, "launch %s grid=%u block=%u lds=%u\n", kernel_name(l.kernel), l.shape.grid[0] * l.shape.grid[1] * l.shape.grid[2],
+             l.shape.block[0] * l.shape.block[1] * l.shape.block[2], l.shape.lds_bytes);
+    s += line;
+    if (l.kernel != K_ROW_PROGRAM) {
+      for (int k = 0; k < kMaxPtrs; ++k)
+        if (l.ptr[k].kind != BUF_NONE) s += "  ptr" + std::to_string(k) + " " + buf_name(l.ptr[k]) + "\n";
+      continue;
+    }
+    const RowProgP& q = l.args.u.prog;
+    snprintf(line, sizeof line, "  program dt=%s rows=%u cols=%u lanes=%d vecs=%d regs=%d sregs=%d\n", dtype_name(q.dt), q.rows, q.cols,
+             q.lanes_per_row, q.vecs_per_lane, q.n_regs, q.n_sregs);
+    s += line;
+    for (int i = 0; i < q.n_full; ++i) s += "  full " + buf_name(l.ptr[i]) + " reg " + std::to_string(q.full_reg[i]) + "\n";
+    for (int i = 0; i < q.n_col; ++i) s += "  col " + buf_name(l.ptr[4 + i]) + " reg " + std::to_string(q.col_reg[i]) + "\n";
+    for (int i = 0; i < q.n_rscal; ++i)
+      s += "  rscal " + buf_name(l.ptr[8 + i]) + " sreg " + std::to_string(q.rscal_sreg[i]) + " " + dtype_name(q.rscal_dt[i]) + "\n";
+    for (int i = 0; i < kProgMaxOperands; ++i)
+      if (l.ptr[12 + i].kind != BUF_NONE) s += "  output " + std::to_string(i) + " " + buf_name(l.ptr[12 + i]) + "\n";
+    for (int i = 0; i < kProgMaxOperands; ++i)
+      if (l.ptr[16 + i].kind != BUF_NONE) s += "  routput " + std::to_string(i) + " " + buf_name(l.ptr[16 + i]) + "\n";
+    static const char* op_names[] = {"add", "sub", "mul", "div", "max", "square", "exp", "rsqrt", "tanh", "gelu", "gelu_grad",
+                                     "mov", "cvt", "rsum", "rmax", "store", "store_scal"};
+    static const char* kind_names[] = {"acc", "sacc", "reg", "scal", "imm"};
+    for (int i = 0; i < q.n_instr; ++i) {
+      const ProgInstr& in = q.instr[i];
+      snprintf(line, sizeof line, "  instr %d %s a=%s:%d b=%s:%d dst=%d flags=%s%s aux=%d imm=%.9g\n", i, op_names[in.op], kind_names[in.a_kind],
+               in.a, kind_names[in.b_kind], in.b, in.dst, (in.flags & PF_SCALAR) ? "s" : "v", (in.flags & PF_KEEP) ? "k" : "-", in.aux,
+               (double)in.imm);
+      s += line;
+    }
+  }
+  if (capacity > 0) {
+    const size_t n = std::min(capacity - 1, s.size());
+    memcpy(text, s.data(), n);
+    text[n] = 0;
+  }
+  return (int64_t)s.size() + 1;
 }
 
 fs_status fs_execute(const fs_plan* p, const void* const* inputs, void* const* outputs, void* workspace,

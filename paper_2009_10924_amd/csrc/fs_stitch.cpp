@@ -1072,14 +1072,21 @@ std::string build_stitched(const fs_graph& g, std::vector<Candidate>* out, PackF
       {"transpose_chain", build_tchain}, {"softmax_backward", build_softmax_backward}, {"rmsnorm", build_rmsnorm},
       {"layernorm_backward", build_layernorm_backward}, {"transpose", build_transpose},
   };
+  std::string recognised;
   for (const Family& f : families) {
     out->clear();
     *pack = PackForm();
-    if (f.build(g, out, pack)) return f.name;
+    if (f.build(g, out, pack)) {
+      if (!out->empty()) return f.name;
+      if (recognised.empty()) recognised = f.name;   // right shape of graph, but no compiled variant fits
+    }
   }
+  // no hand-written family: any row-local pattern still runs as one interpreted kernel
   out->clear();
   *pack = PackForm();
-  return "";
+  if (build_row_program(g, out)) return "row_program";
+  out->clear();
+  return recognised;
 }
 
 }  // namespace fs

@@ -9,4 +9,5 @@ const void* layernorm_kernel_symbol(int32_t kernel, const KernelArgs& a);
 const void* gelu_kernel_symbol(int32_t kernel, const KernelArgs& a);
 const void* tchain_kernel_symbol(int32_t kernel, const KernelArgs& a);
 const void* rowops_kernel_symbol(int32_t kernel, const KernelArgs& a);
+const void* rowprog_kernel_symbol(int32_t kernel, const KernelArgs& a);
 }  // namespace fs

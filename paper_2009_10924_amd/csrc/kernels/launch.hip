@@ -16,7 +16,7 @@ const KernelDesc kDesc[K_COUNT] = {
     {"transpose_rows", 2}, {"transpose_tile", 2},  {"copy", 2},           {"softmax_wave", 3},
     {"softmax_block", 3},  {"layernorm_wave", 6},  {"layernorm_block", 6}, {"bias_gelu", 3},
     {"bias_gelu_dbias", 7}, {"colfold", 3},        {"tchain_wave", 3},    {"tchain_lds", 3},
-    {"row_wave", 6},       {"row_block", 6},       {"layernorm_bwd", 7},
+    {"row_wave", 6},       {"row_block", 6},       {"row_program", 0},    {"layernorm_bwd", 7},
 };
 
 const void* symbol_for(int32_t kernel, const KernelArgs& a) {
@@ -34,6 +34,8 @@ const void* symbol_for(int32_t kernel, const KernelArgs& a) {
       return tchain_kernel_symbol(kernel, a);
     case K_ROW_WAVE: case K_ROW_BLOCK:
       return rowops_kernel_symbol(kernel, a);
+    case K_ROW_PROGRAM:
+      return rowprog_kernel_symbol(kernel, a);
     default:
       return nullptr;
   }
@@ -50,6 +52,27 @@ int launch_kernel(int32_t kernel, const KernelArgs& args, const LaunchShape& s, 
   if (kernel < 0 || kernel >= K_COUNT) return (int)hipErrorInvalidValue;
   const void* sym = symbol_for(kernel, args);
   if (!sym) return (int)hipErrorInvalidDeviceFunction;
+  if (kernel == K_ROW_PROGRAM) {
+    // one by-value argument: pointers by class, then the program
+    ProgArgs pa;
+    for (int i = 0; i < kProgMaxOperands; ++i) {
+      pa.full[i] = args.p[i];
+      pa.col[i] = args.p[4 + i];
+      pa.rscal[i] = args.p[8 + i];
+      pa.out[i] = args.p[12 + i];
+      pa.rout[i] = args.p[16 + i];
+    }
+    pa.p = args.u.prog;
+    if (s.lds_bytes > 64u * 1024u) {
+      // more dynamic LDS than the default cap: the limit is a per-kernel attribute
+      if (s.lds_bytes > (uint32_t)kProgMaxLdsBytes) return (int)hipErrorInvalidValue;
+      const hipError_t e = hipFuncSetAttribute(sym, hipFuncAttributeMaxDynamicSharedMemorySize, (int)s.lds_bytes);
+      if (e != hipSuccess) return (int)e;
+    }
+    void* one[1] = {&pa};
+    return (int)hipLaunchKernel(sym, dim3(s.grid[0], s.grid[1], s.grid[2]), dim3(s.block[0], s.block[1], s.block[2]),
+                                one, s.lds_bytes, static_cast<hipStream_t>(stream));
+  }
   KernelArgs a = args;   // hipLaunchKernel wants addresses of mutable argument storage
   void* argv[kMaxPtrs + 1];
   const int n = kDesc[kernel].n_ptrs;

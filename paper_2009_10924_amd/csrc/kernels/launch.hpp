@@ -6,7 +6,7 @@
 
 namespace fs {
 
-constexpr int kMaxPtrs = 8;
+constexpr int kMaxPtrs = 20;
 
 // storage dtypes, numbered like the public fs_dtype
 enum DType : int32_t { DT_F32 = 0, DT_F16 = 1, DT_BF16 = 2, DT_I32 = 3 };
@@ -32,6 +32,8 @@ enum KernelId : int32_t {
   K_TCHAIN_LDS,
   K_ROW_WAVE,          // p0,p1 row inputs, p2,p3 column vectors, p4 out0, p5 out1 : generic row-stitched skeleton
   K_ROW_BLOCK,         // same operands as K_ROW_WAVE, one workgroup per row, reduced values through LDS
+  K_ROW_PROGRAM,       // interpreted row program: p0-3 full inputs, p4-7 column vectors, p8-11 per-row scalar
+                       // inputs, p12-15 full outputs, p16-19 per-row scalar outputs
   K_LAYERNORM_BWD,     // p0 h, p1 dy, p2 gamma, p3 mu, p4 rstd, p5 dx, p6 partials [n_row_blocks, 2, cols]
   K_COUNT
 };
@@ -164,8 +166,60 @@ struct PackTable {
   uint32_t total_blocks;
   PackEntry e[kPackMaxMembers];
 };
+// ---- interpreted row program -------------------------------------------------------------
+// Any connected pattern of element-wise ops, broadcasts and last-axis reductions over one
+// [rows, cols] space runs as ONE kernel: a lane group (or the workgroup) owns a row, values
+// live in a per-lane register file in LDS plus an accumulator in VGPRs, and the kernel
+// walks a short instruction list carried in its arguments.
+enum ProgOp : uint8_t {
+  PO_ADD = 0, PO_SUB, PO_MUL, PO_DIV, PO_MAX,            // a (op) b
+  PO_SQUARE, PO_EXP, PO_RSQRT, PO_TANH, PO_GELU, PO_GELU_GRAD, PO_MOV,   // (op) a
+  PO_CVT,                                                 // a rounded through storage dtype `aux`
+  PO_RSUM, PO_RMAX,                                       // row reduction of a -> per-row scalar
+  PO_STORE,                                               // a -> full output `dst`, stored as dtype `aux`
+  PO_STORE_SCAL                                           // per-row scalar a -> per-row output `dst`, dtype `aux`
+};
+enum ProgKind : uint8_t {
+  PK_ACC = 0,   // the accumulator: result of the latest full-shaped instruction
+  PK_SACC,      // the scalar accumulator: result of the latest per-row-shaped instruction
+  PK_REG,       // full-shaped register a / b (LDS, private to the lane)
+  PK_SCAL,      // per-row scalar register a / b
+  PK_IMM        // the instruction's immediate
+};
+enum ProgFlags : uint8_t {
+  PF_SCALAR = 1,   // per-row-shaped instruction: one value per row, result to SACC
+  PF_KEEP = 2      // also write the result to register `dst` (full or scalar file by shape)
+};
+struct ProgInstr {
+  uint8_t op, a_kind, b_kind, flags;
+  uint8_t a, b, dst, aux;
+  float imm;
+};
+constexpr int kProgMaxInstr = 64;
+constexpr int kProgMaxOperands = 4;     // per class: full inputs, column vectors, per-row inputs, outputs
+constexpr int kProgMaxReductions = 8;   // LDS slot sets of the workgroup-per-row form
+constexpr int kProgMaxLdsBytes = 128 * 1024;   // register files of one workgroup (a CU has 160 KB)
+struct RowProgP {
+  int32_t dt;                          // storage dtype of full inputs and column vectors
+  uint32_t rows, cols;
+  int32_t lanes_per_row, lanes_log2, vecs_per_lane;   // lanes_per_row > 64: one workgroup per row
+  int32_t n_full, n_col, n_rscal, n_instr;
+  int32_t n_regs, n_sregs;             // register files: full-shaped and per-row
+  uint8_t full_reg[kProgMaxOperands], col_reg[kProgMaxOperands], rscal_sreg[kProgMaxOperands];
+  uint8_t rscal_dt[kProgMaxOperands];
+  ProgInstr instr[kProgMaxInstr];
+};
+struct ProgArgs {
+  const void* full[kProgMaxOperands];
+  const void* col[kProgMaxOperands];
+  const void* rscal[kProgMaxOperands];
+  void* out[kProgMaxOperands];
+  void* rout[kProgMaxOperands];
+  RowProgP p;
+};
+
 struct KernelArgs {
-  void* p[kMaxPtrs] = {nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr};
+  void* p[kMaxPtrs] = {};
   union {
     UnaryP unary;
     BinaryP binary;
@@ -177,6 +231,7 @@ struct KernelArgs {
     TChainP tchain;
     RowP row;
     LnBwdP lnbwd;
+    RowProgP prog;
   } u;
   KernelArgs() { u.binary = BinaryP{}; }
 };

@@ -82,3 +82,18 @@ def run_pack(specs, inputs_list, repeat=1):
                 assert np.array_equal(a[name].view(np.uint8), b[name].view(np.uint8)), f"{name}: not run-to-run identical"
     out = [{name: O.to_f64(res[name], dt) for name, dt in spec.outputs} for spec, res in zip(specs, results[0])]
     return out, pack.info
+
+
+def all_candidates(spec, inputs, ref, floors, repeat=1, unfused=True):
+    """Runs the per-op plan and every stitched candidate of `spec`; returns the worst error per output."""
+    worst = {}
+    g = B.Graph.from_spec(spec)
+    n = B.Plan(g, "auto").info["n_candidates"]
+    runs = ([("unfused", {})] if unfused else []) + [("auto", {"candidate": i}) for i in range(n)]
+    for scheme, opts in runs:
+        note(f"  case {spec.name} scheme={scheme} opts={opts}")
+        got, _, info, _ = run_spec(spec, inputs, scheme, repeat=repeat, **opts)
+        for name, dt in spec.outputs:
+            e = check(got[name], ref[name], dt, floors.get(name, 0.0), f"{spec.name}/{info['kernel']}/{name}")
+            worst[name] = max(worst.get(name, 0.0), e)
+    return worst

@@ -1,0 +1,65 @@
+"""GPU parity of the interpreted row program (the generic stitched path for patterns no
+hand-written kernel family covers): every enumerated launch shape, plus the per-op plan,
+against the float64 oracle; named patterns and seeded random patterns."""
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+from paper_2009_10924_amd import binding as B
+from tests.gpu_util import all_candidates, note
+from workloads import (layernorm_stats_graph, make_inputs, normalize_from_stats_graph, outer_scale_graph,
+                       random_row_pattern, scaled_softmax_colbias_graph, silu_gate_graph)
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(spec, seed=0, repeat=2):
+    info = B.Plan(B.Graph.from_spec(spec), "auto").info
+    assert info["pattern"] == "row_program", (spec.name, info["pattern"])
+    inp = make_inputs(spec, seed=seed)
+    ref = O.evaluate(spec, inp)
+    floors = {name: O.rms(ref[name]) for name, _ in spec.outputs}   # sums and differences cancel in most of these
+    worst = all_candidates(spec, inp, ref, floors, repeat=repeat)
+    return worst, info
+
+
+@pytest.mark.parametrize("rows,cols,in_dt,out_dt", [(100, 768, "f32", "bf16"), (37, 100, "f32", "f32"), (9, 1024, "bf16", "bf16"),
+                                                   (5, 4096, "f32", "f16"), (300, 64, "f16", "f32"), (3, 2048, "f16", "f16")])
+def test_layernorm_with_saved_statistics(rows, cols, in_dt, out_dt):
+    worst, info = _run(layernorm_stats_graph(rows, cols, in_dtype=in_dt, out_dtype=out_dt))
+    note(f"LayerNorm + statistics {rows}x{cols} {in_dt}->{out_dt}: {info['n_candidates']} shapes, worst {worst}")
+
+
+@pytest.mark.parametrize("rows,cols,dtype", [(33, 1024, "bf16"), (257, 40, "f32"), (2, 8192, "f16"), (64, 128, "f32")])
+def test_silu_gate(rows, cols, dtype):
+    worst, _ = _run(silu_gate_graph(rows, cols, dtype))
+    note(f"gated SiLU {rows}x{cols} {dtype}: {worst}")
+
+
+@pytest.mark.parametrize("rows,cols,dtype", [(50, 128, "f32"), (7, 1000, "f32"), (19, 264, "f16"), (4, 4096, "bf16")])
+def test_softmax_with_column_operands(rows, cols, dtype):
+    worst, _ = _run(scaled_softmax_colbias_graph(rows, cols, dtype))
+    note(f"softmax with column bias and gain {rows}x{cols} {dtype}: {worst}")
+
+
+@pytest.mark.parametrize("rows,cols,dtype", [(20, 256, "f16"), (130, 768, "f32"), (3, 4096, "bf16"), (1, 8, "f32")])
+def test_normalize_from_saved_statistics_and_broadcast_outputs(rows, cols, dtype):
+    worst, _ = _run(normalize_from_stats_graph(rows, cols, dtype))
+    note(f"normalise from statistics {rows}x{cols} {dtype}: {worst}")
+
+
+@pytest.mark.parametrize("rows,cols", [(7, 64), (300, 1024), (2, 4096)])
+def test_outer_product_without_full_input(rows, cols):
+    worst, _ = _run(outer_scale_graph(rows, cols))
+    note(f"outer scale {rows}x{cols}: {worst}")
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_random_row_patterns(seed):
+    dtype = ("f32", "f16", "bf16")[seed % 3]
+    rows, cols = [(37, 128), (5, 1000), (130, 64), (3, 4096), (64, 520), (9, 2048)][seed % 6]
+    if dtype != "f32" and cols % 8:
+        cols = cols // 8 * 8
+    spec = random_row_pattern(seed, rows, cols, dtype, n_ops=6 + seed % 14)
+    worst, info = _run(spec, seed=seed, repeat=1)
+    note(f"random pattern {seed} {rows}x{cols} {dtype}: {len(spec.ops)} ops -> {info['kernel']}, worst {worst}")

@@ -103,15 +103,21 @@ def test_scheme_selection_and_locality():
 
 
 def test_unsupported_pattern_and_auto_fallback():
-    # exp(x) * x : valid graph, no stitched kernel
+    # exp(transpose(x)): valid graph, but values move between rows, so no stitched kernel
     spec = GraphSpec("custom", [TensorSpec("x", "f32", (8, 16))],
-                     [OpSpec("e", "exp", ("x",)), OpSpec("y", "mul", ("e", "x"))], [("y", "f32")])
+                     [OpSpec("t", "transpose", ("x",), {"perm": (1, 0)}), OpSpec("y", "exp", ("t",))], [("y", "f32")])
     g = B.Graph.from_spec(spec)
     with pytest.raises(B.FsError) as e:
         B.Plan(g, "wave")
     assert e.value.code == -5                       # FS_ERR_UNSUPPORTED_PATTERN
     info = B.Plan(g, "auto").info
     assert info["scheme"] == "unfused" and info["n_kernels"] == 2
+    # exp(x) * x has no hand-written family, but is row-local: one interpreted kernel
+    spec = GraphSpec("custom", [TensorSpec("x", "f32", (8, 16))],
+                     [OpSpec("e", "exp", ("x",)), OpSpec("y", "mul", ("e", "x"))], [("y", "f32")])
+    info = B.Plan(B.Graph.from_spec(spec), "auto").info
+    assert info["pattern"] == "row_program" and info["n_kernels"] == 1 and info["workspace_bytes"] == 0
+    assert ",I3," in info["kernel"]                 # exp, mul, store
     # ragged softmax still gets a stitched (block-per-row) kernel
     info = B.Plan(B.Graph.from_spec(softmax_graph(5, 37, "f32")), "auto").info
     assert info["pattern"] == "softmax" and info["scheme"] == "lds"

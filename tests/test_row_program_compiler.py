@@ -1,0 +1,174 @@
+"""Host compiler of the interpreted row program, checked on the CPU: the instruction listing the
+library hands out (fs_plan_describe) is executed by a small numpy emulator written here and its
+results are compared with the float64 oracle.  A wrong operand, a register reused too early or a
+value dropped from the accumulator shows up as a numerical mismatch without any GPU."""
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+from paper_2009_10924_amd import binding as B
+from workloads import (layernorm_stats_graph, make_inputs, normalize_from_stats_graph, outer_scale_graph,
+                       random_row_pattern, scaled_softmax_colbias_graph, silu_gate_graph)
+
+NP_DT = {0: "f32", 1: "f16", 2: "bf16"}
+
+
+def _round_through(v, dt):
+    if dt == "f32":
+        return v.astype(np.float32)
+    return O.to_f64(O.round_to(v.astype(np.float64), dt), dt).astype(np.float32)
+
+
+def _gelu(z):
+    z = z.astype(np.float64)
+    return 0.5 * z * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (z + 0.044715 * z ** 3)))
+
+
+def _gelu_grad(z):
+    z = z.astype(np.float64)
+    u = np.sqrt(2.0 / np.pi) * (z + 0.044715 * z ** 3)
+    t = np.tanh(u)
+    return 0.5 * (1.0 + t) + 0.5 * z * (1.0 - t * t) * np.sqrt(2.0 / np.pi) * (1.0 + 3 * 0.044715 * z * z)
+
+
+def emulate(listing, spec, inputs):
+    """Runs the listed program in float32 on whole arrays: full values [R, C], per-row values [R, 1]."""
+    lines = [l.split() for l in listing.splitlines()]
+    head = [l for l in lines if l and l[0] == "program"][0]
+    kv = dict(x.split("=") for x in head[1:])
+    rows, cols = int(kv["rows"]), int(kv["cols"])
+    in_arrays = [O.to_f64(inputs[t.name], t.dtype).astype(np.float32) for t in spec.inputs]
+    regs, sregs, outs = {}, {}, {}
+    out_bind, rout_bind = {}, {}
+    for l in lines:
+        if not l:
+            continue
+        if l[0] == "full":
+            regs[int(l[3])] = in_arrays[int(l[1][2:])].reshape(rows, cols)
+        elif l[0] == "col":
+            regs[int(l[3])] = np.broadcast_to(in_arrays[int(l[1][2:])].reshape(1, cols), (rows, cols))
+        elif l[0] == "rscal":
+            sregs[int(l[3])] = in_arrays[int(l[1][2:])].reshape(rows, 1)
+        elif l[0] == "output":
+            out_bind[int(l[1])] = int(l[2][3:])
+        elif l[0] == "routput":
+            rout_bind[int(l[1])] = int(l[2][3:])
+    acc = np.zeros((rows, cols), np.float32)
+    sacc = np.zeros((rows, 1), np.float32)
+    f32 = np.float32
+    n_instr = 0
+    for l in lines:
+        if not l or l[0] != "instr":
+            continue
+        n_instr += 1
+        op = l[2]
+        f = dict(x.split("=") for x in l[3:])
+        imm = f32(float(f["imm"]))
+        scalar, keep = f["flags"][0] == "s", f["flags"][1] == "k"
+        aux = NP_DT[int(f["aux"])]
+
+        def operand(text):
+            kind, idx = text.split(":")
+            if kind == "acc":
+                return acc
+            if kind == "sacc":
+                return sacc
+            if kind == "reg":
+                return regs[int(idx)]
+            if kind == "scal":
+                return sregs[int(idx)]
+            return np.full((1, 1), imm, np.float32)
+        a = operand(f["a"])
+        dst = int(f["dst"])
+        if op == "store":
+            outs[out_bind[dst]] = np.broadcast_to(a, (rows, cols)).copy()
+            continue
+        if op == "store_scal":
+            assert a.shape == (rows, 1)
+            outs[rout_bind[dst]] = a.copy()
+            continue
+        if op in ("rsum", "rmax"):
+            assert a.shape == (rows, cols)
+            sacc = (a.sum(axis=1, keepdims=True, dtype=np.float32) if op == "rsum" else a.max(axis=1, keepdims=True)).astype(f32)
+            if keep:
+                sregs[dst] = sacc
+            continue
+        b = operand(f["b"])
+        with np.errstate(all="ignore"):
+            r = {"add": lambda: a + b, "sub": lambda: a - b, "mul": lambda: a * b, "div": lambda: a / b,
+                 "max": lambda: np.maximum(a, b), "square": lambda: a * a, "exp": lambda: np.exp(a),
+                 "rsqrt": lambda: 1.0 / np.sqrt(a), "tanh": lambda: np.tanh(a), "gelu": lambda: _gelu(a),
+                 "gelu_grad": lambda: _gelu_grad(a), "mov": lambda: a, "cvt": lambda: _round_through(a, aux)}[op]()
+        r = np.asarray(r, dtype=np.float32)
+        if scalar:
+            assert r.shape in ((rows, 1), (1, 1)), "per-row instruction with a full-shaped operand"
+            sacc = np.broadcast_to(r, (rows, 1)).copy()
+            if keep:
+                sregs[dst] = sacc
+        else:
+            acc = np.broadcast_to(r, (rows, cols)).copy()
+            if keep:
+                regs[dst] = acc
+    result = {}
+    for slot, (name, dt) in enumerate(spec.outputs):
+        result[name] = outs[slot].astype(np.float64)
+    return result, n_instr
+
+
+def _compare(spec, seed=1):
+    plan = B.Plan(B.Graph.from_spec(spec), "auto")
+    assert plan.info["pattern"] == "row_program", (spec.name, plan.info["pattern"])
+    listing = plan.describe()
+    inp = make_inputs(spec, seed=seed)
+    ref = O.evaluate(spec, inp)
+    got, n_instr = emulate(listing, spec, inp)
+    for name, dt in spec.outputs:
+        r = ref[name].reshape(got[name].shape)
+        err = O.max_rel_err(got[name], r, O.rms(r))
+        assert err < 2e-5, f"{spec.name}/{name}: emulated program is off by {err:.3e}\n{listing}"
+    return n_instr, plan.info
+
+
+@pytest.mark.parametrize("make", [
+    lambda: layernorm_stats_graph(24, 96, in_dtype="f32", out_dtype="f32"),
+    lambda: silu_gate_graph(9, 64, "f32"),
+    lambda: scaled_softmax_colbias_graph(13, 40, "f32"),
+    lambda: normalize_from_stats_graph(11, 48, "f32"),
+    lambda: outer_scale_graph(7, 16),
+])
+def test_named_patterns_compile_to_correct_programs(make):
+    _compare(make())
+
+
+def test_layernorm_program_keeps_only_what_is_read_again():
+    spec = layernorm_stats_graph(24, 96, in_dtype="f32", out_dtype="f32")
+    plan = B.Plan(B.Graph.from_spec(spec), "auto")
+    lines = [l.split() for l in plan.describe().splitlines() if l.strip().startswith("instr")]
+    kept = [l for l in lines if "flags=vk" in l or "flags=sk" in l]
+    # h, mean, variance, rstd, the scaled values all pass through the accumulators; only the
+    # centred row (read again after the variance reduction chain) is written to a register
+    assert len(kept) == 1 and kept[0][2] == "sub"
+    head = [l for l in plan.describe().splitlines() if l.strip().startswith("program ")][0]
+    assert "regs=5" in head and "sregs=0" in head       # 2 full inputs + 3 column vectors, the centred row reuses x's slot
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_random_patterns_compile_to_correct_programs(seed):
+    spec = random_row_pattern(seed, 11, 32, "f32", n_ops=6 + seed % 12)
+    _compare(spec, seed=seed)
+
+
+def test_patterns_that_are_not_row_local_are_refused():
+    from workloads.graphs import GraphSpec, OpSpec, TensorSpec
+    # column reduction: values cross rows
+    spec = GraphSpec("pattern_x", [TensorSpec("x", "f32", (8, 16))],
+                     [OpSpec("e", "exp", ("x",)), OpSpec("s", "reduce_sum", ("e",), {"axis": 0})], [("s", "f32")])
+    assert B.Plan(B.Graph.from_spec(spec), "auto").info["scheme"] == "unfused"
+    # operand that varies along a middle axis only
+    spec = GraphSpec("pattern_y", [TensorSpec("x", "f32", (4, 6, 16)), TensorSpec("m", "f32", (4, 1, 16))],
+                     [OpSpec("a", "add", ("x", "m")), OpSpec("y", "exp", ("a",))], [("y", "f32")])
+    assert B.Plan(B.Graph.from_spec(spec), "auto").info["scheme"] == "unfused"
+    # row too long for the register file in LDS: falls back as well
+    spec = GraphSpec("pattern_z", [TensorSpec("x", "f32", (2, 1 << 15))],
+                     [OpSpec("e", "exp", ("x",)), OpSpec("y", "mul", ("e", "x"))], [("y", "f32")])
+    assert B.Plan(B.Graph.from_spec(spec), "auto").info["scheme"] == "unfused"

@@ -279,6 +279,146 @@ NEXT_CONFIGS = {
     "N5": lambda: rmsnorm_graph(8192, 4096, dtype="bf16"),
 }
 
+# ---- row-local patterns no hand-written kernel family covers (served by the interpreted row program) ----
+def layernorm_stats_graph(rows: int, cols: int, eps: float = 1e-5, in_dtype: str = "f32", out_dtype: str = "bf16") -> GraphSpec:
+    """Residual add + bias + LayerNorm that also hands out the per-row mean and reciprocal standard
+    deviation, as a training forward pass does (three outputs, two of them [rows,1])."""
+    base = add_bias_layernorm_graph(rows, cols, eps, in_dtype, out_dtype)
+    return GraphSpec(name=f"pattern_layernorm_stats_{in_dtype}_{rows}x{cols}", inputs=base.inputs, ops=base.ops,
+                     outputs=[("out", out_dtype), ("mu", "f32"), ("r", "f32")])
+
+
+def silu_gate_graph(rows: int, cols: int, dtype: str = "bf16") -> GraphSpec:
+    """Gated SiLU: out = a * sigmoid(a) * b with sigmoid spelt as 1 / (1 + exp(-a))  (6 ops, no reduction)."""
+    ops = [
+        _op("n", "scale", "a", value=-1.0),
+        _op("e", "exp", "n"),
+        _op("d", "add_scalar", "e", value=1.0),
+        _op("s", "div", "a", "d"),
+        _op("out", "mul", "s", "b"),
+    ]
+    return GraphSpec(name=f"pattern_silu_gate_{dtype}_{rows}x{cols}",
+                     inputs=[TensorSpec("a", dtype, (rows, cols)), TensorSpec("b", dtype, (rows, cols))],
+                     ops=ops, outputs=[("out", dtype)])
+
+
+def scaled_softmax_colbias_graph(rows: int, cols: int, dtype: str = "f32") -> GraphSpec:
+    """softmax(scale * x + colbias) followed by a per-column gain: a softmax neighbourhood the softmax family
+    does not match (column-vector operands on both sides)."""
+    ops = [_op("t", "scale", "x", value=0.5), _op("a", "add", "t", "bias")] + _softmax_ops("a", 1) + [_op("out", "mul", "y", "gamma")]
+    return GraphSpec(name=f"pattern_softmax_colbias_{dtype}_{rows}x{cols}",
+                     inputs=[TensorSpec("x", dtype, (rows, cols)), TensorSpec("bias", dtype, (cols,)), TensorSpec("gamma", dtype, (cols,))],
+                     ops=ops, outputs=[("out", dtype)])
+
+
+def normalize_from_stats_graph(rows: int, cols: int, dtype: str = "f16") -> GraphSpec:
+    """(h - mu) * rstd * gamma with saved per-row statistics as inputs, an explicit broadcast op, and the row
+    maximum of the result stretched back to [rows, cols] as a second output."""
+    ops = [
+        _op("mb", "broadcast", "mu", dims=(rows, cols)),
+        _op("c", "sub", "h", "mb"),
+        _op("n", "mul", "c", "rstd"),
+        _op("out", "mul", "n", "gamma"),
+        _op("top", "reduce_max", "out", axis=1),
+        _op("topb", "broadcast", "top", dims=(rows, cols)),
+    ]
+    return GraphSpec(name=f"pattern_normalize_from_stats_{dtype}_{rows}x{cols}",
+                     inputs=[TensorSpec("h", dtype, (rows, cols)), TensorSpec("gamma", dtype, (cols,)),
+                             TensorSpec("mu", "f32", (rows, 1)), TensorSpec("rstd", "f32", (rows, 1))],
+                     ops=ops, outputs=[("out", dtype), ("topb", "f32")])
+
+
+def outer_scale_graph(rows: int, cols: int) -> GraphSpec:
+    """out = tanh(gamma[cols] * rstd[rows,1]): a full-shaped result with no full-shaped input."""
+    ops = [_op("p", "mul", "gamma", "rstd"), _op("out", "tanh", "p")]
+    return GraphSpec(name=f"pattern_outer_scale_f32_{rows}x{cols}",
+                     inputs=[TensorSpec("gamma", "f32", (cols,)), TensorSpec("rstd", "f32", (rows, 1))],
+                     ops=ops, outputs=[("out", "f32")])
+
+
+def random_row_pattern(seed: int, rows: int, cols: int, dtype: str = "f32", n_ops: int = 12) -> GraphSpec:
+    """A random connected pattern of element-wise ops and row reductions over [rows, cols] (descriptor only).
+    Domains are kept safe by construction: exp only of tanh, division and rsqrt only of 1 + square."""
+    import random
+    rnd = random.Random(seed)
+    inputs = [TensorSpec("x0", dtype, (rows, cols))]
+    kinds = {"x0": "full"}
+    for i in range(rnd.randint(0, 2)):
+        inputs.append(TensorSpec(f"x{i + 1}", dtype, (rows, cols)))
+        kinds[f"x{i + 1}"] = "full"
+    for i in range(rnd.randint(0, 2)):
+        inputs.append(TensorSpec(f"g{i}", dtype, (cols,)))
+        kinds[f"g{i}"] = "col"
+    for i in range(rnd.randint(0, 2)):
+        inputs.append(TensorSpec(f"r{i}", "f32", (rows, 1)))
+        kinds[f"r{i}"] = "rscal"
+    ops: List[OpSpec] = []
+    names = list(kinds)
+
+    def pick(want=None):
+        pool = [n for n in names if want is None or kinds[n] in want]
+        recent = pool[-4:]
+        return rnd.choice(recent if rnd.random() < 0.6 else pool)
+
+    def add(opcode, *ins, kind, **attr):
+        name = f"v{len(ops)}"
+        ops.append(_op(name, opcode, *ins, **attr))
+        kinds[name] = kind
+        names.append(name)
+        return name
+
+    def join(ka, kb):
+        if ka == kb and ka != "full":
+            return ka
+        return "full"
+
+    while len(ops) < n_ops:
+        r = rnd.random()
+        if r < 0.40:
+            a, b = pick(), pick()
+            if kinds[a] == "col" and kinds[b] == "col":
+                continue
+            op = rnd.choice(["add", "sub", "mul", "max"])
+            v = add(op, a, b, kind=join(kinds[a], kinds[b]))
+            if op == "mul":
+                add("tanh", v, kind=kinds[v])                    # keeps magnitudes bounded
+        elif r < 0.55:
+            a = pick(("full", "rscal"))
+            add(rnd.choice(["scale", "add_scalar"]), a, kind=kinds[a], value=rnd.choice([-1.5, 0.25, 0.5, 2.0]))
+        elif r < 0.67:
+            a = pick(("full", "rscal"))
+            t = add("tanh", a, kind=kinds[a])
+            add(rnd.choice(["exp", "gelu_tanh", "square"]), t, kind=kinds[a])
+        elif r < 0.77:
+            a, b = pick(), pick(("full", "rscal"))
+            q = add("square", b, kind=kinds[b])
+            d = add("add_scalar", q, kind=kinds[b], value=1.0)
+            if rnd.random() < 0.5:
+                d = add("rsqrt", d, kind=kinds[b])
+                add("mul", a, d, kind=join(kinds[a], kinds[b])) if not (kinds[a] == "col" and kinds[b] == "col") else None
+            else:
+                add("div", a, d, kind=join(kinds[a], kinds[b]))
+        else:
+            a = pick(("full",))
+            add(rnd.choice(["reduce_sum", "reduce_max", "reduce_mean"]), a, kind="rscal", axis=1)
+    # outputs: the last full value, plus up to two more values; ops that reach no output are dropped
+    fulls = [o.out for o in ops if kinds[o.out] == "full"]
+    if not fulls:
+        fulls = [add("add", "x0", names[-1], kind="full")]
+    outs = [fulls[-1]]
+    extra = [o.out for o in ops if kinds[o.out] in ("full", "rscal") and o.out != outs[0]]
+    rnd.shuffle(extra)
+    outs += extra[:rnd.randint(0, 2)]
+    live = set(outs)
+    for o in reversed(ops):
+        if o.out in live:
+            live.update(o.inputs)
+    ops = [o for o in ops if o.out in live]
+    inputs = [t for t in inputs if t.name in live] or inputs[:1]
+    outputs = [(n, dtype if kinds[n] == "full" else "f32") for n in outs]
+    return GraphSpec(name=f"pattern_random{seed}_{dtype}_{rows}x{cols}", inputs=inputs, ops=ops, outputs=outputs)
+
+
 def pack_members_p1() -> List[GraphSpec]:
     """P1: 32 independent tiny subgraphs (each a few microseconds or less on its own, so launch-bound when run
     one kernel each): the many-small-kernels regime that kernel packing addresses."""

@@ -17,7 +17,7 @@ import numpy as np
 
 from .graphs import GraphSpec
 
-CONFIG_INDEX = {"rmsnorm": 10, "softmax_backward": 8, "layernorm_backward": 9, "softmax": 1, "add_bias_layernorm": 2, "attention_scores": 3,
+CONFIG_INDEX = {"pattern": 11, "rmsnorm": 10, "softmax_backward": 8, "layernorm_backward": 9, "softmax": 1, "add_bias_layernorm": 2, "attention_scores": 3,
                 "bias_gelu_dbias": 4, "transpose_chain": 5, "transpose": 6, "bias_gelu": 7}
 
 
@@ -70,6 +70,8 @@ def make_inputs(graph: GraphSpec, seed: int = 0) -> Dict[str, np.ndarray]:
       softmax_backward   y ~ Dirichlet(1,..,1) per row (positive, rows sum to 1); dy ~ N(0,1)
       rmsnorm            x ~ N(0,1); gamma ~ 1+N(0,0.02)
       layernorm_backward h, dy ~ N(0,1); gamma ~ 1+N(0,0.02); mu ~ N(0,0.05); rstd ~ U(0.8,1.2)
+      pattern (any other row-local pattern) by tensor name: g* ~ 1+N(0,0.02); r* ~ U(0.8,1.2); mu* ~ N(0,0.05);
+                         bias*, beta* ~ N(0,0.02); everything else ~ N(0,1)
     """
     kind = _kind(graph)
     cfg = CONFIG_INDEX[kind]
@@ -109,6 +111,17 @@ def make_inputs(graph: GraphSpec, seed: int = 0) -> Dict[str, np.ndarray]:
                 a = 0.05 * g.standard_normal(t.dims)
             else:
                 a = g.uniform(0.8, 1.2, t.dims)
+        elif kind == "pattern":
+            if n.startswith("g"):
+                a = 1.0 + 0.02 * g.standard_normal(t.dims)
+            elif n.startswith("r") and n != "res":
+                a = g.uniform(0.8, 1.2, t.dims)
+            elif n.startswith("mu"):
+                a = 0.05 * g.standard_normal(t.dims)
+            elif n.startswith(("bias", "beta")):
+                a = 0.02 * g.standard_normal(t.dims)
+            else:
+                a = g.standard_normal(t.dims)
         elif kind == "transpose_chain":
             a = g.uniform(-1.0, 1.0, t.dims) if n == "x" else g.uniform(0.5, 1.5, t.dims)
         elif kind == "transpose":
