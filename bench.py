@@ -332,6 +332,11 @@ def main():
                                    for name in ("N1", "N2", "N3", "N4", "N5")}
         torch.cuda.empty_cache()
         result["packing"] = measure_pack("P1", max(200, args.steps // 2), 20)
+        torch.cuda.empty_cache()
+        # row-local patterns outside the hand-written families: one interpreted kernel each
+        from workloads import GENERIC_CONFIGS
+        result["generic_patterns"] = {name: measure_config(name, GENERIC_CONFIGS[name](), max(50, args.steps // 8), 10)
+                                      for name in ("G1", "G2", "G3", "G4")}
     print(json.dumps(result))
 
 

@@ -165,7 +165,7 @@ int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) {
              q.lanes_per_row, q.vecs_per_lane, q.n_regs, q.n_sregs);
     s += line;
     for (int i = 0; i < q.n_full; ++i) s += "  full " + buf_name(l.ptr[i]) + " reg " + std::to_string(q.full_reg[i]) + "\n";
-    for (int i = 0; i < q.n_col; ++i) s += "  col " + buf_name(l.ptr[4 + i]) + " reg " + std::to_string(q.col_reg[i]) + "\n";
+    for (int i = 0; i < q.n_col; ++i) s += "  col " + buf_name(l.ptr[4 + i]) + " index " + std::to_string(i) + "\n";
     for (int i = 0; i < q.n_rscal; ++i)
       s += "  rscal " + buf_name(l.ptr[8 + i]) + " sreg " + std::to_string(q.rscal_sreg[i]) + " " + dtype_name(q.rscal_dt[i]) + "\n";
     for (int i = 0; i < kProgMaxOperands; ++i)
@@ -174,7 +174,7 @@ int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) {
       if (l.ptr[16 + i].kind != BUF_NONE) s += "  routput " + std::to_string(i) + " " + buf_name(l.ptr[16 + i]) + "\n";
     static const char* op_names[] = {"add", "sub", "mul", "div", "max", "square", "exp", "rsqrt", "tanh", "gelu", "gelu_grad",
                                      "mov", "cvt", "rsum", "rmax", "store", "store_scal"};
-    static const char* kind_names[] = {"acc", "sacc", "reg", "scal", "imm"};
+    static const char* kind_names[] = {"acc", "sacc", "reg", "scal", "imm", "col"};
     for (int i = 0; i < q.n_instr; ++i) {
       const ProgInstr& in = q.instr[i];
       snprintf(line, sizeof line, "  instr %d %s a=%s:%d b=%s:%d dst=%d flags=%s%s aux=%d imm=%.9g\n", i, op_names[in.op], kind_names[in.a_kind],

@@ -6,9 +6,10 @@
 // on-chip storage by lifetime).
 //
 // Value classes, relative to the largest tensor of the pattern ([.., C], R rows):
-//   FULL  same extents                      -> per-lane vector, accumulator or LDS register
+//   FULL  same extents                      -> per-lane vector, in the accumulator or an LDS register
 //   RSCAL same leading extents, last = 1    -> per-row scalar, scalar accumulator or scalar register
-//   COL   [C] / [1,..,1,C]                  -> per-lane vector that is the same for every row
+//   COL   [C] / [1,..,1,C]                  -> the same for every row: an input sits in the workgroup's shared
+//                                              column file, an intermediate is handled like a FULL value
 // Each op's result goes to the accumulator of its shape; it is also written to a register
 // only if some reader comes after the accumulator has been overwritten (look-ahead over
 // the op list).  Registers are reused once their last reader has run.
@@ -27,6 +28,7 @@ struct Val {
   int kind = V_NONE;
   int root = -1;        // tensor whose storage this value shares (itself unless an alias)
   int reg = -1;         // register index in the file of its shape, -1 = none
+  int input_index = -1; // column input: its position in the shared column file
   int last_read = -1;   // index of the last op that reads the root
   bool keep = false;
 };
@@ -94,6 +96,11 @@ struct Compiler {
       if (v.reg < 0) return false;
       *kind = PK_SCAL;
     } else {
+      if (v.input_index >= 0) {
+        *kind = PK_COL;
+        *idx = (uint8_t)v.input_index;
+        return true;
+      }
       if (acc_holds == v.root) { *kind = PK_ACC; *idx = 0; return true; }
       if (v.reg < 0) return false;
       *kind = PK_REG;
@@ -114,8 +121,8 @@ struct Compiler {
       ++vec_instr;
     }
     if (!(ins.flags & PF_SCALAR) || ins.op == PO_RSUM || ins.op == PO_RMAX) {
-      if (ins.a_kind == PK_REG) ++reg_reads;
-      if (ins.op <= PO_MAX && ins.b_kind == PK_REG) ++reg_reads;
+      if (ins.a_kind == PK_REG || ins.a_kind == PK_COL) ++reg_reads;
+      if (ins.op <= PO_MAX && (ins.b_kind == PK_REG || ins.b_kind == PK_COL)) ++reg_reads;
       if ((ins.flags & PF_KEEP) && !(ins.op == PO_RSUM || ins.op == PO_RMAX)) ++reg_writes;
     }
     if (ins.op == PO_DIV || ins.op == PO_EXP || ins.op == PO_RSQRT) trans += (ins.flags & PF_SCALAR) ? 0 : 1;
@@ -265,7 +272,7 @@ struct Compiler {
     p.n_col = (int32_t)col_in.size();
     p.n_rscal = (int32_t)rscal_in.size();
     for (size_t i = 0; i < full_in.size(); ++i) p.full_reg[i] = (uint8_t)(val[full_in[i]].reg = alloc(false));
-    for (size_t i = 0; i < col_in.size(); ++i) p.col_reg[i] = (uint8_t)(val[col_in[i]].reg = alloc(false));
+    for (size_t i = 0; i < col_in.size(); ++i) val[col_in[i]].input_index = (int)i;
     for (size_t i = 0; i < rscal_in.size(); ++i) {
       p.rscal_sreg[i] = (uint8_t)(val[rscal_in[i]].reg = alloc(true));
       p.rscal_dt[i] = (uint8_t)g.tensors[rscal_in[i]].dtype;
@@ -375,7 +382,8 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
 
   for (const Shape& s : shapes) {
     const int kv = s.K * vec;
-    const int64_t lds = (int64_t)base.n_regs * kv * 4 * 256 + (int64_t)base.n_sregs * 1024 + kProgMaxReductions * 16;
+    const int64_t lds = (int64_t)base.n_regs * kv * 4 * 256 + (int64_t)base.n_col * base.cols * 4 +
+                        (int64_t)base.n_sregs * 1024 + kProgMaxReductions * 16;
     if (lds > kProgMaxLdsBytes) continue;
     Candidate cand;
     memset(&cand.info, 0, sizeof cand.info);
@@ -418,13 +426,13 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
     kc.elems = n;
     // per element: the op itself plus operand / result moves; per instruction and wave: ~40 scalar-side cycles of dispatch
     const double dispatch = 40.0 * base.n_instr / (64.0 * kv) / 4.0;
-    kc.valu_per_elem = 2.5 * c.vec_instr + dispatch + 2.0 * (base.n_full + base.n_col);
+    kc.valu_per_elem = 2.5 * c.vec_instr + dispatch + 2.0 * base.n_full;
     kc.trans_per_elem = c.trans;
-    kc.lds_traffic_bytes = n * 4.0 * (c.reg_reads + c.reg_writes + base.n_full + base.n_col);
+    kc.lds_traffic_bytes = n * 4.0 * (c.reg_reads + c.reg_writes + base.n_full);
     kc.waves = (double)l.shape.grid[0] * 4;
     kc.waves_per_block = 4;
     kc.bytes_in_flight_per_lane = 16.0 * s.K * std::max(1, base.n_full);
-    kc.vgpr_estimate = 40 + 3 * kv + 4 * s.K * (base.n_full + base.n_col);
+    kc.vgpr_estimate = 40 + 3 * kv + 4 * s.K * (base.n_full <= 1 ? 1 : (base.n_full <= 2 ? 2 : 4));
     int steps = 0;
     for (uint32_t t = 1; t < std::min<uint32_t>(s.L, 64); t <<= 1) ++steps;
     kc.xlane_steps = steps * c.n_reductions;

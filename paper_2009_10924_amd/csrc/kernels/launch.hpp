@@ -184,7 +184,8 @@ enum ProgKind : uint8_t {
   PK_SACC,      // the scalar accumulator: result of the latest per-row-shaped instruction
   PK_REG,       // full-shaped register a / b (LDS, private to the lane)
   PK_SCAL,      // per-row scalar register a / b
-  PK_IMM        // the instruction's immediate
+  PK_IMM,       // the instruction's immediate
+  PK_COL        // column vector a / b, from the workgroup's shared column file
 };
 enum ProgFlags : uint8_t {
   PF_SCALAR = 1,   // per-row-shaped instruction: one value per row, result to SACC
@@ -205,8 +206,8 @@ struct RowProgP {
   int32_t lanes_per_row, lanes_log2, vecs_per_lane;   // lanes_per_row > 64: one workgroup per row
   int32_t n_full, n_col, n_rscal, n_instr;
   int32_t n_regs, n_sregs;             // register files: full-shaped and per-row
-  uint8_t full_reg[kProgMaxOperands], col_reg[kProgMaxOperands], rscal_sreg[kProgMaxOperands];
-  uint8_t rscal_dt[kProgMaxOperands];
+  uint8_t full_reg[kProgMaxOperands];  // register each full-shaped input is parked in
+  uint8_t rscal_sreg[kProgMaxOperands], rscal_dt[kProgMaxOperands];
   ProgInstr instr[kProgMaxInstr];
 };
 struct ProgArgs {

@@ -6,8 +6,9 @@
 //   * a row per lane group of one wavefront (warp composition) or per workgroup (block
 //     composition), exactly like the hand-written row kernels,
 //   * every global load issued before the first instruction runs, each input read once,
-//   * full-shaped values in an accumulator (VGPRs) or a per-lane register file in LDS
-//     (a lane only ever touches its own slots, so no barrier guards them),
+//   * column vectors in an LDS file shared by the workgroup; full-shaped values in an
+//     accumulator (VGPRs) or a per-lane register file in LDS (a lane only ever touches its own
+//     slots, so no barrier guards them); inputs are parked there by the prologue,
 //   * per-row values (reduction results and what is computed from them) in a scalar
 //     accumulator or a per-lane scalar file, identical in all lanes of the row,
 //   * outputs written once, rounded at the store.
@@ -57,7 +58,8 @@ __device__ __forceinline__ float apply_op(int op, float a, float b, int aux) {
   }
 }
 
-template <typename T, int K>
+// NI: capacity for full-shaped inputs (sizes the prologue's load batch).
+template <typename T, int K, int NI>
 __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kernarg) {
   constexpr int VEC = Elem<T>::VEC;
   constexpr int KV = K * VEC;     // floats a lane holds per full-shaped value
@@ -69,8 +71,11 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
   const uint32_t rows = A->p.rows, cols = A->p.cols;
   const int n_regs = A->p.n_regs, n_sregs = A->p.n_sregs;
   const uint32_t tid = threadIdx.x;
-  f32x4* regs = lds;                                                    // [n_regs][CH][256]
-  float* sregs = reinterpret_cast<float*>(lds + (size_t)n_regs * CH * 256);   // [n_sregs][256]
+  const uint32_t nvec = cols / VEC;
+  const int n_col = A->p.n_col;
+  f32x4* regs = lds;                                                    // [n_regs][CH][256], private to the lane
+  f32x4* colfile = lds + (size_t)n_regs * CH * 256;                     // [n_col][nvec][VEC/4], shared by the workgroup
+  float* sregs = reinterpret_cast<float*>(colfile + (size_t)n_col * nvec * (VEC / 4));   // [n_sregs][256]
   float* slots = sregs + (size_t)n_sregs * 256;                         // [kProgMaxReductions][4]
 
   const bool block_mode = A->p.lanes_per_row > 64;
@@ -84,7 +89,6 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
     lane = tid & (L - 1);
     row = blockIdx.x * (256u >> A->p.lanes_log2) + (tid >> A->p.lanes_log2);
   }
-  const uint32_t nvec = cols / VEC;
   const bool row_ok = row < rows;
   const uint32_t row_c = min(row, rows - 1);
   const size_t base = (size_t)row_c * cols;
@@ -105,26 +109,28 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
     }
   };
 
-  // ---- prologue: all loads of a class are issued before any of them is parked -----------
+  // the program itself: one instruction per lane (kProgMaxInstr == 64 lanes of a wavefront)
+  const int n_instr = A->p.n_instr;
+  uint32_t iw0, iw1, iw2;
+  {
+    const uint32_t slot = min(tid & 63u, (uint32_t)max(n_instr - 1, 0));
+    const uint32_t __attribute__((address_space(4)))* w =
+        reinterpret_cast<const uint32_t __attribute__((address_space(4)))*>(&A->p.instr[slot]);
+    iw0 = w[0]; iw1 = w[1]; iw2 = w[2];
+  }
+
+  // ---- prologue: every global load is issued before anything waits ------------------------
+  // full-shaped inputs are parked in registers of the per-lane file; column vectors are unpacked
+  // once per workgroup into the shared column file; per-row scalar inputs go to the scalar file.
   {
     const int n_full = A->p.n_full;
-    u32x4 raw[kProgMaxOperands][K];
+    u32x4 raw[NI][K];
 #pragma unroll
-    for (int i = 0; i < kProgMaxOperands; ++i) {
+    for (int i = 0; i < NI; ++i) {
       if (i < n_full) {
         const T* src = static_cast<const T*>(A->full[i]) + base;
 #pragma unroll
         for (int k = 0; k < K; ++k) raw[i][k] = load_raw_nt(src + (size_t)vec_at(k) * VEC);
-      }
-    }
-    const int n_col = A->p.n_col;
-    u32x4 rawc[kProgMaxOperands][K];
-#pragma unroll
-    for (int i = 0; i < kProgMaxOperands; ++i) {
-      if (i < n_col) {
-        const T* src = static_cast<const T*>(A->col[i]);
-#pragma unroll
-        for (int k = 0; k < K; ++k) rawc[i][k] = load_raw(src + (size_t)vec_at(k) * VEC);
       }
     }
     const int n_rscal = A->p.n_rscal;
@@ -133,8 +139,24 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
     for (int i = 0; i < kProgMaxOperands; ++i) {
       if (i < n_rscal) rs[i] = load_scalar_as(A->rscal[i], row_c, A->p.rscal_dt[i]);
     }
+    for (int i = 0; i < n_col; ++i) {
+      const T* src = static_cast<const T*>(A->col[i]);
+      for (uint32_t j = tid; j < nvec; j += 256u) {
+        float part[VEC];
+        unpack(load_raw(src + (size_t)j * VEC), part, (const T*)nullptr);
+#pragma unroll
+        for (int h = 0; h < VEC / 4; ++h) {
+          const f32x4 t = {part[4 * h], part[4 * h + 1], part[4 * h + 2], part[4 * h + 3]};
+          colfile[((size_t)i * nvec + j) * (VEC / 4) + h] = t;
+        }
+      }
+    }
 #pragma unroll
     for (int i = 0; i < kProgMaxOperands; ++i) {
+      if (i < n_rscal) sregs[(size_t)A->p.rscal_sreg[i] * 256 + tid] = rs[i];
+    }
+#pragma unroll
+    for (int i = 0; i < NI; ++i) {
       if (i < n_full) {
         float v[KV];
 #pragma unroll
@@ -147,24 +169,7 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
         put(A->p.full_reg[i], v);
       }
     }
-#pragma unroll
-    for (int i = 0; i < kProgMaxOperands; ++i) {
-      if (i < n_col) {
-        float v[KV];
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-          float part[VEC];
-          unpack(rawc[i][k], part, (const T*)nullptr);
-#pragma unroll
-          for (int e = 0; e < VEC; ++e) v[k * VEC + e] = part[e];
-        }
-        put(A->p.col_reg[i], v);
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < kProgMaxOperands; ++i) {
-      if (i < n_rscal) sregs[(size_t)A->p.rscal_sreg[i] * 256 + tid] = rs[i];
-    }
+    if (n_col > 0) __syncthreads();   // n_col is uniform: every thread of the workgroup arrives
   }
 
   // ---- instruction walk -------------------------------------------------------------------
@@ -173,16 +178,16 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
   for (int j = 0; j < KV; ++j) acc[j] = 0.0f;
   float sacc = 0.0f;
   int reduction_no = 0;
-  const int n_instr = A->p.n_instr;
   for (int pc = 0; pc < n_instr; ++pc) {
-    // three uniform dword loads from the argument segment, unpacked in scalar registers
-    const uint32_t __attribute__((address_space(4)))* w =
-        reinterpret_cast<const uint32_t __attribute__((address_space(4)))*>(&A->p.instr[pc]);
-    const uint32_t w0 = w[0], w1 = w[1];
+    // lane i of every wavefront holds instruction i (loaded once, below): fetching one is three
+    // cross-lane reads into scalar registers, with no memory latency inside the walk
+    const uint32_t w0 = (uint32_t)__builtin_amdgcn_readlane((int)iw0, pc);
+    const uint32_t w1 = (uint32_t)__builtin_amdgcn_readlane((int)iw1, pc);
+    const uint32_t w2 = (uint32_t)__builtin_amdgcn_readlane((int)iw2, pc);
     ProgInstr ins;
     ins.op = w0 & 0xFF; ins.a_kind = (w0 >> 8) & 0xFF; ins.b_kind = (w0 >> 16) & 0xFF; ins.flags = w0 >> 24;
     ins.a = w1 & 0xFF; ins.b = (w1 >> 8) & 0xFF; ins.dst = (w1 >> 16) & 0xFF; ins.aux = w1 >> 24;
-    ins.imm = __builtin_bit_cast(float, w[2]);
+    ins.imm = __builtin_bit_cast(float, w2);
     auto scalar_operand = [&](int kind, int idx) {
       if (kind == PK_SACC) return sacc;
       if (kind == PK_SCAL) return sregs[(size_t)idx * 256 + tid];
@@ -194,6 +199,16 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
         for (int j = 0; j < KV; ++j) v[j] = acc[j];
       } else if (kind == PK_REG) {
         get(idx, v);
+      } else if (kind == PK_COL) {
+#pragma unroll
+        for (int k = 0; k < K; ++k) {
+          const f32x4* src = colfile + ((size_t)idx * nvec + vec_at(k)) * (VEC / 4);
+#pragma unroll
+          for (int h = 0; h < VEC / 4; ++h) {
+            const f32x4 t = src[h];
+            v[k * VEC + 4 * h] = t.x; v[k * VEC + 4 * h + 1] = t.y; v[k * VEC + 4 * h + 2] = t.z; v[k * VEC + 4 * h + 3] = t.w;
+          }
+        }
       } else {
         const float s = scalar_operand(kind, idx);
 #pragma unroll
@@ -283,23 +298,30 @@ namespace fs {
 using namespace fsk;
 
 namespace {
-template <typename T>
-const void* prog_sym(int K) {
+template <typename T, int NI>
+const void* prog_sym_k(int K) {
   switch (K) {
-    case 1: return (const void*)k_row_program<T, 1>;
-    case 2: return (const void*)k_row_program<T, 2>;
-    case 4: return (const void*)k_row_program<T, 4>;
+    case 1: return (const void*)k_row_program<T, 1, NI>;
+    case 2: return (const void*)k_row_program<T, 2, NI>;
+    case 4: return (const void*)k_row_program<T, 4, NI>;
     default: return nullptr;
   }
+}
+template <typename T>
+const void* prog_sym(int K, int n_full) {
+  if (n_full <= 1) return prog_sym_k<T, 1>(K);
+  if (n_full <= 2) return prog_sym_k<T, 2>(K);
+  return prog_sym_k<T, 4>(K);
 }
 }  // namespace
 
 const void* rowprog_kernel_symbol(int32_t, const KernelArgs& a) {
   const RowProgP& p = a.u.prog;
+  if (p.n_full < 0 || p.n_full > kProgMaxOperands) return nullptr;
   switch (p.dt) {
-    case DT_F32: return prog_sym<float>(p.vecs_per_lane);
-    case DT_F16: return prog_sym<f16_t>(p.vecs_per_lane);
-    case DT_BF16: return prog_sym<bf16_t>(p.vecs_per_lane);
+    case DT_F32: return prog_sym<float>(p.vecs_per_lane, p.n_full);
+    case DT_F16: return prog_sym<f16_t>(p.vecs_per_lane, p.n_full);
+    case DT_BF16: return prog_sym<bf16_t>(p.vecs_per_lane, p.n_full);
     default: return nullptr;
   }
 }

@@ -38,7 +38,7 @@ def emulate(listing, spec, inputs):
     kv = dict(x.split("=") for x in head[1:])
     rows, cols = int(kv["rows"]), int(kv["cols"])
     in_arrays = [O.to_f64(inputs[t.name], t.dtype).astype(np.float32) for t in spec.inputs]
-    regs, sregs, outs = {}, {}, {}
+    regs, sregs, outs, colvecs = {}, {}, {}, {}
     out_bind, rout_bind = {}, {}
     for l in lines:
         if not l:
@@ -46,7 +46,7 @@ def emulate(listing, spec, inputs):
         if l[0] == "full":
             regs[int(l[3])] = in_arrays[int(l[1][2:])].reshape(rows, cols)
         elif l[0] == "col":
-            regs[int(l[3])] = np.broadcast_to(in_arrays[int(l[1][2:])].reshape(1, cols), (rows, cols))
+            colvecs[int(l[3])] = np.broadcast_to(in_arrays[int(l[1][2:])].reshape(1, cols), (rows, cols))
         elif l[0] == "rscal":
             sregs[int(l[3])] = in_arrays[int(l[1][2:])].reshape(rows, 1)
         elif l[0] == "output":
@@ -77,6 +77,8 @@ def emulate(listing, spec, inputs):
                 return regs[int(idx)]
             if kind == "scal":
                 return sregs[int(idx)]
+            if kind == "col":
+                return colvecs[int(idx)]
             return np.full((1, 1), imm, np.float32)
         a = operand(f["a"])
         dst = int(f["dst"])
@@ -149,7 +151,7 @@ def test_layernorm_program_keeps_only_what_is_read_again():
     # centred row (read again after the variance reduction chain) is written to a register
     assert len(kept) == 1 and kept[0][2] == "sub"
     head = [l for l in plan.describe().splitlines() if l.strip().startswith("program ")][0]
-    assert "regs=5" in head and "sregs=0" in head       # 2 full inputs + 3 column vectors, the centred row reuses x's slot
+    assert "regs=2" in head and "sregs=0" in head       # x and res; the centred row reuses a slot; column vectors live in the shared file
 
 
 @pytest.mark.parametrize("seed", range(60))

@@ -433,6 +433,14 @@ def pack_members_p1() -> List[GraphSpec]:
 
 PACK_CONFIGS = {"P1": pack_members_p1}
 
+# Row-local patterns outside the hand-written families, at transformer-block sizes (interpreted row program).
+GENERIC_CONFIGS = {
+    "G1": lambda: layernorm_stats_graph(8192, 768),                          # C2 plus saved mean / rstd outputs
+    "G2": lambda: silu_gate_graph(8192, 4096, "bf16"),
+    "G3": lambda: scaled_softmax_colbias_graph(32 * 12 * 128, 128, "f32"),
+    "G4": lambda: normalize_from_stats_graph(8192, 1024, "f16"),
+}
+
 FULL_CONFIGS = {
     "C1": lambda: softmax_graph(64, 128, "f32"),
     "C2": lambda: add_bias_layernorm_graph(8192, 768),
