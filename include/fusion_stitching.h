@@ -175,8 +175,10 @@ fs_status fs_plan_candidate(const fs_plan *p, int32_t index, fs_plan_info *out);
  * line per launch (kernel, grid, block, dynamic LDS) and per buffer binding; for a
  * pattern that runs as an interpreted row program (the generic path for patterns no
  * hand-written kernel covers, Section 4.2) also its register files and one line per
- * instruction: `instr <n> <op> a=<kind>:<index> b=<kind>:<index> dst=<index>
- * flags=<v|s><k|-> aux=<dtype> imm=<value>`.  Errors: FS_ERR_INVALID_ARG.              */
+ * instruction of its accumulator machine: `instr <n> <op> b=<kind>:<index> dst=<index>
+ * flags=<v|s><k|-> aux=<dtype> imm=<value>` (v: acc <- acc op b on full-shaped values,
+ * s: the same on per-row values; k: result also kept in register dst).
+ * Errors: FS_ERR_INVALID_ARG.                                                          */
 int64_t fs_plan_describe(const fs_plan *p, char *text, size_t capacity);
 
 /* ---- execution (the run-time hot path) --------------------------------------- */

@@ -164,7 +164,8 @@ int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) {
     snprintf(line, sizeof line, "  program dt=%s rows=%u cols=%u lanes=%d vecs=%d regs=%d sregs=%d\n", dtype_name(q.dt), q.rows, q.cols,
              q.lanes_per_row, q.vecs_per_lane, q.n_regs, q.n_sregs);
     s += line;
-    for (int i = 0; i < q.n_full; ++i) s += "  full " + buf_name(l.ptr[i]) + " reg " + std::to_string(q.full_reg[i]) + "\n";
+    for (int i = 0; i < q.n_full; ++i)
+      s += "  full " + buf_name(l.ptr[i]) + " reg " + std::to_string(q.full_reg[i]) + (q.acc_input == i ? " acc" : "") + "\n";
     for (int i = 0; i < q.n_col; ++i) s += "  col " + buf_name(l.ptr[4 + i]) + " index " + std::to_string(i) + "\n";
     for (int i = 0; i < q.n_rscal; ++i)
       s += "  rscal " + buf_name(l.ptr[8 + i]) + " sreg " + std::to_string(q.rscal_sreg[i]) + " " + dtype_name(q.rscal_dt[i]) + "\n";
@@ -172,14 +173,13 @@ int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) {
       if (l.ptr[12 + i].kind != BUF_NONE) s += "  output " + std::to_string(i) + " " + buf_name(l.ptr[12 + i]) + "\n";
     for (int i = 0; i < kProgMaxOperands; ++i)
       if (l.ptr[16 + i].kind != BUF_NONE) s += "  routput " + std::to_string(i) + " " + buf_name(l.ptr[16 + i]) + "\n";
-    static const char* op_names[] = {"add", "sub", "mul", "div", "max", "square", "exp", "rsqrt", "tanh", "gelu", "gelu_grad",
-                                     "mov", "cvt", "rsum", "rmax", "store", "store_scal"};
+    static const char* op_names[] = {"add", "sub", "rsub", "mul", "div", "rdiv", "max", "square", "exp", "rsqrt", "tanh", "gelu",
+                                     "gelu_grad", "cvt", "load", "rsum", "rmax", "rsumsq", "store", "store_scal"};
     static const char* kind_names[] = {"acc", "sacc", "reg", "scal", "imm", "col"};
     for (int i = 0; i < q.n_instr; ++i) {
       const ProgInstr& in = q.instr[i];
-      snprintf(line, sizeof line, "  instr %d %s a=%s:%d b=%s:%d dst=%d flags=%s%s aux=%d imm=%.9g\n", i, op_names[in.op], kind_names[in.a_kind],
-               in.a, kind_names[in.b_kind], in.b, in.dst, (in.flags & PF_SCALAR) ? "s" : "v", (in.flags & PF_KEEP) ? "k" : "-", in.aux,
-               (double)in.imm);
+      snprintf(line, sizeof line, "  instr %d %s b=%s:%d dst=%d flags=%s%s aux=%d imm=%.9g\n", i, op_names[in.op], kind_names[in.b_kind],
+               in.b, in.dst, (in.flags & PF_SCALAR) ? "s" : "v", (in.flags & PF_KEEP) ? "k" : "-", in.aux, (double)in.imm);
       s += line;
     }
   }

@@ -10,9 +10,10 @@
 //   RSCAL same leading extents, last = 1    -> per-row scalar, scalar accumulator or scalar register
 //   COL   [C] / [1,..,1,C]                  -> the same for every row: an input sits in the workgroup's shared
 //                                              column file, an intermediate is handled like a FULL value
-// Each op's result goes to the accumulator of its shape; it is also written to a register
-// only if some reader comes after the accumulator has been overwritten (look-ahead over
-// the op list).  Registers are reused once their last reader has run.
+// The kernel is an accumulator machine: every instruction works on the accumulator of its shape
+// (acc <- acc (op) b).  A first walk over the ops follows what the accumulators hold and marks
+// the values that some reader finds overwritten; only those are also written to a register
+// (PF_KEEP).  A second walk allocates registers by lifetime and emits.
 #include <algorithm>
 #include <cmath>
 #include <cstring>
@@ -30,7 +31,7 @@ struct Val {
   int reg = -1;         // register index in the file of its shape, -1 = none
   int input_index = -1; // column input: its position in the shared column file
   int last_read = -1;   // index of the last op that reads the root
-  bool keep = false;
+  bool keep = false;    // some reader finds the accumulator overwritten: the value needs a register
 };
 
 struct Compiler {
@@ -45,7 +46,8 @@ struct Compiler {
   int n_out = 0, n_rout = 0, n_reductions = 0;
   int vec_instr = 0, scal_instr = 0, reg_reads = 0, reg_writes = 0, trans = 0;
   std::vector<int> free_regs, free_sregs;
-  int acc_holds = -1, sacc_holds = -1;
+  int acc_holds = -1, sacc_holds = -1;   // roots
+  bool planning = true;                  // first pass: only follow the accumulators and note who needs a register
 
   explicit Compiler(const fs_graph& graph) : g(graph), val(graph.tensors.size()) {}
 
@@ -68,14 +70,14 @@ struct Compiler {
     return V_NONE;
   }
 
-  bool is_scalar_shaped(int kind) const { return kind == V_RSCAL; }
+  static bool scalar_shaped(int kind) { return kind == V_RSCAL; }
+  int root_of(int tensor) const { return val[tensor].root; }
 
   int alloc(bool scalar) {
     std::vector<int>& fl = scalar ? free_sregs : free_regs;
     int32_t& n = scalar ? p.n_sregs : p.n_regs;
     if (!fl.empty()) {
-      // lowest index first keeps the files dense
-      auto it = std::min_element(fl.begin(), fl.end());
+      auto it = std::min_element(fl.begin(), fl.end());   // lowest index first keeps the files dense
       const int r = *it;
       fl.erase(it);
       return r;
@@ -84,73 +86,183 @@ struct Compiler {
   }
   void release(int root) {
     Val& v = val[root];
-    if (v.reg < 0) return;
-    (is_scalar_shaped(v.kind) ? free_sregs : free_regs).push_back(v.reg);
+    if (v.reg < 0 || v.input_index >= 0) return;
+    (scalar_shaped(v.kind) ? free_sregs : free_regs).push_back(v.reg);
     v.reg = -1;
   }
 
-  bool operand(int tensor, uint8_t* kind, uint8_t* idx) const {
-    const Val& v = val[val[tensor].root];
-    if (is_scalar_shaped(v.kind)) {
-      if (sacc_holds == v.root) { *kind = PK_SACC; *idx = 0; return true; }
-      if (v.reg < 0) return false;
-      *kind = PK_SCAL;
+  // ---- emission ------------------------------------------------------------------------------
+  bool push(ProgInstr ins) {
+    if (planning) return true;
+    if (p.n_instr >= kProgMaxInstr) return false;
+    p.instr[p.n_instr++] = ins;
+    const bool red = ins.op == PO_RSUM || ins.op == PO_RMAX || ins.op == PO_RSUMSQ;
+    if (red) ++n_reductions;
+    if (red || (ins.flags & PF_SCALAR) || ins.op == PO_STORE_SCAL) {
+      ++scal_instr;
     } else {
-      if (v.input_index >= 0) {
-        *kind = PK_COL;
-        *idx = (uint8_t)v.input_index;
-        return true;
-      }
-      if (acc_holds == v.root) { *kind = PK_ACC; *idx = 0; return true; }
-      if (v.reg < 0) return false;
-      *kind = PK_REG;
+      ++vec_instr;
+      if (ins.op != PO_STORE && (ins.b_kind == PK_REG || ins.b_kind == PK_COL) &&
+          (ins.op <= PO_MAX || ins.op == PO_LOAD)) ++reg_reads;
+      if (ins.flags & PF_KEEP) ++reg_writes;
+      if (ins.op == PO_DIV || ins.op == PO_RDIV || ins.op == PO_EXP || ins.op == PO_RSQRT) trans += 1;
+      if (ins.op == PO_TANH || ins.op == PO_GELU || ins.op == PO_GELU_GRAD) trans += 2;
     }
+    return true;
+  }
+
+  // operand b of an instruction: where root r can be read from, other than "it is the accumulator of
+  // its own shape" (that case is PK_ACC / PK_SACC).  In the planning pass a value that is in no
+  // accumulator is marked as needing a register.
+  bool locate(int r, uint8_t* kind, uint8_t* idx) {
+    Val& v = val[r];
+    const bool scalar = scalar_shaped(v.kind);
+    if (!scalar && v.input_index >= 0) { *kind = PK_COL; *idx = (uint8_t)v.input_index; return true; }
+    if (scalar ? sacc_holds == r : acc_holds == r) { *kind = scalar ? PK_SACC : PK_ACC; *idx = 0; return true; }
+    if (planning) { v.keep = true; *kind = scalar ? PK_SCAL : PK_REG; *idx = 0; return true; }
+    if (v.reg < 0) return false;
+    *kind = scalar ? PK_SCAL : PK_REG;
     *idx = (uint8_t)v.reg;
     return true;
   }
 
-  bool emit(const ProgInstr& ins) {
-    if (p.n_instr >= kProgMaxInstr) return false;
-    p.instr[p.n_instr++] = ins;
-    if (ins.op == PO_RSUM || ins.op == PO_RMAX) {
-      ++n_reductions;
-      ++scal_instr;
-    } else if (ins.flags & PF_SCALAR) {
-      ++scal_instr;
-    } else {
-      ++vec_instr;
-    }
-    if (!(ins.flags & PF_SCALAR) || ins.op == PO_RSUM || ins.op == PO_RMAX) {
-      if (ins.a_kind == PK_REG || ins.a_kind == PK_COL) ++reg_reads;
-      if (ins.op <= PO_MAX && (ins.b_kind == PK_REG || ins.b_kind == PK_COL)) ++reg_reads;
-      if ((ins.flags & PF_KEEP) && !(ins.op == PO_RSUM || ins.op == PO_RMAX)) ++reg_writes;
-    }
-    if (ins.op == PO_DIV || ins.op == PO_EXP || ins.op == PO_RSQRT) trans += (ins.flags & PF_SCALAR) ? 0 : 1;
-    if (ins.op == PO_TANH || ins.op == PO_GELU || ins.op == PO_GELU_GRAD) trans += (ins.flags & PF_SCALAR) ? 0 : 2;
+  // brings root r into the accumulator of the given shape (full-shaped accumulator may also take a
+  // per-row or column value: it is stretched on the way)
+  bool load(int r, bool into_scalar) {
+    if (into_scalar ? sacc_holds == r : acc_holds == r) return true;
+    ProgInstr ld{};
+    ld.op = PO_LOAD;
+    if (into_scalar) ld.flags = PF_SCALAR;
+    if (!locate(r, &ld.b_kind, &ld.b)) return false;
+    if (!push(ld)) return false;
+    (into_scalar ? sacc_holds : acc_holds) = r;
     return true;
   }
 
-  // store of output tensor t (already defined) right now
-  bool emit_store(int t) {
+  bool store_output(int t, bool as_full) {
     const Tensor& T = g.tensors[t];
+    const int r = root_of(t);
     ProgInstr s{};
-    if (!operand(t, &s.a_kind, &s.a)) return false;
     s.aux = (uint8_t)T.store_as;
-    if (val[t].kind == V_RSCAL) {
-      if (n_rout >= kProgMaxOperands) return false;
+    if (as_full) {
+      if (!planning && n_out >= kProgMaxOperands) return false;
+      if (!load(r, false)) return false;
+      s.op = PO_STORE;
+      if (!planning) { s.dst = (uint8_t)n_out; out_slot[n_out++] = T.output_slot; }
+    } else {
+      if (!planning && n_rout >= kProgMaxOperands) return false;
+      if (!load(r, true)) return false;
       s.op = PO_STORE_SCAL;
       s.flags = PF_SCALAR;
-      s.dst = (uint8_t)n_rout;
-      rout_slot[n_rout++] = T.output_slot;
-    } else if (val[t].kind == V_FULL) {
-      if (n_out >= kProgMaxOperands) return false;
-      s.op = PO_STORE;
-      s.dst = (uint8_t)n_out;
-      out_slot[n_out++] = T.output_slot;
-    } else {
-      return false;   // a column-shaped output would be written by every row
+      if (!planning) { s.dst = (uint8_t)n_rout; rout_slot[n_rout++] = T.output_slot; }
     }
-    return emit(s);
+    return push(s);
+  }
+
+  std::vector<std::vector<int>> reads;
+  std::vector<char> is_alias;
+  std::vector<int> square_of;   // op j reduces the square of this root (the squaring op itself emits nothing), else -1
+  std::vector<char> folded;     // op emits nothing: its work is done by a later instruction
+
+  // One walk over the ops.  planning = true: follow the accumulators, mark values that are read
+  // when no accumulator holds them.  planning = false: allocate registers and emit.
+  int acc_start = -1;   // full-shaped input the accumulator holds when the walk begins
+
+  bool walk() {
+    acc_holds = acc_start;
+    sacc_holds = -1;
+    const size_t n_ops = g.ops.size();
+    for (size_t i = 0; i < n_ops; ++i) {
+      const Op& op = g.ops[i];
+      const Tensor& out = g.tensors[op.out];
+      if (folded[i]) continue;
+      if (is_alias[i]) {
+        if (out.output_slot >= 0) {
+          const bool as_full = op.opcode == FS_BROADCAST || val[op.out].kind != V_RSCAL;
+          if (!store_output(op.out, as_full)) return false;
+        }
+      } else {
+        const int ra = square_of[i] >= 0 ? square_of[i] : root_of(op.in[0]), rb = op.n_in > 1 ? root_of(op.in[1]) : -1;
+        const bool scalar = scalar_shaped(val[op.out].kind);
+        const bool reduce = op.opcode == FS_REDUCE_SUM || op.opcode == FS_REDUCE_MAX || op.opcode == FS_REDUCE_MEAN;
+        ProgInstr ins{};
+        ins.b_kind = PK_IMM;
+        if (scalar && !reduce) ins.flags |= PF_SCALAR;
+        int& holds = (scalar && !reduce) ? sacc_holds : acc_holds;   // accumulator the operand(s) go through
+        uint8_t fwd = PO_ADD, rev = PO_ADD;
+        bool binary = false;
+        switch (op.opcode) {
+          case FS_ADD: fwd = rev = PO_ADD; binary = true; break;
+          case FS_MUL: fwd = rev = PO_MUL; binary = true; break;
+          case FS_MAX: fwd = rev = PO_MAX; binary = true; break;
+          case FS_SUB: fwd = PO_SUB; rev = PO_RSUB; binary = true; break;
+          case FS_DIV: fwd = PO_DIV; rev = PO_RDIV; binary = true; break;
+          case FS_SCALE: ins.op = PO_MUL; ins.imm = (float)op.scalar; break;
+          case FS_ADD_SCALAR: ins.op = PO_ADD; ins.imm = (float)op.scalar; break;
+          case FS_SQUARE: ins.op = PO_SQUARE; break;
+          case FS_EXP: ins.op = PO_EXP; break;
+          case FS_RSQRT: ins.op = PO_RSQRT; break;
+          case FS_TANH: ins.op = PO_TANH; break;
+          case FS_GELU_TANH: ins.op = PO_GELU; break;
+          case FS_GELU_TANH_GRAD: ins.op = PO_GELU_GRAD; break;
+          case FS_CONVERT: ins.op = PO_CVT; ins.aux = (uint8_t)op.to_dtype; break;
+          case FS_REDUCE_SUM: case FS_REDUCE_MEAN: ins.op = square_of[i] >= 0 ? PO_RSUMSQ : PO_RSUM; break;
+          case FS_REDUCE_MAX: ins.op = PO_RMAX; break;
+          default: return false;
+        }
+        if (binary) {
+          // the operand already in the accumulator stays there; the other one is b
+          if (holds == ra) {
+            ins.op = fwd;
+            if (!locate(rb, &ins.b_kind, &ins.b)) return false;
+          } else if (holds == rb) {
+            ins.op = rev;
+            if (!locate(ra, &ins.b_kind, &ins.b)) return false;
+          } else {
+            // neither: bring in the one that can only be read through a register, keep the cheaper source as b
+            const bool a_first = !(scalar_shaped(val[ra].kind) && !scalar);   // a per-row value stretches for free as b
+            const int first = a_first ? ra : rb, second = a_first ? rb : ra;
+            if (!load(first, scalar)) return false;
+            ins.op = a_first ? fwd : rev;
+            if (!locate(second, &ins.b_kind, &ins.b)) return false;
+          }
+        } else {
+          if (!load(ra, scalar && !reduce)) return false;
+        }
+        // registers of operands read here for the last time are free for the result
+        if (!planning)
+          for (int r : reads[i])
+            if (val[r].last_read == (int)i) release(r);
+        Val& res = val[op.out];
+        const bool mean = op.opcode == FS_REDUCE_MEAN;
+        if (!planning && res.keep && !mean) {
+          res.reg = alloc(scalar);
+          ins.flags |= PF_KEEP;
+          ins.dst = (uint8_t)res.reg;
+        }
+        if (!push(ins)) return false;
+        if (mean) {
+          ProgInstr m{};
+          m.op = PO_MUL;
+          m.flags = PF_SCALAR;
+          m.b_kind = PK_IMM;
+          m.imm = (float)(1.0 / (double)cols);
+          if (!planning && res.keep) {
+            res.reg = alloc(true);
+            m.flags |= PF_KEEP;
+            m.dst = (uint8_t)res.reg;
+          }
+          if (!push(m)) return false;
+        }
+        (scalar ? sacc_holds : acc_holds) = op.out;
+        if (out.output_slot >= 0 && !store_output(op.out, !scalar)) return false;
+      }
+      if (!planning && is_alias[i])
+        for (int r : reads[i])
+          if (val[r].last_read == (int)i) release(r);
+      if (p.n_regs > 250 || p.n_sregs > 250) return false;
+    }
+    return true;
   }
 
   bool run() {
@@ -197,8 +309,8 @@ struct Compiler {
 
     // aliases and result classes; which ops read which roots
     const size_t n_ops = g.ops.size();
-    std::vector<std::vector<int>> reads(n_ops);
-    std::vector<char> emits_vec(n_ops, 0), emits_scal(n_ops, 0), is_alias(n_ops, 0);
+    reads.assign(n_ops, {});
+    is_alias.assign(n_ops, 0);
     for (size_t i = 0; i < n_ops; ++i) {
       const Op& op = g.ops[i];
       const Tensor& out = g.tensors[op.out];
@@ -214,7 +326,6 @@ struct Compiler {
           want = ka;
           break;
         case FS_BROADCAST:
-          want = val[op.out].kind;   // whatever the stretched extents are, the storage is the source's
           is_alias[i] = 1;
           break;
         case FS_REDUCE_SUM: case FS_REDUCE_MAX: case FS_REDUCE_MEAN: {
@@ -230,130 +341,87 @@ struct Compiler {
       }
       if (is_alias[i]) {
         if (op.opcode == FS_BROADCAST) {
-          // stretching may only go toward the pattern's row space
+          // stretching may only go toward the pattern's row space; the result keeps the source's class
+          // (readers stretch it on the fly)
           if (val[op.out].kind != V_FULL && val[op.out].kind != ka) return false;
-          val[op.out].kind = ka;          // keeps the source's class: readers broadcast it on the fly
+          if (out.output_slot >= 0 && classify(out) != V_FULL) return false;
+          val[op.out].kind = ka;
         }
         val[op.out].root = val[op.in[0]].root;
+        if (out.output_slot >= 0) reads[i].push_back(val[op.out].root);   // its store reads the root
       } else {
         if (val[op.out].kind != want) return false;
         reads[i].push_back(val[op.in[0]].root);
         if (op.n_in > 1) reads[i].push_back(val[op.in[1]].root);
-        if (want == V_RSCAL) emits_scal[i] = 1;
-        else emits_vec[i] = 1;
-      }
-      if (is_alias[i] && out.output_slot >= 0) reads[i].push_back(val[op.out].root);   // its store reads the root
-    }
-    // a broadcast result that is a graph output must be stored with full extents
-    for (int t : g.outputs) {
-      const Tensor& T = g.tensors[t];
-      if (T.producer < 0) return false;
-      if (g.ops[T.producer].opcode == FS_BROADCAST) {
-        if (classify(T) != V_FULL) return false;
       }
     }
-
+    for (int t : g.outputs)
+      if (g.tensors[t].producer < 0) return false;
+    // peepholes.  (1) square feeding only a row sum / mean: the reduction squares on the fly, so the
+    // accumulator keeps the un-squared value.  (2) a convert whose only reader is the store of the same
+    // dtype: the store rounds anyway.
+    std::vector<int> n_reads(g.tensors.size(), 0);
+    for (size_t i = 0; i < n_ops; ++i)
+      for (int r : reads[i]) ++n_reads[r];
+    square_of.assign(n_ops, -1);
+    folded.assign(n_ops, 0);
+    for (size_t i = 0; i + 1 < n_ops; ++i) {
+      const Op& op = g.ops[i];
+      if (op.opcode != FS_SQUARE || is_alias[i] || val[op.out].kind != V_FULL) continue;
+      if (g.tensors[op.out].output_slot >= 0 || n_reads[op.out] != 1) continue;
+      size_t j = i + 1;
+      while (j < n_ops && (is_alias[j] && reads[j].empty())) ++j;
+      if (j >= n_ops || is_alias[j]) continue;
+      const Op& red = g.ops[j];
+      if ((red.opcode != FS_REDUCE_SUM && red.opcode != FS_REDUCE_MEAN) || val[red.in[0]].root != op.out) continue;
+      folded[i] = 1;
+      square_of[j] = val[op.in[0]].root;
+      reads[i].clear();
+      reads[j].assign(1, square_of[j]);
+    }
+    for (size_t i = 0; i < n_ops; ++i) {
+      const Op& op = g.ops[i];
+      const Tensor& out = g.tensors[op.out];
+      if (op.opcode != FS_CONVERT || is_alias[i] || val[op.out].kind != V_FULL) continue;
+      if (out.output_slot < 0 || n_reads[op.out] != 0 || out.store_as != op.to_dtype) continue;
+      is_alias[i] = 1;
+      val[op.out].root = val[op.in[0]].root;
+      reads[i].assign(1, val[op.out].root);
+    }
     for (size_t i = 0; i < n_ops; ++i)
       for (int r : reads[i]) val[r].last_read = (int)i;
-    // look-ahead: a result needs a register if a reader comes after its accumulator was overwritten
-    for (size_t i = 0; i < n_ops; ++i) {
-      if (is_alias[i]) continue;
-      const int r = g.ops[i].out;
-      const bool scalar = is_scalar_shaped(val[r].kind);
-      bool held = true;
-      for (size_t j = i + 1; j < n_ops && !val[r].keep; ++j) {
-        if (std::find(reads[j].begin(), reads[j].end(), r) != reads[j].end() && !held) val[r].keep = true;
-        if (scalar ? emits_scal[j] : emits_vec[j]) held = false;
-      }
-    }
 
-    // park the inputs
+    // inputs: column vectors sit in the shared column file, the others are parked in registers
     p.n_full = (int32_t)full_in.size();
     p.n_col = (int32_t)col_in.size();
     p.n_rscal = (int32_t)rscal_in.size();
-    for (size_t i = 0; i < full_in.size(); ++i) p.full_reg[i] = (uint8_t)(val[full_in[i]].reg = alloc(false));
     for (size_t i = 0; i < col_in.size(); ++i) val[col_in[i]].input_index = (int)i;
+
+    // the first op's full-shaped input operand is handed over in the accumulator by the prologue;
+    // it is parked in a register as well only if something reads it after the accumulator moved on
+    p.acc_input = -1;
+    for (size_t i = 0; i < n_ops && acc_start < 0; ++i) {
+      if (reads[i].empty()) continue;
+      for (int r : reads[i])
+        if (acc_start < 0 && val[r].kind == V_FULL && g.tensors[r].producer < 0) acc_start = r;
+      break;
+    }
+    planning = true;
+    if (!walk()) return false;
+    planning = false;
+    for (size_t i = 0; i < full_in.size(); ++i) {
+      const int t = full_in[i];
+      if (t == acc_start) p.acc_input = (int32_t)i;
+      if (t == acc_start && !val[t].keep) { p.full_reg[i] = 255; continue; }
+      p.full_reg[i] = (uint8_t)(val[t].reg = alloc(false));
+    }
     for (size_t i = 0; i < rscal_in.size(); ++i) {
       p.rscal_sreg[i] = (uint8_t)(val[rscal_in[i]].reg = alloc(true));
       p.rscal_dt[i] = (uint8_t)g.tensors[rscal_in[i]].dtype;
     }
     for (int t : g.inputs)
       if (val[t].last_read < 0) release(t);   // declared but unread
-
-    // emit
-    for (size_t i = 0; i < n_ops; ++i) {
-      const Op& op = g.ops[i];
-      const Tensor& out = g.tensors[op.out];
-      if (is_alias[i]) {
-        if (out.output_slot >= 0) {
-          // stored with the full extents of the output: a per-row or per-column source is stretched by the store
-          const int saved = val[op.out].kind;
-          if (op.opcode == FS_BROADCAST) val[op.out].kind = V_FULL;
-          const bool ok = emit_store(op.out);
-          val[op.out].kind = saved;
-          if (!ok) return false;
-        }
-      } else {
-        ProgInstr ins{};
-        ins.b_kind = PK_IMM;
-        if (!operand(op.in[0], &ins.a_kind, &ins.a)) return false;
-        if (op.n_in > 1 && !operand(op.in[1], &ins.b_kind, &ins.b)) return false;
-        const bool scalar = is_scalar_shaped(val[op.out].kind);
-        if (scalar) ins.flags |= PF_SCALAR;
-        bool mean = false;
-        switch (op.opcode) {
-          case FS_ADD: ins.op = PO_ADD; break;
-          case FS_SUB: ins.op = PO_SUB; break;
-          case FS_MUL: ins.op = PO_MUL; break;
-          case FS_DIV: ins.op = PO_DIV; break;
-          case FS_MAX: ins.op = PO_MAX; break;
-          case FS_SCALE: ins.op = PO_MUL; ins.imm = (float)op.scalar; break;
-          case FS_ADD_SCALAR: ins.op = PO_ADD; ins.imm = (float)op.scalar; break;
-          case FS_SQUARE: ins.op = PO_SQUARE; break;
-          case FS_EXP: ins.op = PO_EXP; break;
-          case FS_RSQRT: ins.op = PO_RSQRT; break;
-          case FS_TANH: ins.op = PO_TANH; break;
-          case FS_GELU_TANH: ins.op = PO_GELU; break;
-          case FS_GELU_TANH_GRAD: ins.op = PO_GELU_GRAD; break;
-          case FS_CONVERT: ins.op = PO_CVT; ins.aux = (uint8_t)op.to_dtype; break;
-          case FS_REDUCE_SUM: ins.op = PO_RSUM; break;
-          case FS_REDUCE_MAX: ins.op = PO_RMAX; break;
-          case FS_REDUCE_MEAN: ins.op = PO_RSUM; mean = true; break;
-          default: return false;
-        }
-        // operands read for the last time give their registers back before the result takes one
-        for (int r : reads[i])
-          if (val[r].last_read == (int)i) release(r);
-        Val& res = val[op.out];
-        if (res.keep && !mean) {
-          res.reg = alloc(scalar);
-          ins.flags |= PF_KEEP;
-          ins.dst = (uint8_t)res.reg;
-        }
-        if (!emit(ins)) return false;
-        if (mean) {
-          ProgInstr m{};
-          m.op = PO_MUL;
-          m.flags = PF_SCALAR;
-          m.a_kind = PK_SACC;
-          m.b_kind = PK_IMM;
-          m.imm = (float)(1.0 / (double)cols);
-          if (res.keep) {
-            res.reg = alloc(true);
-            m.flags |= PF_KEEP;
-            m.dst = (uint8_t)res.reg;
-          }
-          if (!emit(m)) return false;
-        }
-        if (scalar) sacc_holds = op.out;
-        else acc_holds = op.out;
-        if (out.output_slot >= 0 && !emit_store(op.out)) return false;
-      }
-      if (is_alias[i])
-        for (int r : reads[i])
-          if (val[r].last_read == (int)i) release(r);
-      if (p.n_regs > 250 || p.n_sregs > 250) return false;
-    }
+    if (!walk()) return false;
     return n_out + n_rout == (int)g.outputs.size();
   }
 };

@@ -172,28 +172,30 @@ struct PackTable {
 // live in a per-lane register file in LDS plus an accumulator in VGPRs, and the kernel
 // walks a short instruction list carried in its arguments.
 enum ProgOp : uint8_t {
-  PO_ADD = 0, PO_SUB, PO_MUL, PO_DIV, PO_MAX,            // a (op) b
-  PO_SQUARE, PO_EXP, PO_RSQRT, PO_TANH, PO_GELU, PO_GELU_GRAD, PO_MOV,   // (op) a
-  PO_CVT,                                                 // a rounded through storage dtype `aux`
-  PO_RSUM, PO_RMAX,                                       // row reduction of a -> per-row scalar
-  PO_STORE,                                               // a -> full output `dst`, stored as dtype `aux`
-  PO_STORE_SCAL                                           // per-row scalar a -> per-row output `dst`, dtype `aux`
+  PO_ADD = 0, PO_SUB, PO_RSUB, PO_MUL, PO_DIV, PO_RDIV, PO_MAX,   // acc (op) b;  RSUB = b - acc, RDIV = b / acc
+  PO_SQUARE, PO_EXP, PO_RSQRT, PO_TANH, PO_GELU, PO_GELU_GRAD,    // (op) acc
+  PO_CVT,                                                 // acc rounded through storage dtype `aux`
+  PO_LOAD,                                                // acc <- b
+  PO_RSUM, PO_RMAX, PO_RSUMSQ,                            // row reduction of acc (RSUMSQ: of acc squared) -> sacc
+  PO_STORE,                                               // acc -> full output `dst`, stored as dtype `aux`
+  PO_STORE_SCAL                                           // sacc -> per-row output `dst`, dtype `aux`
 };
+// where operand b comes from
 enum ProgKind : uint8_t {
-  PK_ACC = 0,   // the accumulator: result of the latest full-shaped instruction
-  PK_SACC,      // the scalar accumulator: result of the latest per-row-shaped instruction
-  PK_REG,       // full-shaped register a / b (LDS, private to the lane)
-  PK_SCAL,      // per-row scalar register a / b
+  PK_ACC = 0,   // the accumulator itself (x (op) x)
+  PK_SACC,      // the scalar accumulator
+  PK_REG,       // full-shaped register (LDS, private to the lane)
+  PK_SCAL,      // per-row scalar register
   PK_IMM,       // the instruction's immediate
-  PK_COL        // column vector a / b, from the workgroup's shared column file
+  PK_COL        // column vector, from the workgroup's shared column file
 };
 enum ProgFlags : uint8_t {
-  PF_SCALAR = 1,   // per-row-shaped instruction: one value per row, result to SACC
+  PF_SCALAR = 1,   // per-row-shaped instruction: works on sacc
   PF_KEEP = 2      // also write the result to register `dst` (full or scalar file by shape)
 };
 struct ProgInstr {
-  uint8_t op, a_kind, b_kind, flags;
-  uint8_t a, b, dst, aux;
+  uint8_t op, b_kind, flags, pad0;
+  uint8_t b, dst, aux, pad1;
   float imm;
 };
 constexpr int kProgMaxInstr = 64;
@@ -206,7 +208,8 @@ struct RowProgP {
   int32_t lanes_per_row, lanes_log2, vecs_per_lane;   // lanes_per_row > 64: one workgroup per row
   int32_t n_full, n_col, n_rscal, n_instr;
   int32_t n_regs, n_sregs;             // register files: full-shaped and per-row
-  uint8_t full_reg[kProgMaxOperands];  // register each full-shaped input is parked in
+  int32_t acc_input;                   // full-shaped input the accumulator starts out holding, -1 = none
+  uint8_t full_reg[kProgMaxOperands];  // register each full-shaped input is parked in, 255 = not parked
   uint8_t rscal_sreg[kProgMaxOperands], rscal_dt[kProgMaxOperands];
   ProgInstr instr[kProgMaxInstr];
 };

@@ -6,8 +6,8 @@
 //   * a row per lane group of one wavefront (warp composition) or per workgroup (block
 //     composition), exactly like the hand-written row kernels,
 //   * every global load issued before the first instruction runs, each input read once,
-//   * column vectors in an LDS file shared by the workgroup; full-shaped values in an
-//     accumulator (VGPRs) or a per-lane register file in LDS (a lane only ever touches its own
+//   * column vectors in an LDS file shared by the workgroup; full-shaped values in THE
+//     accumulator (VGPRs: every instruction reads and writes it) or a per-lane register file in LDS (a lane only ever touches its own
 //     slots, so no barrier guards them); inputs are parked there by the prologue,
 //   * per-row values (reduction results and what is computed from them) in a scalar
 //     accumulator or a per-lane scalar file, identical in all lanes of the row,
@@ -40,12 +40,15 @@ __device__ __forceinline__ void store_scalar_as(void* p, size_t i, int dt, float
   else store1(static_cast<float*>(p) + i, v);
 }
 
+// a = the accumulator, b = the other operand
 __device__ __forceinline__ float apply_op(int op, float a, float b, int aux) {
   switch (op) {
     case PO_ADD: return a + b;
     case PO_SUB: return a - b;
+    case PO_RSUB: return b - a;
     case PO_MUL: return a * b;
     case PO_DIV: return a * fast_rcp(b);
+    case PO_RDIV: return b * fast_rcp(a);
     case PO_MAX: return fmaxf(a, b);
     case PO_SQUARE: return a * a;
     case PO_EXP: return fast_exp(a);
@@ -54,7 +57,7 @@ __device__ __forceinline__ float apply_op(int op, float a, float b, int aux) {
     case PO_GELU: return gelu_fwd(a);
     case PO_GELU_GRAD: return gelu_grad(a);
     case PO_CVT: return round_through(a, aux);
-    default: return a;   // PO_MOV
+    default: return b;   // PO_LOAD
   }
 }
 
@@ -98,13 +101,13 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
       const f32x4 t = {v[4 * j], v[4 * j + 1], v[4 * j + 2], v[4 * j + 3]};
-      regs[((size_t)reg * CH + j) * 256 + tid] = t;
+      regs[((uint32_t)reg * CH + j) * 256u + tid] = t;
     }
   };
   auto get = [&](int reg, float (&v)[KV]) {
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
-      const f32x4 t = regs[((size_t)reg * CH + j) * 256 + tid];
+      const f32x4 t = regs[((uint32_t)reg * CH + j) * 256u + tid];
       v[4 * j] = t.x; v[4 * j + 1] = t.y; v[4 * j + 2] = t.z; v[4 * j + 3] = t.w;
     }
   };
@@ -118,6 +121,11 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
         reinterpret_cast<const uint32_t __attribute__((address_space(4)))*>(&A->p.instr[slot]);
     iw0 = w[0]; iw1 = w[1]; iw2 = w[2];
   }
+
+  float acc[KV];
+#pragma unroll
+  for (int j = 0; j < KV; ++j) acc[j] = 0.0f;
+  const int acc_input = A->p.acc_input;
 
   // ---- prologue: every global load is issued before anything waits ------------------------
   // full-shaped inputs are parked in registers of the per-lane file; column vectors are unpacked
@@ -147,13 +155,13 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
 #pragma unroll
         for (int h = 0; h < VEC / 4; ++h) {
           const f32x4 t = {part[4 * h], part[4 * h + 1], part[4 * h + 2], part[4 * h + 3]};
-          colfile[((size_t)i * nvec + j) * (VEC / 4) + h] = t;
+          colfile[((uint32_t)i * nvec + j) * (VEC / 4) + h] = t;
         }
       }
     }
 #pragma unroll
     for (int i = 0; i < kProgMaxOperands; ++i) {
-      if (i < n_rscal) sregs[(size_t)A->p.rscal_sreg[i] * 256 + tid] = rs[i];
+      if (i < n_rscal) sregs[(uint32_t)A->p.rscal_sreg[i] * 256u + tid] = rs[i];
     }
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
@@ -166,86 +174,58 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
 #pragma unroll
           for (int e = 0; e < VEC; ++e) v[k * VEC + e] = part[e];
         }
-        put(A->p.full_reg[i], v);
+        if (A->p.full_reg[i] != 255) put(A->p.full_reg[i], v);
+        if (i == acc_input) {
+#pragma unroll
+          for (int j = 0; j < KV; ++j) acc[j] = v[j];
+        }
       }
     }
     if (n_col > 0) __syncthreads();   // n_col is uniform: every thread of the workgroup arrives
   }
 
-  // ---- instruction walk -------------------------------------------------------------------
-  float acc[KV];
-#pragma unroll
-  for (int j = 0; j < KV; ++j) acc[j] = 0.0f;
+  // ---- instruction walk: an accumulator machine ----------------------------------------------
+  // full-shaped:  acc <- acc (op) b | (op) acc | b      per-row:  sacc <- sacc (op) b | (op) sacc | b
+  // b comes from a register, the column file, a per-row scalar (stretched along the row) or the
+  // immediate; PF_KEEP also writes the result to a register.
   float sacc = 0.0f;
   int reduction_no = 0;
   for (int pc = 0; pc < n_instr; ++pc) {
-    // lane i of every wavefront holds instruction i (loaded once, below): fetching one is three
-    // cross-lane reads into scalar registers, with no memory latency inside the walk
+    // lane i of every wavefront holds instruction i: fetching one is three cross-lane reads
+    // into scalar registers, with no memory latency inside the walk
     const uint32_t w0 = (uint32_t)__builtin_amdgcn_readlane((int)iw0, pc);
     const uint32_t w1 = (uint32_t)__builtin_amdgcn_readlane((int)iw1, pc);
-    const uint32_t w2 = (uint32_t)__builtin_amdgcn_readlane((int)iw2, pc);
-    ProgInstr ins;
-    ins.op = w0 & 0xFF; ins.a_kind = (w0 >> 8) & 0xFF; ins.b_kind = (w0 >> 16) & 0xFF; ins.flags = w0 >> 24;
-    ins.a = w1 & 0xFF; ins.b = (w1 >> 8) & 0xFF; ins.dst = (w1 >> 16) & 0xFF; ins.aux = w1 >> 24;
-    ins.imm = __builtin_bit_cast(float, w2);
-    auto scalar_operand = [&](int kind, int idx) {
-      if (kind == PK_SACC) return sacc;
-      if (kind == PK_SCAL) return sregs[(size_t)idx * 256 + tid];
-      return ins.imm;
-    };
-    auto vector_operand = [&](int kind, int idx, float (&v)[KV]) {
-      if (kind == PK_ACC) {
-#pragma unroll
-        for (int j = 0; j < KV; ++j) v[j] = acc[j];
-      } else if (kind == PK_REG) {
-        get(idx, v);
-      } else if (kind == PK_COL) {
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-          const f32x4* src = colfile + ((size_t)idx * nvec + vec_at(k)) * (VEC / 4);
-#pragma unroll
-          for (int h = 0; h < VEC / 4; ++h) {
-            const f32x4 t = src[h];
-            v[k * VEC + 4 * h] = t.x; v[k * VEC + 4 * h + 1] = t.y; v[k * VEC + 4 * h + 2] = t.z; v[k * VEC + 4 * h + 3] = t.w;
-          }
-        }
-      } else {
-        const float s = scalar_operand(kind, idx);
-#pragma unroll
-        for (int j = 0; j < KV; ++j) v[j] = s;
-      }
-    };
+    const float imm = __builtin_bit_cast(float, __builtin_amdgcn_readlane((int)iw2, pc));
+    const uint32_t op = w0 & 0xFF, b_kind = (w0 >> 8) & 0xFF, flags = (w0 >> 16) & 0xFF;
+    const uint32_t b_idx = w1 & 0xFF, dst = (w1 >> 8) & 0xFF, aux = (w1 >> 16) & 0xFF;
 
-    if (ins.op == PO_STORE) {
-      float v[KV];
-      vector_operand(ins.a_kind, ins.a, v);
-      void* out = A->out[ins.dst];
+    if (op == PO_STORE) {
+      void* out = A->out[dst];
 #pragma unroll
       for (int k = 0; k < K; ++k) {
         float part[VEC];
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) part[e] = v[k * VEC + e];
+        for (int e = 0; e < VEC; ++e) part[e] = acc[k * VEC + e];
         if (row_ok && valid(k)) {
           const size_t at = (size_t)row * cols + (size_t)(lane + k * L) * VEC;
-          if (ins.aux == DT_F32) StoreN<float, VEC>::run(static_cast<float*>(out) + at, part);
-          else if (ins.aux == DT_F16) StoreN<f16_t, VEC>::run(static_cast<f16_t*>(out) + at, part);
+          if (aux == DT_F32) StoreN<float, VEC>::run(static_cast<float*>(out) + at, part);
+          else if (aux == DT_F16) StoreN<f16_t, VEC>::run(static_cast<f16_t*>(out) + at, part);
           else StoreN<bf16_t, VEC>::run(static_cast<bf16_t*>(out) + at, part);
         }
       }
-    } else if (ins.op == PO_STORE_SCAL) {
-      const float s = scalar_operand(ins.a_kind, ins.a);
-      if (row_ok && lane == 0) store_scalar_as(A->rout[ins.dst], row, ins.aux, s);
-    } else if (ins.op == PO_RSUM || ins.op == PO_RMAX) {
-      float v[KV];
-      vector_operand(ins.a_kind, ins.a, v);
-      const bool is_max = ins.op == PO_RMAX;
+    } else if (op == PO_STORE_SCAL) {
+      if (row_ok && lane == 0) store_scalar_as(A->rout[dst], row, (int)aux, sacc);
+    } else if (op == PO_RSUM || op == PO_RMAX || op == PO_RSUMSQ) {
+      const bool is_max = op == PO_RMAX;
+      const bool squared = op == PO_RSUMSQ;
       float r = is_max ? -INFINITY : 0.0f;
 #pragma unroll
       for (int k = 0; k < K; ++k) {
         const bool ok = valid(k);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
-          const float x = v[k * VEC + e];
+          const float v = acc[k * VEC + e];
+          const float x = squared ? v * v : v;
           r = is_max ? fmaxf(r, ok ? x : -INFINITY) : r + (ok ? x : 0.0f);
         }
       }
@@ -257,37 +237,49 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
       }
       ++reduction_no;
       sacc = r;
-      if (ins.flags & PF_KEEP) sregs[(size_t)ins.dst * 256 + tid] = r;
-    } else if (ins.flags & PF_SCALAR) {
-      const float a = scalar_operand(ins.a_kind, ins.a);
-      const float b = scalar_operand(ins.b_kind, ins.b);
-      sacc = apply_op(ins.op, a, b, ins.aux);
-      if (ins.flags & PF_KEEP) sregs[(size_t)ins.dst * 256 + tid] = sacc;
+      if (flags & PF_KEEP) sregs[dst * 256u + tid] = r;
+    } else if (flags & PF_SCALAR) {
+      const float b = b_kind == PK_SCAL ? sregs[b_idx * 256u + tid] : (b_kind == PK_SACC ? sacc : imm);
+      sacc = apply_op((int)op, sacc, b, (int)aux);
+      if (flags & PF_KEEP) sregs[dst * 256u + tid] = sacc;
     } else {
-      float a[KV], b[KV];
-      vector_operand(ins.a_kind, ins.a, a);
-      if (ins.op <= PO_MAX) {
-        vector_operand(ins.b_kind, ins.b, b);
-      } else {
+      float b[KV];
+      if (b_kind == PK_REG) {
+        get((int)b_idx, b);
+      } else if (b_kind == PK_COL) {
 #pragma unroll
-        for (int j = 0; j < KV; ++j) b[j] = 0.0f;
+        for (int k = 0; k < K; ++k) {
+          const f32x4* src = colfile + (b_idx * nvec + vec_at(k)) * (VEC / 4);
+#pragma unroll
+          for (int h = 0; h < VEC / 4; ++h) {
+            const f32x4 t = src[h];
+            b[k * VEC + 4 * h] = t.x; b[k * VEC + 4 * h + 1] = t.y; b[k * VEC + 4 * h + 2] = t.z; b[k * VEC + 4 * h + 3] = t.w;
+          }
+        }
+      } else if (b_kind == PK_ACC) {
+#pragma unroll
+        for (int j = 0; j < KV; ++j) b[j] = acc[j];
+      } else {
+        const float sb = b_kind == PK_SCAL ? sregs[b_idx * 256u + tid] : (b_kind == PK_SACC ? sacc : imm);
+#pragma unroll
+        for (int j = 0; j < KV; ++j) b[j] = sb;
       }
       // the op is uniform: one scalar branch per instruction, then straight-line lane work
-      switch (ins.op) {
-#define FS_PROG_CASE(OP)                                                            \
-  case OP:                                                                          \
-    _Pragma("unroll") for (int j = 0; j < KV; ++j) acc[j] = apply_op(OP, a[j], b[j], ins.aux); \
+      switch (op) {
+#define FS_PROG_CASE(OP)                                                               \
+  case OP:                                                                             \
+    _Pragma("unroll") for (int j = 0; j < KV; ++j) acc[j] = apply_op(OP, acc[j], b[j], (int)aux); \
     break;
-        FS_PROG_CASE(PO_ADD) FS_PROG_CASE(PO_SUB) FS_PROG_CASE(PO_MUL) FS_PROG_CASE(PO_DIV) FS_PROG_CASE(PO_MAX)
-        FS_PROG_CASE(PO_SQUARE) FS_PROG_CASE(PO_EXP) FS_PROG_CASE(PO_RSQRT) FS_PROG_CASE(PO_TANH)
-        FS_PROG_CASE(PO_GELU) FS_PROG_CASE(PO_GELU_GRAD) FS_PROG_CASE(PO_CVT)
+        FS_PROG_CASE(PO_ADD) FS_PROG_CASE(PO_SUB) FS_PROG_CASE(PO_RSUB) FS_PROG_CASE(PO_MUL) FS_PROG_CASE(PO_DIV)
+        FS_PROG_CASE(PO_RDIV) FS_PROG_CASE(PO_MAX) FS_PROG_CASE(PO_SQUARE) FS_PROG_CASE(PO_EXP) FS_PROG_CASE(PO_RSQRT)
+        FS_PROG_CASE(PO_TANH) FS_PROG_CASE(PO_GELU) FS_PROG_CASE(PO_GELU_GRAD) FS_PROG_CASE(PO_CVT)
 #undef FS_PROG_CASE
-        default:
+        default:   // PO_LOAD
 #pragma unroll
-          for (int j = 0; j < KV; ++j) acc[j] = a[j];
+          for (int j = 0; j < KV; ++j) acc[j] = b[j];
           break;
       }
-      if (ins.flags & PF_KEEP) put(ins.dst, acc);
+      if (flags & PF_KEEP) put((int)dst, acc);
     }
   }
 }

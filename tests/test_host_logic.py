@@ -117,7 +117,7 @@ def test_unsupported_pattern_and_auto_fallback():
                      [OpSpec("e", "exp", ("x",)), OpSpec("y", "mul", ("e", "x"))], [("y", "f32")])
     info = B.Plan(B.Graph.from_spec(spec), "auto").info
     assert info["pattern"] == "row_program" and info["n_kernels"] == 1 and info["workspace_bytes"] == 0
-    assert ",I3," in info["kernel"]                 # exp, mul, store
+    assert ",I3," in info["kernel"]                 # exp (x arrives in the accumulator), mul by x, store
     # ragged softmax still gets a stitched (block-per-row) kernel
     info = B.Plan(B.Graph.from_spec(softmax_graph(5, 37, "f32")), "auto").info
     assert info["pattern"] == "softmax" and info["scheme"] == "lds"

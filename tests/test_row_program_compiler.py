@@ -39,12 +39,16 @@ def emulate(listing, spec, inputs):
     rows, cols = int(kv["rows"]), int(kv["cols"])
     in_arrays = [O.to_f64(inputs[t.name], t.dtype).astype(np.float32) for t in spec.inputs]
     regs, sregs, outs, colvecs = {}, {}, {}, {}
+    acc0 = None
     out_bind, rout_bind = {}, {}
     for l in lines:
         if not l:
             continue
         if l[0] == "full":
-            regs[int(l[3])] = in_arrays[int(l[1][2:])].reshape(rows, cols)
+            if int(l[3]) != 255:
+                regs[int(l[3])] = in_arrays[int(l[1][2:])].reshape(rows, cols)
+            if l[-1] == "acc":
+                acc0 = in_arrays[int(l[1][2:])].reshape(rows, cols)
         elif l[0] == "col":
             colvecs[int(l[3])] = np.broadcast_to(in_arrays[int(l[1][2:])].reshape(1, cols), (rows, cols))
         elif l[0] == "rscal":
@@ -53,7 +57,7 @@ def emulate(listing, spec, inputs):
             out_bind[int(l[1])] = int(l[2][3:])
         elif l[0] == "routput":
             rout_bind[int(l[1])] = int(l[2][3:])
-    acc = np.zeros((rows, cols), np.float32)
+    acc = np.zeros((rows, cols), np.float32) if acc0 is None else acc0.copy()
     sacc = np.zeros((rows, 1), np.float32)
     f32 = np.float32
     n_instr = 0
@@ -66,44 +70,32 @@ def emulate(listing, spec, inputs):
         imm = f32(float(f["imm"]))
         scalar, keep = f["flags"][0] == "s", f["flags"][1] == "k"
         aux = NP_DT[int(f["aux"])]
-
-        def operand(text):
-            kind, idx = text.split(":")
-            if kind == "acc":
-                return acc
-            if kind == "sacc":
-                return sacc
-            if kind == "reg":
-                return regs[int(idx)]
-            if kind == "scal":
-                return sregs[int(idx)]
-            if kind == "col":
-                return colvecs[int(idx)]
-            return np.full((1, 1), imm, np.float32)
-        a = operand(f["a"])
         dst = int(f["dst"])
+        kind, idx = f["b"].split(":")
         if op == "store":
-            outs[out_bind[dst]] = np.broadcast_to(a, (rows, cols)).copy()
+            outs[out_bind[dst]] = acc.copy()
             continue
         if op == "store_scal":
-            assert a.shape == (rows, 1)
-            outs[rout_bind[dst]] = a.copy()
+            outs[rout_bind[dst]] = sacc.copy()
             continue
-        if op in ("rsum", "rmax"):
-            assert a.shape == (rows, cols)
-            sacc = (a.sum(axis=1, keepdims=True, dtype=np.float32) if op == "rsum" else a.max(axis=1, keepdims=True)).astype(f32)
+        if op in ("rsum", "rmax", "rsumsq"):
+            src = acc * acc if op == "rsumsq" else acc
+            sacc = (src.max(axis=1, keepdims=True) if op == "rmax" else src.sum(axis=1, keepdims=True, dtype=np.float32)).astype(f32)
             if keep:
                 sregs[dst] = sacc
             continue
-        b = operand(f["b"])
+        b = {"acc": lambda: acc, "sacc": lambda: sacc, "reg": lambda: regs[int(idx)], "scal": lambda: sregs[int(idx)],
+             "col": lambda: colvecs[int(idx)], "imm": lambda: np.full((1, 1), imm, np.float32)}[kind]()
+        a = sacc if scalar else acc
+        if scalar:
+            assert kind in ("sacc", "scal", "imm"), "per-row instruction with a full-shaped operand"
         with np.errstate(all="ignore"):
-            r = {"add": lambda: a + b, "sub": lambda: a - b, "mul": lambda: a * b, "div": lambda: a / b,
-                 "max": lambda: np.maximum(a, b), "square": lambda: a * a, "exp": lambda: np.exp(a),
+            r = {"add": lambda: a + b, "sub": lambda: a - b, "rsub": lambda: b - a, "mul": lambda: a * b, "div": lambda: a / b,
+                 "rdiv": lambda: b / a, "max": lambda: np.maximum(a, b), "square": lambda: a * a, "exp": lambda: np.exp(a),
                  "rsqrt": lambda: 1.0 / np.sqrt(a), "tanh": lambda: np.tanh(a), "gelu": lambda: _gelu(a),
-                 "gelu_grad": lambda: _gelu_grad(a), "mov": lambda: a, "cvt": lambda: _round_through(a, aux)}[op]()
+                 "gelu_grad": lambda: _gelu_grad(a), "load": lambda: b, "cvt": lambda: _round_through(a, aux)}[op]()
         r = np.asarray(r, dtype=np.float32)
         if scalar:
-            assert r.shape in ((rows, 1), (1, 1)), "per-row instruction with a full-shaped operand"
             sacc = np.broadcast_to(r, (rows, 1)).copy()
             if keep:
                 sregs[dst] = sacc
@@ -147,11 +139,11 @@ def test_layernorm_program_keeps_only_what_is_read_again():
     plan = B.Plan(B.Graph.from_spec(spec), "auto")
     lines = [l.split() for l in plan.describe().splitlines() if l.strip().startswith("instr")]
     kept = [l for l in lines if "flags=vk" in l or "flags=sk" in l]
-    # h, mean, variance, rstd, the scaled values all pass through the accumulators; only the
-    # centred row (read again after the variance reduction chain) is written to a register
-    assert len(kept) == 1 and kept[0][2] == "sub"
+    # h, mean, the centred row, variance, rstd and the scaled values all pass through the accumulators:
+    # the variance reduction squares on the fly, so nothing is written to a register
+    assert len(kept) == 0 and any(l[2] == "rsumsq" for l in lines) and not any(l[2] in ("square", "cvt") for l in lines)
     head = [l for l in plan.describe().splitlines() if l.strip().startswith("program ")][0]
-    assert "regs=2" in head and "sregs=0" in head       # x and res; the centred row reuses a slot; column vectors live in the shared file
+    assert "regs=1" in head and "sregs=0" in head       # x arrives in the accumulator, res is parked, the centred row reuses its slot
 
 
 @pytest.mark.parametrize("seed", range(60))
