@@ -36,6 +36,7 @@ extern "C" {
 typedef struct fs_graph fs_graph;
 typedef struct fs_plan fs_plan;
 typedef struct fs_pack fs_pack;
+typedef struct fs_program fs_program;
 typedef int32_t fs_status;
 typedef int32_t fs_tensor;
 
@@ -235,6 +236,73 @@ fs_status fs_pack_query(const fs_pack *p, fs_pack_info *out);
  * outputs.  Needs no workspace, allocates nothing, never synchronizes.
  * Errors: FS_ERR_INVALID_ARG, FS_ERR_ALIGN, FS_ERR_HIP.                              */
 fs_status fs_pack_execute(const fs_pack *p, const void *const *inputs, void *const *outputs, void *hip_stream);
+
+/* ---- fusion exploration over a multi-pattern graph (Section 5) ------------------- */
+
+/* Zero fields take the paper's settings: the 3 best candidate patterns per vertex
+ * (Section 5.2), beam width 3 (Section 5.3), packing of launch-bound patterns on.     */
+typedef struct fs_explore_opts {
+  int32_t top_k;        /* candidate patterns kept per vertex and per consumer group, 1..16 */
+  int32_t beam_width;   /* candidate fusion plans kept while traversing the graph, 1..16    */
+  int32_t no_packing;   /* 1: leave independent launch-bound patterns in launches of their own */
+  int32_t no_remote_fusion; /* 1: do not merge patterns that no edge joins (Section 5.2, remote fusion) */
+} fs_explore_opts;
+
+typedef struct fs_program_info {
+  int32_t n_ops;          /* ops of the graph                                             */
+  int32_t n_patterns;     /* fusion patterns of two or more ops in the chosen plan         */
+  int32_t n_single_ops;   /* ops left in a kernel of their own                             */
+  int32_t n_steps;        /* fs_execute / packed launches issued per fs_program_execute    */
+  int32_t n_kernels;      /* kernel launches per fs_program_execute                        */
+  int32_t n_packs;        /* packed launches among the steps                               */
+  int32_t beam_plans;     /* candidate plans the final choice was made among               */
+  int32_t reserved;
+  int64_t workspace_bytes;   /* device scratch fs_program_execute needs                    */
+  int64_t bytes_min;         /* graph inputs read once + graph outputs written once        */
+  int64_t bytes_moved_model; /* bytes the plan's kernels move, tensors between patterns included */
+  double f_total_us;         /* sum of the chosen patterns' delta-evaluator scores (Eq. 3), remote fusion included */
+  double predicted_us;       /* latency-evaluator estimate of one fs_program_execute        */
+  double predicted_unfused_us; /* the same ops one kernel each, by the delta-evaluator's per-op term */
+} fs_program_info;
+
+/* Delta-evaluator (Section 5.4, Eq. 3) for the ops[0..n) of `g` (op index = order of the
+ * fs_graph_op calls) taken as ONE fusion pattern: *f_us receives
+ * T_reduced_mem + T_reduced_calls - T_penalty in microseconds (0 for a single op).
+ * *f_optimistic_us (may be null) receives the score the pattern would have if one kernel
+ * ran it at streaming rate; it is set whenever the ops form a pattern without a cyclic
+ * dependence, also when the call fails with FS_ERR_UNSUPPORTED_PATTERN (the explorer
+ * grows such patterns further, in case a larger one is covered by a kernel family).
+ * `ops`, `f_us`, `f_optimistic_us` are HOST pointers.  Errors: FS_ERR_INVALID_ARG; FS_ERR_CYCLE (fusing
+ * them creates a cyclic dependence, Section 5.2); FS_ERR_UNSUPPORTED_PATTERN (no stitched
+ * kernel can run them as one pattern); FS_ERR_DTYPE (a graph output stored in another
+ * dtype than it was computed in would have to feed ops outside the pattern).            */
+fs_status fs_explore_score(const fs_graph *g, const int32_t *ops, int32_t n, double *f_us, double *f_optimistic_us);
+
+/* Searches a fusion plan for a finalized graph that may hold many patterns (Section 5.2:
+ * candidate patterns per vertex by PatternReduction in post-order; Section 5.3: beam
+ * search over the vertices, final choice by the latency evaluator) and builds the
+ * executable program: one plan per chosen pattern, one per op left alone, packed launches
+ * for independent launch-bound patterns (remote fusion, Section 5.2).  `opts` may be null.
+ * Errors: FS_ERR_INVALID_ARG, FS_ERR_DTYPE (see fs_explore_score; add an explicit convert
+ * op and let the consumers read its result), FS_ERR_UNSUPPORTED_PATTERN, FS_ERR_SHAPE.  */
+fs_status fs_explore(const fs_graph *g, const fs_explore_opts *opts, fs_program **out);
+void fs_program_destroy(fs_program *p);
+fs_status fs_program_query(const fs_program *p, fs_program_info *out);
+/* Step `index` (0 <= index < n_patterns + n_single_ops, in execution order): its op
+ * indices in graph order into ops[0..capacity) (HOST; may be null), their number into
+ * *n_ops, its delta-evaluator score, the packed launch it belongs to (-1: none) and the
+ * figures of its plan.  Every out pointer may be null.  Errors: FS_ERR_INVALID_ARG.      */
+fs_status fs_program_pattern(const fs_program *p, int32_t index, int32_t *ops, int32_t capacity, int32_t *n_ops,
+                             double *f_us, int32_t *pack, fs_plan_info *info);
+/* Enqueues the whole program on `hip_stream` and returns without waiting.  inputs /
+ * outputs: DEVICE pointers in the graph's declaration order, 16-byte aligned.  `workspace`:
+ * DEVICE scratch of at least fs_program_info.workspace_bytes, 256-byte aligned, zero-filled
+ * once after allocation (it holds the tensors that cross from one pattern to the next and
+ * the patterns' own scratch); calls that share it must be ordered on one stream.
+ * Allocates nothing, never synchronizes.
+ * Errors: FS_ERR_INVALID_ARG, FS_ERR_WORKSPACE, FS_ERR_ALIGN, FS_ERR_HIP.               */
+fs_status fs_program_execute(const fs_program *p, const void *const *inputs, void *const *outputs, void *workspace,
+                             size_t workspace_bytes, void *hip_stream);
 
 /* Plain streaming copy of `bytes` (multiple of 16) from src to dst, both DEVICE
  * and 16-byte aligned: the measured HBM ceiling every result is reported beside

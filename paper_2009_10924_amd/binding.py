@@ -30,6 +30,7 @@ EXPORTS = [
     "fs_graph_finalize", "fs_plan_create", "fs_plan_destroy", "fs_plan_query", "fs_plan_candidate", "fs_plan_describe",
     "fs_execute", "fs_stream_copy", "fs_last_error", "fs_version",
     "fs_pack_create", "fs_pack_destroy", "fs_pack_query", "fs_pack_execute",
+    "fs_explore", "fs_explore_score", "fs_program_destroy", "fs_program_query", "fs_program_pattern", "fs_program_execute",
 ]
 FS_PACK_MAX_MEMBERS = 256
 
@@ -100,6 +101,22 @@ class fs_pack_info(C.Structure):
         return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved"}
 
 
+class fs_explore_opts(C.Structure):
+    _fields_ = [("top_k", C.c_int32), ("beam_width", C.c_int32), ("no_packing", C.c_int32), ("no_remote_fusion", C.c_int32)]
+
+
+class fs_program_info(C.Structure):
+    _fields_ = [
+        ("n_ops", C.c_int32), ("n_patterns", C.c_int32), ("n_single_ops", C.c_int32), ("n_steps", C.c_int32),
+        ("n_kernels", C.c_int32), ("n_packs", C.c_int32), ("beam_plans", C.c_int32), ("reserved", C.c_int32),
+        ("workspace_bytes", C.c_int64), ("bytes_min", C.c_int64), ("bytes_moved_model", C.c_int64),
+        ("f_total_us", C.c_double), ("predicted_us", C.c_double), ("predicted_unfused_us", C.c_double),
+    ]
+
+    def as_dict(self) -> Dict:
+        return {k: getattr(self, k) for k, _ in self._fields_ if k != "reserved"}
+
+
 _LIB: Optional[C.CDLL] = None
 
 
@@ -150,6 +167,19 @@ def load() -> C.CDLL:
     lib.fs_execute.restype = i32
     lib.fs_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
     lib.fs_stream_copy.restype = i32
+    lib.fs_explore.argtypes = [vp, C.POINTER(fs_explore_opts), C.POINTER(vp)]
+    lib.fs_explore.restype = i32
+    lib.fs_explore_score.argtypes = [vp, C.POINTER(i32), i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    lib.fs_explore_score.restype = i32
+    lib.fs_program_destroy.argtypes = [vp]
+    lib.fs_program_destroy.restype = None
+    lib.fs_program_query.argtypes = [vp, C.POINTER(fs_program_info)]
+    lib.fs_program_query.restype = i32
+    lib.fs_program_pattern.argtypes = [vp, i32, C.POINTER(i32), i32, C.POINTER(i32), C.POINTER(C.c_double), C.POINTER(i32),
+                                       C.POINTER(fs_plan_info)]
+    lib.fs_program_pattern.restype = i32
+    lib.fs_program_execute.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp, C.c_size_t, vp]
+    lib.fs_program_execute.restype = i32
     lib.fs_pack_create.argtypes = [C.POINTER(vp), i32, C.POINTER(vp)]
     lib.fs_pack_create.restype = i32
     lib.fs_pack_destroy.argtypes = [vp]
@@ -335,6 +365,69 @@ class Pack:
 
     def execute_ptrs(self, inputs: Sequence[int], outputs: Sequence[int], stream: int) -> None:
         self.bind(inputs, outputs, stream)()
+
+
+def explore_score(graph: Graph, ops: Sequence[int]) -> float:
+    """Delta-evaluator score (microseconds) of `ops` taken as one fusion pattern; raises FsError if they cannot be one."""
+    return explore_score_ex(graph, ops)[0]
+
+
+def explore_score_ex(graph: Graph, ops: Sequence[int]):
+    """(f_us, f_optimistic_us, status): status 0 = runnable as one pattern; a negative fs_error otherwise, with f_us None.
+    f_optimistic_us is set for every pattern without a cyclic dependence."""
+    arr = (C.c_int32 * max(1, len(ops)))(*ops)
+    f, fo = C.c_double(), C.c_double()
+    code = load().fs_explore_score(graph.handle, arr, len(ops), C.byref(f), C.byref(fo))
+    if code == -1:
+        _check(code)
+    return (f.value if code == 0 else None), fo.value, code
+
+
+class Program:
+    """Fusion plan found for a multi-pattern graph, and its execution."""
+
+    def __init__(self, graph: Graph, top_k: int = 0, beam_width: int = 0, no_packing: bool = False, no_remote_fusion: bool = False):
+        self._lib = load()
+        self._graph = graph
+        opts = fs_explore_opts(top_k, beam_width, 1 if no_packing else 0, 1 if no_remote_fusion else 0)
+        h = C.c_void_p()
+        _check(self._lib.fs_explore(graph.handle, C.byref(opts), C.byref(h)))
+        self.handle = h
+        info = fs_program_info()
+        _check(self._lib.fs_program_query(self.handle, C.byref(info)))
+        self.info = info.as_dict()
+
+    def __del__(self):
+        if getattr(self, "handle", None):
+            self._lib.fs_program_destroy(self.handle)
+            self.handle = None
+
+    def patterns(self) -> List[Dict]:
+        out = []
+        for i in range(self.info["n_patterns"] + self.info["n_single_ops"]):
+            n, f, pack, info = C.c_int32(), C.c_double(), C.c_int32(), fs_plan_info()
+            _check(self._lib.fs_program_pattern(self.handle, i, None, 0, C.byref(n), C.byref(f), C.byref(pack), C.byref(info)))
+            ops = (C.c_int32 * max(1, n.value))()
+            _check(self._lib.fs_program_pattern(self.handle, i, ops, n.value, None, None, None, None))
+            out.append({"ops": list(ops)[:n.value], "f_us": f.value, "pack": pack.value, "info": info.as_dict()})
+        return out
+
+    def make_workspace(self, device="cuda"):
+        import torch
+        n = int(self.info["workspace_bytes"])
+        return torch.zeros(max(n, 256), dtype=torch.uint8, device=device)
+
+    def bind(self, inputs: Sequence[int], outputs: Sequence[int], workspace: int, workspace_bytes: int, stream: int):
+        ins = (C.c_void_p * max(1, len(inputs)))(*inputs)
+        outs = (C.c_void_p * max(1, len(outputs)))(*outputs)
+        ws, nb, st = C.c_void_p(workspace), C.c_size_t(workspace_bytes), C.c_void_p(stream)
+        fn, handle = self._lib.fs_program_execute, self.handle
+
+        def call(_keep=(ins, outs)):
+            code = fn(handle, ins, outs, ws, nb, st)
+            if code < 0:
+                _check(code)
+        return call
 
 
 def stream_copy(dst, src, stream: Optional[int] = None) -> None:

@@ -1,0 +1,836 @@
+// Fusion exploration over a multi-pattern graph (paper Section 5) and execution of the plan it
+// finds.
+//   * candidate patterns per vertex, from the last vertex to the first, by PatternReduction
+//     (Section 5.2): a vertex joins combinations of its consumers' candidate patterns, consumers
+//     are handled in groups of two, only the top-k patterns by score survive;
+//   * patterns with a cyclic dependence or that the code generator cannot process are discarded
+//     (Section 5.2) -- "can process" here means: a hand-written kernel family matches it or it
+//     compiles to an interpreted row program;
+//   * score f = T_reduced_mem + T_reduced_calls - T_penalty (Section 5.4, Eq. 3), with constants
+//     measured on MI355X (launch cost, streaming rate) and the penalty from the kernel estimate
+//     without compiled register figures;
+//   * the overall plan by beam search over the vertices from producers to consumers (Section 5.3),
+//     the final choice among the beam's plans by the full latency evaluator (Section 4.3);
+//   * independent launch-bound patterns of the chosen plan are packed into one launch (remote
+//     fusion / kernel packing, Section 5.2 and 4.1).
+// Execution runs the patterns in dependence order; tensors that cross from one pattern to another
+// live in the caller's workspace, placed by lifetime.
+#include <algorithm>
+#include <cstring>
+#include <map>
+#include <set>
+#include <string>
+
+#include "fs_internal.hpp"
+
+extern "C" {
+fs_status fs_graph_create(fs_graph** out);
+void fs_graph_destroy(fs_graph* g);
+fs_tensor fs_graph_input(fs_graph* g, int32_t dtype, int32_t rank, const int64_t* dims);
+fs_tensor fs_graph_op(fs_graph* g, int32_t opcode, int32_t n_in, const fs_tensor* in, const void* attr, size_t attr_bytes);
+fs_status fs_graph_output(fs_graph* g, fs_tensor t, int32_t store_as);
+fs_status fs_graph_finalize(fs_graph* g);
+}
+
+namespace fs {
+namespace {
+
+typedef std::vector<int> OpSet;   // sorted op indices
+
+struct SubGraph {
+  fs_graph* g = nullptr;
+  std::vector<int32_t> in_tensor;    // sub input slot  -> tensor id in the big graph
+  std::vector<int32_t> out_tensor;   // sub output slot -> tensor id in the big graph
+  ~SubGraph() { fs_graph_destroy(g); }
+  SubGraph() = default;
+  SubGraph(const SubGraph&) = delete;
+  SubGraph& operator=(const SubGraph&) = delete;
+};
+
+struct Scored {
+  bool valid = false;
+  int32_t why = FS_OK;     // FS_ERR_CYCLE / FS_ERR_UNSUPPORTED_PATTERN / FS_ERR_DTYPE when not valid
+  double f = 0;            // microseconds
+  double f_optimistic = 0; // what f would be if the ops ran as one kernel at streaming rate; set for every convex pattern
+  double t_fused = 0, t_unfused = 0;
+};
+
+struct Explorer {
+  const fs_graph& g;
+  int n;                                     // ops
+  std::vector<std::vector<int>> consumers;   // op -> ops that read its result (sorted, distinct)
+  std::vector<std::vector<uint64_t>> desc;   // op -> bitset of its descendants
+  std::map<OpSet, Scored> memo;
+  int top_k = 3, beam_width = 3;
+
+  explicit Explorer(const fs_graph& graph) : g(graph), n((int)graph.ops.size()) {
+    consumers.resize(n);
+    for (int i = 0; i < n; ++i) {
+      std::set<int> c(g.tensors[g.ops[i].out].consumers.begin(), g.tensors[g.ops[i].out].consumers.end());
+      consumers[i].assign(c.begin(), c.end());
+    }
+    const int words = (n + 63) / 64;
+    desc.assign(n, std::vector<uint64_t>(words, 0));
+    for (int i = n - 1; i >= 0; --i)
+      for (int c : consumers[i]) {
+        desc[i][c / 64] |= 1ull << (c % 64);
+        for (int w = 0; w < words; ++w) desc[i][w] |= desc[c][w];
+      }
+  }
+
+  // No path may leave the pattern and come back (Section 5.2, cyclic dependence).
+  bool convex(const OpSet& p) const {
+    const int words = (n + 63) / 64;
+    std::vector<uint64_t> in(words, 0), below(words, 0);
+    for (int o : p) in[o / 64] |= 1ull << (o % 64);
+    for (int o : p)
+      for (int w = 0; w < words; ++w) below[w] |= desc[o][w];
+    for (int x = 0; x < n; ++x) {
+      if ((in[x / 64] >> (x % 64)) & 1) continue;
+      if (!((below[x / 64] >> (x % 64)) & 1)) continue;
+      for (int w = 0; w < words; ++w)
+        if (desc[x][w] & in[w]) return false;
+    }
+    return true;
+  }
+
+  // The pattern as a graph of its own: operands made outside become its inputs, results read
+  // outside (or graph outputs) become its outputs.
+  fs_status extract(const OpSet& p, SubGraph* sub) const {
+    std::vector<char> inside(n, 0);
+    for (int o : p) inside[o] = 1;
+    if (fs_graph_create(&sub->g) != FS_OK) return FS_ERR_INVALID_ARG;
+    std::map<int32_t, fs_tensor> local;   // big-graph tensor -> sub tensor
+    for (int o : p) {
+      const Op& op = g.ops[o];
+      fs_tensor in[2] = {-1, -1};
+      for (int k = 0; k < op.n_in; ++k) {
+        const int32_t t = op.in[k];
+        auto it = local.find(t);
+        if (it == local.end()) {
+          const Tensor& T = g.tensors[t];
+          // what a neighbouring pattern wrote is what this one reads: an output stored in another dtype than it
+          // was computed in cannot also feed a different pattern
+          if (T.output_slot >= 0 && T.store_as != T.dtype) return FS_ERR_DTYPE;
+          const fs_tensor id = fs_graph_input(sub->g, T.dtype, T.rank, T.dims);
+          if (id < 0) return id;
+          sub->in_tensor.push_back(t);
+          it = local.emplace(t, id).first;
+        }
+        in[k] = it->second;
+      }
+      fs_tensor r;
+      const Tensor& out = g.tensors[op.out];
+      switch (op.opcode) {
+        case FS_SCALE: case FS_ADD_SCALAR: {
+          fs_attr_scalar a = {op.scalar};
+          r = fs_graph_op(sub->g, op.opcode, op.n_in, in, &a, sizeof a);
+          break;
+        }
+        case FS_BROADCAST: {
+          fs_attr_dims a;
+          a.rank = out.rank;
+          for (int k = 0; k < FS_MAX_RANK; ++k) a.dims[k] = k < out.rank ? out.dims[k] : 1;
+          r = fs_graph_op(sub->g, op.opcode, op.n_in, in, &a, sizeof a);
+          break;
+        }
+        case FS_REDUCE_SUM: case FS_REDUCE_MAX: case FS_REDUCE_MEAN: {
+          fs_attr_axis a = {op.axis};
+          r = fs_graph_op(sub->g, op.opcode, op.n_in, in, &a, sizeof a);
+          break;
+        }
+        case FS_TRANSPOSE: {
+          fs_attr_perm a;
+          for (int k = 0; k < FS_MAX_RANK; ++k) a.perm[k] = op.perm[k];
+          r = fs_graph_op(sub->g, op.opcode, op.n_in, in, &a, sizeof a);
+          break;
+        }
+        case FS_CONVERT: {
+          fs_attr_dtype a = {op.to_dtype};
+          r = fs_graph_op(sub->g, op.opcode, op.n_in, in, &a, sizeof a);
+          break;
+        }
+        default:
+          r = fs_graph_op(sub->g, op.opcode, op.n_in, in, nullptr, 0);
+          break;
+      }
+      if (r < 0) return r;
+      local[op.out] = r;
+      bool read_outside = false;
+      for (int c : out.consumers)
+        if (!inside[c]) read_outside = true;
+      if (out.output_slot >= 0 && read_outside && out.store_as != out.dtype) return FS_ERR_DTYPE;
+      if (out.output_slot >= 0 || read_outside) {
+        const fs_status s = fs_graph_output(sub->g, r, out.output_slot >= 0 ? out.store_as : out.dtype);
+        if (s != FS_OK) return s;
+        sub->out_tensor.push_back(op.out);
+      }
+    }
+    return fs_graph_finalize(sub->g);
+  }
+
+  // per-op execution of one op: one launch and one dependent memory round trip, operands read and the result
+  // written (float32 unless the op keeps a dtype)
+  double t_single(int o) const {
+    const DeviceModel& d = device();
+    const Op& op = g.ops[o];
+    double bytes = 0;
+    for (int k = 0; k < op.n_in; ++k) bytes += (double)g.tensors[op.in[k]].numel() * dtype_bytes(g.tensors[op.in[k]].dtype);
+    const Tensor& out = g.tensors[op.out];
+    bytes += (double)out.numel() * dtype_bytes(out.output_slot >= 0 ? out.store_as : out.dtype);
+    return d.launch_s + d.mem_latency_s + bytes / (d.hbm_peak_Bps * d.stream_fraction);
+  }
+
+  // Delta-evaluator (Eq. 3): time saved by running the ops of `p` as one pattern.
+  const Scored& score(const OpSet& p) {
+    auto it = memo.find(p);
+    if (it != memo.end()) return it->second;
+    Scored s;
+    for (int o : p) s.t_unfused += t_single(o);
+    if (p.size() == 1) {
+      s.valid = true;
+      s.t_fused = s.t_unfused;
+      s.f = 0;
+    } else if (!convex(p)) {
+      s.why = FS_ERR_CYCLE;
+    } else {
+      SubGraph sub;
+      const fs_status st = extract(p, &sub);
+      if (st == FS_OK) {
+        const DeviceModel& d = device();
+        s.f_optimistic = (s.t_unfused - (d.launch_s + d.mem_latency_s + (double)graph_bytes_min(*sub.g) / (d.hbm_peak_Bps * d.stream_fraction))) * 1e6;
+      }
+      std::vector<Candidate> cands;
+      if (st != FS_OK) {
+        s.why = st == FS_ERR_DTYPE ? FS_ERR_DTYPE : FS_ERR_UNSUPPORTED_PATTERN;
+      } else if (build_stitched(*sub.g, &cands, nullptr).empty() || cands.empty()) {
+        s.why = FS_ERR_UNSUPPORTED_PATTERN;
+      } else {
+        // T_penalty comes from the kernel estimate with register figures left at their estimates
+        // (the expensive part of the latency evaluator is skipped during exploration)
+        double best = 1e30;
+        for (const Candidate& c : cands) {
+          double t = evaluate(c.cost, 0).seconds;
+          if (c.launches.size() > 1) t += device().launch_s * (double)(c.launches.size() - 1);
+          best = std::min(best, t);
+        }
+        s.valid = true;
+        s.t_fused = best;
+        s.f = (s.t_unfused - s.t_fused) * 1e6;
+      }
+    }
+    return memo.emplace(p, s).first->second;
+  }
+
+  // A candidate pattern.  `tentative`: no kernel can run it as it stands, but it is convex and may grow into
+  // one that a kernel family covers; it takes part in the growth with its optimistic score and never in a plan.
+  struct Pat {
+    OpSet ops;
+    double f = 0;
+    bool tentative = false;
+  };
+  static bool better(const Pat& a, const Pat& b) {
+    if (a.f != b.f) return a.f > b.f;
+    return a.ops < b.ops;
+  }
+  // top-k runnable patterns and top-k tentative ones, each list by score
+  void keep_top(std::vector<Pat>* v) const {
+    std::sort(v->begin(), v->end(), better);
+    v->erase(std::unique(v->begin(), v->end(), [](const Pat& a, const Pat& b) { return a.ops == b.ops; }), v->end());
+    std::vector<Pat> kept;
+    int n_real = 0, n_tent = 0;
+    for (const Pat& p : *v) {
+      int& count = p.tentative ? n_tent : n_real;
+      if (count < top_k) { kept.push_back(p); ++count; }
+    }
+    v->swap(kept);
+  }
+  static OpSet unite(const OpSet& a, const OpSet& b) {
+    OpSet r;
+    std::set_union(a.begin(), a.end(), b.begin(), b.end(), std::back_inserter(r));
+    return r;
+  }
+  // a scored pattern if it is valid and gains time; a tentative one if only the kernel is missing
+  bool consider(const OpSet& ops, std::vector<Pat>* out) {
+    const Scored& s = score(ops);
+    if (s.valid) {
+      if (!(s.f > 0)) return false;
+      out->push_back(Pat{ops, s.f, false});
+      return true;
+    }
+    if (s.why == FS_ERR_UNSUPPORTED_PATTERN && s.f_optimistic > 0 && (int)ops.size() <= max_tentative_ops &&
+        !reads_own_output(ops)) {
+      out->push_back(Pat{ops, s.f_optimistic, true});
+      return true;
+    }
+    return false;
+  }
+  int max_tentative_ops = 24;
+  // A graph output is written to memory whatever the plan: growing a speculative pattern across it gains little
+  // and lets ever larger unrunnable merges crowd out the runnable pattern on either side.
+  bool reads_own_output(const OpSet& p) const {
+    for (int o : p) {
+      const Tensor& T = g.tensors[g.ops[o].out];
+      if (T.output_slot < 0) continue;
+      for (int c : T.consumers)
+        if (std::binary_search(p.begin(), p.end(), c)) return true;
+    }
+    return false;
+  }
+
+  std::vector<std::vector<Pat>> cand;   // per vertex: candidate patterns whose producer is the vertex (without the singleton)
+
+  // Temporary candidates of vertex v from one group of its consumers (Section 5.2).
+  std::vector<Pat> reduce_group(int v, const std::vector<int>& group) {
+    std::vector<Pat> out;
+    if (group.size() <= 2) {
+      // every combination of "one candidate pattern or nothing" per consumer, plus v
+      std::vector<std::vector<OpSet>> choices;
+      for (int c : group) {
+        std::vector<OpSet> ch;
+        ch.push_back(OpSet());            // do not take this consumer
+        ch.push_back(OpSet{c});           // the consumer alone
+        for (const Pat& p : cand[c]) ch.push_back(p.ops);
+        choices.push_back(ch);
+      }
+      std::vector<size_t> idx(choices.size(), 0);
+      while (true) {
+        OpSet u{v};
+        bool any = false;
+        for (size_t k = 0; k < choices.size(); ++k) {
+          if (!choices[k][idx[k]].empty()) any = true;
+          u = unite(u, choices[k][idx[k]]);
+        }
+        if (any) consider(u, &out);
+        size_t k = 0;
+        while (k < idx.size() && ++idx[k] == choices[k].size()) idx[k++] = 0;
+        if (k == idx.size()) break;
+      }
+      keep_top(&out);
+      return out;
+    }
+    // divide, conquer, and reduce: the halves' temporary candidates, and their pairwise unions
+    const size_t half = group.size() / 2;
+    const std::vector<Pat> a = reduce_group(v, std::vector<int>(group.begin(), group.begin() + half));
+    const std::vector<Pat> b = reduce_group(v, std::vector<int>(group.begin() + half, group.end()));
+    out = a;
+    out.insert(out.end(), b.begin(), b.end());
+    for (const Pat& x : a)
+      for (const Pat& y : b) consider(unite(x.ops, y.ops), &out);
+    keep_top(&out);
+    return out;
+  }
+
+  void explore_patterns() {
+    cand.assign(n, {});
+    for (int v = n - 1; v >= 0; --v)
+      if (!consumers[v].empty()) cand[v] = reduce_group(v, consumers[v]);
+    // Seeds beyond the bottom-up growth.  The growth only reaches a pattern through smaller patterns that are
+    // themselves runnable; a hand-written family (say a row pass that ends in a column reduction) is runnable
+    // as a whole while some of its parts are not.  So two whole shapes are offered directly: everything
+    // downstream of a vertex, and the connected component a vertex starts (ops joined by an edge or a shared operand).
+    std::vector<int> comp(n, -1);
+    for (int v = 0; v < n; ++v) {
+      if (comp[v] >= 0) continue;
+      std::vector<int> stack{v};
+      comp[v] = v;
+      while (!stack.empty()) {
+        const int o = stack.back();
+        stack.pop_back();
+        std::vector<int> next = consumers[o];
+        for (int k = 0; k < g.ops[o].n_in; ++k) {
+          const Tensor& operand = g.tensors[g.ops[o].in[k]];
+          if (operand.producer >= 0) next.push_back(operand.producer);
+          for (int c : operand.consumers) next.push_back(c);   // ops that share an operand belong together too
+        }
+        for (int x : next)
+          if (comp[x] < 0) { comp[x] = v; stack.push_back(x); }
+      }
+    }
+    for (int v = 0; v < n; ++v) {
+      OpSet cone{v};
+      for (int x = v + 1; x < n; ++x)
+        if ((desc[v][x / 64] >> (x % 64)) & 1) cone.push_back(x);
+      if (cone.size() > 1) consider(cone, &cand[v]);
+      if (comp[v] == v) {
+        OpSet whole;
+        for (int x = 0; x < n; ++x)
+          if (comp[x] == v) whole.push_back(x);
+        if (whole.size() > 1 && whole != cone) consider(whole, &cand[v]);
+      }
+      keep_top(&cand[v]);
+    }
+  }
+
+  // Remote fusion (Section 5.2): patterns of a plan that are not adjacent in the graph -- no edge joins them --
+  // may still share a kernel.  Greedy reading: among all pairs of the plan's patterns (single ops included)
+  // whose union is a runnable pattern, merge the pair that gains the most over running the two apart; repeat
+  // until no pair gains.  Returns the total gain (microseconds).
+  double merge_remote(std::vector<OpSet>* groups) {
+    if (groups->size() > 64) return 0.0;
+    std::sort(groups->begin(), groups->end());
+    auto f_of = [&](const OpSet& p) { return p.size() > 1 ? score(p).f : 0.0; };
+    double total = 0.0;
+    while (true) {
+      double best_gain = 0.0;
+      size_t bi = 0, bj = 0;
+      for (size_t i = 0; i < groups->size(); ++i)
+        for (size_t j = i + 1; j < groups->size(); ++j) {
+          const OpSet u = unite((*groups)[i], (*groups)[j]);
+          const Scored& s = score(u);
+          if (!s.valid) continue;
+          const double gain = s.f - f_of((*groups)[i]) - f_of((*groups)[j]);
+          if (gain > best_gain) { best_gain = gain; bi = i; bj = j; }
+        }
+      if (!(best_gain > 0.0)) break;
+      const OpSet u = unite((*groups)[bi], (*groups)[bj]);
+      groups->erase(groups->begin() + bj);
+      (*groups)[bi] = u;
+      std::sort(groups->begin(), groups->end());
+      total += best_gain;
+    }
+    return total;
+  }
+
+  struct PlanSet {
+    std::vector<OpSet> patterns;      // multi-op patterns, in the order they were appended
+    std::vector<uint64_t> covered;
+    double f = 0;
+  };
+  std::vector<PlanSet> beam() {
+    const int words = (n + 63) / 64;
+    std::vector<PlanSet> sets(1);
+    sets[0].covered.assign(words, 0);
+    for (int v = 0; v < n; ++v) {
+      std::vector<PlanSet> next = sets;
+      for (const PlanSet& s : sets) {
+        for (const Pat& p : cand[v]) {
+          if (p.tentative) continue;
+          bool overlap = false;
+          for (int o : p.ops)
+            if ((s.covered[o / 64] >> (o % 64)) & 1) { overlap = true; break; }
+          if (overlap) continue;
+          PlanSet t = s;
+          t.patterns.push_back(p.ops);
+          for (int o : p.ops) t.covered[o / 64] |= 1ull << (o % 64);
+          t.f += p.f;
+          next.push_back(t);
+        }
+      }
+      std::stable_sort(next.begin(), next.end(), [](const PlanSet& a, const PlanSet& b) {
+        if (a.f != b.f) return a.f > b.f;
+        return a.patterns < b.patterns;
+      });
+      if ((int)next.size() > beam_width) next.resize(beam_width);
+      sets.swap(next);
+    }
+    return sets;
+  }
+};
+
+}  // namespace
+}  // namespace fs
+
+using namespace fs;
+
+struct fs_program {
+  struct Step {
+    std::vector<int> ops;               // graph op indices
+    double f = 0;                       // delta-evaluator gain (microseconds), 0 for a single op
+    fs_plan* plan = nullptr;
+    std::vector<BufRef> in, out;        // where each plan input / output lives: graph input, graph output or workspace offset
+    int64_t plan_ws_offset = 0;
+    int32_t pack = -1;                  // index into packs, -1 = runs on its own
+  };
+  struct Pack {
+    fs_pack* pack = nullptr;
+    std::vector<int> steps;
+  };
+  std::vector<Step> steps;              // dependence order
+  std::vector<Pack> packs;
+  fs_program_info info{};
+  int32_t n_inputs = 0, n_outputs = 0;
+  ~fs_program() {
+    for (Step& s : steps) fs_plan_destroy(s.plan);
+    for (Pack& p : packs) fs_pack_destroy(p.pack);
+  }
+};
+
+namespace {
+
+int64_t align256(int64_t v) { return (v + 255) / 256 * 256; }
+
+// first-fit placement of [begin, end] lifetimes (in steps) into one arena
+struct Arena {
+  struct Block { int64_t off, size; int begin, end; };
+  std::vector<Block> blocks;
+  int64_t top = 0;
+  int64_t place(int64_t size, int begin, int end) {
+    size = align256(size);
+    std::vector<Block> live;
+    for (const Block& b : blocks)
+      if (!(b.end < begin || end < b.begin)) live.push_back(b);
+    std::sort(live.begin(), live.end(), [](const Block& a, const Block& b) { return a.off < b.off; });
+    int64_t off = 0;
+    for (const Block& b : live) {
+      if (off + size <= b.off) break;
+      off = std::max(off, b.off + b.size);
+    }
+    blocks.push_back({off, size, begin, end});
+    top = std::max(top, off + size);
+    return off;
+  }
+};
+
+}  // namespace
+
+extern "C" {
+
+fs_status fs_explore_score(const fs_graph* g, const int32_t* ops, int32_t n, double* f_us, double* f_optimistic_us) {
+  clear_error();
+  if (!g || !ops || !f_us) return fail(FS_ERR_INVALID_ARG, "fs_explore_score: null argument");
+  if (!g->finalized) return fail(FS_ERR_INVALID_ARG, "fs_explore_score: graph is not finalized");
+  if (n < 1) return fail(FS_ERR_INVALID_ARG, "fs_explore_score: empty pattern");
+  OpSet p(ops, ops + n);
+  std::sort(p.begin(), p.end());
+  if (std::adjacent_find(p.begin(), p.end()) != p.end() || p.front() < 0 || p.back() >= (int)g->ops.size())
+    return fail(FS_ERR_INVALID_ARG, "fs_explore_score: op indices must be distinct and inside the graph");
+  Explorer ex(*g);
+  const Scored& s = ex.score(p);
+  if (f_optimistic_us) *f_optimistic_us = s.f_optimistic;
+  if (!s.valid) {
+    if (s.why == FS_ERR_CYCLE) return fail(FS_ERR_CYCLE, "fs_explore_score: fusing these ops creates a cyclic dependence");
+    if (s.why == FS_ERR_DTYPE)
+      return fail(FS_ERR_DTYPE, "fs_explore_score: a tensor stored in another dtype than it was computed in crosses the pattern boundary");
+    return fail(FS_ERR_UNSUPPORTED_PATTERN, "fs_explore_score: no stitched kernel can run these ops as one pattern");
+  }
+  *f_us = s.f;
+  return FS_OK;
+}
+
+fs_status fs_explore(const fs_graph* g, const fs_explore_opts* opts, fs_program** out) {
+  clear_error();
+  if (!g || !out) return fail(FS_ERR_INVALID_ARG, "fs_explore: null argument");
+  if (!g->finalized) return fail(FS_ERR_INVALID_ARG, "fs_explore: graph is not finalized");
+  Explorer ex(*g);
+  bool pack_tiny = true, remote_fusion = true;
+  if (opts) {
+    if (opts->top_k < 0 || opts->beam_width < 0 || opts->top_k > 16 || opts->beam_width > 16)
+      return fail(FS_ERR_INVALID_ARG, "fs_explore: top_k and beam_width must be 0 (default 3) or 1..16");
+    if (opts->top_k > 0) ex.top_k = opts->top_k;
+    if (opts->beam_width > 0) ex.beam_width = opts->beam_width;
+    pack_tiny = opts->no_packing == 0;
+    remote_fusion = opts->no_remote_fusion == 0;
+  }
+  ex.explore_patterns();
+  const std::vector<Explorer::PlanSet> plans = ex.beam();
+
+  // Final choice among the beam's plans by the full latency evaluator: every pattern (and every op
+  // left alone) is planned for real and the predicted times are added up.
+  struct Built {
+    std::vector<fs_program::Step> steps;
+    double predicted = 0;
+    double f = 0;          // accumulated score after remote fusion
+    bool ok = false;
+  };
+  auto destroy = [](Built* b) {
+    for (fs_program::Step& s : b->steps) fs_plan_destroy(s.plan);
+    b->steps.clear();
+  };
+  std::vector<Built> built(plans.size());
+  fs_status first_error = FS_OK;
+  std::string first_text;
+  for (size_t k = 0; k < plans.size(); ++k) {
+    Built& b = built[k];
+    std::vector<OpSet> groups = plans[k].patterns;
+    for (int o = 0; o < ex.n; ++o)
+      if (!((plans[k].covered[o / 64] >> (o % 64)) & 1)) groups.push_back(OpSet{o});
+    if (remote_fusion) built[k].f = plans[k].f + ex.merge_remote(&groups);
+    else built[k].f = plans[k].f;
+    b.ok = true;
+    for (const OpSet& p : groups) {
+      SubGraph sub;
+      fs_status st = ex.extract(p, &sub);
+      if (st != FS_OK) {
+        b.ok = false;
+        if (first_error == FS_OK) {
+          first_error = st == FS_ERR_DTYPE ? FS_ERR_DTYPE : st;
+          first_text = st == FS_ERR_DTYPE ? "a tensor that is stored as a graph output in another dtype than it was computed in also feeds "
+                                            "ops that cannot join its pattern; add an explicit convert and read its result"
+                                          : fs_last_error();
+        }
+        break;
+      }
+      fs_program::Step step;
+      step.ops = p;
+      step.f = p.size() > 1 ? ex.score(p).f : 0.0;
+      st = fs_plan_create(sub.g, FS_SCHEME_AUTO, nullptr, &step.plan);
+      if (st != FS_OK) {
+        b.ok = false;
+        if (first_error == FS_OK) { first_error = st; first_text = fs_last_error(); }
+        break;
+      }
+      for (int32_t t : sub.in_tensor) {
+        BufRef r;
+        r.kind = BUF_INPUT;
+        r.slot = t;           // big-graph tensor id for now; resolved once the order is known
+        step.in.push_back(r);
+      }
+      for (int32_t t : sub.out_tensor) {
+        BufRef r;
+        r.kind = BUF_OUTPUT;
+        r.slot = t;
+        step.out.push_back(r);
+      }
+      b.predicted += step.plan->candidates[step.plan->chosen].info.predicted_us;
+      b.steps.push_back(std::move(step));
+    }
+    if (!b.ok) destroy(&b);
+  }
+  int best = -1;
+  for (size_t k = 0; k < built.size(); ++k)
+    if (built[k].ok && (best < 0 || built[k].predicted < built[best].predicted)) best = (int)k;
+  if (best < 0) {
+    for (Built& b : built) destroy(&b);
+    return fail(first_error != FS_OK ? first_error : FS_ERR_UNSUPPORTED_PATTERN, "fs_explore: %s", first_text.c_str());
+  }
+  for (size_t k = 0; k < built.size(); ++k)
+    if ((int)k != best) destroy(&built[k]);
+
+  fs_program* prog = new (std::nothrow) fs_program();
+  if (!prog) { destroy(&built[best]); return fail(FS_ERR_INVALID_ARG, "fs_explore: out of host memory"); }
+  // dependence order of the patterns: a pattern runs after every pattern that makes one of its operands.  Patterns are
+  // convex, so ordering them by their last op respects every edge between patterns.
+  std::vector<fs_program::Step>& steps = built[best].steps;
+  std::stable_sort(steps.begin(), steps.end(), [](const fs_program::Step& a, const fs_program::Step& b) { return a.ops.back() < b.ops.back(); });
+  // That order can still place a consumer before a producer whose last op comes later; repair by a topological pass.
+  {
+    std::vector<int> owner(ex.n, -1);
+    for (size_t s = 0; s < steps.size(); ++s)
+      for (int o : steps[s].ops) owner[o] = (int)s;
+    const size_t ns = steps.size();
+    std::vector<std::set<int>> deps(ns);
+    for (size_t s = 0; s < ns; ++s)
+      for (int o : steps[s].ops)
+        for (int k = 0; k < g->ops[o].n_in; ++k) {
+          const int32_t prod = g->tensors[g->ops[o].in[k]].producer;
+          if (prod >= 0 && owner[prod] != (int)s) deps[s].insert(owner[prod]);
+        }
+    std::vector<int> order;
+    std::vector<char> done(ns, 0);
+    while (order.size() < ns) {
+      bool progressed = false;
+      for (size_t s = 0; s < ns; ++s) {
+        if (done[s]) continue;
+        bool ready = true;
+        for (int d : deps[s])
+          if (!done[d]) ready = false;
+        if (ready) { done[s] = 1; order.push_back((int)s); progressed = true; }
+      }
+      if (!progressed) {   // cannot happen for convex patterns
+        delete prog;
+        destroy(&built[best]);
+        return fail(FS_ERR_CYCLE, "fs_explore: the chosen patterns depend on each other cyclically");
+      }
+    }
+    std::vector<fs_program::Step> sorted;
+    for (int s : order) sorted.push_back(std::move(steps[s]));
+    steps.swap(sorted);
+  }
+
+  prog->steps = std::move(steps);
+  steps.clear();
+  const int ns = (int)prog->steps.size();
+  std::vector<int> owner(ex.n, -1);
+  for (int s = 0; s < ns; ++s)
+    for (int o : prog->steps[s].ops) owner[o] = s;
+
+  // remote fusion: launch-bound patterns with no dependence between them share one packed launch, issued where
+  // the first of them stands; a member joins only if everything it reads is made before that point
+  std::vector<int> pos(ns);
+  for (int s = 0; s < ns; ++s) pos[s] = s;
+  if (pack_tiny) {
+    std::vector<int> level(ns, 0);
+    for (int s = 0; s < ns; ++s)
+      for (int o : prog->steps[s].ops)
+        for (int k = 0; k < g->ops[o].n_in; ++k) {
+          const int32_t prod = g->tensors[g->ops[o].in[k]].producer;
+          if (prod >= 0 && owner[prod] != s) level[s] = std::max(level[s], level[owner[prod]] + 1);
+        }
+    const double tiny_us = 2.0 * device().launch_s * 1e6;
+    std::map<int, std::vector<int>> by_level;
+    for (int s = 0; s < ns; ++s) {
+      const fs_plan* p = prog->steps[s].plan;
+      if (p->pack.spec >= 0 && p->candidates[p->chosen].info.predicted_us <= tiny_us) by_level[level[s]].push_back(s);
+    }
+    for (auto& kv : by_level) {
+      if (kv.second.size() < 2) continue;
+      std::vector<const fs_plan*> members;
+      std::vector<int> chosen;
+      const int first = kv.second.front();
+      for (int s : kv.second) {
+        bool ready = true;
+        for (const BufRef& r : prog->steps[s].in) {
+          const int32_t prod = g->tensors[r.slot].producer;
+          if (prod >= 0 && owner[prod] >= first) ready = false;
+        }
+        if (ready) { members.push_back(prog->steps[s].plan); chosen.push_back(s); }
+      }
+      if (members.size() < 2 || members.size() > FS_PACK_MAX_MEMBERS) continue;
+      fs_program::Pack pk;
+      if (fs_pack_create(members.data(), (int32_t)members.size(), &pk.pack) != FS_OK) continue;
+      pk.steps = chosen;
+      for (int s : chosen) {
+        prog->steps[s].pack = (int32_t)prog->packs.size();
+        pos[s] = first;
+      }
+      prog->packs.push_back(pk);
+    }
+    clear_error();
+  }
+
+  // where tensors that cross patterns live: placed by lifetime, from the position their maker runs at to the
+  // position of their last reader
+  std::map<int32_t, int> last_read;
+  for (int s = 0; s < ns; ++s)
+    for (const BufRef& r : prog->steps[s].in) {
+      auto it = last_read.find(r.slot);
+      if (it == last_read.end() || it->second < std::max(pos[s], s)) last_read[r.slot] = std::max(pos[s], s);
+    }
+  int64_t fixed = 0;   // plans' own workspaces: never shared, so arrival counters stay as their kernels left them
+  for (int s = 0; s < ns; ++s) {
+    const int64_t need = prog->steps[s].plan->candidates[prog->steps[s].plan->chosen].info.workspace_bytes;
+    prog->steps[s].plan_ws_offset = fixed;
+    fixed += align256(need);
+  }
+  Arena arena;
+  std::map<int32_t, int64_t> where;
+  for (int s = 0; s < ns; ++s)
+    for (const BufRef& r : prog->steps[s].out) {
+      const Tensor& T = g->tensors[r.slot];
+      if (T.output_slot >= 0) continue;
+      const int begin = pos[s];
+      const int end = std::max(begin, last_read.count(r.slot) ? last_read[r.slot] : begin);
+      where[r.slot] = fixed + arena.place(T.numel() * dtype_bytes(T.dtype), begin, end);
+    }
+  auto resolve = [&](BufRef* r) {
+    const Tensor& T = g->tensors[r->slot];
+    if (T.producer < 0) { r->kind = BUF_INPUT; r->slot = T.input_slot; }
+    else if (T.output_slot >= 0) { r->kind = BUF_OUTPUT; r->slot = T.output_slot; }
+    else { r->kind = BUF_WORKSPACE; r->offset = where[r->slot]; r->slot = 0; }
+  };
+  for (fs_program::Step& s : prog->steps) {
+    for (BufRef& r : s.in) resolve(&r);
+    for (BufRef& r : s.out) resolve(&r);
+  }
+
+  // figures
+  fs_program_info& I = prog->info;
+  I.n_ops = ex.n;
+  I.beam_plans = (int32_t)plans.size();
+  I.workspace_bytes = fixed + arena.top;
+  I.bytes_min = graph_bytes_min(*g);
+  I.f_total_us = built[best].f;
+  std::set<int> counted_packs;
+  for (const fs_program::Step& s : prog->steps) {
+    const fs_plan_info& pi = s.plan->candidates[s.plan->chosen].info;
+    if (s.ops.size() > 1) ++I.n_patterns; else ++I.n_single_ops;
+    I.bytes_moved_model += pi.bytes_moved_model;
+    if (s.pack >= 0) {
+      if (counted_packs.insert(s.pack).second) {
+        I.n_kernels += prog->packs[s.pack].pack->info.n_kernels;
+        I.predicted_us += prog->packs[s.pack].pack->info.predicted_us;
+        ++I.n_steps;
+      }
+    } else {
+      I.n_kernels += pi.n_kernels;
+      I.predicted_us += pi.predicted_us;
+      ++I.n_steps;
+    }
+  }
+  I.n_packs = (int32_t)prog->packs.size();
+  for (int o = 0; o < ex.n; ++o) I.predicted_unfused_us += ex.t_single(o) * 1e6;
+  prog->n_inputs = (int32_t)g->inputs.size();
+  prog->n_outputs = (int32_t)g->outputs.size();
+  *out = prog;
+  return FS_OK;
+}
+
+void fs_program_destroy(fs_program* p) { delete p; }
+
+fs_status fs_program_query(const fs_program* p, fs_program_info* out) {
+  clear_error();
+  if (!p || !out) return fail(FS_ERR_INVALID_ARG, "fs_program_query: null argument");
+  *out = p->info;
+  return FS_OK;
+}
+
+fs_status fs_program_pattern(const fs_program* p, int32_t index, int32_t* ops, int32_t capacity, int32_t* n_ops, double* f_us,
+                             int32_t* pack, fs_plan_info* info) {
+  clear_error();
+  if (!p) return fail(FS_ERR_INVALID_ARG, "fs_program_pattern: null argument");
+  if (index < 0 || index >= (int32_t)p->steps.size())
+    return fail(FS_ERR_INVALID_ARG, "fs_program_pattern: index %d outside 0..%zu", index, p->steps.size() - 1);
+  const fs_program::Step& s = p->steps[index];
+  if (n_ops) *n_ops = (int32_t)s.ops.size();
+  if (ops)
+    for (int32_t k = 0; k < capacity && k < (int32_t)s.ops.size(); ++k) ops[k] = s.ops[k];
+  if (f_us) *f_us = s.f;
+  if (pack) *pack = s.pack;
+  if (info) *info = s.plan->candidates[s.plan->chosen].info;
+  return FS_OK;
+}
+
+fs_status fs_program_execute(const fs_program* p, const void* const* inputs, void* const* outputs, void* workspace,
+                             size_t workspace_bytes, void* hip_stream) {
+  clear_error();
+  if (!p || !inputs || !outputs) return fail(FS_ERR_INVALID_ARG, "fs_program_execute: null argument");
+  for (int i = 0; i < p->n_inputs; ++i) {
+    if (!inputs[i]) return fail(FS_ERR_INVALID_ARG, "fs_program_execute: input %d is null", i);
+    if ((uintptr_t)inputs[i] & 15u) return fail(FS_ERR_ALIGN, "fs_program_execute: input %d is not 16-byte aligned", i);
+  }
+  for (int i = 0; i < p->n_outputs; ++i) {
+    if (!outputs[i]) return fail(FS_ERR_INVALID_ARG, "fs_program_execute: output %d is null", i);
+    if ((uintptr_t)outputs[i] & 15u) return fail(FS_ERR_ALIGN, "fs_program_execute: output %d is not 16-byte aligned", i);
+  }
+  if (p->info.workspace_bytes > 0) {
+    if (!workspace || workspace_bytes < (size_t)p->info.workspace_bytes)
+      return fail(FS_ERR_WORKSPACE, "fs_program_execute: workspace of %lld bytes needed, %zu given", (long long)p->info.workspace_bytes,
+                  workspace_bytes);
+    if ((uintptr_t)workspace & 255u) return fail(FS_ERR_ALIGN, "fs_program_execute: workspace is not 256-byte aligned");
+  }
+  char* ws = static_cast<char*>(workspace);
+  auto address = [&](const BufRef& r) -> void* {
+    if (r.kind == BUF_INPUT) return const_cast<void*>(inputs[r.slot]);
+    if (r.kind == BUF_OUTPUT) return outputs[r.slot];
+    return ws + r.offset;
+  };
+  std::vector<char> pack_done(p->packs.size(), 0);
+  std::vector<const void*> in;
+  std::vector<void*> out;
+  for (const fs_program::Step& s : p->steps) {
+    if (s.pack >= 0) {
+      if (pack_done[s.pack]) continue;
+      pack_done[s.pack] = 1;
+      in.clear();
+      out.clear();
+      for (int m : p->packs[s.pack].steps) {
+        for (const BufRef& r : p->steps[m].in) in.push_back(address(r));
+        for (const BufRef& r : p->steps[m].out) out.push_back(address(r));
+      }
+      const fs_status st = fs_pack_execute(p->packs[s.pack].pack, in.data(), out.data(), hip_stream);
+      if (st != FS_OK) return st;
+      continue;
+    }
+    in.clear();
+    out.clear();
+    for (const BufRef& r : s.in) in.push_back(address(r));
+    for (const BufRef& r : s.out) out.push_back(address(r));
+    const int64_t need = s.plan->candidates[s.plan->chosen].info.workspace_bytes;
+    const fs_status st = fs_execute(s.plan, in.data(), out.data(), need > 0 ? ws + s.plan_ws_offset : nullptr, (size_t)need, hip_stream);
+    if (st != FS_OK) return st;
+  }
+  return FS_OK;
+}
+
+}  // extern "C"

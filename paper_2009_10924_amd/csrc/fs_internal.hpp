@@ -106,6 +106,18 @@ struct fs_plan {
   int64_t bytes_min = 0;
 };
 
+// Several independent plans that run as one packed launch per 32 members.
+struct fs_pack {
+  struct Member {
+    fs::PackForm form;
+    int32_t first_input = 0, n_inputs = 0, first_output = 0;
+  };
+  std::vector<Member> members;
+  std::vector<fs::PackTable> tables;   // one per launch, pointers left null
+  fs_pack_info info{};
+  int32_t n_inputs = 0, n_outputs = 0;
+};
+
 namespace fs {
 
 // matcher + candidate enumeration (fs_match.cpp / fs_cost.cpp)

@@ -8,17 +8,6 @@
 
 #include "fs_internal.hpp"
 
-struct fs_pack {
-  struct Member {
-    fs::PackForm form;
-    int32_t first_input = 0, n_inputs = 0, first_output = 0;
-  };
-  std::vector<Member> members;
-  std::vector<fs::PackTable> tables;   // one per launch, pointers left null
-  fs_pack_info info{};
-  int32_t n_inputs = 0, n_outputs = 0;
-};
-
 namespace fs {
 namespace {
 

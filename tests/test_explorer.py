@@ -1,0 +1,174 @@
+"""Fusion explorer (paper Section 5), checked on the CPU.
+
+The library's search is compared with a plain Python restatement of the paper's procedure
+(oracle/explorer.py) that gets pattern scores from the library's delta-evaluator through a callback, with an
+exhaustive search on tiny graphs, and with structural invariants (patterns disjoint, covering, free of
+cyclic dependences).  Nothing here launches a kernel."""
+import numpy as np
+import pytest
+
+from oracle import explorer as X
+from paper_2009_10924_amd import binding as B
+from workloads import (FULL_CONFIGS, NEXT_CONFIGS, add_bias_layernorm_graph, attention_scores_graph, bias_gelu_dbias_graph,
+                       layernorm_backward_graph, layernorm_stats_graph, random_multi_pattern, random_row_pattern,
+                       softmax_graph, transformer_block_graph, transpose_chain_graph)
+from workloads.graphs import GraphSpec, OpSpec, TensorSpec
+
+
+def _score_fn(graph):
+    def score(ops):
+        f, f_opt, code = B.explore_score_ex(graph, list(ops))
+        return (0 if code == 0 else ("unsupported" if code == -5 else code)), f, f_opt
+    return score
+
+
+def _explore_both(spec, **opts):
+    g = B.Graph.from_spec(spec)
+    prog = B.Program(g, **opts)
+    view = X.GraphView(spec)
+    cand, plans = X.explore(view, _score_fn(g), top_k=opts.get("top_k", 0) or 3, beam_width=opts.get("beam_width", 0) or 3)
+    return prog, view, cand, plans
+
+
+def _multi(prog):
+    return sorted(tuple(p["ops"]) for p in prog.patterns() if len(p["ops"]) > 1)
+
+
+SPECS = {
+    "transformer_block_small": lambda: transformer_block_graph(2, 16, 2, 8, 64, "bf16"),
+    "transformer_block": lambda: transformer_block_graph(32, 128, 12, 64, 3072, "bf16"),
+    "softmax": lambda: softmax_graph(64, 128, "f32"),
+    "layernorm": lambda: add_bias_layernorm_graph(128, 768),
+    "attention": lambda: attention_scores_graph(2, 3, 16, 64),
+    "gelu_dbias": lambda: bias_gelu_dbias_graph(256, 512),
+    "transpose_chain": lambda: transpose_chain_graph(2, 16, 4, 64),
+    "layernorm_backward": lambda: layernorm_backward_graph(64, 256, "f32"),
+    "layernorm_stats": lambda: layernorm_stats_graph(64, 256),
+}
+SPECS.update({f"multi{s}": (lambda s=s: random_multi_pattern(s)) for s in range(16)})
+SPECS.update({f"multi_big{s}": (lambda s=s: random_multi_pattern(100 + s, rows=512, cols=1024, segments=4)) for s in range(4)})
+
+
+@pytest.mark.parametrize("name", sorted(SPECS))
+def test_library_plan_is_one_of_the_oracle_beam_plans(name):
+    spec = SPECS[name]()
+    prog, view, cand, plans = _explore_both(spec)
+    g = B.Graph.from_spec(spec)
+    score = _score_fn(g)
+
+    def finished(plan):       # the beam plan after remote fusion: its multi-op groups and its total score
+        groups, gain = X.remote_fusion(plan[0], len(spec.ops), score)
+        return sorted(p for p in groups if len(p) > 1), plan[1] + gain
+    got = _multi(prog)
+    beam = [finished(p) for p in plans]
+    assert got in [b[0] for b in beam], f"{name}: library chose {got}, the oracle's beam holds {beam}"
+    f_oracle = beam[[b[0] for b in beam].index(got)][1]
+    assert abs(prog.info["f_total_us"] - f_oracle) <= 1e-9 * max(1.0, abs(f_oracle))
+    # with a beam of one there is no final choice left: the plans must be identical
+    prog1, _, _, plans1 = _explore_both(spec, beam_width=1)
+    want1 = finished(plans1[0])
+    assert _multi(prog1) == want1[0]
+    assert abs(prog1.info["f_total_us"] - want1[1]) <= 1e-9 * max(1.0, abs(want1[1]))
+    # and without remote fusion the beam plans themselves
+    prog2 = B.Program(g, no_remote_fusion=True)
+    assert _multi(prog2) in [sorted(p) for p, _ in plans]
+
+
+@pytest.mark.parametrize("name", sorted(SPECS))
+def test_plan_structure(name):
+    spec = SPECS[name]()
+    g = B.Graph.from_spec(spec)
+    prog = B.Program(g)
+    view = X.GraphView(spec)
+    steps = prog.patterns()
+    seen = set()
+    done = set()
+    for st in steps:
+        ops = st["ops"]
+        assert ops == sorted(ops) and not (seen & set(ops))
+        seen |= set(ops)
+        inside = set(ops)
+        # convex: nothing outside lies between two members
+        below = set().union(*(view.desc[o] for o in ops)) - inside
+        assert not any(view.desc[x] & inside for x in below), f"{name}: pattern {ops} has a cyclic dependence"
+        # execution order: every producer outside the pattern has run
+        for o in ops:
+            assert all(p in done or p in inside for p in view.producers[o]), f"{name}: {ops} runs before its producers"
+        done |= inside
+        if len(ops) > 1:
+            assert st["f_us"] > 0 and st["info"]["scheme"] != "unfused"
+            assert abs(st["f_us"] - B.explore_score(g, ops)) < 1e-9
+    assert seen == set(range(len(spec.ops)))
+    info = prog.info
+    assert info["n_patterns"] + info["n_single_ops"] == len(steps)
+    assert info["n_kernels"] <= len(spec.ops) and info["predicted_us"] > 0
+    assert abs(info["f_total_us"] - sum(s["f_us"] for s in steps)) < 1e-6
+
+
+def test_transformer_block_plan_is_the_hand_partition():
+    spec = transformer_block_graph(32, 128, 12, 64, 3072, "bf16")
+    prog = B.Program(B.Graph.from_spec(spec))
+    steps = prog.patterns()
+    names = sorted((s["info"]["pattern"], len(s["ops"])) for s in steps)
+    assert names == sorted([("transpose", 1)] * 4 + [("softmax", 7), ("layernorm", 12), ("bias_gelu", 2), ("layernorm", 12)])
+    assert prog.info["n_kernels"] == 8 and prog.info["workspace_bytes"] == 0   # every tensor between patterns is a graph output
+    # the second LayerNorm reads what the first one stored
+    order = [tuple(s["ops"]) for s in steps]
+    assert order.index(tuple(range(11, 23))) < order.index(tuple(range(25, 37)))
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_explorer_against_exhaustive_search_on_tiny_graphs(seed):
+    if seed % 2:
+        spec = random_multi_pattern(200 + seed, rows=8, cols=16, segments=2)
+    else:
+        spec = random_row_pattern(300 + seed, 8, 16, "f32", n_ops=5 + seed % 4)
+    if len(spec.ops) > 10:
+        pytest.skip("too many ops for the exhaustive search")
+    g = B.Graph.from_spec(spec)
+    best = X.brute_force_best(X.GraphView(spec), _score_fn(g))
+    got = B.Program(g).info["f_total_us"]
+    assert got <= best + 1e-9
+    assert got >= 0.9 * best - 1e-9, f"explorer found {got:.3f} us of gain, exhaustive search {best:.3f}"
+
+
+def test_delta_evaluator_terms():
+    # f = reduced memory time + reduced launches - penalty: for a pure element-wise chain of n ops over N elements
+    # fused into one kernel, the gain grows with n and with N
+    def chain(n, rows):
+        ops = [OpSpec("v0", "exp", ("x",))] + [OpSpec(f"v{i}", "tanh", (f"v{i-1}",)) for i in range(1, n)]
+        return GraphSpec("pattern_chain", [TensorSpec("x", "f32", (rows, 256))], ops, [(f"v{n-1}", "f32")])
+    f = {(n, rows): B.explore_score(B.Graph.from_spec(chain(n, rows)), list(range(n))) for n in (2, 4) for rows in (64, 8192)}
+    assert 0 < f[(2, 64)] < f[(4, 64)] and f[(2, 8192)] < f[(4, 8192)] and f[(2, 64)] < f[(2, 8192)]
+    # a tiny tensor: the gain is about the launches (and their memory round trips) saved
+    assert f[(4, 64)] > 2.0 * 2.2 and f[(2, 64)] < 2.0 * 3.4
+    assert B.explore_score(B.Graph.from_spec(chain(3, 64)), [1]) == 0.0
+
+
+def test_explorer_errors_and_cycles():
+    # A -> B -> C and A -> C: fusing A and C without B would put B between them
+    spec = GraphSpec("pattern_tri", [TensorSpec("x", "f32", (8, 16))],
+                     [OpSpec("a", "exp", ("x",)), OpSpec("b", "transpose", ("a",), {"perm": (1, 0)}),
+                      OpSpec("bt", "transpose", ("b",), {"perm": (1, 0)}), OpSpec("c", "add", ("a", "bt"))], [("c", "f32")])
+    g = B.Graph.from_spec(spec)
+    f, f_opt, code = B.explore_score_ex(g, [0, 3])
+    assert code == -4 and f is None                     # FS_ERR_CYCLE
+    f, f_opt, code = B.explore_score_ex(g, [0, 1])
+    assert code == -5 and f_opt > 0                     # convex, but no kernel runs exp + transpose
+    prog = B.Program(g)
+    assert sorted(len(p["ops"]) for p in prog.patterns()) == [1, 1, 1, 1]
+    with pytest.raises(B.FsError):
+        B.explore_score(g, [0, 0])
+    with pytest.raises(B.FsError):
+        B.explore_score(g, [7])
+    # an output stored narrower than computed that also feeds another pattern: refused, with advice
+    spec = GraphSpec("pattern_narrow", [TensorSpec("x", "f32", (8, 16))],
+                     [OpSpec("a", "exp", ("x",)), OpSpec("t", "transpose", ("a",), {"perm": (1, 0)})], [("a", "bf16"), ("t", "f32")])
+    with pytest.raises(B.FsError) as e:
+        B.Program(B.Graph.from_spec(spec))
+    assert e.value.code == -3 and "convert" in e.value.text
+    lib = B.load()
+    assert lib.fs_explore(None, None, None) == -1
+    assert lib.fs_program_query(None, None) == -1
+    assert lib.fs_program_execute(None, None, None, None, 0, None) == -1
+    lib.fs_program_destroy(None)

@@ -419,6 +419,85 @@ def random_row_pattern(seed: int, rows: int, cols: int, dtype: str = "f32", n_op
     return GraphSpec(name=f"pattern_random{seed}_{dtype}_{rows}x{cols}", inputs=inputs, ops=ops, outputs=outputs)
 
 
+# ---- graphs that hold many fusion patterns (input of the fusion explorer) ----
+def _layernorm_ops(prefix: str, x: str, res: str, bias: str, gamma: str, beta: str, eps: float, out_dtype: str) -> List[OpSpec]:
+    p = prefix
+    return [
+        _op(p + "h0", "add", x, res), _op(p + "h", "add", p + "h0", bias),
+        _op(p + "mu", "reduce_mean", p + "h", axis=1), _op(p + "c", "sub", p + "h", p + "mu"),
+        _op(p + "q", "square", p + "c"), _op(p + "v", "reduce_mean", p + "q", axis=1),
+        _op(p + "ve", "add_scalar", p + "v", value=float(eps)), _op(p + "r", "rsqrt", p + "ve"),
+        _op(p + "n", "mul", p + "c", p + "r"), _op(p + "g", "mul", p + "n", gamma), _op(p + "o", "add", p + "g", beta),
+        _op(p + "out", "convert", p + "o", dtype=out_dtype),
+    ]
+
+
+def transformer_block_graph(batch: int = 32, seq: int = 128, heads: int = 12, dim: int = 64, ffn: int = 3072,
+                            dtype: str = "bf16") -> GraphSpec:
+    """The memory-intensive ops of one transformer encoder block, with the matrix products taken out: their
+    results come in as graph inputs.  Head split / merge transposes, scale + mask + softmax, output bias +
+    residual + LayerNorm, feed-forward bias + GELU, second bias + residual + LayerNorm that reads the first
+    one's stored result (37 ops, 8 patterns by hand)."""
+    hidden, rows = heads * dim, batch * seq
+    t4 = (batch, seq, heads, dim)
+    inputs = [
+        TensorSpec("q_lin", dtype, t4), TensorSpec("k_lin", dtype, t4), TensorSpec("v_lin", dtype, t4),
+        TensorSpec("scores", dtype, (batch, heads, seq, seq)), TensorSpec("mask", dtype, (batch, 1, 1, seq)),
+        TensorSpec("ctx", dtype, (batch, heads, seq, dim)),
+        TensorSpec("attn_out", dtype, (rows, hidden)), TensorSpec("x", dtype, (rows, hidden)),
+        TensorSpec("bias_o", dtype, (hidden,)), TensorSpec("gamma1", dtype, (hidden,)), TensorSpec("beta1", dtype, (hidden,)),
+        TensorSpec("ffn1_out", dtype, (rows, ffn)), TensorSpec("bias1", dtype, (ffn,)),
+        TensorSpec("ffn2_out", dtype, (rows, hidden)), TensorSpec("bias2", dtype, (hidden,)),
+        TensorSpec("gamma2", dtype, (hidden,)), TensorSpec("beta2", dtype, (hidden,)),
+    ]
+    ops = [
+        _op("qt", "transpose", "q_lin", perm=(0, 2, 1, 3)), _op("kt", "transpose", "k_lin", perm=(0, 2, 1, 3)),
+        _op("vt", "transpose", "v_lin", perm=(0, 2, 1, 3)),
+        _op("sc", "scale", "scores", value=float(dim) ** -0.5), _op("sa", "add", "sc", "mask"),
+    ] + _softmax_ops("sa", 3, prefix="p_") + [
+        _op("ctx_t", "transpose", "ctx", perm=(0, 2, 1, 3)),
+    ] + _layernorm_ops("l1_", "attn_out", "x", "bias_o", "gamma1", "beta1", 1e-5, dtype) + [
+        _op("f_a", "add", "ffn1_out", "bias1"), _op("act", "gelu_tanh", "f_a"),
+    ] + _layernorm_ops("l2_", "ffn2_out", "l1_out", "bias2", "gamma2", "beta2", 1e-5, dtype)
+    outputs = [("qt", dtype), ("kt", dtype), ("vt", dtype), ("p_y", dtype), ("ctx_t", dtype), ("l1_out", dtype),
+               ("act", dtype), ("l2_out", dtype)]
+    return GraphSpec(name=f"pattern_transformer_block_{dtype}_b{batch}_s{seq}", inputs=inputs, ops=ops, outputs=outputs)
+
+
+def random_multi_pattern(seed: int, rows: int = 24, cols: int = 32, segments: int = 3, dtype: str = "f32") -> GraphSpec:
+    """Several random row patterns chained through transposes (each transpose turns the previous segment's
+    columns into rows, so no single row kernel can span it) plus an independent side pattern."""
+    import random
+    rnd = random.Random(1000 + seed)
+    inputs: List[TensorSpec] = []
+    ops: List[OpSpec] = []
+    outputs: List[Tuple[str, str]] = []
+    carry = None
+    r, c = rows, cols
+    for s in range(segments):
+        seg = random_row_pattern(seed * 17 + s, r, c, dtype, n_ops=rnd.randint(3, 9))
+        ren = {t.name: f"s{s}_{t.name}" for t in seg.inputs}
+        ren.update({o.out: f"s{s}_{o.out}" for o in seg.ops})
+        seg_inputs = list(seg.inputs)
+        if carry is not None:
+            ren[seg_inputs[0].name] = carry                      # the first full input is the transposed carry
+            seg_inputs = seg_inputs[1:]
+        inputs += [TensorSpec(ren[t.name], t.dtype, t.dims) for t in seg_inputs]
+        ops += [OpSpec(ren[o.out], o.opcode, tuple(ren[i] for i in o.inputs), dict(o.attr)) for o in seg.ops]
+        main = ren[seg.outputs[0][0]]
+        for name, dt in seg.outputs[1:]:
+            outputs.append((ren[name], dt))
+        if s + 1 < segments:
+            cv = f"s{s}_cv"
+            ops.append(_op(cv, "convert", main, dtype=dtype))     # transposes move stored values
+            carry = f"s{s}_t"
+            ops.append(_op(carry, "transpose", cv, perm=(1, 0)))
+            r, c = c, r
+        else:
+            outputs.append((main, dtype))
+    return GraphSpec(name=f"pattern_multi{seed}_{dtype}_{rows}x{cols}", inputs=inputs, ops=ops, outputs=outputs)
+
+
 def pack_members_p1() -> List[GraphSpec]:
     """P1: 32 independent tiny subgraphs (each a few microseconds or less on its own, so launch-bound when run
     one kernel each): the many-small-kernels regime that kernel packing addresses."""
@@ -432,6 +511,9 @@ def pack_members_p1() -> List[GraphSpec]:
 
 
 PACK_CONFIGS = {"P1": pack_members_p1}
+
+# Multi-pattern graphs for the fusion explorer.
+EXPLORE_CONFIGS = {"T1": lambda: transformer_block_graph(32, 128, 12, 64, 3072, "bf16")}
 
 # Row-local patterns outside the hand-written families, at transformer-block sizes (interpreted row program).
 GENERIC_CONFIGS = {

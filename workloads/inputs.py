@@ -70,15 +70,16 @@ def make_inputs(graph: GraphSpec, seed: int = 0) -> Dict[str, np.ndarray]:
       softmax_backward   y ~ Dirichlet(1,..,1) per row (positive, rows sum to 1); dy ~ N(0,1)
       rmsnorm            x ~ N(0,1); gamma ~ 1+N(0,0.02)
       layernorm_backward h, dy ~ N(0,1); gamma ~ 1+N(0,0.02); mu ~ N(0,0.05); rstd ~ U(0.8,1.2)
-      pattern (any other row-local pattern) by tensor name: g* ~ 1+N(0,0.02); r* ~ U(0.8,1.2); mu* ~ N(0,0.05);
-                         bias*, beta* ~ N(0,0.02); everything else ~ N(0,1)
+      pattern (any other pattern or multi-pattern graph) by tensor name (a segment prefix s<k>_ is ignored):
+                         g* ~ 1+N(0,0.02); r* ~ U(0.8,1.2); mu* ~ N(0,0.05); bias*, beta* ~ N(0,0.02);
+                         mask* 0 / -10000 from per-batch valid length; everything else ~ N(0,1)
     """
     kind = _kind(graph)
     cfg = CONFIG_INDEX[kind]
     out: Dict[str, np.ndarray] = {}
     for ti, t in enumerate(graph.inputs):
         g = _rng(seed, cfg, ti)
-        n = t.name
+        n = key = t.name
         if kind == "softmax":
             a = g.standard_normal(t.dims)
         elif kind == "add_bias_layernorm":
@@ -112,6 +113,14 @@ def make_inputs(graph: GraphSpec, seed: int = 0) -> Dict[str, np.ndarray]:
             else:
                 a = g.uniform(0.8, 1.2, t.dims)
         elif kind == "pattern":
+            base = n.split("_", 1)[1] if n[0] == "s" and "_" in n and n[1:n.index("_")].isdigit() else n   # segment prefix s<k>_
+            if base.startswith("mask"):
+                batch, k_len = t.dims[0], t.dims[-1]
+                lens = valid_lengths(batch, k_len, seed)
+                a = np.where(np.arange(k_len)[None, :] < lens[:, None], 0.0, -10000.0).reshape(t.dims)
+                out[key] = quantise(a, t.dtype)
+                continue
+            n = base
             if n.startswith("g"):
                 a = 1.0 + 0.02 * g.standard_normal(t.dims)
             elif n.startswith("r") and n != "res":
@@ -138,5 +147,5 @@ def make_inputs(graph: GraphSpec, seed: int = 0) -> Dict[str, np.ndarray]:
             continue
         else:  # pragma: no cover
             raise ValueError(kind)
-        out[n] = quantise(a, t.dtype)
+        out[key] = quantise(a, t.dtype)
     return out
