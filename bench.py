@@ -239,6 +239,57 @@ def measure_pack(name, steps, warmup):
             "predicted_us": pack.info["predicted_us"], "predicted_separate_us": pack.info["predicted_separate_us"]}
 
 
+def measure_program(name, steps, warmup):
+    """A multi-pattern graph cut into fusion patterns by the explorer, against the same graph one kernel per op."""
+    import torch
+    from paper_2009_10924_amd import binding as B
+    from workloads import EXPLORE_CONFIGS, make_inputs
+    spec = EXPLORE_CONFIGS[name]()
+    g = B.Graph.from_spec(spec)
+    t0 = time.perf_counter()
+    prog = B.Program(g)
+    explore_ms = (time.perf_counter() - t0) * 1e3
+    info = prog.info
+    host = make_inputs(spec, 0)
+    first = [B.to_device(host[t.name], t.dtype) for t in spec.inputs]
+    n_sets = min(_sets_needed(info["bytes_min"] + info["workspace_bytes"]), 64)
+    inputs = [first] + [[t.clone() for t in first] for _ in range(n_sets - 1)]
+    outputs = [B.alloc_outputs(spec) for _ in range(n_sets)]
+    stream = torch.cuda.current_stream().cuda_stream
+    ws = [prog.make_workspace() for _ in range(n_sets)]
+    calls = [prog.bind([t.data_ptr() for t in i], [t.data_ptr() for t in o], w.data_ptr(), w.numel(), stream)
+             for i, o, w in zip(inputs, outputs, ws)]
+    unf = B.Plan(g, "unfused")
+    uws = [unf.make_workspace() for _ in range(2)]
+    ucalls = [unf.bind([t.data_ptr() for t in inputs[k]], [t.data_ptr() for t in outputs[k]],
+                       uws[k].data_ptr() if uws[k] is not None else 0, uws[k].numel() if uws[k] is not None else 0, stream)
+              for k in range(2)]
+
+    def timed(fns, n):
+        for k in range(warmup):
+            fns[k % len(fns)]()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for k in range(n):
+            fns[k % len(fns)]()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / n
+
+    t_prog = timed(calls, steps)
+    t_unf = timed(ucalls, max(5, steps // 8))
+    steps_info = prog.patterns()
+    return {"workload": spec.name, "ops": info["n_ops"], "patterns": info["n_patterns"], "single_ops": info["n_single_ops"],
+            "launches": info["n_kernels"], "packs": info["n_packs"], "workspace_bytes": info["workspace_bytes"],
+            "bytes_min": info["bytes_min"], "us": t_prog, "GBps": info["bytes_min"] / t_prog / 1e3,
+            "frac_of_peak": info["bytes_min"] / t_prog / 1e3 / HBM_PEAK_GBPS,
+            "unfused_us": t_unf, "unfused_launches": unf.info["n_kernels"], "speedup_vs_unfused": t_unf / t_prog,
+            "predicted_us": info["predicted_us"], "delta_evaluator_gain_us": info["f_total_us"], "explore_ms": explore_ms,
+            "plan": [{"ops": len(s["ops"]), "pattern": s["info"]["pattern"], "kernel": s["info"]["kernel"]} for s in steps_info],
+            "buffer_sets": n_sets}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -335,6 +386,8 @@ def main():
         torch.cuda.empty_cache()
         # row-local patterns outside the hand-written families: one interpreted kernel each
         from workloads import GENERIC_CONFIGS
+        result["explorer"] = measure_program("T1", max(100, args.steps // 8), 10)
+        torch.cuda.empty_cache()
         result["generic_patterns"] = {name: measure_config(name, GENERIC_CONFIGS[name](), max(50, args.steps // 8), 10)
                                       for name in ("G1", "G2", "G3", "G4")}
     print(json.dumps(result))

@@ -657,7 +657,7 @@ fs_status fs_explore(const fs_graph* g, const fs_explore_opts* opts, fs_program*
           const int32_t prod = g->tensors[g->ops[o].in[k]].producer;
           if (prod >= 0 && owner[prod] != s) level[s] = std::max(level[s], level[owner[prod]] + 1);
         }
-    const double tiny_us = 2.0 * device().launch_s * 1e6;
+    const double tiny_us = 3.0 * device().launch_s * 1e6;   // the launch is a third or more of the pattern's estimated time
     std::map<int, std::vector<int>> by_level;
     for (int s = 0; s < ns; ++s) {
       const fs_plan* p = prog->steps[s].plan;

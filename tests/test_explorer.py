@@ -117,6 +117,19 @@ def test_transformer_block_plan_is_the_hand_partition():
     assert order.index(tuple(range(11, 23))) < order.index(tuple(range(25, 37)))
 
 
+def test_independent_launch_bound_patterns_share_one_packed_launch():
+    from workloads import independent_tiny_patterns_graph
+    spec = independent_tiny_patterns_graph()
+    g = B.Graph.from_spec(spec)
+    prog = B.Program(g)
+    steps = prog.patterns()
+    assert prog.info["n_patterns"] == 8 and prog.info["n_packs"] == 1 and prog.info["n_kernels"] == 1
+    assert all(s["pack"] == 0 for s in steps)
+    apart = B.Program(g, no_packing=True)
+    assert apart.info["n_packs"] == 0 and apart.info["n_kernels"] == 8
+    assert prog.info["predicted_us"] < apart.info["predicted_us"]
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_explorer_against_exhaustive_search_on_tiny_graphs(seed):
     if seed % 2:

@@ -1,0 +1,115 @@
+"""GPU parity of explored programs: a multi-pattern graph is cut into fusion patterns by the explorer, every
+pattern runs as its own stitched plan (or packed launch), tensors between patterns go through the workspace;
+all graph outputs are compared with the float64 oracle evaluated on the whole graph."""
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+from paper_2009_10924_amd import binding as B
+from tests.gpu_util import TOL, note
+from workloads import EXPLORE_CONFIGS, make_inputs, random_multi_pattern, random_row_pattern, transformer_block_graph
+
+pytestmark = pytest.mark.gpu
+
+
+def run_program(spec, inputs_np, repeat=2, **opts):
+    import torch
+    g = B.Graph.from_spec(spec)
+    prog = B.Program(g, **opts)
+    dev_in = [B.to_device(inputs_np[t.name], t.dtype) for t in spec.inputs]
+    dev_out = B.alloc_outputs(spec)
+    for t in dev_out:
+        t.fill_(float("nan"))
+    ws = prog.make_workspace()
+    stream = torch.cuda.current_stream().cuda_stream
+    call = prog.bind([t.data_ptr() for t in dev_in], [t.data_ptr() for t in dev_out], ws.data_ptr(), ws.numel(), stream)
+    results = []
+    for _ in range(repeat):
+        call()
+        torch.cuda.synchronize()
+        results.append({name: B.to_host(t, dt).copy() for (name, dt), t in zip(spec.outputs, dev_out)})
+    for r in results[1:]:
+        for name in r:
+            assert np.array_equal(r[name].view(np.uint8), results[0][name].view(np.uint8)), f"{name}: not run-to-run identical"
+    return {name: O.to_f64(results[0][name], dt) for name, dt in spec.outputs}, prog
+
+
+def compare(spec, seed=0, **opts):
+    inp = make_inputs(spec, seed=seed)
+    ref = O.evaluate(spec, inp)
+    got, prog = run_program(spec, inp, **opts)
+    worst = 0.0
+    for name, dt in spec.outputs:
+        assert np.isfinite(got[name]).all(), f"{spec.name}/{name}: non-finite values"
+        err = O.max_rel_err(got[name], ref[name].reshape(got[name].shape), O.rms(ref[name]))
+        assert err <= TOL[dt], f"{spec.name}/{name}: max rel err {err:.3e} > {TOL[dt]:.0e}"
+        worst = max(worst, err / TOL[dt])
+    return worst, prog
+
+
+@pytest.mark.parametrize("dims", [(2, 16, 2, 8, 64), (3, 40, 4, 32, 256), (32, 128, 12, 64, 3072)])
+def test_transformer_block(dims):
+    spec = transformer_block_graph(*dims, "bf16")
+    worst, prog = compare(spec)
+    info = prog.info
+    note(f"transformer block {dims}: {info['n_ops']} ops -> {info['n_patterns']} patterns + {info['n_single_ops']} single ops, "
+         f"{info['n_kernels']} launches, {info['n_packs']} packs, workspace {info['workspace_bytes']} B, worst {worst:.3f} of the bar")
+    # transposes are bit-exact copies of stored values
+    inp = make_inputs(spec, seed=0)
+    got, _ = run_program(spec, inp, repeat=1)
+    want = O.to_f64(inp["q_lin"], "bf16").transpose(0, 2, 1, 3)
+    assert np.array_equal(got["qt"], want)
+
+
+def test_transformer_block_without_packing_and_remote_fusion():
+    spec = transformer_block_graph(2, 16, 2, 8, 64, "bf16")
+    a, pa = compare(spec, no_packing=True)
+    b, pb = compare(spec, no_remote_fusion=True, no_packing=True)
+    note(f"small block: {pa.info['n_kernels']} launches without packing, {pb.info['n_kernels']} without remote fusion either")
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_multi_pattern_programs(seed):
+    rows, cols = [(24, 32), (130, 64), (64, 520), (8, 1024)][seed % 4]
+    spec = random_multi_pattern(seed, rows=rows, cols=cols, segments=2 + seed % 3)
+    worst, prog = compare(spec, seed=seed)
+    info = prog.info
+    note(f"multi pattern {seed} {rows}x{cols}: {info['n_ops']} ops -> {info['n_kernels']} launches "
+         f"({info['n_patterns']} patterns, {info['n_packs']} packs), workspace {info['workspace_bytes']} B, worst {worst:.3f} of the bar")
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_single_pattern_graphs_through_the_explorer(seed):
+    spec = random_row_pattern(500 + seed, 37, 128, ("f32", "f16", "bf16")[seed % 3], n_ops=6 + seed)
+    worst, prog = compare(spec, seed=seed)
+    note(f"row pattern {seed}: {prog.info['n_ops']} ops -> {prog.info['n_kernels']} launches, worst {worst:.3f}")
+
+
+def test_independent_tiny_patterns_run_as_one_packed_launch():
+    from workloads import independent_tiny_patterns_graph
+    spec = independent_tiny_patterns_graph()
+    worst, prog = compare(spec)
+    assert prog.info["n_packs"] == 1 and prog.info["n_kernels"] == 1
+    worst2, apart = compare(spec, no_packing=True)
+    assert apart.info["n_kernels"] == 8
+    note(f"eight independent tiny patterns: 1 packed launch (worst {worst:.3f} of the bar), 8 launches apart (worst {worst2:.3f})")
+
+
+def test_program_execute_errors():
+    import torch
+    spec = random_multi_pattern(1)
+    g = B.Graph.from_spec(spec)
+    prog = B.Program(g)
+    inp = make_inputs(spec)
+    dev_in = [B.to_device(inp[t.name], t.dtype) for t in spec.inputs]
+    dev_out = B.alloc_outputs(spec)
+    stream = torch.cuda.current_stream().cuda_stream
+    if prog.info["workspace_bytes"] > 0:
+        with pytest.raises(B.FsError) as e:
+            prog.bind([t.data_ptr() for t in dev_in], [t.data_ptr() for t in dev_out], 0, 0, stream)()
+        assert e.value.code == -7
+    ws = prog.make_workspace()
+    with pytest.raises(B.FsError) as e:
+        prog.bind([t.data_ptr() for t in dev_in], [dev_out[0].data_ptr() + 4] + [t.data_ptr() for t in dev_out[1:]], ws.data_ptr(), ws.numel(), stream)()
+    assert e.value.code == -8
+    torch.cuda.synchronize()

@@ -498,6 +498,26 @@ def random_multi_pattern(seed: int, rows: int = 24, cols: int = 32, segments: in
     return GraphSpec(name=f"pattern_multi{seed}_{dtype}_{rows}x{cols}", inputs=inputs, ops=ops, outputs=outputs)
 
 
+def independent_tiny_patterns_graph() -> GraphSpec:
+    """One graph that holds eight small patterns with no edge between them and different row spaces (two row
+    softmaxes, two residual LayerNorms, two RMSNorms, two softmax backwards): the explorer can only join them
+    by packing their launches."""
+    members = [softmax_graph(64, 128, "f32"), softmax_graph(96, 256, "f32"),
+               add_bias_layernorm_graph(128, 768, in_dtype="bf16", out_dtype="bf16"),
+               add_bias_layernorm_graph(48, 1024, in_dtype="bf16", out_dtype="bf16"),
+               rmsnorm_graph(64, 2048, dtype="bf16"), rmsnorm_graph(40, 512, dtype="bf16"),
+               softmax_backward_graph(384, 64, "f16"), softmax_backward_graph(100, 320, "f16")]
+    inputs: List[TensorSpec] = []
+    ops: List[OpSpec] = []
+    outputs: List[Tuple[str, str]] = []
+    for k, m in enumerate(members):
+        ren = lambda n, k=k: f"s{k}_{n}"
+        inputs += [TensorSpec(ren(t.name), t.dtype, t.dims) for t in m.inputs]
+        ops += [OpSpec(ren(o.out), o.opcode, tuple(ren(i) for i in o.inputs), dict(o.attr)) for o in m.ops]
+        outputs += [(ren(n), dt) for n, dt in m.outputs]
+    return GraphSpec(name="pattern_independent_tiny", inputs=inputs, ops=ops, outputs=outputs)
+
+
 def pack_members_p1() -> List[GraphSpec]:
     """P1: 32 independent tiny subgraphs (each a few microseconds or less on its own, so launch-bound when run
     one kernel each): the many-small-kernels regime that kernel packing addresses."""
