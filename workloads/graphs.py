@@ -464,7 +464,8 @@ def transformer_block_graph(batch: int = 32, seq: int = 128, heads: int = 12, di
     return GraphSpec(name=f"pattern_transformer_block_{dtype}_b{batch}_s{seq}", inputs=inputs, ops=ops, outputs=outputs)
 
 
-def random_multi_pattern(seed: int, rows: int = 24, cols: int = 32, segments: int = 3, dtype: str = "f32") -> GraphSpec:
+def random_multi_pattern(seed: int, rows: int = 24, cols: int = 32, segments: int = 3, dtype: str = "f32",
+                         seg_ops: Tuple[int, int] = (3, 9)) -> GraphSpec:
     """Several random row patterns chained through transposes (each transpose turns the previous segment's
     columns into rows, so no single row kernel can span it) plus an independent side pattern."""
     import random
@@ -475,7 +476,7 @@ def random_multi_pattern(seed: int, rows: int = 24, cols: int = 32, segments: in
     carry = None
     r, c = rows, cols
     for s in range(segments):
-        seg = random_row_pattern(seed * 17 + s, r, c, dtype, n_ops=rnd.randint(3, 9))
+        seg = random_row_pattern(seed * 17 + s, r, c, dtype, n_ops=rnd.randint(*seg_ops))
         ren = {t.name: f"s{s}_{t.name}" for t in seg.inputs}
         ren.update({o.out: f"s{s}_{o.out}" for o in seg.ops})
         seg_inputs = list(seg.inputs)
