@@ -17,11 +17,14 @@ What the paper fixes, and how it is read here (each reading is listed in the des
     would have at streaming rate) so that it can grow into one a kernel family covers; tentative
     patterns never enter a plan and are not grown across a graph output.
   * Section 5.3: beam search of width 3 over the vertices from producers to consumers, appending a
-    vertex's candidate patterns to every kept plan they do not overlap, ranking by accumulated score.
+    vertex's candidate patterns to every kept plan they do not overlap, ranking by accumulated score plus a
+    look-ahead over the ops not visited yet (best score per op of any candidate holding the op); at the last
+    vertex this is the paper's ranking by accumulated score.
   * Section 5.2, remote fusion: patterns of the plan that no edge joins are merged greedily when their union
     is runnable and gains over running them apart (`remote_fusion`).
-  * Seeds: everything downstream of a vertex, and the connected component a vertex starts, are offered
-    as candidates too (a kernel family can be runnable as a whole while parts of it are not).
+  * Seeds: everything downstream of a vertex, the same stopped at graph outputs, and the connected component a
+    vertex starts are offered as candidates too and escape the top-k cut (a kernel family can be runnable as a
+    whole while parts of it are not, and the cut favours ever larger patterns).
 """
 from __future__ import annotations
 
@@ -157,16 +160,45 @@ def explore(view: GraphView, score: ScoreFn, top_k: int = 3, beam_width: int = 3
                     comp[x] = v
                     stack.append(x)
     for v in range(n):
+        seeds: List[Pat] = []
         cone = tuple([v] + sorted(x for x in view.desc[v]))
         if len(cone) > 1:
-            consider(cone, cand[v])
+            consider(cone, seeds)
+        # the same cone, not continued past a graph output
+        inside = {v}
+        for x in range(v, n):
+            if x in inside and not view.is_output[x]:
+                inside.update(view.consumers[x])
+        bounded = tuple(sorted(inside))
+        if len(bounded) > 1 and bounded != cone:
+            consider(bounded, seeds)
         if comp[v] == v:
             whole = tuple(x for x in range(n) if comp[x] == v)
-            if len(whole) > 1 and whole != cone:
-                consider(whole, cand[v])
-        cand[v] = keep_top(cand[v])
+            if len(whole) > 1 and whole != cone and whole != bounded:
+                consider(whole, seeds)
+        # seeds escape the top-k cut
+        for sd in seeds:
+            if all(p.ops != sd.ops for p in cand[v]):
+                cand[v].append(sd)
+        cand[v].sort(key=_key)
 
-    # beam search from producers to consumers
+    # beam search from producers to consumers; plans are ranked by accumulated score plus a look-ahead: every op
+    # not visited yet and still uncovered counts with the best score per op of any candidate that holds it
+    per_op = [0.0] * n
+    for v in range(n):
+        for p in cand[v]:
+            if not p.tentative:
+                share = p.f / len(p.ops)
+                for o in p.ops:
+                    per_op[o] = max(per_op[o], share)
+
+    def rank(covered, f, v):
+        r = f
+        for u in range(v + 1, n):
+            if u not in covered:
+                r += per_op[u]
+        return r
+
     sets: List[Tuple[List[Ops], frozenset, float]] = [([], frozenset(), 0.0)]
     for v in range(n):
         nxt = list(sets)
@@ -175,7 +207,7 @@ def explore(view: GraphView, score: ScoreFn, top_k: int = 3, beam_width: int = 3
                 if p.tentative or any(o in covered for o in p.ops):
                     continue
                 nxt.append((patterns + [p.ops], covered | frozenset(p.ops), f + p.f))
-        nxt.sort(key=lambda s: (-s[2], s[0]))
+        nxt.sort(key=lambda s: (-rank(s[1], s[2], v), s[0]))
         sets = nxt[:beam_width]
     return cand, [(patterns, f) for patterns, _, f in sets]
 

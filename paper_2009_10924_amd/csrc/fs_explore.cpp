@@ -327,8 +327,9 @@ struct Explorer {
       if (!consumers[v].empty()) cand[v] = reduce_group(v, consumers[v]);
     // Seeds beyond the bottom-up growth.  The growth only reaches a pattern through smaller patterns that are
     // themselves runnable; a hand-written family (say a row pass that ends in a column reduction) is runnable
-    // as a whole while some of its parts are not.  So two whole shapes are offered directly: everything
-    // downstream of a vertex, and the connected component a vertex starts (ops joined by an edge or a shared operand).
+    // as a whole while some of its parts are not, and the top-k cut favours ever larger patterns.  So three whole
+    // shapes are offered directly: everything downstream of a vertex, the same stopped at graph outputs, and the
+    // connected component a vertex starts (ops joined by an edge or a shared operand).
     std::vector<int> comp(n, -1);
     for (int v = 0; v < n; ++v) {
       if (comp[v] >= 0) continue;
@@ -348,17 +349,39 @@ struct Explorer {
       }
     }
     for (int v = 0; v < n; ++v) {
+      std::vector<Pat> seeds;
       OpSet cone{v};
       for (int x = v + 1; x < n; ++x)
         if ((desc[v][x / 64] >> (x % 64)) & 1) cone.push_back(x);
-      if (cone.size() > 1) consider(cone, &cand[v]);
+      if (cone.size() > 1) consider(cone, &seeds);
+      // the same cone, but not continued past a graph output: that tensor is written to memory anyway
+      OpSet bounded{v};
+      {
+        std::vector<char> in(n, 0);
+        in[v] = 1;
+        for (int x = v; x < n; ++x) {
+          if (!in[x]) continue;
+          if (g.tensors[g.ops[x].out].output_slot >= 0) continue;
+          for (int c : consumers[x]) in[c] = 1;
+        }
+        for (int x = v + 1; x < n; ++x)
+          if (in[x]) bounded.push_back(x);
+      }
+      if (bounded.size() > 1 && bounded != cone) consider(bounded, &seeds);
       if (comp[v] == v) {
         OpSet whole;
         for (int x = 0; x < n; ++x)
           if (comp[x] == v) whole.push_back(x);
-        if (whole.size() > 1 && whole != cone) consider(whole, &cand[v]);
+        if (whole.size() > 1 && whole != cone && whole != bounded) consider(whole, &seeds);
       }
-      keep_top(&cand[v]);
+      // seeds are not subject to the top-k cut (at most three per vertex)
+      for (const Pat& sd : seeds) {
+        bool have = false;
+        for (const Pat& p : cand[v])
+          if (p.ops == sd.ops) have = true;
+        if (!have) cand[v].push_back(sd);
+      }
+      std::sort(cand[v].begin(), cand[v].end(), better);
     }
   }
 
@@ -397,8 +420,26 @@ struct Explorer {
     std::vector<uint64_t> covered;
     double f = 0;
   };
+  // Beam search (Section 5.3).  Plans are ranked by their accumulated score plus a look-ahead for the part of the
+  // graph not visited yet: every op still uncovered counts with the best score per op of any candidate pattern
+  // that holds it.  Without the look-ahead a large pattern that swallows half of a neighbouring pattern pushes
+  // out the plan that takes both neighbours whole; at the last vertex the look-ahead is zero and the ranking is
+  // the paper's.
   std::vector<PlanSet> beam() {
     const int words = (n + 63) / 64;
+    std::vector<double> per_op(n, 0.0);
+    for (int v = 0; v < n; ++v)
+      for (const Pat& p : cand[v]) {
+        if (p.tentative) continue;
+        const double share = p.f / (double)p.ops.size();
+        for (int o : p.ops) per_op[o] = std::max(per_op[o], share);
+      }
+    auto rank = [&](const PlanSet& s, int v) {
+      double r = s.f;
+      for (int u = v + 1; u < n; ++u)
+        if (!((s.covered[u / 64] >> (u % 64)) & 1)) r += per_op[u];
+      return r;
+    };
     std::vector<PlanSet> sets(1);
     sets[0].covered.assign(words, 0);
     for (int v = 0; v < n; ++v) {
@@ -417,12 +458,15 @@ struct Explorer {
           next.push_back(t);
         }
       }
-      std::stable_sort(next.begin(), next.end(), [](const PlanSet& a, const PlanSet& b) {
-        if (a.f != b.f) return a.f > b.f;
-        return a.patterns < b.patterns;
+      std::vector<std::pair<double, size_t>> order;
+      for (size_t k = 0; k < next.size(); ++k) order.push_back({rank(next[k], v), k});
+      std::stable_sort(order.begin(), order.end(), [&](const std::pair<double, size_t>& a, const std::pair<double, size_t>& b) {
+        if (a.first != b.first) return a.first > b.first;
+        return next[a.second].patterns < next[b.second].patterns;
       });
-      if ((int)next.size() > beam_width) next.resize(beam_width);
-      sets.swap(next);
+      std::vector<PlanSet> kept;
+      for (size_t k = 0; k < order.size() && (int)k < beam_width; ++k) kept.push_back(next[order[k].second]);
+      sets.swap(kept);
     }
     return sets;
   }

@@ -161,12 +161,14 @@ int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) {
       continue;
     }
     const RowProgP& q = l.args.u.prog;
-    snprintf(line, sizeof line, "  program dt=%s rows=%u cols=%u lanes=%d vecs=%d regs=%d sregs=%d\n", dtype_name(q.dt), q.rows, q.cols,
+    snprintf(line, sizeof line, "  program vec=%d rows=%u cols=%u lanes=%d vecs=%d regs=%d sregs=%d\n", q.vec, q.rows, q.cols,
              q.lanes_per_row, q.vecs_per_lane, q.n_regs, q.n_sregs);
     s += line;
     for (int i = 0; i < q.n_full; ++i)
-      s += "  full " + buf_name(l.ptr[i]) + " reg " + std::to_string(q.full_reg[i]) + (q.acc_input == i ? " acc" : "") + "\n";
-    for (int i = 0; i < q.n_col; ++i) s += "  col " + buf_name(l.ptr[4 + i]) + " index " + std::to_string(i) + "\n";
+      s += "  full " + buf_name(l.ptr[i]) + " reg " + std::to_string(q.full_reg[i]) + " " + dtype_name(q.full_dt[i]) +
+           (q.acc_input == i ? " acc" : "") + "\n";
+    for (int i = 0; i < q.n_col; ++i)
+      s += "  col " + buf_name(l.ptr[4 + i]) + " index " + std::to_string(i) + " " + dtype_name(q.col_dt[i]) + "\n";
     for (int i = 0; i < q.n_rscal; ++i)
       s += "  rscal " + buf_name(l.ptr[8 + i]) + " sreg " + std::to_string(q.rscal_sreg[i]) + " " + dtype_name(q.rscal_dt[i]) + "\n";
     for (int i = 0; i < kProgMaxOperands; ++i)

@@ -279,7 +279,6 @@ struct Compiler {
     if (cols < 2) return false;
 
     // classes of all tensors; inputs by class
-    int in_dt = -1;
     for (size_t t = 0; t < g.tensors.size(); ++t) {
       const Tensor& T = g.tensors[t];
       if (T.dtype == FS_I32) return false;
@@ -287,22 +286,23 @@ struct Compiler {
       val[t].root = (int)t;
       if (val[t].kind == V_NONE) return false;
     }
+    bool narrow = false;   // some vector input is 16 bits wide
     for (int t : g.inputs) {
       const Tensor& T = g.tensors[t];
       if (val[t].kind == V_RSCAL) {
         if (rscal_in.size() >= kProgMaxOperands) return false;
         rscal_in.push_back(t);
       } else {
-        if (in_dt >= 0 && T.dtype != in_dt) return false;   // one storage dtype for all vector inputs
-        in_dt = T.dtype;
+        if (dtype_bytes(T.dtype) == 2) narrow = true;
         std::vector<int32_t>& cls = val[t].kind == V_FULL ? full_in : col_in;
         if (cls.size() >= kProgMaxOperands) return false;
         cls.push_back(t);
       }
       if (T.output_slot >= 0) return false;   // an input handed straight to an output is no computation
     }
-    p.dt = in_dt >= 0 ? in_dt : FS_F32;
-    const uint32_t vec = 16u / (uint32_t)dtype_bytes(p.dt);
+    // lane geometry by elements: the narrowest vector input still moves in 128-bit accesses
+    p.vec = narrow ? 8 : 4;
+    const uint32_t vec = (uint32_t)p.vec;
     if (cols % vec != 0) return false;
     p.rows = rows;
     p.cols = cols;
@@ -395,7 +395,11 @@ struct Compiler {
     p.n_full = (int32_t)full_in.size();
     p.n_col = (int32_t)col_in.size();
     p.n_rscal = (int32_t)rscal_in.size();
-    for (size_t i = 0; i < col_in.size(); ++i) val[col_in[i]].input_index = (int)i;
+    for (size_t i = 0; i < col_in.size(); ++i) {
+      val[col_in[i]].input_index = (int)i;
+      p.col_dt[i] = (uint8_t)g.tensors[col_in[i]].dtype;
+    }
+    for (size_t i = 0; i < full_in.size(); ++i) p.full_dt[i] = (uint8_t)g.tensors[full_in[i]].dtype;
 
     // the first op's full-shaped input operand is handed over in the accumulator by the prologue;
     // it is parked in a register as well only if something reads it after the accumulator moved on
@@ -432,8 +436,11 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
   Compiler c(g);
   if (!c.run()) return false;
   const RowProgP& base = c.p;
-  const int vec = 16 / dtype_bytes(base.dt);
+  const int vec = base.vec;
   const uint32_t nvec = base.cols / vec;
+  double in_bytes_per_elem = 0, col_bytes_per_elem = 0;
+  for (int i = 0; i < base.n_full; ++i) in_bytes_per_elem += dtype_bytes(base.full_dt[i]);
+  for (int i = 0; i < base.n_col; ++i) col_bytes_per_elem += dtype_bytes(base.col_dt[i]);
   const double n = (double)base.rows * base.cols;
   const int64_t bytes_min = graph_bytes_min(g);
 
@@ -485,12 +492,11 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
     cand.info.rows_per_block = (int32_t)rows_per_block;
     cand.info.lds_bytes = (int32_t)lds;
     for (int k = 0; k < 3; ++k) { cand.info.block[k] = (int32_t)l.shape.block[k]; cand.info.grid[k] = (int32_t)l.shape.grid[k]; }
-    snprintf(cand.info.kernel, sizeof cand.info.kernel, "row_program<%s,K%d,L%u,I%d,R%d>", dtype_name(base.dt), s.K, s.L,
-             base.n_instr, base.n_regs);
+    snprintf(cand.info.kernel, sizeof cand.info.kernel, "row_program<v%d,K%d,L%u,I%d,R%d>", vec, s.K, s.L, base.n_instr, base.n_regs);
 
     KernelCost kc;
     kc.hbm_bytes = (double)bytes_min;
-    kc.cache_bytes = (double)c.col_in.size() * n * dtype_bytes(base.dt);
+    kc.cache_bytes = col_bytes_per_elem * n;
     kc.elems = n;
     // per element: the op itself plus operand / result moves; per instruction and wave: ~40 scalar-side cycles of dispatch
     const double dispatch = 40.0 * base.n_instr / (64.0 * kv) / 4.0;
@@ -499,7 +505,7 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
     kc.lds_traffic_bytes = n * 4.0 * (c.reg_reads + c.reg_writes + base.n_full);
     kc.waves = (double)l.shape.grid[0] * 4;
     kc.waves_per_block = 4;
-    kc.bytes_in_flight_per_lane = 16.0 * s.K * std::max(1, base.n_full);
+    kc.bytes_in_flight_per_lane = std::max(16.0, (double)vec * in_bytes_per_elem) * s.K;
     kc.vgpr_estimate = 40 + 3 * kv + 4 * s.K * (base.n_full <= 1 ? 1 : (base.n_full <= 2 ? 2 : 4));
     int steps = 0;
     for (uint32_t t = 1; t < std::min<uint32_t>(s.L, 64); t <<= 1) ++steps;

@@ -203,13 +203,15 @@ constexpr int kProgMaxOperands = 4;     // per class: full inputs, column vector
 constexpr int kProgMaxReductions = 8;   // LDS slot sets of the workgroup-per-row form
 constexpr int kProgMaxLdsBytes = 128 * 1024;   // register files of one workgroup (a CU has 160 KB)
 struct RowProgP {
-  int32_t dt;                          // storage dtype of full inputs and column vectors
+  int32_t vec;                         // elements a lane holds per 128-bit step of the narrowest vector input: 4 or 8
+                                       // (a float32 input of a vec-8 program takes two 128-bit loads per step)
   uint32_t rows, cols;
   int32_t lanes_per_row, lanes_log2, vecs_per_lane;   // lanes_per_row > 64: one workgroup per row
   int32_t n_full, n_col, n_rscal, n_instr;
   int32_t n_regs, n_sregs;             // register files: full-shaped and per-row
   int32_t acc_input;                   // full-shaped input the accumulator starts out holding, -1 = none
   uint8_t full_reg[kProgMaxOperands];  // register each full-shaped input is parked in, 255 = not parked
+  uint8_t full_dt[kProgMaxOperands], col_dt[kProgMaxOperands];   // storage dtypes of the vector inputs
   uint8_t rscal_sreg[kProgMaxOperands], rscal_dt[kProgMaxOperands];
   ProgInstr instr[kProgMaxInstr];
 };

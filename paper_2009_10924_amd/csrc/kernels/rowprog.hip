@@ -61,10 +61,45 @@ __device__ __forceinline__ float apply_op(int op, float a, float b, int aux) {
   }
 }
 
-// NI: capacity for full-shaped inputs (sizes the prologue's load batch).
-template <typename T, int K, int NI>
+// VEC elements of a row per lane and step (8 as soon as one vector input is 16-bit wide, so that the narrow
+// inputs still move in 128-bit accesses; a float32 input then takes two).  NI: capacity for full-shaped inputs
+// (sizes the prologue's load batch).
+template <int VEC, int W>
+struct RawVec {      // VEC elements in storage form: W 128-bit words
+  u32x4 w[W];
+};
+template <int VEC>
+__device__ __forceinline__ RawVec<VEC, VEC / 4> load_elems(const void* p, size_t at, int dt, bool streaming) {
+  RawVec<VEC, VEC / 4> r;
+#pragma unroll
+  for (int h = 0; h < VEC / 4; ++h) r.w[h] = u32x4{0u, 0u, 0u, 0u};
+  if (dt == DT_F32) {
+    const float* src = static_cast<const float*>(p) + at;
+#pragma unroll
+    for (int h = 0; h < VEC / 4; ++h) r.w[h] = streaming ? load_raw_nt(src + 4 * h) : load_raw(src + 4 * h);
+  } else if (VEC == 8) {
+    const uint16_t* src = static_cast<const uint16_t*>(p) + at;
+    r.w[0] = streaming ? load_raw_nt(src) : load_raw(src);
+  }
+  return r;
+}
+template <int VEC>
+__device__ __forceinline__ void unpack_elems(const RawVec<VEC, VEC / 4>& r, int dt, float (&v)[VEC]) {
+  if (dt == DT_F32) {
+#pragma unroll
+    for (int h = 0; h < VEC / 4; ++h) {
+      float part[4];
+      unpack(r.w[h], part, (const float*)nullptr);
+      v[4 * h] = part[0]; v[4 * h + 1] = part[1]; v[4 * h + 2] = part[2]; v[4 * h + 3] = part[3];
+    }
+  } else if constexpr (VEC == 8) {
+    if (dt == DT_F16) unpack(r.w[0], v, (const f16_t*)nullptr);
+    else unpack(r.w[0], v, (const bf16_t*)nullptr);
+  }
+}
+
+template <int VEC, int K, int NI>
 __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kernarg) {
-  constexpr int VEC = Elem<T>::VEC;
   constexpr int KV = K * VEC;     // floats a lane holds per full-shaped value
   constexpr int CH = KV / 4;      // 16-byte chunks of one register of one lane
   extern __shared__ f32x4 lds[];
@@ -132,13 +167,13 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
   // once per workgroup into the shared column file; per-row scalar inputs go to the scalar file.
   {
     const int n_full = A->p.n_full;
-    u32x4 raw[NI][K];
+    RawVec<VEC, VEC / 4> raw[NI][K];
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
       if (i < n_full) {
-        const T* src = static_cast<const T*>(A->full[i]) + base;
+        const int dt = A->p.full_dt[i];
 #pragma unroll
-        for (int k = 0; k < K; ++k) raw[i][k] = load_raw_nt(src + (size_t)vec_at(k) * VEC);
+        for (int k = 0; k < K; ++k) raw[i][k] = load_elems<VEC>(A->full[i], base + (size_t)vec_at(k) * VEC, dt, true);
       }
     }
     const int n_rscal = A->p.n_rscal;
@@ -148,10 +183,10 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
       if (i < n_rscal) rs[i] = load_scalar_as(A->rscal[i], row_c, A->p.rscal_dt[i]);
     }
     for (int i = 0; i < n_col; ++i) {
-      const T* src = static_cast<const T*>(A->col[i]);
+      const int dt = A->p.col_dt[i];
       for (uint32_t j = tid; j < nvec; j += 256u) {
         float part[VEC];
-        unpack(load_raw(src + (size_t)j * VEC), part, (const T*)nullptr);
+        unpack_elems<VEC>(load_elems<VEC>(A->col[i], (size_t)j * VEC, dt, false), dt, part);
 #pragma unroll
         for (int h = 0; h < VEC / 4; ++h) {
           const f32x4 t = {part[4 * h], part[4 * h + 1], part[4 * h + 2], part[4 * h + 3]};
@@ -167,10 +202,11 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
     for (int i = 0; i < NI; ++i) {
       if (i < n_full) {
         float v[KV];
+        const int dt = A->p.full_dt[i];
 #pragma unroll
         for (int k = 0; k < K; ++k) {
           float part[VEC];
-          unpack(raw[i][k], part, (const T*)nullptr);
+          unpack_elems<VEC>(raw[i][k], dt, part);
 #pragma unroll
           for (int e = 0; e < VEC; ++e) v[k * VEC + e] = part[e];
         }
@@ -290,32 +326,29 @@ namespace fs {
 using namespace fsk;
 
 namespace {
-template <typename T, int NI>
+template <int VEC, int NI>
 const void* prog_sym_k(int K) {
   switch (K) {
-    case 1: return (const void*)k_row_program<T, 1, NI>;
-    case 2: return (const void*)k_row_program<T, 2, NI>;
-    case 4: return (const void*)k_row_program<T, 4, NI>;
+    case 1: return (const void*)k_row_program<VEC, 1, NI>;
+    case 2: return (const void*)k_row_program<VEC, 2, NI>;
+    case 4: return (const void*)k_row_program<VEC, 4, NI>;
     default: return nullptr;
   }
 }
-template <typename T>
+template <int VEC>
 const void* prog_sym(int K, int n_full) {
-  if (n_full <= 1) return prog_sym_k<T, 1>(K);
-  if (n_full <= 2) return prog_sym_k<T, 2>(K);
-  return prog_sym_k<T, 4>(K);
+  if (n_full <= 1) return prog_sym_k<VEC, 1>(K);
+  if (n_full <= 2) return prog_sym_k<VEC, 2>(K);
+  return prog_sym_k<VEC, 4>(K);
 }
 }  // namespace
 
 const void* rowprog_kernel_symbol(int32_t, const KernelArgs& a) {
   const RowProgP& p = a.u.prog;
   if (p.n_full < 0 || p.n_full > kProgMaxOperands) return nullptr;
-  switch (p.dt) {
-    case DT_F32: return prog_sym<float>(p.vecs_per_lane, p.n_full);
-    case DT_F16: return prog_sym<f16_t>(p.vecs_per_lane, p.n_full);
-    case DT_BF16: return prog_sym<bf16_t>(p.vecs_per_lane, p.n_full);
-    default: return nullptr;
-  }
+  if (p.vec == 4) return prog_sym<4>(p.vecs_per_lane, p.n_full);
+  if (p.vec == 8) return prog_sym<8>(p.vecs_per_lane, p.n_full);
+  return nullptr;
 }
 
 }  // namespace fs
