@@ -73,7 +73,7 @@ __device__ __forceinline__ RawVec<VEC, VEC / 4> load_elems(const void* p, size_t
   RawVec<VEC, VEC / 4> r;
 #pragma unroll
   for (int h = 0; h < VEC / 4; ++h) r.w[h] = u32x4{0u, 0u, 0u, 0u};
-  if (dt == DT_F32) {
+  if (VEC == 4 || dt == DT_F32) {   // a vec-4 program has float32 vector inputs only: no test at run time
     const float* src = static_cast<const float*>(p) + at;
 #pragma unroll
     for (int h = 0; h < VEC / 4; ++h) r.w[h] = streaming ? load_raw_nt(src + 4 * h) : load_raw(src + 4 * h);
@@ -85,7 +85,7 @@ __device__ __forceinline__ RawVec<VEC, VEC / 4> load_elems(const void* p, size_t
 }
 template <int VEC>
 __device__ __forceinline__ void unpack_elems(const RawVec<VEC, VEC / 4>& r, int dt, float (&v)[VEC]) {
-  if (dt == DT_F32) {
+  if (VEC == 4 || dt == DT_F32) {
 #pragma unroll
     for (int h = 0; h < VEC / 4; ++h) {
       float part[4];
@@ -128,6 +128,7 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
     row = blockIdx.x * (256u >> A->p.lanes_log2) + (tid >> A->p.lanes_log2);
   }
   const bool row_ok = row < rows;
+  const bool row_full = nvec == L * (uint32_t)K;
   const uint32_t row_c = min(row, rows - 1);
   const size_t base = (size_t)row_c * cols;
   auto valid = [&](int k) { return lane + k * L < nvec; };
@@ -255,14 +256,22 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
       const bool is_max = op == PO_RMAX;
       const bool squared = op == PO_RSUMSQ;
       float r = is_max ? -INFINITY : 0.0f;
+      if (row_full) {   // the row fills its lanes exactly: no padding slot to leave out
 #pragma unroll
-      for (int k = 0; k < K; ++k) {
-        const bool ok = valid(k);
+        for (int j = 0; j < KV; ++j) {
+          const float x = squared ? acc[j] * acc[j] : acc[j];
+          r = is_max ? fmaxf(r, x) : r + x;
+        }
+      } else {
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) {
-          const float v = acc[k * VEC + e];
-          const float x = squared ? v * v : v;
-          r = is_max ? fmaxf(r, ok ? x : -INFINITY) : r + (ok ? x : 0.0f);
+        for (int k = 0; k < K; ++k) {
+          const bool ok = valid(k);
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) {
+            const float v = acc[k * VEC + e];
+            const float x = squared ? v * v : v;
+            r = is_max ? fmaxf(r, ok ? x : -INFINITY) : r + (ok ? x : 0.0f);
+          }
         }
       }
       if (block_mode) {
@@ -278,6 +287,23 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
       const float b = b_kind == PK_SCAL ? sregs[b_idx * 256u + tid] : (b_kind == PK_SACC ? sacc : imm);
       sacc = apply_op((int)op, sacc, b, (int)aux);
       if (flags & PF_KEEP) sregs[dst * 256u + tid] = sacc;
+    } else if (b_kind == PK_SACC || b_kind == PK_SCAL || b_kind == PK_IMM) {
+      // per-row or immediate operand: one value for the whole lane, used as is (no stretched copy)
+      const float sb = b_kind == PK_SCAL ? sregs[b_idx * 256u + tid] : (b_kind == PK_SACC ? sacc : imm);
+      switch (op) {
+#define FS_PROG_CASE(OP)                                                             \
+  case OP:                                                                           \
+    _Pragma("unroll") for (int j = 0; j < KV; ++j) acc[j] = apply_op(OP, acc[j], sb, (int)aux); \
+    break;
+        FS_PROG_CASE(PO_ADD) FS_PROG_CASE(PO_SUB) FS_PROG_CASE(PO_RSUB) FS_PROG_CASE(PO_MUL) FS_PROG_CASE(PO_DIV)
+        FS_PROG_CASE(PO_RDIV) FS_PROG_CASE(PO_MAX) FS_PROG_CASE(PO_SQUARE) FS_PROG_CASE(PO_EXP) FS_PROG_CASE(PO_RSQRT)
+        FS_PROG_CASE(PO_TANH) FS_PROG_CASE(PO_GELU) FS_PROG_CASE(PO_GELU_GRAD) FS_PROG_CASE(PO_CVT)
+#undef FS_PROG_CASE
+        default:   // PO_LOAD
+#pragma unroll
+          for (int j = 0; j < KV; ++j) acc[j] = sb;
+          break;
+      }
     } else {
       float b[KV];
       if (b_kind == PK_REG) {
@@ -292,13 +318,9 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
             b[k * VEC + 4 * h] = t.x; b[k * VEC + 4 * h + 1] = t.y; b[k * VEC + 4 * h + 2] = t.z; b[k * VEC + 4 * h + 3] = t.w;
           }
         }
-      } else if (b_kind == PK_ACC) {
+      } else {   // PK_ACC
 #pragma unroll
         for (int j = 0; j < KV; ++j) b[j] = acc[j];
-      } else {
-        const float sb = b_kind == PK_SCAL ? sregs[b_idx * 256u + tid] : (b_kind == PK_SACC ? sacc : imm);
-#pragma unroll
-        for (int j = 0; j < KV; ++j) b[j] = sb;
       }
       // the op is uniform: one scalar branch per instruction, then straight-line lane work
       switch (op) {
@@ -307,16 +329,15 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
     _Pragma("unroll") for (int j = 0; j < KV; ++j) acc[j] = apply_op(OP, acc[j], b[j], (int)aux); \
     break;
         FS_PROG_CASE(PO_ADD) FS_PROG_CASE(PO_SUB) FS_PROG_CASE(PO_RSUB) FS_PROG_CASE(PO_MUL) FS_PROG_CASE(PO_DIV)
-        FS_PROG_CASE(PO_RDIV) FS_PROG_CASE(PO_MAX) FS_PROG_CASE(PO_SQUARE) FS_PROG_CASE(PO_EXP) FS_PROG_CASE(PO_RSQRT)
-        FS_PROG_CASE(PO_TANH) FS_PROG_CASE(PO_GELU) FS_PROG_CASE(PO_GELU_GRAD) FS_PROG_CASE(PO_CVT)
+        FS_PROG_CASE(PO_RDIV) FS_PROG_CASE(PO_MAX)
 #undef FS_PROG_CASE
-        default:   // PO_LOAD
+        default:   // PO_LOAD (the one-operand ops never name a vector b)
 #pragma unroll
           for (int j = 0; j < KV; ++j) acc[j] = b[j];
           break;
       }
-      if (flags & PF_KEEP) put((int)dst, acc);
     }
+    if (!(flags & PF_SCALAR) && op <= PO_LOAD && (flags & PF_KEEP)) put((int)dst, acc);
   }
 }
 
