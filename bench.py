@@ -380,7 +380,7 @@ def main():
         from workloads import NEXT_CONFIGS
         # patterns beyond the five configurations: softmax / LayerNorm backward, innermost-axis-moving transposes
         result["next_patterns"] = {name: measure_config(name, NEXT_CONFIGS[name](), max(50, args.steps // 4), 20)
-                                   for name in ("N1", "N2", "N3", "N4", "N5")}
+                                   for name in ("N1", "N2", "N3", "N4", "N5", "N6")}
         torch.cuda.empty_cache()
         result["packing"] = measure_pack("P1", max(200, args.steps // 2), 20)
         torch.cuda.empty_cache()

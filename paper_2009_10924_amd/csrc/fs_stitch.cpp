@@ -320,7 +320,12 @@ bool build_softmax(const fs_graph& g, std::vector<Candidate>* out, PackForm* pac
 
 // ------------------------------------------------------------------ layernorm family
 bool build_layernorm(const fs_graph& g, std::vector<Candidate>* out, PackForm* pack) {
-  if (g.outputs.size() != 1) return false;
+  // one normalised output; a training forward pass may hand out the per-row mean and the reciprocal standard
+  // deviation as well (two more outputs, float32 [rows, 1])
+  if (g.outputs.empty() || g.outputs.size() > 3) return false;
+  int32_t root = -1;
+  for (int32_t t : g.outputs)
+    if (root < 0 || g.tensors[t].numel() > g.tensors[root].numel()) root = t;
   static const char* hs[] = {"add(add($X,$R),$B)", "add($X,$R)", "$X"};
   const std::string c_txt = "sub(@,rmean[-1](@))";
   const std::string norm_txt = "mul(%,rsqrt(addc[#0](rmean[-1](square(%)))))";
@@ -338,7 +343,7 @@ bool build_layernorm(const fs_graph& g, std::vector<Candidate>* out, PackForm* p
       if (variant & 2) top = "cvt(" + top + ")";
       Pattern pat(top);
       MatchState trial;
-      if (pat.match(g, g.outputs[0], &trial) && covers_all(g, trial)) {
+      if (pat.match(g, root, &trial) && covers_all(g, trial)) {
         bool inputs_ok = true;
         for (auto& kv : trial.tensors) inputs_ok = inputs_ok && is_input(g, kv.second);
         if (inputs_ok) {
@@ -367,7 +372,22 @@ bool build_layernorm(const fs_graph& g, std::vector<Candidate>* out, PackForm* p
   if (affine && (!is_row_vector(g.tensors[tg], p.cols) || !is_row_vector(g.tensors[tbt], p.cols))) return true;
   p.in_dt = x.dtype;
   p.par_dt = x.dtype;
-  p.out_dt = g.tensors[g.outputs[0]].store_as;
+  p.out_dt = g.tensors[root].store_as;
+  // the other outputs: the row mean (the reduction whose result is subtracted) and the reciprocal standard
+  // deviation (the rsqrt), stored as float32
+  int32_t t_mean = -1, t_rstd = -1;
+  for (int32_t t : g.outputs) {
+    if (t == root) continue;
+    const Tensor& T = g.tensors[t];
+    if (T.store_as != FS_F32 || T.producer < 0 || T.numel() != (int64_t)p.rows) return true;
+    const Op& maker = g.ops[T.producer];
+    bool feeds_sub = false;
+    for (int c : T.consumers) feeds_sub = feeds_sub || g.ops[c].opcode == FS_SUB;
+    if (maker.opcode == FS_RSQRT && t_rstd < 0) t_rstd = t;
+    else if (maker.opcode == FS_REDUCE_MEAN && feeds_sub && t_mean < 0) t_mean = t;
+    else return true;
+  }
+  const bool with_stats = t_mean >= 0 || t_rstd >= 0;
   for (int32_t t : {tr, tb, tg, tbt})
     if (t >= 0 && g.tensors[t].dtype != x.dtype) return true;
   if (!(p.in_dt == FS_F32 || p.out_dt == p.in_dt)) return true;   // compiled dtype pairs
@@ -383,7 +403,7 @@ bool build_layernorm(const fs_graph& g, std::vector<Candidate>* out, PackForm* p
   const int in_b = dtype_bytes(p.in_dt), out_b = dtype_bytes(p.out_dt);
   const double n = (double)p.rows * p.cols;
   const int n_vec_inputs = (p.has_bias ? 1 : 0) + (affine ? 2 : 0);
-  if (affine && p.has_res == p.has_bias && (p.out_dt == p.in_dt || p.out_dt == FS_BF16)) {
+  if (!with_stats && affine && p.has_res == p.has_bias && (p.out_dt == p.in_dt || p.out_dt == FS_BF16)) {
     pack->spec = p.has_res ? PACK_LN_FULL : PACK_LN_PLAIN;
     pack->in_dt = p.in_dt;
     pack->out_dt = p.out_dt;
@@ -403,7 +423,8 @@ bool build_layernorm(const fs_graph& g, std::vector<Candidate>* out, PackForm* p
     }
   }
   auto base_cost = [&](KernelCost* kc) {
-    kc->hbm_bytes = n * in_b * (1 + p.has_res) + n * out_b + (double)n_vec_inputs * p.cols * in_b;
+    kc->hbm_bytes = n * in_b * (1 + p.has_res) + n * out_b + (double)n_vec_inputs * p.cols * in_b +
+                    4.0 * p.rows * ((t_mean >= 0) + (t_rstd >= 0));
     kc->elems = n;
     kc->valu_per_elem = 8.0 + (in_b == 2 ? 1.0 : 0.0) + (out_b == 2 ? 1.0 : 0.0);
     kc->trans_per_elem = 0.0;
@@ -414,7 +435,9 @@ bool build_layernorm(const fs_graph& g, std::vector<Candidate>* out, PackForm* p
     if (tr >= 0) l.ptr[1] = in_ref(g, tr);
     if (tb >= 0) l.ptr[2] = in_ref(g, tb);
     if (affine) { l.ptr[3] = in_ref(g, tg); l.ptr[4] = in_ref(g, tbt); }
-    l.ptr[5] = out_ref(0);
+    l.ptr[5] = out_ref(g.tensors[root].output_slot);
+    if (t_mean >= 0) l.ptr[6] = out_ref(g.tensors[t_mean].output_slot);
+    if (t_rstd >= 0) l.ptr[7] = out_ref(g.tensors[t_rstd].output_slot);
   };
 
   for (int K : {1, 2, 3, 4, 6, 8}) {

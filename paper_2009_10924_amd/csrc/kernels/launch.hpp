@@ -23,7 +23,7 @@ enum KernelId : int32_t {
   // stitched
   K_SOFTMAX_WAVE,      // p0 x, p1 mask (or null), p2 out
   K_SOFTMAX_BLOCK,     // same operands, one workgroup per row, reduced values through LDS
-  K_LAYERNORM_WAVE,    // p0 x, p1 res, p2 bias, p3 gamma, p4 beta, p5 out
+  K_LAYERNORM_WAVE,    // p0 x, p1 res, p2 bias, p3 gamma, p4 beta, p5 out, p6 row mean out (or null), p7 row rstd out (or null)
   K_LAYERNORM_BLOCK,
   K_BIAS_GELU,         // p0 x, p1 bias, p2 y
   K_BIAS_GELU_DBIAS,   // p0 x, p1 bias, p2 grad, p3 y, p4 dbias, p5 partials, p6 counters

@@ -125,6 +125,7 @@ template <typename TI, typename TO, int K, bool FAST>
 __global__ void __launch_bounds__(256) k_layernorm_wave(const TI* __restrict__ x, const TI* __restrict__ res,
                                                         const TI* __restrict__ bias, const TI* __restrict__ gamma,
                                                         const TI* __restrict__ beta, TO* __restrict__ out,
+                                                        float* __restrict__ mean_out, float* __restrict__ rstd_out,
                                                         LayerNormP p) {
   const uint32_t L = p.lanes_per_row;
   const uint32_t group = threadIdx.x >> p.lanes_log2;
@@ -135,13 +136,20 @@ __global__ void __launch_bounds__(256) k_layernorm_wave(const TI* __restrict__ x
   LnRow<TI, TO, K, FAST> r;
   const float mean = group_allreduce<OpSum>(r.load(x, res, bias, gamma, beta, p, row, lane, L), L) * inv_n;
   const float var = group_allreduce<OpSum>(r.center(p, mean, lane, L), L) * inv_n;
-  r.finish(out, p, row, row_ok, lane, L, fast_rsqrt(var + p.eps));
+  const float rstd = fast_rsqrt(var + p.eps);
+  // per-row statistics for a later backward pass (null when the pattern does not hand them out)
+  if (row_ok && lane == 0) {
+    if (mean_out) mean_out[row] = mean;
+    if (rstd_out) rstd_out[row] = rstd;
+  }
+  r.finish(out, p, row, row_ok, lane, L, rstd);
 }
 
 template <typename TI, typename TO, int K, bool FAST>
 __global__ void __launch_bounds__(256) k_layernorm_block(const TI* __restrict__ x, const TI* __restrict__ res,
                                                          const TI* __restrict__ bias, const TI* __restrict__ gamma,
                                                          const TI* __restrict__ beta, TO* __restrict__ out,
+                                                         float* __restrict__ mean_out, float* __restrict__ rstd_out,
                                                          LayerNormP p) {
   __shared__ float slot_sum[2][4], slot_sq[2][4];
   const uint32_t n_waves = blockDim.x >> 6;
@@ -155,7 +163,12 @@ __global__ void __launch_bounds__(256) k_layernorm_block(const TI* __restrict__ 
                                               slot_sum[it & 1], n_waves) * inv_n;
     const float var = block_allreduce<OpSum>(r.center(p, mean, threadIdx.x, blockDim.x),
                                              slot_sq[it & 1], n_waves) * inv_n;
-    r.finish(out, p, row, true, threadIdx.x, blockDim.x, fast_rsqrt(var + p.eps));
+    const float rstd = fast_rsqrt(var + p.eps);
+    if (threadIdx.x == 0) {
+      if (mean_out) mean_out[row] = mean;
+      if (rstd_out) rstd_out[row] = rstd;
+    }
+    r.finish(out, p, row, true, threadIdx.x, blockDim.x, rstd);
   }
 }
 

@@ -43,7 +43,7 @@ SPECS = {
     "gelu_dbias": lambda: bias_gelu_dbias_graph(256, 512),
     "transpose_chain": lambda: transpose_chain_graph(2, 16, 4, 64),
     "layernorm_backward": lambda: layernorm_backward_graph(64, 256, "f32"),
-    "layernorm_stats": lambda: layernorm_stats_graph(64, 256),
+    "layernorm_stats": lambda: layernorm_stats_graph(64, 256, with_variance=True),
 }
 SPECS.update({f"multi{s}": (lambda s=s: random_multi_pattern(s)) for s in range(16)})
 SPECS.update({f"multi_big{s}": (lambda s=s: random_multi_pattern(100 + s, rows=512, cols=1024, segments=4)) for s in range(4)})

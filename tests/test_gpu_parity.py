@@ -174,6 +174,18 @@ def test_layernorm_backward(rows, cols, dtype):
     note(f"layernorm backward {rows}x{cols} {dtype}: {worst}")
 
 
+@pytest.mark.parametrize("rows,cols,in_dt,out_dt", [(100, 768, "f32", "bf16"), (37, 100, "f32", "f32"), (9, 1024, "bf16", "bf16"),
+                                                   (5, 4096, "f32", "f32"), (300, 64, "f16", "f16"), (1, 8, "f32", "f32")])
+def test_layernorm_with_saved_statistics(rows, cols, in_dt, out_dt):
+    from workloads import layernorm_stats_graph
+    spec = layernorm_stats_graph(rows, cols, in_dtype=in_dt, out_dtype=out_dt)
+    assert B.Plan(B.Graph.from_spec(spec), "auto").info["pattern"] == "layernorm"
+    inp = make_inputs(spec, seed=0)
+    ref = O.evaluate(spec, inp)
+    worst = all_candidates(spec, inp, ref, {"out": O.rms(ref["out"]), "mu": O.rms(ref["mu"])}, repeat=2)
+    note(f"LayerNorm + mean/rstd outputs {rows}x{cols} {in_dt}->{out_dt}: {worst}")
+
+
 # ------------------------------------------------------------------ transpose: bit-exact
 @pytest.mark.parametrize("dims,perm,dtype", [
     ((4, 37, 12, 64), (0, 2, 1, 3), "f32"), ((3, 5, 7, 6), (0, 2, 1, 3), "i32"), ((2, 33, 5, 8), (2, 0, 1, 3), "bf16"),

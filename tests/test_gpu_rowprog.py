@@ -26,7 +26,7 @@ def _run(spec, seed=0, repeat=2):
 @pytest.mark.parametrize("rows,cols,in_dt,out_dt", [(100, 768, "f32", "bf16"), (37, 100, "f32", "f32"), (9, 1024, "bf16", "bf16"),
                                                    (5, 4096, "f32", "f16"), (300, 64, "f16", "f32"), (3, 2048, "f16", "f16")])
 def test_layernorm_with_saved_statistics(rows, cols, in_dt, out_dt):
-    worst, info = _run(layernorm_stats_graph(rows, cols, in_dtype=in_dt, out_dtype=out_dt))
+    worst, info = _run(layernorm_stats_graph(rows, cols, in_dtype=in_dt, out_dtype=out_dt, with_variance=True))
     note(f"LayerNorm + statistics {rows}x{cols} {in_dt}->{out_dt}: {info['n_candidates']} shapes, worst {worst}")
 
 

@@ -124,7 +124,7 @@ def _compare(spec, seed=1):
 
 
 @pytest.mark.parametrize("make", [
-    lambda: layernorm_stats_graph(24, 96, in_dtype="f32", out_dtype="f32"),
+    lambda: layernorm_stats_graph(24, 96, in_dtype="f32", out_dtype="f32", with_variance=True),
     lambda: silu_gate_graph(9, 64, "f32"),
     lambda: scaled_softmax_colbias_graph(13, 40, "f32"),
     lambda: normalize_from_stats_graph(11, 48, "f32"),
@@ -135,7 +135,7 @@ def test_named_patterns_compile_to_correct_programs(make):
 
 
 def test_layernorm_program_keeps_only_what_is_read_again():
-    spec = layernorm_stats_graph(24, 96, in_dtype="f32", out_dtype="f32")
+    spec = layernorm_stats_graph(24, 96, in_dtype="f32", out_dtype="f32", with_variance=True)
     plan = B.Plan(B.Graph.from_spec(spec), "auto")
     lines = [l.split() for l in plan.describe().splitlines() if l.strip().startswith("instr")]
     kept = [l for l in lines if "flags=vk" in l or "flags=sk" in l]

@@ -277,15 +277,18 @@ NEXT_CONFIGS = {
     "N3": lambda: transpose_graph((64, 512, 12, 64), (0, 2, 3, 1), "f32"),   # innermost axis moves: [B,S,H,D] -> [B,H,D,S]
     "N4": lambda: transpose_graph((64, 512, 12, 64), (0, 2, 3, 1), "bf16"),
     "N5": lambda: rmsnorm_graph(8192, 4096, dtype="bf16"),
+    "N6": lambda: layernorm_stats_graph(8192, 768),                          # C2 that also saves mean and rstd for backward
 }
 
 # ---- row-local patterns no hand-written kernel family covers (served by the interpreted row program) ----
-def layernorm_stats_graph(rows: int, cols: int, eps: float = 1e-5, in_dtype: str = "f32", out_dtype: str = "bf16") -> GraphSpec:
+def layernorm_stats_graph(rows: int, cols: int, eps: float = 1e-5, in_dtype: str = "f32", out_dtype: str = "bf16",
+                          with_variance: bool = False) -> GraphSpec:
     """Residual add + bias + LayerNorm that also hands out the per-row mean and reciprocal standard
-    deviation, as a training forward pass does (three outputs, two of them [rows,1])."""
+    deviation, as a training forward pass does (three outputs, two of them [rows,1]).  with_variance adds the
+    row variance as a fourth output, which no hand-written kernel provides."""
     base = add_bias_layernorm_graph(rows, cols, eps, in_dtype, out_dtype)
-    return GraphSpec(name=f"pattern_layernorm_stats_{in_dtype}_{rows}x{cols}", inputs=base.inputs, ops=base.ops,
-                     outputs=[("out", out_dtype), ("mu", "f32"), ("r", "f32")])
+    outputs = [("out", out_dtype), ("mu", "f32"), ("r", "f32")] + ([("v", "f32")] if with_variance else [])
+    return GraphSpec(name=f"pattern_layernorm_stats_{in_dtype}_{rows}x{cols}", inputs=base.inputs, ops=base.ops, outputs=outputs)
 
 
 def silu_gate_graph(rows: int, cols: int, dtype: str = "bf16") -> GraphSpec:
@@ -538,7 +541,7 @@ EXPLORE_CONFIGS = {"T1": lambda: transformer_block_graph(32, 128, 12, 64, 3072, 
 
 # Row-local patterns outside the hand-written families, at transformer-block sizes (interpreted row program).
 GENERIC_CONFIGS = {
-    "G1": lambda: layernorm_stats_graph(8192, 768),                          # C2 plus saved mean / rstd outputs
+    "G1": lambda: layernorm_stats_graph(8192, 768, with_variance=True),      # C2 plus mean / rstd / variance outputs
     "G2": lambda: silu_gate_graph(8192, 4096, "bf16"),
     "G3": lambda: scaled_softmax_colbias_graph(32 * 12 * 128, 128, "f32"),
     "G4": lambda: normalize_from_stats_graph(8192, 1024, "f16"),
