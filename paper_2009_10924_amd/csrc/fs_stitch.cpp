@@ -394,6 +394,7 @@ bool build_layernorm(const fs_graph& g, std::vector<Candidate>* out, PackForm* p
   p.has_res = tr >= 0;
   p.has_bias = tb >= 0;
   p.has_affine = affine;
+  p.stats = with_stats ? 1 : 0;
   p.eps = (float)st.scalars[0];
   p.inv_cols = (float)(1.0 / (double)p.cols);
 
@@ -487,7 +488,7 @@ bool build_layernorm(const fs_graph& g, std::vector<Candidate>* out, PackForm* p
     q.lanes_per_row = (int32_t)T;
     q.vecs_per_lane = K;
     q.rows_per_block = 1;
-    q.fast = p.has_res && p.has_bias && affine && (uint64_t)T * K == nvec;
+    q.fast = !with_stats && p.has_res && p.has_bias && affine && (uint64_t)T * K == nvec;
     l.args.u.layernorm = q;
     fill_ptrs(l);
     l.shape.block[0] = T;

@@ -97,6 +97,7 @@ struct SoftmaxP {
 struct LayerNormP {
   int32_t in_dt, out_dt, par_dt;    // x/res dtype, output dtype, bias/gamma/beta dtype
   int32_t has_res, has_bias, has_affine;
+  int32_t stats;                    // 1: the per-row mean / rstd pointers are live
   uint32_t rows, cols;
   float eps, inv_cols;              // inv_cols = 1 / cols, rounded on the host
   int32_t lanes_per_row, vecs_per_lane, rows_per_block;

@@ -121,7 +121,9 @@ struct LnRow {
   }
 };
 
-template <typename TI, typename TO, int K, bool FAST>
+// STATS: the pattern also hands out the per-row mean and reciprocal standard deviation.  A template flag, not a
+// run-time test of the pointers: the kernel without statistics must stay one basic block (see the file header).
+template <typename TI, typename TO, int K, bool FAST, bool STATS>
 __global__ void __launch_bounds__(256) k_layernorm_wave(const TI* __restrict__ x, const TI* __restrict__ res,
                                                         const TI* __restrict__ bias, const TI* __restrict__ gamma,
                                                         const TI* __restrict__ beta, TO* __restrict__ out,
@@ -137,12 +139,13 @@ __global__ void __launch_bounds__(256) k_layernorm_wave(const TI* __restrict__ x
   const float mean = group_allreduce<OpSum>(r.load(x, res, bias, gamma, beta, p, row, lane, L), L) * inv_n;
   const float var = group_allreduce<OpSum>(r.center(p, mean, lane, L), L) * inv_n;
   const float rstd = fast_rsqrt(var + p.eps);
-  // per-row statistics for a later backward pass (null when the pattern does not hand them out)
-  if (row_ok && lane == 0) {
-    if (mean_out) mean_out[row] = mean;
-    if (rstd_out) rstd_out[row] = rstd;
-  }
   r.finish(out, p, row, row_ok, lane, L, rstd);
+  if constexpr (STATS) {
+    if (row_ok && lane == 0) {
+      if (mean_out) mean_out[row] = mean;
+      if (rstd_out) rstd_out[row] = rstd;
+    }
+  }
 }
 
 template <typename TI, typename TO, int K, bool FAST>
@@ -164,11 +167,13 @@ __global__ void __launch_bounds__(256) k_layernorm_block(const TI* __restrict__ 
     const float var = block_allreduce<OpSum>(r.center(p, mean, threadIdx.x, blockDim.x),
                                              slot_sq[it & 1], n_waves) * inv_n;
     const float rstd = fast_rsqrt(var + p.eps);
-    if (threadIdx.x == 0) {
-      if (mean_out) mean_out[row] = mean;
-      if (rstd_out) rstd_out[row] = rstd;
-    }
     r.finish(out, p, row, true, threadIdx.x, blockDim.x, rstd);
+    if constexpr (!FAST) {   // patterns with statistics use the general form of this kernel
+      if (threadIdx.x == 0) {
+        if (mean_out) mean_out[row] = mean;
+        if (rstd_out) rstd_out[row] = rstd;
+      }
+    }
   }
 }
 
@@ -308,14 +313,17 @@ const void* ln_bwd_sym(const LnBwdP& b) {
   return nullptr;
 }
 template <typename TI, typename TO>
-const void* ln_sym(int32_t kernel, int K, bool fast) {
+const void* ln_sym(int32_t kernel, int K, bool fast, bool stats) {
 #define FS_LN_CASE(KK)                                                                                     \
   case KK:                                                                                                 \
-    if (fast)                                                                                              \
-      return kernel == K_LAYERNORM_WAVE ? (const void*)k_layernorm_wave<TI, TO, KK, true>                  \
-                                        : (const void*)k_layernorm_block<TI, TO, KK, true>;                \
-    return kernel == K_LAYERNORM_WAVE ? (const void*)k_layernorm_wave<TI, TO, KK, false>                   \
-                                      : (const void*)k_layernorm_block<TI, TO, KK, false>;
+    if (kernel == K_LAYERNORM_WAVE) {                                                                      \
+      if (stats) return fast ? (const void*)k_layernorm_wave<TI, TO, KK, true, true>                       \
+                             : (const void*)k_layernorm_wave<TI, TO, KK, false, true>;                     \
+      return fast ? (const void*)k_layernorm_wave<TI, TO, KK, true, false>                                 \
+                  : (const void*)k_layernorm_wave<TI, TO, KK, false, false>;                               \
+    }                                                                                                      \
+    return fast && !stats ? (const void*)k_layernorm_block<TI, TO, KK, true>                               \
+                          : (const void*)k_layernorm_block<TI, TO, KK, false>;
   switch (K) {
     FS_LN_CASE(1) FS_LN_CASE(2) FS_LN_CASE(3) FS_LN_CASE(4) FS_LN_CASE(6) FS_LN_CASE(8)
     default: return nullptr;
@@ -335,11 +343,11 @@ const void* layernorm_kernel_symbol(int32_t kernel, const KernelArgs& a) {
   }
   const LayerNormP& p = a.u.layernorm;
   const int K = p.vecs_per_lane;
-  if (p.in_dt == DT_F32 && p.out_dt == DT_F32) return ln_sym<float, float>(kernel, K, p.fast != 0);
-  if (p.in_dt == DT_F32 && p.out_dt == DT_BF16) return ln_sym<float, bf16_t>(kernel, K, p.fast != 0);
-  if (p.in_dt == DT_F32 && p.out_dt == DT_F16) return ln_sym<float, f16_t>(kernel, K, p.fast != 0);
-  if (p.in_dt == DT_BF16 && p.out_dt == DT_BF16) return ln_sym<bf16_t, bf16_t>(kernel, K, p.fast != 0);
-  if (p.in_dt == DT_F16 && p.out_dt == DT_F16) return ln_sym<f16_t, f16_t>(kernel, K, p.fast != 0);
+  if (p.in_dt == DT_F32 && p.out_dt == DT_F32) return ln_sym<float, float>(kernel, K, p.fast != 0, p.stats != 0);
+  if (p.in_dt == DT_F32 && p.out_dt == DT_BF16) return ln_sym<float, bf16_t>(kernel, K, p.fast != 0, p.stats != 0);
+  if (p.in_dt == DT_F32 && p.out_dt == DT_F16) return ln_sym<float, f16_t>(kernel, K, p.fast != 0, p.stats != 0);
+  if (p.in_dt == DT_BF16 && p.out_dt == DT_BF16) return ln_sym<bf16_t, bf16_t>(kernel, K, p.fast != 0, p.stats != 0);
+  if (p.in_dt == DT_F16 && p.out_dt == DT_F16) return ln_sym<f16_t, f16_t>(kernel, K, p.fast != 0, p.stats != 0);
   return nullptr;
 }
 
