@@ -389,7 +389,7 @@ def main():
         result["explorer"] = measure_program("T1", max(100, args.steps // 8), 10)
         torch.cuda.empty_cache()
         result["generic_patterns"] = {name: measure_config(name, GENERIC_CONFIGS[name](), max(50, args.steps // 8), 10)
-                                      for name in ("G1", "G2", "G3", "G4")}
+                                      for name in ("G1", "G2", "G3", "G4", "G5")}
     print(json.dumps(result))
 
 

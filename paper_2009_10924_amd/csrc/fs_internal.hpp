@@ -129,6 +129,8 @@ std::string build_stitched(const fs_graph& g, std::vector<Candidate>* out, PackF
 // pattern of element-wise ops and last-axis reductions over one row space.
 bool build_row_program(const fs_graph& g, std::vector<Candidate>* out);
 int64_t graph_bytes_min(const fs_graph& g);
+// Multiply-high constants for n / d with n < 2^31 (d == 0 in the result marks "no usable constants").
+FastDiv make_fastdiv(uint32_t d);
 void predict(Candidate* c);  // fills info.predicted_us, waves_per_simd, vgprs, lds
 
 }  // namespace fs

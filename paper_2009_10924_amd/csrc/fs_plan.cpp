@@ -166,11 +166,15 @@ int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) {
     s += line;
     for (int i = 0; i < q.n_full; ++i)
       s += "  full " + buf_name(l.ptr[i]) + " reg " + std::to_string(q.full_reg[i]) + " " + dtype_name(q.full_dt[i]) +
+           (((q.full_bcast >> i) & 1u) ? " rowstrides=" + std::to_string(q.ms[i][0]) + "," + std::to_string(q.ms[i][1]) + "," +
+                                             std::to_string(q.ms[i][2]) : std::string()) +
            (q.acc_input == i ? " acc" : "") + "\n";
     for (int i = 0; i < q.n_col; ++i)
       s += "  col " + buf_name(l.ptr[4 + i]) + " index " + std::to_string(i) + " " + dtype_name(q.col_dt[i]) + "\n";
     for (int i = 0; i < q.n_rscal; ++i)
-      s += "  rscal " + buf_name(l.ptr[8 + i]) + " sreg " + std::to_string(q.rscal_sreg[i]) + " " + dtype_name(q.rscal_dt[i]) + "\n";
+      s += "  rscal " + buf_name(l.ptr[8 + i]) + " sreg " + std::to_string(q.rscal_sreg[i]) + " " + dtype_name(q.rscal_dt[i]) +
+           (((q.rscal_bcast >> i) & 1u) ? " rowstrides=" + std::to_string(q.rms[i][0]) + "," + std::to_string(q.rms[i][1]) + "," +
+                                              std::to_string(q.rms[i][2]) : std::string()) + "\n";
     for (int i = 0; i < kProgMaxOperands; ++i)
       if (l.ptr[12 + i].kind != BUF_NONE) s += "  output " + std::to_string(i) + " " + buf_name(l.ptr[12 + i]) + "\n";
     for (int i = 0; i < kProgMaxOperands; ++i)

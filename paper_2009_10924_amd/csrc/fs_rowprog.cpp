@@ -58,16 +58,38 @@ struct Compiler {
       const int kt = k - (rank - t.rank);
       d[k] = kt >= 0 ? t.dims[kt] : 1;
     }
-    bool full = true, rscal = d[rank - 1] == 1, col = d[rank - 1] == dims[rank - 1];
+    bool full = true, rscal = d[rank - 1] == 1, col = d[rank - 1] == dims[rank - 1], stretched = true;
     for (int k = 0; k < rank; ++k) {
       if (d[k] != dims[k]) full = false;
       if (k < rank - 1 && d[k] != dims[k]) rscal = false;
       if (k < rank - 1 && d[k] != 1) col = false;
+      if (k < rank - 1 && d[k] != 1 && d[k] != dims[k]) stretched = false;
     }
     if (full) return V_FULL;
     if (rscal) return V_RSCAL;
     if (col) return V_COL;
+    // full rows or per-row scalars repeated along some leading axes (see `stretched_rows`)
+    if (stretched && d[rank - 1] == dims[rank - 1]) return V_FULL;
+    if (stretched && d[rank - 1] == 1) return V_RSCAL;
     return V_NONE;
+  }
+  // true if `t` has extent 1 on some leading axis where the pattern's row space has more
+  bool stretched_rows(const Tensor& t) const {
+    const int k0 = rank - t.rank;
+    for (int k = 0; k < rank - 1; ++k) {
+      const int64_t d = k >= k0 ? t.dims[k - k0] : 1;
+      if (d != dims[k]) return true;
+    }
+    return false;
+  }
+  void row_strides(const Tensor& T, uint32_t (&ms)[3]) const {
+    int64_t acc = 1;
+    for (int k = rank - 2; k >= 0; --k) {
+      const int kt = k - (rank - T.rank);
+      const int64_t d = kt >= 0 ? T.dims[kt] : 1;
+      ms[3 - (rank - 1) + k] = d == 1 ? 0u : (uint32_t)acc;
+      acc *= d;
+    }
   }
 
   static bool scalar_shaped(int kind) { return kind == V_RSCAL; }
@@ -355,8 +377,10 @@ struct Compiler {
         if (op.n_in > 1) reads[i].push_back(val[op.in[1]].root);
       }
     }
-    for (int t : g.outputs)
+    for (int t : g.outputs) {
       if (g.tensors[t].producer < 0) return false;
+      if (val[t].kind != V_COL && stretched_rows(g.tensors[t])) return false;   // an output must own every row it is stored to
+    }
     // peepholes.  (1) square feeding only a row sum / mean: the reduction squares on the fly, so the
     // accumulator keeps the un-squared value.  (2) a convert whose only reader is the store of the same
     // dtype: the store rounds anyway.
@@ -400,6 +424,27 @@ struct Compiler {
       p.col_dt[i] = (uint8_t)g.tensors[col_in[i]].dtype;
     }
     for (size_t i = 0; i < full_in.size(); ++i) p.full_dt[i] = (uint8_t)g.tensors[full_in[i]].dtype;
+    // leading axes of the row space, collapsed to three; inputs stretched along some of them get row strides
+    {
+      uint32_t od[3] = {1, 1, 1};
+      for (int k = 0; k < rank - 1; ++k) od[3 - (rank - 1) + k] = (uint32_t)dims[k];
+      for (int k = 0; k < 3; ++k) {
+        p.od[k] = make_fastdiv(od[k]);
+        if (p.od[k].d == 0) return false;
+      }
+      for (size_t i = 0; i < full_in.size(); ++i) {
+        const Tensor& T = g.tensors[full_in[i]];
+        if (!stretched_rows(T)) continue;
+        p.full_bcast |= 1u << i;
+        row_strides(T, p.ms[i]);
+      }
+      for (size_t i = 0; i < rscal_in.size(); ++i) {
+        const Tensor& T = g.tensors[rscal_in[i]];
+        if (!stretched_rows(T)) continue;
+        p.rscal_bcast |= 1u << i;
+        row_strides(T, p.rms[i]);
+      }
+    }
 
     // the first op's full-shaped input operand is handed over in the accumulator by the prologue;
     // it is parked in a register as well only if something reads it after the accumulator moved on

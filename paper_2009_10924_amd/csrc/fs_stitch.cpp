@@ -13,20 +13,6 @@
 
 namespace fs {
 
-namespace {
-
-uint32_t pow2_at_least(uint32_t v) {
-  uint32_t p = 1;
-  while (p < v) p <<= 1;
-  return p;
-}
-int vec_of(int32_t dt) { return 16 / dtype_bytes(dt); }
-int log2_of(uint32_t pow2) {
-  int l = 0;
-  while ((1u << l) < pow2) ++l;
-  return l;
-}
-
 // Magic numbers for n / d, n < 2^31; checked on the spot against plain division.
 FastDiv make_fastdiv(uint32_t d) {
   FastDiv f = {d == 0 ? 1u : d, 0u, 0u};
@@ -41,6 +27,20 @@ FastDiv make_fastdiv(uint32_t d) {
     if (q != n / d) { f.m = 0; f.s = 0; f.d = 0; break; }   // d == 0 marks "unusable"; callers then offer no candidate
   }
   return f;
+}
+
+namespace {
+
+uint32_t pow2_at_least(uint32_t v) {
+  uint32_t p = 1;
+  while (p < v) p <<= 1;
+  return p;
+}
+int vec_of(int32_t dt) { return 16 / dtype_bytes(dt); }
+int log2_of(uint32_t pow2) {
+  int l = 0;
+  while ((1u << l) < pow2) ++l;
+  return l;
 }
 
 bool is_input(const fs_graph& g, int32_t t) { return t >= 0 && g.tensors[t].producer < 0; }

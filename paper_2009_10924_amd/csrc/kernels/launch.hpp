@@ -213,6 +213,14 @@ struct RowProgP {
   int32_t acc_input;                   // full-shaped input the accumulator starts out holding, -1 = none
   uint8_t full_reg[kProgMaxOperands];  // register each full-shaped input is parked in, 255 = not parked
   uint8_t full_dt[kProgMaxOperands], col_dt[kProgMaxOperands];   // storage dtypes of the vector inputs
+  // full-shaped inputs that are stretched along some leading axes (an attention mask [B,1,1,T] under scores
+  // [B,H,S,T]): bit i of full_bcast set -> the row of input i is c0*ms[i][0] + c1*ms[i][1] + c2*ms[i][2] with
+  // (c0, c1, c2) the row's index along the pattern's leading axes, od[] their extents (collapsed to three)
+  uint32_t full_bcast;
+  uint32_t ms[kProgMaxOperands][3];
+  uint32_t rscal_bcast;                 // the same for per-row scalar inputs (a per-head value [H,1,1] under [B,H,S,T])
+  uint32_t rms[kProgMaxOperands][3];
+  FastDiv od[3];
   uint8_t rscal_sreg[kProgMaxOperands], rscal_dt[kProgMaxOperands];
   ProgInstr instr[kProgMaxInstr];
 };

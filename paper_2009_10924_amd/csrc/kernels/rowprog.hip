@@ -53,7 +53,7 @@ __device__ __forceinline__ float apply_op(int op, float a, float b, int aux) {
     case PO_SQUARE: return a * a;
     case PO_EXP: return fast_exp(a);
     case PO_RSQRT: return fast_rsqrt(a);
-    case PO_TANH: return tanhf(a);
+    case PO_TANH: return fast_tanh(a);
     case PO_GELU: return gelu_fwd(a);
     case PO_GELU_GRAD: return gelu_grad(a);
     case PO_CVT: return round_through(a, aux);
@@ -168,20 +168,36 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
   // once per workgroup into the shared column file; per-row scalar inputs go to the scalar file.
   {
     const int n_full = A->p.n_full;
+    // the row's index along the pattern's (collapsed) leading axes, for inputs stretched along some of them
+    uint32_t c0 = 0, c1 = 0, c2 = 0;
+    if (A->p.full_bcast | A->p.rscal_bcast) {
+      const FastDiv od1 = {A->p.od[1].d, A->p.od[1].m, A->p.od[1].s}, od2 = {A->p.od[2].d, A->p.od[2].m, A->p.od[2].s};
+      const uint32_t r1 = fast_div(row_c, od2);
+      c2 = row_c - r1 * od2.d;
+      c0 = fast_div(r1, od1);
+      c1 = r1 - c0 * od1.d;
+    }
     RawVec<VEC, VEC / 4> raw[NI][K];
 #pragma unroll
     for (int i = 0; i < NI; ++i) {
       if (i < n_full) {
         const int dt = A->p.full_dt[i];
+        size_t base_i = base;
+        if ((A->p.full_bcast >> i) & 1u)   // stretched along leading axes: its own row index
+          base_i = (size_t)(c0 * A->p.ms[i][0] + c1 * A->p.ms[i][1] + c2 * A->p.ms[i][2]) * cols;
 #pragma unroll
-        for (int k = 0; k < K; ++k) raw[i][k] = load_elems<VEC>(A->full[i], base + (size_t)vec_at(k) * VEC, dt, true);
+        for (int k = 0; k < K; ++k) raw[i][k] = load_elems<VEC>(A->full[i], base_i + (size_t)vec_at(k) * VEC, dt, true);
       }
     }
     const int n_rscal = A->p.n_rscal;
     float rs[kProgMaxOperands];
 #pragma unroll
     for (int i = 0; i < kProgMaxOperands; ++i) {
-      if (i < n_rscal) rs[i] = load_scalar_as(A->rscal[i], row_c, A->p.rscal_dt[i]);
+      if (i < n_rscal) {
+        size_t at = row_c;
+        if ((A->p.rscal_bcast >> i) & 1u) at = c0 * A->p.rms[i][0] + c1 * A->p.rms[i][1] + c2 * A->p.rms[i][2];
+        rs[i] = load_scalar_as(A->rscal[i], at, A->p.rscal_dt[i]);
+      }
     }
     for (int i = 0; i < n_col; ++i) {
       const int dt = A->p.col_dt[i];

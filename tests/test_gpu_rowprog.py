@@ -54,6 +54,14 @@ def test_outer_product_without_full_input(rows, cols):
     note(f"outer scale {rows}x{cols}: {worst}")
 
 
+@pytest.mark.parametrize("dims,dtype", [((3, 2, 9, 128), "f16"), ((2, 3, 5, 64), "f32"), ((2, 2, 7, 40), "bf16"), ((4, 1, 3, 1024), "f16"),
+                                        ((32, 12, 128, 128), "f16")])
+def test_operands_stretched_along_leading_axes(dims, dtype):
+    from workloads import masked_scores_gate_graph
+    worst, info = _run(masked_scores_gate_graph(*dims, dtype=dtype))
+    note(f"masked, per-head scaled, soft-capped softmax {dims} {dtype}: {info['kernel']}, worst {worst}")
+
+
 @pytest.mark.parametrize("seed", range(48))
 def test_random_row_patterns(seed):
     dtype = ("f32", "f16", "bf16")[seed % 3]

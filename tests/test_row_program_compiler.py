@@ -31,8 +31,9 @@ def _gelu_grad(z):
     return 0.5 * (1.0 + t) + 0.5 * z * (1.0 - t * t) * np.sqrt(2.0 / np.pi) * (1.0 + 3 * 0.044715 * z * z)
 
 
-def emulate(listing, spec, inputs):
-    """Runs the listed program in float32 on whole arrays: full values [R, C], per-row values [R, 1]."""
+def emulate(listing, spec, inputs, anchor_dims):
+    """Runs the listed program in float32 on whole arrays: full values [R, C], per-row values [R, 1].
+    anchor_dims: extents of the pattern's row space (inputs stretched along leading axes are repeated to it)."""
     lines = [l.split() for l in listing.splitlines()]
     head = [l for l in lines if l and l[0] == "program"][0]
     kv = dict(x.split("=") for x in head[1:])
@@ -45,14 +46,15 @@ def emulate(listing, spec, inputs):
         if not l:
             continue
         if l[0] == "full":
+            full = np.broadcast_to(in_arrays[int(l[1][2:])], anchor_dims).reshape(rows, cols)
             if int(l[3]) != 255:
-                regs[int(l[3])] = in_arrays[int(l[1][2:])].reshape(rows, cols)
+                regs[int(l[3])] = full
             if l[-1] == "acc":
-                acc0 = in_arrays[int(l[1][2:])].reshape(rows, cols)
+                acc0 = full
         elif l[0] == "col":
             colvecs[int(l[3])] = np.broadcast_to(in_arrays[int(l[1][2:])].reshape(1, cols), (rows, cols))
         elif l[0] == "rscal":
-            sregs[int(l[3])] = in_arrays[int(l[1][2:])].reshape(rows, 1)
+            sregs[int(l[3])] = np.broadcast_to(in_arrays[int(l[1][2:])], tuple(anchor_dims[:-1]) + (1,)).reshape(rows, 1)
         elif l[0] == "output":
             out_bind[int(l[1])] = int(l[2][3:])
         elif l[0] == "routput":
@@ -115,7 +117,8 @@ def _compare(spec, seed=1):
     listing = plan.describe()
     inp = make_inputs(spec, seed=seed)
     ref = O.evaluate(spec, inp)
-    got, n_instr = emulate(listing, spec, inp)
+    anchor = max([ref[name].shape for name, _ in spec.outputs] + [tuple(t.dims) for t in spec.inputs], key=lambda d: int(np.prod(d)))
+    got, n_instr = emulate(listing, spec, inp, anchor)
     for name, dt in spec.outputs:
         r = ref[name].reshape(got[name].shape)
         err = O.max_rel_err(got[name], r, O.rms(r))
@@ -132,6 +135,13 @@ def _compare(spec, seed=1):
 ])
 def test_named_patterns_compile_to_correct_programs(make):
     _compare(make())
+
+
+def test_inputs_stretched_along_leading_axes():
+    from workloads import masked_scores_gate_graph
+    for dims in [(2, 3, 5, 16), (3, 1, 4, 32), (2, 2, 2, 8)]:
+        n, info = _compare(masked_scores_gate_graph(*dims, dtype="f32"))
+        assert info["pattern"] == "row_program"
 
 
 def test_layernorm_program_keeps_only_what_is_read_again():
@@ -158,9 +168,9 @@ def test_patterns_that_are_not_row_local_are_refused():
     spec = GraphSpec("pattern_x", [TensorSpec("x", "f32", (8, 16))],
                      [OpSpec("e", "exp", ("x",)), OpSpec("s", "reduce_sum", ("e",), {"axis": 0})], [("s", "f32")])
     assert B.Plan(B.Graph.from_spec(spec), "auto").info["scheme"] == "unfused"
-    # operand that varies along a middle axis only
-    spec = GraphSpec("pattern_y", [TensorSpec("x", "f32", (4, 6, 16)), TensorSpec("m", "f32", (4, 1, 16))],
-                     [OpSpec("a", "add", ("x", "m")), OpSpec("y", "exp", ("a",))], [("y", "f32")])
+    # an output that is stretched itself would be written by several rows
+    spec = GraphSpec("pattern_w", [TensorSpec("x", "f32", (4, 6, 16)), TensorSpec("m", "f32", (4, 1, 16))],
+                     [OpSpec("a", "add", ("x", "m")), OpSpec("e", "exp", ("m",))], [("a", "f32"), ("e", "f32")])
     assert B.Plan(B.Graph.from_spec(spec), "auto").info["scheme"] == "unfused"
     # row too long for the register file in LDS: falls back as well
     spec = GraphSpec("pattern_z", [TensorSpec("x", "f32", (2, 1 << 15))],

@@ -339,6 +339,22 @@ def outer_scale_graph(rows: int, cols: int) -> GraphSpec:
                      ops=ops, outputs=[("out", "f32")])
 
 
+def masked_scores_gate_graph(batch: int, heads: int, q_len: int, k_len: int, dtype: str = "f16") -> GraphSpec:
+    """Attention scores with an additive key mask [batch,1,1,k_len], a per-head temperature [heads,1,1] and a
+    tanh soft-cap before the softmax: a softmax neighbourhood with two operands stretched along different
+    leading axes, which the softmax family does not match."""
+    ops = [
+        _op("t", "mul", "scores", "temp"),
+        _op("cap", "tanh", "t"),
+        _op("c30", "scale", "cap", value=30.0),
+        _op("a", "add", "c30", "mask"),
+    ] + _softmax_ops("a", 3)
+    return GraphSpec(name=f"pattern_masked_gate_{dtype}_{batch}x{heads}x{q_len}x{k_len}",
+                     inputs=[TensorSpec("scores", dtype, (batch, heads, q_len, k_len)), TensorSpec("mask", dtype, (batch, 1, 1, k_len)),
+                             TensorSpec("temp", "f32", (heads, 1, 1))],
+                     ops=ops, outputs=[("y", dtype)])
+
+
 def random_row_pattern(seed: int, rows: int, cols: int, dtype: str = "f32", n_ops: int = 12) -> GraphSpec:
     """A random connected pattern of element-wise ops and row reductions over [rows, cols] (descriptor only).
     Domains are kept safe by construction: exp only of tanh, division and rsqrt only of 1 + square."""
@@ -545,6 +561,7 @@ GENERIC_CONFIGS = {
     "G2": lambda: silu_gate_graph(8192, 4096, "bf16"),
     "G3": lambda: scaled_softmax_colbias_graph(32 * 12 * 128, 128, "f32"),
     "G4": lambda: normalize_from_stats_graph(8192, 1024, "f16"),
+    "G5": lambda: masked_scores_gate_graph(32, 12, 128, 128, "f16"),        # C3's shape: mask [B,1,1,T], per-head scale [H,1,1]
 }
 
 FULL_CONFIGS = {
