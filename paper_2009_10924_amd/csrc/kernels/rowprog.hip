@@ -303,53 +303,53 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
       const float b = b_kind == PK_SCAL ? sregs[b_idx * 256u + tid] : (b_kind == PK_SACC ? sacc : imm);
       sacc = apply_op((int)op, sacc, b, (int)aux);
       if (flags & PF_KEEP) sregs[dst * 256u + tid] = sacc;
-    } else if (b_kind == PK_SACC || b_kind == PK_SCAL || b_kind == PK_IMM) {
-      // per-row or immediate operand: one value for the whole lane, used as is (no stretched copy)
+    } else {
+      // one flat dispatch on (op, where b comes from): every case updates the accumulator in place and the
+      // cases meet again in a single place, so the accumulator is not copied around between nested merges
+      const uint32_t b_class = b_kind == PK_REG ? 1u : (b_kind == PK_COL ? 2u : (b_kind == PK_ACC ? 3u : 0u));
       const float sb = b_kind == PK_SCAL ? sregs[b_idx * 256u + tid] : (b_kind == PK_SACC ? sacc : imm);
-      switch (op) {
-#define FS_PROG_CASE(OP)                                                             \
-  case OP:                                                                           \
+      switch (op * 4u + b_class) {
+#define FS_B_SCALAR(OP)                                                                \
+  case (OP) * 4u + 0u:                                                                 \
     _Pragma("unroll") for (int j = 0; j < KV; ++j) acc[j] = apply_op(OP, acc[j], sb, (int)aux); \
     break;
-        FS_PROG_CASE(PO_ADD) FS_PROG_CASE(PO_SUB) FS_PROG_CASE(PO_RSUB) FS_PROG_CASE(PO_MUL) FS_PROG_CASE(PO_DIV)
-        FS_PROG_CASE(PO_RDIV) FS_PROG_CASE(PO_MAX) FS_PROG_CASE(PO_SQUARE) FS_PROG_CASE(PO_EXP) FS_PROG_CASE(PO_RSQRT)
-        FS_PROG_CASE(PO_TANH) FS_PROG_CASE(PO_GELU) FS_PROG_CASE(PO_GELU_GRAD) FS_PROG_CASE(PO_CVT)
-#undef FS_PROG_CASE
-        default:   // PO_LOAD
-#pragma unroll
-          for (int j = 0; j < KV; ++j) acc[j] = sb;
-          break;
-      }
-    } else {
-      float b[KV];
-      if (b_kind == PK_REG) {
-        get((int)b_idx, b);
-      } else if (b_kind == PK_COL) {
-#pragma unroll
-        for (int k = 0; k < K; ++k) {
-          const f32x4* src = colfile + (b_idx * nvec + vec_at(k)) * (VEC / 4);
-#pragma unroll
-          for (int h = 0; h < VEC / 4; ++h) {
-            const f32x4 t = src[h];
-            b[k * VEC + 4 * h] = t.x; b[k * VEC + 4 * h + 1] = t.y; b[k * VEC + 4 * h + 2] = t.z; b[k * VEC + 4 * h + 3] = t.w;
-          }
-        }
-      } else {   // PK_ACC
-#pragma unroll
-        for (int j = 0; j < KV; ++j) b[j] = acc[j];
-      }
-      // the op is uniform: one scalar branch per instruction, then straight-line lane work
-      switch (op) {
-#define FS_PROG_CASE(OP)                                                               \
-  case OP:                                                                             \
-    _Pragma("unroll") for (int j = 0; j < KV; ++j) acc[j] = apply_op(OP, acc[j], b[j], (int)aux); \
+#define FS_B_REG(OP)                                                                   \
+  case (OP) * 4u + 1u: {                                                               \
+    float b[KV];                                                                       \
+    get((int)b_idx, b);                                                                \
+    _Pragma("unroll") for (int j = 0; j < KV; ++j) acc[j] = apply_op(OP, acc[j], b[j], 0); \
+    break;                                                                             \
+  }
+#define FS_B_COL(OP)                                                                   \
+  case (OP) * 4u + 2u: {                                                               \
+    _Pragma("unroll") for (int k = 0; k < K; ++k) {                                    \
+      const f32x4* src = colfile + (b_idx * nvec + vec_at(k)) * (VEC / 4);             \
+      _Pragma("unroll") for (int h = 0; h < VEC / 4; ++h) {                            \
+        const f32x4 t = src[h];                                                        \
+        const int j = k * VEC + 4 * h;                                                 \
+        acc[j] = apply_op(OP, acc[j], t.x, 0);                                         \
+        acc[j + 1] = apply_op(OP, acc[j + 1], t.y, 0);                                 \
+        acc[j + 2] = apply_op(OP, acc[j + 2], t.z, 0);                                 \
+        acc[j + 3] = apply_op(OP, acc[j + 3], t.w, 0);                                 \
+      }                                                                                \
+    }                                                                                  \
+    break;                                                                             \
+  }
+#define FS_B_ACC(OP)                                                                   \
+  case (OP) * 4u + 3u:                                                                 \
+    _Pragma("unroll") for (int j = 0; j < KV; ++j) acc[j] = apply_op(OP, acc[j], acc[j], 0); \
     break;
-        FS_PROG_CASE(PO_ADD) FS_PROG_CASE(PO_SUB) FS_PROG_CASE(PO_RSUB) FS_PROG_CASE(PO_MUL) FS_PROG_CASE(PO_DIV)
-        FS_PROG_CASE(PO_RDIV) FS_PROG_CASE(PO_MAX)
-#undef FS_PROG_CASE
-        default:   // PO_LOAD (the one-operand ops never name a vector b)
-#pragma unroll
-          for (int j = 0; j < KV; ++j) acc[j] = b[j];
+#define FS_BINARY(OP) FS_B_SCALAR(OP) FS_B_REG(OP) FS_B_COL(OP) FS_B_ACC(OP)
+        FS_BINARY(PO_ADD) FS_BINARY(PO_SUB) FS_BINARY(PO_RSUB) FS_BINARY(PO_MUL) FS_BINARY(PO_DIV) FS_BINARY(PO_RDIV)
+        FS_BINARY(PO_MAX) FS_BINARY(PO_LOAD)
+        FS_B_SCALAR(PO_SQUARE) FS_B_SCALAR(PO_EXP) FS_B_SCALAR(PO_RSQRT) FS_B_SCALAR(PO_TANH) FS_B_SCALAR(PO_GELU)
+        FS_B_SCALAR(PO_GELU_GRAD) FS_B_SCALAR(PO_CVT)
+#undef FS_BINARY
+#undef FS_B_ACC
+#undef FS_B_COL
+#undef FS_B_REG
+#undef FS_B_SCALAR
+        default:
           break;
       }
     }
