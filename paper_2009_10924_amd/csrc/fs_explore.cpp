@@ -526,6 +526,214 @@ struct Arena {
   }
 };
 
+struct BuiltPlan {
+  std::vector<fs_program::Step> steps;
+  double predicted = 0;   // latency-evaluator estimate, microseconds
+  double f = 0;           // accumulated delta-evaluator score after remote fusion
+  bool ok = false;
+  void destroy() {
+    for (fs_program::Step& s : steps) fs_plan_destroy(s.plan);
+    steps.clear();
+    ok = false;
+  }
+};
+
+// One plan of the beam made executable: remote fusion, then a stitched plan per pattern and per op left alone.
+fs_status build_steps(Explorer* ex, const Explorer::PlanSet& plan, bool remote_fusion, BuiltPlan* b, std::string* error_text) {
+  std::vector<OpSet> groups = plan.patterns;
+  for (int o = 0; o < ex->n; ++o)
+    if (!((plan.covered[o / 64] >> (o % 64)) & 1)) groups.push_back(OpSet{o});
+  b->f = plan.f + (remote_fusion ? ex->merge_remote(&groups) : 0.0);
+  b->ok = true;
+  for (const OpSet& p : groups) {
+    SubGraph sub;
+    fs_status st = ex->extract(p, &sub);
+    if (st == FS_ERR_DTYPE)
+      *error_text = "a tensor that is stored as a graph output in another dtype than it was computed in also feeds ops that "
+                    "cannot join its pattern; add an explicit convert and read its result";
+    else if (st != FS_OK)
+      *error_text = fs_last_error();
+    fs_program::Step step;
+    if (st == FS_OK) {
+      step.ops = p;
+      step.f = p.size() > 1 ? ex->score(p).f : 0.0;
+      st = fs_plan_create(sub.g, FS_SCHEME_AUTO, nullptr, &step.plan);
+      if (st != FS_OK) *error_text = fs_last_error();
+    }
+    if (st != FS_OK) {
+      b->destroy();
+      return st;
+    }
+    for (int32_t t : sub.in_tensor) {
+      BufRef r;
+      r.kind = BUF_INPUT;
+      r.slot = t;           // tensor id in the whole graph for now; resolved once the order is known
+      step.in.push_back(r);
+    }
+    for (int32_t t : sub.out_tensor) {
+      BufRef r;
+      r.kind = BUF_OUTPUT;
+      r.slot = t;
+      step.out.push_back(r);
+    }
+    b->predicted += step.plan->candidates[step.plan->chosen].info.predicted_us;
+    b->steps.push_back(std::move(step));
+  }
+  return FS_OK;
+}
+
+std::vector<int> owners(const fs_graph& g, const std::vector<fs_program::Step>& steps) {
+  std::vector<int> owner(g.ops.size(), -1);
+  for (size_t s = 0; s < steps.size(); ++s)
+    for (int o : steps[s].ops) owner[o] = (int)s;
+  return owner;
+}
+
+// Dependence order: a pattern runs after every pattern that makes one of its operands.  False if none exists.
+bool order_steps(const fs_graph& g, std::vector<fs_program::Step>* steps) {
+  std::stable_sort(steps->begin(), steps->end(),
+                   [](const fs_program::Step& a, const fs_program::Step& b) { return a.ops.back() < b.ops.back(); });
+  const std::vector<int> owner = owners(g, *steps);
+  const size_t ns = steps->size();
+  std::vector<std::set<int>> deps(ns);
+  for (size_t s = 0; s < ns; ++s)
+    for (int o : (*steps)[s].ops)
+      for (int k = 0; k < g.ops[o].n_in; ++k) {
+        const int32_t prod = g.tensors[g.ops[o].in[k]].producer;
+        if (prod >= 0 && owner[prod] != (int)s) deps[s].insert(owner[prod]);
+      }
+  std::vector<int> order;
+  std::vector<char> done(ns, 0);
+  while (order.size() < ns) {
+    bool progressed = false;
+    for (size_t s = 0; s < ns; ++s) {
+      if (done[s]) continue;
+      bool ready = true;
+      for (int d : deps[s])
+        if (!done[d]) ready = false;
+      if (ready) { done[s] = 1; order.push_back((int)s); progressed = true; }
+    }
+    if (!progressed) return false;
+  }
+  std::vector<fs_program::Step> sorted;
+  for (int s : order) sorted.push_back(std::move((*steps)[s]));
+  steps->swap(sorted);
+  return true;
+}
+
+// Launch-bound patterns with no dependence between them share one packed launch, issued where the first of them
+// stands; a member joins only if everything it reads is made before that point (remote fusion as kernel packing).
+void decide_packs(const fs_graph& g, fs_program* prog, std::vector<int>* pos) {
+  const int ns = (int)prog->steps.size();
+  const std::vector<int> owner = owners(g, prog->steps);
+  std::vector<int> level(ns, 0);
+  for (int s = 0; s < ns; ++s)
+    for (int o : prog->steps[s].ops)
+      for (int k = 0; k < g.ops[o].n_in; ++k) {
+        const int32_t prod = g.tensors[g.ops[o].in[k]].producer;
+        if (prod >= 0 && owner[prod] != s) level[s] = std::max(level[s], level[owner[prod]] + 1);
+      }
+  const double tiny_us = 3.0 * device().launch_s * 1e6;   // the launch is a third or more of the pattern's estimated time
+  std::map<int, std::vector<int>> by_level;
+  for (int s = 0; s < ns; ++s) {
+    const fs_plan* p = prog->steps[s].plan;
+    if (p->pack.spec >= 0 && p->candidates[p->chosen].info.predicted_us <= tiny_us) by_level[level[s]].push_back(s);
+  }
+  for (auto& kv : by_level) {
+    if (kv.second.size() < 2) continue;
+    std::vector<const fs_plan*> members;
+    std::vector<int> chosen;
+    const int first = kv.second.front();
+    for (int s : kv.second) {
+      bool ready = true;
+      for (const BufRef& r : prog->steps[s].in) {
+        const int32_t prod = g.tensors[r.slot].producer;
+        if (prod >= 0 && owner[prod] >= first) ready = false;
+      }
+      if (ready) { members.push_back(prog->steps[s].plan); chosen.push_back(s); }
+    }
+    if (members.size() < 2 || members.size() > FS_PACK_MAX_MEMBERS) continue;
+    fs_program::Pack pk;
+    if (fs_pack_create(members.data(), (int32_t)members.size(), &pk.pack) != FS_OK) continue;
+    pk.steps = chosen;
+    for (int s : chosen) {
+      prog->steps[s].pack = (int32_t)prog->packs.size();
+      (*pos)[s] = first;
+    }
+    prog->packs.push_back(pk);
+  }
+  clear_error();
+}
+
+// Where tensors that cross patterns live: placed by lifetime, from the position their maker runs at to the position
+// of their last reader; then every buffer reference of every step is resolved to a graph input, a graph output or
+// a workspace offset.  Returns the workspace size.
+int64_t place_buffers(const fs_graph& g, fs_program* prog, const std::vector<int>& pos) {
+  const int ns = (int)prog->steps.size();
+  std::map<int32_t, int> last_read;
+  for (int s = 0; s < ns; ++s)
+    for (const BufRef& r : prog->steps[s].in) {
+      const int at = std::max(pos[s], s);
+      auto it = last_read.find(r.slot);
+      if (it == last_read.end() || it->second < at) last_read[r.slot] = at;
+    }
+  int64_t fixed = 0;   // the plans' own workspaces: never shared, so arrival counters stay as their kernels left them
+  for (int s = 0; s < ns; ++s) {
+    const int64_t need = prog->steps[s].plan->candidates[prog->steps[s].plan->chosen].info.workspace_bytes;
+    prog->steps[s].plan_ws_offset = fixed;
+    fixed += align256(need);
+  }
+  Arena arena;
+  std::map<int32_t, int64_t> where;
+  for (int s = 0; s < ns; ++s)
+    for (const BufRef& r : prog->steps[s].out) {
+      const Tensor& T = g.tensors[r.slot];
+      if (T.output_slot >= 0) continue;
+      const int begin = pos[s];
+      const int end = std::max(begin, last_read.count(r.slot) ? last_read[r.slot] : begin);
+      where[r.slot] = fixed + arena.place(T.numel() * dtype_bytes(T.dtype), begin, end);
+    }
+  auto resolve = [&](BufRef* r) {
+    const Tensor& T = g.tensors[r->slot];
+    if (T.producer < 0) { r->kind = BUF_INPUT; r->slot = T.input_slot; }
+    else if (T.output_slot >= 0) { r->kind = BUF_OUTPUT; r->slot = T.output_slot; }
+    else { r->kind = BUF_WORKSPACE; r->offset = where[r->slot]; r->slot = 0; }
+  };
+  for (fs_program::Step& s : prog->steps) {
+    for (BufRef& r : s.in) resolve(&r);
+    for (BufRef& r : s.out) resolve(&r);
+  }
+  return fixed + arena.top;
+}
+
+void fill_info(const Explorer& ex, fs_program* prog, int32_t beam_plans, double f_total_us, int64_t workspace_bytes) {
+  fs_program_info& I = prog->info;
+  I.n_ops = ex.n;
+  I.beam_plans = beam_plans;
+  I.workspace_bytes = workspace_bytes;
+  I.bytes_min = graph_bytes_min(ex.g);
+  I.f_total_us = f_total_us;
+  std::set<int> counted_packs;
+  for (const fs_program::Step& s : prog->steps) {
+    const fs_plan_info& pi = s.plan->candidates[s.plan->chosen].info;
+    if (s.ops.size() > 1) ++I.n_patterns; else ++I.n_single_ops;
+    I.bytes_moved_model += pi.bytes_moved_model;
+    if (s.pack >= 0) {
+      if (counted_packs.insert(s.pack).second) {
+        I.n_kernels += prog->packs[s.pack].pack->info.n_kernels;
+        I.predicted_us += prog->packs[s.pack].pack->info.predicted_us;
+        ++I.n_steps;
+      }
+    } else {
+      I.n_kernels += pi.n_kernels;
+      I.predicted_us += pi.predicted_us;
+      ++I.n_steps;
+    }
+  }
+  I.n_packs = (int32_t)prog->packs.size();
+  for (int o = 0; o < ex.n; ++o) I.predicted_unfused_us += ex.t_single(o) * 1e6;
+}
+
 }  // namespace
 
 extern "C" {
@@ -569,231 +777,37 @@ fs_status fs_explore(const fs_graph* g, const fs_explore_opts* opts, fs_program*
   ex.explore_patterns();
   const std::vector<Explorer::PlanSet> plans = ex.beam();
 
-  // Final choice among the beam's plans by the full latency evaluator: every pattern (and every op
-  // left alone) is planned for real and the predicted times are added up.
-  struct Built {
-    std::vector<fs_program::Step> steps;
-    double predicted = 0;
-    double f = 0;          // accumulated score after remote fusion
-    bool ok = false;
-  };
-  auto destroy = [](Built* b) {
-    for (fs_program::Step& s : b->steps) fs_plan_destroy(s.plan);
-    b->steps.clear();
-  };
-  std::vector<Built> built(plans.size());
+  // Final choice among the beam's plans by the full latency evaluator (Section 5.3): every pattern, and every op
+  // left alone, is planned for real and the predicted times are added up.
+  std::vector<BuiltPlan> built(plans.size());
   fs_status first_error = FS_OK;
   std::string first_text;
   for (size_t k = 0; k < plans.size(); ++k) {
-    Built& b = built[k];
-    std::vector<OpSet> groups = plans[k].patterns;
-    for (int o = 0; o < ex.n; ++o)
-      if (!((plans[k].covered[o / 64] >> (o % 64)) & 1)) groups.push_back(OpSet{o});
-    if (remote_fusion) built[k].f = plans[k].f + ex.merge_remote(&groups);
-    else built[k].f = plans[k].f;
-    b.ok = true;
-    for (const OpSet& p : groups) {
-      SubGraph sub;
-      fs_status st = ex.extract(p, &sub);
-      if (st != FS_OK) {
-        b.ok = false;
-        if (first_error == FS_OK) {
-          first_error = st == FS_ERR_DTYPE ? FS_ERR_DTYPE : st;
-          first_text = st == FS_ERR_DTYPE ? "a tensor that is stored as a graph output in another dtype than it was computed in also feeds "
-                                            "ops that cannot join its pattern; add an explicit convert and read its result"
-                                          : fs_last_error();
-        }
-        break;
-      }
-      fs_program::Step step;
-      step.ops = p;
-      step.f = p.size() > 1 ? ex.score(p).f : 0.0;
-      st = fs_plan_create(sub.g, FS_SCHEME_AUTO, nullptr, &step.plan);
-      if (st != FS_OK) {
-        b.ok = false;
-        if (first_error == FS_OK) { first_error = st; first_text = fs_last_error(); }
-        break;
-      }
-      for (int32_t t : sub.in_tensor) {
-        BufRef r;
-        r.kind = BUF_INPUT;
-        r.slot = t;           // big-graph tensor id for now; resolved once the order is known
-        step.in.push_back(r);
-      }
-      for (int32_t t : sub.out_tensor) {
-        BufRef r;
-        r.kind = BUF_OUTPUT;
-        r.slot = t;
-        step.out.push_back(r);
-      }
-      b.predicted += step.plan->candidates[step.plan->chosen].info.predicted_us;
-      b.steps.push_back(std::move(step));
-    }
-    if (!b.ok) destroy(&b);
+    std::string text;
+    const fs_status st = build_steps(&ex, plans[k], remote_fusion, &built[k], &text);
+    if (st != FS_OK && first_error == FS_OK) { first_error = st; first_text = text; }
   }
   int best = -1;
   for (size_t k = 0; k < built.size(); ++k)
     if (built[k].ok && (best < 0 || built[k].predicted < built[best].predicted)) best = (int)k;
-  if (best < 0) {
-    for (Built& b : built) destroy(&b);
-    return fail(first_error != FS_OK ? first_error : FS_ERR_UNSUPPORTED_PATTERN, "fs_explore: %s", first_text.c_str());
-  }
   for (size_t k = 0; k < built.size(); ++k)
-    if ((int)k != best) destroy(&built[k]);
+    if ((int)k != best) built[k].destroy();
+  if (best < 0) return fail(first_error != FS_OK ? first_error : FS_ERR_UNSUPPORTED_PATTERN, "fs_explore: %s", first_text.c_str());
 
   fs_program* prog = new (std::nothrow) fs_program();
-  if (!prog) { destroy(&built[best]); return fail(FS_ERR_INVALID_ARG, "fs_explore: out of host memory"); }
-  // dependence order of the patterns: a pattern runs after every pattern that makes one of its operands.  Patterns are
-  // convex, so ordering them by their last op respects every edge between patterns.
-  std::vector<fs_program::Step>& steps = built[best].steps;
-  std::stable_sort(steps.begin(), steps.end(), [](const fs_program::Step& a, const fs_program::Step& b) { return a.ops.back() < b.ops.back(); });
-  // That order can still place a consumer before a producer whose last op comes later; repair by a topological pass.
-  {
-    std::vector<int> owner(ex.n, -1);
-    for (size_t s = 0; s < steps.size(); ++s)
-      for (int o : steps[s].ops) owner[o] = (int)s;
-    const size_t ns = steps.size();
-    std::vector<std::set<int>> deps(ns);
-    for (size_t s = 0; s < ns; ++s)
-      for (int o : steps[s].ops)
-        for (int k = 0; k < g->ops[o].n_in; ++k) {
-          const int32_t prod = g->tensors[g->ops[o].in[k]].producer;
-          if (prod >= 0 && owner[prod] != (int)s) deps[s].insert(owner[prod]);
-        }
-    std::vector<int> order;
-    std::vector<char> done(ns, 0);
-    while (order.size() < ns) {
-      bool progressed = false;
-      for (size_t s = 0; s < ns; ++s) {
-        if (done[s]) continue;
-        bool ready = true;
-        for (int d : deps[s])
-          if (!done[d]) ready = false;
-        if (ready) { done[s] = 1; order.push_back((int)s); progressed = true; }
-      }
-      if (!progressed) {   // cannot happen for convex patterns
-        delete prog;
-        destroy(&built[best]);
-        return fail(FS_ERR_CYCLE, "fs_explore: the chosen patterns depend on each other cyclically");
-      }
-    }
-    std::vector<fs_program::Step> sorted;
-    for (int s : order) sorted.push_back(std::move(steps[s]));
-    steps.swap(sorted);
+  if (!prog) { built[best].destroy(); return fail(FS_ERR_INVALID_ARG, "fs_explore: out of host memory"); }
+  if (!order_steps(*g, &built[best].steps)) {   // cannot happen for convex patterns
+    delete prog;
+    built[best].destroy();
+    return fail(FS_ERR_CYCLE, "fs_explore: the chosen patterns depend on each other cyclically");
   }
-
-  prog->steps = std::move(steps);
-  steps.clear();
-  const int ns = (int)prog->steps.size();
-  std::vector<int> owner(ex.n, -1);
-  for (int s = 0; s < ns; ++s)
-    for (int o : prog->steps[s].ops) owner[o] = s;
-
-  // remote fusion: launch-bound patterns with no dependence between them share one packed launch, issued where
-  // the first of them stands; a member joins only if everything it reads is made before that point
-  std::vector<int> pos(ns);
-  for (int s = 0; s < ns; ++s) pos[s] = s;
-  if (pack_tiny) {
-    std::vector<int> level(ns, 0);
-    for (int s = 0; s < ns; ++s)
-      for (int o : prog->steps[s].ops)
-        for (int k = 0; k < g->ops[o].n_in; ++k) {
-          const int32_t prod = g->tensors[g->ops[o].in[k]].producer;
-          if (prod >= 0 && owner[prod] != s) level[s] = std::max(level[s], level[owner[prod]] + 1);
-        }
-    const double tiny_us = 3.0 * device().launch_s * 1e6;   // the launch is a third or more of the pattern's estimated time
-    std::map<int, std::vector<int>> by_level;
-    for (int s = 0; s < ns; ++s) {
-      const fs_plan* p = prog->steps[s].plan;
-      if (p->pack.spec >= 0 && p->candidates[p->chosen].info.predicted_us <= tiny_us) by_level[level[s]].push_back(s);
-    }
-    for (auto& kv : by_level) {
-      if (kv.second.size() < 2) continue;
-      std::vector<const fs_plan*> members;
-      std::vector<int> chosen;
-      const int first = kv.second.front();
-      for (int s : kv.second) {
-        bool ready = true;
-        for (const BufRef& r : prog->steps[s].in) {
-          const int32_t prod = g->tensors[r.slot].producer;
-          if (prod >= 0 && owner[prod] >= first) ready = false;
-        }
-        if (ready) { members.push_back(prog->steps[s].plan); chosen.push_back(s); }
-      }
-      if (members.size() < 2 || members.size() > FS_PACK_MAX_MEMBERS) continue;
-      fs_program::Pack pk;
-      if (fs_pack_create(members.data(), (int32_t)members.size(), &pk.pack) != FS_OK) continue;
-      pk.steps = chosen;
-      for (int s : chosen) {
-        prog->steps[s].pack = (int32_t)prog->packs.size();
-        pos[s] = first;
-      }
-      prog->packs.push_back(pk);
-    }
-    clear_error();
-  }
-
-  // where tensors that cross patterns live: placed by lifetime, from the position their maker runs at to the
-  // position of their last reader
-  std::map<int32_t, int> last_read;
-  for (int s = 0; s < ns; ++s)
-    for (const BufRef& r : prog->steps[s].in) {
-      auto it = last_read.find(r.slot);
-      if (it == last_read.end() || it->second < std::max(pos[s], s)) last_read[r.slot] = std::max(pos[s], s);
-    }
-  int64_t fixed = 0;   // plans' own workspaces: never shared, so arrival counters stay as their kernels left them
-  for (int s = 0; s < ns; ++s) {
-    const int64_t need = prog->steps[s].plan->candidates[prog->steps[s].plan->chosen].info.workspace_bytes;
-    prog->steps[s].plan_ws_offset = fixed;
-    fixed += align256(need);
-  }
-  Arena arena;
-  std::map<int32_t, int64_t> where;
-  for (int s = 0; s < ns; ++s)
-    for (const BufRef& r : prog->steps[s].out) {
-      const Tensor& T = g->tensors[r.slot];
-      if (T.output_slot >= 0) continue;
-      const int begin = pos[s];
-      const int end = std::max(begin, last_read.count(r.slot) ? last_read[r.slot] : begin);
-      where[r.slot] = fixed + arena.place(T.numel() * dtype_bytes(T.dtype), begin, end);
-    }
-  auto resolve = [&](BufRef* r) {
-    const Tensor& T = g->tensors[r->slot];
-    if (T.producer < 0) { r->kind = BUF_INPUT; r->slot = T.input_slot; }
-    else if (T.output_slot >= 0) { r->kind = BUF_OUTPUT; r->slot = T.output_slot; }
-    else { r->kind = BUF_WORKSPACE; r->offset = where[r->slot]; r->slot = 0; }
-  };
-  for (fs_program::Step& s : prog->steps) {
-    for (BufRef& r : s.in) resolve(&r);
-    for (BufRef& r : s.out) resolve(&r);
-  }
-
-  // figures
-  fs_program_info& I = prog->info;
-  I.n_ops = ex.n;
-  I.beam_plans = (int32_t)plans.size();
-  I.workspace_bytes = fixed + arena.top;
-  I.bytes_min = graph_bytes_min(*g);
-  I.f_total_us = built[best].f;
-  std::set<int> counted_packs;
-  for (const fs_program::Step& s : prog->steps) {
-    const fs_plan_info& pi = s.plan->candidates[s.plan->chosen].info;
-    if (s.ops.size() > 1) ++I.n_patterns; else ++I.n_single_ops;
-    I.bytes_moved_model += pi.bytes_moved_model;
-    if (s.pack >= 0) {
-      if (counted_packs.insert(s.pack).second) {
-        I.n_kernels += prog->packs[s.pack].pack->info.n_kernels;
-        I.predicted_us += prog->packs[s.pack].pack->info.predicted_us;
-        ++I.n_steps;
-      }
-    } else {
-      I.n_kernels += pi.n_kernels;
-      I.predicted_us += pi.predicted_us;
-      ++I.n_steps;
-    }
-  }
-  I.n_packs = (int32_t)prog->packs.size();
-  for (int o = 0; o < ex.n; ++o) I.predicted_unfused_us += ex.t_single(o) * 1e6;
+  prog->steps = std::move(built[best].steps);
+  built[best].steps.clear();
+  std::vector<int> pos(prog->steps.size());   // where in the order a step's kernel is issued (packed members: at the first member)
+  for (size_t s = 0; s < pos.size(); ++s) pos[s] = (int)s;
+  if (pack_tiny) decide_packs(*g, prog, &pos);
+  const int64_t workspace = place_buffers(*g, prog, pos);
+  fill_info(ex, prog, (int32_t)plans.size(), built[best].f, workspace);
   prog->n_inputs = (int32_t)g->inputs.size();
   prog->n_outputs = (int32_t)g->outputs.size();
   *out = prog;
