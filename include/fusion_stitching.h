@@ -182,6 +182,32 @@ fs_status fs_plan_candidate(const fs_plan *p, int32_t index, fs_plan_info *out);
  * Errors: FS_ERR_INVALID_ARG.                                                          */
 int64_t fs_plan_describe(const fs_plan *p, char *text, size_t capacity);
 
+/* ---- generated kernels (Section 4: the code generator turns a fusion pattern into one
+ * kernel) -------------------------------------------------------------------------
+ * A pattern that no hand-written kernel family covers, but whose reuse stays inside a
+ * row, is offered in two forms: as an interpreted row program (one fixed kernel walks an
+ * instruction list) and as a generated kernel (HIP source specialised to the pattern, its
+ * extents and its launch shape, compiled for gfx950 by the HIP run-time compiler when the
+ * plan is created; fs_plan_info.kernel then starts with "row_generated").  Compiled kernels
+ * are shared between plans with identical source and stay loaded until the process ends.
+ * Compilation needs no GPU; the module is loaded on the device that is current at plan
+ * creation (or, without one, by the first fs_execute: do that one outside stream capture).
+ * If the compiler is not available, compilation fails or the kernel would spill registers,
+ * the choice falls back to the next best candidate.                                   */
+
+/* Process-wide switch for offering generated kernels (default 1; the environment variable
+ * FS_CODEGEN=0 sets the default to 0).  Affects plans, scores and programs created
+ * afterwards.  Returns the previous effective setting.                                 */
+int32_t fs_codegen_enable(int32_t on);
+/* 1 if the run-time compiler could be loaded in this process, else 0.                 */
+int32_t fs_codegen_available(void);
+/* Writes the HIP source of the plan's generated kernel(s) (the kernel function only, not
+ * the fixed device headers it is compiled with) into `text` (HOST buffer of `capacity`
+ * bytes, NUL-terminated, truncated if too small) and returns the size needed including
+ * the NUL (1 for a plan without a generated kernel), or a negative error.
+ * Errors: FS_ERR_INVALID_ARG.                                                          */
+int64_t fs_plan_source(const fs_plan *p, char *text, size_t capacity);
+
 /* ---- execution (the run-time hot path) --------------------------------------- */
 
 /* Enqueues the plan's kernel(s) on `hip_stream` (a hipStream_t; null = the

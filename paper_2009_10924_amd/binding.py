@@ -28,7 +28,7 @@ ERROR_NAME = {0: "FS_OK", -1: "FS_ERR_INVALID_ARG", -2: "FS_ERR_SHAPE", -3: "FS_
 EXPORTS = [
     "fs_graph_create", "fs_graph_destroy", "fs_graph_input", "fs_graph_op", "fs_graph_output",
     "fs_graph_finalize", "fs_plan_create", "fs_plan_destroy", "fs_plan_query", "fs_plan_candidate", "fs_plan_describe",
-    "fs_execute", "fs_stream_copy", "fs_last_error", "fs_version",
+    "fs_plan_source", "fs_codegen_enable", "fs_codegen_available", "fs_execute", "fs_stream_copy", "fs_last_error", "fs_version",
     "fs_pack_create", "fs_pack_destroy", "fs_pack_query", "fs_pack_execute",
     "fs_explore", "fs_explore_score", "fs_program_destroy", "fs_program_query", "fs_program_pattern", "fs_program_execute",
 ]
@@ -163,6 +163,12 @@ def load() -> C.CDLL:
     lib.fs_plan_candidate.restype = i32
     lib.fs_plan_describe.argtypes = [vp, C.c_char_p, C.c_size_t]
     lib.fs_plan_describe.restype = C.c_int64
+    lib.fs_plan_source.argtypes = [vp, C.c_char_p, C.c_size_t]
+    lib.fs_plan_source.restype = C.c_int64
+    lib.fs_codegen_enable.argtypes = [C.c_int32]
+    lib.fs_codegen_enable.restype = C.c_int32
+    lib.fs_codegen_available.argtypes = []
+    lib.fs_codegen_available.restype = C.c_int32
     lib.fs_execute.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp, C.c_size_t, vp]
     lib.fs_execute.restype = i32
     lib.fs_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
@@ -290,6 +296,15 @@ class Plan:
         self._lib.fs_plan_describe(self.handle, buf, int(need))
         return buf.value.decode()
 
+    def source(self) -> str:
+        """HIP source of the plan's generated kernel ('' if it runs a compiled-in kernel)."""
+        need = self._lib.fs_plan_source(self.handle, None, 0)
+        if need < 0:
+            _check(int(need))
+        buf = C.create_string_buffer(int(need))
+        self._lib.fs_plan_source(self.handle, buf, int(need))
+        return buf.value.decode()
+
     def candidates(self) -> List[Dict]:
         out = []
         for i in range(self.info["n_candidates"]):
@@ -365,6 +380,15 @@ class Pack:
 
     def execute_ptrs(self, inputs: Sequence[int], outputs: Sequence[int], stream: int) -> None:
         self.bind(inputs, outputs, stream)()
+
+
+def codegen_enable(on: bool) -> bool:
+    """Process-wide switch for offering generated kernels; returns the previous setting."""
+    return bool(load().fs_codegen_enable(1 if on else 0))
+
+
+def codegen_available() -> bool:
+    return bool(load().fs_codegen_available())
 
 
 def explore_score(graph: Graph, ops: Sequence[int]) -> float:

@@ -16,10 +16,14 @@ LIB_PATH = os.path.join(PKG_DIR, "libfusion_stitching.so")
 
 SOURCES = [
     "fs_graph.cpp", "fs_unfused.cpp", "fs_match.cpp", "fs_cost.cpp", "fs_stitch.cpp", "fs_family_softmax.cpp", "fs_family_layernorm.cpp", "fs_family_gelu.cpp",
-    "fs_family_transpose.cpp", "fs_family_rows.cpp", "fs_plan.cpp", "fs_pack.cpp", "fs_rowprog.cpp", "fs_explore.cpp",
+    "fs_family_transpose.cpp", "fs_family_rows.cpp", "fs_plan.cpp", "fs_pack.cpp", "fs_rowprog.cpp", "fs_explore.cpp", "fs_codegen.cpp",
     "kernels/launch.hip", "kernels/unfused.hip", "kernels/softmax.hip", "kernels/layernorm.hip",
     "kernels/gelu.hip", "kernels/tchain.hip", "kernels/rowops.hip", "kernels/pack.hip", "kernels/rowprog.hip",
+    "kernels/gen_runtime.hip", "kernels/gen_sample.hip",
 ]
+
+# device headers the run-time compiler gets as text in front of a generated kernel: (file, name of the C string)
+EMBEDDED = [("kernels/device_utils.hpp", "kEmbeddedDeviceUtils"), ("kernels/gen_support.hpp", "kEmbeddedGenSupport")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function"]
@@ -47,8 +51,27 @@ def _compile(src: str, verbose: bool) -> str:
     return obj
 
 
+def _embed_sources() -> None:
+    """csrc/build/embedded_sources.inc: each embedded header as a raw string literal, without `#pragma once`
+    and without its includes of the library's own headers (their text is concatenated in order instead)."""
+    parts = []
+    for rel, name in EMBEDDED:
+        with open(os.path.join(CSRC, rel)) as f:
+            lines = [l for l in f.read().splitlines() if l.strip() != "#pragma once" and not l.startswith('#include "')]
+        text = "\n".join(lines) + "\n"
+        assert ')FSRC"' not in text
+        parts.append(f'static const char {name}[] = R"FSRC({text})FSRC";\n')
+    path = os.path.join(OBJ_DIR, "embedded_sources.inc")
+    new = "".join(parts)
+    old = open(path).read() if os.path.exists(path) else None
+    if new != old:
+        with open(path, "w") as f:
+            f.write(new)
+
+
 def build(verbose: bool = False, jobs: int | None = None) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
+    _embed_sources()
     jobs = jobs or min(8, len(SOURCES), os.cpu_count() or 1)
     with cf.ThreadPoolExecutor(max_workers=jobs) as pool:
         objs = list(pool.map(lambda s: _compile(s, verbose), SOURCES))

@@ -1,0 +1,183 @@
+// Code generator for row patterns (paper Section 4: "the code generator takes a fusion
+// pattern as input and produces a GPU kernel").  Input is the instruction list the row-program
+// compiler made for the pattern (an accumulator machine over full-shaped and per-row values);
+// output is HIP source of ONE straight-line kernel specialised to the pattern, its extents
+// and its launch shape: every kept value is a named array of registers, so the device
+// compiler does the register allocation and scheduling that the interpreter pays for at
+// run time with an LDS register file and a dispatch per instruction.  The source is
+// compiled at plan time by the run-time compiler (kernels/gen_runtime.hip).
+#include <cstring>
+#include <string>
+
+#include "fs_internal.hpp"
+
+namespace fs {
+namespace {
+
+#include "build/embedded_sources.inc"   // kEmbeddedDeviceUtils, kEmbeddedGenSupport: the two device headers as text
+
+const char* storage_type(int dt) {
+  switch (dt) {
+    case DT_F16: return "f16_t";
+    case DT_BF16: return "bf16_t";
+    default: return "float";
+  }
+}
+
+// a float as source text that compiles back to the same bits
+std::string literal(float v) {
+  uint32_t u;
+  memcpy(&u, &v, 4);
+  char b[96];
+  snprintf(b, sizeof b, "__builtin_bit_cast(float, 0x%08xu /* %.9g */)", u, (double)v);
+  return b;
+}
+
+std::string fmt(const char* f, ...) __attribute__((format(printf, 1, 2)));
+std::string fmt(const char* f, ...) {
+  char b[512];
+  va_list ap;
+  va_start(ap, f);
+  vsnprintf(b, sizeof b, f, ap);
+  va_end(ap);
+  return b;
+}
+
+// `a` (op) `b` as an expression; a is the accumulator's element, b the other operand
+std::string expression(int op, const std::string& a, const std::string& b, int aux) {
+  switch (op) {
+    case PO_ADD: return a + " + " + b;
+    case PO_SUB: return a + " - " + b;
+    case PO_RSUB: return b + " - " + a;
+    case PO_MUL: return a + " * " + b;
+    case PO_DIV: return a + " * fast_rcp(" + b + ")";
+    case PO_RDIV: return b + " * fast_rcp(" + a + ")";
+    case PO_MAX: return "fmaxf(" + a + ", " + b + ")";
+    case PO_SQUARE: return a + " * " + a;
+    case PO_EXP: return "fast_exp(" + a + ")";
+    case PO_RSQRT: return "fast_rsqrt(" + a + ")";
+    case PO_TANH: return "fast_tanh(" + a + ")";
+    case PO_GELU: return "gelu_fwd(" + a + ")";
+    case PO_GELU_GRAD: return "gelu_grad(" + a + ")";
+    case PO_CVT: return fmt("gen_round<%d>(", aux) + a + ")";
+    default: return b;   // PO_LOAD
+  }
+}
+
+// row index of an input stretched along some leading axes, from the row's index (c0, c1, c2) along them
+std::string stretched_row(const uint32_t (&ms)[3]) {
+  return fmt("(size_t)(c0 * %uu + c1 * %uu + c2 * %uu)", ms[0], ms[1], ms[2]);
+}
+
+}  // namespace
+
+const char* generated_kernel_entry() { return "fs_generated_row_kernel"; }
+
+std::string generate_row_kernel_body(const RowProgP& p) {
+  const bool block = p.lanes_per_row > 64;
+  int n_reductions = 0;
+  for (int i = 0; i < p.n_instr; ++i)
+    if (p.instr[i].op == PO_RSUM || p.instr[i].op == PO_RMAX || p.instr[i].op == PO_RSUMSQ) ++n_reductions;
+
+  std::string s;
+  s += "using namespace fsk;\n";
+  s += fmt("extern \"C\" __global__ void __launch_bounds__(256) %s(const GenArgs a) {\n", generated_kernel_entry());
+  s += fmt("  typedef GenRow<%uu, %uu, %d, %d, %uu, %s> Row;\n", p.rows, p.cols, p.vec, p.vecs_per_lane,
+           block ? 256u : (uint32_t)p.lanes_per_row, block ? "true" : "false");
+  s += "  constexpr int KV = Row::KV;\n";
+  if (block && n_reductions > 0) s += fmt("  __shared__ float slots[%d];\n", 4 * n_reductions);
+  s += "  const Row row;\n";
+
+  // ---- every global load is issued before anything waits
+  if (p.full_bcast | p.rscal_bcast) {
+    s += fmt("  const uint32_t q1 = row.row_c / %uu, c2 = row.row_c - q1 * %uu, c0 = q1 / %uu, c1 = q1 - c0 * %uu;\n", p.od[2].d, p.od[2].d,
+             p.od[1].d, p.od[1].d);
+  }
+  for (int i = 0; i < p.n_full; ++i) {
+    const std::string at = ((p.full_bcast >> i) & 1u) ? stretched_row(p.ms[i]) : std::string("(size_t)row.row_c");
+    s += fmt("  const auto raw_full%d = row.load<%s, true>(a.full[%d], %s);\n", i, storage_type(p.full_dt[i]), i, at.c_str());
+  }
+  for (int i = 0; i < p.n_col; ++i)
+    s += fmt("  const auto raw_col%d = row.load<%s, false>(a.col[%d], 0);\n", i, storage_type(p.col_dt[i]), i);
+  for (int i = 0; i < p.n_rscal; ++i) {
+    const std::string at = ((p.rscal_bcast >> i) & 1u) ? stretched_row(p.rms[i]) : std::string("(size_t)row.row_c");
+    s += fmt("  const float in_rscal%d = load1(static_cast<const %s*>(a.rscal[%d]) + %s);\n", i, storage_type(p.rscal_dt[i]), i, at.c_str());
+  }
+
+  // ---- values: the accumulators, the kept full-shaped values, the column vectors, the kept per-row values
+  s += "  float acc[KV], sacc = 0.0f;\n";
+  s += "#pragma unroll\n  for (int j = 0; j < KV; ++j) acc[j] = 0.0f;\n";
+  for (int r = 0; r < p.n_regs; ++r) s += fmt("  float r%d[KV];\n", r);
+  for (int r = 0; r < p.n_sregs; ++r) s += fmt("  float s%d = 0.0f;\n", r);
+  for (int i = 0; i < p.n_col; ++i) {
+    s += fmt("  float c%d[KV];\n", i);
+    s += fmt("  row.unpack_to<%s>(raw_col%d, c%d);\n", storage_type(p.col_dt[i]), i, i);
+  }
+  for (int i = 0; i < p.n_full; ++i) {
+    const bool parked = p.full_reg[i] != 255;
+    const bool to_acc = p.acc_input == i;
+    if (parked) {
+      s += fmt("  row.unpack_to<%s>(raw_full%d, r%d);\n", storage_type(p.full_dt[i]), i, p.full_reg[i]);
+      if (to_acc) s += fmt("#pragma unroll\n  for (int j = 0; j < KV; ++j) acc[j] = r%d[j];\n", p.full_reg[i]);
+    } else if (to_acc) {
+      s += fmt("  row.unpack_to<%s>(raw_full%d, acc);\n", storage_type(p.full_dt[i]), i);
+    }
+  }
+  for (int i = 0; i < p.n_rscal; ++i) s += fmt("  s%d = in_rscal%d;\n", p.rscal_sreg[i], i);
+
+  // ---- the pattern's ops, in the order of the instruction list
+  int reduction_no = 0;
+  for (int i = 0; i < p.n_instr; ++i) {
+    const ProgInstr& in = p.instr[i];
+    const bool scalar = (in.flags & PF_SCALAR) != 0, keep = (in.flags & PF_KEEP) != 0;
+    switch (in.op) {
+      case PO_STORE:
+        s += fmt("  row.store<%s>(a.out[%d], acc);\n", storage_type(in.aux), in.dst);
+        continue;
+      case PO_STORE_SCAL:
+        s += fmt("  row.store_scalar<%s>(a.rout[%d], sacc);\n", storage_type(in.aux), in.dst);
+        continue;
+      case PO_RSUM: case PO_RMAX: case PO_RSUMSQ: {
+        const bool is_max = in.op == PO_RMAX;
+        const std::string slot = block ? fmt("slots + %d", 4 * reduction_no) : std::string("nullptr");
+        s += fmt("  sacc = row.reduce<%s, %s, %s>(acc, %s);\n", is_max ? "OpMax" : "OpSum", is_max ? "true" : "false",
+                 in.op == PO_RSUMSQ ? "true" : "false", slot.c_str());
+        ++reduction_no;
+        if (keep) s += fmt("  s%d = sacc;\n", in.dst);
+        continue;
+      }
+      default:
+        break;
+    }
+    if (scalar) {
+      const std::string b = in.b_kind == PK_SCAL ? fmt("s%d", in.b) : (in.b_kind == PK_SACC ? std::string("sacc") : literal(in.imm));
+      s += "  sacc = " + expression(in.op, "sacc", b, in.aux) + ";\n";
+      if (keep) s += fmt("  s%d = sacc;\n", in.dst);
+      continue;
+    }
+    std::string b;
+    switch (in.b_kind) {
+      case PK_REG: b = fmt("r%d[j]", in.b); break;
+      case PK_COL: b = fmt("c%d[j]", in.b); break;
+      case PK_ACC: b = "acc[j]"; break;
+      case PK_SCAL: b = fmt("s%d", in.b); break;
+      case PK_SACC: b = "sacc"; break;
+      default: b = literal(in.imm); break;
+    }
+    s += "#pragma unroll\n  for (int j = 0; j < KV; ++j) acc[j] = " + expression(in.op, "acc[j]", b, in.aux) + ";\n";
+    if (keep) s += fmt("#pragma unroll\n  for (int j = 0; j < KV; ++j) r%d[j] = acc[j];\n", in.dst);
+  }
+  s += "}\n";
+  return s;
+}
+
+std::string generate_row_kernel(const RowProgP& p) {
+  std::string s;
+  s.reserve(48 * 1024);
+  s += kEmbeddedDeviceUtils;
+  s += kEmbeddedGenSupport;
+  s += generate_row_kernel_body(p);
+  return s;
+}
+
+}  // namespace fs

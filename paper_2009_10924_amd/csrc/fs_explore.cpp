@@ -557,7 +557,7 @@ fs_status build_steps(Explorer* ex, const Explorer::PlanSet& plan, bool remote_f
     if (st == FS_OK) {
       step.ops = p;
       step.f = p.size() > 1 ? ex->score(p).f : 0.0;
-      st = fs_plan_create(sub.g, FS_SCHEME_AUTO, nullptr, &step.plan);
+      st = create_plan(sub.g, FS_SCHEME_AUTO, nullptr, false, &step.plan);   // generated kernels are compiled for the winner only
       if (st != FS_OK) *error_text = fs_last_error();
     }
     if (st != FS_OK) {
@@ -794,6 +794,13 @@ fs_status fs_explore(const fs_graph* g, const fs_explore_opts* opts, fs_program*
     if ((int)k != best) built[k].destroy();
   if (best < 0) return fail(first_error != FS_OK ? first_error : FS_ERR_UNSUPPORTED_PATTERN, "fs_explore: %s", first_text.c_str());
 
+  for (fs_program::Step& s : built[best].steps) {
+    const fs_status st = complete_plan(s.plan);
+    if (st != FS_OK) {
+      built[best].destroy();
+      return st;
+    }
+  }
   fs_program* prog = new (std::nothrow) fs_program();
   if (!prog) { built[best].destroy(); return fail(FS_ERR_INVALID_ARG, "fs_explore: out of host memory"); }
   if (!order_steps(*g, &built[best].steps)) {   // cannot happen for convex patterns

@@ -76,6 +76,7 @@ struct Launch {
   KernelArgs args;               // shapes, flags; pointers patched per execute
   BufRef ptr[kMaxPtrs];          // which buffer each pointer slot takes
   LaunchShape shape;
+  std::shared_ptr<GenKernel> gen;   // K_ROW_GENERATED: the compiled kernel, once the plan that chose it is complete
 };
 
 // Form in which a matched pattern can join a packed launch (one kernel over many
@@ -104,6 +105,7 @@ struct fs_plan {
   std::vector<int64_t> input_bytes, output_bytes;
   fs::PackForm pack;
   int64_t bytes_min = 0;
+  fs_plan_opts opts = {-1, 0, 0, 0};   // what the caller asked for (a re-choice after a failed compile honours it)
 };
 
 // Several independent plans that run as one packed launch per 32 members.
@@ -128,6 +130,19 @@ std::string build_stitched(const fs_graph& g, std::vector<Candidate>* out, PackF
 // Candidates that run `g` as an interpreted row program (fs_rowprog.cpp); false if `g` is not a
 // pattern of element-wise ops and last-axis reductions over one row space.
 bool build_row_program(const fs_graph& g, std::vector<Candidate>* out);
+// Generated row kernels (fs_codegen.cpp): HIP source of the kernel specialised to the program `p` and its
+// launch shape; the body alone (without the embedded device headers) for listings.
+std::string generate_row_kernel(const RowProgP& p);
+std::string generate_row_kernel_body(const RowProgP& p);
+const char* generated_kernel_entry();
+// Process-wide switch: candidates with generated kernels are offered only while it is on (default: on
+// unless the environment says FS_CODEGEN=0) and the run-time compiler is available.
+bool codegen_enabled();
+// fs_plan_create without the last step: generated kernels are not compiled yet.  complete_plan() compiles
+// the chosen candidate's kernel; if that fails, or the kernel spills registers, it moves the choice to the
+// next best candidate (unless the caller fixed the candidate, then it fails).
+fs_status create_plan(const fs_graph* g, int32_t scheme, const fs_plan_opts* opts, bool complete, fs_plan** out);
+fs_status complete_plan(fs_plan* p);
 int64_t graph_bytes_min(const fs_graph& g);
 // Multiply-high constants for n / d with n < 2^31 (d == 0 in the result marks "no usable constants").
 FastDiv make_fastdiv(uint32_t d);

@@ -2,6 +2,8 @@
 // (patch device pointers, enqueue the launches).  fs_execute is the only place where
 // control crosses from host to device.
 #include <algorithm>
+#include <atomic>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 
@@ -25,7 +27,13 @@ void predict(Candidate* c) {
     return;
   }
   const Launch& l = c->launches.front();
-  const KernelResources res = kernel_resources(l.kernel, l.args);
+  KernelResources res;
+  if (l.kernel != K_ROW_GENERATED) {
+    res = kernel_resources(l.kernel, l.args);
+  } else if (l.gen) {   // compiled: the code object states its registers
+    res.vgprs = gen_resources(l.gen.get()).vgprs;
+    res.from_device = res.vgprs > 0;
+  }
   const CostResult r = evaluate(c->cost, res.from_device ? res.vgprs : 0);
   c->info.predicted_us = r.seconds * 1e6;
   c->info.waves_per_simd = r.waves_per_simd;
@@ -40,14 +48,67 @@ static bool satisfies(const fs_plan_info& i, const fs_plan_opts& o) {
   return true;
 }
 
+namespace {
+std::atomic<int> g_codegen{-1};   // -1: not decided yet (the environment decides at first use)
+}
+
+bool codegen_enabled() {
+  int v = g_codegen.load(std::memory_order_relaxed);
+  if (v < 0) {
+    const char* e = getenv("FS_CODEGEN");
+    v = (e && e[0] == '0') ? 0 : 1;
+    g_codegen.store(v, std::memory_order_relaxed);
+  }
+  return v != 0 && gen_available();
+}
+
+fs_status complete_plan(fs_plan* p) {
+  const fs_plan_opts& o = p->opts;
+  for (;;) {
+    Candidate& c = p->candidates[p->chosen];
+    Launch* gen = nullptr;
+    for (Launch& l : c.launches)
+      if (l.kernel == K_ROW_GENERATED && !l.gen) gen = &l;
+    if (!gen) return FS_OK;
+    std::string log;
+    const int err = gen_compile(generate_row_kernel(gen->args.u.prog), generated_kernel_entry(), &gen->gen, &log);
+    bool usable = err == 0;
+    std::string why;
+    if (!usable) {
+      why = "compiling the generated kernel failed: " + log;
+    } else {
+      const GenResources res = gen_resources(gen->gen.get());
+      if (res.scratch_bytes > 0) {   // values spilled to per-lane scratch memory: the shape holds too much per lane
+        usable = false;
+        why = "the generated kernel keeps " + std::to_string(res.scratch_bytes) + " bytes per lane in scratch memory";
+      }
+    }
+    if (usable) {
+      const int e = gen_preload(gen->gen.get());
+      if (e != 0) return fail(FS_ERR_HIP, "fs_plan_create: loading the generated kernel failed: %s", hip_error_text(e));
+      predict(&c);   // with the compiled kernel's own register count
+      return FS_OK;
+    }
+    gen->gen.reset();
+    if (o.candidate >= 0) return fail(FS_ERR_UNSUPPORTED_PATTERN, "fs_plan_create: candidate %d: %s", o.candidate, why.c_str());
+    // this candidate is out; take the best of the rest
+    c.info.predicted_us = 1e30;
+    int best = -1;
+    for (int i = 0; i < (int)p->candidates.size(); ++i) {
+      const Candidate& k = p->candidates[i];
+      if (k.info.predicted_us >= 1e30 || !satisfies(k.info, o)) continue;
+      if (best < 0 || k.info.predicted_us < p->candidates[best].info.predicted_us) best = i;
+    }
+    if (best < 0) return fail(FS_ERR_UNSUPPORTED_PATTERN, "fs_plan_create: %s, and no other candidate has the requested launch shape", why.c_str());
+    p->chosen = best;
+  }
+}
+
 }  // namespace fs
 
 using namespace fs;
 
-extern "C" {
-
-fs_status fs_plan_create(const fs_graph* g, int32_t scheme, const fs_plan_opts* opts, fs_plan** out) {
-  clear_error();
+fs_status fs::create_plan(const fs_graph* g, int32_t scheme, const fs_plan_opts* opts, bool complete, fs_plan** out) {
   if (!g || !out) return fail(FS_ERR_INVALID_ARG, "fs_plan_create: null argument");
   if (!g->finalized) return fail(FS_ERR_INVALID_ARG, "fs_plan_create: graph is not finalized");
   if (scheme < FS_SCHEME_AUTO || scheme > FS_SCHEME_GLOBAL) return fail(FS_ERR_INVALID_ARG, "fs_plan_create: bad scheme %d", scheme);
@@ -108,14 +169,37 @@ fs_status fs_plan_create(const fs_graph* g, int32_t scheme, const fs_plan_opts* 
     p->candidates[i].info.candidate = (int32_t)i;
   }
   p->pack = pack_form;
+  p->opts = o;
   p->bytes_min = graph_bytes_min(*g);
   p->n_inputs = (int32_t)g->inputs.size();
   p->n_outputs = (int32_t)g->outputs.size();
   for (int t : g->inputs) p->input_bytes.push_back(g->tensors[t].numel() * dtype_bytes(g->tensors[t].dtype));
   for (int t : g->outputs) p->output_bytes.push_back(g->tensors[t].numel() * dtype_bytes(g->tensors[t].store_as));
+  if (complete) {
+    const fs_status s = complete_plan(p);
+    if (s != FS_OK) {
+      delete p;
+      return s;
+    }
+  }
   *out = p;
   return FS_OK;
 }
+
+extern "C" {
+
+fs_status fs_plan_create(const fs_graph* g, int32_t scheme, const fs_plan_opts* opts, fs_plan** out) {
+  clear_error();
+  return create_plan(g, scheme, opts, true, out);
+}
+
+int32_t fs_codegen_enable(int32_t on) {
+  const int32_t before = codegen_enabled() ? 1 : 0;
+  g_codegen.store(on ? 1 : 0, std::memory_order_relaxed);
+  return before;
+}
+
+int32_t fs_codegen_available(void) { return gen_available() ? 1 : 0; }
 
 void fs_plan_destroy(fs_plan* p) { delete p; }
 
@@ -155,7 +239,7 @@ int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) {
     snprintf(line, sizeof line, "launch %s grid=%u block=%u lds=%u\n", kernel_name(l.kernel), l.shape.grid[0] * l.shape.grid[1] * l.shape.grid[2],
              l.shape.block[0] * l.shape.block[1] * l.shape.block[2], l.shape.lds_bytes);
     s += line;
-    if (l.kernel != K_ROW_PROGRAM) {
+    if (l.kernel != K_ROW_PROGRAM && l.kernel != K_ROW_GENERATED) {
       for (int k = 0; k < kMaxPtrs; ++k)
         if (l.ptr[k].kind != BUF_NONE) s += "  ptr" + std::to_string(k) + " " + buf_name(l.ptr[k]) + "\n";
       continue;
@@ -197,6 +281,20 @@ int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) {
   return (int64_t)s.size() + 1;
 }
 
+int64_t fs_plan_source(const fs_plan* p, char* text, size_t capacity) {
+  clear_error();
+  if (!p || (!text && capacity > 0)) return fail(FS_ERR_INVALID_ARG, "fs_plan_source: null argument");
+  std::string s;
+  for (const Launch& l : p->candidates[p->chosen].launches)
+    if (l.kernel == K_ROW_GENERATED) s += generate_row_kernel_body(l.args.u.prog);
+  if (capacity > 0) {
+    const size_t n = std::min(capacity - 1, s.size());
+    memcpy(text, s.data(), n);
+    text[n] = 0;
+  }
+  return (int64_t)s.size() + 1;
+}
+
 fs_status fs_execute(const fs_plan* p, const void* const* inputs, void* const* outputs, void* workspace,
                      size_t workspace_bytes, void* hip_stream) {
   clear_error();
@@ -225,7 +323,13 @@ fs_status fs_execute(const fs_plan* p, const void* const* inputs, void* const* o
         default: a.p[k] = nullptr; break;
       }
     }
-    const int err = launch_kernel(l.kernel, a, l.shape, hip_stream);
+    int err;
+    if (l.kernel == K_ROW_GENERATED) {
+      if (!l.gen) return fail(FS_ERR_INVALID_ARG, "fs_execute: the plan's generated kernel was never compiled");
+      err = gen_launch(l.gen.get(), a.p, sizeof(void*) * kMaxPtrs, l.shape, hip_stream);
+    } else {
+      err = launch_kernel(l.kernel, a, l.shape, hip_stream);
+    }
     if (err != 0) return fail(FS_ERR_HIP, "fs_execute: launching %s failed: %s", kernel_name(l.kernel), hip_error_text(err));
   }
   return FS_OK;

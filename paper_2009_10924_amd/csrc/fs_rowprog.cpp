@@ -489,22 +489,33 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
   const double n = (double)base.rows * base.cols;
   const int64_t bytes_min = graph_bytes_min(g);
 
-  struct Shape { uint32_t L; int K; bool block; };
+  struct Shape { uint32_t L; int K; bool block; bool generated; };
   std::vector<Shape> shapes;
   for (int K : {1, 2, 4}) {
     uint32_t L = 1;
     while (L * (uint32_t)K < nvec) L <<= 1;
-    if (L <= 64 && !(K > 1 && (uint64_t)L * K >= 2ull * nvec)) shapes.push_back({L, K, false});
+    if (L <= 64 && !(K > 1 && (uint64_t)L * K >= 2ull * nvec)) shapes.push_back({L, K, false, false});
   }
   if (c.n_reductions <= kProgMaxReductions)
     for (int K : {1, 2, 4})
-      if (256ull * K >= nvec && 64ull * K < nvec) shapes.push_back({256, K, true});   // rows a wavefront cannot hold at this K
+      if (256ull * K >= nvec && 64ull * K < nvec) shapes.push_back({256, K, true, false});   // rows a wavefront cannot hold at this K
+  if (codegen_enabled()) {
+    // generated kernels (listed after the interpreted ones, whose indices stay): any number of vectors per lane
+    // up to 8, so a row can fill its lanes exactly (768 floats: 32 lanes x 6 vectors)
+    for (uint32_t L = 1; L <= 64; L <<= 1) {
+      const uint32_t K = (nvec + L - 1) / L;
+      if (K >= 1 && K <= 8 && (L == 1 || (uint64_t)(L / 2) * K < nvec)) shapes.push_back({L, (int)K, false, true});
+    }
+    const uint32_t KB = (nvec + 255) / 256;
+    if (KB <= 8 && 64ull * 8 < nvec) shapes.push_back({256, (int)KB, true, true});   // rows a wavefront cannot hold
+    if (KB <= 8 && 64ull * 8 >= nvec && 64ull * 2 < nvec) shapes.push_back({256, (int)KB, true, true});
+  }
 
   for (const Shape& s : shapes) {
     const int kv = s.K * vec;
     const int64_t lds = (int64_t)base.n_regs * kv * 4 * 256 + (int64_t)base.n_col * base.cols * 4 +
                         (int64_t)base.n_sregs * 1024 + kProgMaxReductions * 16;
-    if (lds > kProgMaxLdsBytes) continue;
+    if (!s.generated && lds > kProgMaxLdsBytes) continue;
     Candidate cand;
     memset(&cand.info, 0, sizeof cand.info);
     cand.info.scheme = s.block ? FS_SCHEME_LDS : (s.L == 1 ? FS_SCHEME_LOCAL : FS_SCHEME_WAVE);
@@ -561,6 +572,23 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
     kc.access_run_bytes = s.L >= 8 ? 0 : s.L * 16.0;
     kc.preamble_instr = 60;
     cand.cost = kc;
+    if (s.generated) {
+      // the same program as straight-line code of its own: every value in registers, no dispatch, no LDS files
+      Launch& gl = cand.launches.back();
+      gl.kernel = K_ROW_GENERATED;
+      gl.shape.lds_bytes = 0;
+      const int32_t slots = s.block ? 16 * c.n_reductions : 0;
+      cand.info.lds_bytes = slots;
+      snprintf(cand.info.pattern, sizeof cand.info.pattern, "row_generated");
+      snprintf(cand.info.kernel, sizeof cand.info.kernel, "row_generated<v%d,K%d,L%u,I%d,R%d>", vec, s.K, s.L, base.n_instr, base.n_regs);
+      KernelCost& gc = cand.cost;
+      gc.valu_per_elem = 1.0 * c.vec_instr + 1.0 * base.n_full + 1.0 * c.n_out;
+      gc.lds_traffic_bytes = 0;
+      gc.lds_bytes_per_block = slots;
+      gc.vgpr_estimate = 24 + kv * (base.n_regs + 1 + (base.n_col > 0 ? 1 : 0)) + 2 * s.K * base.n_full;
+      gc.preamble_instr = 40;
+      if (gc.vgpr_estimate > 256) continue;   // would not fit the register file without spilling
+    }
     out->push_back(cand);
   }
   return !out->empty();

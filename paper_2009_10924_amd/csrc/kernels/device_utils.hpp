@@ -1,8 +1,14 @@
 // Device-side helpers for gfx950: 128-bit typed loads/stores that widen to float32,
 // round-to-nearest-even narrowing, and wave64 cross-lane reductions.
 #pragma once
+#ifndef __HIPCC_RTC__
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#else
+// run-time compilation: the HIP device declarations are built in, the C headers are not there
+typedef unsigned int uint32_t;
+typedef unsigned short uint16_t;
+#endif
 
 namespace fsk {
 
@@ -150,6 +156,26 @@ __device__ __forceinline__ void store_vec4(f16_t* p, const float (&v)[4]) {
   u32x2 t = {pack_f16(v[0], v[1]), pack_f16(v[2], v[3])};
   *reinterpret_cast<u32x2*>(p) = t;
 }
+
+// Stores VEC(TI) float32 values as TO: a full 128-bit access when the two types are equally
+// wide, a 64-bit one when float32 rows are stored as a 16-bit type.
+template <typename TO, int N> struct StoreN;
+template <typename TO> struct StoreN<TO, 4> {
+  __device__ __forceinline__ static void run(TO* p, const float (&v)[4]) { store_vec4_nt(p, v); }
+};
+template <> struct StoreN<float, 8> {
+  __device__ __forceinline__ static void run(float* p, const float (&v)[8]) {
+    float a[4] = {v[0], v[1], v[2], v[3]}, b[4] = {v[4], v[5], v[6], v[7]};
+    store_vec_nt(p, a);
+    store_vec_nt(p + 4, b);
+  }
+};
+template <> struct StoreN<f16_t, 8> {
+  __device__ __forceinline__ static void run(f16_t* p, const float (&v)[8]) { store_vec_nt(p, v); }
+};
+template <> struct StoreN<bf16_t, 8> {
+  __device__ __forceinline__ static void run(bf16_t* p, const float (&v)[8]) { store_vec_nt(p, v); }
+};
 
 // ---- division by a run-time constant (see fs::FastDiv) -------------------------------
 template <typename FD>

@@ -17,6 +17,7 @@ const KernelDesc kDesc[K_COUNT] = {
     {"softmax_block", 3},  {"layernorm_wave", 8},  {"layernorm_block", 8}, {"bias_gelu", 3},
     {"bias_gelu_dbias", 7}, {"colfold", 3},        {"tchain_wave", 3},    {"tchain_lds", 3},
     {"row_wave", 6},       {"row_block", 6},       {"row_program", 0},    {"layernorm_bwd", 7},
+    {"row_generated", 0},
 };
 
 const void* symbol_for(int32_t kernel, const KernelArgs& a) {

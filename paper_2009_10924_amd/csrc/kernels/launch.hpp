@@ -3,6 +3,8 @@
 // host-only translation units can include it.
 #pragma once
 #include <cstdint>
+#include <memory>
+#include <string>
 
 namespace fs {
 
@@ -35,6 +37,8 @@ enum KernelId : int32_t {
   K_ROW_PROGRAM,       // interpreted row program: p0-3 full inputs, p4-7 column vectors, p8-11 per-row scalar
                        // inputs, p12-15 full outputs, p16-19 per-row scalar outputs
   K_LAYERNORM_BWD,     // p0 h, p1 dy, p2 gamma, p3 mu, p4 rstd, p5 dx, p6 partials [n_row_blocks, 2, cols]
+  K_ROW_GENERATED,     // a kernel generated and compiled for one row pattern at plan time; pointer slots as K_ROW_PROGRAM.
+                       // Not in the compiled-in table: launched through its own handle (gen_launch)
   K_COUNT
 };
 
@@ -266,5 +270,23 @@ int launch_pack(const PackTable& table, void* stream);
 KernelResources pack_kernel_resources();
 const char* kernel_name(int32_t kernel);
 const char* hip_error_text(int err);
+
+// ---- kernels compiled at plan time (kernels/gen_runtime.hip) -------------------------------
+struct GenKernel;   // a compiled code object and, per device, the loaded function
+struct GenResources {
+  int32_t vgprs = 0, static_lds = 0;
+  int32_t scratch_bytes = 0, spilled_vgprs = 0;   // per-lane scratch memory: registers did not suffice
+  int64_t code_bytes = 0;
+};
+// true if the run-time compiler can be loaded in this process
+bool gen_available();
+// Compiles `source` (HIP, one extern "C" kernel `entry`) for gfx950; needs no GPU.  Identical sources share one
+// compiled kernel for the life of the process.  Returns 0 or a hipError_t; *log receives the compiler's messages.
+int gen_compile(const std::string& source, const char* entry, std::shared_ptr<GenKernel>* out, std::string* log);
+GenResources gen_resources(const GenKernel* k);
+// Loads the kernel's module on the current device if there is one (otherwise the first launch does).
+int gen_preload(GenKernel* k);
+// Launches with `args` (args_bytes of by-value kernel arguments).  Returns hipError_t as int.
+int gen_launch(GenKernel* k, const void* args, size_t args_bytes, const LaunchShape& shape, void* stream);
 
 }  // namespace fs

@@ -15,26 +15,6 @@
 namespace fsk {
 using namespace fs;
 
-// Stores VEC(TI) float32 values as TO: a full 128-bit access when the two types are equally
-// wide, a 64-bit one when float32 rows are stored as a 16-bit type.
-template <typename TO, int N> struct StoreN;
-template <typename TO> struct StoreN<TO, 4> {
-  __device__ __forceinline__ static void run(TO* p, const float (&v)[4]) { store_vec4_nt(p, v); }
-};
-template <> struct StoreN<float, 8> {
-  __device__ __forceinline__ static void run(float* p, const float (&v)[8]) {
-    float a[4] = {v[0], v[1], v[2], v[3]}, b[4] = {v[4], v[5], v[6], v[7]};
-    store_vec_nt(p, a);
-    store_vec_nt(p + 4, b);
-  }
-};
-template <> struct StoreN<f16_t, 8> {
-  __device__ __forceinline__ static void run(f16_t* p, const float (&v)[8]) { store_vec_nt(p, v); }
-};
-template <> struct StoreN<bf16_t, 8> {
-  __device__ __forceinline__ static void run(bf16_t* p, const float (&v)[8]) { store_vec_nt(p, v); }
-};
-
 // MODE_WAVE   : a lane group of L lanes of one wavefront owns the row (warp composition).
 // MODE_BLOCK  : the whole workgroup owns the row, per-wave partial results meet in LDS
 //               (block composition); each reduction of a pattern uses its own LDS slot.

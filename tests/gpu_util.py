@@ -92,7 +92,15 @@ def all_candidates(spec, inputs, ref, floors, repeat=1, unfused=True):
     runs = ([("unfused", {})] if unfused else []) + [("auto", {"candidate": i}) for i in range(n)]
     for scheme, opts in runs:
         note(f"  case {spec.name} scheme={scheme} opts={opts}")
-        got, _, info, _ = run_spec(spec, inputs, scheme, repeat=repeat, **opts)
+        try:
+            got, _, info, _ = run_spec(spec, inputs, scheme, repeat=repeat, **opts)
+        except B.FsError as e:
+            # a generated kernel whose launch shape holds more per lane than the register file: the library
+            # refuses the shape when it is asked for by index (AUTO moves on to the next candidate)
+            if "scratch memory" in e.text:
+                note(f"  case {spec.name} opts={opts}: refused, {e.text}")
+                continue
+            raise
         for name, dt in spec.outputs:
             e = check(got[name], ref[name], dt, floors.get(name, 0.0), f"{spec.name}/{info['kernel']}/{name}")
             worst[name] = max(worst.get(name, 0.0), e)

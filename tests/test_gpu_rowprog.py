@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 
 def _run(spec, seed=0, repeat=2):
     info = B.Plan(B.Graph.from_spec(spec), "auto").info
-    assert info["pattern"] == "row_program", (spec.name, info["pattern"])
+    assert info["pattern"] in ("row_program", "row_generated"), (spec.name, info["pattern"])
     inp = make_inputs(spec, seed=seed)
     ref = O.evaluate(spec, inp)
     floors = {name: O.rms(ref[name]) for name, _ in spec.outputs}   # sums and differences cancel in most of these

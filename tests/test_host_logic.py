@@ -116,7 +116,7 @@ def test_unsupported_pattern_and_auto_fallback():
     spec = GraphSpec("custom", [TensorSpec("x", "f32", (8, 16))],
                      [OpSpec("e", "exp", ("x",)), OpSpec("y", "mul", ("e", "x"))], [("y", "f32")])
     info = B.Plan(B.Graph.from_spec(spec), "auto").info
-    assert info["pattern"] == "row_program" and info["n_kernels"] == 1 and info["workspace_bytes"] == 0
+    assert info["pattern"] in ("row_program", "row_generated") and info["n_kernels"] == 1 and info["workspace_bytes"] == 0
     assert ",I3," in info["kernel"]                 # exp (x arrives in the accumulator), mul by x, store
     # ragged softmax still gets a stitched (block-per-row) kernel
     info = B.Plan(B.Graph.from_spec(softmax_graph(5, 37, "f32")), "auto").info
