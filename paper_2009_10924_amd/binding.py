@@ -391,6 +391,21 @@ def codegen_available() -> bool:
     return bool(load().fs_codegen_available())
 
 
+class codegen:
+    """`with codegen(False): ...` plans, scores and explores without generated kernels inside the block."""
+
+    def __init__(self, on: bool):
+        self.on = on
+
+    def __enter__(self):
+        self.before = codegen_enable(self.on)
+        return self
+
+    def __exit__(self, *exc):
+        codegen_enable(self.before)
+        return False
+
+
 def explore_score(graph: Graph, ops: Sequence[int]) -> float:
     """Delta-evaluator score (microseconds) of `ops` taken as one fusion pattern; raises FsError if they cannot be one."""
     return explore_score_ex(graph, ops)[0]

@@ -94,8 +94,12 @@ std::string generate_row_kernel_body(const RowProgP& p) {
              p.od[1].d, p.od[1].d);
   }
   for (int i = 0; i < p.n_full; ++i) {
-    const std::string at = ((p.full_bcast >> i) & 1u) ? stretched_row(p.ms[i]) : std::string("(size_t)row.row_c");
-    s += fmt("  const auto raw_full%d = row.load<%s, true>(a.full[%d], %s);\n", i, storage_type(p.full_dt[i]), i, at.c_str());
+    // an input stretched along leading axes is read by many rows: it goes through the caches like a column vector;
+    // the others are read once and stream past them
+    const bool stretched = ((p.full_bcast >> i) & 1u) != 0;
+    const std::string at = stretched ? stretched_row(p.ms[i]) : std::string("(size_t)row.row_c");
+    s += fmt("  const auto raw_full%d = row.load<%s, %s>(a.full[%d], %s);\n", i, storage_type(p.full_dt[i]), stretched ? "false" : "true", i,
+             at.c_str());
   }
   for (int i = 0; i < p.n_col; ++i)
     s += fmt("  const auto raw_col%d = row.load<%s, false>(a.col[%d], 0);\n", i, storage_type(p.col_dt[i]), i);

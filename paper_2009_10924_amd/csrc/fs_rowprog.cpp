@@ -587,6 +587,11 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
       gc.lds_bytes_per_block = slots;
       gc.vgpr_estimate = 24 + kv * (base.n_regs + 1 + (base.n_col > 0 ? 1 : 0)) + 2 * s.K * base.n_full;
       gc.preamble_instr = 40;
+      // a lane's own instruction stream between its loads landing and its stores leaving: the first and the last
+      // wavefronts of the launch run it with the memory system idle, so long per-lane chains (many vectors per
+      // lane) cost time that more, shorter wavefronts would have overlapped
+      const DeviceModel& d = device();
+      gc.serial_tail_s = 1.5 * kv * (gc.valu_per_elem * d.cycles_valu + gc.trans_per_elem * d.cycles_trans) / d.clock_hz;
       if (gc.vgpr_estimate > 256) continue;   // would not fit the register file without spilling
     }
     out->push_back(cand);

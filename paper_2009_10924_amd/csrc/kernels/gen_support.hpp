@@ -112,16 +112,25 @@ struct GenRow {
   // elements.  slot: 4 floats of LDS private to this reduction (BLOCK only).
   template <typename OP, bool IS_MAX, bool SQUARE>
   __device__ __forceinline__ float reduce(const float (&v)[KV], float* slot) const {
-    float r = IS_MAX ? -__builtin_huge_valf() : 0.0f;
+    // the lane's own elements are combined pairwise (a tree, not a chain): log2(KV) dependent steps instead of
+    // KV, and a float32 sum whose rounding error grows with the depth of the tree
+    float t[KV];
 #pragma unroll
     for (int k = 0; k < K; ++k) {
       const bool ok = valid(k);
 #pragma unroll
       for (int e = 0; e < VEC; ++e) {
         const float x = SQUARE ? v[k * VEC + e] * v[k * VEC + e] : v[k * VEC + e];
-        r = OP::apply(r, FULL_COLS ? x : (ok ? x : (IS_MAX ? -__builtin_huge_valf() : 0.0f)));
+        t[k * VEC + e] = FULL_COLS ? x : (ok ? x : (IS_MAX ? -__builtin_huge_valf() : 0.0f));
       }
     }
+#pragma unroll
+    for (int n = KV; n > 1; n = (n + 1) / 2) {
+#pragma unroll
+      for (int i = 0; i < n / 2; ++i) t[i] = OP::apply(t[2 * i], t[2 * i + 1]);
+      if (n & 1) t[n / 2] = t[n - 1];
+    }
+    const float r = t[0];
     if constexpr (BLOCK) return block_allreduce<OP>(r, slot, 4);
     else return group_allreduce<OP>(r, (int)L);
   }

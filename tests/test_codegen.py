@@ -1,0 +1,116 @@
+"""Host side of the code generator (Section 4: a fusion pattern becomes one kernel): the generated HIP source,
+its compilation by the run-time compiler (needs no GPU), the process-wide switch and the listing calls."""
+import re
+
+import pytest
+
+from paper_2009_10924_amd import binding as B
+from workloads import (layernorm_stats_graph, masked_scores_gate_graph, random_multi_pattern, random_row_pattern,
+                       silu_gate_graph, softmax_graph)
+from workloads.graphs import GraphSpec, OpSpec, TensorSpec
+
+pytestmark = pytest.mark.skipif(not B.codegen_available(), reason="the HIP run-time compiler is not installed here")
+
+
+def _plan(spec, **opts):
+    return B.Plan(B.Graph.from_spec(spec), "auto", **opts)
+
+
+def test_switch_controls_which_candidates_are_offered():
+    spec = layernorm_stats_graph(64, 768, with_variance=True)
+    before = B.codegen_enable(True)
+    try:
+        with B.codegen(True):
+            on = _plan(spec)
+        with B.codegen(False):
+            off = _plan(spec)
+            assert B.codegen_enable(False) is False          # reports the setting it replaces
+        kinds_on = [c["pattern"] for c in on.candidates()]
+        kinds_off = [c["pattern"] for c in off.candidates()]
+        assert set(kinds_off) == {"row_program"}
+        # interpreted candidates first and unchanged, generated ones after them
+        assert kinds_on[:len(kinds_off)] == kinds_off and set(kinds_on[len(kinds_off):]) == {"row_generated"}
+        assert on.info["pattern"] == "row_generated" and off.info["pattern"] == "row_program"
+        assert off.source() == ""
+    finally:
+        B.codegen_enable(before)
+
+
+def test_generated_source_is_specialised_to_pattern_extents_and_shape():
+    spec = layernorm_stats_graph(100, 768, in_dtype="f32", out_dtype="bf16", with_variance=True)
+    plan = _plan(spec)
+    info, src = plan.info, plan.source()
+    assert info["pattern"] == "row_generated" and info["n_kernels"] == 1 and info["workspace_bytes"] == 0
+    m = re.search(r"typedef GenRow<(\d+)u, (\d+)u, (\d+), (\d+), (\d+)u, (true|false)> Row;", src)
+    assert m, src
+    rows, cols, vec, k, lanes, block = int(m[1]), int(m[2]), int(m[3]), int(m[4]), int(m[5]), m[6] == "true"
+    assert (rows, cols, vec) == (100, 768, 4)
+    assert k == info["vecs_per_lane"] and (256 if block else lanes) == info["lanes_per_row"]
+    assert lanes * k * vec >= cols                           # the row fits its lanes
+    # one load per input, every load before the first arithmetic, one store per output
+    body = src.splitlines()
+    first_math = min(i for i, l in enumerate(body) if "acc[j] = acc[j]" in l)
+    loads = [i for i, l in enumerate(body) if "row.load<" in l]
+    assert len(loads) == 5 and max(loads) < first_math
+    assert src.count("row.store<bf16_t>") == 1 and src.count("row.store_scalar<float>") == 3
+    assert src.count("row.reduce<OpSum") == 2 and "true>(acc" in src      # the variance reduction squares on the fly
+    # the compiled kernel's own register count, read from the code object: no GPU needed
+    assert 16 <= info["vgprs"] <= 256
+
+
+def test_every_generated_candidate_compiles_and_reports_registers():
+    spec = silu_gate_graph(64, 4096, "bf16")
+    n = _plan(spec).info["n_candidates"]
+    seen = 0
+    for i in range(n):
+        try:
+            p = _plan(spec, candidate=i)
+        except B.FsError as e:
+            assert "scratch memory" in e.text                # a shape that would spill is refused by index
+            continue
+        if p.info["pattern"] == "row_generated":
+            seen += 1
+            assert p.info["vgprs"] > 0 and "fs_generated_row_kernel" in p.source()
+    assert seen >= 2
+
+
+def test_stretched_operands_and_scalars_appear_as_constants():
+    spec = masked_scores_gate_graph(2, 3, 16, 64, dtype="f16")
+    src = _plan(spec).source()
+    assert "row.row_c / 16u" in src and "/ 3u" in src       # the row's index along the leading axes, by constant divisors
+    assert "row.load<f16_t, false>(a.full[1]" in src         # the mask is re-read by many rows: cached load
+    assert "row.load<f16_t, true>(a.full[0]" in src          # the scores stream
+    assert re.search(r"0x41f00000u /\* 30 \*/", src)         # the immediate, bit-exact
+
+
+def test_patterns_of_hand_written_families_keep_their_kernels():
+    info = _plan(softmax_graph(64, 128, "f32")).info
+    assert info["pattern"] == "softmax" and not info["kernel"].startswith("row_generated")
+
+
+@pytest.mark.parametrize("seed", [3, 17, 42])
+def test_random_patterns_generate_and_compile(seed):
+    spec = random_row_pattern(seed, 37, 96, "f32", n_ops=6 + seed % 12)     # ragged: 37 rows, 24 vectors per row
+    plan = _plan(spec)
+    assert plan.info["pattern"] == "row_generated", plan.info
+    assert plan.source().count("row.store") == len(spec.outputs)
+
+
+def test_explorer_compiles_only_what_the_chosen_plan_runs():
+    spec = random_multi_pattern(5, 24, 64, segments=3, dtype="f32", seg_ops=(4, 8))
+    g = B.Graph.from_spec(spec)
+    with B.codegen(True):
+        prog = B.Program(g)
+    kinds = [p["info"]["pattern"] for p in prog.patterns()]
+    assert "row_generated" in kinds
+    with B.codegen(False):
+        prog_off = B.Program(g)
+    assert "row_generated" not in [p["info"]["pattern"] for p in prog_off.patterns()]
+    # generated kernels are estimated (and measured) faster than the interpreter, so the plan's total drops
+    assert prog.info["predicted_us"] < prog_off.info["predicted_us"]
+
+
+def test_unsupported_pattern_is_not_rescued_by_code_generation():
+    spec = GraphSpec("pattern_x", [TensorSpec("x", "f32", (8, 16))],
+                     [OpSpec("e", "exp", ("x",)), OpSpec("s", "reduce_sum", ("e",), {"axis": 0})], [("s", "f32")])
+    assert _plan(spec).info["scheme"] == "unfused"

@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 
 from oracle import oracle as O
+from paper_2009_10924_amd import binding as B
 from tests.gpu_util import TOL, check, note, run_spec
 from workloads import FULL_CONFIGS, GENERIC_CONFIGS, NEXT_CONFIGS, make_inputs
 
@@ -36,9 +37,19 @@ def test_full_size_config(cfg):
     inp = make_inputs(spec, seed=0)
     note("  oracle")
     ref = O.evaluate(spec, inp)
-    for scheme in ("auto", "unfused"):
+    # patterns on the generic path run three ways: the generated kernel (AUTO), the interpreted row program
+    # (code generation switched off) and per op
+    runs = ("auto", "interpreted", "unfused") if cfg.startswith("G") else ("auto", "unfused")
+    for scheme in runs:
         note(f"  gpu scheme={scheme}")
-        got, _, info, _ = run_spec(spec, inp, scheme, repeat=2)
+        if scheme == "interpreted":
+            with B.codegen(False):
+                got, _, info, _ = run_spec(spec, inp, "auto", repeat=2)
+            assert info["pattern"] == "row_program"
+        else:
+            got, _, info, _ = run_spec(spec, inp, scheme, repeat=2)
+            if cfg.startswith("G") and scheme == "auto":
+                assert info["pattern"] == "row_generated"
         for name, dt in spec.outputs:
             floor = O.rms(ref[name]) if name in RMS_FLOOR.get(cfg, ()) else 0.0
             err = check(got[name], ref[name], dt, floor, f"{cfg}/{info['kernel']}/{name}")

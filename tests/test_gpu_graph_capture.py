@@ -82,11 +82,15 @@ def test_packed_launch_and_explored_program_under_capture():
     _capture_and_replay(call2, outs2, lambda k: ins2[0].mul_(1.0))
 
 
-def test_interpreted_row_program_under_capture():
+@pytest.mark.parametrize("generated", [False, True])
+def test_row_program_under_capture(generated):
+    """The interpreted form (register file beyond 64 KB of LDS) and the generated kernel (launched through its
+    module handle; the module was loaded when the plan was made)."""
     from workloads import layernorm_stats_graph
-    spec = layernorm_stats_graph(5, 4096, in_dtype="f32", out_dtype="f16", with_variance=True)   # register file beyond 64 KB of LDS
-    plan = B.Plan(B.Graph.from_spec(spec), "auto")
-    assert plan.info["pattern"] in ("row_program", "row_generated")
+    spec = layernorm_stats_graph(5, 4096, in_dtype="f32", out_dtype="f16", with_variance=True)
+    with B.codegen(generated):
+        plan = B.Plan(B.Graph.from_spec(spec), "auto")
+    assert plan.info["pattern"] == ("row_generated" if generated else "row_program")
     ins, outs = _buffers(spec)
 
     def call(stream):
