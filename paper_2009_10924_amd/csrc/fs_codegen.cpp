@@ -64,9 +64,9 @@ std::string expression(int op, const std::string& a, const std::string& b, int a
   }
 }
 
-// row index of an input stretched along some leading axes, from the row's index (c0, c1, c2) along them
+// row index of an operand stretched or permuted along the leading axes, from the row's index (lead0, lead1, lead2) along them
 std::string stretched_row(const uint32_t (&ms)[3]) {
-  return fmt("(size_t)(c0 * %uu + c1 * %uu + c2 * %uu)", ms[0], ms[1], ms[2]);
+  return fmt("(size_t)(lead0 * %uu + lead1 * %uu + lead2 * %uu)", ms[0], ms[1], ms[2]);
 }
 
 }  // namespace
@@ -89,9 +89,9 @@ std::string generate_row_kernel_body(const RowProgP& p) {
   s += "  const Row row;\n";
 
   // ---- every global load is issued before anything waits
-  if (p.full_bcast | p.rscal_bcast) {
-    s += fmt("  const uint32_t q1 = row.row_c / %uu, c2 = row.row_c - q1 * %uu, c0 = q1 / %uu, c1 = q1 - c0 * %uu;\n", p.od[2].d, p.od[2].d,
-             p.od[1].d, p.od[1].d);
+  if (p.full_bcast | p.rscal_bcast | p.out_perm) {
+    s += fmt("  const uint32_t q1 = row.row_c / %uu, lead2 = row.row_c - q1 * %uu, lead0 = q1 / %uu, lead1 = q1 - lead0 * %uu;\n", p.od[2].d,
+             p.od[2].d, p.od[1].d, p.od[1].d);
   }
   for (int i = 0; i < p.n_full; ++i) {
     // an input stretched along leading axes is read by many rows: it goes through the caches like a column vector;
@@ -136,7 +136,10 @@ std::string generate_row_kernel_body(const RowProgP& p) {
     const bool scalar = (in.flags & PF_SCALAR) != 0, keep = (in.flags & PF_KEEP) != 0;
     switch (in.op) {
       case PO_STORE:
-        s += fmt("  row.store<%s>(a.out[%d], acc);\n", storage_type(in.aux), in.dst);
+        if ((p.out_perm >> in.dst) & 1u)   // stored through a folded transpose: the row lands at its permuted place
+          s += fmt("  row.store_at<%s>(a.out[%d], %s, acc);\n", storage_type(in.aux), in.dst, stretched_row(p.oms[in.dst]).c_str());
+        else
+          s += fmt("  row.store<%s>(a.out[%d], acc);\n", storage_type(in.aux), in.dst);
         continue;
       case PO_STORE_SCAL:
         s += fmt("  row.store_scalar<%s>(a.rout[%d], sacc);\n", storage_type(in.aux), in.dst);

@@ -245,8 +245,8 @@ int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) {
       continue;
     }
     const RowProgP& q = l.args.u.prog;
-    snprintf(line, sizeof line, "  program vec=%d rows=%u cols=%u lanes=%d vecs=%d regs=%d sregs=%d\n", q.vec, q.rows, q.cols,
-             q.lanes_per_row, q.vecs_per_lane, q.n_regs, q.n_sregs);
+    snprintf(line, sizeof line, "  program vec=%d rows=%u cols=%u lanes=%d vecs=%d regs=%d sregs=%d lead=%u,%u,%u\n", q.vec, q.rows, q.cols,
+             q.lanes_per_row, q.vecs_per_lane, q.n_regs, q.n_sregs, q.od[0].d, q.od[1].d, q.od[2].d);
     s += line;
     for (int i = 0; i < q.n_full; ++i)
       s += "  full " + buf_name(l.ptr[i]) + " reg " + std::to_string(q.full_reg[i]) + " " + dtype_name(q.full_dt[i]) +
@@ -260,7 +260,10 @@ int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) {
            (((q.rscal_bcast >> i) & 1u) ? " rowstrides=" + std::to_string(q.rms[i][0]) + "," + std::to_string(q.rms[i][1]) + "," +
                                               std::to_string(q.rms[i][2]) : std::string()) + "\n";
     for (int i = 0; i < kProgMaxOperands; ++i)
-      if (l.ptr[12 + i].kind != BUF_NONE) s += "  output " + std::to_string(i) + " " + buf_name(l.ptr[12 + i]) + "\n";
+      if (l.ptr[12 + i].kind != BUF_NONE)
+        s += "  output " + std::to_string(i) + " " + buf_name(l.ptr[12 + i]) +
+             (((q.out_perm >> i) & 1u) ? " rowstrides=" + std::to_string(q.oms[i][0]) + "," + std::to_string(q.oms[i][1]) + "," +
+                                            std::to_string(q.oms[i][2]) : std::string()) + "\n";
     for (int i = 0; i < kProgMaxOperands; ++i)
       if (l.ptr[16 + i].kind != BUF_NONE) s += "  routput " + std::to_string(i) + " " + buf_name(l.ptr[16 + i]) + "\n";
     static const char* op_names[] = {"add", "sub", "rsub", "mul", "div", "rdiv", "max", "square", "exp", "rsqrt", "tanh", "gelu",

@@ -41,7 +41,13 @@ struct Compiler {
   int64_t dims[FS_MAX_RANK] = {1, 1, 1, 1};
   uint32_t rows = 0, cols = 0;
   RowProgP p{};
-  std::vector<int32_t> full_in, col_in, rscal_in;   // tensor ids by class
+  std::vector<int32_t> full_in, col_in, rscal_in;   // tensor ids by class (a transposed view of an input: the transpose's result)
+  // Transposes that keep the innermost axis only renumber rows.  One applied to a graph input is folded into
+  // that input's addressing (the view is then an input of the row program, read with permuted row strides); one
+  // that produces a graph output nobody else reads is folded into the store.
+  std::vector<int32_t> view_src;     // per tensor: the graph input it is a transposed view of, else -1
+  std::vector<int32_t> view_op;      // per tensor: the transpose op that makes the view
+  std::vector<int32_t> stored_via;   // per tensor: the transpose op through which it is stored permuted, else -1
   int32_t out_slot[kProgMaxOperands], rout_slot[kProgMaxOperands];
   int n_out = 0, n_rout = 0, n_reductions = 0;
   int vec_instr = 0, scal_instr = 0, reg_reads = 0, reg_writes = 0, trans = 0;
@@ -91,6 +97,28 @@ struct Compiler {
       acc *= d;
     }
   }
+
+  // view = transpose(src, perm), both of the pattern's rank: row of src that holds the view's row, as strides
+  // along the pattern's leading axes (axis k of the view is axis perm[k] of src)
+  void view_row_strides(const Tensor& src, const int32_t* perm, uint32_t (&ms)[3]) const {
+    int64_t stride[FS_MAX_RANK];   // of src, in rows
+    int64_t acc = 1;
+    for (int k = rank - 2; k >= 0; --k) { stride[k] = acc; acc *= src.dims[k]; }
+    for (int k = 0; k < rank - 1; ++k) {
+      const int64_t d = src.dims[perm[k]];
+      ms[3 - (rank - 1) + k] = (d == 1 && dims[k] != 1) ? 0u : (uint32_t)stride[perm[k]];
+    }
+  }
+  // out = transpose(value, perm): row of out that receives the pattern's row (axis j of the pattern's space is
+  // axis k of out with perm[k] == j)
+  void store_row_strides(const Tensor& out, const int32_t* perm, uint32_t (&ms)[3]) const {
+    int64_t acc = 1;
+    for (int k = rank - 2; k >= 0; --k) {
+      ms[3 - (rank - 1) + perm[k]] = (uint32_t)acc;
+      acc *= out.dims[k];
+    }
+  }
+  bool input_like(int t) const { return g.tensors[t].producer < 0 || view_src[t] >= 0; }
 
   static bool scalar_shaped(int kind) { return kind == V_RSCAL; }
   int root_of(int tensor) const { return val[tensor].root; }
@@ -170,7 +198,14 @@ struct Compiler {
       if (!planning && n_out >= kProgMaxOperands) return false;
       if (!load(r, false)) return false;
       s.op = PO_STORE;
-      if (!planning) { s.dst = (uint8_t)n_out; out_slot[n_out++] = T.output_slot; }
+      if (!planning) {
+        if (stored_via[t] >= 0) {
+          p.out_perm |= 1u << n_out;
+          store_row_strides(T, g.ops[stored_via[t]].perm, p.oms[n_out]);
+        }
+        s.dst = (uint8_t)n_out;
+        out_slot[n_out++] = T.output_slot;
+      }
     } else {
       if (!planning && n_rout >= kProgMaxOperands) return false;
       if (!load(r, true)) return false;
@@ -288,10 +323,39 @@ struct Compiler {
   }
 
   bool run() {
-    // anchor = the largest tensor
+    // transposes first: which ones fold into a load or a store (any other kind does not fit a row program)
+    const size_t n_tensors = g.tensors.size();
+    view_src.assign(n_tensors, -1);
+    view_op.assign(n_tensors, -1);
+    stored_via.assign(n_tensors, -1);
+    std::vector<char> skip_for_anchor(n_tensors, 0);
+    for (size_t i = 0; i < g.ops.size(); ++i) {
+      const Op& op = g.ops[i];
+      if (op.opcode != FS_TRANSPOSE) continue;
+      const Tensor& src = g.tensors[op.in[0]];
+      const Tensor& out = g.tensors[op.out];
+      if (op.perm[src.rank - 1] != src.rank - 1) return false;   // the innermost axis moves: data crosses rows
+      if (src.producer < 0) {
+        view_src[op.out] = op.in[0];
+        view_op[op.out] = (int32_t)i;
+      } else if (out.output_slot >= 0 && out.consumers.empty()) {
+        stored_via[op.out] = (int32_t)i;
+        skip_for_anchor[op.out] = 1;
+      } else {
+        return false;
+      }
+    }
+    for (int t : g.inputs) {
+      // an input that is only read through transposed views has no place in the row space by itself
+      bool only_views = !g.tensors[t].consumers.empty();
+      for (int c : g.tensors[t].consumers)
+        if (g.ops[c].opcode != FS_TRANSPOSE) only_views = false;
+      if (only_views) skip_for_anchor[t] = 1;
+    }
+    // anchor = the largest tensor of the row space
     int anchor = -1;
-    for (size_t t = 0; t < g.tensors.size(); ++t)
-      if (anchor < 0 || g.tensors[t].numel() > g.tensors[anchor].numel()) anchor = (int)t;
+    for (size_t t = 0; t < n_tensors; ++t)
+      if (!skip_for_anchor[t] && (anchor < 0 || g.tensors[t].numel() > g.tensors[anchor].numel())) anchor = (int)t;
     if (anchor < 0) return false;
     const Tensor& a = g.tensors[anchor];
     rank = a.rank;
@@ -301,16 +365,34 @@ struct Compiler {
     if (cols < 2) return false;
 
     // classes of all tensors; inputs by class
-    for (size_t t = 0; t < g.tensors.size(); ++t) {
+    for (size_t t = 0; t < n_tensors; ++t) {
       const Tensor& T = g.tensors[t];
       if (T.dtype == FS_I32) return false;
-      val[t].kind = classify(T);
       val[t].root = (int)t;
+      if (skip_for_anchor[t]) {   // lives outside the row space: reached only through its view / its permuted store
+        if (T.rank != rank) return false;
+        val[t].kind = V_FULL;
+        continue;
+      }
+      if (view_src[t] >= 0 && T.rank != rank) return false;
+      val[t].kind = classify(T);
       if (val[t].kind == V_NONE) return false;
     }
+    for (size_t t = 0; t < n_tensors; ++t) {
+      if (stored_via[t] < 0) continue;
+      // what is stored permuted must be a full-shaped value of the row space, with nothing stretched
+      const int src = g.ops[stored_via[t]].in[0];
+      if (val[src].kind != V_FULL || classify(g.tensors[src]) != V_FULL || stretched_rows(g.tensors[src])) return false;
+    }
     bool narrow = false;   // some vector input is 16 bits wide
-    for (int t : g.inputs) {
+    std::vector<int32_t> input_like_tensors;
+    for (int t : g.inputs)
+      if (!skip_for_anchor[t]) input_like_tensors.push_back(t);
+    for (size_t t = 0; t < n_tensors; ++t)
+      if (view_src[t] >= 0) input_like_tensors.push_back((int32_t)t);
+    for (int t : input_like_tensors) {
       const Tensor& T = g.tensors[t];
+      if (view_src[t] >= 0 && val[t].kind != V_FULL) return false;   // a view is addressed by rows
       if (val[t].kind == V_RSCAL) {
         if (rscal_in.size() >= kProgMaxOperands) return false;
         rscal_in.push_back(t);
@@ -333,6 +415,7 @@ struct Compiler {
     const size_t n_ops = g.ops.size();
     reads.assign(n_ops, {});
     is_alias.assign(n_ops, 0);
+    std::vector<char> view_fold(n_ops, 0);
     for (size_t i = 0; i < n_ops; ++i) {
       const Op& op = g.ops[i];
       const Tensor& out = g.tensors[op.out];
@@ -358,8 +441,13 @@ struct Compiler {
           else return false;
           break;
         }
+        case FS_TRANSPOSE:
+          if (view_src[op.out] >= 0) { view_fold[i] = 1; continue; }   // folded into the input's addressing
+          if (stored_via[op.out] != (int32_t)i) return false;
+          is_alias[i] = 1;                                              // folded into the store
+          break;
         default:
-          return false;   // transposes move data between rows
+          return false;
       }
       if (is_alias[i]) {
         if (op.opcode == FS_BROADCAST) {
@@ -379,6 +467,7 @@ struct Compiler {
     }
     for (int t : g.outputs) {
       if (g.tensors[t].producer < 0) return false;
+      if (stored_via[t] >= 0) continue;   // a permutation of the row space: every row is written once
       if (val[t].kind != V_COL && stretched_rows(g.tensors[t])) return false;   // an output must own every row it is stored to
     }
     // peepholes.  (1) square feeding only a row sum / mean: the reduction squares on the fly, so the
@@ -389,6 +478,8 @@ struct Compiler {
       for (int r : reads[i]) ++n_reads[r];
     square_of.assign(n_ops, -1);
     folded.assign(n_ops, 0);
+    for (size_t i = 0; i < n_ops; ++i)
+      if (view_fold[i]) folded[i] = 1;
     for (size_t i = 0; i + 1 < n_ops; ++i) {
       const Op& op = g.ops[i];
       if (op.opcode != FS_SQUARE || is_alias[i] || val[op.out].kind != V_FULL) continue;
@@ -434,6 +525,11 @@ struct Compiler {
       }
       for (size_t i = 0; i < full_in.size(); ++i) {
         const Tensor& T = g.tensors[full_in[i]];
+        if (view_src[full_in[i]] >= 0) {   // rows renumbered by the folded transpose
+          p.full_bcast |= 1u << i;
+          view_row_strides(g.tensors[view_src[full_in[i]]], g.ops[view_op[full_in[i]]].perm, p.ms[i]);
+          continue;
+        }
         if (!stretched_rows(T)) continue;
         p.full_bcast |= 1u << i;
         row_strides(T, p.ms[i]);
@@ -452,7 +548,7 @@ struct Compiler {
     for (size_t i = 0; i < n_ops && acc_start < 0; ++i) {
       if (reads[i].empty()) continue;
       for (int r : reads[i])
-        if (acc_start < 0 && val[r].kind == V_FULL && g.tensors[r].producer < 0) acc_start = r;
+        if (acc_start < 0 && val[r].kind == V_FULL && input_like(r)) acc_start = r;
       break;
     }
     planning = true;
@@ -533,7 +629,12 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
     q.lanes_log2 = lg;
     q.vecs_per_lane = s.K;
     l.args.u.prog = q;
-    auto in_ref = [&](int32_t t) { BufRef r; r.kind = BUF_INPUT; r.slot = g.tensors[t].input_slot; return r; };
+    auto in_ref = [&](int32_t t) {   // a transposed view binds the buffer of the input it views
+      BufRef r;
+      r.kind = BUF_INPUT;
+      r.slot = g.tensors[c.view_src[t] >= 0 ? c.view_src[t] : t].input_slot;
+      return r;
+    };
     for (size_t i = 0; i < c.full_in.size(); ++i) l.ptr[i] = in_ref(c.full_in[i]);
     for (size_t i = 0; i < c.col_in.size(); ++i) l.ptr[4 + i] = in_ref(c.col_in[i]);
     for (size_t i = 0; i < c.rscal_in.size(); ++i) l.ptr[8 + i] = in_ref(c.rscal_in[i]);
@@ -571,6 +672,11 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
     kc.lane_utilisation = (double)nvec / ((double)s.L * s.K);
     kc.access_run_bytes = s.L >= 8 ? 0 : s.L * 16.0;
     kc.preamble_instr = 60;
+    // a lane's own instruction stream between its loads landing and its stores leaving: the first and the last
+    // wavefronts of the launch run it with the memory system idle, so long per-lane chains (many vectors per
+    // lane) cost time that more, shorter wavefronts would have overlapped
+    const DeviceModel& d = device();
+    kc.serial_tail_s = 1.5 * kv * (kc.valu_per_elem * d.cycles_valu + kc.trans_per_elem * d.cycles_trans) / d.clock_hz;
     cand.cost = kc;
     if (s.generated) {
       // the same program as straight-line code of its own: every value in registers, no dispatch, no LDS files
@@ -587,10 +693,6 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
       gc.lds_bytes_per_block = slots;
       gc.vgpr_estimate = 24 + kv * (base.n_regs + 1 + (base.n_col > 0 ? 1 : 0)) + 2 * s.K * base.n_full;
       gc.preamble_instr = 40;
-      // a lane's own instruction stream between its loads landing and its stores leaving: the first and the last
-      // wavefronts of the launch run it with the memory system idle, so long per-lane chains (many vectors per
-      // lane) cost time that more, shorter wavefronts would have overlapped
-      const DeviceModel& d = device();
       gc.serial_tail_s = 1.5 * kv * (gc.valu_per_elem * d.cycles_valu + gc.trans_per_elem * d.cycles_trans) / d.clock_hz;
       if (gc.vgpr_estimate > 256) continue;   // would not fit the register file without spilling
     }

@@ -92,8 +92,12 @@ struct GenRow {
   }
 
   template <typename TO>
-  __device__ __forceinline__ void store(void* p, const float (&v)[KV]) const {
-    TO* base = static_cast<TO*>(p) + (size_t)row * COLS;
+  __device__ __forceinline__ void store(void* p, const float (&v)[KV]) const { store_at<TO>(p, (size_t)row, v); }
+
+  // the row's values to row `at_row` of the output (its own row, or the place a folded transpose gives it)
+  template <typename TO>
+  __device__ __forceinline__ void store_at(void* p, size_t at_row, const float (&v)[KV]) const {
+    TO* base = static_cast<TO*>(p) + at_row * COLS;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
       float part[VEC];

@@ -225,6 +225,10 @@ struct RowProgP {
   uint32_t rscal_bcast;                 // the same for per-row scalar inputs (a per-head value [H,1,1] under [B,H,S,T])
   uint32_t rms[kProgMaxOperands][3];
   FastDiv od[3];
+  // full-shaped outputs stored through a transpose of the leading axes: bit i of out_perm set -> the pattern's
+  // row (c0, c1, c2) is row c0*oms[i][0] + c1*oms[i][1] + c2*oms[i][2] of output i
+  uint32_t out_perm;
+  uint32_t oms[kProgMaxOperands][3];
   uint8_t rscal_sreg[kProgMaxOperands], rscal_dt[kProgMaxOperands];
   ProgInstr instr[kProgMaxInstr];
 };

@@ -163,14 +163,15 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
   for (int j = 0; j < KV; ++j) acc[j] = 0.0f;
   const int acc_input = A->p.acc_input;
 
+  // the row's index along the pattern's (collapsed) leading axes, for inputs stretched along some of them and for
+  // inputs / outputs whose rows are renumbered by a folded transpose
+  uint32_t c0 = 0, c1 = 0, c2 = 0;
   // ---- prologue: every global load is issued before anything waits ------------------------
   // full-shaped inputs are parked in registers of the per-lane file; column vectors are unpacked
   // once per workgroup into the shared column file; per-row scalar inputs go to the scalar file.
   {
     const int n_full = A->p.n_full;
-    // the row's index along the pattern's (collapsed) leading axes, for inputs stretched along some of them
-    uint32_t c0 = 0, c1 = 0, c2 = 0;
-    if (A->p.full_bcast | A->p.rscal_bcast) {
+    if (A->p.full_bcast | A->p.rscal_bcast | A->p.out_perm) {
       const FastDiv od1 = {A->p.od[1].d, A->p.od[1].m, A->p.od[1].s}, od2 = {A->p.od[2].d, A->p.od[2].m, A->p.od[2].s};
       const uint32_t r1 = fast_div(row_c, od2);
       c2 = row_c - r1 * od2.d;
@@ -254,13 +255,15 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
 
     if (op == PO_STORE) {
       void* out = A->out[dst];
+      size_t out_row = row;
+      if ((A->p.out_perm >> dst) & 1u) out_row = (size_t)(c0 * A->p.oms[dst][0] + c1 * A->p.oms[dst][1] + c2 * A->p.oms[dst][2]);
 #pragma unroll
       for (int k = 0; k < K; ++k) {
         float part[VEC];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) part[e] = acc[k * VEC + e];
         if (row_ok && valid(k)) {
-          const size_t at = (size_t)row * cols + (size_t)(lane + k * L) * VEC;
+          const size_t at = out_row * cols + (size_t)(lane + k * L) * VEC;
           if (aux == DT_F32) StoreN<float, VEC>::run(static_cast<float*>(out) + at, part);
           else if (aux == DT_F16) StoreN<f16_t, VEC>::run(static_cast<f16_t*>(out) + at, part);
           else StoreN<bf16_t, VEC>::run(static_cast<bf16_t*>(out) + at, part);

@@ -74,10 +74,40 @@ def test_every_generated_candidate_compiles_and_reports_registers():
     assert seen >= 2
 
 
+def _force_every_generated_candidate(spec):
+    """AUTO falls back to another candidate when a generated kernel does not compile; asking for the candidate by
+    index turns such a failure into an error, so a mistake in the generator cannot hide behind the fallback."""
+    g = B.Graph.from_spec(spec)
+    n = B.Plan(g, "auto").info["n_candidates"]
+    seen = 0
+    for i in range(n):
+        try:
+            p = B.Plan(g, "auto", candidate=i)
+        except B.FsError as e:
+            assert "scratch memory" in e.text, f"{spec.name} candidate {i}: {e.text[:2000]}"
+            continue
+        seen += p.info["pattern"] == "row_generated"
+    return seen
+
+
+def test_generated_source_compiles_for_every_kind_of_operand():
+    from workloads import (bias_head_split_graph, head_merge_residual_graph, normalize_from_stats_graph, outer_scale_graph,
+                           scaled_softmax_colbias_graph, transpose_chain_stats_graph, transposed_softmax_graph)
+    specs = [layernorm_stats_graph(24, 96, in_dtype="bf16", out_dtype="f16", with_variance=True),
+             silu_gate_graph(9, 64, "f16"), scaled_softmax_colbias_graph(13, 40, "f32"),
+             normalize_from_stats_graph(11, 48, "bf16"), outer_scale_graph(7, 16),
+             masked_scores_gate_graph(2, 3, 5, 64, dtype="bf16"),
+             bias_head_split_graph(2, 5, 3, 16, "bf16"), head_merge_residual_graph(2, 5, 3, 64, "f16"),   # column vector + permuted rows
+             transpose_chain_stats_graph(2, 5, 3, 16), transposed_softmax_graph(2, 5, 3, 32, "f16"),
+             layernorm_stats_graph(3, 4096, in_dtype="f32", out_dtype="f32", with_variance=True)]           # workgroup per row
+    for spec in specs:
+        assert _force_every_generated_candidate(spec) >= 1, spec.name
+
+
 def test_stretched_operands_and_scalars_appear_as_constants():
     spec = masked_scores_gate_graph(2, 3, 16, 64, dtype="f16")
     src = _plan(spec).source()
-    assert "row.row_c / 16u" in src and "/ 3u" in src       # the row's index along the leading axes, by constant divisors
+    assert "row.row_c / 16u" in src and "/ 3u" in src and "lead0 * 1u" in src      # the row's index along the leading axes, by constant divisors
     assert "row.load<f16_t, false>(a.full[1]" in src         # the mask is re-read by many rows: cached load
     assert "row.load<f16_t, true>(a.full[0]" in src          # the scores stream
     assert re.search(r"0x41f00000u /\* 30 \*/", src)         # the immediate, bit-exact

@@ -1,14 +1,16 @@
-"""GPU parity of the interpreted row program (the generic stitched path for patterns no
-hand-written kernel family covers): every enumerated launch shape, plus the per-op plan,
-against the float64 oracle; named patterns and seeded random patterns."""
+"""GPU parity of the generic stitched path (patterns no hand-written kernel family covers) in both its
+forms, the interpreted row program and the kernel generated for the pattern: every enumerated launch
+shape of either, plus the per-op plan, against the float64 oracle; named patterns and seeded random
+patterns."""
 import numpy as np
 import pytest
 
 from oracle import oracle as O
 from paper_2009_10924_amd import binding as B
 from tests.gpu_util import all_candidates, note
-from workloads import (layernorm_stats_graph, make_inputs, normalize_from_stats_graph, outer_scale_graph,
-                       random_row_pattern, scaled_softmax_colbias_graph, silu_gate_graph)
+from workloads import (bias_head_split_graph, head_merge_residual_graph, layernorm_stats_graph, make_inputs,
+                       normalize_from_stats_graph, outer_scale_graph, random_row_pattern, scaled_softmax_colbias_graph,
+                       silu_gate_graph, transpose_chain_stats_graph, transposed_softmax_graph)
 
 pytestmark = pytest.mark.gpu
 
@@ -60,6 +62,42 @@ def test_operands_stretched_along_leading_axes(dims, dtype):
     from workloads import masked_scores_gate_graph
     worst, info = _run(masked_scores_gate_graph(*dims, dtype=dtype))
     note(f"masked, per-head scaled, soft-capped softmax {dims} {dtype}: {info['kernel']}, worst {worst}")
+
+
+@pytest.mark.parametrize("dims,dtype", [((2, 40, 3, 64), "bf16"), ((3, 7, 5, 16), "f32"), ((2, 130, 4, 128), "f16"), ((1, 33, 2, 1024), "f32")])
+def test_transposes_folded_into_loads_and_stores(dims, dtype):
+    """[B,S,H,D] <-> [B,H,S,D] around element-wise work and row reductions: the transposes cost no instruction,
+    only the row addressing of a load or of the store changes."""
+    for make in (bias_head_split_graph, head_merge_residual_graph, transposed_softmax_graph):
+        worst, info = _run(make(*dims, dtype=dtype))
+        note(f"{make.__name__} {dims} {dtype}: {info['n_candidates']} shapes, worst {worst}")
+    worst, _ = _run(transpose_chain_stats_graph(*dims, dtype=dtype))
+    note(f"transpose chain + stored row sums {dims} {dtype}: worst {worst}")
+
+
+def test_folded_transposes_move_values_exactly():
+    """x + 0 through a store-side transpose, and a load-side transpose times 1: what arrives is bit-identical to
+    numpy's transpose of the input (float32, bfloat16 and float16 values survive the trip through float32 lanes)."""
+    import torch
+    from workloads.graphs import GraphSpec, OpSpec, TensorSpec
+    from tests.gpu_util import run_spec
+    for dtype in ("f32", "bf16", "f16"):
+        for perm in ((0, 2, 1, 3), (2, 0, 1, 3)):
+            dims = (3, 5, 4, 64)
+            store = GraphSpec(f"pattern_exact_store_{dtype}", [TensorSpec("x", dtype, dims)],
+                              [OpSpec("z", "add_scalar", ("x",), {"value": 0.0}), OpSpec("zc", "convert", ("z",), {"dtype": dtype}),
+                               OpSpec("out", "transpose", ("zc",), {"perm": perm})],
+                              [("out", dtype)])
+            load = GraphSpec(f"pattern_exact_load_{dtype}", [TensorSpec("x", dtype, dims)],
+                             [OpSpec("t", "transpose", ("x",), {"perm": perm}), OpSpec("out", "scale", ("t",), {"value": 1.0})],
+                             [("out", dtype)])
+            for spec in (store, load):
+                inp = make_inputs(spec, seed=3)
+                want = np.transpose(inp["x"], perm)
+                n = B.Plan(B.Graph.from_spec(spec), "auto").info["n_candidates"]
+                for i in range(n):
+                    _, raw, info, _ = run_spec(spec, inp, "auto", candidate=i)
+                    assert np.array_equal(raw["out"].view(np.uint8), np.ascontiguousarray(want).view(np.uint8)), (spec.name, perm, info["kernel"])
 
 
 @pytest.mark.parametrize("seed", range(48))

@@ -41,12 +41,26 @@ def emulate(listing, spec, inputs, anchor_dims):
     in_arrays = [O.to_f64(inputs[t.name], t.dtype).astype(np.float32) for t in spec.inputs]
     regs, sregs, outs, colvecs = {}, {}, {}, {}
     acc0 = None
-    out_bind, rout_bind = {}, {}
+    out_bind, rout_bind, out_rows = {}, {}, {}
+    # the row's index along the (collapsed) leading axes, as the kernels derive it
+    lead = [int(x) for x in kv["lead"].split(",")]
+    r = np.arange(rows)
+    c2, q1 = r % lead[2], r // lead[2]
+    c1, c0 = q1 % lead[1], q1 // lead[1]
+
+    def strided_rows(field):
+        ms = [int(x) for x in field.split("=")[1].split(",")]
+        return c0 * ms[0] + c1 * ms[1] + c2 * ms[2]
+
     for l in lines:
         if not l:
             continue
         if l[0] == "full":
-            full = np.broadcast_to(in_arrays[int(l[1][2:])], anchor_dims).reshape(rows, cols)
+            strides = [x for x in l if x.startswith("rowstrides=")]
+            if strides:   # stretched along leading axes, or rows renumbered by a folded transpose: gather by row strides
+                full = in_arrays[int(l[1][2:])].reshape(-1, cols)[strided_rows(strides[0])]
+            else:
+                full = in_arrays[int(l[1][2:])].reshape(rows, cols)
             if int(l[3]) != 255:
                 regs[int(l[3])] = full
             if l[-1] == "acc":
@@ -54,9 +68,16 @@ def emulate(listing, spec, inputs, anchor_dims):
         elif l[0] == "col":
             colvecs[int(l[3])] = np.broadcast_to(in_arrays[int(l[1][2:])].reshape(1, cols), (rows, cols))
         elif l[0] == "rscal":
-            sregs[int(l[3])] = np.broadcast_to(in_arrays[int(l[1][2:])], tuple(anchor_dims[:-1]) + (1,)).reshape(rows, 1)
+            strides = [x for x in l if x.startswith("rowstrides=")]
+            if strides:
+                sregs[int(l[3])] = in_arrays[int(l[1][2:])].reshape(-1, 1)[strided_rows(strides[0])]
+            else:
+                sregs[int(l[3])] = in_arrays[int(l[1][2:])].reshape(rows, 1)
         elif l[0] == "output":
             out_bind[int(l[1])] = int(l[2][3:])
+            strides = [x for x in l if x.startswith("rowstrides=")]
+            if strides:   # stored through a folded transpose: scatter
+                out_rows[int(l[1])] = strided_rows(strides[0])
         elif l[0] == "routput":
             rout_bind[int(l[1])] = int(l[2][3:])
     acc = np.zeros((rows, cols), np.float32) if acc0 is None else acc0.copy()
@@ -75,7 +96,13 @@ def emulate(listing, spec, inputs, anchor_dims):
         dst = int(f["dst"])
         kind, idx = f["b"].split(":")
         if op == "store":
-            outs[out_bind[dst]] = acc.copy()
+            if dst in out_rows:
+                assert sorted(out_rows[dst]) == list(range(rows)), "the permuted store must write every row once"
+                t = np.empty_like(acc)
+                t[out_rows[dst]] = acc
+                outs[out_bind[dst]] = t
+            else:
+                outs[out_bind[dst]] = acc.copy()
             continue
         if op == "store_scal":
             outs[rout_bind[dst]] = sacc.copy()
@@ -146,6 +173,61 @@ def test_inputs_stretched_along_leading_axes():
     for dims in [(2, 3, 5, 16), (3, 1, 4, 32), (2, 2, 2, 8)]:
         n, info = _compare(masked_scores_gate_graph(*dims, dtype="f32"))
         assert info["pattern"] in ("row_program", "row_generated")
+
+
+def _permuted(dims, perm):
+    return tuple(dims[p] for p in perm)
+
+
+@pytest.mark.parametrize("dims,perm", [
+    ((2, 5, 3, 16), (0, 2, 1, 3)),    # head split / merge: an involution
+    ((2, 5, 3, 16), (2, 0, 1, 3)),    # a rotation of the leading axes: perm and its inverse differ
+    ((3, 2, 4, 8), (1, 2, 0, 3)),
+    ((6, 4, 32), (1, 0, 2)),          # rank 3
+    ((1, 7, 3, 8), (2, 1, 0, 3)),     # an extent of 1 among the permuted axes
+])
+def test_transposes_of_leading_axes_fold_into_loads_and_stores(dims, perm):
+    from workloads.graphs import GraphSpec, OpSpec, TensorSpec
+    out_dims = _permuted(dims, perm)
+    rank = len(dims)
+    # load side: y = exp(tanh(transpose(x))) * g + res, all in the transposed space; the row sums are stored too
+    load = GraphSpec(f"pattern_view_load_{'x'.join(map(str, dims))}_{''.join(map(str, perm))}",
+                     [TensorSpec("x", "f32", dims), TensorSpec("g", "f32", (dims[-1],)), TensorSpec("res", "f32", out_dims)],
+                     [OpSpec("t", "transpose", ("x",), {"perm": perm}), OpSpec("h", "tanh", ("t",)), OpSpec("e", "exp", ("h",)),
+                      OpSpec("u", "mul", ("e", "g")), OpSpec("y", "add", ("u", "res")),
+                      OpSpec("s", "reduce_sum", ("y",), {"axis": rank - 1})],
+                     [("y", "f32"), ("s", "f32")])
+    _, info = _compare(load)
+    listing = B.Plan(B.Graph.from_spec(load), "auto").describe()
+    assert "transpose" not in listing and "rowstrides=" in listing          # no instruction: the load's addressing does it
+    # store side: z = x * r + bias, stored transposed; z's row maxima stored in the original order
+    store = GraphSpec(f"pattern_view_store_{'x'.join(map(str, dims))}_{''.join(map(str, perm))}",
+                      [TensorSpec("x", "f32", dims), TensorSpec("r", "f32", dims[:-1] + (1,)), TensorSpec("bias", "f32", dims[-2:])],
+                      [OpSpec("a", "mul", ("x", "r")), OpSpec("z", "add", ("a", "bias")),
+                       OpSpec("m", "reduce_max", ("z",), {"axis": rank - 1}), OpSpec("out", "transpose", ("z",), {"perm": perm})],
+                      [("out", "f32"), ("m", "f32")])
+    _compare(store)
+    # both sides at once: transposed in, the inverse permutation out (only the arithmetic remains)
+    inverse = tuple(perm.index(k) for k in range(rank))
+    both = GraphSpec(f"pattern_view_both_{'x'.join(map(str, dims))}_{''.join(map(str, perm))}",
+                     [TensorSpec("x", "f32", dims)],
+                     [OpSpec("t", "transpose", ("x",), {"perm": perm}), OpSpec("q", "square", ("t",)),
+                      OpSpec("out", "transpose", ("q",), {"perm": inverse})],
+                     [("out", "f32")])
+    _compare(both)
+
+
+def test_transposes_a_row_program_cannot_fold():
+    from workloads.graphs import GraphSpec, OpSpec, TensorSpec
+    # the innermost axis moves: data crosses rows -> the pattern is not one row kernel
+    spec = GraphSpec("pattern_inner", [TensorSpec("x", "f32", (4, 8, 16))],
+                     [OpSpec("e", "exp", ("x",)), OpSpec("t", "transpose", ("e",), {"perm": (0, 2, 1)})], [("t", "f32")])
+    assert B.Plan(B.Graph.from_spec(spec), "auto").info["scheme"] == "unfused"
+    # a transposed intermediate that is computed on afterwards: neither a load nor a store
+    spec = GraphSpec("pattern_mid", [TensorSpec("x", "f32", (4, 8, 16))],
+                     [OpSpec("e", "exp", ("x",)), OpSpec("t", "transpose", ("e",), {"perm": (1, 0, 2)}), OpSpec("y", "tanh", ("t",))],
+                     [("y", "f32")])
+    assert B.Plan(B.Graph.from_spec(spec), "auto").info["scheme"] == "unfused"
 
 
 def test_layernorm_program_keeps_only_what_is_read_again():

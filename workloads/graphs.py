@@ -355,6 +355,54 @@ def masked_scores_gate_graph(batch: int, heads: int, q_len: int, k_len: int, dty
                      ops=ops, outputs=[("y", dtype)])
 
 
+def bias_head_split_graph(batch: int, seq: int, heads: int, dim: int, dtype: str = "bf16") -> GraphSpec:
+    """Projection bias, then the head split: x[B,S,H,D] + bias[H,D], stored as [B,H,S,D].  The transpose keeps the
+    innermost axis, so a row kernel can fold it into its store."""
+    # arithmetic results are float32; a transpose moves values as they are, so the rounding to the storage dtype
+    # is an op of its own in front of it
+    ops = [_op("z", "add", "x", "bias")]
+    if dtype != "f32":
+        ops.append(_op("zc", "convert", "z", dtype=dtype))
+    ops.append(_op("out", "transpose", ops[-1].out, perm=(0, 2, 1, 3)))
+    return GraphSpec(name=f"pattern_bias_head_split_{dtype}_{batch}x{seq}x{heads}x{dim}",
+                     inputs=[TensorSpec("x", dtype, (batch, seq, heads, dim)), TensorSpec("bias", dtype, (heads, dim))],
+                     ops=ops, outputs=[("out", dtype)])
+
+
+def head_merge_residual_graph(batch: int, seq: int, heads: int, dim: int, dtype: str = "bf16") -> GraphSpec:
+    """Head merge, then a gain per column and a residual: ctx[B,H,S,D] -> [B,S,H,D], times g[D], plus res[B,S,H,D]
+    (the transpose is folded into the load of ctx)."""
+    ops = [_op("t", "transpose", "ctx", perm=(0, 2, 1, 3)), _op("u", "mul", "t", "g"), _op("out", "add", "u", "res")]
+    return GraphSpec(name=f"pattern_head_merge_{dtype}_{batch}x{seq}x{heads}x{dim}",
+                     inputs=[TensorSpec("ctx", dtype, (batch, heads, seq, dim)), TensorSpec("g", dtype, (dim,)),
+                             TensorSpec("res", dtype, (batch, seq, heads, dim))],
+                     ops=ops, outputs=[("out", dtype)])
+
+
+def transpose_chain_stats_graph(batch: int, seq: int, heads: int, dim: int, eps: float = 1e-6, dtype: str = "f32") -> GraphSpec:
+    """The transpose chain ([B,S,H,D] -> [B,H,S,D], per-head scale, L2-normalise the last axis) that also stores the
+    row sums of squares: one more output than the hand-written transpose-chain family takes."""
+    ops = [
+        _op("t", "transpose", "x", perm=(0, 2, 1, 3)),
+        _op("u", "mul", "t", "r_scale"),
+        _op("q", "square", "u"),
+        _op("ss", "reduce_sum", "q", axis=3),
+        _op("e", "add_scalar", "ss", value=float(eps)),
+        _op("r", "rsqrt", "e"),
+        _op("out", "mul", "u", "r"),
+    ]
+    return GraphSpec(name=f"pattern_tchain_stats_{dtype}_{batch}x{seq}x{heads}x{dim}",
+                     inputs=[TensorSpec("x", dtype, (batch, seq, heads, dim)), TensorSpec("r_scale", dtype, (heads, 1, 1))],
+                     ops=ops, outputs=[("out", dtype), ("ss", "f32")])
+
+
+def transposed_softmax_graph(batch: int, q_len: int, heads: int, k_len: int, dtype: str = "f16") -> GraphSpec:
+    """Scores laid out [B,S,H,T], wanted as probabilities [B,H,S,T]: transpose, scale, softmax over T."""
+    ops = [_op("t", "transpose", "scores", perm=(0, 2, 1, 3)), _op("a", "scale", "t", value=0.125)] + _softmax_ops("a", 3)
+    return GraphSpec(name=f"pattern_transposed_softmax_{dtype}_{batch}x{q_len}x{heads}x{k_len}",
+                     inputs=[TensorSpec("scores", dtype, (batch, q_len, heads, k_len))], ops=ops, outputs=[("y", dtype)])
+
+
 def random_row_pattern(seed: int, rows: int, cols: int, dtype: str = "f32", n_ops: int = 12) -> GraphSpec:
     """A random connected pattern of element-wise ops and row reductions over [rows, cols] (descriptor only).
     Domains are kept safe by construction: exp only of tanh, division and rsqrt only of 1 + square."""
@@ -562,6 +610,10 @@ GENERIC_CONFIGS = {
     "G3": lambda: scaled_softmax_colbias_graph(32 * 12 * 128, 128, "f32"),
     "G4": lambda: normalize_from_stats_graph(8192, 1024, "f16"),
     "G5": lambda: masked_scores_gate_graph(32, 12, 128, 128, "f16"),        # C3's shape: mask [B,1,1,T], per-head scale [H,1,1]
+    # leading-axis transposes folded into a row kernel's load or store
+    "G6": lambda: bias_head_split_graph(64, 512, 16, 64, "bf16"),            # projection bias + head split (store side)
+    "G7": lambda: transpose_chain_stats_graph(64, 512, 12, 64),              # C5 plus the stored row sums (load side)
+    "G8": lambda: head_merge_residual_graph(64, 512, 16, 64, "bf16"),        # head merge + gain + residual (load side)
 }
 
 FULL_CONFIGS = {
