@@ -174,8 +174,11 @@ fs_status fs_plan_candidate(const fs_plan *p, int32_t index, fs_plan_info *out);
  * bytes, always NUL-terminated when capacity > 0; truncated if too small) and returns
  * the size needed for the whole listing including the NUL, or a negative error.  One
  * line per launch (kernel, grid, block, dynamic LDS) and per buffer binding; for a
- * pattern that runs as an interpreted row program (the generic path for patterns no
- * hand-written kernel covers, Section 4.2) also its register files and one line per
+ * pattern that runs as a row program (the generic path for patterns no hand-written
+ * kernel covers, Section 4.2; interpreted or as a generated kernel) also its register
+ * files, the extents of the leading axes (`lead=a,b,c`), for operands and outputs that
+ * are stretched or transposed along them their row strides (`rowstrides=m0,m1,m2`: row
+ * (c0,c1,c2) of the pattern is row c0*m0+c1*m1+c2*m2 of that buffer), and one line per
  * instruction of its accumulator machine: `instr <n> <op> b=<kind>:<index> dst=<index>
  * flags=<v|s><k|-> aux=<dtype> imm=<value>` (v: acc <- acc op b on full-shaped values,
  * s: the same on per-row values; k: result also kept in register dst).

@@ -209,7 +209,10 @@ struct Explorer {
         // T_penalty comes from the kernel estimate with register figures left at their estimates
         // (the expensive part of the latency evaluator is skipped during exploration)
         double best = 1e30;
+        bool only_fallbacks = true;
+        for (const Candidate& c : cands) only_fallbacks = only_fallbacks && c.fallback;
         for (const Candidate& c : cands) {
+          if (c.fallback && !only_fallbacks) continue;   // the plan would not pick it either
           double t = evaluate(c.cost, 0).seconds;
           if (c.launches.size() > 1) t += device().launch_s * (double)(c.launches.size() - 1);
           best = std::min(best, t);

@@ -94,6 +94,9 @@ struct Candidate {
   fs_plan_info info;
   std::vector<Launch> launches;
   KernelCost cost;               // description of the (single) stitched kernel; unused for unfused plans
+  bool fallback = false;         // offered only for the case that no other candidate can be used (the interpreted row
+                                 // program beside the kernels generated for the same pattern): passed over by the choice
+                                 // while another candidate stands, still reachable by index
 };
 
 }  // namespace fs

@@ -41,6 +41,12 @@ void predict(Candidate* c) {
   if (res.from_device && res.static_lds > c->info.lds_bytes) c->info.lds_bytes = res.static_lds;
 }
 
+// the choice among candidates: a fallback only when nothing else stands, otherwise the lower estimate
+static bool preferred(const Candidate& a, const Candidate& b) {
+  if (a.fallback != b.fallback) return !a.fallback;
+  return a.info.predicted_us < b.info.predicted_us;
+}
+
 static bool satisfies(const fs_plan_info& i, const fs_plan_opts& o) {
   if (o.block_threads > 0 && i.block[0] != o.block_threads) return false;
   if (o.lanes_per_row > 0 && i.lanes_per_row != o.lanes_per_row) return false;
@@ -97,7 +103,7 @@ fs_status complete_plan(fs_plan* p) {
     for (int i = 0; i < (int)p->candidates.size(); ++i) {
       const Candidate& k = p->candidates[i];
       if (k.info.predicted_us >= 1e30 || !satisfies(k.info, o)) continue;
-      if (best < 0 || k.info.predicted_us < p->candidates[best].info.predicted_us) best = i;
+      if (best < 0 || preferred(k, p->candidates[best])) best = i;
     }
     if (best < 0) return fail(FS_ERR_UNSUPPORTED_PATTERN, "fs_plan_create: %s, and no other candidate has the requested launch shape", why.c_str());
     p->chosen = best;
@@ -153,7 +159,7 @@ fs_status fs::create_plan(const fs_graph* g, int32_t scheme, const fs_plan_opts*
   } else {
     for (int i = 0; i < (int)kept.size(); ++i) {
       if (!satisfies(kept[i].info, o)) continue;
-      if (best < 0 || kept[i].info.predicted_us < kept[best].info.predicted_us) best = i;
+      if (best < 0 || preferred(kept[i], kept[best])) best = i;
     }
     if (best < 0)
       return fail(FS_ERR_LOCALITY, "fs_plan_create: no %s candidate of pattern '%s' has the requested launch shape",

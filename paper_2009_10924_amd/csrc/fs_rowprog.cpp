@@ -672,12 +672,8 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
     kc.lane_utilisation = (double)nvec / ((double)s.L * s.K);
     kc.access_run_bytes = s.L >= 8 ? 0 : s.L * 16.0;
     kc.preamble_instr = 60;
-    // a lane's own instruction stream between its loads landing and its stores leaving: the first and the last
-    // wavefronts of the launch run it with the memory system idle, so long per-lane chains (many vectors per
-    // lane) cost time that more, shorter wavefronts would have overlapped
-    const DeviceModel& d = device();
-    kc.serial_tail_s = 1.5 * kv * (kc.valu_per_elem * d.cycles_valu + kc.trans_per_elem * d.cycles_trans) / d.clock_hz;
     cand.cost = kc;
+    cand.fallback = !s.generated && codegen_enabled();
     if (s.generated) {
       // the same program as straight-line code of its own: every value in registers, no dispatch, no LDS files
       Launch& gl = cand.launches.back();
@@ -693,6 +689,10 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
       gc.lds_bytes_per_block = slots;
       gc.vgpr_estimate = 24 + kv * (base.n_regs + 1 + (base.n_col > 0 ? 1 : 0)) + 2 * s.K * base.n_full;
       gc.preamble_instr = 40;
+      // a lane's own instruction stream between its loads landing and its stores leaving: the first and the last
+      // wavefronts of the launch run it with the memory system idle, so long per-lane chains (many vectors per
+      // lane) cost time that more, shorter wavefronts would have overlapped
+      const DeviceModel& d = device();
       gc.serial_tail_s = 1.5 * kv * (gc.valu_per_elem * d.cycles_valu + gc.trans_per_elem * d.cycles_trans) / d.clock_hz;
       if (gc.vgpr_estimate > 256) continue;   // would not fit the register file without spilling
     }
