@@ -61,6 +61,25 @@ def test_transformer_block(dims):
     assert np.array_equal(got["qt"], want)
 
 
+@pytest.mark.parametrize("dims", [(2, 16, 2, 8, 64), (3, 40, 4, 32, 256), (32, 128, 12, 64, 3072)])
+def test_transformer_block_with_projection_biases(dims):
+    """Bias add + rounding + head split are three ops per projection: the explorer makes row patterns of them whose
+    transposes are folded into the stores (generated kernels where the run-time compiler is there)."""
+    spec = transformer_block_graph(*dims, "bf16", projection_bias=True)
+    worst, prog = compare(spec)
+    info = prog.info
+    plans = [p["info"]["pattern"] for p in prog.patterns()]
+    note(f"transformer block with projection biases {dims}: {info['n_ops']} ops -> {info['n_kernels']} launches {plans}, worst {worst:.3f}")
+    assert info["n_kernels"] <= 8 and "transpose" not in plans[:2]      # no lone head-split transposes are left
+    inp = make_inputs(spec, seed=0)
+    got, _ = run_program(spec, inp, repeat=1)
+    # the stored sum is the float32 sum of two bf16 values rounded once: compare exactly with that definition
+    import torch
+    q = torch.from_numpy(O.to_f64(inp["q_lin"], "bf16")).float() + torch.from_numpy(O.to_f64(inp["bias_q"], "bf16")).float()
+    want = q.to(torch.bfloat16).float().numpy().transpose(0, 2, 1, 3)
+    assert np.array_equal(got["qt"], want.astype(np.float64))
+
+
 def test_transformer_block_without_packing_and_remote_fusion():
     spec = transformer_block_graph(2, 16, 2, 8, 64, "bf16")
     a, pa = compare(spec, no_packing=True)

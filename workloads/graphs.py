@@ -500,14 +500,28 @@ def _layernorm_ops(prefix: str, x: str, res: str, bias: str, gamma: str, beta: s
 
 
 def transformer_block_graph(batch: int = 32, seq: int = 128, heads: int = 12, dim: int = 64, ffn: int = 3072,
-                            dtype: str = "bf16") -> GraphSpec:
+                            dtype: str = "bf16", projection_bias: bool = False) -> GraphSpec:
     """The memory-intensive ops of one transformer encoder block, with the matrix products taken out: their
     results come in as graph inputs.  Head split / merge transposes, scale + mask + softmax, output bias +
     residual + LayerNorm, feed-forward bias + GELU, second bias + residual + LayerNorm that reads the first
-    one's stored result (37 ops, 8 patterns by hand)."""
+    one's stored result (37 ops, 8 patterns by hand).  projection_bias: the query / key / value projections come
+    without their biases [H,D], which are added (and the sum rounded to the storage dtype) in front of the head
+    split (43 ops, or 46 with the rounding when the storage dtype is not float32)."""
     hidden, rows = heads * dim, batch * seq
     t4 = (batch, seq, heads, dim)
-    inputs = [
+    split, bias_inputs = [], []
+    for n in ("q", "k", "v"):
+        if projection_bias:
+            bias_inputs.append(TensorSpec(f"bias_{n}", dtype, (heads, dim)))
+            split.append(_op(f"{n}_b", "add", f"{n}_lin", f"bias_{n}"))
+            src = f"{n}_b"
+            if dtype != "f32":
+                split.append(_op(f"{n}_c", "convert", src, dtype=dtype))
+                src = f"{n}_c"
+            split.append(_op(f"{n}t", "transpose", src, perm=(0, 2, 1, 3)))
+        else:
+            split.append(_op(f"{n}t", "transpose", f"{n}_lin", perm=(0, 2, 1, 3)))
+    inputs = bias_inputs + [
         TensorSpec("q_lin", dtype, t4), TensorSpec("k_lin", dtype, t4), TensorSpec("v_lin", dtype, t4),
         TensorSpec("scores", dtype, (batch, heads, seq, seq)), TensorSpec("mask", dtype, (batch, 1, 1, seq)),
         TensorSpec("ctx", dtype, (batch, heads, seq, dim)),
@@ -517,9 +531,7 @@ def transformer_block_graph(batch: int = 32, seq: int = 128, heads: int = 12, di
         TensorSpec("ffn2_out", dtype, (rows, hidden)), TensorSpec("bias2", dtype, (hidden,)),
         TensorSpec("gamma2", dtype, (hidden,)), TensorSpec("beta2", dtype, (hidden,)),
     ]
-    ops = [
-        _op("qt", "transpose", "q_lin", perm=(0, 2, 1, 3)), _op("kt", "transpose", "k_lin", perm=(0, 2, 1, 3)),
-        _op("vt", "transpose", "v_lin", perm=(0, 2, 1, 3)),
+    ops = split + [
         _op("sc", "scale", "scores", value=float(dim) ** -0.5), _op("sa", "add", "sc", "mask"),
     ] + _softmax_ops("sa", 3, prefix="p_") + [
         _op("ctx_t", "transpose", "ctx", perm=(0, 2, 1, 3)),
@@ -528,7 +540,8 @@ def transformer_block_graph(batch: int = 32, seq: int = 128, heads: int = 12, di
     ] + _layernorm_ops("l2_", "ffn2_out", "l1_out", "bias2", "gamma2", "beta2", 1e-5, dtype)
     outputs = [("qt", dtype), ("kt", dtype), ("vt", dtype), ("p_y", dtype), ("ctx_t", dtype), ("l1_out", dtype),
                ("act", dtype), ("l2_out", dtype)]
-    return GraphSpec(name=f"pattern_transformer_block_{dtype}_b{batch}_s{seq}", inputs=inputs, ops=ops, outputs=outputs)
+    return GraphSpec(name=f"pattern_transformer_block_{'pb_' if projection_bias else ''}{dtype}_b{batch}_s{seq}", inputs=inputs, ops=ops,
+                     outputs=outputs)
 
 
 def random_multi_pattern(seed: int, rows: int = 24, cols: int = 32, segments: int = 3, dtype: str = "f32",
@@ -601,7 +614,9 @@ def pack_members_p1() -> List[GraphSpec]:
 PACK_CONFIGS = {"P1": pack_members_p1}
 
 # Multi-pattern graphs for the fusion explorer.
-EXPLORE_CONFIGS = {"T1": lambda: transformer_block_graph(32, 128, 12, 64, 3072, "bf16")}
+EXPLORE_CONFIGS = {"T1": lambda: transformer_block_graph(32, 128, 12, 64, 3072, "bf16"),
+                   # the same block with the q/k/v projection biases added in front of the head split
+                   "T2": lambda: transformer_block_graph(32, 128, 12, 64, 3072, "bf16", projection_bias=True)}
 
 # Row-local patterns outside the hand-written families, at transformer-block sizes (interpreted row program).
 GENERIC_CONFIGS = {
