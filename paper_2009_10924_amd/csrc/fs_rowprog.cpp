@@ -54,6 +54,7 @@ struct Compiler {
   std::vector<int> free_regs, free_sregs;
   int acc_holds = -1, sacc_holds = -1;   // roots
   bool planning = true;                  // first pass: only follow the accumulators and note who needs a register
+  bool interpretable = true;             // the interpreter has the program's step width (generated kernels have all)
 
   explicit Compiler(const fs_graph& graph) : g(graph), val(graph.tensors.size()) {}
 
@@ -404,10 +405,11 @@ struct Compiler {
       }
       if (T.output_slot >= 0) return false;   // an input handed straight to an output is no computation
     }
-    // lane geometry by elements: the narrowest vector input still moves in 128-bit accesses
-    p.vec = narrow ? 8 : 4;
-    const uint32_t vec = (uint32_t)p.vec;
-    if (cols % vec != 0) return false;
+    // lane geometry by elements: the narrowest vector input still moves in 128-bit accesses where the row length
+    // allows it; otherwise 4 elements per step (16-bit inputs then move in 64-bit accesses) or, for rows that are
+    // no multiple of 4 elements, single elements (the last two forms exist as generated kernels only)
+    p.vec = (narrow && cols % 8 == 0) ? 8 : (cols % 4 == 0 ? 4 : 1);
+    interpretable = p.vec == 8 || (p.vec == 4 && !narrow);
     p.rows = rows;
     p.cols = cols;
 
@@ -587,24 +589,26 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
 
   struct Shape { uint32_t L; int K; bool block; bool generated; };
   std::vector<Shape> shapes;
-  for (int K : {1, 2, 4}) {
-    uint32_t L = 1;
-    while (L * (uint32_t)K < nvec) L <<= 1;
-    if (L <= 64 && !(K > 1 && (uint64_t)L * K >= 2ull * nvec)) shapes.push_back({L, K, false, false});
+  if (c.interpretable) {
+    for (int K : {1, 2, 4}) {
+      uint32_t L = 1;
+      while (L * (uint32_t)K < nvec) L <<= 1;
+      if (L <= 64 && !(K > 1 && (uint64_t)L * K >= 2ull * nvec)) shapes.push_back({L, K, false, false});
+    }
+    if (c.n_reductions <= kProgMaxReductions)
+      for (int K : {1, 2, 4})
+        if (256ull * K >= nvec && 64ull * K < nvec) shapes.push_back({256, K, true, false});   // rows a wavefront cannot hold at this K
   }
-  if (c.n_reductions <= kProgMaxReductions)
-    for (int K : {1, 2, 4})
-      if (256ull * K >= nvec && 64ull * K < nvec) shapes.push_back({256, K, true, false});   // rows a wavefront cannot hold at this K
   if (codegen_enabled()) {
-    // generated kernels (listed after the interpreted ones, whose indices stay): any number of vectors per lane
-    // up to 8, so a row can fill its lanes exactly (768 floats: 32 lanes x 6 vectors)
+    // generated kernels (listed after the interpreted ones, whose indices stay): any number of steps per lane up to
+    // 8 (32 single-element steps), so a row can fill its lanes exactly (768 floats: 32 lanes x 6 vectors)
+    const uint32_t max_k = vec == 1 ? 32 : 8;
     for (uint32_t L = 1; L <= 64; L <<= 1) {
       const uint32_t K = (nvec + L - 1) / L;
-      if (K >= 1 && K <= 8 && (L == 1 || (uint64_t)(L / 2) * K < nvec)) shapes.push_back({L, (int)K, false, true});
+      if (K >= 1 && K <= max_k && (L == 1 || (uint64_t)(L / 2) * K < nvec)) shapes.push_back({L, (int)K, false, true});
     }
     const uint32_t KB = (nvec + 255) / 256;
-    if (KB <= 8 && 64ull * 8 < nvec) shapes.push_back({256, (int)KB, true, true});   // rows a wavefront cannot hold
-    if (KB <= 8 && 64ull * 8 >= nvec && 64ull * 2 < nvec) shapes.push_back({256, (int)KB, true, true});
+    if (KB <= max_k && 64ull * 2 < nvec) shapes.push_back({256, (int)KB, true, true});   // long rows: a workgroup per row
   }
 
   for (const Shape& s : shapes) {
@@ -662,7 +666,7 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
     kc.lds_traffic_bytes = n * 4.0 * (c.reg_reads + c.reg_writes + base.n_full);
     kc.waves = (double)l.shape.grid[0] * 4;
     kc.waves_per_block = 4;
-    kc.bytes_in_flight_per_lane = std::max(16.0, (double)vec * in_bytes_per_elem) * s.K;
+    kc.bytes_in_flight_per_lane = (vec == 1 ? (double)in_bytes_per_elem : std::max(16.0, (double)vec * in_bytes_per_elem)) * s.K;
     kc.vgpr_estimate = 40 + 3 * kv + 4 * s.K * (base.n_full <= 1 ? 1 : (base.n_full <= 2 ? 2 : 4));
     int steps = 0;
     for (uint32_t t = 1; t < std::min<uint32_t>(s.L, 64); t <<= 1) ++steps;
@@ -670,7 +674,13 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
     kc.barriers = s.block ? c.n_reductions : 0;
     kc.lds_bytes_per_block = (int32_t)lds;
     kc.lane_utilisation = (double)nvec / ((double)s.L * s.K);
-    kc.access_run_bytes = s.L >= 8 ? 0 : s.L * 16.0;
+    {
+      // contiguous bytes the lanes of one row touch per access of the narrowest input
+      double narrowest = 4.0;
+      for (int i = 0; i < base.n_full; ++i) narrowest = std::min(narrowest, (double)dtype_bytes(base.full_dt[i]));
+      const double run = (double)std::min<uint32_t>(s.L, 64) * vec * narrowest;
+      kc.access_run_bytes = run >= 128.0 ? 0.0 : run;
+    }
     kc.preamble_instr = 60;
     cand.cost = kc;
     cand.fallback = !s.generated && codegen_enabled();

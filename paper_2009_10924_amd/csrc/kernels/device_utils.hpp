@@ -160,6 +160,9 @@ __device__ __forceinline__ void store_vec4(f16_t* p, const float (&v)[4]) {
 // Stores VEC(TI) float32 values as TO: a full 128-bit access when the two types are equally
 // wide, a 64-bit one when float32 rows are stored as a 16-bit type.
 template <typename TO, int N> struct StoreN;
+template <typename TO> struct StoreN<TO, 1> {   // rows whose length allows no wider access: one element
+  __device__ __forceinline__ static void run(TO* p, const float (&v)[1]) { store1(p, v[0]); }
+};
 template <typename TO> struct StoreN<TO, 4> {
   __device__ __forceinline__ static void run(TO* p, const float (&v)[4]) { store_vec4_nt(p, v); }
 };

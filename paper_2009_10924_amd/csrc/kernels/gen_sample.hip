@@ -32,3 +32,8 @@ extern "C" __global__ void __launch_bounds__(256) fs_gen_sample_wave_f32(const G
 extern "C" __global__ void __launch_bounds__(256) fs_gen_sample_wave_f16(const GenArgs a) { sample_body<f16_t, float, 8, 1, 64u, false>(a); }
 extern "C" __global__ void __launch_bounds__(256) fs_gen_sample_block_bf16(const GenArgs a) { sample_body<bf16_t, f16_t, 8, 4, 256u, true>(a); }
 extern "C" __global__ void __launch_bounds__(256) fs_gen_sample_wide_f32(const GenArgs a) { sample_body<float, float, 8, 1, 8u, false>(a); }
+extern "C" __global__ void __launch_bounds__(256) fs_gen_sample_half_width_bf16(const GenArgs a) { sample_body<bf16_t, bf16_t, 4, 2, 16u, false>(a); }
+extern "C" __global__ void __launch_bounds__(256) fs_gen_sample_half_width_f16(const GenArgs a) { sample_body<f16_t, f16_t, 4, 1, 256u, true>(a); }
+extern "C" __global__ void __launch_bounds__(256) fs_gen_sample_element_f32(const GenArgs a) { sample_body<float, float, 1, 5, 64u, false>(a); }
+extern "C" __global__ void __launch_bounds__(256) fs_gen_sample_element_bf16(const GenArgs a) { sample_body<bf16_t, f16_t, 1, 3, 32u, false>(a); }
+extern "C" __global__ void __launch_bounds__(256) fs_gen_sample_element_f16(const GenArgs a) { sample_body<f16_t, bf16_t, 1, 7, 256u, true>(a); }

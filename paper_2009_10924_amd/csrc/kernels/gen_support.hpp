@@ -21,6 +21,85 @@ struct GenArgs {
   void* rout[4];
 };
 
+// One step of one lane in storage form: VEC elements of 2 or 4 bytes are 2, 4, 8, 16 or 32 bytes.  VEC is 8 or 4
+// where the row length allows 128-bit (or, for 16-bit elements under VEC = 4, 64-bit) accesses, and 1 for rows
+// whose length is not a multiple of 4 elements: every access is then a single element, still contiguous over
+// the lanes of a row.
+template <int BYTES> struct StepBits;
+template <> struct StepBits<32> {
+  u32x4 lo, hi;
+  template <bool STREAM, typename T>
+  __device__ __forceinline__ static StepBits load(const T* p) {
+    StepBits r;
+    const u32x4* q = reinterpret_cast<const u32x4*>(p);
+    r.lo = STREAM ? __builtin_nontemporal_load(q) : q[0];
+    r.hi = STREAM ? __builtin_nontemporal_load(q + 1) : q[1];
+    return r;
+  }
+};
+template <> struct StepBits<16> {
+  u32x4 w;
+  template <bool STREAM, typename T>
+  __device__ __forceinline__ static StepBits load(const T* p) {
+    StepBits r;
+    r.w = STREAM ? load_raw_nt(p) : load_raw(p);
+    return r;
+  }
+};
+template <> struct StepBits<8> {
+  u32x2 w;
+  template <bool STREAM, typename T>
+  __device__ __forceinline__ static StepBits load(const T* p) {
+    StepBits r;
+    const u32x2* q = reinterpret_cast<const u32x2*>(p);
+    r.w = STREAM ? __builtin_nontemporal_load(q) : *q;
+    return r;
+  }
+};
+template <> struct StepBits<4> {
+  uint32_t w;
+  template <bool STREAM, typename T>
+  __device__ __forceinline__ static StepBits load(const T* p) {
+    StepBits r;
+    const uint32_t* q = reinterpret_cast<const uint32_t*>(p);
+    r.w = STREAM ? __builtin_nontemporal_load(q) : *q;
+    return r;
+  }
+};
+template <> struct StepBits<2> {
+  uint16_t w;
+  template <bool STREAM, typename T>
+  __device__ __forceinline__ static StepBits load(const T* p) {
+    StepBits r;
+    const uint16_t* q = reinterpret_cast<const uint16_t*>(p);
+    r.w = STREAM ? __builtin_nontemporal_load(q) : *q;
+    return r;
+  }
+};
+__device__ __forceinline__ void unpack_step(const StepBits<32>& r, float (&v)[8], const float*) {
+  float a[4], b[4];
+  unpack(r.lo, a, (const float*)nullptr);
+  unpack(r.hi, b, (const float*)nullptr);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) { v[e] = a[e]; v[4 + e] = b[e]; }
+}
+__device__ __forceinline__ void unpack_step(const StepBits<16>& r, float (&v)[4], const float*) { unpack(r.w, v, (const float*)nullptr); }
+template <typename T>
+__device__ __forceinline__ void unpack_step(const StepBits<16>& r, float (&v)[8], const T*) { unpack(r.w, v, (const T*)nullptr); }
+__device__ __forceinline__ void unpack_step(const StepBits<8>& r, float (&v)[4], const bf16_t*) {
+  v[0] = __builtin_bit_cast(float, r.w.x << 16); v[1] = __builtin_bit_cast(float, r.w.x & 0xFFFF0000u);
+  v[2] = __builtin_bit_cast(float, r.w.y << 16); v[3] = __builtin_bit_cast(float, r.w.y & 0xFFFF0000u);
+}
+__device__ __forceinline__ void unpack_step(const StepBits<8>& r, float (&v)[4], const f16_t*) {
+  unpack_f16(r.w.x, v[0], v[1]);
+  unpack_f16(r.w.y, v[2], v[3]);
+}
+__device__ __forceinline__ void unpack_step(const StepBits<4>& r, float (&v)[1], const float*) { v[0] = __builtin_bit_cast(float, r.w); }
+__device__ __forceinline__ void unpack_step(const StepBits<2>& r, float (&v)[1], const bf16_t*) { v[0] = bf16_bits_to_f32(r.w); }
+__device__ __forceinline__ void unpack_step(const StepBits<2>& r, float (&v)[1], const f16_t*) {
+  v[0] = (float)__builtin_bit_cast(_Float16, r.w);
+}
+
 // ROWS x COLS row space; VEC elements per lane and step; K steps per lane; L lanes per row
 // (a lane group of one wavefront), or the whole 256-thread workgroup when BLOCK.
 template <uint32_t ROWS, uint32_t COLS, int VEC, int K, uint32_t L, bool BLOCK>
@@ -46,27 +125,18 @@ struct GenRow {
   __device__ __forceinline__ bool valid(int k) const { return FULL_COLS || lane + k * LANES < NVEC; }
   __device__ __forceinline__ uint32_t vec_at(int k) const { return FULL_COLS ? lane + k * LANES : min(lane + k * LANES, NVEC - 1u); }
 
-  // VEC elements of storage type T are W 128-bit words
+  // the lane's K steps of row `at_row` of a [.., COLS] tensor, in storage form; STREAM: read once, so the loads
+  // carry the streaming hint and do not displace the operands that every row re-reads from cache
   template <typename T>
   struct Raw {
-    static constexpr int W = VEC * (int)sizeof(T) / 16;
-    u32x4 w[K][W];
+    StepBits<VEC * (int)sizeof(T)> w[K];
   };
-
-  // the lane's K vectors of row `at_row` of a [.., COLS] tensor; STREAM: read once, bypass the caches' keep policy
   template <typename T, bool STREAM>
   __device__ __forceinline__ Raw<T> load(const void* p, size_t at_row) const {
     Raw<T> r;
     const T* base = static_cast<const T*>(p) + at_row * COLS;
 #pragma unroll
-    for (int k = 0; k < K; ++k) {
-      const T* src = base + (size_t)vec_at(k) * VEC;
-#pragma unroll
-      for (int h = 0; h < Raw<T>::W; ++h) {
-        const T* q = src + h * (16 / (int)sizeof(T));
-        r.w[k][h] = STREAM ? load_raw_nt(q) : load_raw(q);
-      }
-    }
+    for (int k = 0; k < K; ++k) r.w[k] = StepBits<VEC * (int)sizeof(T)>::template load<STREAM>(base + (size_t)vec_at(k) * VEC);
     return r;
   }
 
@@ -74,20 +144,10 @@ struct GenRow {
   __device__ __forceinline__ void unpack_to(const Raw<T>& r, float (&v)[KV]) const {
 #pragma unroll
     for (int k = 0; k < K; ++k) {
-      if constexpr (Raw<T>::W == 1) {
-        float part[VEC];
-        unpack(r.w[k][0], part, (const T*)nullptr);
+      float part[VEC];
+      unpack_step(r.w[k], part, (const T*)nullptr);
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) v[k * VEC + e] = part[e];
-      } else {   // float32 under an 8-element step: two words
-#pragma unroll
-        for (int h = 0; h < Raw<T>::W; ++h) {
-          float part[4];
-          unpack(r.w[k][h], part, (const float*)nullptr);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[k * VEC + 4 * h + e] = part[e];
-        }
-      }
+      for (int e = 0; e < VEC; ++e) v[k * VEC + e] = part[e];
     }
   }
 

@@ -100,6 +100,22 @@ def test_folded_transposes_move_values_exactly():
                     assert np.array_equal(raw["out"].view(np.uint8), np.ascontiguousarray(want).view(np.uint8)), (spec.name, perm, info["kernel"])
 
 
+@pytest.mark.parametrize("rows,cols,dtype", [(10, 50, "f32"), (9, 1001, "bf16"), (13, 36, "f16"), (70, 127, "f16"), (3, 3003, "f32"),
+                                             (300, 6, "bf16")])
+def test_row_lengths_that_allow_no_128_bit_access(rows, cols, dtype):
+    """Rows that are no multiple of 8 (16-bit) or 4 elements: the generated kernels step by 4 elements with 64-bit
+    accesses for the 16-bit operands, or by single elements; before, such patterns ran per op."""
+    if not B.codegen_available():
+        pytest.skip("these step widths exist as generated kernels only")
+    for make in (lambda: layernorm_stats_graph(rows, cols, in_dtype=dtype, out_dtype=dtype, with_variance=True),
+                 lambda: silu_gate_graph(rows, cols, dtype), lambda: scaled_softmax_colbias_graph(rows, cols, dtype),
+                 lambda: random_row_pattern(rows + cols, rows, cols, dtype, n_ops=10)):
+        spec = make()
+        worst, info = _run(spec)
+        assert info["pattern"] == "row_generated"
+        note(f"{spec.name}: {info['kernel']}, {info['n_candidates']} shapes, worst {worst}")
+
+
 @pytest.mark.parametrize("seed", range(48))
 def test_random_row_patterns(seed):
     dtype = ("f32", "f16", "bf16")[seed % 3]
