@@ -65,8 +65,8 @@ std::string expression(int op, const std::string& a, const std::string& b, int a
 }
 
 // row index of an operand stretched or permuted along the leading axes, from the row's index (lead0, lead1, lead2) along them
-std::string stretched_row(const uint32_t (&ms)[3]) {
-  return fmt("(size_t)(lead0 * %uu + lead1 * %uu + lead2 * %uu)", ms[0], ms[1], ms[2]);
+std::string stretched_row(const uint32_t (&ms)[3], const char* pre = "") {
+  return fmt("(size_t)(%slead0 * %uu + %slead1 * %uu + %slead2 * %uu)", pre, ms[0], pre, ms[1], pre, ms[2]);
 }
 
 }  // namespace
@@ -82,30 +82,76 @@ std::string generate_row_kernel_body(const RowProgP& p) {
   std::string s;
   s += "using namespace fsk;\n";
   s += fmt("extern \"C\" __global__ void __launch_bounds__(256) %s(const GenArgs a) {\n", generated_kernel_entry());
-  s += fmt("  typedef GenRow<%uu, %uu, %d, %d, %uu, %s> Row;\n", p.rows, p.cols, p.vec, p.vecs_per_lane,
-           block ? 256u : (uint32_t)p.lanes_per_row, block ? "true" : "false");
+  const uint32_t R = p.rows_per_group > 1 ? (uint32_t)p.rows_per_group : 1u;
+  s += fmt("  typedef GenRow<%uu, %uu, %d, %d, %uu, %s, %uu> Row;\n", p.rows, p.cols, p.vec, p.vecs_per_lane,
+           block ? 256u : (uint32_t)p.lanes_per_row, block ? "true" : "false", R);
   s += "  constexpr int KV = Row::KV;\n";
   if (block && n_reductions > 0) s += fmt("  __shared__ float slots[%d];\n", 4 * n_reductions);
-  s += "  const Row row;\n";
-
-  // ---- every global load is issued before anything waits
-  if (p.full_bcast | p.rscal_bcast | p.out_perm) {
-    s += fmt("  const uint32_t q1 = row.row_c / %uu, lead2 = row.row_c - q1 * %uu, lead0 = q1 / %uu, lead1 = q1 - lead0 * %uu;\n", p.od[2].d,
-             p.od[2].d, p.od[1].d, p.od[1].d);
-  }
-  for (int i = 0; i < p.n_full; ++i) {
-    // an input stretched along leading axes is read by many rows: it goes through the caches like a column vector;
-    // the others are read once and stream past them
-    const bool stretched = ((p.full_bcast >> i) & 1u) != 0;
-    const std::string at = stretched ? stretched_row(p.ms[i]) : std::string("(size_t)row.row_c");
-    s += fmt("  const auto raw_full%d = row.load<%s, %s>(a.full[%d], %s);\n", i, storage_type(p.full_dt[i]), stretched ? "false" : "true", i,
-             at.c_str());
-  }
-  for (int i = 0; i < p.n_col; ++i)
-    s += fmt("  const auto raw_col%d = row.load<%s, false>(a.col[%d], 0);\n", i, storage_type(p.col_dt[i]), i);
-  for (int i = 0; i < p.n_rscal; ++i) {
-    const std::string at = ((p.rscal_bcast >> i) & 1u) ? stretched_row(p.rms[i]) : std::string("(size_t)row.row_c");
-    s += fmt("  const float in_rscal%d = load1(static_cast<const %s*>(a.rscal[%d]) + %s);\n", i, storage_type(p.rscal_dt[i]), i, at.c_str());
+  const bool looped = p.n_colsum > 0;
+  const bool needs_lead = (p.full_bcast | p.rscal_bcast | p.out_perm) != 0;
+  // the row's index along the leading axes, for the row object `rv`; names carry the prefix `pre`
+  auto lead_of = [&](const char* rv, const char* pre, bool declare) {
+    return fmt("  %s%sq1 = %s.row_c / %uu, %slead2 = %s.row_c - %sq1 * %uu, %slead0 = %sq1 / %uu, %slead1 = %sq1 - %slead0 * %uu;\n",
+               declare ? "const uint32_t " : "", pre, rv, p.od[2].d, pre, rv, pre, p.od[2].d, pre, pre, p.od[1].d, pre, pre, pre, p.od[1].d);
+  };
+  // the loads of one row's operands (everything but the column vectors); `decl` declares the variables or is empty
+  auto row_loads = [&](const char* rv, const char* pre, const char* decl_raw, const char* decl_scalar) {
+    std::string t;
+    for (int i = 0; i < p.n_full; ++i) {
+      // an input stretched along leading axes is read by many rows: it goes through the caches like a column vector;
+      // the others are read once and stream past them
+      const bool stretched = ((p.full_bcast >> i) & 1u) != 0;
+      const std::string at = stretched ? stretched_row(p.ms[i], pre) : fmt("(size_t)%s.row_c", rv);
+      t += fmt("  %s%sraw_full%d = %s.load<%s, %s>(a.full[%d], %s);\n", decl_raw, pre, i, rv, storage_type(p.full_dt[i]),
+               stretched ? "false" : "true", i, at.c_str());
+    }
+    for (int i = 0; i < p.n_rscal; ++i) {
+      const std::string at = ((p.rscal_bcast >> i) & 1u) ? stretched_row(p.rms[i], pre) : fmt("(size_t)%s.row_c", rv);
+      t += fmt("  %s%sin_rscal%d = load1(static_cast<const %s*>(a.rscal[%d]) + %s);\n", decl_scalar, pre, i, storage_type(p.rscal_dt[i]), i,
+               at.c_str());
+    }
+    return t;
+  };
+  auto col_loads = [&](const char* rv) {
+    std::string t;
+    for (int i = 0; i < p.n_col; ++i)
+      t += fmt("  const auto raw_col%d = %s.load<%s, false>(a.col[%d], 0);\n", i, rv, storage_type(p.col_dt[i]), i);
+    return t;
+  };
+  auto col_unpack = [&](const char* rv) {
+    std::string t;
+    for (int i = 0; i < p.n_col; ++i) {
+      t += fmt("  float c%d[KV];\n", i);
+      t += fmt("  %s.unpack_to<%s>(raw_col%d, c%d);\n", rv, storage_type(p.col_dt[i]), i, i);
+    }
+    return t;
+  };
+  if (looped) {
+    // Running column sums live across the rows a lane group works through; the rows' own work is the loop body.
+    // The loop is software-pipelined: the next row's loads are issued before this row's arithmetic starts (in the
+    // last trip they re-read the last row), and the column vectors are loaded once.
+    if (!block) s += fmt("  __shared__ float colred[%d][4 * Row::PADDED_COLS];\n", p.n_colsum);
+    for (int i = 0; i < p.n_colsum; ++i)
+      s += fmt("  float cs%d[KV];\n#pragma unroll\n  for (int j = 0; j < KV; ++j) cs%d[j] = 0.0f;\n", i, i);
+    s += "  Row nrow(blockIdx.x);\n";
+    s += col_loads("nrow");
+    if (needs_lead) s += "  uint32_t nq1, nlead0, nlead1, nlead2;\n" + lead_of("nrow", "n", false);
+    s += row_loads("nrow", "n", "auto ", "float ");
+    s += col_unpack("nrow");
+    s += fmt("#pragma unroll 1\n  for (uint32_t it = 0; it < %uu; ++it) {\n", R);
+    s += "  const Row row = nrow;\n";
+    if (p.out_perm) s += lead_of("row", "", true);
+    for (int i = 0; i < p.n_full; ++i) s += fmt("  const auto raw_full%d = nraw_full%d;\n", i, i);
+    for (int i = 0; i < p.n_rscal; ++i) s += fmt("  const float in_rscal%d = nin_rscal%d;\n", i, i);
+    s += fmt("  nrow = Row(min(it + 1u, %uu) * gridDim.x + blockIdx.x);\n", R - 1u);
+    if (needs_lead) s += lead_of("nrow", "n", false);
+    s += row_loads("nrow", "n", "", "");
+  } else {
+    s += "  const Row row(blockIdx.x);\n";
+    // ---- every global load is issued before anything waits
+    if (needs_lead) s += lead_of("row", "", true);
+    s += row_loads("row", "", "const auto ", "const float ");
+    s += col_loads("row");
   }
 
   // ---- values: the accumulators, the kept full-shaped values, the column vectors, the kept per-row values
@@ -113,10 +159,7 @@ std::string generate_row_kernel_body(const RowProgP& p) {
   s += "#pragma unroll\n  for (int j = 0; j < KV; ++j) acc[j] = 0.0f;\n";
   for (int r = 0; r < p.n_regs; ++r) s += fmt("  float r%d[KV];\n", r);
   for (int r = 0; r < p.n_sregs; ++r) s += fmt("  float s%d = 0.0f;\n", r);
-  for (int i = 0; i < p.n_col; ++i) {
-    s += fmt("  float c%d[KV];\n", i);
-    s += fmt("  row.unpack_to<%s>(raw_col%d, c%d);\n", storage_type(p.col_dt[i]), i, i);
-  }
+  if (!looped) s += col_unpack("row");
   for (int i = 0; i < p.n_full; ++i) {
     const bool parked = p.full_reg[i] != 255;
     const bool to_acc = p.acc_input == i;
@@ -143,6 +186,9 @@ std::string generate_row_kernel_body(const RowProgP& p) {
         continue;
       case PO_STORE_SCAL:
         s += fmt("  row.store_scalar<%s>(a.rout[%d], sacc);\n", storage_type(in.aux), in.dst);
+        continue;
+      case PO_COLSUM:
+        s += fmt("  row.colsum_add(acc, cs%d);\n", in.dst);
         continue;
       case PO_RSUM: case PO_RMAX: case PO_RSUMSQ: {
         const bool is_max = in.op == PO_RMAX;
@@ -173,6 +219,14 @@ std::string generate_row_kernel_body(const RowProgP& p) {
     }
     s += "#pragma unroll\n  for (int j = 0; j < KV; ++j) acc[j] = " + expression(in.op, "acc[j]", b, in.aux) + ";\n";
     if (keep) s += fmt("#pragma unroll\n  for (int j = 0; j < KV; ++j) r%d[j] = acc[j];\n", in.dst);
+  }
+  if (looped) {
+    // the next row's reductions reuse this row's LDS slots: nobody may still be reading them
+    if (block && n_reductions > 0) s += "  __syncthreads();\n";
+    s += "  }\n";
+    for (int i = 0; i < p.n_colsum; ++i)
+      s += fmt("  Row::colsum_flush(cs%d, %s, static_cast<float*>(a.ws) + (size_t)blockIdx.x * %uu + %uu);\n", i,
+               block ? "nullptr" : fmt("colred[%d]", i).c_str(), (uint32_t)p.n_colsum * p.cols, (uint32_t)i * p.cols);
   }
   s += "}\n";
   return s;

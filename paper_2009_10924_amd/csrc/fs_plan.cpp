@@ -272,8 +272,11 @@ int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) {
                                             std::to_string(q.oms[i][2]) : std::string()) + "\n";
     for (int i = 0; i < kProgMaxOperands; ++i)
       if (l.ptr[16 + i].kind != BUF_NONE) s += "  routput " + std::to_string(i) + " " + buf_name(l.ptr[16 + i]) + "\n";
+    if (q.n_colsum > 0)   // partial sums: one row of n_colsum * cols floats per workgroup, folded by the next launch
+      s += "  colsums " + std::to_string(q.n_colsum) + " partials " + buf_name(l.ptr[20]) + " rows_per_group " +
+           std::to_string(q.rows_per_group) + "\n";
     static const char* op_names[] = {"add", "sub", "rsub", "mul", "div", "rdiv", "max", "square", "exp", "rsqrt", "tanh", "gelu",
-                                     "gelu_grad", "cvt", "load", "rsum", "rmax", "rsumsq", "store", "store_scal"};
+                                     "gelu_grad", "cvt", "load", "rsum", "rmax", "rsumsq", "store", "store_scal", "colsum"};
     static const char* kind_names[] = {"acc", "sacc", "reg", "scal", "imm", "col"};
     for (int i = 0; i < q.n_instr; ++i) {
       const ProgInstr& in = q.instr[i];
@@ -335,7 +338,7 @@ fs_status fs_execute(const fs_plan* p, const void* const* inputs, void* const* o
     int err;
     if (l.kernel == K_ROW_GENERATED) {
       if (!l.gen) return fail(FS_ERR_INVALID_ARG, "fs_execute: the plan's generated kernel was never compiled");
-      err = gen_launch(l.gen.get(), a.p, sizeof(void*) * kMaxPtrs, l.shape, hip_stream);
+      err = gen_launch(l.gen.get(), a.p, sizeof(void*) * kGenArgPtrs, l.shape, hip_stream);
     } else {
       err = launch_kernel(l.kernel, a, l.shape, hip_stream);
     }

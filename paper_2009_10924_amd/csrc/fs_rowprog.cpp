@@ -19,6 +19,7 @@
 #include <cstring>
 
 #include "fs_internal.hpp"
+#include "fs_stitch_util.hpp"
 
 namespace fs {
 namespace {
@@ -50,6 +51,9 @@ struct Compiler {
   std::vector<int32_t> stored_via;   // per tensor: the transpose op through which it is stored permuted, else -1
   int32_t out_slot[kProgMaxOperands], rout_slot[kProgMaxOperands];
   int n_out = 0, n_rout = 0, n_reductions = 0;
+  int n_colsum = 0;                       // column sums over all rows: outputs only, handed out by a fold launch
+  int32_t colsum_slot[kProgMaxColSums];   // their fs_execute output slots
+  std::vector<char> is_colsum;            // per op
   int vec_instr = 0, scal_instr = 0, reg_reads = 0, reg_writes = 0, trans = 0;
   std::vector<int> free_regs, free_sregs;
   int acc_holds = -1, sacc_holds = -1;   // roots
@@ -234,7 +238,18 @@ struct Compiler {
       const Op& op = g.ops[i];
       const Tensor& out = g.tensors[op.out];
       if (folded[i]) continue;
-      if (is_alias[i]) {
+      if (is_colsum[i]) {
+        if (!planning && n_colsum >= kProgMaxColSums) return false;
+        if (!load(root_of(op.in[0]), false)) return false;
+        ProgInstr cs{};
+        cs.op = PO_COLSUM;
+        cs.b_kind = PK_ACC;
+        if (!planning) { cs.dst = (uint8_t)n_colsum; colsum_slot[n_colsum++] = out.output_slot; }
+        if (!push(cs)) return false;
+        if (!planning)
+          for (int r : reads[i])
+            if (val[r].last_read == (int)i) release(r);
+      } else if (is_alias[i]) {
         if (out.output_slot >= 0) {
           const bool as_full = op.opcode == FS_BROADCAST || val[op.out].kind != V_RSCAL;
           if (!store_output(op.out, as_full)) return false;
@@ -418,6 +433,7 @@ struct Compiler {
     reads.assign(n_ops, {});
     is_alias.assign(n_ops, 0);
     std::vector<char> view_fold(n_ops, 0);
+    is_colsum.assign(n_ops, 0);
     for (size_t i = 0; i < n_ops; ++i) {
       const Op& op = g.ops[i];
       const Tensor& out = g.tensors[op.out];
@@ -437,6 +453,14 @@ struct Compiler {
           break;
         case FS_REDUCE_SUM: case FS_REDUCE_MAX: case FS_REDUCE_MEAN: {
           const Tensor& src = g.tensors[op.in[0]];
+          if (op.opcode == FS_REDUCE_SUM && op.axis == 0 && src.rank == 2 && rank == 2 && ka == V_FULL && !stretched_rows(src) &&
+              out.output_slot >= 0 && out.consumers.empty() && out.store_as == FS_F32 && cols % 4 == 0) {
+            // the sum over all rows: every workgroup leaves partial sums, a second launch folds them.  Nothing in the
+            // pattern can read it (that would take a grid-wide wait), so it has to be a graph output.
+            is_colsum[i] = 1;
+            want = V_COL;
+            break;
+          }
           if (op.axis != src.rank - 1) return false;              // only the row axis stays on chip
           if (ka == V_RSCAL) { want = V_RSCAL; is_alias[i] = 1; }  // reducing one element
           else if (ka == V_FULL) want = V_RSCAL;
@@ -490,7 +514,7 @@ struct Compiler {
       while (j < n_ops && (is_alias[j] && reads[j].empty())) ++j;
       if (j >= n_ops || is_alias[j]) continue;
       const Op& red = g.ops[j];
-      if ((red.opcode != FS_REDUCE_SUM && red.opcode != FS_REDUCE_MEAN) || val[red.in[0]].root != op.out) continue;
+      if ((red.opcode != FS_REDUCE_SUM && red.opcode != FS_REDUCE_MEAN) || val[red.in[0]].root != op.out || is_colsum[j]) continue;
       folded[i] = 1;
       square_of[j] = val[op.in[0]].root;
       reads[i].clear();
@@ -569,7 +593,10 @@ struct Compiler {
     for (int t : g.inputs)
       if (val[t].last_read < 0) release(t);   // declared but unread
     if (!walk()) return false;
-    return n_out + n_rout == (int)g.outputs.size();
+    p.n_colsum = n_colsum;
+    p.rows_per_group = 1;
+    if (n_colsum > 0) interpretable = false;
+    return n_out + n_rout + n_colsum == (int)g.outputs.size();
   }
 };
 
@@ -587,7 +614,7 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
   const double n = (double)base.rows * base.cols;
   const int64_t bytes_min = graph_bytes_min(g);
 
-  struct Shape { uint32_t L; int K; bool block; bool generated; };
+  struct Shape { uint32_t L; int K; bool block; bool generated; uint32_t R = 1; };
   std::vector<Shape> shapes;
   if (c.interpretable) {
     for (int K : {1, 2, 4}) {
@@ -609,6 +636,23 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
     }
     const uint32_t KB = (nvec + 255) / 256;
     if (KB <= max_k && 64ull * 2 < nvec) shapes.push_back({256, (int)KB, true, true});   // long rows: a workgroup per row
+    if (c.n_colsum > 0) {
+      // Column sums: a workgroup's lane groups work through R rows each and leave one row of partial sums, so R trades
+      // extra traffic (2 x workgroups x columns x 4 bytes) against workgroups to fill the chip with.
+      std::vector<Shape> with_r;
+      for (const Shape& sh : shapes) {
+        if (!sh.generated) continue;
+        const uint32_t rows_per_wg = sh.block ? 1 : 256 / sh.L;
+        for (uint32_t R : {1u, 2u, 4u, 8u, 16u, 32u, 64u}) {
+          const uint64_t n_wg = (base.rows + (uint64_t)rows_per_wg * R - 1) / ((uint64_t)rows_per_wg * R);
+          if (R > 1 && n_wg < 256) break;    // one workgroup per compute unit at the least
+          Shape t = sh;
+          t.R = R;
+          with_r.push_back(t);
+        }
+      }
+      shapes.swap(with_r);
+    }
   }
 
   for (const Shape& s : shapes) {
@@ -644,9 +688,10 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
     for (size_t i = 0; i < c.rscal_in.size(); ++i) l.ptr[8 + i] = in_ref(c.rscal_in[i]);
     for (int i = 0; i < c.n_out; ++i) { l.ptr[12 + i].kind = BUF_OUTPUT; l.ptr[12 + i].slot = c.out_slot[i]; }
     for (int i = 0; i < c.n_rout; ++i) { l.ptr[16 + i].kind = BUF_OUTPUT; l.ptr[16 + i].slot = c.rout_slot[i]; }
-    const uint32_t rows_per_block = s.block ? 1 : 256 / s.L;
+    const uint32_t rows_per_block = (s.block ? 1 : 256 / s.L) * s.R;
     l.shape.block[0] = 256;
     l.shape.grid[0] = (base.rows + rows_per_block - 1) / rows_per_block;
+    l.args.u.prog.rows_per_group = (int32_t)s.R;
     l.shape.lds_bytes = (uint32_t)lds;
     cand.info.lanes_per_row = (int32_t)s.L;
     cand.info.vecs_per_lane = s.K;
@@ -704,6 +749,37 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
       // lane) cost time that more, shorter wavefronts would have overlapped
       const DeviceModel& d = device();
       gc.serial_tail_s = 1.5 * kv * (gc.valu_per_elem * d.cycles_valu + gc.trans_per_elem * d.cycles_trans) / d.clock_hz;
+      if (c.n_colsum > 0) {
+        // partial sums of every workgroup through the workspace, folded by a second launch (one hand-off through
+        // device memory: the GLOBAL scheme)
+        Launch& ml = cand.launches.back();
+        const uint32_t n_wg = ml.shape.grid[0];
+        const uint32_t width = (uint32_t)c.n_colsum * base.cols;
+        ml.ptr[20].kind = BUF_WORKSPACE;
+        ml.ptr[20].offset = 0;
+        ml.shape.lds_bytes = 0;
+        cand.info.lds_bytes = slots + (s.block ? 0 : c.n_colsum * 4 * (int32_t)(s.L * kv) * 4);
+        cand.launches.emplace_back();
+        Launch& f = cand.launches.back();
+        make_fold_launch(&f, n_wg, width, base.cols);
+        f.ptr[0].kind = BUF_WORKSPACE;
+        f.ptr[0].offset = 0;
+        f.ptr[1].kind = BUF_OUTPUT;
+        f.ptr[1].slot = c.colsum_slot[0];
+        if (c.n_colsum > 1) { f.ptr[2].kind = BUF_OUTPUT; f.ptr[2].slot = c.colsum_slot[1]; }
+        cand.info.scheme = FS_SCHEME_GLOBAL;
+        cand.info.n_kernels = 2;
+        cand.info.workspace_bytes = (int64_t)n_wg * width * 4;
+        cand.info.bytes_moved_model = bytes_min + 2 * cand.info.workspace_bytes;
+        snprintf(cand.info.kernel, sizeof cand.info.kernel, "row_generated<v%d,K%d,L%u,I%d,R%d,rows%u>+colfold", vec, s.K, s.L, base.n_instr,
+                 base.n_regs, s.R);
+        gc.hbm_bytes += 2.0 * (double)cand.info.workspace_bytes;
+        gc.vgpr_estimate += kv * c.n_colsum;
+        gc.rows_per_wave_loop = s.R;
+        gc.lds_bytes_per_block = cand.info.lds_bytes;
+        gc.barriers = 1;
+        gc.serial_tail_s += d.mem_latency_s + 0.5 * d.launch_s + d.mem_latency_s * std::ceil(n_wg / 64.0 / 8.0) * 0.5;
+      }
       if (gc.vgpr_estimate > 256) continue;   // would not fit the register file without spilling
     }
     out->push_back(cand);

@@ -19,7 +19,14 @@ struct GenArgs {
   const void* rscal[4];
   void* out[4];
   void* rout[4];
+  void* ws;   // partial column sums, one row per workgroup (patterns with column sums), else null
 };
+
+// value of `v` in lane (own lane ^ mask) of the wavefront
+__device__ __forceinline__ float xor_lane(float v, uint32_t mask) {
+  const int addr = (int)(((threadIdx.x ^ mask) & 63u) << 2);
+  return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute(addr, __builtin_bit_cast(int, v)));
+}
 
 // One step of one lane in storage form: VEC elements of 2 or 4 bytes are 2, 4, 8, 16 or 32 bytes.  VEC is 8 or 4
 // where the row length allows 128-bit (or, for 16-bit elements under VEC = 4, 64-bit) accesses, and 1 for rows
@@ -102,23 +109,26 @@ __device__ __forceinline__ void unpack_step(const StepBits<2>& r, float (&v)[1],
 
 // ROWS x COLS row space; VEC elements per lane and step; K steps per lane; L lanes per row
 // (a lane group of one wavefront), or the whole 256-thread workgroup when BLOCK.
-template <uint32_t ROWS, uint32_t COLS, int VEC, int K, uint32_t L, bool BLOCK>
+// R: rows each lane group works through, one after the other (the kernel body runs R times with virtual
+// workgroup indices it * gridDim.x + blockIdx.x, so that at any moment the resident workgroups sweep one band of rows).
+template <uint32_t ROWS, uint32_t COLS, int VEC, int K, uint32_t L, bool BLOCK, uint32_t R = 1>
 struct GenRow {
   static constexpr uint32_t NVEC = COLS / VEC;
   static constexpr uint32_t LANES = BLOCK ? 256u : L;
   static constexpr uint32_t ROWS_PER_WG = BLOCK ? 1u : 256u / L;
   // the row fills its lanes / the rows fill the workgroups: no clamp, no padding test
   static constexpr bool FULL_COLS = NVEC == LANES * K;
-  static constexpr bool FULL_ROWS = ROWS % ROWS_PER_WG == 0;
+  static constexpr bool FULL_ROWS = ROWS % (ROWS_PER_WG * R) == 0;
   static constexpr int KV = K * VEC;
+  static constexpr uint32_t PADDED_COLS = LANES * K * VEC;   // columns the lanes of a row cover, padding included
 
   uint32_t lane, row, row_c;
   bool row_ok;
 
-  __device__ __forceinline__ GenRow() {
+  __device__ __forceinline__ explicit GenRow(uint32_t vblock) {
     const uint32_t tid = threadIdx.x;
     lane = BLOCK ? tid : (tid & (L - 1u));
-    row = BLOCK ? blockIdx.x : blockIdx.x * ROWS_PER_WG + tid / L;
+    row = BLOCK ? vblock : vblock * ROWS_PER_WG + tid / L;
     row_ok = FULL_ROWS || row < ROWS;
     row_c = FULL_ROWS ? row : min(row, ROWS - 1u);
   }
@@ -197,6 +207,53 @@ struct GenRow {
     const float r = t[0];
     if constexpr (BLOCK) return block_allreduce<OP>(r, slot, 4);
     else return group_allreduce<OP>(r, (int)L);
+  }
+
+  // ---- column sums over all rows (lane-group rows only) ----------------------------------------------------
+  // the row's values join the lane's running sums; padding lanes and rows beyond the last add nothing
+  __device__ __forceinline__ void colsum_add(const float (&v)[KV], float (&sum)[KV]) const {
+#pragma unroll
+    for (int k = 0; k < K; ++k) {
+      const bool ok = row_ok && valid(k);
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) sum[k * VEC + e] += ok ? v[k * VEC + e] : 0.0f;
+    }
+  }
+  // Lane-group rows: the workgroup's lane groups hold sums of the same columns: first the groups of a wavefront are folded lane to
+  // lane (lane ^ L, lane ^ 2L, ...: every lane ends with the wavefront's sum), then the four wavefronts through
+  // `lds` (4 * PADDED_COLS floats, used by this sum only), and one row of COLS partial sums goes to `dst`.  Fixed
+  // order throughout, so the result is the same from run to run.
+  __device__ __forceinline__ static void colsum_flush(const float (&sum)[KV], float* lds, float* dst) {
+    if constexpr (BLOCK) {
+      // a workgroup per row: every lane owns its columns alone, the sums over the workgroup's rows are complete
+#pragma unroll
+      for (int k = 0; k < K; ++k) {
+        const uint32_t at = (threadIdx.x + k * 256u) * VEC;
+        if (FULL_COLS || at < COLS) {
+#pragma unroll
+          for (int e = 0; e < VEC; ++e) dst[at + e] = sum[k * VEC + e];
+        }
+      }
+      return;
+    }
+    float v[KV];
+#pragma unroll
+    for (int j = 0; j < KV; ++j) v[j] = sum[j];
+#pragma unroll
+    for (uint32_t s = L; s < 64u; s <<= 1) {
+#pragma unroll
+      for (int j = 0; j < KV; ++j) v[j] += xor_lane(v[j], s);
+    }
+    const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = tid & (L - 1u);
+    if ((tid & 63u) < L) {
+#pragma unroll
+      for (int k = 0; k < K; ++k)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) lds[wave * PADDED_COLS + (lane + k * L) * VEC + e] = v[k * VEC + e];
+    }
+    __syncthreads();
+    for (uint32_t c = tid; c < COLS; c += 256u)
+      dst[c] = ((lds[c] + lds[PADDED_COLS + c]) + lds[2u * PADDED_COLS + c]) + lds[3u * PADDED_COLS + c];
   }
 };
 

@@ -8,7 +8,8 @@
 
 namespace fs {
 
-constexpr int kMaxPtrs = 20;
+constexpr int kMaxPtrs = 24;
+constexpr int kGenArgPtrs = 21;   // pointers of a generated kernel: the 20 operand slots of K_ROW_PROGRAM + the workspace
 
 // storage dtypes, numbered like the public fs_dtype
 enum DType : int32_t { DT_F32 = 0, DT_F16 = 1, DT_BF16 = 2, DT_I32 = 3 };
@@ -37,7 +38,8 @@ enum KernelId : int32_t {
   K_ROW_PROGRAM,       // interpreted row program: p0-3 full inputs, p4-7 column vectors, p8-11 per-row scalar
                        // inputs, p12-15 full outputs, p16-19 per-row scalar outputs
   K_LAYERNORM_BWD,     // p0 h, p1 dy, p2 gamma, p3 mu, p4 rstd, p5 dx, p6 partials [n_row_blocks, 2, cols]
-  K_ROW_GENERATED,     // a kernel generated and compiled for one row pattern at plan time; pointer slots as K_ROW_PROGRAM.
+  K_ROW_GENERATED,     // a kernel generated and compiled for one row pattern at plan time; pointer slots as K_ROW_PROGRAM,
+                       // p20 the workspace for column partial sums (or null).
                        // Not in the compiled-in table: launched through its own handle (gen_launch)
   K_COUNT
 };
@@ -183,7 +185,10 @@ enum ProgOp : uint8_t {
   PO_LOAD,                                                // acc <- b
   PO_RSUM, PO_RMAX, PO_RSUMSQ,                            // row reduction of acc (RSUMSQ: of acc squared) -> sacc
   PO_STORE,                                               // acc -> full output `dst`, stored as dtype `aux`
-  PO_STORE_SCAL                                           // sacc -> per-row output `dst`, dtype `aux`
+  PO_STORE_SCAL,                                          // sacc -> per-row output `dst`, dtype `aux`
+  PO_COLSUM                                               // acc is added to column sum `dst` (the sum over all rows of the
+                                                          // pattern; generated kernels only: partial sums per workgroup go
+                                                          // to the workspace and a second launch folds them)
 };
 // where operand b comes from
 enum ProgKind : uint8_t {
@@ -205,6 +210,7 @@ struct ProgInstr {
 };
 constexpr int kProgMaxInstr = 64;
 constexpr int kProgMaxOperands = 4;     // per class: full inputs, column vectors, per-row inputs, outputs
+constexpr int kProgMaxColSums = 2;      // what one fold launch hands out
 constexpr int kProgMaxReductions = 8;   // LDS slot sets of the workgroup-per-row form
 constexpr int kProgMaxLdsBytes = 128 * 1024;   // register files of one workgroup (a CU has 160 KB)
 struct RowProgP {
@@ -230,6 +236,9 @@ struct RowProgP {
   uint32_t out_perm;
   uint32_t oms[kProgMaxOperands][3];
   uint8_t rscal_sreg[kProgMaxOperands], rscal_dt[kProgMaxOperands];
+  int32_t n_colsum;                    // column sums over all rows (generated kernels only), at most kProgMaxColSums
+  int32_t rows_per_group;              // rows each lane group works through, one after the other (> 1 only with column sums:
+                                       // fewer, longer partial sums)
   ProgInstr instr[kProgMaxInstr];
 };
 struct ProgArgs {

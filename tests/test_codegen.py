@@ -41,7 +41,7 @@ def test_generated_source_is_specialised_to_pattern_extents_and_shape():
     plan = _plan(spec)
     info, src = plan.info, plan.source()
     assert info["pattern"] == "row_generated" and info["n_kernels"] == 1 and info["workspace_bytes"] == 0
-    m = re.search(r"typedef GenRow<(\d+)u, (\d+)u, (\d+), (\d+), (\d+)u, (true|false)> Row;", src)
+    m = re.search(r"typedef GenRow<(\d+)u, (\d+)u, (\d+), (\d+), (\d+)u, (true|false), 1u> Row;", src)
     assert m, src
     rows, cols, vec, k, lanes, block = int(m[1]), int(m[2]), int(m[3]), int(m[4]), int(m[5]), m[6] == "true"
     assert (rows, cols, vec) == (100, 768, 4)
@@ -91,7 +91,8 @@ def _force_every_generated_candidate(spec):
 
 
 def test_generated_source_compiles_for_every_kind_of_operand():
-    from workloads import (bias_head_split_graph, head_merge_residual_graph, normalize_from_stats_graph, outer_scale_graph,
+    from workloads import (bias_head_split_graph, gelu_backward_graph, head_merge_residual_graph, normalize_from_stats_graph, outer_scale_graph,
+                           rmsnorm_backward_graph,
                            scaled_softmax_colbias_graph, transpose_chain_stats_graph, transposed_softmax_graph)
     specs = [layernorm_stats_graph(24, 96, in_dtype="bf16", out_dtype="f16", with_variance=True),
              silu_gate_graph(9, 64, "f16"), scaled_softmax_colbias_graph(13, 40, "f32"),
@@ -99,7 +100,8 @@ def test_generated_source_compiles_for_every_kind_of_operand():
              masked_scores_gate_graph(2, 3, 5, 64, dtype="bf16"),
              bias_head_split_graph(2, 5, 3, 16, "bf16"), head_merge_residual_graph(2, 5, 3, 64, "f16"),   # column vector + permuted rows
              transpose_chain_stats_graph(2, 5, 3, 16), transposed_softmax_graph(2, 5, 3, 32, "f16"),
-             layernorm_stats_graph(3, 4096, in_dtype="f32", out_dtype="f32", with_variance=True)]           # workgroup per row
+             layernorm_stats_graph(3, 4096, in_dtype="f32", out_dtype="f32", with_variance=True),           # workgroup per row
+             gelu_backward_graph(300, 96, "bf16"), rmsnorm_backward_graph(5000, 2048, "f16")]               # column sums, both row forms
     for spec in specs:
         assert _force_every_generated_candidate(spec) >= 1, spec.name
 
@@ -140,6 +142,12 @@ def test_explorer_compiles_only_what_the_chosen_plan_runs():
 
 
 def test_unsupported_pattern_is_not_rescued_by_code_generation():
+    # a column sum that the pattern itself reads again would take a grid-wide wait inside the kernel
+    spec = GraphSpec("pattern_x", [TensorSpec("x", "f32", (8, 16))],
+                     [OpSpec("e", "exp", ("x",)), OpSpec("s", "reduce_sum", ("e",), {"axis": 0}), OpSpec("y", "div", ("e", "s"))],
+                     [("y", "f32")])
+    assert _plan(spec).info["scheme"] == "unfused"
+    # as an output it is fine: partial sums + fold
     spec = GraphSpec("pattern_x", [TensorSpec("x", "f32", (8, 16))],
                      [OpSpec("e", "exp", ("x",)), OpSpec("s", "reduce_sum", ("e",), {"axis": 0})], [("s", "f32")])
-    assert _plan(spec).info["scheme"] == "unfused"
+    assert _plan(spec).info["scheme"] == "global"

@@ -16,6 +16,7 @@ pytestmark = pytest.mark.gpu
 RMS_FLOOR = {"C2": {"out"}, "C4": {"dbias"}, "N1": {"dx"}, "N2": {"dx", "dgamma", "dbeta"}, "N6": {"out", "mu"},
              "G1": {"out", "mu"}, "G4": {"out", "topb"},
              "G8": {"out"},    # gain * ctx + residual cancels
+             "G9": {"dx", "dbias"}, "G10": {"dx", "dgamma"},   # signed column sums; dx of RMSNorm is a difference
              "G5": {"y"}}     # probabilities down to exp(-60) sit below the smallest fp16 number and are stored as 0
 ALL = dict(FULL_CONFIGS, **NEXT_CONFIGS, **GENERIC_CONFIGS)
 
@@ -31,7 +32,7 @@ def test_full_size_transpose_bit_exact(cfg):
         note(f"    {cfg} {scheme} {info['kernel']}: bit-exact over {want.size} elements")
 
 
-@pytest.mark.parametrize("cfg", ["C1", "C2", "C3", "C4", "C5", "N1", "N2", "N5", "N6", "G1", "G2", "G3", "G4", "G5", "G6", "G7", "G8"])
+@pytest.mark.parametrize("cfg", ["C1", "C2", "C3", "C4", "C5", "N1", "N2", "N5", "N6", "G1", "G2", "G3", "G4", "G5", "G6", "G7", "G8", "G9", "G10"])
 def test_full_size_config(cfg):
     spec = ALL[cfg]()
     note(f"  full-size {cfg}: {spec.name}: generating inputs")

@@ -8,7 +8,8 @@ import pytest
 from oracle import oracle as O
 from paper_2009_10924_amd import binding as B
 from tests.gpu_util import all_candidates, note
-from workloads import (bias_head_split_graph, head_merge_residual_graph, layernorm_stats_graph, make_inputs,
+from workloads import (bias_head_split_graph, gelu_backward_graph, head_merge_residual_graph, layernorm_stats_graph, make_inputs,
+                       rmsnorm_backward_graph,
                        normalize_from_stats_graph, outer_scale_graph, random_row_pattern, scaled_softmax_colbias_graph,
                        silu_gate_graph, transpose_chain_stats_graph, transposed_softmax_graph)
 
@@ -113,6 +114,21 @@ def test_row_lengths_that_allow_no_128_bit_access(rows, cols, dtype):
         spec = make()
         worst, info = _run(spec)
         assert info["pattern"] == "row_generated"
+        note(f"{spec.name}: {info['kernel']}, {info['n_candidates']} shapes, worst {worst}")
+
+
+@pytest.mark.parametrize("rows,cols,dtype", [(37, 96, "f32"), (1000, 128, "bf16"), (4100, 64, "f16"), (300, 768, "f32"), (2500, 1024, "bf16"),
+                                             (70, 4096, "f16"), (5000, 8, "f32")])
+def test_column_sums_beside_row_work(rows, cols, dtype):
+    """A column sum over all rows next to row-local outputs (backward of bias + GELU, backward of RMSNorm): partial
+    sums per workgroup in the workspace, folded by a second launch; every launch shape and every number of rows per
+    lane group, ragged row counts included, and bit-identical results from run to run."""
+    if not B.codegen_available():
+        pytest.skip("column sums inside a row pattern exist as generated kernels only")
+    for make in (gelu_backward_graph, rmsnorm_backward_graph):
+        spec = make(rows, cols, dtype)
+        worst, info = _run(spec, repeat=3)
+        assert info["pattern"] == "row_generated" and info["n_kernels"] == 2 and info["scheme"] == "global"
         note(f"{spec.name}: {info['kernel']}, {info['n_candidates']} shapes, worst {worst}")
 
 

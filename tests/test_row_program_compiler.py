@@ -80,6 +80,13 @@ def emulate(listing, spec, inputs, anchor_dims):
                 out_rows[int(l[1])] = strided_rows(strides[0])
         elif l[0] == "routput":
             rout_bind[int(l[1])] = int(l[2][3:])
+    # column sums leave through the fold launch that follows: its pointer lines name the outputs
+    fold = [i for i, l in enumerate(lines) if l[:2] == ["launch", "colfold"]]
+    colsum_bind = {}
+    if fold:
+        for l in lines[fold[0] + 1:]:
+            if l and l[0] in ("ptr1", "ptr2"):
+                colsum_bind[int(l[0][3:]) - 1] = int(l[1][3:])
     acc = np.zeros((rows, cols), np.float32) if acc0 is None else acc0.copy()
     sacc = np.zeros((rows, 1), np.float32)
     f32 = np.float32
@@ -106,6 +113,9 @@ def emulate(listing, spec, inputs, anchor_dims):
             continue
         if op == "store_scal":
             outs[rout_bind[dst]] = sacc.copy()
+            continue
+        if op == "colsum":
+            outs[colsum_bind[dst]] = acc.astype(np.float64).sum(axis=0).astype(np.float32)
             continue
         if op in ("rsum", "rmax", "rsumsq"):
             src = acc * acc if op == "rsumsq" else acc
@@ -144,7 +154,7 @@ def _compare(spec, seed=1):
     assert plan.info["pattern"] in ("row_program", "row_generated"), (spec.name, plan.info["pattern"])
     if plan.info["pattern"] == "row_generated":
         src = plan.source()
-        assert "fs_generated_row_kernel" in src and src.count("row.store") == len(spec.outputs)
+        assert "fs_generated_row_kernel" in src and src.count("row.store") + src.count("colsum_flush") == len(spec.outputs)
     listing = plan.describe()
     inp = make_inputs(spec, seed=seed)
     ref = O.evaluate(spec, inp)
@@ -217,6 +227,17 @@ def test_transposes_of_leading_axes_fold_into_loads_and_stores(dims, perm):
     _compare(both)
 
 
+@pytest.mark.parametrize("rows,cols", [(37, 96), (50, 128), (9, 1024)])
+def test_column_sums_compile_to_partial_sums_and_a_fold(rows, cols):
+    from workloads import gelu_backward_graph, rmsnorm_backward_graph
+    for make in (gelu_backward_graph, rmsnorm_backward_graph):
+        spec = make(rows, cols, "f32")
+        _, info = _compare(spec)
+        if B.codegen_available():
+            assert info["n_kernels"] == 2 and info["scheme"] == "global"
+            assert info["workspace_bytes"] % (cols * 4) == 0 and info["workspace_bytes"] > 0
+
+
 def test_transposes_a_row_program_cannot_fold():
     from workloads.graphs import GraphSpec, OpSpec, TensorSpec
     # the innermost axis moves: data crosses rows -> the pattern is not one row kernel
@@ -250,9 +271,14 @@ def test_random_patterns_compile_to_correct_programs(seed):
 
 def test_patterns_that_are_not_row_local_are_refused():
     from workloads.graphs import GraphSpec, OpSpec, TensorSpec
-    # column reduction: values cross rows
+    # a column reduction whose result is read inside the pattern: values cross rows
     spec = GraphSpec("pattern_x", [TensorSpec("x", "f32", (8, 16))],
-                     [OpSpec("e", "exp", ("x",)), OpSpec("s", "reduce_sum", ("e",), {"axis": 0})], [("s", "f32")])
+                     [OpSpec("e", "exp", ("x",)), OpSpec("s", "reduce_sum", ("e",), {"axis": 0}), OpSpec("y", "div", ("e", "s"))],
+                     [("y", "f32")])
+    assert B.Plan(B.Graph.from_spec(spec), "auto").info["scheme"] == "unfused"
+    # a column maximum, or a column sum stored in 16 bits: no fold kernel hands those out
+    spec = GraphSpec("pattern_x", [TensorSpec("x", "f32", (8, 16))],
+                     [OpSpec("e", "exp", ("x",)), OpSpec("s", "reduce_max", ("e",), {"axis": 0})], [("s", "f32")])
     assert B.Plan(B.Graph.from_spec(spec), "auto").info["scheme"] == "unfused"
     # an output that is stretched itself would be written by several rows
     spec = GraphSpec("pattern_w", [TensorSpec("x", "f32", (4, 6, 16)), TensorSpec("m", "f32", (4, 1, 16))],

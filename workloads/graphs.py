@@ -403,6 +403,36 @@ def transposed_softmax_graph(batch: int, q_len: int, heads: int, k_len: int, dty
                      inputs=[TensorSpec("scores", dtype, (batch, q_len, heads, k_len))], ops=ops, outputs=[("y", dtype)])
 
 
+def gelu_backward_graph(rows: int, cols: int, dtype: str = "bf16") -> GraphSpec:
+    """Backward of bias + tanh-GELU: dx = g * gelu'(x + bias) and the bias gradient, the column sum of dx (float32)."""
+    ops = [_op("z", "add", "x", "bias"), _op("d", "gelu_tanh_grad", "z"), _op("dx", "mul", "g", "d"),
+           _op("dbias", "reduce_sum", "dx", axis=0)]
+    return GraphSpec(name=f"pattern_gelu_backward_{dtype}_{rows}x{cols}",
+                     inputs=[TensorSpec("x", dtype, (rows, cols)), TensorSpec("bias", dtype, (cols,)), TensorSpec("g", dtype, (rows, cols))],
+                     ops=ops, outputs=[("dx", dtype), ("dbias", "f32")])
+
+
+def rmsnorm_backward_graph(rows: int, cols: int, dtype: str = "bf16") -> GraphSpec:
+    """Backward of RMSNorm from the saved reciprocal rms: xhat = x * rrms; dgamma = column sum of dy * xhat;
+    gy = dy * gamma; dx = (gy - xhat * rowmean(gy * xhat)) * rrms.  A row reduction and a column reduction in one
+    pattern."""
+    ops = [
+        _op("xhat", "mul", "x", "rrms"),
+        _op("dyx", "mul", "dy", "xhat"),
+        _op("dgamma", "reduce_sum", "dyx", axis=0),
+        _op("gy", "mul", "dy", "g"),
+        _op("gx", "mul", "gy", "xhat"),
+        _op("m", "reduce_mean", "gx", axis=1),
+        _op("xm", "mul", "xhat", "m"),
+        _op("c", "sub", "gy", "xm"),
+        _op("dx", "mul", "c", "rrms"),
+    ]
+    return GraphSpec(name=f"pattern_rmsnorm_backward_{dtype}_{rows}x{cols}",
+                     inputs=[TensorSpec("x", dtype, (rows, cols)), TensorSpec("dy", dtype, (rows, cols)), TensorSpec("g", dtype, (cols,)),
+                             TensorSpec("rrms", "f32", (rows, 1))],
+                     ops=ops, outputs=[("dx", dtype), ("dgamma", "f32")])
+
+
 def random_row_pattern(seed: int, rows: int, cols: int, dtype: str = "f32", n_ops: int = 12) -> GraphSpec:
     """A random connected pattern of element-wise ops and row reductions over [rows, cols] (descriptor only).
     Domains are kept safe by construction: exp only of tanh, division and rsqrt only of 1 + square."""
@@ -629,6 +659,9 @@ GENERIC_CONFIGS = {
     "G6": lambda: bias_head_split_graph(64, 512, 16, 64, "bf16"),            # projection bias + head split (store side)
     "G7": lambda: transpose_chain_stats_graph(64, 512, 12, 64),              # C5 plus the stored row sums (load side)
     "G8": lambda: head_merge_residual_graph(64, 512, 16, 64, "bf16"),        # head merge + gain + residual (load side)
+    # column sums over all rows beside the row-local work: partial sums per workgroup + a fold launch
+    "G9": lambda: gelu_backward_graph(16384, 3072, "bf16"),                  # C4's shape
+    "G10": lambda: rmsnorm_backward_graph(8192, 4096, "bf16"),               # N5's shape
 }
 
 FULL_CONFIGS = {
