@@ -169,6 +169,8 @@ def measure_config(name, spec, steps, warmup, with_unfused=True):
         "GBps": r.info["bytes_min"] / sec / 1e9, "frac_of_peak": r.info["bytes_min"] / sec / 1e9 / HBM_PEAK_GBPS,
         "predicted_us": r.info["predicted_us"], "buffer_sets": r.n_sets,
     }
+    if r.info["pattern"] == "row_generated":   # the generated kernel's own name, as kernel traces show it
+        out["entry"] = [l.split()[1] for l in r.plan.describe().splitlines() if l.strip().startswith("entry ")][0]
     if with_unfused:
         host = r.host_inputs
         del r

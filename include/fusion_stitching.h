@@ -173,7 +173,8 @@ fs_status fs_plan_candidate(const fs_plan *p, int32_t index, fs_plan_info *out);
 /* Writes a text listing of what the plan will run into `text` (HOST buffer of `capacity`
  * bytes, always NUL-terminated when capacity > 0; truncated if too small) and returns
  * the size needed for the whole listing including the NUL, or a negative error.  One
- * line per launch (kernel, grid, block, dynamic LDS) and per buffer binding; for a
+ * line per launch (kernel, grid, block, dynamic LDS) and per buffer binding (a generated
+ * kernel also `entry <name of its entry point>`, the name kernel traces show); for a
  * pattern that runs as a row program (the generic path for patterns no hand-written
  * kernel covers, Section 4.2; interpreted or as a generated kernel) also its register
  * files, the extents of the leading axes (`lead=a,b,c`), for operands and outputs that

@@ -71,9 +71,24 @@ std::string stretched_row(const uint32_t (&ms)[3], const char* pre = "") {
 
 }  // namespace
 
-const char* generated_kernel_entry() { return "fs_generated_row_kernel"; }
+namespace {
+std::string body_with_entry(const RowProgP& p, const char* entry);
+const char kEntryPlaceholder[] = "@ENTRY@";
+}  // namespace
 
-std::string generate_row_kernel_body(const RowProgP& p) {
+// The kernel's name carries a hash of its own source (pattern, extents and launch shape), so that kernel traces
+// tell the generated kernels of a process apart.
+std::string generated_kernel_entry(const RowProgP& p) {
+  const std::string body = body_with_entry(p, kEntryPlaceholder);
+  uint32_t h = 2166136261u;   // FNV-1a
+  for (unsigned char ch : body) h = (h ^ ch) * 16777619u;
+  return fmt("fs_gen_row_%08x", h);
+}
+
+std::string generate_row_kernel_body(const RowProgP& p) { return body_with_entry(p, generated_kernel_entry(p).c_str()); }
+
+namespace {
+std::string body_with_entry(const RowProgP& p, const char* entry) {
   const bool block = p.lanes_per_row > 64;
   int n_reductions = 0;
   for (int i = 0; i < p.n_instr; ++i)
@@ -81,7 +96,7 @@ std::string generate_row_kernel_body(const RowProgP& p) {
 
   std::string s;
   s += "using namespace fsk;\n";
-  s += fmt("extern \"C\" __global__ void __launch_bounds__(256) %s(const GenArgs a) {\n", generated_kernel_entry());
+  s += fmt("extern \"C\" __global__ void __launch_bounds__(256) %s(const GenArgs a) {\n", entry);
   const uint32_t R = p.rows_per_group > 1 ? (uint32_t)p.rows_per_group : 1u;
   s += fmt("  typedef GenRow<%uu, %uu, %d, %d, %uu, %s, %uu> Row;\n", p.rows, p.cols, p.vec, p.vecs_per_lane,
            block ? 256u : (uint32_t)p.lanes_per_row, block ? "true" : "false", R);
@@ -231,6 +246,7 @@ std::string generate_row_kernel_body(const RowProgP& p) {
   s += "}\n";
   return s;
 }
+}  // namespace
 
 std::string generate_row_kernel(const RowProgP& p) {
   std::string s;

@@ -137,7 +137,7 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out);
 // launch shape; the body alone (without the embedded device headers) for listings.
 std::string generate_row_kernel(const RowProgP& p);
 std::string generate_row_kernel_body(const RowProgP& p);
-const char* generated_kernel_entry();
+std::string generated_kernel_entry(const RowProgP& p);   // fs_gen_row_<hash of the source>
 // Process-wide switch: candidates with generated kernels are offered only while it is on (default: on
 // unless the environment says FS_CODEGEN=0) and the run-time compiler is available.
 bool codegen_enabled();

@@ -77,7 +77,7 @@ fs_status complete_plan(fs_plan* p) {
       if (l.kernel == K_ROW_GENERATED && !l.gen) gen = &l;
     if (!gen) return FS_OK;
     std::string log;
-    const int err = gen_compile(generate_row_kernel(gen->args.u.prog), generated_kernel_entry(), &gen->gen, &log);
+    const int err = gen_compile(generate_row_kernel(gen->args.u.prog), generated_kernel_entry(gen->args.u.prog).c_str(), &gen->gen, &log);
     bool usable = err == 0;
     std::string why;
     if (!usable) {
@@ -245,6 +245,7 @@ int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) {
     snprintf(line, sizeof line, "launch %s grid=%u block=%u lds=%u\n", kernel_name(l.kernel), l.shape.grid[0] * l.shape.grid[1] * l.shape.grid[2],
              l.shape.block[0] * l.shape.block[1] * l.shape.block[2], l.shape.lds_bytes);
     s += line;
+    if (l.kernel == K_ROW_GENERATED) s += "  entry " + generated_kernel_entry(l.args.u.prog) + "\n";
     if (l.kernel != K_ROW_PROGRAM && l.kernel != K_ROW_GENERATED) {
       for (int k = 0; k < kMaxPtrs; ++k)
         if (l.ptr[k].kind != BUF_NONE) s += "  ptr" + std::to_string(k) + " " + buf_name(l.ptr[k]) + "\n";

@@ -154,7 +154,7 @@ def _compare(spec, seed=1):
     assert plan.info["pattern"] in ("row_program", "row_generated"), (spec.name, plan.info["pattern"])
     if plan.info["pattern"] == "row_generated":
         src = plan.source()
-        assert "fs_generated_row_kernel" in src and src.count("row.store") + src.count("colsum_flush") == len(spec.outputs)
+        assert "__global__ void __launch_bounds__(256) fs_gen_row_" in src and src.count("row.store") + src.count("colsum_flush") == len(spec.outputs)
     listing = plan.describe()
     inp = make_inputs(spec, seed=seed)
     ref = O.evaluate(spec, inp)
