@@ -98,8 +98,9 @@ std::string body_with_entry(const RowProgP& p, const char* entry) {
   s += "using namespace fsk;\n";
   s += fmt("extern \"C\" __global__ void __launch_bounds__(256) %s(const GenArgs a) {\n", entry);
   const uint32_t R = p.rows_per_group > 1 ? (uint32_t)p.rows_per_group : 1u;
-  s += fmt("  typedef GenRow<%uu, %uu, %d, %d, %uu, %s, %uu> Row;\n", p.rows, p.cols, p.vec, p.vecs_per_lane,
-           block ? 256u : (uint32_t)p.lanes_per_row, block ? "true" : "false", R);
+  const uint32_t CT = p.col_tiles > 1 ? (uint32_t)p.col_tiles : 1u;   // column tiles of cols / CT elements
+  s += fmt("  typedef GenRow<%uu, %uu, %d, %d, %uu, %s, %uu, %uu> Row;\n", p.rows, p.cols / CT, p.vec, p.vecs_per_lane,
+           block ? 256u : (uint32_t)p.lanes_per_row, block ? "true" : "false", R, p.cols);
   s += "  constexpr int KV = Row::KV;\n";
   if (block && n_reductions > 0) s += fmt("  __shared__ float slots[%d];\n", 4 * n_reductions);
   const bool looped = p.n_colsum > 0;
@@ -148,7 +149,10 @@ std::string body_with_entry(const RowProgP& p, const char* entry) {
     if (!block) s += fmt("  __shared__ float colred[%d][4 * Row::PADDED_COLS];\n", p.n_colsum);
     for (int i = 0; i < p.n_colsum; ++i)
       s += fmt("  float cs%d[KV];\n#pragma unroll\n  for (int j = 0; j < KV; ++j) cs%d[j] = 0.0f;\n", i, i);
-    s += "  Row nrow(blockIdx.x);\n";
+    // neighbouring workgroups take neighbouring column tiles of the same rows
+    if (CT > 1) s += fmt("  const uint32_t tile = blockIdx.x %% %uu, row_wg = blockIdx.x / %uu, n_row_wgs = gridDim.x / %uu;\n", CT, CT, CT);
+    else s += "  const uint32_t tile = 0, row_wg = blockIdx.x, n_row_wgs = gridDim.x;\n";
+    s += "  Row nrow(row_wg, tile);\n";
     s += col_loads("nrow");
     if (needs_lead) s += "  uint32_t nq1, nlead0, nlead1, nlead2;\n" + lead_of("nrow", "n", false);
     s += row_loads("nrow", "n", "auto ", "float ");
@@ -158,7 +162,7 @@ std::string body_with_entry(const RowProgP& p, const char* entry) {
     if (p.out_perm) s += lead_of("row", "", true);
     for (int i = 0; i < p.n_full; ++i) s += fmt("  const auto raw_full%d = nraw_full%d;\n", i, i);
     for (int i = 0; i < p.n_rscal; ++i) s += fmt("  const float in_rscal%d = nin_rscal%d;\n", i, i);
-    s += fmt("  nrow = Row(min(it + 1u, %uu) * gridDim.x + blockIdx.x);\n", R - 1u);
+    s += fmt("  nrow = Row(min(it + 1u, %uu) * n_row_wgs + row_wg, tile);\n", R - 1u);
     if (needs_lead) s += lead_of("nrow", "n", false);
     s += row_loads("nrow", "n", "", "");
   } else {
@@ -240,8 +244,8 @@ std::string body_with_entry(const RowProgP& p, const char* entry) {
     if (block && n_reductions > 0) s += "  __syncthreads();\n";
     s += "  }\n";
     for (int i = 0; i < p.n_colsum; ++i)
-      s += fmt("  Row::colsum_flush(cs%d, %s, static_cast<float*>(a.ws) + (size_t)blockIdx.x * %uu + %uu);\n", i,
-               block ? "nullptr" : fmt("colred[%d]", i).c_str(), (uint32_t)p.n_colsum * p.cols, (uint32_t)i * p.cols);
+      s += fmt("  Row::colsum_flush(cs%d, %s, static_cast<float*>(a.ws) + (size_t)row_wg * %uu + %uu + tile * %uu);\n", i,
+               block ? "nullptr" : fmt("colred[%d]", i).c_str(), (uint32_t)p.n_colsum * p.cols, (uint32_t)i * p.cols, p.cols / CT);
   }
   s += "}\n";
   return s;

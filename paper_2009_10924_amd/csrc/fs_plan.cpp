@@ -275,7 +275,7 @@ int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) {
       if (l.ptr[16 + i].kind != BUF_NONE) s += "  routput " + std::to_string(i) + " " + buf_name(l.ptr[16 + i]) + "\n";
     if (q.n_colsum > 0)   // partial sums: one row of n_colsum * cols floats per workgroup, folded by the next launch
       s += "  colsums " + std::to_string(q.n_colsum) + " partials " + buf_name(l.ptr[20]) + " rows_per_group " +
-           std::to_string(q.rows_per_group) + "\n";
+           std::to_string(q.rows_per_group) + " col_tiles " + std::to_string(q.col_tiles > 1 ? q.col_tiles : 1) + "\n";
     static const char* op_names[] = {"add", "sub", "rsub", "mul", "div", "rdiv", "max", "square", "exp", "rsqrt", "tanh", "gelu",
                                      "gelu_grad", "cvt", "load", "rsum", "rmax", "rsumsq", "store", "store_scal", "colsum"};
     static const char* kind_names[] = {"acc", "sacc", "reg", "scal", "imm", "col"};

@@ -595,6 +595,7 @@ struct Compiler {
     if (!walk()) return false;
     p.n_colsum = n_colsum;
     p.rows_per_group = 1;
+    p.col_tiles = 1;
     if (n_colsum > 0) interpretable = false;
     return n_out + n_rout + n_colsum == (int)g.outputs.size();
   }
@@ -614,7 +615,7 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
   const double n = (double)base.rows * base.cols;
   const int64_t bytes_min = graph_bytes_min(g);
 
-  struct Shape { uint32_t L; int K; bool block; bool generated; uint32_t R = 1; };
+  struct Shape { uint32_t L; int K; bool block; bool generated; uint32_t R = 1; uint32_t CT = 1; };
   std::vector<Shape> shapes;
   if (c.interpretable) {
     for (int K : {1, 2, 4}) {
@@ -639,15 +640,36 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
     if (c.n_colsum > 0) {
       // Column sums: a workgroup's lane groups work through R rows each and leave one row of partial sums, so R trades
       // extra traffic (2 x workgroups x columns x 4 bytes) against workgroups to fill the chip with.
+      // Without row reductions nothing ties the columns of a row together: a workgroup may take one tile of 64 or 128
+      // vectors, so a lane keeps one or two vectors per value whatever the row length.
+      if (c.n_reductions == 0 && c.n_rout == 0)
+        for (int K : {1, 2}) {
+          const uint32_t tile_vecs = 64u * K;
+          if (nvec % tile_vecs == 0 && nvec / tile_vecs > 1 && nvec / tile_vecs <= 4096) {
+            Shape t{64, K, false, true};
+            t.CT = nvec / tile_vecs;
+            shapes.push_back(t);
+          }
+        }
       std::vector<Shape> with_r;
       for (const Shape& sh : shapes) {
         if (!sh.generated) continue;
         const uint32_t rows_per_wg = sh.block ? 1 : 256 / sh.L;
+        std::vector<Shape> of_shape;
+        bool some_moderate = false;
         for (uint32_t R : {1u, 2u, 4u, 8u, 16u, 32u, 64u}) {
-          const uint64_t n_wg = (base.rows + (uint64_t)rows_per_wg * R - 1) / ((uint64_t)rows_per_wg * R);
+          const uint64_t n_wg = (base.rows + (uint64_t)rows_per_wg * R - 1) / ((uint64_t)rows_per_wg * R) * sh.CT;
           if (R > 1 && n_wg < 256) break;    // one workgroup per compute unit at the least
           Shape t = sh;
           t.R = R;
+          of_shape.push_back(t);
+          some_moderate = some_moderate || n_wg <= 8192;
+        }
+        for (const Shape& t : of_shape) {
+          // thousands of workgroups more than the chip holds only multiply the partial sums: not offered when a
+          // larger R brings the count down
+          const uint64_t n_wg = (base.rows + (uint64_t)rows_per_wg * t.R - 1) / ((uint64_t)rows_per_wg * t.R) * sh.CT;
+          if (some_moderate && n_wg > 8192) continue;
           with_r.push_back(t);
         }
       }
@@ -690,8 +712,10 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
     for (int i = 0; i < c.n_rout; ++i) { l.ptr[16 + i].kind = BUF_OUTPUT; l.ptr[16 + i].slot = c.rout_slot[i]; }
     const uint32_t rows_per_block = (s.block ? 1 : 256 / s.L) * s.R;
     l.shape.block[0] = 256;
-    l.shape.grid[0] = (base.rows + rows_per_block - 1) / rows_per_block;
+    const uint32_t n_row_wgs = (base.rows + rows_per_block - 1) / rows_per_block;
+    l.shape.grid[0] = n_row_wgs * s.CT;
     l.args.u.prog.rows_per_group = (int32_t)s.R;
+    l.args.u.prog.col_tiles = (int32_t)s.CT;
     l.shape.lds_bytes = (uint32_t)lds;
     cand.info.lanes_per_row = (int32_t)s.L;
     cand.info.vecs_per_lane = s.K;
@@ -718,7 +742,7 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
     kc.xlane_steps = steps * c.n_reductions;
     kc.barriers = s.block ? c.n_reductions : 0;
     kc.lds_bytes_per_block = (int32_t)lds;
-    kc.lane_utilisation = (double)nvec / ((double)s.L * s.K);
+    kc.lane_utilisation = (double)(nvec / s.CT) / ((double)s.L * s.K);
     {
       // contiguous bytes the lanes of one row touch per access of the narrowest input
       double narrowest = 4.0;
@@ -753,7 +777,7 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
         // partial sums of every workgroup through the workspace, folded by a second launch (one hand-off through
         // device memory: the GLOBAL scheme)
         Launch& ml = cand.launches.back();
-        const uint32_t n_wg = ml.shape.grid[0];
+        const uint32_t n_wg = n_row_wgs;   // one row of partial sums per row block (its column tiles share the row)
         const uint32_t width = (uint32_t)c.n_colsum * base.cols;
         ml.ptr[20].kind = BUF_WORKSPACE;
         ml.ptr[20].offset = 0;
@@ -771,11 +795,20 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
         cand.info.n_kernels = 2;
         cand.info.workspace_bytes = (int64_t)n_wg * width * 4;
         cand.info.bytes_moved_model = bytes_min + 2 * cand.info.workspace_bytes;
-        snprintf(cand.info.kernel, sizeof cand.info.kernel, "row_generated<v%d,K%d,L%u,I%d,R%d,rows%u>+colfold", vec, s.K, s.L, base.n_instr,
-                 base.n_regs, s.R);
+        if (s.CT > 1)
+          snprintf(cand.info.kernel, sizeof cand.info.kernel, "row_generated<v%d,K%d,L%u,I%d,R%d,rows%u,tiles%u>+colfold", vec, s.K, s.L,
+                   base.n_instr, base.n_regs, s.R, s.CT);
+        else
+          snprintf(cand.info.kernel, sizeof cand.info.kernel, "row_generated<v%d,K%d,L%u,I%d,R%d,rows%u>+colfold", vec, s.K, s.L, base.n_instr,
+                   base.n_regs, s.R);
         gc.hbm_bytes += 2.0 * (double)cand.info.workspace_bytes;
         gc.vgpr_estimate += kv * c.n_colsum;
         gc.rows_per_wave_loop = s.R;
+        if (s.R > 1) {   // software-pipelined: only the first row's load latency is exposed
+          gc.dep_phases = 0;
+          gc.serial_tail_s += d.mem_latency_s;
+          gc.bytes_in_flight_per_lane *= 2.0;   // this row's and the next row's loads
+        }
         gc.lds_bytes_per_block = cand.info.lds_bytes;
         gc.barriers = 1;
         gc.serial_tail_s += d.mem_latency_s + 0.5 * d.launch_s + d.mem_latency_s * std::ceil(n_wg / 64.0 / 8.0) * 0.5;

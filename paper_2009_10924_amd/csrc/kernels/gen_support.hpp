@@ -111,7 +111,9 @@ __device__ __forceinline__ void unpack_step(const StepBits<2>& r, float (&v)[1],
 // (a lane group of one wavefront), or the whole 256-thread workgroup when BLOCK.
 // R: rows each lane group works through, one after the other (the kernel body runs R times with virtual
 // workgroup indices it * gridDim.x + blockIdx.x, so that at any moment the resident workgroups sweep one band of rows).
-template <uint32_t ROWS, uint32_t COLS, int VEC, int K, uint32_t L, bool BLOCK, uint32_t R = 1>
+// ROW_STRIDE > COLS: the pattern's rows are ROW_STRIDE elements long and the kernel works on column tiles of COLS
+// elements (patterns without row reductions only: nothing ties the tiles of a row together); `tile` picks the tile.
+template <uint32_t ROWS, uint32_t COLS, int VEC, int K, uint32_t L, bool BLOCK, uint32_t R = 1, uint32_t ROW_STRIDE = COLS>
 struct GenRow {
   static constexpr uint32_t NVEC = COLS / VEC;
   static constexpr uint32_t LANES = BLOCK ? 256u : L;
@@ -122,11 +124,12 @@ struct GenRow {
   static constexpr int KV = K * VEC;
   static constexpr uint32_t PADDED_COLS = LANES * K * VEC;   // columns the lanes of a row cover, padding included
 
-  uint32_t lane, row, row_c;
+  uint32_t lane, row, row_c, col0;
   bool row_ok;
 
-  __device__ __forceinline__ explicit GenRow(uint32_t vblock) {
+  __device__ __forceinline__ explicit GenRow(uint32_t vblock, uint32_t tile = 0) {
     const uint32_t tid = threadIdx.x;
+    col0 = tile * COLS;
     lane = BLOCK ? tid : (tid & (L - 1u));
     row = BLOCK ? vblock : vblock * ROWS_PER_WG + tid / L;
     row_ok = FULL_ROWS || row < ROWS;
@@ -144,7 +147,7 @@ struct GenRow {
   template <typename T, bool STREAM>
   __device__ __forceinline__ Raw<T> load(const void* p, size_t at_row) const {
     Raw<T> r;
-    const T* base = static_cast<const T*>(p) + at_row * COLS;
+    const T* base = static_cast<const T*>(p) + at_row * ROW_STRIDE + col0;
 #pragma unroll
     for (int k = 0; k < K; ++k) r.w[k] = StepBits<VEC * (int)sizeof(T)>::template load<STREAM>(base + (size_t)vec_at(k) * VEC);
     return r;
@@ -167,7 +170,7 @@ struct GenRow {
   // the row's values to row `at_row` of the output (its own row, or the place a folded transpose gives it)
   template <typename TO>
   __device__ __forceinline__ void store_at(void* p, size_t at_row, const float (&v)[KV]) const {
-    TO* base = static_cast<TO*>(p) + at_row * COLS;
+    TO* base = static_cast<TO*>(p) + at_row * ROW_STRIDE + col0;
 #pragma unroll
     for (int k = 0; k < K; ++k) {
       float part[VEC];

@@ -239,6 +239,8 @@ struct RowProgP {
   int32_t n_colsum;                    // column sums over all rows (generated kernels only), at most kProgMaxColSums
   int32_t rows_per_group;              // rows each lane group works through, one after the other (> 1 only with column sums:
                                        // fewer, longer partial sums)
+  int32_t col_tiles;                   // > 1: a workgroup handles one of col_tiles column tiles of cols / col_tiles elements
+                                       // (generated kernels for patterns with column sums and no row reduction)
   ProgInstr instr[kProgMaxInstr];
 };
 struct ProgArgs {

@@ -41,7 +41,7 @@ def test_generated_source_is_specialised_to_pattern_extents_and_shape():
     plan = _plan(spec)
     info, src = plan.info, plan.source()
     assert info["pattern"] == "row_generated" and info["n_kernels"] == 1 and info["workspace_bytes"] == 0
-    m = re.search(r"typedef GenRow<(\d+)u, (\d+)u, (\d+), (\d+), (\d+)u, (true|false), 1u> Row;", src)
+    m = re.search(r"typedef GenRow<(\d+)u, (\d+)u, (\d+), (\d+), (\d+)u, (true|false), 1u, 768u> Row;", src)
     assert m, src
     rows, cols, vec, k, lanes, block = int(m[1]), int(m[2]), int(m[3]), int(m[4]), int(m[5]), m[6] == "true"
     assert (rows, cols, vec) == (100, 768, 4)
