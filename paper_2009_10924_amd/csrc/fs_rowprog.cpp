@@ -607,7 +607,17 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
   Compiler c(g);
   if (!c.run()) return false;
   const RowProgP& base = c.p;
-  const int vec = base.vec;
+  // Step widths to offer.  A pattern whose 16-bit vector inputs ask for 8 elements per step may also move float32
+  // rows (an input, or an output stored as float32): those take two 128-bit accesses per step, 32 bytes apart per
+  // lane, which the memory system likes less than one; 4 elements per step turns that around (float32 in one
+  // access, the 16-bit operands in 64-bit ones).  Both are offered then, the narrower one as generated kernels.
+  bool moves_f32_rows = false;
+  for (int i = 0; i < base.n_full; ++i) moves_f32_rows = moves_f32_rows || base.full_dt[i] == DT_F32;
+  for (int i = 0; i < base.n_instr; ++i) moves_f32_rows = moves_f32_rows || (base.instr[i].op == PO_STORE && base.instr[i].aux == DT_F32);
+  std::vector<int> widths(1, base.vec);
+  if (base.vec == 8 && moves_f32_rows && codegen_enabled()) widths.push_back(4);
+  for (int vec : widths) {
+  const bool interpretable = c.interpretable && vec == base.vec;
   const uint32_t nvec = base.cols / vec;
   double in_bytes_per_elem = 0, col_bytes_per_elem = 0;
   for (int i = 0; i < base.n_full; ++i) in_bytes_per_elem += dtype_bytes(base.full_dt[i]);
@@ -617,7 +627,7 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
 
   struct Shape { uint32_t L; int K; bool block; bool generated; uint32_t R = 1; uint32_t CT = 1; };
   std::vector<Shape> shapes;
-  if (c.interpretable) {
+  if (interpretable) {
     for (int K : {1, 2, 4}) {
       uint32_t L = 1;
       while (L * (uint32_t)K < nvec) L <<= 1;
@@ -693,6 +703,7 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
     Launch& l = cand.launches.back();
     l.kernel = K_ROW_PROGRAM;
     RowProgP q = base;
+    q.vec = vec;
     q.lanes_per_row = (int32_t)s.L;
     int lg = 0;
     while ((1u << lg) < s.L) ++lg;
@@ -726,6 +737,14 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
 
     KernelCost kc;
     kc.hbm_bytes = (double)bytes_min;
+    if (vec == 8) {
+      // float32 rows under 8-element steps move as two 128-bit accesses 32 bytes apart per lane (measured: about a
+      // quarter more time for those bytes than one access per lane takes)
+      int f32_rows = 0;
+      for (int i = 0; i < base.n_full; ++i) f32_rows += base.full_dt[i] == DT_F32 && !((base.full_bcast >> i) & 1u);
+      for (int i = 0; i < base.n_instr; ++i) f32_rows += base.instr[i].op == PO_STORE && base.instr[i].aux == DT_F32;
+      kc.hbm_bytes += 0.25 * 4.0 * n * f32_rows;
+    }
     kc.cache_bytes = col_bytes_per_elem * n;
     kc.elems = n;
     // per element: the op itself plus operand / result moves; per instruction and wave: ~40 scalar-side cycles of dispatch
@@ -817,6 +836,7 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
     }
     out->push_back(cand);
   }
+  }   // step widths
   return !out->empty();
 }
 
