@@ -261,20 +261,20 @@ int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) {
                                              std::to_string(q.ms[i][2]) : std::string()) +
            (q.acc_input == i ? " acc" : "") + "\n";
     for (int i = 0; i < q.n_col; ++i)
-      s += "  col " + buf_name(l.ptr[4 + i]) + " index " + std::to_string(i) + " " + dtype_name(q.col_dt[i]) + "\n";
+      s += "  col " + buf_name(l.ptr[kSlotCol + i]) + " index " + std::to_string(i) + " " + dtype_name(q.col_dt[i]) + "\n";
     for (int i = 0; i < q.n_rscal; ++i)
-      s += "  rscal " + buf_name(l.ptr[8 + i]) + " sreg " + std::to_string(q.rscal_sreg[i]) + " " + dtype_name(q.rscal_dt[i]) +
+      s += "  rscal " + buf_name(l.ptr[kSlotRscal + i]) + " sreg " + std::to_string(q.rscal_sreg[i]) + " " + dtype_name(q.rscal_dt[i]) +
            (((q.rscal_bcast >> i) & 1u) ? " rowstrides=" + std::to_string(q.rms[i][0]) + "," + std::to_string(q.rms[i][1]) + "," +
                                               std::to_string(q.rms[i][2]) : std::string()) + "\n";
     for (int i = 0; i < kProgMaxOperands; ++i)
-      if (l.ptr[12 + i].kind != BUF_NONE)
-        s += "  output " + std::to_string(i) + " " + buf_name(l.ptr[12 + i]) +
+      if (l.ptr[kSlotOut + i].kind != BUF_NONE)
+        s += "  output " + std::to_string(i) + " " + buf_name(l.ptr[kSlotOut + i]) +
              (((q.out_perm >> i) & 1u) ? " rowstrides=" + std::to_string(q.oms[i][0]) + "," + std::to_string(q.oms[i][1]) + "," +
                                             std::to_string(q.oms[i][2]) : std::string()) + "\n";
     for (int i = 0; i < kProgMaxOperands; ++i)
-      if (l.ptr[16 + i].kind != BUF_NONE) s += "  routput " + std::to_string(i) + " " + buf_name(l.ptr[16 + i]) + "\n";
+      if (l.ptr[kSlotRout + i].kind != BUF_NONE) s += "  routput " + std::to_string(i) + " " + buf_name(l.ptr[kSlotRout + i]) + "\n";
     if (q.n_colsum > 0)   // partial sums: one row of n_colsum * cols floats per workgroup, folded by the next launch
-      s += "  colsums " + std::to_string(q.n_colsum) + " partials " + buf_name(l.ptr[20]) + " rows_per_group " +
+      s += "  colsums " + std::to_string(q.n_colsum) + " partials " + buf_name(l.ptr[kSlotWs]) + " rows_per_group " +
            std::to_string(q.rows_per_group) + " col_tiles " + std::to_string(q.col_tiles > 1 ? q.col_tiles : 1) + "\n";
     static const char* op_names[] = {"add", "sub", "rsub", "mul", "div", "rdiv", "max", "square", "exp", "rsqrt", "tanh", "gelu",
                                      "gelu_grad", "cvt", "load", "rsum", "rmax", "rsumsq", "store", "store_scal", "colsum"};

@@ -593,6 +593,7 @@ struct Compiler {
     for (int t : g.inputs)
       if (val[t].last_read < 0) release(t);   // declared but unread
     if (!walk()) return false;
+    if ((int)full_in.size() > kProgMaxInterpretedFull) interpretable = false;
     p.n_colsum = n_colsum;
     p.rows_per_group = 1;
     p.col_tiles = 1;
@@ -717,10 +718,10 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
       return r;
     };
     for (size_t i = 0; i < c.full_in.size(); ++i) l.ptr[i] = in_ref(c.full_in[i]);
-    for (size_t i = 0; i < c.col_in.size(); ++i) l.ptr[4 + i] = in_ref(c.col_in[i]);
-    for (size_t i = 0; i < c.rscal_in.size(); ++i) l.ptr[8 + i] = in_ref(c.rscal_in[i]);
-    for (int i = 0; i < c.n_out; ++i) { l.ptr[12 + i].kind = BUF_OUTPUT; l.ptr[12 + i].slot = c.out_slot[i]; }
-    for (int i = 0; i < c.n_rout; ++i) { l.ptr[16 + i].kind = BUF_OUTPUT; l.ptr[16 + i].slot = c.rout_slot[i]; }
+    for (size_t i = 0; i < c.col_in.size(); ++i) l.ptr[kSlotCol + i] = in_ref(c.col_in[i]);
+    for (size_t i = 0; i < c.rscal_in.size(); ++i) l.ptr[kSlotRscal + i] = in_ref(c.rscal_in[i]);
+    for (int i = 0; i < c.n_out; ++i) { l.ptr[kSlotOut + i].kind = BUF_OUTPUT; l.ptr[kSlotOut + i].slot = c.out_slot[i]; }
+    for (int i = 0; i < c.n_rout; ++i) { l.ptr[kSlotRout + i].kind = BUF_OUTPUT; l.ptr[kSlotRout + i].slot = c.rout_slot[i]; }
     const uint32_t rows_per_block = (s.block ? 1 : 256 / s.L) * s.R;
     l.shape.block[0] = 256;
     const uint32_t n_row_wgs = (base.rows + rows_per_block - 1) / rows_per_block;
@@ -798,8 +799,8 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
         Launch& ml = cand.launches.back();
         const uint32_t n_wg = n_row_wgs;   // one row of partial sums per row block (its column tiles share the row)
         const uint32_t width = (uint32_t)c.n_colsum * base.cols;
-        ml.ptr[20].kind = BUF_WORKSPACE;
-        ml.ptr[20].offset = 0;
+        ml.ptr[kSlotWs].kind = BUF_WORKSPACE;
+        ml.ptr[kSlotWs].offset = 0;
         ml.shape.lds_bytes = 0;
         cand.info.lds_bytes = slots + (s.block ? 0 : c.n_colsum * 4 * (int32_t)(s.L * kv) * 4);
         cand.launches.emplace_back();

@@ -14,11 +14,11 @@ namespace fsk {
 
 // Pointer block of a generated kernel, one by-value argument (slots as in K_ROW_PROGRAM).
 struct GenArgs {
-  const void* full[4];
-  const void* col[4];
-  const void* rscal[4];
-  void* out[4];
-  void* rout[4];
+  const void* full[8];
+  const void* col[8];
+  const void* rscal[8];
+  void* out[8];
+  void* rout[8];
   void* ws;   // partial column sums, one row per workgroup (patterns with column sums), else null
 };
 

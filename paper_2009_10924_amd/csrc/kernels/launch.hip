@@ -57,11 +57,11 @@ int launch_kernel(int32_t kernel, const KernelArgs& args, const LaunchShape& s, 
     // one by-value argument: pointers by class, then the program
     ProgArgs pa;
     for (int i = 0; i < kProgMaxOperands; ++i) {
-      pa.full[i] = args.p[i];
-      pa.col[i] = args.p[4 + i];
-      pa.rscal[i] = args.p[8 + i];
-      pa.out[i] = args.p[12 + i];
-      pa.rout[i] = args.p[16 + i];
+      pa.full[i] = args.p[kSlotFull + i];
+      pa.col[i] = args.p[kSlotCol + i];
+      pa.rscal[i] = args.p[kSlotRscal + i];
+      pa.out[i] = args.p[kSlotOut + i];
+      pa.rout[i] = args.p[kSlotRout + i];
     }
     pa.p = args.u.prog;
     if (s.lds_bytes > 64u * 1024u) {

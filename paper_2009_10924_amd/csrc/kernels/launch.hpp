@@ -8,8 +8,11 @@
 
 namespace fs {
 
-constexpr int kMaxPtrs = 24;
-constexpr int kGenArgPtrs = 21;   // pointers of a generated kernel: the 20 operand slots of K_ROW_PROGRAM + the workspace
+constexpr int kMaxPtrs = 44;
+// Pointer slots of a row program (interpreted or generated): kProgMaxOperands each of full-shaped inputs, column
+// vectors, per-row scalar inputs, full-shaped outputs, per-row outputs, then the workspace of a generated kernel.
+constexpr int kSlotFull = 0, kSlotCol = 8, kSlotRscal = 16, kSlotOut = 24, kSlotRout = 32, kSlotWs = 40;
+constexpr int kGenArgPtrs = 41;   // pointers of a generated kernel: the operand slots + the workspace
 
 // storage dtypes, numbered like the public fs_dtype
 enum DType : int32_t { DT_F32 = 0, DT_F16 = 1, DT_BF16 = 2, DT_I32 = 3 };
@@ -35,11 +38,11 @@ enum KernelId : int32_t {
   K_TCHAIN_LDS,
   K_ROW_WAVE,          // p0,p1 row inputs, p2,p3 column vectors, p4 out0, p5 out1 : generic row-stitched skeleton
   K_ROW_BLOCK,         // same operands as K_ROW_WAVE, one workgroup per row, reduced values through LDS
-  K_ROW_PROGRAM,       // interpreted row program: p0-3 full inputs, p4-7 column vectors, p8-11 per-row scalar
-                       // inputs, p12-15 full outputs, p16-19 per-row scalar outputs
+  K_ROW_PROGRAM,       // interpreted row program: p0-7 full inputs, p8-15 column vectors, p16-23 per-row scalar
+                       // inputs, p24-31 full outputs, p32-39 per-row scalar outputs (kSlot*)
   K_LAYERNORM_BWD,     // p0 h, p1 dy, p2 gamma, p3 mu, p4 rstd, p5 dx, p6 partials [n_row_blocks, 2, cols]
   K_ROW_GENERATED,     // a kernel generated and compiled for one row pattern at plan time; pointer slots as K_ROW_PROGRAM,
-                       // p20 the workspace for column partial sums (or null).
+                       // p40 the workspace for column partial sums (or null).
                        // Not in the compiled-in table: launched through its own handle (gen_launch)
   K_COUNT
 };
@@ -209,7 +212,8 @@ struct ProgInstr {
   float imm;
 };
 constexpr int kProgMaxInstr = 64;
-constexpr int kProgMaxOperands = 4;     // per class: full inputs, column vectors, per-row inputs, outputs
+constexpr int kProgMaxOperands = 8;     // per class: full inputs, column vectors, per-row inputs, outputs
+constexpr int kProgMaxInterpretedFull = 4;   // full-shaped inputs the interpreter's load batch is built for
 constexpr int kProgMaxColSums = 2;      // what one fold launch hands out
 constexpr int kProgMaxReductions = 8;   // LDS slot sets of the workgroup-per-row form
 constexpr int kProgMaxLdsBytes = 128 * 1024;   // register files of one workgroup (a CU has 160 KB)

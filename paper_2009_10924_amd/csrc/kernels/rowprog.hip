@@ -385,7 +385,7 @@ const void* prog_sym(int K, int n_full) {
 
 const void* rowprog_kernel_symbol(int32_t, const KernelArgs& a) {
   const RowProgP& p = a.u.prog;
-  if (p.n_full < 0 || p.n_full > kProgMaxOperands) return nullptr;
+  if (p.n_full < 0 || p.n_full > kProgMaxInterpretedFull) return nullptr;
   if (p.vec == 4) return prog_sym<4>(p.vecs_per_lane, p.n_full);
   if (p.vec == 8) return prog_sym<8>(p.vecs_per_lane, p.n_full);
   return nullptr;

@@ -106,8 +106,10 @@ def test_plan_structure(name):
 
 
 def test_transformer_block_plan_is_the_hand_partition():
+    """With the compiled-in kernels alone the explorer finds the partition one would write by hand."""
     spec = transformer_block_graph(32, 128, 12, 64, 3072, "bf16")
-    prog = B.Program(B.Graph.from_spec(spec))
+    with B.codegen(False):
+        prog = B.Program(B.Graph.from_spec(spec))
     steps = prog.patterns()
     names = sorted((s["info"]["pattern"], len(s["ops"])) for s in steps)
     assert names == sorted([("transpose", 1)] * 4 + [("softmax", 7), ("layernorm", 12), ("bias_gelu", 2), ("layernorm", 12)])
@@ -115,6 +117,24 @@ def test_transformer_block_plan_is_the_hand_partition():
     # the second LayerNorm reads what the first one stored
     order = [tuple(s["ops"]) for s in steps]
     assert order.index(tuple(range(11, 23))) < order.index(tuple(range(25, 37)))
+
+
+def test_transformer_block_plan_with_generated_kernels_goes_beyond_the_hand_partition():
+    """A generated kernel is not bound to a family's operand list: the two LayerNorm neighbourhoods, the second of
+    which reads what the first stored, become one 24-op pattern (one launch less, one read of the stored tensor less)."""
+    if not B.codegen_available():
+        pytest.skip("needs the run-time compiler")
+    spec = transformer_block_graph(32, 128, 12, 64, 3072, "bf16")
+    g = B.Graph.from_spec(spec)
+    with B.codegen(True):
+        prog = B.Program(g)
+    with B.codegen(False):
+        hand = B.Program(g)
+    steps = prog.patterns()
+    assert prog.info["n_kernels"] < hand.info["n_kernels"] and prog.info["predicted_us"] < hand.info["predicted_us"]
+    big = max(steps, key=lambda s: len(s["ops"]))
+    assert big["info"]["pattern"] == "row_generated" and tuple(big["ops"]) == tuple(range(11, 23)) + tuple(range(25, 37))
+    assert sorted(o for s in steps for o in s["ops"]) == list(range(len(spec.ops)))
 
 
 def test_independent_launch_bound_patterns_share_one_packed_launch():
