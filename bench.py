@@ -228,13 +228,18 @@ def measure_pack(name, steps, warmup):
             c()
 
     t_pack = timed(packed, steps)
+    with B.codegen(False):   # the fixed packed kernel (run-time table of members) beside the generated one
+        fixed_pack = B.Pack([B.Plan(B.Graph.from_spec(s), "auto") for s in specs])
+    fixed = fixed_pack.bind([t.data_ptr() for m in dev_in for t in m], [t.data_ptr() for m in dev_out for t in m], stream)
+    t_fixed = timed(fixed, steps)
     t_sep = timed(all_separate, max(10, steps // 8))
     t_unf = timed(all_unfused, max(5, steps // 32))
     return {"workload": f"{name}: {len(specs)} independent tiny subgraphs (8 softmax f32 [64,128], 8 add+bias+LayerNorm f32->bf16 "
                         "[128,768], 8 softmax backward f16 [384,128], 4 RMSNorm bf16 [64,1024], 4 bias+GELU bf16 [64,3072])",
             "members": len(specs), "bytes_min": pack.info["bytes_min"],
             "packed_us": t_pack, "packed_launches": pack.info["n_kernels"], "packed_grid": pack.info["grid"], "packed_vgprs": pack.info["vgprs"],
-            "packed_GBps": pack.info["bytes_min"] / t_pack / 1e3,
+            "packed_GBps": pack.info["bytes_min"] / t_pack / 1e3, "packed_generated": pack.info["generated"],
+            "fixed_pack_us": t_fixed, "fixed_pack_vgprs": fixed_pack.info["vgprs"],
             "stitched_one_launch_each_us": t_sep, "stitched_launches": sum(p.info["n_kernels"] for p in plans),
             "unfused_us": t_unf, "unfused_launches": sum(p.info["n_kernels"] for p in unfused),
             "speedup_vs_one_launch_each": t_sep / t_pack, "speedup_vs_unfused": t_unf / t_pack,

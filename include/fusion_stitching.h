@@ -240,20 +240,26 @@ typedef struct fs_pack_info {
   int32_t grid, block;          /* workgroups over all launches, threads per workgroup          */
   int32_t vgprs;                /* registers per lane of the packed kernel (0 without a device) */
   int32_t n_inputs, n_outputs;  /* lengths of fs_pack_execute's pointer arrays                  */
-  int32_t reserved;
+  int32_t generated;            /* 1: the pack runs kernels generated for exactly its members   */
   int64_t bytes_min;            /* sum of the members' bytes_min                                */
   double predicted_us;          /* model estimate for one fs_pack_execute                       */
   double predicted_separate_us; /* sum of the members' own predicted_us (one launch each)       */
 } fs_pack_info;
 
 /* Packs plans[0..n) -- independent patterns, none reading another's output -- into
- * one object whose execution runs all of them in ceil(n/32) launches.  A member must
- * be a plan made with a scheme other than FS_SCHEME_UNFUSED whose pattern has a
- * row-stitched packed form: softmax without mask, softmax backward, RMS norm,
- * LayerNorm with affine output (alone, or with residual and bias), bias + GELU; input
- * and output storage of the same dtype (LayerNorm also float32 -> bfloat16); rows of
- * at most 1024 128-bit vectors.  The plans may be destroyed afterwards; the pack keeps
- * what it needs.  `plans` is a HOST array.
+ * one object whose execution runs all of them in ceil(n/32) launches.  Two forms:
+ *   generated (where the run-time compiler is available, see fs_codegen_enable): every
+ *     member is any plan, not made with FS_SCHEME_UNFUSED, whose pattern is row-local
+ *     (what runs as a row program: element-wise ops, broadcasts, last-axis reductions,
+ *     transposes of leading axes; no column sums); one kernel per launch is generated
+ *     with a device function per member;
+ *   fixed (otherwise): one pre-compiled kernel reads a table of members; a member's
+ *     pattern must be softmax without mask, softmax backward, RMS norm, LayerNorm with
+ *     affine output (alone, or with residual and bias) or bias + GELU; input and output
+ *     storage of the same dtype (LayerNorm also float32 -> bfloat16); rows of at most
+ *     1024 128-bit vectors.
+ * The plans may be destroyed afterwards; the pack keeps what it needs.  `plans` is a
+ * HOST array.
  * Errors: FS_ERR_INVALID_ARG, FS_ERR_UNSUPPORTED_PATTERN (names the member),
  * FS_ERR_LOCALITY (a member's row is too long for one workgroup), FS_ERR_SHAPE.      */
 fs_status fs_pack_create(const fs_plan *const *plans, int32_t n, fs_pack **out);

@@ -93,7 +93,7 @@ class fs_plan_info(C.Structure):
 class fs_pack_info(C.Structure):
     _fields_ = [
         ("n_members", C.c_int32), ("n_kernels", C.c_int32), ("grid", C.c_int32), ("block", C.c_int32),
-        ("vgprs", C.c_int32), ("n_inputs", C.c_int32), ("n_outputs", C.c_int32), ("reserved", C.c_int32),
+        ("vgprs", C.c_int32), ("n_inputs", C.c_int32), ("n_outputs", C.c_int32), ("generated", C.c_int32),
         ("bytes_min", C.c_int64), ("predicted_us", C.c_double), ("predicted_separate_us", C.c_double),
     ]
 

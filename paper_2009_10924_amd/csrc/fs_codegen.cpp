@@ -72,31 +72,40 @@ std::string stretched_row(const uint32_t (&ms)[3], const char* pre = "") {
 }  // namespace
 
 namespace {
-std::string body_with_entry(const RowProgP& p, const char* entry);
+// member = false: an extern "C" kernel `entry(const GenArgs a)`.  member = true: a device function
+// `entry(const GenArgs& a, uint32_t fs_block)` that a packed kernel calls for the member's range of workgroups.
+std::string body_with_entry(const RowProgP& p, const char* entry, bool member = false);
 const char kEntryPlaceholder[] = "@ENTRY@";
+uint32_t fnv1a(const std::string& text) {
+  uint32_t h = 2166136261u;
+  for (unsigned char ch : text) h = (h ^ ch) * 16777619u;
+  return h;
+}
 }  // namespace
 
 // The kernel's name carries a hash of its own source (pattern, extents and launch shape), so that kernel traces
 // tell the generated kernels of a process apart.
 std::string generated_kernel_entry(const RowProgP& p) {
-  const std::string body = body_with_entry(p, kEntryPlaceholder);
-  uint32_t h = 2166136261u;   // FNV-1a
-  for (unsigned char ch : body) h = (h ^ ch) * 16777619u;
-  return fmt("fs_gen_row_%08x", h);
+  return fmt("fs_gen_row_%08x", fnv1a(body_with_entry(p, kEntryPlaceholder)));
 }
 
 std::string generate_row_kernel_body(const RowProgP& p) { return body_with_entry(p, generated_kernel_entry(p).c_str()); }
 
 namespace {
-std::string body_with_entry(const RowProgP& p, const char* entry) {
+std::string body_with_entry(const RowProgP& p, const char* entry, bool member) {
   const bool block = p.lanes_per_row > 64;
   int n_reductions = 0;
   for (int i = 0; i < p.n_instr; ++i)
     if (p.instr[i].op == PO_RSUM || p.instr[i].op == PO_RMAX || p.instr[i].op == PO_RSUMSQ) ++n_reductions;
 
   std::string s;
-  s += "using namespace fsk;\n";
-  s += fmt("extern \"C\" __global__ void __launch_bounds__(256) %s(const GenArgs a) {\n", entry);
+  if (member) {
+    s += fmt("static __device__ __forceinline__ void %s(const GenArgs& a, const uint32_t fs_block) {\n", entry);
+  } else {
+    s += "using namespace fsk;\n";
+    s += fmt("extern \"C\" __global__ void __launch_bounds__(256) %s(const GenArgs a) {\n", entry);
+    s += "  const uint32_t fs_block = blockIdx.x;\n";
+  }
   const uint32_t R = p.rows_per_group > 1 ? (uint32_t)p.rows_per_group : 1u;
   const uint32_t CT = p.col_tiles > 1 ? (uint32_t)p.col_tiles : 1u;   // column tiles of cols / CT elements
   s += fmt("  typedef GenRow<%uu, %uu, %d, %d, %uu, %s, %uu, %uu> Row;\n", p.rows, p.cols / CT, p.vec, p.vecs_per_lane,
@@ -166,7 +175,7 @@ std::string body_with_entry(const RowProgP& p, const char* entry) {
     if (needs_lead) s += lead_of("nrow", "n", false);
     s += row_loads("nrow", "n", "", "");
   } else {
-    s += "  const Row row(blockIdx.x);\n";
+    s += "  const Row row(fs_block);\n";
     // ---- every global load is issued before anything waits
     if (needs_lead) s += lead_of("row", "", true);
     s += row_loads("row", "", "const auto ", "const float ");
@@ -251,6 +260,54 @@ std::string body_with_entry(const RowProgP& p, const char* entry) {
   return s;
 }
 }  // namespace
+
+// One kernel over several independent row patterns (kernel packing, Section 4.1, across patterns): every member is
+// a device function made from its own row program; a workgroup finds its member from its index (the members own
+// consecutive ranges of workgroups) and runs it with a virtual workgroup index.  The operand pointers of all members
+// travel in one table in the kernel arguments; `ptr_slots[m]` lists, for member m, the row-program pointer slots
+// (kSlot*) behind its consecutive table entries.
+std::string generate_pack_kernel(const std::vector<RowProgP>& members, const std::vector<uint32_t>& blocks,
+                                 std::vector<std::vector<int>>* ptr_slots, std::string* entry) {
+  std::string body;
+  ptr_slots->assign(members.size(), {});
+  size_t n_ptrs = 0;
+  for (size_t m = 0; m < members.size(); ++m) {
+    const RowProgP& p = members[m];
+    std::vector<int>& slots = (*ptr_slots)[m];
+    for (int i = 0; i < p.n_full; ++i) slots.push_back(kSlotFull + i);
+    for (int i = 0; i < p.n_col; ++i) slots.push_back(kSlotCol + i);
+    for (int i = 0; i < p.n_rscal; ++i) slots.push_back(kSlotRscal + i);
+    for (int i = 0; i < p.n_instr; ++i) {
+      if (p.instr[i].op == PO_STORE) slots.push_back(kSlotOut + p.instr[i].dst);
+      if (p.instr[i].op == PO_STORE_SCAL) slots.push_back(kSlotRout + p.instr[i].dst);
+    }
+    n_ptrs += slots.size();
+    body += body_with_entry(p, fmt("fs_member_%zu", m).c_str(), true);
+  }
+  std::string k;
+  k += fmt("struct PackPtrs { void* p[%zu]; };\n", std::max<size_t>(n_ptrs, 1));
+  k += fmt("extern \"C\" __global__ void __launch_bounds__(256) %s(const PackPtrs t) {\n", kEntryPlaceholder);
+  k += "  const uint32_t b = blockIdx.x;\n";
+  size_t at = 0;
+  uint32_t first = 0;
+  for (size_t m = 0; m < members.size(); ++m) {
+    k += fmt("  if (b < %uu) {\n    GenArgs a{};\n", first + blocks[m]);
+    for (int slot : (*ptr_slots)[m]) {
+      const char* field = slot >= kSlotRout ? "rout" : slot >= kSlotOut ? "out" : slot >= kSlotRscal ? "rscal" : slot >= kSlotCol ? "col" : "full";
+      k += fmt("    a.%s[%d] = t.p[%zu];\n", field, slot % 8, at++);
+    }
+    k += fmt("    fs_member_%zu(a, b - %uu);\n    return;\n  }\n", m, first);
+    first += blocks[m];
+  }
+  k += "}\n";
+  const std::string text = "using namespace fsk;\n" + body + k;
+  *entry = fmt("fs_gen_pack_%08x", fnv1a(text));
+  std::string out = text;
+  out.replace(out.find(kEntryPlaceholder), sizeof kEntryPlaceholder - 1, *entry);
+  return out;
+}
+
+std::string embedded_prelude() { return std::string(kEmbeddedDeviceUtils) + kEmbeddedGenSupport; }
 
 std::string generate_row_kernel(const RowProgP& p) {
   std::string s;

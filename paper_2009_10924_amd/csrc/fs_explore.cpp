@@ -640,7 +640,7 @@ void decide_packs(const fs_graph& g, fs_program* prog, std::vector<int>* pos) {
   std::map<int, std::vector<int>> by_level;
   for (int s = 0; s < ns; ++s) {
     const fs_plan* p = prog->steps[s].plan;
-    if (p->pack.spec >= 0 && p->candidates[p->chosen].info.predicted_us <= tiny_us) by_level[level[s]].push_back(s);
+    if ((p->pack.spec >= 0 || p->generic.valid) && p->candidates[p->chosen].info.predicted_us <= tiny_us) by_level[level[s]].push_back(s);
   }
   for (auto& kv : by_level) {
     if (kv.second.size() < 2) continue;

@@ -101,7 +101,18 @@ struct Candidate {
 
 }  // namespace fs
 
+namespace fs {
+// A plan's pattern as a row program with a launch shape: the form in which it can join a generated packed kernel.
+struct GenericForm {
+  bool valid = false;
+  RowProgP prog;
+  BufRef ptr[kMaxPtrs];
+  uint32_t blocks = 0;
+};
+}  // namespace fs
+
 struct fs_plan {
+  fs::GenericForm generic;
   std::vector<fs::Candidate> candidates;
   int32_t chosen = 0;
   int32_t n_inputs = 0, n_outputs = 0;
@@ -119,6 +130,14 @@ struct fs_pack {
   };
   std::vector<Member> members;
   std::vector<fs::PackTable> tables;   // one per launch, pointers left null
+  // generated form: one kernel per launch, made for exactly these members
+  struct PtrRef { int32_t kind; int32_t index; };   // BUF_INPUT / BUF_OUTPUT, position in fs_pack_execute's arrays
+  struct GenLaunch {
+    std::shared_ptr<fs::GenKernel> kernel;
+    uint32_t blocks = 0;
+    std::vector<PtrRef> ptrs;
+  };
+  std::vector<GenLaunch> generated;    // non-empty: these run instead of `tables`
   fs_pack_info info{};
   int32_t n_inputs = 0, n_outputs = 0;
 };
@@ -138,6 +157,12 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out);
 std::string generate_row_kernel(const RowProgP& p);
 std::string generate_row_kernel_body(const RowProgP& p);
 std::string generated_kernel_entry(const RowProgP& p);   // fs_gen_row_<hash of the source>
+// Source (without the embedded device headers, see embedded_prelude) of one kernel that runs several row programs,
+// member m on workgroups [sum of blocks before m, + blocks[m]); ptr_slots[m]: the members' pointer slots in the
+// order of the kernel's pointer table; *entry: the kernel's name.
+std::string generate_pack_kernel(const std::vector<RowProgP>& members, const std::vector<uint32_t>& blocks,
+                                 std::vector<std::vector<int>>* ptr_slots, std::string* entry);
+std::string embedded_prelude();
 // Process-wide switch: candidates with generated kernels are offered only while it is on (default: on
 // unless the environment says FS_CODEGEN=0) and the run-time compiler is available.
 bool codegen_enabled();

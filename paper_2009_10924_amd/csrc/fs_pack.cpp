@@ -58,6 +58,59 @@ bool shape_member(const PackForm& f, PackEntry* e, uint32_t* blocks) {
   return true;
 }
 
+// The pack as generated kernels, one per 32 members, each made for exactly its members (a device function per
+// member, dispatched on the workgroup index; the operand pointers travel in one table in the kernel arguments).
+// false if some member has no row-program form or a kernel does not compile: the caller then tries the fixed
+// packed kernel.
+bool build_generated_pack(const fs_plan* const* plans, int32_t n, fs_pack* pk) {
+  if (!codegen_enabled()) return false;
+  for (int i = 0; i < n; ++i)
+    if (!plans[i] || !plans[i]->generic.valid) return false;
+  int32_t first_input = 0, first_output = 0;
+  int32_t vgprs = 0;
+  for (int begin = 0; begin < n; begin += kPackMaxMembers) {
+    const int end = std::min(n, begin + kPackMaxMembers);
+    std::vector<RowProgP> progs;
+    std::vector<uint32_t> blocks;
+    uint64_t total = 0;
+    for (int i = begin; i < end; ++i) {
+      progs.push_back(plans[i]->generic.prog);
+      blocks.push_back(plans[i]->generic.blocks);
+      total += plans[i]->generic.blocks;
+    }
+    if (total >= (1ull << 31)) return false;
+    std::vector<std::vector<int>> slots;
+    std::string entry;
+    const std::string source = embedded_prelude() + generate_pack_kernel(progs, blocks, &slots, &entry);
+    fs_pack::GenLaunch gl;
+    std::string log;
+    if (gen_compile(source, entry.c_str(), &gl.kernel, &log) != 0) return false;
+    const GenResources res = gen_resources(gl.kernel.get());
+    if (res.scratch_bytes > 0) return false;
+    if (gen_preload(gl.kernel.get()) != 0) return false;
+    vgprs = std::max(vgprs, res.vgprs);
+    gl.blocks = (uint32_t)total;
+    for (int i = begin; i < end; ++i) {
+      const fs_plan* p = plans[i];
+      for (int slot : slots[i - begin]) {
+        const BufRef& r = p->generic.ptr[slot];
+        fs_pack::PtrRef pr;
+        pr.kind = r.kind;
+        pr.index = (r.kind == BUF_INPUT ? first_input : first_output) + r.slot;
+        if (r.kind != BUF_INPUT && r.kind != BUF_OUTPUT) return false;
+        gl.ptrs.push_back(pr);
+      }
+      first_input += p->n_inputs;
+      first_output += p->n_outputs;
+    }
+    if (gl.ptrs.size() > 480) return false;   // the table travels in 4 KB of kernel arguments
+    pk->info.grid += (int32_t)total;
+    pk->generated.push_back(gl);
+  }
+  pk->info.vgprs = vgprs;
+  return true;
+}
+
 }  // namespace
 }  // namespace fs
 
@@ -73,6 +126,36 @@ fs_status fs_pack_create(const fs_plan* const* plans, int32_t n, fs_pack** out) 
   if (!pk) return fail(FS_ERR_INVALID_ARG, "fs_pack_create: out of host memory");
   double separate_us = 0, body_s = 0;
   int64_t bytes = 0;
+  for (int i = 0; i < n; ++i)
+    if (!plans[i]) { delete pk; return fail(FS_ERR_INVALID_ARG, "fs_pack_create: plan %d is null", i); }
+  if (build_generated_pack(plans, n, pk)) {
+    const DeviceModel& dm = device();
+    for (int i = 0; i < n; ++i) {
+      fs_pack::Member m;
+      m.first_input = pk->n_inputs;
+      m.n_inputs = plans[i]->n_inputs;
+      m.first_output = pk->n_outputs;
+      pk->n_inputs += plans[i]->n_inputs;
+      pk->n_outputs += plans[i]->n_outputs;
+      pk->members.push_back(m);
+      separate_us += plans[i]->candidates[plans[i]->chosen].info.predicted_us;
+      bytes += plans[i]->bytes_min;
+    }
+    body_s = std::max((double)bytes / (dm.hbm_peak_Bps * dm.stream_fraction), dm.mem_latency_s * 2);
+    pk->info.n_members = n;
+    pk->info.n_kernels = (int32_t)pk->generated.size();
+    pk->info.block = 256;
+    pk->info.n_inputs = pk->n_inputs;
+    pk->info.n_outputs = pk->n_outputs;
+    pk->info.bytes_min = bytes;
+    pk->info.predicted_us = (dm.launch_s * pk->info.n_kernels + body_s) * 1e6;
+    pk->info.predicted_separate_us = separate_us;
+    pk->info.generated = 1;
+    *out = pk;
+    return FS_OK;
+  }
+  pk->generated.clear();
+  pk->info = fs_pack_info{};
   auto empty_table = [] {
     PackTable t{};
     for (uint32_t& fb : t.first_block) fb = 0xFFFFFFFFu;
@@ -156,6 +239,17 @@ fs_status fs_pack_execute(const fs_pack* p, const void* const* inputs, void* con
     if (!outputs[i]) return fail(FS_ERR_INVALID_ARG, "fs_pack_execute: output %d is null", i);
     if ((uintptr_t)outputs[i] & 15u) return fail(FS_ERR_ALIGN, "fs_pack_execute: output %d is not 16-byte aligned", i);
   }
+  for (const fs_pack::GenLaunch& gl : p->generated) {
+    void* table[512];
+    for (size_t k = 0; k < gl.ptrs.size(); ++k)
+      table[k] = gl.ptrs[k].kind == BUF_INPUT ? const_cast<void*>(inputs[gl.ptrs[k].index]) : outputs[gl.ptrs[k].index];
+    LaunchShape shape;
+    shape.grid[0] = gl.blocks;
+    shape.block[0] = 256;
+    const int err = gen_launch(gl.kernel.get(), table, sizeof(void*) * std::max<size_t>(gl.ptrs.size(), 1), shape, hip_stream);
+    if (err != 0) return fail(FS_ERR_HIP, "fs_pack_execute: launching the generated packed kernel failed: %s", hip_error_text(err));
+  }
+  if (!p->generated.empty()) return FS_OK;
   size_t m = 0;
   for (const PackTable& tpl : p->tables) {
     PackTable t = tpl;

@@ -68,6 +68,33 @@ bool codegen_enabled() {
   return v != 0 && gen_available();
 }
 
+// The pattern as a row program with a launch shape, for packed launches generated over several plans: the chosen
+// candidate's own program if it runs one, else (a hand-written family) the best generated shape of the same pattern.
+// Patterns with column sums stay out: their fold is a launch of its own.
+static void fill_generic_form(const fs_graph& g, fs_plan* p) {
+  auto take = [&](const Candidate& c) {
+    if (c.launches.size() != 1) return false;
+    const Launch& l = c.launches.front();
+    if ((l.kernel != K_ROW_GENERATED && l.kernel != K_ROW_PROGRAM) || l.args.u.prog.n_colsum > 0) return false;
+    p->generic.valid = true;
+    p->generic.prog = l.args.u.prog;
+    for (int k = 0; k < kMaxPtrs; ++k) p->generic.ptr[k] = l.ptr[k];
+    p->generic.blocks = l.shape.grid[0];
+    return true;
+  };
+  if (take(p->candidates[p->chosen])) return;
+  if (p->candidates[p->chosen].info.scheme == FS_SCHEME_UNFUSED) return;
+  std::vector<Candidate> cands;
+  if (!build_row_program(g, &cands)) return;
+  int best = -1;
+  for (int i = 0; i < (int)cands.size(); ++i) {
+    if (cands[i].launches.size() != 1 || cands[i].launches.front().kernel != K_ROW_GENERATED) continue;
+    predict(&cands[i]);
+    if (best < 0 || cands[i].info.predicted_us < cands[best].info.predicted_us) best = i;
+  }
+  if (best >= 0) take(cands[best]);
+}
+
 fs_status complete_plan(fs_plan* p) {
   const fs_plan_opts& o = p->opts;
   for (;;) {
@@ -181,6 +208,7 @@ fs_status fs::create_plan(const fs_graph* g, int32_t scheme, const fs_plan_opts*
   p->n_outputs = (int32_t)g->outputs.size();
   for (int t : g->inputs) p->input_bytes.push_back(g->tensors[t].numel() * dtype_bytes(g->tensors[t].dtype));
   for (int t : g->outputs) p->output_bytes.push_back(g->tensors[t].numel() * dtype_bytes(g->tensors[t].store_as));
+  if (scheme != FS_SCHEME_UNFUSED && codegen_enabled()) fill_generic_form(*g, p);
   if (complete) {
     const fs_status s = complete_plan(p);
     if (s != FS_OK) {

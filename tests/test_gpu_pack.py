@@ -12,6 +12,17 @@ from workloads.graphs import (add_bias_layernorm_graph, bias_gelu_graph, rmsnorm
 
 pytestmark = pytest.mark.gpu
 
+
+@pytest.fixture(params=["fixed", "generated"], autouse=True)
+def pack_form(request):
+    """Every test runs twice: with the fixed packed kernel (a table of members dispatched at run time) and with
+    kernels generated for exactly the members."""
+    from paper_2009_10924_amd import binding as B
+    if request.param == "generated" and not B.codegen_available():
+        pytest.skip("needs the run-time compiler")
+    with B.codegen(request.param == "generated"):
+        yield request.param
+
 # outputs formed by cancelling sums are judged against max(|ref|, rms(ref))
 RMS_FLOOR = ("add_bias_layernorm", "softmax_backward")
 
@@ -28,6 +39,30 @@ def _check_members(specs, seeds, repeat=2):
     return worst, info
 
 
+def test_pack_of_patterns_outside_the_fixed_forms(pack_form):
+    """Masked softmax, several outputs, folded transposes, patterns of no family, odd row lengths: members of a
+    generated pack only."""
+    from paper_2009_10924_amd import binding as B
+    from workloads import (attention_scores_graph, bias_head_split_graph, layernorm_stats_graph, masked_scores_gate_graph,
+                           random_row_pattern, silu_gate_graph, transposed_softmax_graph)
+    specs = [attention_scores_graph(2, 3, 16, 64), layernorm_stats_graph(30, 96, with_variance=True), bias_head_split_graph(2, 9, 3, 16, "bf16"),
+             silu_gate_graph(9, 50, "f16"), random_row_pattern(5, 20, 64, "f32", n_ops=9), transposed_softmax_graph(2, 7, 3, 32, "f32"),
+             masked_scores_gate_graph(2, 3, 5, 64, dtype="f16"), softmax_graph(5, 8192, "bf16"), random_row_pattern(11, 33, 40, "bf16", n_ops=12)]
+    if pack_form == "fixed":
+        with pytest.raises(B.FsError) as e:
+            _check_members(specs, seeds=range(len(specs)))
+        assert e.value.code == -5
+        return
+    inputs = [make_inputs(s, seed=seed) for seed, s in enumerate(specs)]
+    got, info = run_pack(specs, inputs, repeat=2)
+    assert info["generated"] == 1 and info["n_kernels"] == 1
+    for i, (spec, inp, res) in enumerate(zip(specs, inputs, got)):
+        ref = O.evaluate(spec, inp)
+        for name, dt in spec.outputs:
+            check(res[name], ref[name].reshape(res[name].shape), dt, O.rms(ref[name]), f"member {i} {spec.name}/{name}")
+    note(f"generated pack of {len(specs)} members outside the fixed forms: {info['grid']} workgroups, vgprs {info['vgprs']}")
+
+
 def test_pack_mixed_patterns_dtypes_and_shapes():
     # every packed form, every dtype pair, wave rows (1, 2, 4 vectors per lane), workgroup rows, ragged row counts
     specs = [
@@ -42,7 +77,7 @@ def test_pack_mixed_patterns_dtypes_and_shapes():
     ]
     worst, info = _check_members(specs, seeds=range(len(specs)))
     assert info["n_kernels"] == 1 and info["n_members"] == len(specs)
-    note(f"pack of {len(specs)} mixed members, {info['grid']} workgroups, vgprs {info['vgprs']}: worst error {worst:.3f} of the bar")
+    note(f"pack ({'generated' if info['generated'] else 'fixed'}) of {len(specs)} mixed members, {info['grid']} workgroups, vgprs {info['vgprs']}: worst error {worst:.3f} of the bar")
 
 
 def test_pack_single_member_and_repeated_member():

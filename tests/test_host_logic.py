@@ -209,8 +209,17 @@ def test_pack_creation_and_errors(lib):
     from workloads.graphs import add_bias_layernorm_graph, rmsnorm_graph, softmax_backward_graph
     specs = [softmax_graph(64, 128, "f32"), add_bias_layernorm_graph(100, 768), rmsnorm_graph(50, 4096),
              softmax_backward_graph(77, 256, "f16"), bias_gelu_graph(33, 3072)]
+    before = B.codegen_enable(False)          # the fixed packed kernel and its closed set of member forms
+    try:
+        _fixed_pack_checks(lib, specs)
+    finally:
+        B.codegen_enable(before)
+
+
+def _fixed_pack_checks(lib, specs):
     plans = [B.Plan(B.Graph.from_spec(s), "auto") for s in specs]
     info = B.Pack(plans).info
+    assert info["generated"] == 0
     # 8 rows / workgroup, 4 rows / workgroup, then one workgroup per row (rows longer than 64 lanes x 4 vectors), 8 rows, per row
     assert info["grid"] == 8 + 25 + 50 + 10 + 33 and info["block"] == 256
     assert info["n_members"] == 5 and info["n_kernels"] == 1
@@ -236,3 +245,29 @@ def test_pack_creation_and_errors(lib):
     assert lib.fs_pack_query(None, None) == -1
     assert lib.fs_pack_execute(None, None, None, None) == -1
     lib.fs_pack_destroy(None)
+
+
+def test_generated_pack_takes_any_row_local_member(lib):
+    """With the run-time compiler a pack is a kernel generated for exactly its members: masked softmax, patterns with
+    several outputs, folded transposes and patterns of no family at all can join; column reductions and per-op plans
+    cannot."""
+    if not B.codegen_available():
+        pytest.skip("needs the run-time compiler")
+    from workloads import bias_head_split_graph, layernorm_stats_graph, random_row_pattern, silu_gate_graph
+    from workloads.graphs import add_bias_layernorm_graph
+    specs = [softmax_graph(64, 128, "f32"), attention_scores_graph(2, 2, 16, 64), layernorm_stats_graph(30, 96, with_variance=True),
+             bias_head_split_graph(2, 5, 3, 16, "bf16"), silu_gate_graph(9, 50, "f16"), random_row_pattern(5, 20, 64, "f32", n_ops=9),
+             add_bias_layernorm_graph(100, 768)]
+    plans = [B.Plan(B.Graph.from_spec(s), "auto") for s in specs]
+    pack = B.Pack(plans)
+    info = pack.info
+    assert info["generated"] == 1 and info["n_kernels"] == 1 and info["n_members"] == len(specs)
+    assert info["n_inputs"] == sum(len(s.inputs) for s in specs) and info["n_outputs"] == sum(len(s.outputs) for s in specs)
+    assert info["grid"] >= len(specs) and 0 < info["vgprs"] <= 256
+    assert B.Pack([plans[0]] * 33).info["n_kernels"] == 2
+    with pytest.raises(B.FsError) as e:       # a column reduction needs a fold launch of its own
+        B.Pack([plans[0], B.Plan(B.Graph.from_spec(bias_gelu_dbias_graph(100, 520)), "auto")])
+    assert e.value.code == -5
+    with pytest.raises(B.FsError) as e:       # per-op plans carry no pattern
+        B.Pack([B.Plan(B.Graph.from_spec(softmax_graph(8, 64)), "unfused")])
+    assert e.value.code == -5
