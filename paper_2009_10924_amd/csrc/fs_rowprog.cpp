@@ -602,31 +602,62 @@ struct Compiler {
   }
 };
 
-}  // namespace
+// ---- launch shapes and candidates ------------------------------------------------------------------------
 
-bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
-  Compiler c(g);
-  if (!c.run()) return false;
-  const RowProgP& base = c.p;
-  // Step widths to offer.  A pattern whose 16-bit vector inputs ask for 8 elements per step may also move float32
-  // rows (an input, or an output stored as float32): those take two 128-bit accesses per step, 32 bytes apart per
-  // lane, which the memory system likes less than one; 4 elements per step turns that around (float32 in one
-  // access, the 16-bit operands in 64-bit ones).  Both are offered then, the narrower one as generated kernels.
+// How a row program is laid over the device: L lanes of a wavefront (or the whole 256-thread workgroup) per row, K
+// steps of `vec` elements per lane; generated kernels with column sums also R rows per lane group, one after the
+// other, and CT column tiles.
+struct Shape {
+  uint32_t L;
+  int K;
+  bool block;
+  bool generated;
+  uint32_t R = 1, CT = 1;
+};
+
+// Step widths to offer.  A pattern whose 16-bit vector inputs ask for 8 elements per step may also move float32
+// rows (an input, or an output stored as float32): those take two 128-bit accesses per step, 32 bytes apart per
+// lane, which the memory system likes less than one; 4 elements per step turns that around (float32 in one
+// access, the 16-bit operands in 64-bit ones).  Both are offered then, the narrower one as generated kernels.
+std::vector<int> step_widths(const RowProgP& base) {
   bool moves_f32_rows = false;
   for (int i = 0; i < base.n_full; ++i) moves_f32_rows = moves_f32_rows || base.full_dt[i] == DT_F32;
   for (int i = 0; i < base.n_instr; ++i) moves_f32_rows = moves_f32_rows || (base.instr[i].op == PO_STORE && base.instr[i].aux == DT_F32);
   std::vector<int> widths(1, base.vec);
   if (base.vec == 8 && moves_f32_rows && codegen_enabled()) widths.push_back(4);
-  for (int vec : widths) {
-  const bool interpretable = c.interpretable && vec == base.vec;
-  const uint32_t nvec = base.cols / vec;
-  double in_bytes_per_elem = 0, col_bytes_per_elem = 0;
-  for (int i = 0; i < base.n_full; ++i) in_bytes_per_elem += dtype_bytes(base.full_dt[i]);
-  for (int i = 0; i < base.n_col; ++i) col_bytes_per_elem += dtype_bytes(base.col_dt[i]);
-  const double n = (double)base.rows * base.cols;
-  const int64_t bytes_min = graph_bytes_min(g);
+  return widths;
+}
 
-  struct Shape { uint32_t L; int K; bool block; bool generated; uint32_t R = 1; uint32_t CT = 1; };
+// Column sums: a workgroup's lane groups work through R rows each and leave one row of partial sums, so R trades
+// extra traffic (2 x workgroups x columns x 4 bytes) against workgroups to fill the chip with.  Every generated
+// shape is offered with R = 1, 2, 4, ... while at least one workgroup per compute unit remains.
+std::vector<Shape> with_rows_per_group(const std::vector<Shape>& shapes, uint32_t rows) {
+  std::vector<Shape> out;
+  for (const Shape& sh : shapes) {
+    if (!sh.generated) continue;
+    const uint32_t rows_per_wg = sh.block ? 1 : 256 / sh.L;
+    auto workgroups = [&](uint32_t R) { return (rows + (uint64_t)rows_per_wg * R - 1) / ((uint64_t)rows_per_wg * R) * sh.CT; };
+    std::vector<uint32_t> offered;
+    bool some_moderate = false;
+    for (uint32_t R : {1u, 2u, 4u, 8u, 16u, 32u, 64u}) {
+      if (R > 1 && workgroups(R) < 256) break;
+      offered.push_back(R);
+      some_moderate = some_moderate || workgroups(R) <= 8192;
+    }
+    for (uint32_t R : offered) {
+      // thousands of workgroups more than the chip holds only multiply the partial sums: not offered when a
+      // larger R brings the count down
+      if (some_moderate && workgroups(R) > 8192) continue;
+      Shape t = sh;
+      t.R = R;
+      out.push_back(t);
+    }
+  }
+  return out;
+}
+
+std::vector<Shape> enumerate_shapes(const Compiler& c, int vec, bool interpretable) {
+  const uint32_t nvec = c.p.cols / vec;
   std::vector<Shape> shapes;
   if (interpretable) {
     for (int K : {1, 2, 4}) {
@@ -638,206 +669,220 @@ bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
       for (int K : {1, 2, 4})
         if (256ull * K >= nvec && 64ull * K < nvec) shapes.push_back({256, K, true, false});   // rows a wavefront cannot hold at this K
   }
-  if (codegen_enabled()) {
-    // generated kernels (listed after the interpreted ones, whose indices stay): any number of steps per lane up to
-    // 8 (32 single-element steps), so a row can fill its lanes exactly (768 floats: 32 lanes x 6 vectors)
-    const uint32_t max_k = vec == 1 ? 32 : 8;
-    for (uint32_t L = 1; L <= 64; L <<= 1) {
-      const uint32_t K = (nvec + L - 1) / L;
-      if (K >= 1 && K <= max_k && (L == 1 || (uint64_t)(L / 2) * K < nvec)) shapes.push_back({L, (int)K, false, true});
-    }
-    const uint32_t KB = (nvec + 255) / 256;
-    if (KB <= max_k && 64ull * 2 < nvec) shapes.push_back({256, (int)KB, true, true});   // long rows: a workgroup per row
-    if (c.n_colsum > 0) {
-      // Column sums: a workgroup's lane groups work through R rows each and leave one row of partial sums, so R trades
-      // extra traffic (2 x workgroups x columns x 4 bytes) against workgroups to fill the chip with.
-      // Without row reductions nothing ties the columns of a row together: a workgroup may take one tile of 64 or 128
-      // vectors, so a lane keeps one or two vectors per value whatever the row length.
-      if (c.n_reductions == 0 && c.n_rout == 0)
-        for (int K : {1, 2}) {
-          const uint32_t tile_vecs = 64u * K;
-          if (nvec % tile_vecs == 0 && nvec / tile_vecs > 1 && nvec / tile_vecs <= 4096) {
-            Shape t{64, K, false, true};
-            t.CT = nvec / tile_vecs;
-            shapes.push_back(t);
-          }
-        }
-      std::vector<Shape> with_r;
-      for (const Shape& sh : shapes) {
-        if (!sh.generated) continue;
-        const uint32_t rows_per_wg = sh.block ? 1 : 256 / sh.L;
-        std::vector<Shape> of_shape;
-        bool some_moderate = false;
-        for (uint32_t R : {1u, 2u, 4u, 8u, 16u, 32u, 64u}) {
-          const uint64_t n_wg = (base.rows + (uint64_t)rows_per_wg * R - 1) / ((uint64_t)rows_per_wg * R) * sh.CT;
-          if (R > 1 && n_wg < 256) break;    // one workgroup per compute unit at the least
-          Shape t = sh;
-          t.R = R;
-          of_shape.push_back(t);
-          some_moderate = some_moderate || n_wg <= 8192;
-        }
-        for (const Shape& t : of_shape) {
-          // thousands of workgroups more than the chip holds only multiply the partial sums: not offered when a
-          // larger R brings the count down
-          const uint64_t n_wg = (base.rows + (uint64_t)rows_per_wg * t.R - 1) / ((uint64_t)rows_per_wg * t.R) * sh.CT;
-          if (some_moderate && n_wg > 8192) continue;
-          with_r.push_back(t);
-        }
+  if (!codegen_enabled()) return shapes;
+  // generated kernels (listed after the interpreted ones, whose indices stay): any number of steps per lane up to
+  // 8 (32 single-element steps), so a row can fill its lanes exactly (768 floats: 32 lanes x 6 vectors)
+  const uint32_t max_k = vec == 1 ? 32 : 8;
+  for (uint32_t L = 1; L <= 64; L <<= 1) {
+    const uint32_t K = (nvec + L - 1) / L;
+    if (K >= 1 && K <= max_k && (L == 1 || (uint64_t)(L / 2) * K < nvec)) shapes.push_back({L, (int)K, false, true});
+  }
+  const uint32_t KB = (nvec + 255) / 256;
+  if (KB <= max_k && 64ull * 2 < nvec) shapes.push_back({256, (int)KB, true, true});   // long rows: a workgroup per row
+  if (c.n_colsum == 0) return shapes;
+  // Without row reductions nothing ties the columns of a row together: a workgroup may take one tile of 64 or 128
+  // vectors, so a lane keeps one or two vectors per value whatever the row length.
+  if (c.n_reductions == 0 && c.n_rout == 0)
+    for (int K : {1, 2}) {
+      const uint32_t tile_vecs = 64u * K;
+      if (nvec % tile_vecs == 0 && nvec / tile_vecs > 1 && nvec / tile_vecs <= 4096) {
+        Shape t{64, K, false, true};
+        t.CT = nvec / tile_vecs;
+        shapes.push_back(t);
       }
-      shapes.swap(with_r);
+    }
+  return with_rows_per_group(shapes, c.p.rows);
+}
+
+// The launch of the program in shape `s` (interpreted form), with its buffer bindings.
+void fill_launch(const fs_graph& g, const Compiler& c, int vec, const Shape& s, int64_t lds, Launch* l) {
+  l->kernel = K_ROW_PROGRAM;
+  RowProgP q = c.p;
+  q.vec = vec;
+  q.lanes_per_row = (int32_t)s.L;
+  int lg = 0;
+  while ((1u << lg) < s.L) ++lg;
+  q.lanes_log2 = lg;
+  q.vecs_per_lane = s.K;
+  q.rows_per_group = (int32_t)s.R;
+  q.col_tiles = (int32_t)s.CT;
+  l->args.u.prog = q;
+  auto in_ref = [&](int32_t t) {   // a transposed view binds the buffer of the input it views
+    BufRef r;
+    r.kind = BUF_INPUT;
+    r.slot = g.tensors[c.view_src[t] >= 0 ? c.view_src[t] : t].input_slot;
+    return r;
+  };
+  for (size_t i = 0; i < c.full_in.size(); ++i) l->ptr[kSlotFull + i] = in_ref(c.full_in[i]);
+  for (size_t i = 0; i < c.col_in.size(); ++i) l->ptr[kSlotCol + i] = in_ref(c.col_in[i]);
+  for (size_t i = 0; i < c.rscal_in.size(); ++i) l->ptr[kSlotRscal + i] = in_ref(c.rscal_in[i]);
+  for (int i = 0; i < c.n_out; ++i) { l->ptr[kSlotOut + i].kind = BUF_OUTPUT; l->ptr[kSlotOut + i].slot = c.out_slot[i]; }
+  for (int i = 0; i < c.n_rout; ++i) { l->ptr[kSlotRout + i].kind = BUF_OUTPUT; l->ptr[kSlotRout + i].slot = c.rout_slot[i]; }
+  const uint32_t rows_per_block = (s.block ? 1 : 256 / s.L) * s.R;
+  l->shape.block[0] = 256;
+  l->shape.grid[0] = (c.p.rows + rows_per_block - 1) / rows_per_block * s.CT;
+  l->shape.lds_bytes = (uint32_t)lds;
+}
+
+// What the interpreter does per element and per wavefront in shape `s`.
+KernelCost interpreted_cost(const Compiler& c, int vec, const Shape& s, int64_t lds, int64_t bytes_min, uint32_t grid) {
+  const RowProgP& base = c.p;
+  const int kv = s.K * vec;
+  const uint32_t nvec = base.cols / vec;
+  const double n = (double)base.rows * base.cols;
+  double in_bytes_per_elem = 0, col_bytes_per_elem = 0, narrowest = 4.0;
+  for (int i = 0; i < base.n_full; ++i) {
+    in_bytes_per_elem += dtype_bytes(base.full_dt[i]);
+    narrowest = std::min(narrowest, (double)dtype_bytes(base.full_dt[i]));
+  }
+  for (int i = 0; i < base.n_col; ++i) col_bytes_per_elem += dtype_bytes(base.col_dt[i]);
+  KernelCost kc;
+  kc.hbm_bytes = (double)bytes_min;
+  if (vec == 8) {
+    // float32 rows under 8-element steps move as two 128-bit accesses 32 bytes apart per lane (measured: about a
+    // quarter more time for those bytes than one access per lane takes)
+    int f32_rows = 0;
+    for (int i = 0; i < base.n_full; ++i) f32_rows += base.full_dt[i] == DT_F32 && !((base.full_bcast >> i) & 1u);
+    for (int i = 0; i < base.n_instr; ++i) f32_rows += base.instr[i].op == PO_STORE && base.instr[i].aux == DT_F32;
+    kc.hbm_bytes += 0.25 * 4.0 * n * f32_rows;
+  }
+  kc.cache_bytes = col_bytes_per_elem * n;
+  kc.elems = n;
+  // per element: the op itself plus operand / result moves; per instruction and wave: ~40 scalar-side cycles of dispatch
+  const double dispatch = 40.0 * base.n_instr / (64.0 * kv) / 4.0;
+  kc.valu_per_elem = 2.5 * c.vec_instr + dispatch + 2.0 * base.n_full;
+  kc.trans_per_elem = c.trans;
+  kc.lds_traffic_bytes = n * 4.0 * (c.reg_reads + c.reg_writes + base.n_full);
+  kc.waves = (double)grid * 4;
+  kc.waves_per_block = 4;
+  kc.bytes_in_flight_per_lane = (vec == 1 ? (double)in_bytes_per_elem : std::max(16.0, (double)vec * in_bytes_per_elem)) * s.K;
+  kc.vgpr_estimate = 40 + 3 * kv + 4 * s.K * (base.n_full <= 1 ? 1 : (base.n_full <= 2 ? 2 : 4));
+  int steps = 0;
+  for (uint32_t t = 1; t < std::min<uint32_t>(s.L, 64); t <<= 1) ++steps;
+  kc.xlane_steps = steps * c.n_reductions;
+  kc.barriers = s.block ? c.n_reductions : 0;
+  kc.lds_bytes_per_block = (int32_t)lds;
+  kc.lane_utilisation = (double)(nvec / s.CT) / ((double)s.L * s.K);
+  // contiguous bytes the lanes of one row touch per access of the narrowest input
+  const double run = (double)std::min<uint32_t>(s.L, 64) * vec * narrowest;
+  kc.access_run_bytes = run >= 128.0 ? 0.0 : run;
+  kc.preamble_instr = 60;
+  return kc;
+}
+
+// Turns an interpreted candidate into the generated one of the same shape: the same program as straight-line
+// code of its own, every value in registers, no dispatch, no LDS files.
+void make_generated(const Compiler& c, int vec, const Shape& s, Candidate* cand) {
+  const RowProgP& base = c.p;
+  const int kv = s.K * vec;
+  Launch& gl = cand->launches.back();
+  gl.kernel = K_ROW_GENERATED;
+  gl.shape.lds_bytes = 0;
+  const int32_t slots = s.block ? 16 * c.n_reductions : 0;
+  cand->info.lds_bytes = slots;
+  snprintf(cand->info.pattern, sizeof cand->info.pattern, "row_generated");
+  snprintf(cand->info.kernel, sizeof cand->info.kernel, "row_generated<v%d,K%d,L%u,I%d,R%d>", vec, s.K, s.L, base.n_instr, base.n_regs);
+  KernelCost& gc = cand->cost;
+  gc.valu_per_elem = 1.0 * c.vec_instr + 1.0 * base.n_full + 1.0 * c.n_out;
+  gc.lds_traffic_bytes = 0;
+  gc.lds_bytes_per_block = slots;
+  gc.vgpr_estimate = 24 + kv * (base.n_regs + 1 + (base.n_col > 0 ? 1 : 0)) + 2 * s.K * base.n_full;
+  gc.preamble_instr = 40;
+  // a lane's own instruction stream between its loads landing and its stores leaving: the first and the last
+  // wavefronts of the launch run it with the memory system idle, so long per-lane chains (many vectors per
+  // lane) cost time that more, shorter wavefronts would have overlapped
+  const DeviceModel& d = device();
+  gc.serial_tail_s = 1.5 * kv * (gc.valu_per_elem * d.cycles_valu + gc.trans_per_elem * d.cycles_trans) / d.clock_hz;
+}
+
+// Column sums of a generated candidate: partial sums of every workgroup through the workspace, folded by a second
+// launch (one hand-off through device memory: the GLOBAL scheme).
+void add_column_sums(const Compiler& c, int vec, const Shape& s, int64_t bytes_min, Candidate* cand) {
+  const RowProgP& base = c.p;
+  const int kv = s.K * vec;
+  const DeviceModel& d = device();
+  Launch& ml = cand->launches.back();
+  const uint32_t n_wg = ml.shape.grid[0] / s.CT;   // one row of partial sums per row block (its column tiles share the row)
+  const uint32_t width = (uint32_t)c.n_colsum * base.cols;
+  ml.ptr[kSlotWs].kind = BUF_WORKSPACE;
+  ml.ptr[kSlotWs].offset = 0;
+  cand->info.lds_bytes += s.block ? 0 : c.n_colsum * 4 * (int32_t)(s.L * kv) * 4;
+  cand->launches.emplace_back();
+  Launch& f = cand->launches.back();
+  make_fold_launch(&f, n_wg, width, base.cols);
+  f.ptr[0].kind = BUF_WORKSPACE;
+  f.ptr[0].offset = 0;
+  f.ptr[1].kind = BUF_OUTPUT;
+  f.ptr[1].slot = c.colsum_slot[0];
+  if (c.n_colsum > 1) { f.ptr[2].kind = BUF_OUTPUT; f.ptr[2].slot = c.colsum_slot[1]; }
+  cand->info.scheme = FS_SCHEME_GLOBAL;
+  cand->info.n_kernels = 2;
+  cand->info.workspace_bytes = (int64_t)n_wg * width * 4;
+  cand->info.bytes_moved_model = bytes_min + 2 * cand->info.workspace_bytes;
+  if (s.CT > 1)
+    snprintf(cand->info.kernel, sizeof cand->info.kernel, "row_generated<v%d,K%d,L%u,I%d,R%d,rows%u,tiles%u>+colfold", vec, s.K, s.L,
+             base.n_instr, base.n_regs, s.R, s.CT);
+  else
+    snprintf(cand->info.kernel, sizeof cand->info.kernel, "row_generated<v%d,K%d,L%u,I%d,R%d,rows%u>+colfold", vec, s.K, s.L, base.n_instr,
+             base.n_regs, s.R);
+  KernelCost& gc = cand->cost;
+  gc.hbm_bytes += 2.0 * (double)cand->info.workspace_bytes;
+  gc.vgpr_estimate += kv * c.n_colsum;
+  gc.rows_per_wave_loop = s.R;
+  if (s.R > 1) {   // software-pipelined: only the first row's load latency is exposed
+    gc.dep_phases = 0;
+    gc.serial_tail_s += d.mem_latency_s;
+    gc.bytes_in_flight_per_lane *= 2.0;   // this row's and the next row's loads
+  }
+  gc.lds_bytes_per_block = cand->info.lds_bytes;
+  gc.barriers = 1;
+  gc.serial_tail_s += d.mem_latency_s + 0.5 * d.launch_s + d.mem_latency_s * std::ceil(n_wg / 64.0 / 8.0) * 0.5;
+}
+
+// One candidate: the program in shape `s`, interpreted or generated.  false: the shape does not fit (the
+// interpreter's register files beyond its LDS budget, a generated kernel beyond the register file).
+bool make_candidate(const fs_graph& g, const Compiler& c, int vec, const Shape& s, int64_t bytes_min, Candidate* cand) {
+  const RowProgP& base = c.p;
+  const int kv = s.K * vec;
+  const int64_t lds = (int64_t)base.n_regs * kv * 4 * 256 + (int64_t)base.n_col * base.cols * 4 + (int64_t)base.n_sregs * 1024 +
+                      kProgMaxReductions * 16;
+  if (!s.generated && lds > kProgMaxLdsBytes) return false;
+  memset(&cand->info, 0, sizeof cand->info);
+  cand->info.scheme = s.block ? FS_SCHEME_LDS : (s.L == 1 ? FS_SCHEME_LOCAL : FS_SCHEME_WAVE);
+  cand->info.n_kernels = 1;
+  cand->info.bytes_min = bytes_min;
+  cand->info.bytes_moved_model = bytes_min;
+  snprintf(cand->info.pattern, sizeof cand->info.pattern, "row_program");
+  cand->launches.emplace_back();
+  Launch& l = cand->launches.back();
+  fill_launch(g, c, vec, s, lds, &l);
+  cand->info.lanes_per_row = (int32_t)s.L;
+  cand->info.vecs_per_lane = s.K;
+  cand->info.rows_per_block = (int32_t)((s.block ? 1 : 256 / s.L) * s.R);
+  cand->info.lds_bytes = (int32_t)lds;
+  for (int k = 0; k < 3; ++k) { cand->info.block[k] = (int32_t)l.shape.block[k]; cand->info.grid[k] = (int32_t)l.shape.grid[k]; }
+  snprintf(cand->info.kernel, sizeof cand->info.kernel, "row_program<v%d,K%d,L%u,I%d,R%d>", vec, s.K, s.L, base.n_instr, base.n_regs);
+  cand->cost = interpreted_cost(c, vec, s, lds, bytes_min, l.shape.grid[0]);
+  cand->fallback = !s.generated && codegen_enabled();
+  if (!s.generated) return true;
+  make_generated(c, vec, s, cand);
+  if (c.n_colsum > 0) add_column_sums(c, vec, s, bytes_min, cand);
+  return cand->cost.vgpr_estimate <= 256;   // more would not fit the register file without spilling
+}
+
+}  // namespace
+
+bool build_row_program(const fs_graph& g, std::vector<Candidate>* out) {
+  Compiler c(g);
+  if (!c.run()) return false;
+  const int64_t bytes_min = graph_bytes_min(g);
+  for (int vec : step_widths(c.p)) {
+    const bool interpretable = c.interpretable && vec == c.p.vec;
+    for (const Shape& s : enumerate_shapes(c, vec, interpretable)) {
+      Candidate cand;
+      if (make_candidate(g, c, vec, s, bytes_min, &cand)) out->push_back(cand);
     }
   }
-
-  for (const Shape& s : shapes) {
-    const int kv = s.K * vec;
-    const int64_t lds = (int64_t)base.n_regs * kv * 4 * 256 + (int64_t)base.n_col * base.cols * 4 +
-                        (int64_t)base.n_sregs * 1024 + kProgMaxReductions * 16;
-    if (!s.generated && lds > kProgMaxLdsBytes) continue;
-    Candidate cand;
-    memset(&cand.info, 0, sizeof cand.info);
-    cand.info.scheme = s.block ? FS_SCHEME_LDS : (s.L == 1 ? FS_SCHEME_LOCAL : FS_SCHEME_WAVE);
-    cand.info.n_kernels = 1;
-    cand.info.bytes_min = bytes_min;
-    cand.info.bytes_moved_model = bytes_min;
-    snprintf(cand.info.pattern, sizeof cand.info.pattern, "row_program");
-    cand.launches.emplace_back();
-    Launch& l = cand.launches.back();
-    l.kernel = K_ROW_PROGRAM;
-    RowProgP q = base;
-    q.vec = vec;
-    q.lanes_per_row = (int32_t)s.L;
-    int lg = 0;
-    while ((1u << lg) < s.L) ++lg;
-    q.lanes_log2 = lg;
-    q.vecs_per_lane = s.K;
-    l.args.u.prog = q;
-    auto in_ref = [&](int32_t t) {   // a transposed view binds the buffer of the input it views
-      BufRef r;
-      r.kind = BUF_INPUT;
-      r.slot = g.tensors[c.view_src[t] >= 0 ? c.view_src[t] : t].input_slot;
-      return r;
-    };
-    for (size_t i = 0; i < c.full_in.size(); ++i) l.ptr[i] = in_ref(c.full_in[i]);
-    for (size_t i = 0; i < c.col_in.size(); ++i) l.ptr[kSlotCol + i] = in_ref(c.col_in[i]);
-    for (size_t i = 0; i < c.rscal_in.size(); ++i) l.ptr[kSlotRscal + i] = in_ref(c.rscal_in[i]);
-    for (int i = 0; i < c.n_out; ++i) { l.ptr[kSlotOut + i].kind = BUF_OUTPUT; l.ptr[kSlotOut + i].slot = c.out_slot[i]; }
-    for (int i = 0; i < c.n_rout; ++i) { l.ptr[kSlotRout + i].kind = BUF_OUTPUT; l.ptr[kSlotRout + i].slot = c.rout_slot[i]; }
-    const uint32_t rows_per_block = (s.block ? 1 : 256 / s.L) * s.R;
-    l.shape.block[0] = 256;
-    const uint32_t n_row_wgs = (base.rows + rows_per_block - 1) / rows_per_block;
-    l.shape.grid[0] = n_row_wgs * s.CT;
-    l.args.u.prog.rows_per_group = (int32_t)s.R;
-    l.args.u.prog.col_tiles = (int32_t)s.CT;
-    l.shape.lds_bytes = (uint32_t)lds;
-    cand.info.lanes_per_row = (int32_t)s.L;
-    cand.info.vecs_per_lane = s.K;
-    cand.info.rows_per_block = (int32_t)rows_per_block;
-    cand.info.lds_bytes = (int32_t)lds;
-    for (int k = 0; k < 3; ++k) { cand.info.block[k] = (int32_t)l.shape.block[k]; cand.info.grid[k] = (int32_t)l.shape.grid[k]; }
-    snprintf(cand.info.kernel, sizeof cand.info.kernel, "row_program<v%d,K%d,L%u,I%d,R%d>", vec, s.K, s.L, base.n_instr, base.n_regs);
-
-    KernelCost kc;
-    kc.hbm_bytes = (double)bytes_min;
-    if (vec == 8) {
-      // float32 rows under 8-element steps move as two 128-bit accesses 32 bytes apart per lane (measured: about a
-      // quarter more time for those bytes than one access per lane takes)
-      int f32_rows = 0;
-      for (int i = 0; i < base.n_full; ++i) f32_rows += base.full_dt[i] == DT_F32 && !((base.full_bcast >> i) & 1u);
-      for (int i = 0; i < base.n_instr; ++i) f32_rows += base.instr[i].op == PO_STORE && base.instr[i].aux == DT_F32;
-      kc.hbm_bytes += 0.25 * 4.0 * n * f32_rows;
-    }
-    kc.cache_bytes = col_bytes_per_elem * n;
-    kc.elems = n;
-    // per element: the op itself plus operand / result moves; per instruction and wave: ~40 scalar-side cycles of dispatch
-    const double dispatch = 40.0 * base.n_instr / (64.0 * kv) / 4.0;
-    kc.valu_per_elem = 2.5 * c.vec_instr + dispatch + 2.0 * base.n_full;
-    kc.trans_per_elem = c.trans;
-    kc.lds_traffic_bytes = n * 4.0 * (c.reg_reads + c.reg_writes + base.n_full);
-    kc.waves = (double)l.shape.grid[0] * 4;
-    kc.waves_per_block = 4;
-    kc.bytes_in_flight_per_lane = (vec == 1 ? (double)in_bytes_per_elem : std::max(16.0, (double)vec * in_bytes_per_elem)) * s.K;
-    kc.vgpr_estimate = 40 + 3 * kv + 4 * s.K * (base.n_full <= 1 ? 1 : (base.n_full <= 2 ? 2 : 4));
-    int steps = 0;
-    for (uint32_t t = 1; t < std::min<uint32_t>(s.L, 64); t <<= 1) ++steps;
-    kc.xlane_steps = steps * c.n_reductions;
-    kc.barriers = s.block ? c.n_reductions : 0;
-    kc.lds_bytes_per_block = (int32_t)lds;
-    kc.lane_utilisation = (double)(nvec / s.CT) / ((double)s.L * s.K);
-    {
-      // contiguous bytes the lanes of one row touch per access of the narrowest input
-      double narrowest = 4.0;
-      for (int i = 0; i < base.n_full; ++i) narrowest = std::min(narrowest, (double)dtype_bytes(base.full_dt[i]));
-      const double run = (double)std::min<uint32_t>(s.L, 64) * vec * narrowest;
-      kc.access_run_bytes = run >= 128.0 ? 0.0 : run;
-    }
-    kc.preamble_instr = 60;
-    cand.cost = kc;
-    cand.fallback = !s.generated && codegen_enabled();
-    if (s.generated) {
-      // the same program as straight-line code of its own: every value in registers, no dispatch, no LDS files
-      Launch& gl = cand.launches.back();
-      gl.kernel = K_ROW_GENERATED;
-      gl.shape.lds_bytes = 0;
-      const int32_t slots = s.block ? 16 * c.n_reductions : 0;
-      cand.info.lds_bytes = slots;
-      snprintf(cand.info.pattern, sizeof cand.info.pattern, "row_generated");
-      snprintf(cand.info.kernel, sizeof cand.info.kernel, "row_generated<v%d,K%d,L%u,I%d,R%d>", vec, s.K, s.L, base.n_instr, base.n_regs);
-      KernelCost& gc = cand.cost;
-      gc.valu_per_elem = 1.0 * c.vec_instr + 1.0 * base.n_full + 1.0 * c.n_out;
-      gc.lds_traffic_bytes = 0;
-      gc.lds_bytes_per_block = slots;
-      gc.vgpr_estimate = 24 + kv * (base.n_regs + 1 + (base.n_col > 0 ? 1 : 0)) + 2 * s.K * base.n_full;
-      gc.preamble_instr = 40;
-      // a lane's own instruction stream between its loads landing and its stores leaving: the first and the last
-      // wavefronts of the launch run it with the memory system idle, so long per-lane chains (many vectors per
-      // lane) cost time that more, shorter wavefronts would have overlapped
-      const DeviceModel& d = device();
-      gc.serial_tail_s = 1.5 * kv * (gc.valu_per_elem * d.cycles_valu + gc.trans_per_elem * d.cycles_trans) / d.clock_hz;
-      if (c.n_colsum > 0) {
-        // partial sums of every workgroup through the workspace, folded by a second launch (one hand-off through
-        // device memory: the GLOBAL scheme)
-        Launch& ml = cand.launches.back();
-        const uint32_t n_wg = n_row_wgs;   // one row of partial sums per row block (its column tiles share the row)
-        const uint32_t width = (uint32_t)c.n_colsum * base.cols;
-        ml.ptr[kSlotWs].kind = BUF_WORKSPACE;
-        ml.ptr[kSlotWs].offset = 0;
-        ml.shape.lds_bytes = 0;
-        cand.info.lds_bytes = slots + (s.block ? 0 : c.n_colsum * 4 * (int32_t)(s.L * kv) * 4);
-        cand.launches.emplace_back();
-        Launch& f = cand.launches.back();
-        make_fold_launch(&f, n_wg, width, base.cols);
-        f.ptr[0].kind = BUF_WORKSPACE;
-        f.ptr[0].offset = 0;
-        f.ptr[1].kind = BUF_OUTPUT;
-        f.ptr[1].slot = c.colsum_slot[0];
-        if (c.n_colsum > 1) { f.ptr[2].kind = BUF_OUTPUT; f.ptr[2].slot = c.colsum_slot[1]; }
-        cand.info.scheme = FS_SCHEME_GLOBAL;
-        cand.info.n_kernels = 2;
-        cand.info.workspace_bytes = (int64_t)n_wg * width * 4;
-        cand.info.bytes_moved_model = bytes_min + 2 * cand.info.workspace_bytes;
-        if (s.CT > 1)
-          snprintf(cand.info.kernel, sizeof cand.info.kernel, "row_generated<v%d,K%d,L%u,I%d,R%d,rows%u,tiles%u>+colfold", vec, s.K, s.L,
-                   base.n_instr, base.n_regs, s.R, s.CT);
-        else
-          snprintf(cand.info.kernel, sizeof cand.info.kernel, "row_generated<v%d,K%d,L%u,I%d,R%d,rows%u>+colfold", vec, s.K, s.L, base.n_instr,
-                   base.n_regs, s.R);
-        gc.hbm_bytes += 2.0 * (double)cand.info.workspace_bytes;
-        gc.vgpr_estimate += kv * c.n_colsum;
-        gc.rows_per_wave_loop = s.R;
-        if (s.R > 1) {   // software-pipelined: only the first row's load latency is exposed
-          gc.dep_phases = 0;
-          gc.serial_tail_s += d.mem_latency_s;
-          gc.bytes_in_flight_per_lane *= 2.0;   // this row's and the next row's loads
-        }
-        gc.lds_bytes_per_block = cand.info.lds_bytes;
-        gc.barriers = 1;
-        gc.serial_tail_s += d.mem_latency_s + 0.5 * d.launch_s + d.mem_latency_s * std::ceil(n_wg / 64.0 / 8.0) * 0.5;
-      }
-      if (gc.vgpr_estimate > 256) continue;   // would not fit the register file without spilling
-    }
-    out->push_back(cand);
-  }
-  }   // step widths
   return !out->empty();
 }
 
