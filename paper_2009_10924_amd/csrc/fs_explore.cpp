@@ -798,7 +798,18 @@ fs_status fs_explore(const fs_graph* g, const fs_explore_opts* opts, fs_program*
   if (best < 0) return fail(first_error != FS_OK ? first_error : FS_ERR_UNSUPPORTED_PATTERN, "fs_explore: %s", first_text.c_str());
 
   for (fs_program::Step& s : built[best].steps) {
-    const fs_status st = complete_plan(s.plan);
+    fs_status st = complete_plan(s.plan);
+    if (st == FS_ERR_UNSUPPORTED_PATTERN) {
+      // the pattern's only stitched form was a generated kernel that did not compile: it runs per op instead
+      SubGraph sub;
+      fs_plan* per_op = nullptr;
+      st = ex.extract(s.ops, &sub);
+      if (st == FS_OK) st = create_plan(sub.g, FS_SCHEME_UNFUSED, nullptr, true, &per_op);
+      if (st == FS_OK) {
+        fs_plan_destroy(s.plan);
+        s.plan = per_op;
+      }
+    }
     if (st != FS_OK) {
       built[best].destroy();
       return st;

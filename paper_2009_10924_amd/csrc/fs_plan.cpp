@@ -213,6 +213,12 @@ fs_status fs::create_plan(const fs_graph* g, int32_t scheme, const fs_plan_opts*
     const fs_status s = complete_plan(p);
     if (s != FS_OK) {
       delete p;
+      // AUTO promises a plan for every valid graph: when the only stitched form was a generated kernel and that
+      // did not compile, the per-op plan is what remains
+      if (scheme == FS_SCHEME_AUTO && o.candidate < 0 && s == FS_ERR_UNSUPPORTED_PATTERN) {
+        fs_plan_opts plain = o;
+        return create_plan(g, FS_SCHEME_UNFUSED, &plain, true, out);
+      }
       return s;
     }
   }

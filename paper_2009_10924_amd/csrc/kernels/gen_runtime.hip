@@ -8,6 +8,7 @@
 #include <hip/hiprtc.h>
 
 #include <atomic>
+#include <cstdlib>
 #include <cstring>
 #include <map>
 #include <mutex>
@@ -146,6 +147,11 @@ int gen_compile(const std::string& source, const char* entry, std::shared_ptr<Ge
   if (!r.ok) {
     if (log) *log = "the HIP run-time compiler (libhiprtc) could not be loaded";
     return (int)hipErrorNotSupported;
+  }
+  if (const char* inject = getenv("FS_CODEGEN_INJECT_FAILURE"); inject && inject[0] == '1') {
+    // for tests of the fall-back paths: behave as if the compiler had rejected the source
+    if (log) *log = "compilation failure injected by FS_CODEGEN_INJECT_FAILURE";
+    return (int)hipErrorUnknown;
   }
   std::lock_guard<std::mutex> guard(big_lock());
   auto it = cache().find(source);

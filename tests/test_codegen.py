@@ -167,3 +167,27 @@ def test_unsupported_pattern_is_not_rescued_by_code_generation():
     spec = GraphSpec("pattern_x", [TensorSpec("x", "f32", (8, 16))],
                      [OpSpec("e", "exp", ("x",)), OpSpec("s", "reduce_sum", ("e",), {"axis": 0})], [("s", "f32")])
     assert _plan(spec).info["scheme"] == "global"
+
+
+def test_fall_back_when_compilation_fails(monkeypatch):
+    """With every compilation reported as failed: AUTO moves to the interpreted candidate; a pattern whose only
+    stitched form is a generated kernel runs per op (plan and explored program alike); by index the failure is an
+    error; a pack falls back to the fixed packed kernel."""
+    from workloads import gelu_backward_graph
+    monkeypatch.setenv("FS_CODEGEN_INJECT_FAILURE", "1")
+    spec = layernorm_stats_graph(64, 768, with_variance=True)
+    plan = _plan(spec)
+    assert plan.info["pattern"] == "row_program" and plan.source() == ""
+    generated = [c["candidate"] for c in plan.candidates() if c["pattern"] == "row_generated"]
+    with pytest.raises(B.FsError) as e:
+        _plan(spec, candidate=generated[0])
+    assert e.value.code == -5 and "injected" in e.value.text
+    colsum = gelu_backward_graph(300, 96, "bf16")          # no interpreted form
+    info = _plan(colsum).info
+    assert info["scheme"] == "unfused" and info["n_kernels"] >= len(colsum.ops)    # (the column sum takes two launches)
+    prog = B.Program(B.Graph.from_spec(colsum))
+    assert prog.info["n_kernels"] >= 2 and "row_generated" not in [p["info"]["pattern"] for p in prog.patterns()]
+    pack = B.Pack([_plan(softmax_graph(64, 128, "f32")), _plan(softmax_graph(9, 256, "f32"))])
+    assert pack.info["generated"] == 0 and pack.info["n_kernels"] == 1
+    monkeypatch.delenv("FS_CODEGEN_INJECT_FAILURE")
+    assert _plan(spec).info["pattern"] == "row_generated"
