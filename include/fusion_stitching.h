@@ -197,7 +197,10 @@ int64_t fs_plan_describe(const fs_plan *p, char *text, size_t capacity);
  * Compilation needs no GPU; the module is loaded on the device that is current at plan
  * creation (or, without one, by the first fs_execute: do that one outside stream capture).
  * If the compiler is not available, compilation fails or the kernel would spill registers,
- * the choice falls back to the next best candidate.                                   */
+ * the choice falls back to the next best candidate (for FS_SCHEME_AUTO in the end to the
+ * per-op plan).  Environment: FS_CODEGEN=0 switches generated kernels off by default;
+ * FS_CODEGEN_CACHE_DIR=<existing directory> keeps compiled code objects there between
+ * processes (files fs_gfx950_<hash>.co, verified against the full source when read).    */
 
 /* Process-wide switch for offering generated kernels (default 1; the environment variable
  * FS_CODEGEN=0 sets the default to 0).  Affects plans, scores and programs created

@@ -4,10 +4,12 @@
 // process-wide cache keyed by the source, loads a code object as a module on the device it
 // is first launched on, and launches it.  Host code only.
 #include <dlfcn.h>
+#include <unistd.h>
 #include <hip/hip_runtime.h>
 #include <hip/hiprtc.h>
 
 #include <atomic>
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <map>
@@ -96,6 +98,50 @@ std::mutex& big_lock() {
   return m;
 }
 
+// Optional on-disk cache of code objects, for processes that start often: FS_CODEGEN_CACHE_DIR names a directory
+// (it must exist); a file there is named by a 64-bit hash of the source and holds the source's length, the source
+// and the code object, so a hash collision or a damaged file reads as a miss.  Unset: nothing is read or written.
+uint64_t fnv1a64(const std::string& text) {
+  uint64_t h = 1469598103934665603ull;
+  for (unsigned char ch : text) h = (h ^ ch) * 1099511628211ull;
+  return h;
+}
+std::string cache_path(const std::string& source) {
+  const char* dir = getenv("FS_CODEGEN_CACHE_DIR");
+  if (!dir || !dir[0]) return std::string();
+  char name[64];
+  // the compiler settings are part of the key (the source alone would survive a change of them)
+  snprintf(name, sizeof name, "/fs_gfx950_%016llx.co", (unsigned long long)fnv1a64("gfx950|O3|c++17|no-packed-fp32|" + source));
+  return std::string(dir) + name;
+}
+bool cache_read(const std::string& source, std::string* code) {
+  const std::string path = cache_path(source);
+  if (path.empty()) return false;
+  FILE* f = fopen(path.c_str(), "rb");
+  if (!f) return false;
+  bool ok = false;
+  uint64_t n_source = 0, n_code = 0;
+  if (fread(&n_source, 8, 1, f) == 1 && fread(&n_code, 8, 1, f) == 1 && n_source == source.size() && n_code > 0 && n_code < (1ull << 28)) {
+    std::string stored(n_source, '\0');
+    code->assign(n_code, '\0');
+    ok = fread(&stored[0], 1, n_source, f) == n_source && stored == source && fread(&(*code)[0], 1, n_code, f) == n_code;
+  }
+  fclose(f);
+  return ok;
+}
+void cache_write(const std::string& source, const std::string& code) {
+  const std::string path = cache_path(source);
+  if (path.empty()) return;
+  const std::string tmp = path + ".tmp" + std::to_string((long)getpid());
+  FILE* f = fopen(tmp.c_str(), "wb");
+  if (!f) return;
+  const uint64_t n_source = source.size(), n_code = code.size();
+  const bool ok = fwrite(&n_source, 8, 1, f) == 1 && fwrite(&n_code, 8, 1, f) == 1 && fwrite(source.data(), 1, n_source, f) == n_source &&
+                  fwrite(code.data(), 1, n_code, f) == n_code;
+  fclose(f);
+  if (!ok || rename(tmp.c_str(), path.c_str()) != 0) remove(tmp.c_str());   // complete files only, whoever wins the race
+}
+
 }  // namespace
 
 struct GenKernel {
@@ -159,6 +205,24 @@ int gen_compile(const std::string& source, const char* entry, std::shared_ptr<Ge
     *out = it->second;
     return 0;
   }
+  auto finish = [&](const std::shared_ptr<GenKernel>& k) {
+    const int64_t vg = metadata_uint(k->code, ".vgpr_count"), lds = metadata_uint(k->code, ".group_segment_fixed_size"),
+                  scratch = metadata_uint(k->code, ".private_segment_fixed_size"), spill = metadata_uint(k->code, ".vgpr_spill_count");
+    k->vgprs = vg > 0 ? (int32_t)vg : 0;
+    k->static_lds = lds > 0 ? (int32_t)lds : 0;
+    k->scratch_bytes = scratch > 0 ? (int32_t)scratch : 0;
+    k->spilled_vgprs = spill > 0 ? (int32_t)spill : 0;
+    cache()[source] = k;
+    *out = k;
+  };
+  {
+    auto k = std::make_shared<GenKernel>();
+    k->entry = entry;
+    if (cache_read(source, &k->code)) {
+      finish(k);
+      return 0;
+    }
+  }
   hiprtcProgram prog = nullptr;
   hiprtcResult rc = r.create(&prog, source.c_str(), "fs_generated.hip", 0, nullptr, nullptr);
   if (rc != HIPRTC_SUCCESS) {
@@ -194,14 +258,8 @@ int gen_compile(const std::string& source, const char* entry, std::shared_ptr<Ge
     if (log) *log = "the run-time compiler returned no code object";
     return (int)hipErrorUnknown;
   }
-  const int64_t vg = metadata_uint(k->code, ".vgpr_count"), lds = metadata_uint(k->code, ".group_segment_fixed_size"),
-                scratch = metadata_uint(k->code, ".private_segment_fixed_size"), spill = metadata_uint(k->code, ".vgpr_spill_count");
-  k->vgprs = vg > 0 ? (int32_t)vg : 0;
-  k->static_lds = lds > 0 ? (int32_t)lds : 0;
-  k->scratch_bytes = scratch > 0 ? (int32_t)scratch : 0;
-  k->spilled_vgprs = spill > 0 ? (int32_t)spill : 0;
-  cache()[source] = k;
-  *out = k;
+  cache_write(source, k->code);
+  finish(k);
   return 0;
 }
 

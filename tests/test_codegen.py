@@ -191,3 +191,48 @@ def test_fall_back_when_compilation_fails(monkeypatch):
     assert pack.info["generated"] == 0 and pack.info["n_kernels"] == 1
     monkeypatch.delenv("FS_CODEGEN_INJECT_FAILURE")
     assert _plan(spec).info["pattern"] == "row_generated"
+
+
+def test_code_objects_survive_the_process_in_the_cache_directory(tmp_path):
+    """FS_CODEGEN_CACHE_DIR: the first process compiles and leaves a file, the second one loads it (and says the same
+    about the kernel); a damaged file is a miss, not an error."""
+    import os
+    import subprocess
+    import sys
+    script = ("import time; t0 = time.time();"
+              "from paper_2009_10924_amd import binding as B; from workloads import layernorm_stats_graph;"
+              "p = B.Plan(B.Graph.from_spec(layernorm_stats_graph(64, 768, with_variance=True)));"
+              "print(p.info['pattern'], p.info['vgprs'])")
+    env = dict(os.environ, FS_CODEGEN_CACHE_DIR=str(tmp_path))
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    first = subprocess.run([sys.executable, "-c", script], cwd=root, env=env, capture_output=True, text=True, check=True).stdout.split()
+    files = sorted(tmp_path.glob("fs_gfx950_*.co"))
+    assert first[0] == "row_generated" and len(files) == 1 and files[0].stat().st_size > 4096
+    stamp = files[0].stat().st_mtime_ns
+    second = subprocess.run([sys.executable, "-c", script], cwd=root, env=env, capture_output=True, text=True, check=True).stdout.split()
+    assert second == first and files[0].stat().st_mtime_ns == stamp          # read, not rewritten
+    data = files[0].read_bytes()
+    files[0].write_bytes(data[:100] + bytes(50) + data[150:])               # the stored source no longer matches
+    third = subprocess.run([sys.executable, "-c", script], cwd=root, env=env, capture_output=True, text=True, check=True).stdout.split()
+    assert third == first and files[0].read_bytes() == data                  # compiled again and written back
+
+
+def test_plans_can_be_made_from_several_threads_at_once():
+    """Compilation and the process-wide kernel cache are serialised inside the library: eight threads making plans of
+    overlapping patterns all get working plans, and identical sources end up as one kernel (one name)."""
+    from concurrent.futures import ThreadPoolExecutor
+    specs = [layernorm_stats_graph(32 + 8 * (i % 3), 768, with_variance=True) for i in range(12)] + \
+            [silu_gate_graph(16, 256 + 64 * (i % 2), "f32") for i in range(4)]
+
+    def make(spec):
+        p = _plan(spec)
+        entry = [l.split()[1] for l in p.describe().splitlines() if l.strip().startswith("entry ")]
+        return spec.name, p.info["pattern"], entry[0] if entry else ""
+
+    with ThreadPoolExecutor(max_workers=8) as pool:
+        results = list(pool.map(make, specs))
+    assert all(pattern == "row_generated" and entry for _, pattern, entry in results)
+    by_name = {}
+    for name, _, entry in results:
+        by_name.setdefault(name, set()).add(entry)
+    assert all(len(v) == 1 for v in by_name.values())

@@ -280,7 +280,7 @@ NEXT_CONFIGS = {
     "N6": lambda: layernorm_stats_graph(8192, 768),                          # C2 that also saves mean and rstd for backward
 }
 
-# ---- row-local patterns no hand-written kernel family covers (served by the interpreted row program) ----
+# ---- row-local patterns no hand-written kernel family covers (served by the row-program compiler: generated kernel or interpreter) ----
 def layernorm_stats_graph(rows: int, cols: int, eps: float = 1e-5, in_dtype: str = "f32", out_dtype: str = "bf16",
                           with_variance: bool = False) -> GraphSpec:
     """Residual add + bias + LayerNorm that also hands out the per-row mean and reciprocal standard
@@ -648,7 +648,7 @@ EXPLORE_CONFIGS = {"T1": lambda: transformer_block_graph(32, 128, 12, 64, 3072, 
                    # the same block with the q/k/v projection biases added in front of the head split
                    "T2": lambda: transformer_block_graph(32, 128, 12, 64, 3072, "bf16", projection_bias=True)}
 
-# Row-local patterns outside the hand-written families, at transformer-block sizes (interpreted row program).
+# Row-local patterns outside the hand-written families, at transformer-block sizes (generated kernels; the interpreted row program beside them).
 GENERIC_CONFIGS = {
     "G1": lambda: layernorm_stats_graph(8192, 768, with_variance=True),      # C2 plus mean / rstd / variance outputs
     "G2": lambda: silu_gate_graph(8192, 4096, "bf16"),
