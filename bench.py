@@ -397,6 +397,8 @@ def main():
         torch.cuda.empty_cache()
         result["explorer_T2"] = measure_program("T2", max(100, args.steps // 8), 10)
         torch.cuda.empty_cache()
+        result["explorer_T3"] = measure_program("T3", max(100, args.steps // 8), 10)
+        torch.cuda.empty_cache()
         from paper_2009_10924_amd import binding as B
         generic = {}
         for name in ("G1", "G2", "G3", "G4", "G5", "G6", "G7", "G8", "G9", "G10"):

@@ -3,11 +3,11 @@
 
 namespace fs {
 
-void make_fold_launch(Launch* f, uint32_t n_rows, uint32_t width, uint32_t split) {
+void make_fold_launch(Launch* f, uint32_t n_rows, uint32_t width, uint32_t split, uint32_t stride) {
   f->kernel = K_COLFOLD;
   GeluP fp{};
   fp.n_row_tiles = n_rows;
-  fp.cols = width;
+  fp.cols = stride ? stride : width;   // distance between partial rows (a fold may take a slice of wider rows)
   fp.fold_cols = width;
   fp.fold_split = split;
   fp.fold_quads = n_rows > 128 ? 4 : 16;

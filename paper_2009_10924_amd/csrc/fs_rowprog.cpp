@@ -807,16 +807,22 @@ void add_column_sums(const Compiler& c, int vec, const Shape& s, int64_t bytes_m
   ml.ptr[kSlotWs].kind = BUF_WORKSPACE;
   ml.ptr[kSlotWs].offset = 0;
   cand->info.lds_bytes += s.block ? 0 : c.n_colsum * 4 * (int32_t)(s.L * kv) * 4;
-  cand->launches.emplace_back();
-  Launch& f = cand->launches.back();
-  make_fold_launch(&f, n_wg, width, base.cols);
-  f.ptr[0].kind = BUF_WORKSPACE;
-  f.ptr[0].offset = 0;
-  f.ptr[1].kind = BUF_OUTPUT;
-  f.ptr[1].slot = c.colsum_slot[0];
-  if (c.n_colsum > 1) { f.ptr[2].kind = BUF_OUTPUT; f.ptr[2].slot = c.colsum_slot[1]; }
+  // a fold launch hands out two sums: sums 0 and 1 by the first, 2 and 3 by a second one over the other half of
+  // the partial rows
+  for (int first = 0; first < c.n_colsum; first += 2) {
+    const int here = std::min(2, c.n_colsum - first);
+    cand->launches.emplace_back();
+    Launch& f = cand->launches.back();
+    make_fold_launch(&f, n_wg, (uint32_t)here * base.cols, base.cols, width);
+    f.ptr[0].kind = BUF_WORKSPACE;
+    f.ptr[0].offset = (int64_t)first * base.cols * 4;
+    for (int i = 0; i < here; ++i) {
+      f.ptr[1 + i].kind = BUF_OUTPUT;
+      f.ptr[1 + i].slot = c.colsum_slot[first + i];
+    }
+  }
   cand->info.scheme = FS_SCHEME_GLOBAL;
-  cand->info.n_kernels = 2;
+  cand->info.n_kernels = (int32_t)cand->launches.size();
   cand->info.workspace_bytes = (int64_t)n_wg * width * 4;
   cand->info.bytes_moved_model = bytes_min + 2 * cand->info.workspace_bytes;
   if (s.CT > 1)
@@ -836,7 +842,7 @@ void add_column_sums(const Compiler& c, int vec, const Shape& s, int64_t bytes_m
   }
   gc.lds_bytes_per_block = cand->info.lds_bytes;
   gc.barriers = 1;
-  gc.serial_tail_s += d.mem_latency_s + 0.5 * d.launch_s + d.mem_latency_s * std::ceil(n_wg / 64.0 / 8.0) * 0.5;
+  gc.serial_tail_s += (d.mem_latency_s + 0.5 * d.launch_s + d.mem_latency_s * std::ceil(n_wg / 64.0 / 8.0) * 0.5) * (cand->launches.size() - 1);
 }
 
 // One candidate: the program in shape `s`, interpreted or generated.  false: the shape does not fit (the

@@ -163,7 +163,7 @@ __global__ void __launch_bounds__(WAVES * 64) k_bias_gelu_dbias(const T* __restr
   }
 }
 
-// ---- fold of column partials: [n_rows, width] float32 -> [width] -------------------------
+// ---- fold of column partials: [n_rows, width] float32 (rows `stride` floats apart) -> [width] ---------
 // Workgroup = Q column quads x G row groups (256 threads).  Each thread sums its rows in
 // order with eight independent loads in flight, LDS folds the G groups in order.  Few
 // partial rows: (Q,G) = (16,16); many: (4,64), so a thread still needs one batch of loads.
@@ -173,18 +173,18 @@ __global__ void __launch_bounds__(256) k_colfold(const float* __restrict__ parti
   __shared__ f32x4 sm[G][Q];
   const uint32_t q = threadIdx.x % Q, g = threadIdx.x / Q;
   const uint32_t col = (blockIdx.x * Q + q) * 4u;
-  const uint32_t n = p.n_row_tiles, width = p.fold_cols;
+  const uint32_t n = p.n_row_tiles, width = p.fold_cols, stride = p.cols;   // stride >= width: a slice of wider partial rows
   f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
   if (col < width) {
     uint32_t t = g;
     for (; t + 7 * G < n; t += 8 * G) {
       f32x4 v[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x4*>(partials + (size_t)(t + u * G) * width + col);
+      for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const f32x4*>(partials + (size_t)(t + u * G) * stride + col);
 #pragma unroll
       for (int u = 0; u < 8; ++u) s += v[u];
     }
-    for (; t < n; t += G) s += *reinterpret_cast<const f32x4*>(partials + (size_t)t * width + col);
+    for (; t < n; t += G) s += *reinterpret_cast<const f32x4*>(partials + (size_t)t * stride + col);
   }
   sm[g][q] = s;
   __syncthreads();

@@ -115,7 +115,7 @@ struct LayerNormP {
 };
 struct GeluP {
   int32_t dt, bias_dt;              // x / grad / y share dt
-  uint32_t rows, cols;
+  uint32_t rows, cols;              // K_COLFOLD: cols = floats between two partial rows
   uint32_t n_row_tiles;             // row blocks = rows of the partials workspace
   int32_t waves, unroll;            // workgroup = waves x 64 lanes; a row tile = waves * unroll rows
   int32_t ticket;                   // 1: fold inside the launch (last ticket), 0: fold by K_COLFOLD
@@ -214,7 +214,7 @@ struct ProgInstr {
 constexpr int kProgMaxInstr = 64;
 constexpr int kProgMaxOperands = 8;     // per class: full inputs, column vectors, per-row inputs, outputs
 constexpr int kProgMaxInterpretedFull = 4;   // full-shaped inputs the interpreter's load batch is built for
-constexpr int kProgMaxColSums = 2;      // what one fold launch hands out
+constexpr int kProgMaxColSums = 4;      // one fold launch hands out two: at most two fold launches
 constexpr int kProgMaxReductions = 8;   // LDS slot sets of the workgroup-per-row form
 constexpr int kProgMaxLdsBytes = 128 * 1024;   // register files of one workgroup (a CU has 160 KB)
 struct RowProgP {

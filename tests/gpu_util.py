@@ -84,8 +84,12 @@ def run_pack(specs, inputs_list, repeat=1):
     return out, pack.info
 
 
-def all_candidates(spec, inputs, ref, floors, repeat=1, unfused=True):
-    """Runs the per-op plan and every stitched candidate of `spec`; returns the worst error per output."""
+def all_candidates(spec, inputs, ref, floors, repeat=1, unfused=True, after_rounding=None):
+    """Runs the per-op plan and every stitched candidate of `spec`; returns the worst error per output.
+    after_rounding: {output name: 16-bit dtype} for float32 outputs computed from values the graph itself rounded to
+    that dtype: near a rounding tie float32 and float64 upstream arithmetic pick different neighbours, so such an output
+    is held to the 16-bit bar."""
+    after_rounding = after_rounding or {}
     worst = {}
     g = B.Graph.from_spec(spec)
     n = B.Plan(g, "auto").info["n_candidates"]
@@ -102,6 +106,6 @@ def all_candidates(spec, inputs, ref, floors, repeat=1, unfused=True):
                 continue
             raise
         for name, dt in spec.outputs:
-            e = check(got[name], ref[name], dt, floors.get(name, 0.0), f"{spec.name}/{info['kernel']}/{name}")
+            e = check(got[name], ref[name], after_rounding.get(name, dt), floors.get(name, 0.0), f"{spec.name}/{info['kernel']}/{name}")
             worst[name] = max(worst.get(name, 0.0), e)
     return worst

@@ -34,7 +34,10 @@ def run_program(spec, inputs_np, repeat=2, **opts):
     return {name: O.to_f64(results[0][name], dt) for name, dt in spec.outputs}, prog
 
 
-def compare(spec, seed=0, **opts):
+def compare(spec, seed=0, after_rounding=(), **opts):
+    """after_rounding: float32 outputs computed from values that the graph itself rounded to a 16-bit dtype.  Near a
+    rounding tie float32 and float64 upstream arithmetic pick different neighbours (one 16-bit ulp apart), so such an
+    output can only be held to the bar of the 16-bit dtype."""
     inp = make_inputs(spec, seed=seed)
     ref = O.evaluate(spec, inp)
     got, prog = run_program(spec, inp, **opts)
@@ -42,8 +45,9 @@ def compare(spec, seed=0, **opts):
     for name, dt in spec.outputs:
         assert np.isfinite(got[name]).all(), f"{spec.name}/{name}: non-finite values"
         err = O.max_rel_err(got[name], ref[name].reshape(got[name].shape), O.rms(ref[name]))
-        assert err <= TOL[dt], f"{spec.name}/{name}: max rel err {err:.3e} > {TOL[dt]:.0e}"
-        worst = max(worst, err / TOL[dt])
+        tol = TOL["bf16"] if name in after_rounding else TOL[dt]
+        assert err <= tol, f"{spec.name}/{name}: max rel err {err:.3e} > {tol:.0e}"
+        worst = max(worst, err / tol)
     return worst, prog
 
 
@@ -78,6 +82,22 @@ def test_transformer_block_with_projection_biases(dims):
     q = torch.from_numpy(O.to_f64(inp["q_lin"], "bf16")).float() + torch.from_numpy(O.to_f64(inp["bias_q"], "bf16")).float()
     want = q.to(torch.bfloat16).float().numpy().transpose(0, 2, 1, 3)
     assert np.array_equal(got["qt"], want.astype(np.float64))
+
+
+@pytest.mark.parametrize("dims", [(2, 16, 2, 8, 64), (3, 40, 4, 32, 256), (32, 128, 12, 64, 3072)])
+def test_transformer_block_backward(dims):
+    """Backward pass through the block: LayerNorm and GELU backward with their column sums (partial sums + fold launches
+    inside generated kernels where the run-time compiler is there, per-op column reductions otherwise), softmax
+    backward, gradient transposes; every output against the float64 oracle."""
+    from workloads import transformer_block_backward_graph
+    spec = transformer_block_backward_graph(*dims, "bf16")
+    # the bias gradients sum gradients that were rounded to bf16 on the way out; LayerNorm 1's column sums start from one
+    worst, prog = compare(spec, after_rounding=("dbias2", "dbias1", "dbias_o", "l1_dgamma", "l1_dbeta"))
+    info = prog.info
+    plans = [p["info"]["pattern"] for p in prog.patterns()]
+    note(f"transformer block backward {dims}: {info['n_ops']} ops -> {info['n_patterns']} patterns + {info['n_single_ops']} single ops, "
+         f"{info['n_kernels']} launches {plans}, workspace {info['workspace_bytes']} B, worst {worst:.3f} of the bar")
+    assert info["n_kernels"] < info["n_ops"] // 2
 
 
 def test_transformer_block_without_packing_and_remote_fusion():

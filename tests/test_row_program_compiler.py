@@ -83,10 +83,10 @@ def emulate(listing, spec, inputs, anchor_dims):
     # column sums leave through the fold launch that follows: its pointer lines name the outputs
     fold = [i for i, l in enumerate(lines) if l[:2] == ["launch", "colfold"]]
     colsum_bind = {}
-    if fold:
-        for l in lines[fold[0] + 1:]:
+    for k, start in enumerate(fold):          # each fold launch hands out two sums, in order
+        for l in lines[start + 1:(fold[k + 1] if k + 1 < len(fold) else len(lines))]:
             if l and l[0] in ("ptr1", "ptr2"):
-                colsum_bind[int(l[0][3:]) - 1] = int(l[1][3:])
+                colsum_bind[2 * k + int(l[0][3:]) - 1] = int(l[1][3:])
     acc = np.zeros((rows, cols), np.float32) if acc0 is None else acc0.copy()
     sacc = np.zeros((rows, 1), np.float32)
     f32 = np.float32
@@ -229,12 +229,12 @@ def test_transposes_of_leading_axes_fold_into_loads_and_stores(dims, perm):
 
 @pytest.mark.parametrize("rows,cols", [(37, 96), (50, 128), (9, 1024)])
 def test_column_sums_compile_to_partial_sums_and_a_fold(rows, cols):
-    from workloads import gelu_backward_graph, rmsnorm_backward_graph
-    for make in (gelu_backward_graph, rmsnorm_backward_graph):
+    from workloads import gelu_backward_graph, layernorm_backward_bias_graph, rmsnorm_backward_graph
+    for make, launches in ((gelu_backward_graph, 2), (rmsnorm_backward_graph, 2), (layernorm_backward_bias_graph, 3)):
         spec = make(rows, cols, "f32")
         _, info = _compare(spec)
         if B.codegen_available():
-            assert info["n_kernels"] == 2 and info["scheme"] == "global"
+            assert info["n_kernels"] == launches and info["scheme"] == "global"    # a fold launch per two column sums
             assert info["workspace_bytes"] % (cols * 4) == 0 and info["workspace_bytes"] > 0
 
 

@@ -5,7 +5,8 @@ from .graphs import (DTYPE_BYTES, DTYPES, EXPLORE_CONFIGS, FULL_CONFIGS, GENERIC
                      transpose_chain_graph, transpose_graph, layernorm_stats_graph, silu_gate_graph,
                      scaled_softmax_colbias_graph, normalize_from_stats_graph, outer_scale_graph, random_row_pattern, transformer_block_graph, random_multi_pattern, independent_tiny_patterns_graph, masked_scores_gate_graph,
                      bias_head_split_graph, head_merge_residual_graph, transpose_chain_stats_graph, transposed_softmax_graph,
-                     gelu_backward_graph, rmsnorm_backward_graph)
+                     gelu_backward_graph, rmsnorm_backward_graph, transformer_block_backward_graph,
+                     layernorm_backward_bias_graph)
 from .inputs import f64_to_bf16_bits, make_inputs, quantise, valid_lengths
 
 __all__ = [
@@ -14,5 +15,5 @@ __all__ = [
     "softmax_graph", "softmax_backward_graph", "layernorm_backward_graph", "rmsnorm_graph", "transpose_chain_graph", "transpose_graph",
     "layernorm_stats_graph", "silu_gate_graph", "scaled_softmax_colbias_graph", "normalize_from_stats_graph",
     "outer_scale_graph", "random_row_pattern", "transformer_block_graph", "random_multi_pattern", "independent_tiny_patterns_graph", "masked_scores_gate_graph", "bias_head_split_graph", "head_merge_residual_graph",
-    "transpose_chain_stats_graph", "transposed_softmax_graph", "gelu_backward_graph", "rmsnorm_backward_graph", "f64_to_bf16_bits", "make_inputs", "quantise", "valid_lengths",
+    "transpose_chain_stats_graph", "transposed_softmax_graph", "gelu_backward_graph", "rmsnorm_backward_graph", "transformer_block_backward_graph", "layernorm_backward_bias_graph", "f64_to_bf16_bits", "make_inputs", "quantise", "valid_lengths",
 ]

@@ -412,6 +412,23 @@ def gelu_backward_graph(rows: int, cols: int, dtype: str = "bf16") -> GraphSpec:
                      ops=ops, outputs=[("dx", dtype), ("dbias", "f32")])
 
 
+def layernorm_backward_bias_graph(rows: int, cols: int, dtype: str = "bf16") -> GraphSpec:
+    """LayerNorm backward from saved statistics together with the gradient of the bias that was added in front of the
+    LayerNorm: dx (rounded to the storage dtype), dgamma, dbeta and dbias = column sum of the rounded dx.  Two row
+    reductions and three column sums in one pattern."""
+    ops = [
+        _op("c", "sub", "h", "mu"), _op("xh", "mul", "c", "rstd"), _op("g", "mul", "dy", "gamma"),
+        _op("m1", "reduce_mean", "g", axis=1), _op("gx", "mul", "g", "xh"), _op("m2", "reduce_mean", "gx", axis=1),
+        _op("t1", "sub", "g", "m1"), _op("t2", "mul", "xh", "m2"), _op("t3", "sub", "t1", "t2"), _op("dx", "mul", "t3", "rstd"),
+        _op("dxc", "convert", "dx", dtype=dtype), _op("dbias", "reduce_sum", "dxc", axis=0),
+        _op("dyx", "mul", "dy", "xh"), _op("dgamma", "reduce_sum", "dyx", axis=0), _op("dbeta", "reduce_sum", "dy", axis=0),
+    ]
+    return GraphSpec(name=f"pattern_layernorm_backward_bias_{dtype}_{rows}x{cols}",
+                     inputs=[TensorSpec("h", dtype, (rows, cols)), TensorSpec("dy", dtype, (rows, cols)), TensorSpec("gamma", dtype, (cols,)),
+                             TensorSpec("mu", "f32", (rows, 1)), TensorSpec("rstd", "f32", (rows, 1))],
+                     ops=ops, outputs=[("dxc", dtype), ("dbias", "f32"), ("dgamma", "f32"), ("dbeta", "f32")])
+
+
 def rmsnorm_backward_graph(rows: int, cols: int, dtype: str = "bf16") -> GraphSpec:
     """Backward of RMSNorm from the saved reciprocal rms: xhat = x * rrms; dgamma = column sum of dy * xhat;
     gy = dy * gamma; dx = (gy - xhat * rowmean(gy * xhat)) * rrms.  A row reduction and a column reduction in one
@@ -574,6 +591,57 @@ def transformer_block_graph(batch: int = 32, seq: int = 128, heads: int = 12, di
                      outputs=outputs)
 
 
+def transformer_block_backward_graph(batch: int = 32, seq: int = 128, heads: int = 12, dim: int = 64, ffn: int = 3072,
+                                     dtype: str = "bf16") -> GraphSpec:
+    """The memory-intensive ops of the backward pass through one transformer encoder block, matrix products taken out
+    (the gradients they produce come in as graph inputs, the gradients they consume go out as graph outputs):
+    LayerNorm 2 backward from saved statistics (dx, dgamma, dbeta) and the bias gradient behind it, bias + GELU
+    backward with its bias gradient, the residual sum into LayerNorm 1 backward and its bias gradient, softmax backward
+    on the attention probabilities with the score scale, and the head split / merge transposes of the gradients.
+    Row reductions, column sums over all rows and transposes side by side (45 ops)."""
+    hidden, rows = heads * dim, batch * seq
+    t_bshd, t_bhsd = (batch, seq, heads, dim), (batch, heads, seq, dim)
+
+    def ln_backward(p: str, h: str, dy: str, gamma: str, mu: str, rstd: str) -> List[OpSpec]:
+        return [
+            _op(p + "c", "sub", h, mu), _op(p + "xh", "mul", p + "c", rstd), _op(p + "g", "mul", dy, gamma),
+            _op(p + "m1", "reduce_mean", p + "g", axis=1), _op(p + "gx", "mul", p + "g", p + "xh"),
+            _op(p + "m2", "reduce_mean", p + "gx", axis=1), _op(p + "t1", "sub", p + "g", p + "m1"),
+            _op(p + "t2", "mul", p + "xh", p + "m2"), _op(p + "t3", "sub", p + "t1", p + "t2"),
+            _op(p + "dx", "mul", p + "t3", rstd), _op(p + "dxc", "convert", p + "dx", dtype=dtype),
+            _op(p + "dyx", "mul", dy, p + "xh"), _op(p + "dgamma", "reduce_sum", p + "dyx", axis=0),
+            _op(p + "dbeta", "reduce_sum", dy, axis=0),
+        ]
+
+    inputs = [
+        TensorSpec("dy2", dtype, (rows, hidden)), TensorSpec("h2", dtype, (rows, hidden)), TensorSpec("gamma2", dtype, (hidden,)),
+        TensorSpec("mu2", "f32", (rows, 1)), TensorSpec("rstd2", "f32", (rows, 1)),
+        TensorSpec("ffn1_pre", dtype, (rows, ffn)), TensorSpec("bias1", dtype, (ffn,)), TensorSpec("up_act", dtype, (rows, ffn)),
+        TensorSpec("up_l1", dtype, (rows, hidden)), TensorSpec("h1", dtype, (rows, hidden)), TensorSpec("gamma1", dtype, (hidden,)),
+        TensorSpec("mu1", "f32", (rows, 1)), TensorSpec("rstd1", "f32", (rows, 1)),
+        TensorSpec("probs", dtype, (batch, heads, seq, seq)), TensorSpec("up_probs", dtype, (batch, heads, seq, seq)),
+        TensorSpec("up_ctx", dtype, t_bshd), TensorSpec("up_q", dtype, t_bhsd), TensorSpec("up_k", dtype, t_bhsd),
+        TensorSpec("up_v", dtype, t_bhsd),
+    ]
+    ops = ln_backward("l2_", "h2", "dy2", "gamma2", "mu2", "rstd2") + [
+        _op("dbias2", "reduce_sum", "l2_dxc", axis=0),
+        _op("f_z", "add", "ffn1_pre", "bias1"), _op("f_d", "gelu_tanh_grad", "f_z"), _op("f_dx", "mul", "up_act", "f_d"),
+        _op("f_dxc", "convert", "f_dx", dtype=dtype), _op("dbias1", "reduce_sum", "f_dxc", axis=0),
+        _op("dy1", "add", "l2_dxc", "up_l1"),
+    ] + ln_backward("l1_", "h1", "dy1", "gamma1", "mu1", "rstd1") + [
+        _op("dbias_o", "reduce_sum", "l1_dxc", axis=0),
+        _op("d_ctx", "transpose", "up_ctx", perm=(0, 2, 1, 3)),
+        _op("a_p", "mul", "probs", "up_probs"), _op("a_s", "reduce_sum", "a_p", axis=3), _op("a_d", "sub", "up_probs", "a_s"),
+        _op("a_ds", "mul", "probs", "a_d"), _op("d_scores", "scale", "a_ds", value=float(dim) ** -0.5),
+        _op("d_q", "transpose", "up_q", perm=(0, 2, 1, 3)), _op("d_k", "transpose", "up_k", perm=(0, 2, 1, 3)),
+        _op("d_v", "transpose", "up_v", perm=(0, 2, 1, 3)),
+    ]
+    outputs = [("l2_dxc", dtype), ("l2_dgamma", "f32"), ("l2_dbeta", "f32"), ("dbias2", "f32"), ("f_dxc", dtype), ("dbias1", "f32"),
+               ("l1_dxc", dtype), ("l1_dgamma", "f32"), ("l1_dbeta", "f32"), ("dbias_o", "f32"), ("d_ctx", dtype), ("d_scores", dtype),
+               ("d_q", dtype), ("d_k", dtype), ("d_v", dtype)]
+    return GraphSpec(name=f"pattern_transformer_block_backward_{dtype}_b{batch}_s{seq}", inputs=inputs, ops=ops, outputs=outputs)
+
+
 def random_multi_pattern(seed: int, rows: int = 24, cols: int = 32, segments: int = 3, dtype: str = "f32",
                          seg_ops: Tuple[int, int] = (3, 9)) -> GraphSpec:
     """Several random row patterns chained through transposes (each transpose turns the previous segment's
@@ -646,7 +714,9 @@ PACK_CONFIGS = {"P1": pack_members_p1}
 # Multi-pattern graphs for the fusion explorer.
 EXPLORE_CONFIGS = {"T1": lambda: transformer_block_graph(32, 128, 12, 64, 3072, "bf16"),
                    # the same block with the q/k/v projection biases added in front of the head split
-                   "T2": lambda: transformer_block_graph(32, 128, 12, 64, 3072, "bf16", projection_bias=True)}
+                   "T2": lambda: transformer_block_graph(32, 128, 12, 64, 3072, "bf16", projection_bias=True),
+                   # the backward pass through the block: row reductions, column sums and transposes side by side
+                   "T3": lambda: transformer_block_backward_graph(32, 128, 12, 64, 3072, "bf16")}
 
 # Row-local patterns outside the hand-written families, at transformer-block sizes (generated kernels; the interpreted row program beside them).
 GENERIC_CONFIGS = {
