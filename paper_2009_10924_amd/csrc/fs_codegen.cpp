@@ -103,15 +103,16 @@ std::string body_with_entry(const RowProgP& p, const char* entry, bool member) {
     s += fmt("static __device__ __forceinline__ void %s(const GenArgs& a, const uint32_t fs_block) {\n", entry);
   } else {
     s += "using namespace fsk;\n";
-    s += fmt("extern \"C\" __global__ void __launch_bounds__(256) %s(const GenArgs a) {\n", entry);
+    s += fmt("extern \"C\" __global__ void __launch_bounds__(%d) %s(const GenArgs a) {\n", block ? p.lanes_per_row : 256, entry);
     s += "  const uint32_t fs_block = blockIdx.x;\n";
   }
   const uint32_t R = p.rows_per_group > 1 ? (uint32_t)p.rows_per_group : 1u;
   const uint32_t CT = p.col_tiles > 1 ? (uint32_t)p.col_tiles : 1u;   // column tiles of cols / CT elements
   s += fmt("  typedef GenRow<%uu, %uu, %d, %d, %uu, %s, %uu, %uu> Row;\n", p.rows, p.cols / CT, p.vec, p.vecs_per_lane,
-           block ? 256u : (uint32_t)p.lanes_per_row, block ? "true" : "false", R, p.cols);
+           (uint32_t)p.lanes_per_row, block ? "true" : "false", R, p.cols);
   s += "  constexpr int KV = Row::KV;\n";
-  if (block && n_reductions > 0) s += fmt("  __shared__ float slots[%d];\n", 4 * n_reductions);
+  const int n_waves = block ? p.lanes_per_row / 64 : 4;
+  if (block && n_reductions > 0) s += fmt("  __shared__ float slots[%d];\n", n_waves * n_reductions);
   const bool looped = p.n_colsum > 0;
   const bool needs_lead = (p.full_bcast | p.rscal_bcast | p.out_perm) != 0;
   // the row's index along the leading axes, for the row object `rv`; names carry the prefix `pre`
@@ -220,7 +221,7 @@ std::string body_with_entry(const RowProgP& p, const char* entry, bool member) {
         continue;
       case PO_RSUM: case PO_RMAX: case PO_RSUMSQ: {
         const bool is_max = in.op == PO_RMAX;
-        const std::string slot = block ? fmt("slots + %d", 4 * reduction_no) : std::string("nullptr");
+        const std::string slot = block ? fmt("slots + %d", n_waves * reduction_no) : std::string("nullptr");
         s += fmt("  sacc = row.reduce<%s, %s, %s>(acc, %s);\n", is_max ? "OpMax" : "OpSum", is_max ? "true" : "false",
                  in.op == PO_RSUMSQ ? "true" : "false", slot.c_str());
         ++reduction_no;

@@ -207,6 +207,7 @@ bool build_softmax(const fs_graph& g, std::vector<Candidate>* out, PackForm* pac
     kc.barriers = 2;
     kc.lds_bytes_per_block = 32;
     finish_candidate(&c, "<generic>", kc);
+    c.fallback = true;   // three passes over the row: passed over where a kernel generated for the row length exists
     out->push_back(c);
   }
   return true;

@@ -76,6 +76,7 @@ static void fill_generic_form(const fs_graph& g, fs_plan* p) {
     if (c.launches.size() != 1) return false;
     const Launch& l = c.launches.front();
     if ((l.kernel != K_ROW_GENERATED && l.kernel != K_ROW_PROGRAM) || l.args.u.prog.n_colsum > 0) return false;
+    if (l.shape.block[0] != 256) return false;   // a packed kernel's workgroups have 256 threads
     p->generic.valid = true;
     p->generic.prog = l.args.u.prog;
     for (int k = 0; k < kMaxPtrs; ++k) p->generic.ptr[k] = l.ptr[k];
@@ -89,6 +90,7 @@ static void fill_generic_form(const fs_graph& g, fs_plan* p) {
   int best = -1;
   for (int i = 0; i < (int)cands.size(); ++i) {
     if (cands[i].launches.size() != 1 || cands[i].launches.front().kernel != K_ROW_GENERATED) continue;
+    if (cands[i].launches.front().shape.block[0] != 256) continue;
     predict(&cands[i]);
     if (best < 0 || cands[i].info.predicted_us < cands[best].info.predicted_us) best = i;
   }

@@ -677,8 +677,11 @@ std::vector<Shape> enumerate_shapes(const Compiler& c, int vec, bool interpretab
     const uint32_t K = (nvec + L - 1) / L;
     if (K >= 1 && K <= max_k && (L == 1 || (uint64_t)(L / 2) * K < nvec)) shapes.push_back({L, (int)K, false, true});
   }
-  const uint32_t KB = (nvec + 255) / 256;
-  if (KB <= max_k && 64ull * 2 < nvec) shapes.push_back({256, (int)KB, true, true});   // long rows: a workgroup per row
+  // long rows: a workgroup per row, of 256 threads, or of 512 / 1024 when that takes steps off every lane
+  for (uint32_t T : {256u, 512u, 1024u}) {
+    const uint32_t KB = (nvec + T - 1) / T;
+    if (KB <= max_k && 64ull * 2 < nvec && (T == 256 || nvec > (uint64_t)T)) shapes.push_back({T, (int)KB, true, true});
+  }
   if (c.n_colsum == 0) return shapes;
   // Without row reductions nothing ties the columns of a row together: a workgroup may take one tile of 64 or 128
   // vectors, so a lane keeps one or two vectors per value whatever the row length.
@@ -719,7 +722,7 @@ void fill_launch(const fs_graph& g, const Compiler& c, int vec, const Shape& s, 
   for (int i = 0; i < c.n_out; ++i) { l->ptr[kSlotOut + i].kind = BUF_OUTPUT; l->ptr[kSlotOut + i].slot = c.out_slot[i]; }
   for (int i = 0; i < c.n_rout; ++i) { l->ptr[kSlotRout + i].kind = BUF_OUTPUT; l->ptr[kSlotRout + i].slot = c.rout_slot[i]; }
   const uint32_t rows_per_block = (s.block ? 1 : 256 / s.L) * s.R;
-  l->shape.block[0] = 256;
+  l->shape.block[0] = s.block ? s.L : 256;
   l->shape.grid[0] = (c.p.rows + rows_per_block - 1) / rows_per_block * s.CT;
   l->shape.lds_bytes = (uint32_t)lds;
 }
@@ -753,8 +756,8 @@ KernelCost interpreted_cost(const Compiler& c, int vec, const Shape& s, int64_t 
   kc.valu_per_elem = 2.5 * c.vec_instr + dispatch + 2.0 * base.n_full;
   kc.trans_per_elem = c.trans;
   kc.lds_traffic_bytes = n * 4.0 * (c.reg_reads + c.reg_writes + base.n_full);
-  kc.waves = (double)grid * 4;
-  kc.waves_per_block = 4;
+  kc.waves_per_block = s.block ? (int32_t)(s.L / 64) : 4;
+  kc.waves = (double)grid * kc.waves_per_block;
   kc.bytes_in_flight_per_lane = (vec == 1 ? (double)in_bytes_per_elem : std::max(16.0, (double)vec * in_bytes_per_elem)) * s.K;
   kc.vgpr_estimate = 40 + 3 * kv + 4 * s.K * (base.n_full <= 1 ? 1 : (base.n_full <= 2 ? 2 : 4));
   int steps = 0;
@@ -778,7 +781,7 @@ void make_generated(const Compiler& c, int vec, const Shape& s, Candidate* cand)
   Launch& gl = cand->launches.back();
   gl.kernel = K_ROW_GENERATED;
   gl.shape.lds_bytes = 0;
-  const int32_t slots = s.block ? 16 * c.n_reductions : 0;
+  const int32_t slots = s.block ? (int32_t)(s.L / 64) * 4 * c.n_reductions : 0;
   cand->info.lds_bytes = slots;
   snprintf(cand->info.pattern, sizeof cand->info.pattern, "row_generated");
   snprintf(cand->info.kernel, sizeof cand->info.kernel, "row_generated<v%d,K%d,L%u,I%d,R%d>", vec, s.K, s.L, base.n_instr, base.n_regs);
@@ -873,7 +876,10 @@ bool make_candidate(const fs_graph& g, const Compiler& c, int vec, const Shape& 
   if (!s.generated) return true;
   make_generated(c, vec, s, cand);
   if (c.n_colsum > 0) add_column_sums(c, vec, s, bytes_min, cand);
-  return cand->cost.vgpr_estimate <= 256;   // more would not fit the register file without spilling
+  // more would not fit the register file without spilling: 512 registers per SIMD lane are shared by the workgroup's
+  // wavefronts on that SIMD (4 of a 1024-thread workgroup, 2 of a 512-thread one)
+  const int budget = s.block && s.L > 256 ? 512 / (int)(s.L / 256) : 256;
+  return cand->cost.vgpr_estimate <= budget;
 }
 
 }  // namespace

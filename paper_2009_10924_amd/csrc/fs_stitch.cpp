@@ -37,7 +37,17 @@ std::string build_stitched(const fs_graph& g, std::vector<Candidate>* out, PackF
     out->clear();
     *pack = PackForm();
     if (f.build(g, out, pack)) {
-      if (!out->empty()) return f.name;
+      if (!out->empty()) {
+        // a family that only has its slow catch-all kernel for these extents (ragged or very long rows): the row
+        // program's candidates join the list, and the choice passes the catch-all over while one of them stands
+        bool only_fallbacks = true;
+        for (const Candidate& c : *out) only_fallbacks = only_fallbacks && c.fallback;
+        if (only_fallbacks) {
+          std::vector<Candidate> more;
+          if (build_row_program(g, &more)) out->insert(out->end(), more.begin(), more.end());
+        }
+        return f.name;
+      }
       if (recognised.empty()) recognised = f.name;   // right shape of graph, but no compiled variant fits
     }
   }

@@ -107,8 +107,8 @@ __device__ __forceinline__ void unpack_step(const StepBits<2>& r, float (&v)[1],
   v[0] = (float)__builtin_bit_cast(_Float16, r.w);
 }
 
-// ROWS x COLS row space; VEC elements per lane and step; K steps per lane; L lanes per row
-// (a lane group of one wavefront), or the whole 256-thread workgroup when BLOCK.
+// ROWS x COLS row space; VEC elements per lane and step; K steps per lane; L lanes per row: a lane group of one
+// wavefront in a 256-thread workgroup, or, when BLOCK, the whole workgroup of L = 256, 512 or 1024 threads.
 // R: rows each lane group works through, one after the other (the kernel body runs R times with virtual
 // workgroup indices it * gridDim.x + blockIdx.x, so that at any moment the resident workgroups sweep one band of rows).
 // ROW_STRIDE > COLS: the pattern's rows are ROW_STRIDE elements long and the kernel works on column tiles of COLS
@@ -116,7 +116,7 @@ __device__ __forceinline__ void unpack_step(const StepBits<2>& r, float (&v)[1],
 template <uint32_t ROWS, uint32_t COLS, int VEC, int K, uint32_t L, bool BLOCK, uint32_t R = 1, uint32_t ROW_STRIDE = COLS>
 struct GenRow {
   static constexpr uint32_t NVEC = COLS / VEC;
-  static constexpr uint32_t LANES = BLOCK ? 256u : L;
+  static constexpr uint32_t LANES = L;
   static constexpr uint32_t ROWS_PER_WG = BLOCK ? 1u : 256u / L;
   // the row fills its lanes / the rows fill the workgroups: no clamp, no padding test
   static constexpr bool FULL_COLS = NVEC == LANES * K;
@@ -186,7 +186,7 @@ struct GenRow {
   }
 
   // all-reduce over the row: every lane of the row ends with the same value.  SQUARE: of the squared
-  // elements.  slot: 4 floats of LDS private to this reduction (BLOCK only).
+  // elements.  slot: one float per wavefront of the workgroup, LDS private to this reduction (BLOCK only).
   template <typename OP, bool IS_MAX, bool SQUARE>
   __device__ __forceinline__ float reduce(const float (&v)[KV], float* slot) const {
     // the lane's own elements are combined pairwise (a tree, not a chain): log2(KV) dependent steps instead of
@@ -208,7 +208,7 @@ struct GenRow {
       if (n & 1) t[n / 2] = t[n - 1];
     }
     const float r = t[0];
-    if constexpr (BLOCK) return block_allreduce<OP>(r, slot, 4);
+    if constexpr (BLOCK) return block_allreduce<OP>(r, slot, (int)(L / 64u));
     else return group_allreduce<OP>(r, (int)L);
   }
 
@@ -231,7 +231,7 @@ struct GenRow {
       // a workgroup per row: every lane owns its columns alone, the sums over the workgroup's rows are complete
 #pragma unroll
       for (int k = 0; k < K; ++k) {
-        const uint32_t at = (threadIdx.x + k * 256u) * VEC;
+        const uint32_t at = (threadIdx.x + k * L) * VEC;
         if (FULL_COLS || at < COLS) {
 #pragma unroll
           for (int e = 0; e < VEC; ++e) dst[at + e] = sum[k * VEC + e];

@@ -135,6 +135,28 @@ def test_column_sums_beside_row_work(rows, cols, dtype):
         note(f"{spec.name}: {info['kernel']}, {info['n_candidates']} shapes, worst {worst}")
 
 
+@pytest.mark.parametrize("rows,cols,dtype", [(8, 16384, "bf16"), (5, 32768, "f16"), (3, 20000, "f32"), (4, 24576, "bf16")])
+def test_long_rows_on_workgroups_of_512_and_1024_threads(rows, cols, dtype):
+    """Rows beyond 256 threads x 8 vectors: generated kernels put 512 or 1024 threads on a row (reductions through LDS
+    over 8 or 16 wavefronts)."""
+    if not B.codegen_available():
+        pytest.skip("workgroups wider than 256 threads exist as generated kernels only")
+    from workloads import softmax_graph
+    for spec in (layernorm_stats_graph(rows, cols, in_dtype=dtype, out_dtype=dtype, with_variance=True), silu_gate_graph(rows, cols, dtype),
+                 softmax_graph(rows, cols, dtype)):
+        g = B.Graph.from_spec(spec)
+        info = B.Plan(g, "auto").info
+        if spec.name.startswith("softmax") and info["pattern"] == "softmax":
+            continue                                    # the softmax family's own block kernel still holds this row
+        if "layernorm_stats" in spec.name and cols > 24576 and info["scheme"] == "unfused":
+            continue                                    # three live rows of this length do not fit 128 registers per lane
+        assert info["pattern"] == "row_generated" and info["block"][0] in (512, 1024), (spec.name, info)
+        inp = make_inputs(spec, seed=1)
+        ref = O.evaluate(spec, inp)
+        worst = all_candidates(spec, inp, ref, {name: O.rms(ref[name]) for name, _ in spec.outputs}, repeat=2)
+        note(f"{spec.name}: {info['kernel']} on {info['block'][0]} threads, worst {worst}")
+
+
 @pytest.mark.parametrize("seed", range(48))
 def test_random_row_patterns(seed):
     dtype = ("f32", "f16", "bf16")[seed % 3]

@@ -284,7 +284,15 @@ def test_patterns_that_are_not_row_local_are_refused():
     spec = GraphSpec("pattern_w", [TensorSpec("x", "f32", (4, 6, 16)), TensorSpec("m", "f32", (4, 1, 16))],
                      [OpSpec("a", "add", ("x", "m")), OpSpec("e", "exp", ("m",))], [("a", "f32"), ("e", "f32")])
     assert B.Plan(B.Graph.from_spec(spec), "auto").info["scheme"] == "unfused"
-    # row too long for the register file in LDS: falls back as well
-    spec = GraphSpec("pattern_z", [TensorSpec("x", "f32", (2, 1 << 15))],
+    # a row too long for one workgroup's registers (1024 threads x 8 vectors at most) falls back as well
+    spec = GraphSpec("pattern_z", [TensorSpec("x", "f32", (2, 1 << 17))],
                      [OpSpec("e", "exp", ("x",)), OpSpec("y", "mul", ("e", "x"))], [("y", "f32")])
     assert B.Plan(B.Graph.from_spec(spec), "auto").info["scheme"] == "unfused"
+    # ... while 32768 floats fit 1024 threads (generated kernels) but not the interpreter's 256
+    spec = GraphSpec("pattern_z", [TensorSpec("x", "f32", (2, 1 << 15))],
+                     [OpSpec("e", "exp", ("x",)), OpSpec("y", "mul", ("e", "x"))], [("y", "f32")])
+    with B.codegen(False):
+        assert B.Plan(B.Graph.from_spec(spec), "auto").info["scheme"] == "unfused"
+    if B.codegen_available():
+        info = B.Plan(B.Graph.from_spec(spec), "auto").info
+        assert info["scheme"] == "lds" and info["block"][0] == 1024
