@@ -92,6 +92,56 @@ std::string generated_kernel_entry(const RowProgP& p) {
 std::string generate_row_kernel_body(const RowProgP& p) { return body_with_entry(p, generated_kernel_entry(p).c_str()); }
 
 namespace {
+// Source text of one instruction of the accumulator machine (see ProgInstr): an unrolled loop over the lane's elements
+// for full-shaped work, a scalar statement for per-row work, a call into GenRow for reductions and stores.
+std::string instruction_text(const RowProgP& p, const ProgInstr& in, bool block, int n_waves, int* reduction_no) {
+  std::string t;
+  const bool scalar = (in.flags & PF_SCALAR) != 0, keep = (in.flags & PF_KEEP) != 0;
+  switch (in.op) {
+    case PO_STORE:
+      if ((p.out_perm >> in.dst) & 1u)   // stored through a folded transpose: the row lands at its permuted place
+        t += fmt("  row.store_at<%s>(a.out[%d], %s, acc);\n", storage_type(in.aux), in.dst, stretched_row(p.oms[in.dst]).c_str());
+      else
+        t += fmt("  row.store<%s>(a.out[%d], acc);\n", storage_type(in.aux), in.dst);
+      return t;
+    case PO_STORE_SCAL:
+      t += fmt("  row.store_scalar<%s>(a.rout[%d], sacc);\n", storage_type(in.aux), in.dst);
+      return t;
+    case PO_COLSUM:
+      t += fmt("  row.colsum_add(acc, cs%d);\n", in.dst);
+      return t;
+    case PO_RSUM: case PO_RMAX: case PO_RSUMSQ: {
+      const bool is_max = in.op == PO_RMAX;
+      const std::string slot = block ? fmt("slots + %d", n_waves * *reduction_no) : std::string("nullptr");
+      t += fmt("  sacc = row.reduce<%s, %s, %s>(acc, %s);\n", is_max ? "OpMax" : "OpSum", is_max ? "true" : "false",
+               in.op == PO_RSUMSQ ? "true" : "false", slot.c_str());
+      ++*reduction_no;
+      if (keep) t += fmt("  s%d = sacc;\n", in.dst);
+      return t;
+    }
+    default:
+      break;
+  }
+  if (scalar) {
+    const std::string b = in.b_kind == PK_SCAL ? fmt("s%d", in.b) : (in.b_kind == PK_SACC ? std::string("sacc") : literal(in.imm));
+    t += "  sacc = " + expression(in.op, "sacc", b, in.aux) + ";\n";
+    if (keep) t += fmt("  s%d = sacc;\n", in.dst);
+    return t;
+  }
+  std::string b;
+  switch (in.b_kind) {
+    case PK_REG: b = fmt("r%d[j]", in.b); break;
+    case PK_COL: b = fmt("c%d[j]", in.b); break;
+    case PK_ACC: b = "acc[j]"; break;
+    case PK_SCAL: b = fmt("s%d", in.b); break;
+    case PK_SACC: b = "sacc"; break;
+    default: b = literal(in.imm); break;
+  }
+  t += "#pragma unroll\n  for (int j = 0; j < KV; ++j) acc[j] = " + expression(in.op, "acc[j]", b, in.aux) + ";\n";
+  if (keep) t += fmt("#pragma unroll\n  for (int j = 0; j < KV; ++j) r%d[j] = acc[j];\n", in.dst);
+  return t;
+}
+
 std::string body_with_entry(const RowProgP& p, const char* entry, bool member) {
   const bool block = p.lanes_per_row > 64;
   int n_reductions = 0;
@@ -203,52 +253,7 @@ std::string body_with_entry(const RowProgP& p, const char* entry, bool member) {
 
   // ---- the pattern's ops, in the order of the instruction list
   int reduction_no = 0;
-  for (int i = 0; i < p.n_instr; ++i) {
-    const ProgInstr& in = p.instr[i];
-    const bool scalar = (in.flags & PF_SCALAR) != 0, keep = (in.flags & PF_KEEP) != 0;
-    switch (in.op) {
-      case PO_STORE:
-        if ((p.out_perm >> in.dst) & 1u)   // stored through a folded transpose: the row lands at its permuted place
-          s += fmt("  row.store_at<%s>(a.out[%d], %s, acc);\n", storage_type(in.aux), in.dst, stretched_row(p.oms[in.dst]).c_str());
-        else
-          s += fmt("  row.store<%s>(a.out[%d], acc);\n", storage_type(in.aux), in.dst);
-        continue;
-      case PO_STORE_SCAL:
-        s += fmt("  row.store_scalar<%s>(a.rout[%d], sacc);\n", storage_type(in.aux), in.dst);
-        continue;
-      case PO_COLSUM:
-        s += fmt("  row.colsum_add(acc, cs%d);\n", in.dst);
-        continue;
-      case PO_RSUM: case PO_RMAX: case PO_RSUMSQ: {
-        const bool is_max = in.op == PO_RMAX;
-        const std::string slot = block ? fmt("slots + %d", n_waves * reduction_no) : std::string("nullptr");
-        s += fmt("  sacc = row.reduce<%s, %s, %s>(acc, %s);\n", is_max ? "OpMax" : "OpSum", is_max ? "true" : "false",
-                 in.op == PO_RSUMSQ ? "true" : "false", slot.c_str());
-        ++reduction_no;
-        if (keep) s += fmt("  s%d = sacc;\n", in.dst);
-        continue;
-      }
-      default:
-        break;
-    }
-    if (scalar) {
-      const std::string b = in.b_kind == PK_SCAL ? fmt("s%d", in.b) : (in.b_kind == PK_SACC ? std::string("sacc") : literal(in.imm));
-      s += "  sacc = " + expression(in.op, "sacc", b, in.aux) + ";\n";
-      if (keep) s += fmt("  s%d = sacc;\n", in.dst);
-      continue;
-    }
-    std::string b;
-    switch (in.b_kind) {
-      case PK_REG: b = fmt("r%d[j]", in.b); break;
-      case PK_COL: b = fmt("c%d[j]", in.b); break;
-      case PK_ACC: b = "acc[j]"; break;
-      case PK_SCAL: b = fmt("s%d", in.b); break;
-      case PK_SACC: b = "sacc"; break;
-      default: b = literal(in.imm); break;
-    }
-    s += "#pragma unroll\n  for (int j = 0; j < KV; ++j) acc[j] = " + expression(in.op, "acc[j]", b, in.aux) + ";\n";
-    if (keep) s += fmt("#pragma unroll\n  for (int j = 0; j < KV; ++j) r%d[j] = acc[j];\n", in.dst);
-  }
+  for (int i = 0; i < p.n_instr; ++i) s += instruction_text(p, p.instr[i], block, n_waves, &reduction_no);
   if (looped) {
     // the next row's reductions reuse this row's LDS slots: nobody may still be reading them
     if (block && n_reductions > 0) s += "  __syncthreads();\n";
