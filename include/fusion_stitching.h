@@ -285,6 +285,7 @@ typedef struct fs_explore_opts {
   int32_t beam_width;   /* candidate fusion plans kept while traversing the graph, 1..16    */
   int32_t no_packing;   /* 1: leave independent launch-bound patterns in launches of their own */
   int32_t no_remote_fusion; /* 1: do not merge patterns that no edge joins (Section 5.2, remote fusion) */
+  int32_t no_joint_folds;   /* 1: every pattern with column sums finishes them in launches of its own     */
 } fs_explore_opts;
 
 typedef struct fs_program_info {
@@ -295,7 +296,8 @@ typedef struct fs_program_info {
   int32_t n_kernels;      /* kernel launches per fs_program_execute                        */
   int32_t n_packs;        /* packed launches among the steps                               */
   int32_t beam_plans;     /* candidate plans the final choice was made among               */
-  int32_t reserved;
+  int32_t n_joint_folds;  /* column-sum folds moved behind the last step and issued as one launch (per 8): sums over
+                             all rows that nothing in the graph reads need only be complete when the program ends */
   int64_t workspace_bytes;   /* device scratch fs_program_execute needs                    */
   int64_t bytes_min;         /* graph inputs read once + graph outputs written once        */
   int64_t bytes_moved_model; /* bytes the plan's kernels move, tensors between patterns included */

@@ -102,13 +102,14 @@ class fs_pack_info(C.Structure):
 
 
 class fs_explore_opts(C.Structure):
-    _fields_ = [("top_k", C.c_int32), ("beam_width", C.c_int32), ("no_packing", C.c_int32), ("no_remote_fusion", C.c_int32)]
+    _fields_ = [("top_k", C.c_int32), ("beam_width", C.c_int32), ("no_packing", C.c_int32), ("no_remote_fusion", C.c_int32),
+                ("no_joint_folds", C.c_int32)]
 
 
 class fs_program_info(C.Structure):
     _fields_ = [
         ("n_ops", C.c_int32), ("n_patterns", C.c_int32), ("n_single_ops", C.c_int32), ("n_steps", C.c_int32),
-        ("n_kernels", C.c_int32), ("n_packs", C.c_int32), ("beam_plans", C.c_int32), ("reserved", C.c_int32),
+        ("n_kernels", C.c_int32), ("n_packs", C.c_int32), ("beam_plans", C.c_int32), ("n_joint_folds", C.c_int32),
         ("workspace_bytes", C.c_int64), ("bytes_min", C.c_int64), ("bytes_moved_model", C.c_int64),
         ("f_total_us", C.c_double), ("predicted_us", C.c_double), ("predicted_unfused_us", C.c_double),
     ]
@@ -425,10 +426,11 @@ def explore_score_ex(graph: Graph, ops: Sequence[int]):
 class Program:
     """Fusion plan found for a multi-pattern graph, and its execution."""
 
-    def __init__(self, graph: Graph, top_k: int = 0, beam_width: int = 0, no_packing: bool = False, no_remote_fusion: bool = False):
+    def __init__(self, graph: Graph, top_k: int = 0, beam_width: int = 0, no_packing: bool = False, no_remote_fusion: bool = False,
+                 no_joint_folds: bool = False):
         self._lib = load()
         self._graph = graph
-        opts = fs_explore_opts(top_k, beam_width, 1 if no_packing else 0, 1 if no_remote_fusion else 0)
+        opts = fs_explore_opts(top_k, beam_width, 1 if no_packing else 0, 1 if no_remote_fusion else 0, 1 if no_joint_folds else 0)
         h = C.c_void_p()
         _check(self._lib.fs_explore(graph.handle, C.byref(opts), C.byref(h)))
         self.handle = h

@@ -178,7 +178,10 @@ struct Explorer {
     for (int k = 0; k < op.n_in; ++k) bytes += (double)g.tensors[op.in[k]].numel() * dtype_bytes(g.tensors[op.in[k]].dtype);
     const Tensor& out = g.tensors[op.out];
     bytes += (double)out.numel() * dtype_bytes(out.output_slot >= 0 ? out.store_as : out.dtype);
-    return d.launch_s + d.mem_latency_s + bytes / (d.hbm_peak_Bps * d.stream_fraction);
+    // a sum over rows that different workgroups own takes a second launch to fold their partial sums
+    const bool across_rows = (op.opcode == FS_REDUCE_SUM || op.opcode == FS_REDUCE_MAX || op.opcode == FS_REDUCE_MEAN) &&
+                             op.axis != g.tensors[op.in[0]].rank - 1;
+    return d.launch_s * (across_rows ? 2.0 : 1.0) + d.mem_latency_s + bytes / (d.hbm_peak_Bps * d.stream_fraction);
   }
 
   // Delta-evaluator (Eq. 3): time saved by running the ops of `p` as one pattern.
@@ -488,13 +491,16 @@ struct fs_program {
     std::vector<BufRef> in, out;        // where each plan input / output lives: graph input, graph output or workspace offset
     int64_t plan_ws_offset = 0;
     int32_t pack = -1;                  // index into packs, -1 = runs on its own
+    size_t own_launches = 0;            // launches of the plan issued at the step itself (the rest are joint folds)
   };
+  struct JointFold { int step; size_t launch; };   // a K_COLFOLD launch of a step's plan, issued after the last step
   struct Pack {
     fs_pack* pack = nullptr;
     std::vector<int> steps;
   };
   std::vector<Step> steps;              // dependence order
   std::vector<Pack> packs;
+  std::vector<std::vector<JointFold>> joint_folds;   // one launch each, at most kFoldManyMax folds in it
   fs_program_info info{};
   int32_t n_inputs = 0, n_outputs = 0;
   ~fs_program() {
@@ -709,6 +715,39 @@ int64_t place_buffers(const fs_graph& g, fs_program* prog, const std::vector<int
   return fixed + arena.top;
 }
 
+// Column sums that nothing in the graph reads are finished by fold launches that only need to run before the
+// program ends: instead of one tiny launch (or two) after each pattern, all of them run as one launch after the
+// last step.  The plans' own workspaces, where the partial sums wait, are never shared between steps.
+void join_folds(const fs_graph& g, fs_program* prog) {
+  std::vector<fs_program::JointFold> found;
+  for (size_t si = 0; si < prog->steps.size(); ++si) {
+    fs_program::Step& s = prog->steps[si];
+    const std::vector<Launch>& launches = s.plan->candidates[s.plan->chosen].launches;
+    s.own_launches = launches.size();
+    if (s.pack >= 0) continue;
+    size_t first = launches.size();
+    while (first > 1 && launches[first - 1].kernel == K_COLFOLD) {
+      bool free_standing = true;
+      for (int k = 0; k < 3; ++k) {
+        const BufRef& r = launches[first - 1].ptr[k];
+        if (r.kind != BUF_OUTPUT) continue;
+        const Tensor& T = g.tensors[s.out[r.slot].slot];
+        if (T.output_slot < 0 || !T.consumers.empty()) free_standing = false;
+      }
+      if (!free_standing) break;
+      --first;
+    }
+    for (size_t l = first; l < launches.size(); ++l) found.push_back({(int)si, l});
+  }
+  if (found.size() < 2) return;   // one fold alone gains nothing by moving
+  for (const fs_program::JointFold& f : found) {
+    fs_program::Step& s = prog->steps[f.step];
+    s.own_launches = std::min(s.own_launches, f.launch);
+    if (prog->joint_folds.empty() || prog->joint_folds.back().size() >= (size_t)kFoldManyMax) prog->joint_folds.emplace_back();
+    prog->joint_folds.back().push_back(f);
+  }
+}
+
 void fill_info(const Explorer& ex, fs_program* prog, int32_t beam_plans, double f_total_us, int64_t workspace_bytes) {
   fs_program_info& I = prog->info;
   I.n_ops = ex.n;
@@ -732,6 +771,12 @@ void fill_info(const Explorer& ex, fs_program* prog, int32_t beam_plans, double 
       I.predicted_us += pi.predicted_us;
       ++I.n_steps;
     }
+  }
+  for (const std::vector<fs_program::JointFold>& j : prog->joint_folds) {
+    // the estimate keeps the folds' own times and drops the launches they no longer pay for
+    I.n_joint_folds += (int32_t)j.size();
+    I.n_kernels -= (int32_t)j.size() - 1;
+    I.predicted_us -= (double)(j.size() - 1) * device().launch_s * 1e6;
   }
   I.n_packs = (int32_t)prog->packs.size();
   for (int o = 0; o < ex.n; ++o) I.predicted_unfused_us += ex.t_single(o) * 1e6;
@@ -768,7 +813,7 @@ fs_status fs_explore(const fs_graph* g, const fs_explore_opts* opts, fs_program*
   if (!g || !out) return fail(FS_ERR_INVALID_ARG, "fs_explore: null argument");
   if (!g->finalized) return fail(FS_ERR_INVALID_ARG, "fs_explore: graph is not finalized");
   Explorer ex(*g);
-  bool pack_tiny = true, remote_fusion = true;
+  bool pack_tiny = true, remote_fusion = true, joint_folds = true;
   if (opts) {
     if (opts->top_k < 0 || opts->beam_width < 0 || opts->top_k > 16 || opts->beam_width > 16)
       return fail(FS_ERR_INVALID_ARG, "fs_explore: top_k and beam_width must be 0 (default 3) or 1..16");
@@ -776,6 +821,7 @@ fs_status fs_explore(const fs_graph* g, const fs_explore_opts* opts, fs_program*
     if (opts->beam_width > 0) ex.beam_width = opts->beam_width;
     pack_tiny = opts->no_packing == 0;
     remote_fusion = opts->no_remote_fusion == 0;
+    joint_folds = opts->no_joint_folds == 0;
   }
   ex.explore_patterns();
   const std::vector<Explorer::PlanSet> plans = ex.beam();
@@ -827,6 +873,8 @@ fs_status fs_explore(const fs_graph* g, const fs_explore_opts* opts, fs_program*
   std::vector<int> pos(prog->steps.size());   // where in the order a step's kernel is issued (packed members: at the first member)
   for (size_t s = 0; s < pos.size(); ++s) pos[s] = (int)s;
   if (pack_tiny) decide_packs(*g, prog, &pos);
+  for (fs_program::Step& s : prog->steps) s.own_launches = s.plan->candidates[s.plan->chosen].launches.size();
+  if (joint_folds) join_folds(*g, prog);
   const int64_t workspace = place_buffers(*g, prog, pos);
   fill_info(ex, prog, (int32_t)plans.size(), built[best].f, workspace);
   prog->n_inputs = (int32_t)g->inputs.size();
@@ -906,8 +954,36 @@ fs_status fs_program_execute(const fs_program* p, const void* const* inputs, voi
     for (const BufRef& r : s.in) in.push_back(address(r));
     for (const BufRef& r : s.out) out.push_back(address(r));
     const int64_t need = s.plan->candidates[s.plan->chosen].info.workspace_bytes;
-    const fs_status st = fs_execute(s.plan, in.data(), out.data(), need > 0 ? ws + s.plan_ws_offset : nullptr, (size_t)need, hip_stream);
+    const fs_status st = run_launches(s.plan, in.data(), out.data(), need > 0 ? ws + s.plan_ws_offset : nullptr, hip_stream, s.own_launches);
     if (st != FS_OK) return st;
+  }
+  for (const std::vector<fs_program::JointFold>& joint : p->joint_folds) {
+    FoldManyP t{};
+    uint32_t blocks = 0;
+    for (int k = 0; k < kFoldManyMax; ++k) t.first_block[k] = 0xffffffffu;
+    for (size_t k = 0; k < joint.size(); ++k) {
+      const fs_program::Step& s = p->steps[joint[k].step];
+      const Launch& l = s.plan->candidates[s.plan->chosen].launches[joint[k].launch];
+      void* ptr[3];
+      for (int a = 0; a < 3; ++a) {
+        const BufRef& r = l.ptr[a];
+        ptr[a] = r.kind == BUF_INPUT ? address(s.in[r.slot]) : r.kind == BUF_OUTPUT ? address(s.out[r.slot])
+                 : r.kind == BUF_WORKSPACE ? (void*)(ws + s.plan_ws_offset + r.offset) : nullptr;
+      }
+      const GeluP& f = l.args.u.gelu;
+      t.partials[k] = static_cast<const float*>(ptr[0]);
+      t.out0[k] = static_cast<float*>(ptr[1]);
+      t.out1[k] = static_cast<float*>(ptr[2]);
+      t.first_block[k] = blocks;
+      t.n[k] = f.n_row_tiles;
+      t.width[k] = f.fold_cols;
+      t.stride[k] = f.cols;
+      t.split[k] = f.fold_split;
+      t.quads[k] = f.fold_quads;
+      blocks += l.shape.grid[0];
+    }
+    const int err = launch_fold_many(t, blocks, hip_stream);
+    if (err != 0) return fail(FS_ERR_HIP, "fs_program_execute: launching the joint fold failed: %s", hip_error_text(err));
   }
   return FS_OK;
 }

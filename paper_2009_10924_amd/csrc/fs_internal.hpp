@@ -170,6 +170,9 @@ bool codegen_enabled();
 // the chosen candidate's kernel; if that fails, or the kernel spills registers, it moves the choice to the
 // next best candidate (unless the caller fixed the candidate, then it fails).
 fs_status create_plan(const fs_graph* g, int32_t scheme, const fs_plan_opts* opts, bool complete, fs_plan** out);
+// The first `n_launches` launches of the plan's chosen candidate (arguments already validated by the caller).
+fs_status run_launches(const fs_plan* p, const void* const* inputs, void* const* outputs, void* workspace, void* hip_stream,
+                       size_t n_launches);
 fs_status complete_plan(fs_plan* p);
 int64_t graph_bytes_min(const fs_graph& g);
 // Multiply-high constants for n / d with n < 2^31 (d == 0 in the result marks "no usable constants").

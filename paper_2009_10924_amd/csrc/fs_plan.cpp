@@ -143,6 +143,32 @@ fs_status complete_plan(fs_plan* p) {
 
 using namespace fs;
 
+fs_status fs::run_launches(const fs_plan* p, const void* const* inputs, void* const* outputs, void* workspace, void* hip_stream,
+                       size_t n_launches) {
+  const Candidate& c = p->candidates[p->chosen];
+  for (size_t li = 0; li < n_launches && li < c.launches.size(); ++li) {
+    const Launch& l = c.launches[li];
+    KernelArgs a = l.args;
+    for (int k = 0; k < kMaxPtrs; ++k) {
+      switch (l.ptr[k].kind) {
+        case BUF_INPUT: a.p[k] = const_cast<void*>(inputs[l.ptr[k].slot]); break;
+        case BUF_OUTPUT: a.p[k] = outputs[l.ptr[k].slot]; break;
+        case BUF_WORKSPACE: a.p[k] = static_cast<char*>(workspace) + l.ptr[k].offset; break;
+        default: a.p[k] = nullptr; break;
+      }
+    }
+    int err;
+    if (l.kernel == K_ROW_GENERATED) {
+      if (!l.gen) return fail(FS_ERR_INVALID_ARG, "fs_execute: the plan's generated kernel was never compiled");
+      err = gen_launch(l.gen.get(), a.p, sizeof(void*) * kGenArgPtrs, l.shape, hip_stream);
+    } else {
+      err = launch_kernel(l.kernel, a, l.shape, hip_stream);
+    }
+    if (err != 0) return fail(FS_ERR_HIP, "fs_execute: launching %s failed: %s", kernel_name(l.kernel), hip_error_text(err));
+  }
+  return FS_OK;
+}
+
 fs_status fs::create_plan(const fs_graph* g, int32_t scheme, const fs_plan_opts* opts, bool complete, fs_plan** out) {
   if (!g || !out) return fail(FS_ERR_INVALID_ARG, "fs_plan_create: null argument");
   if (!g->finalized) return fail(FS_ERR_INVALID_ARG, "fs_plan_create: graph is not finalized");
@@ -362,26 +388,7 @@ fs_status fs_execute(const fs_plan* p, const void* const* inputs, void* const* o
       return fail(FS_ERR_WORKSPACE, "fs_execute: workspace of %lld bytes needed, %zu given", (long long)c.info.workspace_bytes, workspace_bytes);
     if ((uintptr_t)workspace & 15u) return fail(FS_ERR_ALIGN, "fs_execute: workspace is not 16-byte aligned");
   }
-  for (const Launch& l : c.launches) {
-    KernelArgs a = l.args;
-    for (int k = 0; k < kMaxPtrs; ++k) {
-      switch (l.ptr[k].kind) {
-        case BUF_INPUT: a.p[k] = const_cast<void*>(inputs[l.ptr[k].slot]); break;
-        case BUF_OUTPUT: a.p[k] = outputs[l.ptr[k].slot]; break;
-        case BUF_WORKSPACE: a.p[k] = static_cast<char*>(workspace) + l.ptr[k].offset; break;
-        default: a.p[k] = nullptr; break;
-      }
-    }
-    int err;
-    if (l.kernel == K_ROW_GENERATED) {
-      if (!l.gen) return fail(FS_ERR_INVALID_ARG, "fs_execute: the plan's generated kernel was never compiled");
-      err = gen_launch(l.gen.get(), a.p, sizeof(void*) * kGenArgPtrs, l.shape, hip_stream);
-    } else {
-      err = launch_kernel(l.kernel, a, l.shape, hip_stream);
-    }
-    if (err != 0) return fail(FS_ERR_HIP, "fs_execute: launching %s failed: %s", kernel_name(l.kernel), hip_error_text(err));
-  }
-  return FS_OK;
+  return run_launches(p, inputs, outputs, workspace, hip_stream, c.launches.size());
 }
 
 fs_status fs_stream_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {

@@ -237,7 +237,14 @@ struct Compiler {
     for (size_t i = 0; i < n_ops; ++i) {
       const Op& op = g.ops[i];
       const Tensor& out = g.tensors[op.out];
-      if (folded[i]) continue;
+      if (folded[i]) {
+        // a transposed view that is itself an output: the pattern's work on it is the move
+        if (op.opcode == FS_TRANSPOSE && view_op[op.out] == (int32_t)i && out.output_slot >= 0) {
+          if (!store_output(op.out, true)) return false;
+          if (!planning && val[op.out].last_read == (int)i) release(op.out);
+        }
+        continue;
+      }
       if (is_colsum[i]) {
         if (!planning && n_colsum >= kProgMaxColSums) return false;
         if (!load(root_of(op.in[0]), false)) return false;
@@ -418,7 +425,7 @@ struct Compiler {
         if (cls.size() >= kProgMaxOperands) return false;
         cls.push_back(t);
       }
-      if (T.output_slot >= 0) return false;   // an input handed straight to an output is no computation
+      if (T.output_slot >= 0 && view_src[t] < 0) return false;   // an input handed straight to an output is no computation
     }
     // lane geometry by elements: the narrowest vector input still moves in 128-bit accesses where the row length
     // allows it; otherwise 4 elements per step (16-bit inputs then move in 64-bit accesses) or, for rows that are
@@ -468,7 +475,11 @@ struct Compiler {
           break;
         }
         case FS_TRANSPOSE:
-          if (view_src[op.out] >= 0) { view_fold[i] = 1; continue; }   // folded into the input's addressing
+          if (view_src[op.out] >= 0) {   // folded into the input's addressing
+            view_fold[i] = 1;
+            if (out.output_slot >= 0) reads[i].push_back(op.out);   // stored as it is read
+            continue;
+          }
           if (stored_via[op.out] != (int32_t)i) return false;
           is_alias[i] = 1;                                              // folded into the store
           break;
@@ -494,7 +505,10 @@ struct Compiler {
     for (int t : g.outputs) {
       if (g.tensors[t].producer < 0) return false;
       if (stored_via[t] >= 0) continue;   // a permutation of the row space: every row is written once
-      if (val[t].kind != V_COL && stretched_rows(g.tensors[t])) return false;   // an output must own every row it is stored to
+      if (is_colsum[g.tensors[t].producer]) continue;   // one value per column, left by the fold launch
+      const int shape = classify(g.tensors[t]);
+      if (shape != V_FULL && shape != V_RSCAL) return false;   // a per-column value has no row to be stored to
+      if (stretched_rows(g.tensors[t])) return false;   // an output must own every row it is stored to
     }
     // peepholes.  (1) square feeding only a row sum / mean: the reduction squares on the fly, so the
     // accumulator keeps the un-squared value.  (2) a convert whose only reader is the store of the same

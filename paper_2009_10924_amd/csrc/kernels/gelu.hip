@@ -168,12 +168,11 @@ __global__ void __launch_bounds__(WAVES * 64) k_bias_gelu_dbias(const T* __restr
 // order with eight independent loads in flight, LDS folds the G groups in order.  Few
 // partial rows: (Q,G) = (16,16); many: (4,64), so a thread still needs one batch of loads.
 template <int Q, int G>
-__global__ void __launch_bounds__(256) k_colfold(const float* __restrict__ partials, float* __restrict__ out0,
-                                                 float* __restrict__ out1, GeluP p) {
-  __shared__ f32x4 sm[G][Q];
+__device__ __forceinline__ void fold_tile(const float* __restrict__ partials, float* __restrict__ out0, float* __restrict__ out1,
+                                          uint32_t n, uint32_t width, uint32_t stride, uint32_t split, uint32_t block,
+                                          f32x4* __restrict__ sm) {
   const uint32_t q = threadIdx.x % Q, g = threadIdx.x / Q;
-  const uint32_t col = (blockIdx.x * Q + q) * 4u;
-  const uint32_t n = p.n_row_tiles, width = p.fold_cols, stride = p.cols;   // stride >= width: a slice of wider partial rows
+  const uint32_t col = (block * Q + q) * 4u;
   f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
   if (col < width) {
     uint32_t t = g;
@@ -186,16 +185,47 @@ __global__ void __launch_bounds__(256) k_colfold(const float* __restrict__ parti
     }
     for (; t < n; t += G) s += *reinterpret_cast<const f32x4*>(partials + (size_t)t * stride + col);
   }
-  sm[g][q] = s;
+  sm[g * Q + q] = s;
   __syncthreads();
   if (g == 0 && col < width) {
-    f32x4 v = sm[0][q];
+    f32x4 v = sm[q];
 #pragma unroll
-    for (int k = 1; k < G; ++k) v += sm[k][q];
-    // fold_split is a multiple of 4, so a quad never straddles the two outputs
-    float* dst = col < p.fold_split ? out0 + col : out1 + (col - p.fold_split);
+    for (int k = 1; k < G; ++k) v += sm[k * Q + q];
+    // the split is a multiple of 4, so a quad never straddles the two outputs
+    float* dst = col < split ? out0 + col : out1 + (col - split);
     *reinterpret_cast<f32x4*>(dst) = v;
   }
+}
+
+template <int Q, int G>
+__global__ void __launch_bounds__(256) k_colfold(const float* __restrict__ partials, float* __restrict__ out0,
+                                                 float* __restrict__ out1, GeluP p) {
+  __shared__ f32x4 sm[G * Q];
+  // stride >= width: a fold may take a slice of wider partial rows
+  fold_tile<Q, G>(partials, out0, out1, p.n_row_tiles, p.fold_cols, p.cols, p.fold_split, blockIdx.x, sm);
+}
+
+// Several independent folds in one launch: workgroups [first_block[i], first_block[i+1]) run fold i.  The table
+// is read from the kernel-argument segment with wave-uniform addresses (indexing the by-value parameter would
+// make the compiler copy it to per-lane scratch first).
+typedef const FoldManyP __attribute__((address_space(4))) * ConstFolds;
+
+__global__ void __launch_bounds__(256) k_colfold_many(const FoldManyP table_in_kernarg) {
+  __shared__ f32x4 sm[256];
+  ConstFolds tab = (ConstFolds)__builtin_amdgcn_kernarg_segment_ptr();
+  const uint32_t b = blockIdx.x;
+  int i = -1;
+#pragma unroll
+  for (int j = 0; j < kFoldManyMax; ++j) i += b >= tab->first_block[j] ? 1 : 0;   // first_block[0] = 0, unused ones ~0
+  i = __builtin_amdgcn_readfirstlane(i);
+  const float* partials = tab->partials[i];
+  float* out0 = tab->out0[i];
+  float* out1 = tab->out1[i];
+  const uint32_t block = b - tab->first_block[i];
+  if (tab->quads[i] == 4)
+    fold_tile<4, 64>(partials, out0, out1, tab->n[i], tab->width[i], tab->stride[i], tab->split[i], block, sm);
+  else
+    fold_tile<16, 16>(partials, out0, out1, tab->n[i], tab->width[i], tab->stride[i], tab->split[i], block, sm);
 }
 
 }  // namespace fsk
@@ -218,6 +248,13 @@ const void* gelu_sym(int32_t kernel, const GeluP& p) {
   return p.ticket ? dbias_sym<T, true>(p.waves, p.unroll) : dbias_sym<T, false>(p.waves, p.unroll);
 }
 }  // namespace
+
+int launch_fold_many(const FoldManyP& table, uint32_t n_blocks, void* stream) {
+  if (n_blocks == 0) return 0;
+  FoldManyP t = table;
+  void* argv[1] = {&t};
+  return (int)hipLaunchKernel((const void*)k_colfold_many, dim3(n_blocks), dim3(256), argv, 0, static_cast<hipStream_t>(stream));
+}
 
 const void* gelu_kernel_symbol(int32_t kernel, const KernelArgs& a) {
   const GeluP& p = a.u.gelu;

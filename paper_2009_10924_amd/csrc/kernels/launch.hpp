@@ -274,6 +274,17 @@ struct KernelArgs {
   KernelArgs() { u.binary = BinaryP{}; }
 };
 
+// Up to kFoldManyMax K_COLFOLD jobs as one launch (each entry = that kernel's pointers and GeluP fields).
+constexpr int kFoldManyMax = 8;
+struct FoldManyP {
+  const float* partials[kFoldManyMax];
+  float* out0[kFoldManyMax];
+  float* out1[kFoldManyMax];
+  uint32_t first_block[kFoldManyMax];   // first workgroup of each job; [0] = 0, unused entries = 0xffffffff
+  uint32_t n[kFoldManyMax], width[kFoldManyMax], stride[kFoldManyMax], split[kFoldManyMax], quads[kFoldManyMax];
+};
+int launch_fold_many(const FoldManyP& table, uint32_t n_blocks, void* stream);
+
 struct KernelResources {
   int32_t vgprs = 0;       // architected vector registers per lane
   int32_t static_lds = 0;  // bytes

@@ -106,14 +106,15 @@ def test_plan_structure(name):
 
 
 def test_transformer_block_plan_is_the_hand_partition():
-    """With the compiled-in kernels alone the explorer finds the partition one would write by hand."""
+    """With the compiled-in kernels alone the explorer finds the partition one would write by hand (the three head-split
+    moves of q, k and v, which share a row space, go out as one interpreted row program)."""
     spec = transformer_block_graph(32, 128, 12, 64, 3072, "bf16")
     with B.codegen(False):
         prog = B.Program(B.Graph.from_spec(spec))
     steps = prog.patterns()
     names = sorted((s["info"]["pattern"], len(s["ops"])) for s in steps)
-    assert names == sorted([("transpose", 1)] * 4 + [("softmax", 7), ("layernorm", 12), ("bias_gelu", 2), ("layernorm", 12)])
-    assert prog.info["n_kernels"] == 8 and prog.info["workspace_bytes"] == 0   # every tensor between patterns is a graph output
+    assert names == sorted([("transpose", 1), ("row_program", 3), ("softmax", 7), ("layernorm", 12), ("bias_gelu", 2), ("layernorm", 12)])
+    assert prog.info["n_kernels"] == 6 and prog.info["workspace_bytes"] == 0   # every tensor between patterns is a graph output
     # the second LayerNorm reads what the first one stored
     order = [tuple(s["ops"]) for s in steps]
     assert order.index(tuple(range(11, 23))) < order.index(tuple(range(25, 37)))
@@ -135,6 +136,23 @@ def test_transformer_block_plan_with_generated_kernels_goes_beyond_the_hand_part
     big = max(steps, key=lambda s: len(s["ops"]))
     assert big["info"]["pattern"] == "row_generated" and tuple(big["ops"]) == tuple(range(11, 23)) + tuple(range(25, 37))
     assert sorted(o for s in steps for o in s["ops"]) == list(range(len(spec.ops)))
+
+
+def test_backward_block_folds_its_column_sums_in_one_launch_at_the_end():
+    """Bias and gain gradients are sums over all rows that nothing in the graph reads: their fold launches move behind
+    the last step and run as one; the two bias gradients whose operands are graph inputs share one pattern."""
+    if not B.codegen_available():
+        pytest.skip("column sums inside patterns need the run-time compiler")
+    from workloads import transformer_block_backward_graph
+    spec = transformer_block_backward_graph(3, 40, 4, 32, 256, "bf16")
+    g = B.Graph.from_spec(spec)
+    prog, apart = B.Program(g), B.Program(g, no_joint_folds=True)
+    assert prog.info["n_joint_folds"] >= 3 and apart.info["n_joint_folds"] == 0
+    assert prog.info["n_kernels"] == apart.info["n_kernels"] - prog.info["n_joint_folds"] + 1
+    assert prog.info["predicted_us"] < apart.info["predicted_us"]
+    assert [s["ops"] for s in prog.patterns()] == [s["ops"] for s in apart.patterns()]      # the patterns are the same
+    sums = [s for s in prog.patterns() if s["info"]["kernel"].endswith("+colfold")]
+    assert len(sums) >= 2 and all(s["info"]["n_kernels"] >= 2 for s in sums)                  # a plan alone keeps its folds
 
 
 def test_independent_launch_bound_patterns_share_one_packed_launch():

@@ -98,6 +98,44 @@ def test_transformer_block_backward(dims):
     note(f"transformer block backward {dims}: {info['n_ops']} ops -> {info['n_patterns']} patterns + {info['n_single_ops']} single ops, "
          f"{info['n_kernels']} launches {plans}, workspace {info['workspace_bytes']} B, worst {worst:.3f} of the bar")
     assert info["n_kernels"] < info["n_ops"] // 2
+    if B.codegen_available():
+        # the folds that finish the column sums run as one launch behind the last step; the sums are the same bits
+        assert info["n_joint_folds"] >= 4
+        inp = make_inputs(spec, seed=0)
+        joint, _ = run_program(spec, inp, repeat=1)
+        apart, p2 = run_program(spec, inp, repeat=1, no_joint_folds=True)
+        assert p2.info["n_joint_folds"] == 0 and p2.info["n_kernels"] == info["n_kernels"] + info["n_joint_folds"] - 1
+        for name, _ in spec.outputs:
+            assert np.array_equal(joint[name], apart[name]), name
+
+
+def _three_bias_gradients(rows, cols, dtype="f32"):
+    """Three independent GELU-backward patterns over different row counts (so that they stay three patterns); the
+    second one's bias gradient is read again (scaled) by a later op."""
+    from workloads.graphs import GraphSpec, OpSpec, TensorSpec
+    inputs, ops, outputs = [], [], []
+    for k in range(3):
+        r = rows + 8 * k
+        inputs += [TensorSpec(f"x{k}", dtype, (r, cols)), TensorSpec(f"b{k}", dtype, (cols,)), TensorSpec(f"g{k}", dtype, (r, cols))]
+        ops += [OpSpec(f"z{k}", "add", (f"x{k}", f"b{k}")), OpSpec(f"d{k}", "gelu_tanh_grad", (f"z{k}",)),
+                OpSpec(f"dx{k}", "mul", (f"g{k}", f"d{k}")), OpSpec(f"db{k}", "reduce_sum", (f"dx{k}",), {"axis": 0})]
+        outputs += [(f"dx{k}", dtype), (f"db{k}", "f32")]
+    ops.append(OpSpec("half", "scale", ("db1",), {"value": 0.5}))
+    outputs.append(("half", "f32"))
+    return GraphSpec(f"pattern_three_bias_gradients_{dtype}_{rows}x{cols}", inputs, ops, outputs)
+
+
+@pytest.mark.parametrize("rows,cols", [(300, 256), (2100, 768)])
+def test_folds_of_column_sums_that_are_read_again_stay_in_place(rows, cols):
+    if not B.codegen_available():
+        pytest.skip("column sums inside a pattern need the run-time compiler")
+    spec = _three_bias_gradients(rows, cols)
+    worst, prog = compare(spec)
+    # db0 and db2 are finished by the joint launch at the end; db1 has a reader and is folded before it runs
+    assert prog.info["n_joint_folds"] == 2
+    _, apart = compare(spec, no_joint_folds=True)
+    assert apart.info["n_kernels"] == prog.info["n_kernels"] + 1
+    note(f"three bias gradients {rows}x{cols}: {prog.info['n_kernels']} launches ({apart.info['n_kernels']} with every fold in place), worst {worst:.3f}")
 
 
 def test_transformer_block_without_packing_and_remote_fusion():

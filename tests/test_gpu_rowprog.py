@@ -102,6 +102,29 @@ def test_folded_transposes_move_values_exactly():
                     assert np.array_equal(raw["out"].view(np.uint8), np.ascontiguousarray(want).view(np.uint8)), (spec.name, perm, info["kernel"])
 
 
+def test_several_leading_axis_moves_as_one_kernel():
+    """Three tensors each moved [B,S,H,D] -> [B,H,S,D] and stored (the head split of q, k and v), one of them also
+    computed on: one launch, every moved value bit-identical to numpy's transpose."""
+    from workloads.graphs import GraphSpec, OpSpec, TensorSpec
+    from tests.gpu_util import run_spec
+    perm = (0, 2, 1, 3)
+    for dtype, dims in (("bf16", (2, 37, 3, 64)), ("f32", (3, 5, 4, 36)), ("f16", (1, 130, 2, 30))):
+        spec = GraphSpec(f"pattern_three_moves_{dtype}", [TensorSpec(n, dtype, dims) for n in "qkv"],
+                         [OpSpec("tq", "transpose", ("q",), {"perm": perm}), OpSpec("tk", "transpose", ("k",), {"perm": perm}),
+                          OpSpec("tv", "transpose", ("v",), {"perm": perm}), OpSpec("e", "tanh", ("tv",))],
+                         [("tq", dtype), ("tk", dtype), ("tv", dtype), ("e", dtype)])
+        inp = make_inputs(spec, seed=5)
+        ref = O.evaluate(spec, inp)
+        plan = B.Plan(B.Graph.from_spec(spec), "auto")
+        assert plan.info["n_kernels"] == 1 and plan.info["pattern"] in ("row_program", "row_generated")
+        for i in range(plan.info["n_candidates"]):
+            got, raw, info, _ = run_spec(spec, inp, "auto", candidate=i)
+            for name, src in (("tq", "q"), ("tk", "k"), ("tv", "v")):
+                want = np.ascontiguousarray(np.transpose(inp[src], perm))
+                assert np.array_equal(raw[name].view(np.uint8), want.view(np.uint8)), (spec.name, name, info["kernel"])
+            assert O.max_rel_err(got["e"], ref["e"], O.rms(ref["e"])) <= (1e-5 if dtype == "f32" else 1e-2)
+
+
 @pytest.mark.parametrize("rows,cols,dtype", [(10, 50, "f32"), (9, 1001, "bf16"), (13, 36, "f16"), (70, 127, "f16"), (3, 3003, "f32"),
                                              (300, 6, "bf16")])
 def test_row_lengths_that_allow_no_128_bit_access(rows, cols, dtype):

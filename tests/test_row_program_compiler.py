@@ -227,6 +227,21 @@ def test_transposes_of_leading_axes_fold_into_loads_and_stores(dims, perm):
     _compare(both)
 
 
+def test_transposed_views_that_are_outputs_compile_to_load_and_store():
+    """A leading-axis transpose whose result is itself an output is a move: a load through the permuted row strides
+    and a plain store, as many of them in one program as the operand limit allows."""
+    from workloads.graphs import GraphSpec, OpSpec, TensorSpec
+    dims, perm = (2, 5, 3, 16), (0, 2, 1, 3)
+    spec = GraphSpec("pattern_three_moves", [TensorSpec(n, "f32", dims) for n in "qkv"],
+                     [OpSpec("tq", "transpose", ("q",), {"perm": perm}), OpSpec("tk", "transpose", ("k",), {"perm": perm}),
+                      OpSpec("tv", "transpose", ("v",), {"perm": perm}), OpSpec("e", "exp", ("tv",))],
+                     [("tq", "f32"), ("tk", "f32"), ("tv", "f32"), ("e", "f32")])
+    n_instr, info = _compare(spec)
+    assert info["n_kernels"] == 1 and n_instr <= 8
+    listing = B.Plan(B.Graph.from_spec(spec), "auto").describe()
+    assert listing.count("rowstrides=15,1,3") == 3 and listing.count(" store ") == 4
+
+
 @pytest.mark.parametrize("rows,cols", [(37, 96), (50, 128), (9, 1024)])
 def test_column_sums_compile_to_partial_sums_and_a_fold(rows, cols):
     from workloads import gelu_backward_graph, layernorm_backward_bias_graph, rmsnorm_backward_graph
@@ -283,6 +298,11 @@ def test_patterns_that_are_not_row_local_are_refused():
     # an output that is stretched itself would be written by several rows
     spec = GraphSpec("pattern_w", [TensorSpec("x", "f32", (4, 6, 16)), TensorSpec("m", "f32", (4, 1, 16))],
                      [OpSpec("a", "add", ("x", "m")), OpSpec("e", "exp", ("m",))], [("a", "f32"), ("e", "f32")])
+    assert B.Plan(B.Graph.from_spec(spec), "auto").info["scheme"] == "unfused"
+    # likewise a per-column value that is no sum over the rows (here beside one that is): it has no row to be stored to
+    spec = GraphSpec("pattern_v", [TensorSpec("x", "f32", (40, 64)), TensorSpec("c", "f32", (64,))],
+                     [OpSpec("e", "exp", ("x",)), OpSpec("s", "reduce_sum", ("e",), {"axis": 0}), OpSpec("h", "scale", ("c",), {"value": 0.5})],
+                     [("e", "f32"), ("s", "f32"), ("h", "f32")])
     assert B.Plan(B.Graph.from_spec(spec), "auto").info["scheme"] == "unfused"
     # a row too long for one workgroup's registers (1024 threads x 8 vectors at most) falls back as well
     spec = GraphSpec("pattern_z", [TensorSpec("x", "f32", (2, 1 << 17))],
