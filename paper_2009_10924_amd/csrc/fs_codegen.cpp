@@ -8,6 +8,7 @@
 // compiled at plan time by the run-time compiler (kernels/gen_runtime.hip).
 #include <cstring>
 #include <string>
+#include <vector>
 
 #include "fs_internal.hpp"
 
@@ -94,9 +95,33 @@ std::string generate_row_kernel_body(const RowProgP& p) { return body_with_entry
 namespace {
 // Source text of one instruction of the accumulator machine (see ProgInstr): an unrolled loop over the lane's elements
 // for full-shaped work, a scalar statement for per-row work, a call into GenRow for reductions and stores.
-std::string instruction_text(const RowProgP& p, const ProgInstr& in, bool block, int n_waves, int* reduction_no) {
+// A pass over a row that is worked through in chunks (see chunked_body): reductions before `reduction` are known
+// (red<q>), that one gathers the lanes' partial values and ends the pass; stores happen in the last pass only.
+struct ChunkPass {
+  int reduction;      // the reduction this pass is for; the number of reductions = the last pass, with the stores
+  bool last_pass, last_chunk;
+  bool ended = false; // set when the pass's reduction has been emitted: nothing after it belongs to the pass
+};
+
+std::string instruction_text(const RowProgP& p, const ProgInstr& in, bool block, int n_waves, int* reduction_no, ChunkPass* cp = nullptr) {
   std::string t;
   const bool scalar = (in.flags & PF_SCALAR) != 0, keep = (in.flags & PF_KEEP) != 0;
+  if (cp) {
+    if ((in.op == PO_STORE && !cp->last_pass) || (in.op == PO_STORE_SCAL && !(cp->last_pass && cp->last_chunk))) return t;
+    if (in.op == PO_RSUM || in.op == PO_RMAX || in.op == PO_RSUMSQ) {
+      const int q = (*reduction_no)++;
+      if (q < cp->reduction) {
+        t += fmt("  sacc = red%d;\n", q);
+        if (keep) t += fmt("  s%d = sacc;\n", in.dst);
+      } else {
+        const bool is_max = in.op == PO_RMAX;
+        t += fmt("  part = %s::apply(part, row.partial<%s, %s, %s>(acc));\n", is_max ? "OpMax" : "OpSum", is_max ? "OpMax" : "OpSum",
+                 is_max ? "true" : "false", in.op == PO_RSUMSQ ? "true" : "false");
+        cp->ended = true;
+      }
+      return t;
+    }
+  }
   switch (in.op) {
     case PO_STORE:
       if ((p.out_perm >> in.dst) & 1u)   // stored through a folded transpose: the row lands at its permuted place
@@ -142,7 +167,89 @@ std::string instruction_text(const RowProgP& p, const ProgInstr& in, bool block,
   return t;
 }
 
+// A row longer than the lanes' registers hold (beyond 1024 threads x 8 steps) is worked through in chunks of
+// lanes x steps elements, one pass over the row per row reduction and a last one for the stores.  Every pass runs
+// the instruction list from the start up to its reduction on each chunk, with the reductions of earlier passes
+// replaced by their results; what a pass does not need of that (other operands' loads, values kept for later
+// stores) is dead code to the device compiler.  The operands are read once per pass: the re-reads are the price of
+// keeping the pattern in one kernel (Section 4.2 keeps such a value on chip; a row of this length has no chip
+// memory to stay in), and they come from the caches as far as the rows in flight fit there.
+std::string chunked_body(const RowProgP& p, const char* entry) {
+  const uint32_t L = (uint32_t)p.lanes_per_row, chunk = L * (uint32_t)p.vecs_per_lane * (uint32_t)p.vec, NC = (uint32_t)p.col_chunks;
+  const uint32_t tail = p.cols - (NC - 1u) * chunk;
+  const int n_waves = (int)(L / 64u);
+  std::vector<int> is_max;
+  for (int i = 0; i < p.n_instr; ++i)
+    if (p.instr[i].op == PO_RSUM || p.instr[i].op == PO_RMAX || p.instr[i].op == PO_RSUMSQ) is_max.push_back(p.instr[i].op == PO_RMAX);
+  const int n_red = (int)is_max.size();
+  std::string s = "using namespace fsk;\n";
+  s += fmt("extern \"C\" __global__ void __launch_bounds__(%u) %s(const GenArgs a) {\n", L, entry);
+  s += "  const uint32_t fs_block = blockIdx.x;\n";
+  s += fmt("  typedef GenRow<%uu, %uu, %d, %d, %uu, true, 1u, %uu> Row;       // a whole chunk\n", p.rows, chunk, p.vec, p.vecs_per_lane, L, p.cols);
+  s += fmt("  typedef GenRow<%uu, %uu, %d, %d, %uu, true, 1u, %uu> TailRow;   // the row's last chunk\n", p.rows, tail, p.vec, p.vecs_per_lane, L, p.cols);
+  s += "  constexpr int KV = Row::KV;\n";
+  if (n_red > 0) s += fmt("  __shared__ float slots[%d];\n", n_waves * n_red);
+  for (int q = 0; q < n_red; ++q) s += fmt("  float red%d;\n", q);
+  s += "  const Row row0(fs_block);\n";
+  if ((p.full_bcast | p.rscal_bcast | p.out_perm) != 0)
+    s += fmt("  const uint32_t q1 = row0.row_c / %uu, lead2 = row0.row_c - q1 * %uu, lead0 = q1 / %uu, lead1 = q1 - lead0 * %uu;\n", p.od[2].d,
+             p.od[2].d, p.od[1].d, p.od[1].d);
+  for (int i = 0; i < p.n_rscal; ++i) {
+    const std::string at = ((p.rscal_bcast >> i) & 1u) ? stretched_row(p.rms[i]) : std::string("(size_t)row0.row_c");
+    s += fmt("  const float in_rscal%d = load1(static_cast<const %s*>(a.rscal[%d]) + %s);\n", i, storage_type(p.rscal_dt[i]), i, at.c_str());
+  }
+  // one chunk's share of a pass, for the row object `row` in scope
+  auto piece = [&](int pass, bool last_chunk) {
+    std::string t;
+    const bool last_pass = pass == n_red;
+    for (int i = 0; i < p.n_full; ++i) {
+      const bool stretched = ((p.full_bcast >> i) & 1u) != 0;
+      const std::string at = stretched ? stretched_row(p.ms[i]) : std::string("(size_t)row.row_c");
+      // only the last pass reads an operand for the last time
+      t += fmt("  const auto raw_full%d = row.load<%s, %s>(a.full[%d], %s);\n", i, storage_type(p.full_dt[i]),
+               (stretched || !last_pass) ? "false" : "true", i, at.c_str());
+    }
+    for (int i = 0; i < p.n_col; ++i)
+      t += fmt("  const auto raw_col%d = row.load<%s, false>(a.col[%d], 0);\n", i, storage_type(p.col_dt[i]), i);
+    t += "  float acc[KV], sacc = 0.0f;\n#pragma unroll\n  for (int j = 0; j < KV; ++j) acc[j] = 0.0f;\n";
+    for (int r = 0; r < p.n_regs; ++r) t += fmt("  float r%d[KV];\n", r);
+    for (int r = 0; r < p.n_sregs; ++r) t += fmt("  float s%d = 0.0f;\n", r);
+    for (int i = 0; i < p.n_col; ++i) t += fmt("  float c%d[KV];\n  row.unpack_to<%s>(raw_col%d, c%d);\n", i, storage_type(p.col_dt[i]), i, i);
+    for (int i = 0; i < p.n_full; ++i) {
+      const bool parked = p.full_reg[i] != 255, to_acc = p.acc_input == i;
+      if (parked) {
+        t += fmt("  row.unpack_to<%s>(raw_full%d, r%d);\n", storage_type(p.full_dt[i]), i, p.full_reg[i]);
+        if (to_acc) t += fmt("#pragma unroll\n  for (int j = 0; j < KV; ++j) acc[j] = r%d[j];\n", p.full_reg[i]);
+      } else if (to_acc) {
+        t += fmt("  row.unpack_to<%s>(raw_full%d, acc);\n", storage_type(p.full_dt[i]), i);
+      }
+    }
+    for (int i = 0; i < p.n_rscal; ++i) t += fmt("  s%d = in_rscal%d;\n", p.rscal_sreg[i], i);
+    ChunkPass cp{pass, last_pass, last_chunk};
+    int reduction_no = 0;
+    for (int i = 0; i < p.n_instr && !cp.ended; ++i) t += instruction_text(p, p.instr[i], true, n_waves, &reduction_no, &cp);
+    return t;
+  };
+  for (int pass = 0; pass <= n_red; ++pass) {
+    s += "  {\n";
+    if (pass < n_red) s += fmt("  float part = %s;\n", is_max[pass] ? "-__builtin_huge_valf()" : "0.0f");
+    // every other pass walks the row backwards: it starts with the chunks the pass before read last, which the
+    // caches are likeliest to hold still
+    const bool backwards = (pass & 1) != 0;
+    const std::string whole = fmt("#pragma unroll 1\n  for (uint32_t chunk = 0; chunk < %uu; ++chunk) {\n  const Row row(fs_block, 0, %s * %uu);\n",
+                                  NC - 1u, backwards ? fmt("(%uu - chunk)", NC - 2u).c_str() : "chunk", chunk) +
+                              piece(pass, false) + "  }\n";
+    const std::string last = fmt("  {\n  const TailRow row(fs_block, 0, %uu);\n", (NC - 1u) * chunk) + piece(pass, true) + "  }\n";
+    s += backwards ? last + whole : whole + last;
+    if (pass < n_red) s += fmt("  red%d = Row::finish<%s>(part, slots + %d);\n", pass, is_max[pass] ? "OpMax" : "OpSum", n_waves * pass);
+    s += "  }\n";
+  }
+  s += "}\n";
+  return s;
+}
+
 std::string body_with_entry(const RowProgP& p, const char* entry, bool member) {
+  if (p.col_chunks > 1) return chunked_body(p, entry);   // never a pack member: more than 256 threads
   const bool block = p.lanes_per_row > 64;
   int n_reductions = 0;
   for (int i = 0; i < p.n_instr; ++i)

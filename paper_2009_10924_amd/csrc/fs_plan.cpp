@@ -77,6 +77,7 @@ static void fill_generic_form(const fs_graph& g, fs_plan* p) {
     const Launch& l = c.launches.front();
     if ((l.kernel != K_ROW_GENERATED && l.kernel != K_ROW_PROGRAM) || l.args.u.prog.n_colsum > 0) return false;
     if (l.shape.block[0] != 256) return false;   // a packed kernel's workgroups have 256 threads
+    if (l.args.u.prog.col_chunks > 1) return false;   // rows worked through in chunks: a launch of its own
     p->generic.valid = true;
     p->generic.prog = l.args.u.prog;
     for (int k = 0; k < kMaxPtrs; ++k) p->generic.ptr[k] = l.ptr[k];
@@ -90,7 +91,7 @@ static void fill_generic_form(const fs_graph& g, fs_plan* p) {
   int best = -1;
   for (int i = 0; i < (int)cands.size(); ++i) {
     if (cands[i].launches.size() != 1 || cands[i].launches.front().kernel != K_ROW_GENERATED) continue;
-    if (cands[i].launches.front().shape.block[0] != 256) continue;
+    if (cands[i].launches.front().shape.block[0] != 256 || cands[i].launches.front().args.u.prog.col_chunks > 1) continue;
     predict(&cands[i]);
     if (best < 0 || cands[i].info.predicted_us < cands[best].info.predicted_us) best = i;
   }
@@ -338,6 +339,8 @@ int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) {
     if (q.n_colsum > 0)   // partial sums: one row of n_colsum * cols floats per workgroup, folded by the next launch
       s += "  colsums " + std::to_string(q.n_colsum) + " partials " + buf_name(l.ptr[kSlotWs]) + " rows_per_group " +
            std::to_string(q.rows_per_group) + " col_tiles " + std::to_string(q.col_tiles > 1 ? q.col_tiles : 1) + "\n";
+    if (q.col_chunks > 1)   // the row in pieces of lanes * vecs steps, a pass per row reduction and one for the stores
+      s += "  chunks " + std::to_string(q.col_chunks) + " of " + std::to_string(q.lanes_per_row * q.vecs_per_lane * q.vec) + " columns\n";
     static const char* op_names[] = {"add", "sub", "rsub", "mul", "div", "rdiv", "max", "square", "exp", "rsqrt", "tanh", "gelu",
                                      "gelu_grad", "cvt", "load", "rsum", "rmax", "rsumsq", "store", "store_scal", "colsum"};
     static const char* kind_names[] = {"acc", "sacc", "reg", "scal", "imm", "col"};

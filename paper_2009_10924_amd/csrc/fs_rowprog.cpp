@@ -611,6 +611,7 @@ struct Compiler {
     p.n_colsum = n_colsum;
     p.rows_per_group = 1;
     p.col_tiles = 1;
+    p.col_chunks = 1;
     if (n_colsum > 0) interpretable = false;
     return n_out + n_rout + n_colsum == (int)g.outputs.size();
   }
@@ -627,6 +628,7 @@ struct Shape {
   bool block;
   bool generated;
   uint32_t R = 1, CT = 1;
+  uint32_t NC = 1;   // > 1: the row is worked through in NC chunks of L * K steps (rows beyond any workgroup's registers)
 };
 
 // Step widths to offer.  A pattern whose 16-bit vector inputs ask for 8 elements per step may also move float32
@@ -696,6 +698,16 @@ std::vector<Shape> enumerate_shapes(const Compiler& c, int vec, bool interpretab
     const uint32_t KB = (nvec + T - 1) / T;
     if (KB <= max_k && 64ull * 2 < nvec && (T == 256 || nvec > (uint64_t)T)) shapes.push_back({T, (int)KB, true, true});
   }
+  // rows beyond 1024 threads x max_k steps: chunks of a workgroup's worth of steps, a pass per row reduction
+  // (also offered, on 1024 threads, to shorter rows whose pattern keeps more values than a lane has registers for)
+  if (nvec > 256ull * max_k && c.n_colsum == 0)
+    for (uint32_t T : {256u, 512u, 1024u})
+      for (uint32_t K : {max_k / 4, max_k / 2, max_k}) {
+        if (nvec <= 1024ull * max_k ? !(T == 1024 && K < max_k) : K == max_k / 4) continue;
+        Shape t{T, (int)K, true, true};
+        t.NC = (nvec + T * K - 1) / (T * K);
+        if (t.NC >= 2 && t.NC <= 4096) shapes.push_back(t);
+      }
   if (c.n_colsum == 0) return shapes;
   // Without row reductions nothing ties the columns of a row together: a workgroup may take one tile of 64 or 128
   // vectors, so a lane keeps one or two vectors per value whatever the row length.
@@ -723,6 +735,7 @@ void fill_launch(const fs_graph& g, const Compiler& c, int vec, const Shape& s, 
   q.vecs_per_lane = s.K;
   q.rows_per_group = (int32_t)s.R;
   q.col_tiles = (int32_t)s.CT;
+  q.col_chunks = (int32_t)s.NC;
   l->args.u.prog = q;
   auto in_ref = [&](int32_t t) {   // a transposed view binds the buffer of the input it views
     BufRef r;
@@ -810,6 +823,21 @@ void make_generated(const Compiler& c, int vec, const Shape& s, Candidate* cand)
   // lane) cost time that more, shorter wavefronts would have overlapped
   const DeviceModel& d = device();
   gc.serial_tail_s = 1.5 * kv * (gc.valu_per_elem * d.cycles_valu + gc.trans_per_elem * d.cycles_trans) / d.clock_hz;
+  if (s.NC > 1) {
+    // a pass over the row per reduction re-reads the operands (counted as device-memory traffic: the rows in flight
+    // are larger than the caches in general) and repeats the arithmetic before its reduction
+    snprintf(cand->info.kernel, sizeof cand->info.kernel, "row_generated<v%d,K%d,L%u,I%d,R%d,chunks%u>", vec, s.K, s.L, base.n_instr,
+             base.n_regs, s.NC);
+    double in_bytes = 0;
+    for (int i = 0; i < base.n_full; ++i)
+      if (!((base.full_bcast >> i) & 1u)) in_bytes += (double)dtype_bytes(base.full_dt[i]) * base.rows * base.cols;
+    gc.hbm_bytes += in_bytes * c.n_reductions;
+    cand->info.bytes_moved_model += (int64_t)(in_bytes * c.n_reductions);
+    gc.valu_per_elem *= 1.0 + 0.5 * c.n_reductions;
+    gc.trans_per_elem *= 1.0 + 0.5 * c.n_reductions;
+    gc.lane_utilisation = (double)(base.cols / vec) / ((double)s.L * s.K * s.NC);
+    gc.serial_tail_s += d.mem_latency_s * c.n_reductions;
+  }
 }
 
 // Column sums of a generated candidate: partial sums of every workgroup through the workspace, folded by a second

@@ -135,6 +135,8 @@ struct GenRow {
     row_ok = FULL_ROWS || row < ROWS;
     row_c = FULL_ROWS ? row : min(row, ROWS - 1u);
   }
+  // a chunk of a long row: COLS columns from column `first_col` on (the row itself is ROW_STRIDE elements long)
+  __device__ __forceinline__ GenRow(uint32_t vblock, uint32_t tile, uint32_t first_col) : GenRow(vblock, tile) { col0 = first_col; }
   __device__ __forceinline__ bool valid(int k) const { return FULL_COLS || lane + k * LANES < NVEC; }
   __device__ __forceinline__ uint32_t vec_at(int k) const { return FULL_COLS ? lane + k * LANES : min(lane + k * LANES, NVEC - 1u); }
 
@@ -189,6 +191,12 @@ struct GenRow {
   // elements.  slot: one float per wavefront of the workgroup, LDS private to this reduction (BLOCK only).
   template <typename OP, bool IS_MAX, bool SQUARE>
   __device__ __forceinline__ float reduce(const float (&v)[KV], float* slot) const {
+    return finish<OP>(partial<OP, IS_MAX, SQUARE>(v), slot);
+  }
+  // the two halves of reduce(): the lane's own elements folded to one value (rows worked through in chunks fold
+  // their chunks' values lane by lane first), and the all-reduce of the lanes' values over the row
+  template <typename OP, bool IS_MAX, bool SQUARE>
+  __device__ __forceinline__ float partial(const float (&v)[KV]) const {
     // the lane's own elements are combined pairwise (a tree, not a chain): log2(KV) dependent steps instead of
     // KV, and a float32 sum whose rounding error grows with the depth of the tree
     float t[KV];
@@ -207,7 +215,10 @@ struct GenRow {
       for (int i = 0; i < n / 2; ++i) t[i] = OP::apply(t[2 * i], t[2 * i + 1]);
       if (n & 1) t[n / 2] = t[n - 1];
     }
-    const float r = t[0];
+    return t[0];
+  }
+  template <typename OP>
+  __device__ __forceinline__ static float finish(float r, float* slot) {
     if constexpr (BLOCK) return block_allreduce<OP>(r, slot, (int)(L / 64u));
     else return group_allreduce<OP>(r, (int)L);
   }

@@ -245,6 +245,8 @@ struct RowProgP {
                                        // fewer, longer partial sums)
   int32_t col_tiles;                   // > 1: a workgroup handles one of col_tiles column tiles of cols / col_tiles elements
                                        // (generated kernels for patterns with column sums and no row reduction)
+  int32_t col_chunks;                  // > 1: a row too long for the lanes' registers is worked through in col_chunks pieces of
+                                       // lanes_per_row * vecs_per_lane steps, once per row reduction and once more for the stores
   ProgInstr instr[kProgMaxInstr];
 };
 struct ProgArgs {

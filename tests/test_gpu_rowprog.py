@@ -171,13 +171,30 @@ def test_long_rows_on_workgroups_of_512_and_1024_threads(rows, cols, dtype):
         info = B.Plan(g, "auto").info
         if spec.name.startswith("softmax") and info["pattern"] == "softmax":
             continue                                    # the softmax family's own block kernel still holds this row
-        if "layernorm_stats" in spec.name and cols > 24576 and info["scheme"] == "unfused":
-            continue                                    # three live rows of this length do not fit 128 registers per lane
         assert info["pattern"] == "row_generated" and info["block"][0] in (512, 1024), (spec.name, info)
         inp = make_inputs(spec, seed=1)
         ref = O.evaluate(spec, inp)
         worst = all_candidates(spec, inp, ref, {name: O.rms(ref[name]) for name, _ in spec.outputs}, repeat=2)
         note(f"{spec.name}: {info['kernel']} on {info['block'][0]} threads, worst {worst}")
+
+
+@pytest.mark.parametrize("rows,cols,dtype", [(4, 131072, "bf16"), (3, 50257, "f32"), (5, 70000, "f16"), (2, 128256, "bf16"), (3, 40000, "f32")])
+def test_rows_beyond_a_workgroups_registers_are_worked_through_in_chunks(rows, cols, dtype):
+    """Rows longer than 1024 threads x 8 steps (a softmax over a vocabulary): the generated kernel walks the row in
+    chunks, one pass per row reduction and one for the stores; whole chunks and a ragged last one, 8-, 4- and
+    1-element steps, column operands, two outputs."""
+    if not B.codegen_available():
+        pytest.skip("rows of this length exist as generated kernels only")
+    from workloads import softmax_graph
+    for spec in (softmax_graph(rows, cols, dtype), layernorm_stats_graph(rows, cols, in_dtype=dtype, out_dtype=dtype, with_variance=True),
+                 scaled_softmax_colbias_graph(rows, cols, dtype), silu_gate_graph(rows, cols, dtype)):
+        plan = B.Plan(B.Graph.from_spec(spec), "auto")
+        info = plan.info
+        assert info["pattern"] == "row_generated" and "chunks" in info["kernel"] and info["n_kernels"] == 1, (spec.name, info)
+        inp = make_inputs(spec, seed=2)
+        ref = O.evaluate(spec, inp)
+        worst = all_candidates(spec, inp, ref, {name: O.rms(ref[name]) for name, _ in spec.outputs}, repeat=2)
+        note(f"{spec.name}: {info['kernel']} on {info['block'][0]} threads, {info['n_candidates']} shapes, worst {worst}")
 
 
 @pytest.mark.parametrize("seed", range(48))

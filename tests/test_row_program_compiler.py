@@ -304,11 +304,12 @@ def test_patterns_that_are_not_row_local_are_refused():
                      [OpSpec("e", "exp", ("x",)), OpSpec("s", "reduce_sum", ("e",), {"axis": 0}), OpSpec("h", "scale", ("c",), {"value": 0.5})],
                      [("e", "f32"), ("s", "f32"), ("h", "f32")])
     assert B.Plan(B.Graph.from_spec(spec), "auto").info["scheme"] == "unfused"
-    # a row too long for one workgroup's registers (1024 threads x 8 vectors at most) falls back as well
+    # a row too long for one workgroup's registers (1024 threads x 8 vectors at most) falls back without the run-time compiler
     spec = GraphSpec("pattern_z", [TensorSpec("x", "f32", (2, 1 << 17))],
                      [OpSpec("e", "exp", ("x",)), OpSpec("y", "mul", ("e", "x"))], [("y", "f32")])
-    assert B.Plan(B.Graph.from_spec(spec), "auto").info["scheme"] == "unfused"
-    # ... while 32768 floats fit 1024 threads (generated kernels) but not the interpreter's 256
+    with B.codegen(False):
+        assert B.Plan(B.Graph.from_spec(spec), "auto").info["scheme"] == "unfused"
+    # ... and 32768 floats fit 1024 threads (generated kernels) but not the interpreter's 256
     spec = GraphSpec("pattern_z", [TensorSpec("x", "f32", (2, 1 << 15))],
                      [OpSpec("e", "exp", ("x",)), OpSpec("y", "mul", ("e", "x"))], [("y", "f32")])
     with B.codegen(False):
@@ -316,3 +317,28 @@ def test_patterns_that_are_not_row_local_are_refused():
     if B.codegen_available():
         info = B.Plan(B.Graph.from_spec(spec), "auto").info
         assert info["scheme"] == "lds" and info["block"][0] == 1024
+
+
+@pytest.mark.parametrize("cols,dtype", [(1 << 17, "f32"), (50257, "f32"), (70000, "bf16")])
+def test_rows_beyond_a_workgroups_registers_compile_to_passes_over_chunks(cols, dtype):
+    """One pass over the row's chunks per row reduction, one more for the stores; the last chunk has its own extent."""
+    if not B.codegen_available():
+        pytest.skip("needs the run-time compiler")
+    from workloads import softmax_graph
+    for spec, reductions in ((softmax_graph(3, cols, dtype), 2), (layernorm_stats_graph(3, cols, in_dtype=dtype, out_dtype=dtype, with_variance=True), 2),
+                             (silu_gate_graph(3, cols, dtype), 0)):
+        plan = B.Plan(B.Graph.from_spec(spec), "auto")
+        info, src, listing = plan.info, plan.source(), plan.describe()
+        assert info["pattern"] == "row_generated" and "chunks" in info["kernel"] and info["n_kernels"] == 1
+        chunks, width = [int(w) for w in listing[listing.index("  chunks "):].split()[1:4:2]]
+        assert (chunks - 1) * width < cols <= chunks * width and width == info["lanes_per_row"] * info["vecs_per_lane"] * (8 if "<v8" in info["kernel"] else 4 if "<v4" in info["kernel"] else 1)
+        assert src.count("for (uint32_t chunk = 0;") == reductions + 1 and src.count("Row::finish<") == reductions
+        assert f"TailRow row(fs_block, 0, {(chunks - 1) * width}u)" in src
+        # every full-shaped output is stored in the last pass only: once per whole chunk and once for the last one
+        ref = O.evaluate(spec, make_inputs(spec, seed=4))
+        n_full_out = sum(1 for name, _ in spec.outputs if ref[name].shape[-1] == cols)
+        assert src.count("row.store<") == 2 * n_full_out and src.count("row.store_scalar<") == len(spec.outputs) - n_full_out
+        got, _ = emulate(listing, spec, make_inputs(spec, seed=4), (3, cols))
+        for name, dt in spec.outputs:
+            r = ref[name].reshape(got[name].shape)
+            assert O.max_rel_err(got[name], r, O.rms(r)) < 2e-5, (spec.name, name)

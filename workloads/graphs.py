@@ -732,6 +732,8 @@ GENERIC_CONFIGS = {
     # column sums over all rows beside the row-local work: partial sums per workgroup + a fold launch
     "G9": lambda: gelu_backward_graph(16384, 3072, "bf16"),                  # C4's shape
     "G10": lambda: rmsnorm_backward_graph(8192, 4096, "bf16"),               # N5's shape
+    # a row far beyond one workgroup's registers (probabilities over a vocabulary): chunks, a pass per row reduction
+    "G11": lambda: softmax_graph(4096, 128256, "bf16"),
 }
 
 FULL_CONFIGS = {
