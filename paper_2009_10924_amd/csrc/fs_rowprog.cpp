@@ -831,7 +831,12 @@ void make_generated(const Compiler& c, int vec, const Shape& s, Candidate* cand)
     double in_bytes = 0;
     for (int i = 0; i < base.n_full; ++i)
       if (!((base.full_bcast >> i) & 1u)) in_bytes += (double)dtype_bytes(base.full_dt[i]) * base.rows * base.cols;
-    gc.hbm_bytes += in_bytes * c.n_reductions;
+    // ... unless the rows the resident workgroups are working on fit the memory-side cache (with room for the
+    // outputs passing through): wide workgroups keep fewer rows in flight
+    const double wgs_per_cu = std::max(1.0, std::floor(2048.0 / s.L));
+    const double rows_in_flight_bytes = d.n_cu * wgs_per_cu * in_bytes / base.rows;
+    const double reread = rows_in_flight_bytes <= 0.6 * d.last_level_cache_bytes ? d.last_level_reread : 1.0;
+    gc.hbm_bytes += in_bytes * c.n_reductions * reread;
     cand->info.bytes_moved_model += (int64_t)(in_bytes * c.n_reductions);
     gc.valu_per_elem *= 1.0 + 0.5 * c.n_reductions;
     gc.trans_per_elem *= 1.0 + 0.5 * c.n_reductions;
