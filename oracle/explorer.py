@@ -70,6 +70,35 @@ class GraphView:
                 self.desc[i] |= self.desc[c]
 
 
+def plan_is_acyclic(view: GraphView, groups: Sequence[Sequence[int]]) -> bool:
+    """Section 5.2's "no cyclic dependence", for a whole plan: the graph whose vertices are the plan's patterns (and
+    the ops outside them, one each) must have a topological order.  Patterns that are convex one by one can still wait
+    for each other: {a, d} and {b, c} with edges a -> b and c -> d."""
+    gid = {}
+    for k, p in enumerate(groups):
+        for o in p:
+            gid[o] = k
+    for o in range(view.n):
+        gid.setdefault(o, len(groups) + o)
+    succ: Dict[int, set] = {}
+    waiting: Dict[int, int] = {k: 0 for k in set(gid.values())}
+    for o in range(view.n):
+        for c in view.consumers[o]:
+            if gid[c] != gid[o] and gid[c] not in succ.setdefault(gid[o], set()):
+                succ[gid[o]].add(gid[c])
+                waiting[gid[c]] += 1
+    ready = [k for k, w in waiting.items() if w == 0]
+    done = 0
+    while ready:
+        k = ready.pop()
+        done += 1
+        for c in succ.get(k, ()):
+            waiting[c] -= 1
+            if waiting[c] == 0:
+                ready.append(c)
+    return done == len(waiting)
+
+
 class Pat:
     __slots__ = ("ops", "f", "tentative")
 
@@ -206,15 +235,18 @@ def explore(view: GraphView, score: ScoreFn, top_k: int = 3, beam_width: int = 3
             for p in cand[v]:
                 if p.tentative or any(o in covered for o in p.ops):
                     continue
+                if not plan_is_acyclic(view, patterns + [p.ops]):
+                    continue
                 nxt.append((patterns + [p.ops], covered | frozenset(p.ops), f + p.f))
         nxt.sort(key=lambda s: (-rank(s[1], s[2], v), s[0]))
         sets = nxt[:beam_width]
     return cand, [(patterns, f) for patterns, _, f in sets]
 
 
-def remote_fusion(patterns: List[Ops], n_ops: int, score: ScoreFn) -> Tuple[List[Ops], float]:
+def remote_fusion(patterns: List[Ops], n_ops: int, score: ScoreFn, view: Optional[GraphView] = None) -> Tuple[List[Ops], float]:
     """Section 5.2, remote fusion, read greedily: of all pairs of the plan's patterns (ops left alone count as
-    patterns of one) whose union is runnable, merge the pair that gains the most; repeat until none gains.
+    patterns of one) whose union is runnable and leaves the plan free of cyclic dependences (checked when `view`
+    is given), merge the pair that gains the most; repeat until none gains.
     Returns (all groups of the plan after merging, total gain)."""
     covered = {o for p in patterns for o in p}
     groups = sorted([tuple(p) for p in patterns] + [(o,) for o in range(n_ops) if o not in covered])
@@ -235,6 +267,9 @@ def remote_fusion(patterns: List[Ops], n_ops: int, score: ScoreFn) -> Tuple[List
                     continue
                 gain = f - f_of(groups[i]) - f_of(groups[j])
                 if gain > best_gain:
+                    merged = [g for k, g in enumerate(groups) if k not in (i, j)] + [u]
+                    if view is not None and not plan_is_acyclic(view, merged):
+                        continue
                     best_gain, pair = gain, (i, j)
         if pair is None:
             break
@@ -263,10 +298,13 @@ def brute_force_best(view: GraphView, score: ScoreFn, max_ops: int = 10) -> floa
                 cache[ops] = f if status == 0 else None
         return cache[ops]
 
+    blocks: List[Ops] = []
+
     def rec(remaining: Tuple[int, ...], total: float) -> None:
         nonlocal best
         if not remaining:
-            best = max(best, total)
+            if plan_is_acyclic(view, blocks):
+                best = max(best, total)
             return
         first, rest = remaining[0], remaining[1:]
         # the block that holds `first`: first plus any subset of the rest
@@ -275,7 +313,9 @@ def brute_force_best(view: GraphView, score: ScoreFn, max_ops: int = 10) -> floa
             f = f_of(block)
             if f is None:
                 continue
+            blocks.append(block)
             rec(tuple(x for x in rest if x not in block), total + f)
+            blocks.pop()
 
     rec(tuple(range(n)), 0.0)
     return best

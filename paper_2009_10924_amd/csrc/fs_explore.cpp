@@ -391,6 +391,42 @@ struct Explorer {
     }
   }
 
+  // Patterns that are convex one by one can still wait for each other in a circle (P = {a, d}, Q = {b, c} with edges
+  // a -> b and c -> d and no path from b to c): Section 5.2's "no cyclic dependence" is a property of the plan, checked
+  // on the graph whose vertices are the plan's patterns and the ops outside them.
+  bool acyclic(const std::vector<OpSet>& groups) const {
+    std::vector<int> gid(n, -1);
+    int n_groups = 0;
+    for (const OpSet& p : groups) {
+      for (int o : p) gid[o] = n_groups;
+      ++n_groups;
+    }
+    for (int o = 0; o < n; ++o)
+      if (gid[o] < 0) gid[o] = n_groups++;
+    std::vector<std::vector<int>> next(n_groups);
+    std::vector<int> waiting(n_groups, 0);
+    for (int o = 0; o < n; ++o)
+      for (int c : consumers[o])
+        if (gid[c] != gid[o]) next[gid[o]].push_back(gid[c]);
+    for (int a = 0; a < n_groups; ++a) {
+      std::sort(next[a].begin(), next[a].end());
+      next[a].erase(std::unique(next[a].begin(), next[a].end()), next[a].end());
+      for (int b : next[a]) ++waiting[b];
+    }
+    std::vector<int> ready;
+    for (int a = 0; a < n_groups; ++a)
+      if (waiting[a] == 0) ready.push_back(a);
+    int done = 0;
+    while (!ready.empty()) {
+      const int a = ready.back();
+      ready.pop_back();
+      ++done;
+      for (int b : next[a])
+        if (--waiting[b] == 0) ready.push_back(b);
+    }
+    return done == n_groups;
+  }
+
   // Remote fusion (Section 5.2): patterns of a plan that are not adjacent in the graph -- no edge joins them --
   // may still share a kernel.  Greedy reading: among all pairs of the plan's patterns (single ops included)
   // whose union is a runnable pattern, merge the pair that gains the most over running the two apart; repeat
@@ -409,7 +445,15 @@ struct Explorer {
           const Scored& s = score(u);
           if (!s.valid) continue;
           const double gain = s.f - f_of((*groups)[i]) - f_of((*groups)[j]);
-          if (gain > best_gain) { best_gain = gain; bi = i; bj = j; }
+          if (!(gain > best_gain)) continue;
+          std::vector<OpSet> merged;
+          for (size_t k = 0; k < groups->size(); ++k)
+            if (k != i && k != j) merged.push_back((*groups)[k]);
+          merged.push_back(u);
+          if (!acyclic(merged)) continue;   // the union is convex, but the plan with it would wait for itself
+          best_gain = gain;
+          bi = i;
+          bj = j;
         }
       if (!(best_gain > 0.0)) break;
       const OpSet u = unite((*groups)[bi], (*groups)[bj]);
@@ -459,6 +503,7 @@ struct Explorer {
           if (overlap) continue;
           PlanSet t = s;
           t.patterns.push_back(p.ops);
+          if (!acyclic(t.patterns)) continue;
           for (int o : p.ops) t.covered[o / 64] |= 1ull << (o % 64);
           t.f += p.f;
           next.push_back(t);

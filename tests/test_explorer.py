@@ -46,7 +46,25 @@ SPECS = {
     "layernorm_stats": lambda: layernorm_stats_graph(64, 256, with_variance=True),
 }
 SPECS.update({f"multi{s}": (lambda s=s: random_multi_pattern(s)) for s in range(16)})
+SPECS.update({f"multi_sums{s}": (lambda s=s: random_multi_pattern(s, rows=64, cols=128, segments=2 + s % 3, column_sums=1 + s % 2)) for s in range(8)})
 SPECS.update({f"multi_big{s}": (lambda s=s: random_multi_pattern(100 + s, rows=512, cols=1024, segments=4)) for s in range(4)})
+
+
+def test_patterns_that_wait_for_each_other_are_not_a_plan():
+    """{a, d} and {b, c} with a -> b and c -> d: each is convex, together they have no order of execution."""
+    from workloads.graphs import GraphSpec, OpSpec, TensorSpec
+    spec = GraphSpec("pattern_circle", [TensorSpec("x", "f32", (8, 16)), TensorSpec("y", "f32", (8, 16))],
+                     [OpSpec("a", "exp", ("x",)), OpSpec("b", "tanh", ("a",)), OpSpec("c", "tanh", ("y",)), OpSpec("d", "exp", ("c",))],
+                     [("a", "f32"), ("b", "f32"), ("c", "f32"), ("d", "f32")])
+    view = X.GraphView(spec)
+    assert X.plan_is_acyclic(view, [(0, 1), (2, 3)]) and X.plan_is_acyclic(view, [(0, 2), (1, 3)]) and X.plan_is_acyclic(view, [(0, 3)])
+    assert not X.plan_is_acyclic(view, [(0, 3), (1, 2)])
+    # the library never returns such a plan: whatever it merges, the steps come back in an order that runs
+    prog = B.Program(B.Graph.from_spec(spec))
+    done = set()
+    for st in prog.patterns():
+        assert all(p in done or p in st["ops"] for o in st["ops"] for p in view.producers[o])
+        done |= set(st["ops"])
 
 
 @pytest.mark.parametrize("name", sorted(SPECS))
@@ -57,7 +75,7 @@ def test_library_plan_is_one_of_the_oracle_beam_plans(name):
     score = _score_fn(g)
 
     def finished(plan):       # the beam plan after remote fusion: its multi-op groups and its total score
-        groups, gain = X.remote_fusion(plan[0], len(spec.ops), score)
+        groups, gain = X.remote_fusion(plan[0], len(spec.ops), score, view)
         return sorted(p for p in groups if len(p) > 1), plan[1] + gain
     got = _multi(prog)
     beam = [finished(p) for p in plans]

@@ -155,6 +155,26 @@ def test_random_multi_pattern_programs(seed):
          f"({info['n_patterns']} patterns, {info['n_packs']} packs), workspace {info['workspace_bytes']} B, worst {worst:.3f} of the bar")
 
 
+@pytest.mark.parametrize("seed", range(12))
+def test_random_multi_pattern_programs_with_column_sums(seed):
+    """Random segments that also sum one or two of their values over all rows: the folds of all segments run as one
+    launch behind the last step (where two or more are free to move), and the result equals the one with every fold
+    in place bit for bit."""
+    rows, cols = [(64, 128), (130, 64), (40, 520)][seed % 3]
+    spec = random_multi_pattern(seed, rows=rows, cols=cols, segments=2 + seed % 3, column_sums=1 + seed % 2)
+    worst, prog = compare(spec, seed=seed)
+    info = prog.info
+    if B.codegen_available():
+        inp = make_inputs(spec, seed=seed)
+        joint, _ = run_program(spec, inp, repeat=1)
+        apart, p2 = run_program(spec, inp, repeat=1, no_joint_folds=True)
+        assert p2.info["n_joint_folds"] == 0
+        for name, _ in spec.outputs:
+            assert np.array_equal(joint[name], apart[name]), name
+    note(f"multi pattern {seed} with column sums {rows}x{cols}: {info['n_ops']} ops -> {info['n_kernels']} launches "
+         f"({info['n_joint_folds']} folds in the joint launch), worst {worst:.3f} of the bar")
+
+
 @pytest.mark.parametrize("seed", range(8))
 def test_single_pattern_graphs_through_the_explorer(seed):
     spec = random_row_pattern(500 + seed, 37, 128, ("f32", "f16", "bf16")[seed % 3], n_ops=6 + seed)

@@ -206,3 +206,20 @@ def test_random_row_patterns(seed):
     spec = random_row_pattern(seed, rows, cols, dtype, n_ops=6 + seed % 14)
     worst, info = _run(spec, seed=seed, repeat=1)
     note(f"random pattern {seed} {rows}x{cols} {dtype}: {len(spec.ops)} ops -> {info['kernel']}, worst {worst}")
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_row_patterns_with_column_sums(seed):
+    """Seeded random patterns of which one to three full-shaped values are also summed over all rows: every launch
+    shape (rows per lane group, column tiles where no row reduction ties the columns together) and the per-op plan."""
+    dtype = ("f32", "f16", "bf16")[seed % 3]
+    rows, cols = [(37, 96), (130, 64), (64, 520), (300, 256), (1000, 128), (9, 1024)][seed % 6]
+    spec = random_row_pattern(900 + seed, rows, cols, dtype, n_ops=6 + seed % 9, column_sums=1 + seed % 3)
+    inp = make_inputs(spec, seed=seed)
+    ref = O.evaluate(spec, inp)
+    floors = {name: O.rms(ref[name]) for name, _ in spec.outputs}
+    info = B.Plan(B.Graph.from_spec(spec), "auto").info
+    if B.codegen_available():
+        assert info["pattern"] == "row_generated" and info["scheme"] == "global", (spec.name, info)
+    worst = all_candidates(spec, inp, ref, floors, repeat=2)
+    note(f"random pattern {seed} with column sums {rows}x{cols} {dtype}: {info['kernel']}, {info['n_candidates']} shapes, worst {worst}")

@@ -450,9 +450,10 @@ def rmsnorm_backward_graph(rows: int, cols: int, dtype: str = "bf16") -> GraphSp
                      ops=ops, outputs=[("dx", dtype), ("dgamma", "f32")])
 
 
-def random_row_pattern(seed: int, rows: int, cols: int, dtype: str = "f32", n_ops: int = 12) -> GraphSpec:
+def random_row_pattern(seed: int, rows: int, cols: int, dtype: str = "f32", n_ops: int = 12, column_sums: int = 0) -> GraphSpec:
     """A random connected pattern of element-wise ops and row reductions over [rows, cols] (descriptor only).
-    Domains are kept safe by construction: exp only of tanh, division and rsqrt only of 1 + square."""
+    Domains are kept safe by construction: exp only of tanh, division and rsqrt only of 1 + square.
+    column_sums: up to that many full-shaped values of the pattern are also summed over all rows (float32 outputs)."""
     import random
     rnd = random.Random(seed)
     inputs = [TensorSpec("x0", dtype, (rows, cols))]
@@ -530,7 +531,14 @@ def random_row_pattern(seed: int, rows: int, cols: int, dtype: str = "f32", n_op
     ops = [o for o in ops if o.out in live]
     inputs = [t for t in inputs if t.name in live] or inputs[:1]
     outputs = [(n, dtype if kinds[n] == "full" else "f32") for n in outs]
-    return GraphSpec(name=f"pattern_random{seed}_{dtype}_{rows}x{cols}", inputs=inputs, ops=ops, outputs=outputs)
+    if column_sums > 0:
+        summed = [o.out for o in ops if kinds[o.out] == "full"]
+        rnd.shuffle(summed)
+        for i, n in enumerate(sorted(summed[:column_sums], key=lambda n: int(n[1:]))):
+            ops.append(_op(f"cs{i}", "reduce_sum", n, axis=0))
+            outputs.append((f"cs{i}", "f32"))
+    return GraphSpec(name=f"pattern_random{seed}_{dtype}_{rows}x{cols}" + (f"_cs{column_sums}" if column_sums else ""),
+                     inputs=inputs, ops=ops, outputs=outputs)
 
 
 # ---- graphs that hold many fusion patterns (input of the fusion explorer) ----
@@ -643,7 +651,7 @@ def transformer_block_backward_graph(batch: int = 32, seq: int = 128, heads: int
 
 
 def random_multi_pattern(seed: int, rows: int = 24, cols: int = 32, segments: int = 3, dtype: str = "f32",
-                         seg_ops: Tuple[int, int] = (3, 9)) -> GraphSpec:
+                         seg_ops: Tuple[int, int] = (3, 9), column_sums: int = 0) -> GraphSpec:
     """Several random row patterns chained through transposes (each transpose turns the previous segment's
     columns into rows, so no single row kernel can span it) plus an independent side pattern."""
     import random
@@ -654,7 +662,7 @@ def random_multi_pattern(seed: int, rows: int = 24, cols: int = 32, segments: in
     carry = None
     r, c = rows, cols
     for s in range(segments):
-        seg = random_row_pattern(seed * 17 + s, r, c, dtype, n_ops=rnd.randint(*seg_ops))
+        seg = random_row_pattern(seed * 17 + s, r, c, dtype, n_ops=rnd.randint(*seg_ops), column_sums=column_sums)
         ren = {t.name: f"s{s}_{t.name}" for t in seg.inputs}
         ren.update({o.out: f"s{s}_{o.out}" for o in seg.ops})
         seg_inputs = list(seg.inputs)
