@@ -6,6 +6,7 @@
 // compiler does the register allocation and scheduling that the interpreter pays for at
 // run time with an LDS register file and a dispatch per instruction.  The source is
 // compiled at plan time by the run-time compiler (kernels/gen_runtime.hip).
+#include <algorithm>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -198,16 +199,31 @@ std::string chunked_body(const RowProgP& p, const char* entry) {
     const std::string at = ((p.rscal_bcast >> i) & 1u) ? stretched_row(p.rms[i]) : std::string("(size_t)row0.row_c");
     s += fmt("  const float in_rscal%d = load1(static_cast<const %s*>(a.rscal[%d]) + %s);\n", i, storage_type(p.rscal_dt[i]), i, at.c_str());
   }
-  // one chunk's share of a pass, for the row object `row` in scope
-  auto piece = [&](int pass, bool last_chunk) {
+  // The first `kept` chunks stay in registers, in storage form, from the first pass on: 1024 lanes hold more of a
+  // row in their registers (64 of them hold 256 KB) than the compute unit's LDS would, and later passes then read
+  // nothing of those chunks again.  Register arrays cannot be indexed at run time, so the kept chunks are written
+  // out one by one; the others are walked by a loop.
+  const uint32_t kept = (uint32_t)std::max(0, std::min(p.col_kept, p.col_chunks));
+  for (uint32_t c = 0; c < kept; ++c)
+    for (int i = 0; i < p.n_full; ++i)
+      s += fmt("  %s::Raw<%s> kept%d_%u;\n", c == NC - 1u ? "TailRow" : "Row", storage_type(p.full_dt[i]), i, c);
+  // one chunk's share of a pass, for the row object `row` in scope; kept_chunk >= 0: that chunk stays in registers
+  auto piece = [&](int pass, bool last_chunk, int kept_chunk) {
     std::string t;
     const bool last_pass = pass == n_red;
     for (int i = 0; i < p.n_full; ++i) {
       const bool stretched = ((p.full_bcast >> i) & 1u) != 0;
       const std::string at = stretched ? stretched_row(p.ms[i]) : std::string("(size_t)row.row_c");
-      // only the last pass reads an operand for the last time
-      t += fmt("  const auto raw_full%d = row.load<%s, %s>(a.full[%d], %s);\n", i, storage_type(p.full_dt[i]),
-               (stretched || !last_pass) ? "false" : "true", i, at.c_str());
+      if (kept_chunk >= 0 && pass > 0) {
+        // (the compiler must not carry the unpacked form over from the pass before: that would take the registers twice)
+        t += fmt("  kept%d_%d.forget_contents();\n  const auto& raw_full%d = kept%d_%d;\n", i, kept_chunk, i, i, kept_chunk);
+        continue;
+      }
+      // an operand is read for the last time in the last pass, or in the first one where its chunk is kept
+      const bool once = !stretched && (last_pass || kept_chunk >= 0);
+      t += fmt("  const auto raw_full%d = row.load<%s, %s>(a.full[%d], %s);\n", i, storage_type(p.full_dt[i]), once ? "true" : "false", i,
+               at.c_str());
+      if (kept_chunk >= 0) t += fmt("  kept%d_%d = raw_full%d;\n", i, kept_chunk, i);
     }
     for (int i = 0; i < p.n_col; ++i)
       t += fmt("  const auto raw_col%d = row.load<%s, false>(a.col[%d], 0);\n", i, storage_type(p.col_dt[i]), i);
@@ -233,14 +249,22 @@ std::string chunked_body(const RowProgP& p, const char* entry) {
   for (int pass = 0; pass <= n_red; ++pass) {
     s += "  {\n";
     if (pass < n_red) s += fmt("  float part = %s;\n", is_max[pass] ? "-__builtin_huge_valf()" : "0.0f");
-    // every other pass walks the row backwards: it starts with the chunks the pass before read last, which the
-    // caches are likeliest to hold still
+    // the kept chunks, one block each
+    std::string in_registers;
+    for (uint32_t c = 0; c < kept; ++c) {
+      const bool is_tail = c == NC - 1u;
+      in_registers += fmt("  {\n  const %s row(fs_block, 0, %uu);\n", is_tail ? "TailRow" : "Row", c * chunk) + piece(pass, is_tail, (int)c) + "  }\n";
+    }
+    // the others: whole chunks by a loop, then the row's last chunk.  Every other pass walks them backwards: it
+    // starts with the chunks the pass before read last, which the caches are likeliest to hold still
     const bool backwards = (pass & 1) != 0;
-    const std::string whole = fmt("#pragma unroll 1\n  for (uint32_t chunk = 0; chunk < %uu; ++chunk) {\n  const Row row(fs_block, 0, %s * %uu);\n",
-                                  NC - 1u, backwards ? fmt("(%uu - chunk)", NC - 2u).c_str() : "chunk", chunk) +
-                              piece(pass, false) + "  }\n";
-    const std::string last = fmt("  {\n  const TailRow row(fs_block, 0, %uu);\n", (NC - 1u) * chunk) + piece(pass, true) + "  }\n";
-    s += backwards ? last + whole : whole + last;
+    std::string from_memory_whole, from_memory_last;
+    if (kept < NC - 1u)
+      from_memory_whole = fmt("#pragma unroll 1\n  for (uint32_t chunk = %uu; chunk < %uu; ++chunk) {\n  const Row row(fs_block, 0, %s * %uu);\n",
+                              kept, NC - 1u, backwards ? fmt("(%uu - chunk)", NC - 2u + kept).c_str() : "chunk", chunk) +
+                          piece(pass, false, -1) + "  }\n";
+    if (kept < NC) from_memory_last = fmt("  {\n  const TailRow row(fs_block, 0, %uu);\n", (NC - 1u) * chunk) + piece(pass, true, -1) + "  }\n";
+    s += backwards ? from_memory_last + from_memory_whole + in_registers : in_registers + from_memory_whole + from_memory_last;
     if (pass < n_red) s += fmt("  red%d = Row::finish<%s>(part, slots + %d);\n", pass, is_max[pass] ? "OpMax" : "OpSum", n_waves * pass);
     s += "  }\n";
   }

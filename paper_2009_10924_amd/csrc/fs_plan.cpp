@@ -340,7 +340,8 @@ int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) {
       s += "  colsums " + std::to_string(q.n_colsum) + " partials " + buf_name(l.ptr[kSlotWs]) + " rows_per_group " +
            std::to_string(q.rows_per_group) + " col_tiles " + std::to_string(q.col_tiles > 1 ? q.col_tiles : 1) + "\n";
     if (q.col_chunks > 1)   // the row in pieces of lanes * vecs steps, a pass per row reduction and one for the stores
-      s += "  chunks " + std::to_string(q.col_chunks) + " of " + std::to_string(q.lanes_per_row * q.vecs_per_lane * q.vec) + " columns\n";
+      s += "  chunks " + std::to_string(q.col_chunks) + " of " + std::to_string(q.lanes_per_row * q.vecs_per_lane * q.vec) + " columns" +
+           (q.col_kept > 0 ? ", the first " + std::to_string(q.col_kept) + " kept in registers" : std::string()) + "\n";
     static const char* op_names[] = {"add", "sub", "rsub", "mul", "div", "rdiv", "max", "square", "exp", "rsqrt", "tanh", "gelu",
                                      "gelu_grad", "cvt", "load", "rsum", "rmax", "rsumsq", "store", "store_scal", "colsum"};
     static const char* kind_names[] = {"acc", "sacc", "reg", "scal", "imm", "col"};

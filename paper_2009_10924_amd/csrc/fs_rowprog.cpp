@@ -612,6 +612,7 @@ struct Compiler {
     p.rows_per_group = 1;
     p.col_tiles = 1;
     p.col_chunks = 1;
+    p.col_kept = 0;
     if (n_colsum > 0) interpretable = false;
     return n_out + n_rout + n_colsum == (int)g.outputs.size();
   }
@@ -629,6 +630,7 @@ struct Shape {
   bool generated;
   uint32_t R = 1, CT = 1;
   uint32_t NC = 1;   // > 1: the row is worked through in NC chunks of L * K steps (rows beyond any workgroup's registers)
+  uint32_t kept = 0; // of those, the first `kept` stay in registers in storage form after the first pass
 };
 
 // Step widths to offer.  A pattern whose 16-bit vector inputs ask for 8 elements per step may also move float32
@@ -699,14 +701,25 @@ std::vector<Shape> enumerate_shapes(const Compiler& c, int vec, bool interpretab
     if (KB <= max_k && 64ull * 2 < nvec && (T == 256 || nvec > (uint64_t)T)) shapes.push_back({T, (int)KB, true, true});
   }
   // rows beyond 1024 threads x max_k steps: chunks of a workgroup's worth of steps, a pass per row reduction
-  // (also offered, on 1024 threads, to shorter rows whose pattern keeps more values than a lane has registers for)
+  // (also offered, on 1024 threads, to shorter rows whose pattern keeps more values than a lane has registers for).
+  // Patterns with reductions are offered a second form of each wide shape in which as many chunks as the register
+  // file has room for stay in registers in storage form after the first pass.
   if (nvec > 256ull * max_k && c.n_colsum == 0)
     for (uint32_t T : {256u, 512u, 1024u})
       for (uint32_t K : {max_k / 4, max_k / 2, max_k}) {
-        if (nvec <= 1024ull * max_k ? !(T == 1024 && K < max_k) : K == max_k / 4) continue;
         Shape t{T, (int)K, true, true};
         t.NC = (nvec + T * K - 1) / (T * K);
-        if (t.NC >= 2 && t.NC <= 4096) shapes.push_back(t);
+        if (t.NC < 2 || t.NC > 4096) continue;
+        const bool plain = nvec <= 1024ull * max_k ? (T == 1024 && K < max_k) : K != max_k / 4;
+        if (plain) shapes.push_back(t);
+        if (c.n_reductions == 0 || T == 256) continue;
+        int regs_per_chunk = 0;   // registers a lane needs to keep one chunk of every row operand
+        for (int i = 0; i < c.p.n_full; ++i) regs_per_chunk += (int)K * ((vec * dtype_bytes(c.p.full_dt[i]) + 3) / 4);
+        const int body = 24 + (int)K * vec * (c.p.n_regs + 1 + (c.p.n_col > 0 ? 1 : 0)) + 2 * (int)K * c.p.n_full;
+        const int room = 512 / (int)(T / 256) - body - 8;
+        if (regs_per_chunk == 0 || room < regs_per_chunk) continue;
+        t.kept = std::min<uint32_t>(t.NC, (uint32_t)(room / regs_per_chunk));
+        if (t.NC - t.kept <= 64) shapes.push_back(t);   // the kept chunks are written out one by one: keep the source short
       }
   if (c.n_colsum == 0) return shapes;
   // Without row reductions nothing ties the columns of a row together: a workgroup may take one tile of 64 or 128
@@ -736,6 +749,7 @@ void fill_launch(const fs_graph& g, const Compiler& c, int vec, const Shape& s, 
   q.rows_per_group = (int32_t)s.R;
   q.col_tiles = (int32_t)s.CT;
   q.col_chunks = (int32_t)s.NC;
+  q.col_kept = (int32_t)s.kept;
   l->args.u.prog = q;
   auto in_ref = [&](int32_t t) {   // a transposed view binds the buffer of the input it views
     BufRef r;
@@ -826,11 +840,20 @@ void make_generated(const Compiler& c, int vec, const Shape& s, Candidate* cand)
   if (s.NC > 1) {
     // a pass over the row per reduction re-reads the operands (counted as device-memory traffic: the rows in flight
     // are larger than the caches in general) and repeats the arithmetic before its reduction
-    snprintf(cand->info.kernel, sizeof cand->info.kernel, "row_generated<v%d,K%d,L%u,I%d,R%d,chunks%u>", vec, s.K, s.L, base.n_instr,
-             base.n_regs, s.NC);
+    if (s.kept > 0)
+      snprintf(cand->info.kernel, sizeof cand->info.kernel, "row_generated<v%d,K%d,L%u,I%d,R%d,chunks%u,kept%u>", vec, s.K, s.L, base.n_instr,
+               base.n_regs, s.NC, s.kept);
+    else
+      snprintf(cand->info.kernel, sizeof cand->info.kernel, "row_generated<v%d,K%d,L%u,I%d,R%d,chunks%u>", vec, s.K, s.L, base.n_instr,
+               base.n_regs, s.NC);
     double in_bytes = 0;
-    for (int i = 0; i < base.n_full; ++i)
+    int regs_per_chunk = 0;
+    for (int i = 0; i < base.n_full; ++i) {
       if (!((base.full_bcast >> i) & 1u)) in_bytes += (double)dtype_bytes(base.full_dt[i]) * base.rows * base.cols;
+      regs_per_chunk += s.K * ((vec * dtype_bytes(base.full_dt[i]) + 3) / 4);
+    }
+    in_bytes *= 1.0 - (double)s.kept / s.NC;   // chunks kept in registers are not read again
+    gc.vgpr_estimate += regs_per_chunk * (int)s.kept;
     // ... unless the rows the resident workgroups are working on fit the memory-side cache (with room for the
     // outputs passing through): wide workgroups keep fewer rows in flight
     const double wgs_per_cu = std::max(1.0, std::floor(2048.0 / s.L));

@@ -83,6 +83,19 @@ template <> struct StepBits<2> {
     return r;
   }
 };
+// Registers that hold a step in storage form across several passes: after this the compiler no longer knows what is
+// in them, so it cannot carry the unpacked float32 form (twice the registers of a 16-bit step) from one pass to the
+// next instead.  No instruction is emitted.
+__device__ __forceinline__ void forget_contents(StepBits<32>& s) { asm volatile("" : "+v"(s.lo), "+v"(s.hi)); }
+__device__ __forceinline__ void forget_contents(StepBits<16>& s) { asm volatile("" : "+v"(s.w)); }
+__device__ __forceinline__ void forget_contents(StepBits<8>& s) { asm volatile("" : "+v"(s.w)); }
+__device__ __forceinline__ void forget_contents(StepBits<4>& s) { asm volatile("" : "+v"(s.w)); }
+__device__ __forceinline__ void forget_contents(StepBits<2>& s) {
+  uint32_t t = s.w;
+  asm volatile("" : "+v"(t));
+  s.w = (uint16_t)t;
+}
+
 __device__ __forceinline__ void unpack_step(const StepBits<32>& r, float (&v)[8], const float*) {
   float a[4], b[4];
   unpack(r.lo, a, (const float*)nullptr);
@@ -145,6 +158,10 @@ struct GenRow {
   template <typename T>
   struct Raw {
     StepBits<VEC * (int)sizeof(T)> w[K];
+    __device__ __forceinline__ void forget_contents() {
+#pragma unroll
+      for (int k = 0; k < K; ++k) fsk::forget_contents(w[k]);
+    }
   };
   template <typename T, bool STREAM>
   __device__ __forceinline__ Raw<T> load(const void* p, size_t at_row) const {

@@ -247,6 +247,8 @@ struct RowProgP {
                                        // (generated kernels for patterns with column sums and no row reduction)
   int32_t col_chunks;                  // > 1: a row too long for the lanes' registers is worked through in col_chunks pieces of
                                        // lanes_per_row * vecs_per_lane steps, once per row reduction and once more for the stores
+  int32_t col_kept;                    // of those chunks, the first col_kept stay in registers in storage form after the first
+                                       // pass (the later passes do not read them again)
   ProgInstr instr[kProgMaxInstr];
 };
 struct ProgArgs {

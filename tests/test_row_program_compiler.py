@@ -330,14 +330,20 @@ def test_rows_beyond_a_workgroups_registers_compile_to_passes_over_chunks(cols, 
         plan = B.Plan(B.Graph.from_spec(spec), "auto")
         info, src, listing = plan.info, plan.source(), plan.describe()
         assert info["pattern"] == "row_generated" and "chunks" in info["kernel"] and info["n_kernels"] == 1
-        chunks, width = [int(w) for w in listing[listing.index("  chunks "):].split()[1:4:2]]
+        line = listing[listing.index("  chunks "):].splitlines()[0].split()
+        chunks, width, kept = int(line[1]), int(line[3]), (int(line[7]) if "kept" in line else 0)
         assert (chunks - 1) * width < cols <= chunks * width and width == info["lanes_per_row"] * info["vecs_per_lane"] * (8 if "<v8" in info["kernel"] else 4 if "<v4" in info["kernel"] else 1)
-        assert src.count("for (uint32_t chunk = 0;") == reductions + 1 and src.count("Row::finish<") == reductions
-        assert f"TailRow row(fs_block, 0, {(chunks - 1) * width}u)" in src
-        # every full-shaped output is stored in the last pass only: once per whole chunk and once for the last one
+        assert kept == 0 or reductions > 0                      # keeping chunks in registers only pays when a later pass reads them
+        passes = reductions + 1
+        looped, tail_apart = kept < chunks - 1, kept < chunks    # what is not kept: whole chunks by a loop, the last chunk by itself
+        assert src.count("for (uint32_t chunk = ") == (passes if looped else 0) and src.count("Row::finish<") == reductions
+        assert src.count(f"TailRow row(fs_block, 0, {(chunks - 1) * width}u)") == passes
+        assert src.count(".forget_contents();") == kept * len(spec.inputs[:1]) * (passes - 1) * sum(1 for t in spec.inputs if len(t.dims) == 2 and t.dims[-1] == cols)
+        # every full-shaped output is stored in the last pass only, once per piece of source that handles a chunk
         ref = O.evaluate(spec, make_inputs(spec, seed=4))
         n_full_out = sum(1 for name, _ in spec.outputs if ref[name].shape[-1] == cols)
-        assert src.count("row.store<") == 2 * n_full_out and src.count("row.store_scalar<") == len(spec.outputs) - n_full_out
+        pieces = kept + (1 if looped else 0) + (1 if tail_apart else 0)
+        assert src.count("row.store<") == pieces * n_full_out and src.count("row.store_scalar<") == len(spec.outputs) - n_full_out
         got, _ = emulate(listing, spec, make_inputs(spec, seed=4), (3, cols))
         for name, dt in spec.outputs:
             r = ref[name].reshape(got[name].shape)
