@@ -82,6 +82,37 @@ def test_packed_launch_and_explored_program_under_capture():
     _capture_and_replay(call2, outs2, lambda k: ins2[0].mul_(1.0))
 
 
+def test_program_with_joint_fold_launch_under_capture():
+    """The backward block: generated kernels with column sums, their partial sums in the plans' workspaces, and the
+    one fold launch behind the last step that finishes all of them."""
+    if not B.codegen_available():
+        pytest.skip("column sums inside patterns need the run-time compiler")
+    from workloads import transformer_block_backward_graph
+    spec = transformer_block_backward_graph(3, 40, 4, 32, 256, "bf16")
+    prog = B.Program(B.Graph.from_spec(spec))
+    assert prog.info["n_joint_folds"] >= 2
+    ins, outs = _buffers(spec)
+    ws = prog.make_workspace()
+
+    def call(stream):
+        prog.bind([t.data_ptr() for t in ins], [t.data_ptr() for t in outs], ws.data_ptr(), ws.numel(), stream)()
+    _capture_and_replay(call, outs, lambda k: ins[0].mul_(1.0))
+
+
+def test_row_worked_through_in_chunks_under_capture():
+    if not B.codegen_available():
+        pytest.skip("rows of this length exist as generated kernels only")
+    from workloads import softmax_graph
+    spec = softmax_graph(6, 70000, "bf16")
+    plan = B.Plan(B.Graph.from_spec(spec), "auto")
+    assert "chunks" in plan.info["kernel"]
+    ins, outs = _buffers(spec)
+
+    def call(stream):
+        plan.bind([t.data_ptr() for t in ins], [t.data_ptr() for t in outs], 0, 0, stream)()
+    _capture_and_replay(call, outs, lambda k: ins[0].mul_(1.0))
+
+
 @pytest.mark.parametrize("generated", [False, True])
 def test_row_program_under_capture(generated):
     """The interpreted form (register file beyond 64 KB of LDS) and the generated kernel (launched through its
