@@ -1025,6 +1025,7 @@ fs_status fs_program_execute(const fs_program* p, const void* const* inputs, voi
       t.stride[k] = f.cols;
       t.split[k] = f.fold_split;
       t.quads[k] = f.fold_quads;
+      t.out_dt[k] = f.dt;
       blocks += l.shape.grid[0];
     }
     const int err = launch_fold_many(t, blocks, hip_stream);

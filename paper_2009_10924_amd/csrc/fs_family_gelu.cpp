@@ -3,9 +3,10 @@
 
 namespace fs {
 
-void make_fold_launch(Launch* f, uint32_t n_rows, uint32_t width, uint32_t split, uint32_t stride) {
+void make_fold_launch(Launch* f, uint32_t n_rows, uint32_t width, uint32_t split, uint32_t stride, int32_t out_dt) {
   f->kernel = K_COLFOLD;
   GeluP fp{};
+  fp.dt = out_dt;
   fp.n_row_tiles = n_rows;
   fp.cols = stride ? stride : width;   // distance between partial rows (a fold may take a slice of wider rows)
   fp.fold_cols = width;

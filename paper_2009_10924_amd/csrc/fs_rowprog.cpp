@@ -53,6 +53,7 @@ struct Compiler {
   int n_out = 0, n_rout = 0, n_reductions = 0;
   int n_colsum = 0;                       // column sums over all rows: outputs only, handed out by a fold launch
   int32_t colsum_slot[kProgMaxColSums];   // their fs_execute output slots
+  int32_t colsum_dt = -1;                 // the dtype they are handed out in (one for all of a pattern's sums)
   std::vector<char> is_colsum;            // per op
   int vec_instr = 0, scal_instr = 0, reg_reads = 0, reg_writes = 0, trans = 0;
   std::vector<int> free_regs, free_sregs;
@@ -461,10 +462,12 @@ struct Compiler {
         case FS_REDUCE_SUM: case FS_REDUCE_MAX: case FS_REDUCE_MEAN: {
           const Tensor& src = g.tensors[op.in[0]];
           if (op.opcode == FS_REDUCE_SUM && op.axis == 0 && src.rank == 2 && rank == 2 && ka == V_FULL && !stretched_rows(src) &&
-              out.output_slot >= 0 && out.consumers.empty() && out.store_as == FS_F32 && cols % 4 == 0) {
+              out.output_slot >= 0 && out.consumers.empty() && out.store_as != FS_I32 && cols % 4 == 0 &&
+              (colsum_dt < 0 || colsum_dt == (int32_t)out.store_as)) {
             // the sum over all rows: every workgroup leaves partial sums, a second launch folds them.  Nothing in the
             // pattern can read it (that would take a grid-wide wait), so it has to be a graph output.
             is_colsum[i] = 1;
+            colsum_dt = (int32_t)out.store_as;
             want = V_COL;
             break;
           }
@@ -886,7 +889,7 @@ void add_column_sums(const Compiler& c, int vec, const Shape& s, int64_t bytes_m
     const int here = std::min(2, c.n_colsum - first);
     cand->launches.emplace_back();
     Launch& f = cand->launches.back();
-    make_fold_launch(&f, n_wg, (uint32_t)here * base.cols, base.cols, width);
+    make_fold_launch(&f, n_wg, (uint32_t)here * base.cols, base.cols, width, c.colsum_dt);
     f.ptr[0].kind = BUF_WORKSPACE;
     f.ptr[0].offset = (int64_t)first * base.cols * 4;
     for (int i = 0; i < here; ++i) {

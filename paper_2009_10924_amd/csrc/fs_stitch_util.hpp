@@ -104,6 +104,6 @@ bool build_rmsnorm(const fs_graph& g, std::vector<Candidate>* out, PackForm* pac
 // The launch that folds [n_rows, width] float32 column partials (second step of a global hand-off).
 // K_COLFOLD over partial rows of `width` floats (`stride` floats apart, 0 = width): columns below `split` go to the
 // launch's first output, the rest to its second.
-void make_fold_launch(Launch* f, uint32_t n_rows, uint32_t width, uint32_t split, uint32_t stride = 0);
+void make_fold_launch(Launch* f, uint32_t n_rows, uint32_t width, uint32_t split, uint32_t stride = 0, int32_t out_dt = DT_F32);
 
 }  // namespace fs

@@ -170,7 +170,7 @@ __global__ void __launch_bounds__(WAVES * 64) k_bias_gelu_dbias(const T* __restr
 template <int Q, int G>
 __device__ __forceinline__ void fold_tile(const float* __restrict__ partials, float* __restrict__ out0, float* __restrict__ out1,
                                           uint32_t n, uint32_t width, uint32_t stride, uint32_t split, uint32_t block,
-                                          f32x4* __restrict__ sm) {
+                                          f32x4* __restrict__ sm, int32_t out_dt) {
   const uint32_t q = threadIdx.x % Q, g = threadIdx.x / Q;
   const uint32_t col = (block * Q + q) * 4u;
   f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -191,9 +191,17 @@ __device__ __forceinline__ void fold_tile(const float* __restrict__ partials, fl
     f32x4 v = sm[q];
 #pragma unroll
     for (int k = 1; k < G; ++k) v += sm[k * Q + q];
-    // the split is a multiple of 4, so a quad never straddles the two outputs
-    float* dst = col < split ? out0 + col : out1 + (col - split);
-    *reinterpret_cast<f32x4*>(dst) = v;
+    // the split is a multiple of 4, so a quad never straddles the two outputs; sums handed out in 16 bits are
+    // rounded here, once
+    float* const base = col < split ? out0 : out1;
+    const uint32_t at = col < split ? col : col - split;
+    if (out_dt == DT_F32) {
+      *reinterpret_cast<f32x4*>(base + at) = v;
+    } else {
+      const float quad[4] = {v.x, v.y, v.z, v.w};
+      if (out_dt == DT_BF16) StoreN<bf16_t, 4>::run(reinterpret_cast<bf16_t*>(base) + at, quad);
+      else StoreN<f16_t, 4>::run(reinterpret_cast<f16_t*>(base) + at, quad);
+    }
   }
 }
 
@@ -202,7 +210,7 @@ __global__ void __launch_bounds__(256) k_colfold(const float* __restrict__ parti
                                                  float* __restrict__ out1, GeluP p) {
   __shared__ f32x4 sm[G * Q];
   // stride >= width: a fold may take a slice of wider partial rows
-  fold_tile<Q, G>(partials, out0, out1, p.n_row_tiles, p.fold_cols, p.cols, p.fold_split, blockIdx.x, sm);
+  fold_tile<Q, G>(partials, out0, out1, p.n_row_tiles, p.fold_cols, p.cols, p.fold_split, blockIdx.x, sm, p.dt);
 }
 
 // Several independent folds in one launch: workgroups [first_block[i], first_block[i+1]) run fold i.  The table
@@ -223,9 +231,9 @@ __global__ void __launch_bounds__(256) k_colfold_many(const FoldManyP table_in_k
   float* out1 = tab->out1[i];
   const uint32_t block = b - tab->first_block[i];
   if (tab->quads[i] == 4)
-    fold_tile<4, 64>(partials, out0, out1, tab->n[i], tab->width[i], tab->stride[i], tab->split[i], block, sm);
+    fold_tile<4, 64>(partials, out0, out1, tab->n[i], tab->width[i], tab->stride[i], tab->split[i], block, sm, tab->out_dt[i]);
   else
-    fold_tile<16, 16>(partials, out0, out1, tab->n[i], tab->width[i], tab->stride[i], tab->split[i], block, sm);
+    fold_tile<16, 16>(partials, out0, out1, tab->n[i], tab->width[i], tab->stride[i], tab->split[i], block, sm, tab->out_dt[i]);
 }
 
 }  // namespace fsk

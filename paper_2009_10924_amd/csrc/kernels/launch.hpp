@@ -33,7 +33,7 @@ enum KernelId : int32_t {
   K_LAYERNORM_BLOCK,
   K_BIAS_GELU,         // p0 x, p1 bias, p2 y
   K_BIAS_GELU_DBIAS,   // p0 x, p1 bias, p2 grad, p3 y, p4 dbias, p5 partials, p6 counters
-  K_COLFOLD,           // p0 partials [n_row_tiles, fold_cols] f32, p1 out0 (columns < fold_split), p2 out1 (the rest)
+  K_COLFOLD,           // p0 partials [n_row_tiles, fold_cols] f32, p1 out0 (columns < fold_split), p2 out1 (the rest), both of dtype dt
   K_TCHAIN_WAVE,       // p0 x, p1 scale, p2 out
   K_TCHAIN_LDS,
   K_ROW_WAVE,          // p0,p1 row inputs, p2,p3 column vectors, p4 out0, p5 out1 : generic row-stitched skeleton
@@ -114,7 +114,7 @@ struct LayerNormP {
   int32_t fast;                     // 1: all operands present, row and row count fill lanes / workgroups exactly
 };
 struct GeluP {
-  int32_t dt, bias_dt;              // x / grad / y share dt
+  int32_t dt, bias_dt;              // x / grad / y share dt; K_COLFOLD: dt = dtype the sums are handed out in
   uint32_t rows, cols;              // K_COLFOLD: cols = floats between two partial rows
   uint32_t n_row_tiles;             // row blocks = rows of the partials workspace
   int32_t waves, unroll;            // workgroup = waves x 64 lanes; a row tile = waves * unroll rows
@@ -286,6 +286,7 @@ struct FoldManyP {
   float* out1[kFoldManyMax];
   uint32_t first_block[kFoldManyMax];   // first workgroup of each job; [0] = 0, unused entries = 0xffffffff
   uint32_t n[kFoldManyMax], width[kFoldManyMax], stride[kFoldManyMax], split[kFoldManyMax], quads[kFoldManyMax];
+  int32_t out_dt[kFoldManyMax];         // dtype the sums are handed out in
 };
 int launch_fold_many(const FoldManyP& table, uint32_t n_blocks, void* stream);
 

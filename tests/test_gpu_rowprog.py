@@ -208,6 +208,18 @@ def test_random_row_patterns(seed):
     note(f"random pattern {seed} {rows}x{cols} {dtype}: {len(spec.ops)} ops -> {info['kernel']}, worst {worst}")
 
 
+@pytest.mark.parametrize("rows,cols,dtype,sum_dtype", [(1000, 128, "bf16", "bf16"), (300, 768, "f16", "f16"), (2500, 1024, "f32", "bf16"), (37, 96, "bf16", "f16")])
+def test_column_sums_handed_out_in_16_bits(rows, cols, dtype, sum_dtype):
+    """The fold launch rounds the float32 sum once, to the dtype the gradient is wanted in."""
+    if not B.codegen_available():
+        pytest.skip("column sums inside a row pattern exist as generated kernels only")
+    for make, launches in ((gelu_backward_graph, 2), (layernorm_backward_bias_graph, 3)):
+        spec = make(rows, cols, dtype, sum_dtype=sum_dtype)
+        worst, info = _run(spec, repeat=2)
+        assert info["pattern"] == "row_generated" and info["n_kernels"] == launches and info["scheme"] == "global"
+        note(f"{spec.name} sums as {sum_dtype}: {info['kernel']}, worst {worst}")
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_random_row_patterns_with_column_sums(seed):
     """Seeded random patterns of which one to three full-shaped values are also summed over all rows: every launch

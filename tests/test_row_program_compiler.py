@@ -242,6 +242,19 @@ def test_transposed_views_that_are_outputs_compile_to_load_and_store():
     assert listing.count("rowstrides=15,1,3") == 3 and listing.count(" store ") == 4
 
 
+def test_column_sums_of_one_pattern_share_the_dtype_they_are_handed_out_in():
+    from workloads import gelu_backward_graph, layernorm_backward_bias_graph
+    from workloads.graphs import GraphSpec
+    if not B.codegen_available():
+        pytest.skip("needs the run-time compiler")
+    plan = B.Plan(B.Graph.from_spec(gelu_backward_graph(64, 128, "bf16", sum_dtype="bf16")), "auto")
+    assert plan.info["pattern"] == "row_generated" and plan.info["n_kernels"] == 2
+    spec = layernorm_backward_bias_graph(64, 128, "bf16", sum_dtype="bf16")
+    mixed = GraphSpec(spec.name + "_mixed", spec.inputs, spec.ops, [(n, "f32" if n == "dgamma" else d) for n, d in spec.outputs])
+    assert B.Plan(B.Graph.from_spec(spec), "auto").info["pattern"] == "row_generated"
+    assert B.Plan(B.Graph.from_spec(mixed), "auto").info["scheme"] == "unfused"     # one fold launch rounds to one dtype
+
+
 @pytest.mark.parametrize("rows,cols", [(37, 96), (50, 128), (9, 1024)])
 def test_column_sums_compile_to_partial_sums_and_a_fold(rows, cols):
     from workloads import gelu_backward_graph, layernorm_backward_bias_graph, rmsnorm_backward_graph
@@ -291,7 +304,7 @@ def test_patterns_that_are_not_row_local_are_refused():
                      [OpSpec("e", "exp", ("x",)), OpSpec("s", "reduce_sum", ("e",), {"axis": 0}), OpSpec("y", "div", ("e", "s"))],
                      [("y", "f32")])
     assert B.Plan(B.Graph.from_spec(spec), "auto").info["scheme"] == "unfused"
-    # a column maximum, or a column sum stored in 16 bits: no fold kernel hands those out
+    # a column maximum: the fold kernel hands out sums only
     spec = GraphSpec("pattern_x", [TensorSpec("x", "f32", (8, 16))],
                      [OpSpec("e", "exp", ("x",)), OpSpec("s", "reduce_max", ("e",), {"axis": 0})], [("s", "f32")])
     assert B.Plan(B.Graph.from_spec(spec), "auto").info["scheme"] == "unfused"

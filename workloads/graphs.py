@@ -403,16 +403,17 @@ def transposed_softmax_graph(batch: int, q_len: int, heads: int, k_len: int, dty
                      inputs=[TensorSpec("scores", dtype, (batch, q_len, heads, k_len))], ops=ops, outputs=[("y", dtype)])
 
 
-def gelu_backward_graph(rows: int, cols: int, dtype: str = "bf16") -> GraphSpec:
-    """Backward of bias + tanh-GELU: dx = g * gelu'(x + bias) and the bias gradient, the column sum of dx (float32)."""
+def gelu_backward_graph(rows: int, cols: int, dtype: str = "bf16", sum_dtype: str = "f32") -> GraphSpec:
+    """Backward of bias + tanh-GELU: dx = g * gelu'(x + bias) and the bias gradient, the column sum of dx (handed out
+    as float32, or rounded once to `sum_dtype`)."""
     ops = [_op("z", "add", "x", "bias"), _op("d", "gelu_tanh_grad", "z"), _op("dx", "mul", "g", "d"),
            _op("dbias", "reduce_sum", "dx", axis=0)]
-    return GraphSpec(name=f"pattern_gelu_backward_{dtype}_{rows}x{cols}",
+    return GraphSpec(name=f"pattern_gelu_backward_{dtype}_{rows}x{cols}" + ("" if sum_dtype == "f32" else f"_sum_{sum_dtype}"),
                      inputs=[TensorSpec("x", dtype, (rows, cols)), TensorSpec("bias", dtype, (cols,)), TensorSpec("g", dtype, (rows, cols))],
-                     ops=ops, outputs=[("dx", dtype), ("dbias", "f32")])
+                     ops=ops, outputs=[("dx", dtype), ("dbias", sum_dtype)])
 
 
-def layernorm_backward_bias_graph(rows: int, cols: int, dtype: str = "bf16") -> GraphSpec:
+def layernorm_backward_bias_graph(rows: int, cols: int, dtype: str = "bf16", sum_dtype: str = "f32") -> GraphSpec:
     """LayerNorm backward from saved statistics together with the gradient of the bias that was added in front of the
     LayerNorm: dx (rounded to the storage dtype), dgamma, dbeta and dbias = column sum of the rounded dx.  Two row
     reductions and three column sums in one pattern."""
@@ -426,7 +427,7 @@ def layernorm_backward_bias_graph(rows: int, cols: int, dtype: str = "bf16") -> 
     return GraphSpec(name=f"pattern_layernorm_backward_bias_{dtype}_{rows}x{cols}",
                      inputs=[TensorSpec("h", dtype, (rows, cols)), TensorSpec("dy", dtype, (rows, cols)), TensorSpec("gamma", dtype, (cols,)),
                              TensorSpec("mu", "f32", (rows, 1)), TensorSpec("rstd", "f32", (rows, 1))],
-                     ops=ops, outputs=[("dxc", dtype), ("dbias", "f32"), ("dgamma", "f32"), ("dbeta", "f32")])
+                     ops=ops, outputs=[("dxc", dtype), ("dbias", sum_dtype), ("dgamma", sum_dtype), ("dbeta", sum_dtype)])
 
 
 def rmsnorm_backward_graph(rows: int, cols: int, dtype: str = "bf16") -> GraphSpec:
