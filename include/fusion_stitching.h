@@ -182,7 +182,10 @@ fs_status fs_plan_candidate(const fs_plan *p, int32_t index, fs_plan_info *out);
  * (c0,c1,c2) of the pattern is row c0*m0+c1*m1+c2*m2 of that buffer), and one line per
  * instruction of its accumulator machine: `instr <n> <op> b=<kind>:<index> dst=<index>
  * flags=<v|s><k|-> aux=<dtype> imm=<value>` (v: acc <- acc op b on full-shaped values,
- * s: the same on per-row values; k: result also kept in register dst).
+ * s: the same on per-row values; k: result also kept in register dst).  A pattern with
+ * sums over all rows adds `colsums <n> partials <buffer> rows_per_group <r> col_tiles <t>`
+ * (and the fold launches after it); a row that is worked through in pieces adds
+ * `chunks <n> of <w> columns[, the first <k> kept in registers]`.
  * Errors: FS_ERR_INVALID_ARG.                                                          */
 int64_t fs_plan_describe(const fs_plan *p, char *text, size_t capacity);
 
@@ -194,6 +197,12 @@ int64_t fs_plan_describe(const fs_plan *p, char *text, size_t capacity);
  * extents and its launch shape, compiled for gfx950 by the HIP run-time compiler when the
  * plan is created; fs_plan_info.kernel then starts with "row_generated").  Compiled kernels
  * are shared between plans with identical source and stay loaded until the process ends.
+ * Generated kernels only: row lengths that are no multiple of 4 elements; rows of more than
+ * 2048 128-bit vectors (workgroups of 512 / 1024 threads; beyond 8192 vectors the row is
+ * worked through in chunks, one pass per row reduction, the chunks kept in registers where
+ * they fit); sums over all rows of a rank-2 pattern (reduce_sum along axis 0, a graph
+ * output nothing else reads, float32 or rounded once to a 16-bit dtype; the plan then has
+ * fold launches and a workspace); more than 4 full-shaped inputs.
  * Compilation needs no GPU; the module is loaded on the device that is current at plan
  * creation (or, without one, by the first fs_execute: do that one outside stream capture).
  * If the compiler is not available, compilation fails or the kernel would spill registers,
