@@ -208,6 +208,19 @@ def test_random_row_patterns(seed):
     note(f"random pattern {seed} {rows}x{cols} {dtype}: {len(spec.ops)} ops -> {info['kernel']}, worst {worst}")
 
 
+@pytest.mark.parametrize("dims,dtype", [((2, 3, 2, 70000), "bf16"), ((1, 2, 3, 40004), "f32")])
+def test_rows_in_chunks_with_folded_transposes(dims, dtype):
+    """The row addressing of a folded transpose (permuted row strides in a load, a permuted row in the store) is the
+    same whether a row is handled at once or chunk by chunk."""
+    if not B.codegen_available():
+        pytest.skip("rows of this length exist as generated kernels only")
+    for make in (bias_head_split_graph, head_merge_residual_graph, transposed_softmax_graph):
+        spec = make(*dims, dtype=dtype)
+        worst, info = _run(spec)
+        assert info["pattern"] == "row_generated" and "chunks" in info["kernel"], (spec.name, info)
+        note(f"{make.__name__} {dims} {dtype}: {info['kernel']}, {info['n_candidates']} shapes, worst {worst}")
+
+
 @pytest.mark.parametrize("rows,cols,dtype,sum_dtype", [(1000, 128, "bf16", "bf16"), (300, 768, "f16", "f16"), (2500, 1024, "f32", "bf16"), (37, 96, "bf16", "f16")])
 def test_column_sums_handed_out_in_16_bits(rows, cols, dtype, sum_dtype):
     """The fold launch rounds the float32 sum once, to the dtype the gradient is wanted in."""
