@@ -346,13 +346,22 @@ struct Compiler {
     return true;
   }
 
+  std::vector<char> skip_for_anchor;   // per tensor: lives outside the row space (reached through a view or a permuted store)
+  std::vector<char> view_fold;         // per op: a transpose folded into an input's addressing
+
+  // The phases of the compilation, in order; each returns false when the pattern does not fit a row program.
   bool run() {
+    return fold_transposes() && choose_row_space() && classify_tensors() && classify_ops() && check_outputs() && peepholes() &&
+           describe_inputs() && allocate_and_emit();
+  }
+
+  bool fold_transposes() {
     // transposes first: which ones fold into a load or a store (any other kind does not fit a row program)
     const size_t n_tensors = g.tensors.size();
     view_src.assign(n_tensors, -1);
     view_op.assign(n_tensors, -1);
     stored_via.assign(n_tensors, -1);
-    std::vector<char> skip_for_anchor(n_tensors, 0);
+    skip_for_anchor.assign(n_tensors, 0);
     for (size_t i = 0; i < g.ops.size(); ++i) {
       const Op& op = g.ops[i];
       if (op.opcode != FS_TRANSPOSE) continue;
@@ -376,6 +385,11 @@ struct Compiler {
         if (g.ops[c].opcode != FS_TRANSPOSE) only_views = false;
       if (only_views) skip_for_anchor[t] = 1;
     }
+    return true;
+  }
+
+  bool choose_row_space() {
+    const size_t n_tensors = g.tensors.size();
     // anchor = the largest tensor of the row space
     int anchor = -1;
     for (size_t t = 0; t < n_tensors; ++t)
@@ -387,7 +401,11 @@ struct Compiler {
     cols = (uint32_t)dims[rank - 1];
     rows = (uint32_t)(a.numel() / cols);
     if (cols < 2) return false;
+    return true;
+  }
 
+  bool classify_tensors() {
+    const size_t n_tensors = g.tensors.size();
     // classes of all tensors; inputs by class
     for (size_t t = 0; t < n_tensors; ++t) {
       const Tensor& T = g.tensors[t];
@@ -435,12 +453,15 @@ struct Compiler {
     interpretable = p.vec == 8 || (p.vec == 4 && !narrow);
     p.rows = rows;
     p.cols = cols;
+    return true;
+  }
 
+  bool classify_ops() {
     // aliases and result classes; which ops read which roots
     const size_t n_ops = g.ops.size();
     reads.assign(n_ops, {});
     is_alias.assign(n_ops, 0);
-    std::vector<char> view_fold(n_ops, 0);
+    view_fold.assign(n_ops, 0);
     is_colsum.assign(n_ops, 0);
     for (size_t i = 0; i < n_ops; ++i) {
       const Op& op = g.ops[i];
@@ -505,6 +526,10 @@ struct Compiler {
         if (op.n_in > 1) reads[i].push_back(val[op.in[1]].root);
       }
     }
+    return true;
+  }
+
+  bool check_outputs() {
     for (int t : g.outputs) {
       if (g.tensors[t].producer < 0) return false;
       if (stored_via[t] >= 0) continue;   // a permutation of the row space: every row is written once
@@ -513,6 +538,11 @@ struct Compiler {
       if (shape != V_FULL && shape != V_RSCAL) return false;   // a per-column value has no row to be stored to
       if (stretched_rows(g.tensors[t])) return false;   // an output must own every row it is stored to
     }
+    return true;
+  }
+
+  bool peepholes() {
+    const size_t n_ops = g.ops.size();
     // peepholes.  (1) square feeding only a row sum / mean: the reduction squares on the fly, so the
     // accumulator keeps the un-squared value.  (2) a convert whose only reader is the store of the same
     // dtype: the store rounds anyway.
@@ -548,7 +578,10 @@ struct Compiler {
     }
     for (size_t i = 0; i < n_ops; ++i)
       for (int r : reads[i]) val[r].last_read = (int)i;
+    return true;
+  }
 
+  bool describe_inputs() {
     // inputs: column vectors sit in the shared column file, the others are parked in registers
     p.n_full = (int32_t)full_in.size();
     p.n_col = (int32_t)col_in.size();
@@ -584,7 +617,11 @@ struct Compiler {
         row_strides(T, p.rms[i]);
       }
     }
+    return true;
+  }
 
+  bool allocate_and_emit() {
+    const size_t n_ops = g.ops.size();
     // the first op's full-shaped input operand is handed over in the accumulator by the prologue;
     // it is parked in a register as well only if something reads it after the accumulator moved on
     p.acc_input = -1;
