@@ -75,7 +75,11 @@ enum fs_opcode {
   FS_REDUCE_SUM = 14, FS_REDUCE_MAX = 15, FS_REDUCE_MEAN = 16, /* attr: fs_attr_axis               */
   FS_TRANSPOSE = 17,     /* out.dims[i] = in.dims[perm[i]] attr: fs_attr_perm                      */
   FS_CONVERT = 18,       /* round to dtype                 attr: fs_attr_dtype                     */
-  FS_OPCODE_COUNT = 19
+  FS_LOG = 19,           /* natural logarithm                                                      */
+  FS_SIGMOID = 20,       /* 1 / (1 + exp(-x))                                                      */
+  FS_RELU = 21,          /* max(x, 0)                                                              */
+  FS_ABS = 22, FS_SQRT = 23,                                  /* 1 operand, attr: none             */
+  FS_OPCODE_COUNT = 24
 };
 
 typedef struct fs_attr_scalar { double value; } fs_attr_scalar;

@@ -18,6 +18,7 @@ Readings of points the paper leaves open (it states no numerics at all):
     subgraph is therefore the population variance of squared deviations;
   * tanh-GELU: gelu(z) = z/2 * (1 + tanh(u)), u = sqrt(2/pi) * (z + 0.044715 z^3),
     and gelu_tanh_grad is its derivative with respect to z;
+  * log is the natural logarithm, sigmoid(x) = 1 / (1 + exp(-x)), relu(x) = max(x, 0);
   * `convert` rounds to the target dtype (nearest-even) when other ops consume
     it; when it produces a subgraph output the un-rounded float64 value is
     reported unless `round_outputs=True`, so the comparison tolerance, not the
@@ -134,6 +135,26 @@ def op_gelu_tanh_grad(z):
     return 0.5 * (1.0 + t) + 0.5 * z * (1.0 - t * t) * du
 
 
+def op_log(a):
+    return np.log(a)
+
+
+def op_sigmoid(a):
+    return 1.0 / (1.0 + np.exp(-a))
+
+
+def op_relu(a):
+    return np.maximum(a, 0.0)
+
+
+def op_abs(a):
+    return np.abs(a)
+
+
+def op_sqrt(a):
+    return np.sqrt(a)
+
+
 def op_broadcast(a, dims):
     return np.broadcast_to(a, tuple(dims)).copy()
 
@@ -160,7 +181,8 @@ def op_convert(a, dtype):
 
 _BINARY = {"add": op_add, "sub": op_sub, "mul": op_mul, "div": op_div, "max": op_max}
 _UNARY = {"square": op_square, "exp": op_exp, "rsqrt": op_rsqrt, "tanh": op_tanh,
-          "gelu_tanh": op_gelu_tanh, "gelu_tanh_grad": op_gelu_tanh_grad}
+          "gelu_tanh": op_gelu_tanh, "gelu_tanh_grad": op_gelu_tanh_grad,
+          "log": op_log, "sigmoid": op_sigmoid, "relu": op_relu, "abs": op_abs, "sqrt": op_sqrt}
 
 
 def evaluate(graph, inputs: Mapping[str, np.ndarray], round_outputs: bool = False,

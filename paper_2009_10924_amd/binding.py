@@ -17,6 +17,7 @@ DTYPE_NAME = {v: k for k, v in DTYPE.items()}
 OPCODE = {
     "add": 0, "sub": 1, "mul": 2, "div": 3, "max": 4, "scale": 5, "add_scalar": 6, "square": 7,
     "exp": 8, "rsqrt": 9, "tanh": 10, "gelu_tanh": 11, "gelu_tanh_grad": 12, "broadcast": 13,
+    "log": 19, "sigmoid": 20, "relu": 21, "abs": 22, "sqrt": 23,
     "reduce_sum": 14, "reduce_max": 15, "reduce_mean": 16, "transpose": 17, "convert": 18,
 }
 SCHEME = {"auto": 0, "unfused": 1, "local": 2, "wave": 3, "lds": 4, "global": 5}

@@ -61,6 +61,11 @@ std::string expression(int op, const std::string& a, const std::string& b, int a
     case PO_TANH: return "fast_tanh(" + a + ")";
     case PO_GELU: return "gelu_fwd(" + a + ")";
     case PO_GELU_GRAD: return "gelu_grad(" + a + ")";
+    case PO_LOG: return "full_log(" + a + ")";
+    case PO_SIGMOID: return "fast_sigmoid(" + a + ")";
+    case PO_RELU: return "fmaxf(" + a + ", 0.0f)";
+    case PO_ABS: return "__builtin_fabsf(" + a + ")";
+    case PO_SQRT: return "full_sqrt(" + a + ")";
     case PO_CVT: return fmt("gen_round<%d>(", aux) + a + ")";
     default: return b;   // PO_LOAD
   }

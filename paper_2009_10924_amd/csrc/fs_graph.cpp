@@ -34,7 +34,8 @@ const char* dtype_name(int32_t dt) {
 const char* opcode_name(int32_t op) {
   static const char* names[FS_OPCODE_COUNT] = {
       "add", "sub", "mul", "div", "max", "scale", "add_scalar", "square", "exp", "rsqrt", "tanh",
-      "gelu_tanh", "gelu_tanh_grad", "broadcast", "reduce_sum", "reduce_max", "reduce_mean", "transpose", "convert"};
+      "gelu_tanh", "gelu_tanh_grad", "broadcast", "reduce_sum", "reduce_max", "reduce_mean", "transpose", "convert",
+      "log", "sigmoid", "relu", "abs", "sqrt"};
   return (op >= 0 && op < FS_OPCODE_COUNT) ? names[op] : "?";
 }
 const char* scheme_name(int32_t s) {

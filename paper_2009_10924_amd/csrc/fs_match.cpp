@@ -12,7 +12,8 @@ const Name kNames[] = {
     {"scale", FS_SCALE}, {"addc", FS_ADD_SCALAR}, {"square", FS_SQUARE}, {"exp", FS_EXP},
     {"rsqrt", FS_RSQRT}, {"tanh", FS_TANH}, {"gelu", FS_GELU_TANH}, {"gelugrad", FS_GELU_TANH_GRAD},
     {"bcast", FS_BROADCAST}, {"rsum", FS_REDUCE_SUM}, {"rmax", FS_REDUCE_MAX}, {"rmean", FS_REDUCE_MEAN},
-    {"tr", FS_TRANSPOSE}, {"cvt", FS_CONVERT},
+    {"tr", FS_TRANSPOSE}, {"cvt", FS_CONVERT}, {"log", FS_LOG}, {"sigmoid", FS_SIGMOID}, {"relu", FS_RELU}, {"abs", FS_ABS},
+    {"sqrt", FS_SQRT},
 };
 int32_t opcode_of(const std::string& s) {
   for (const Name& n : kNames)

@@ -343,7 +343,7 @@ int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) {
       s += "  chunks " + std::to_string(q.col_chunks) + " of " + std::to_string(q.lanes_per_row * q.vecs_per_lane * q.vec) + " columns" +
            (q.col_kept > 0 ? ", the first " + std::to_string(q.col_kept) + " kept in registers" : std::string()) + "\n";
     static const char* op_names[] = {"add", "sub", "rsub", "mul", "div", "rdiv", "max", "square", "exp", "rsqrt", "tanh", "gelu",
-                                     "gelu_grad", "cvt", "load", "rsum", "rmax", "rsumsq", "store", "store_scal", "colsum"};
+                                     "gelu_grad", "log", "sigmoid", "relu", "abs", "sqrt", "cvt", "load", "rsum", "rmax", "rsumsq", "store", "store_scal", "colsum"};
     static const char* kind_names[] = {"acc", "sacc", "reg", "scal", "imm", "col"};
     for (int i = 0; i < q.n_instr; ++i) {
       const ProgInstr& in = q.instr[i];

@@ -162,7 +162,8 @@ struct Compiler {
           (ins.op <= PO_MAX || ins.op == PO_LOAD)) ++reg_reads;
       if (ins.flags & PF_KEEP) ++reg_writes;
       if (ins.op == PO_DIV || ins.op == PO_RDIV || ins.op == PO_EXP || ins.op == PO_RSQRT) trans += 1;
-      if (ins.op == PO_TANH || ins.op == PO_GELU || ins.op == PO_GELU_GRAD) trans += 2;
+      if (ins.op == PO_TANH || ins.op == PO_GELU || ins.op == PO_GELU_GRAD || ins.op == PO_SIGMOID) trans += 2;
+      if (ins.op == PO_LOG || ins.op == PO_SQRT) trans += 3;   // the quarter-rate instruction plus its range fix-ups
     }
     return true;
   }
@@ -286,6 +287,11 @@ struct Compiler {
           case FS_TANH: ins.op = PO_TANH; break;
           case FS_GELU_TANH: ins.op = PO_GELU; break;
           case FS_GELU_TANH_GRAD: ins.op = PO_GELU_GRAD; break;
+          case FS_LOG: ins.op = PO_LOG; break;
+          case FS_SIGMOID: ins.op = PO_SIGMOID; break;
+          case FS_RELU: ins.op = PO_RELU; break;
+          case FS_ABS: ins.op = PO_ABS; break;
+          case FS_SQRT: ins.op = PO_SQRT; break;
           case FS_CONVERT: ins.op = PO_CVT; ins.aux = (uint8_t)op.to_dtype; break;
           case FS_REDUCE_SUM: case FS_REDUCE_MEAN: ins.op = square_of[i] >= 0 ? PO_RSUMSQ : PO_RSUM; break;
           case FS_REDUCE_MAX: ins.op = PO_RMAX; break;
@@ -475,6 +481,7 @@ struct Compiler {
           break;
         case FS_SCALE: case FS_ADD_SCALAR: case FS_SQUARE: case FS_EXP: case FS_RSQRT: case FS_TANH:
         case FS_GELU_TANH: case FS_GELU_TANH_GRAD: case FS_CONVERT:
+        case FS_LOG: case FS_SIGMOID: case FS_RELU: case FS_ABS: case FS_SQRT:
           want = ka;
           break;
         case FS_BROADCAST:

@@ -252,6 +252,11 @@ fs_status build_unfused(const fs_graph& g, Candidate* out) {
         case FS_TANH: p.op = U_TANH; break;
         case FS_GELU_TANH: p.op = U_GELU; break;
         case FS_GELU_TANH_GRAD: p.op = U_GELU_GRAD; break;
+        case FS_LOG: p.op = U_LOG; break;
+        case FS_SIGMOID: p.op = U_SIGMOID; break;
+        case FS_RELU: p.op = U_RELU; break;
+        case FS_ABS: p.op = U_ABS; break;
+        case FS_SQRT: p.op = U_SQRT; break;
         default: p.op = U_COPY; break;   // FS_CONVERT: the store does the rounding
       }
       p.in_dt = dt[op.in[0]]; p.out_dt = dst_dt;

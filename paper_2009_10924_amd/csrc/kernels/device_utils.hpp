@@ -191,6 +191,11 @@ constexpr float kLog2e = 1.4426950408889634f;
 __device__ __forceinline__ float fast_exp(float x) { return __builtin_amdgcn_exp2f(x * kLog2e); }
 __device__ __forceinline__ float fast_rcp(float x) { return __builtin_amdgcn_rcpf(x); }
 __device__ __forceinline__ float fast_rsqrt(float x) { return __builtin_amdgcn_rsqf(x); }
+// 1 / (1 + exp(-x)); saturates to 0 and 1 by itself (exp2 overflows to +inf, whose reciprocal is 0)
+__device__ __forceinline__ float fast_sigmoid(float x) { return fast_rcp(1.0f + __builtin_amdgcn_exp2f(-kLog2e * x)); }
+// the compiler's own expansions (no library call): accurate to about one unit in the last place over the whole range
+__device__ __forceinline__ float full_log(float x) { return __builtin_logf(x); }
+__device__ __forceinline__ float full_sqrt(float x) { return __builtin_sqrtf(x); }
 
 // tanh without the library routine's range reduction: 1 - 2/(1 + exp(2x)) away from zero (saturates to +-1 by
 // itself), the odd Taylor polynomial up to x^7 below |x| = 0.25 where the first form cancels.  Relative error

@@ -60,7 +60,7 @@ struct LaunchShape {
 };
 
 // ---- per-op baseline ----------------------------------------------------------
-enum UnaryOp : int32_t { U_COPY = 0, U_SCALE, U_ADD_SCALAR, U_SQUARE, U_EXP, U_RSQRT, U_TANH, U_GELU, U_GELU_GRAD };
+enum UnaryOp : int32_t { U_COPY = 0, U_SCALE, U_ADD_SCALAR, U_SQUARE, U_EXP, U_RSQRT, U_TANH, U_GELU, U_GELU_GRAD, U_LOG, U_SIGMOID, U_RELU, U_ABS, U_SQRT };
 struct UnaryP {
   int32_t op, in_dt, out_dt, vec;   // vec: elements per lane per step (8, 4 or 1)
   uint32_t n;
@@ -184,6 +184,7 @@ struct PackTable {
 enum ProgOp : uint8_t {
   PO_ADD = 0, PO_SUB, PO_RSUB, PO_MUL, PO_DIV, PO_RDIV, PO_MAX,   // acc (op) b;  RSUB = b - acc, RDIV = b / acc
   PO_SQUARE, PO_EXP, PO_RSQRT, PO_TANH, PO_GELU, PO_GELU_GRAD,    // (op) acc
+  PO_LOG, PO_SIGMOID, PO_RELU, PO_ABS, PO_SQRT,
   PO_CVT,                                                 // acc rounded through storage dtype `aux`
   PO_LOAD,                                                // acc <- b
   PO_RSUM, PO_RMAX, PO_RSUMSQ,                            // row reduction of acc (RSUMSQ: of acc squared) -> sacc

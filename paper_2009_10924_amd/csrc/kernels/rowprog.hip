@@ -56,6 +56,11 @@ __device__ __forceinline__ float apply_op(int op, float a, float b, int aux) {
     case PO_TANH: return fast_tanh(a);
     case PO_GELU: return gelu_fwd(a);
     case PO_GELU_GRAD: return gelu_grad(a);
+    case PO_LOG: return full_log(a);
+    case PO_SIGMOID: return fast_sigmoid(a);
+    case PO_RELU: return fmaxf(a, 0.0f);
+    case PO_ABS: return __builtin_fabsf(a);
+    case PO_SQRT: return full_sqrt(a);
     case PO_CVT: return round_through(a, aux);
     default: return b;   // PO_LOAD
   }
@@ -347,6 +352,7 @@ __global__ void __launch_bounds__(256) k_row_program(const ProgArgs args_in_kern
         FS_BINARY(PO_MAX) FS_BINARY(PO_LOAD)
         FS_B_SCALAR(PO_SQUARE) FS_B_SCALAR(PO_EXP) FS_B_SCALAR(PO_RSQRT) FS_B_SCALAR(PO_TANH) FS_B_SCALAR(PO_GELU)
         FS_B_SCALAR(PO_GELU_GRAD) FS_B_SCALAR(PO_CVT)
+        FS_B_SCALAR(PO_LOG) FS_B_SCALAR(PO_SIGMOID) FS_B_SCALAR(PO_RELU) FS_B_SCALAR(PO_ABS) FS_B_SCALAR(PO_SQRT)
 #undef FS_BINARY
 #undef FS_B_ACC
 #undef FS_B_COL

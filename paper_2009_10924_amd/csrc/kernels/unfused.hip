@@ -80,6 +80,11 @@ __device__ __forceinline__ float unary_apply(int op, float x, float value) {
     case U_TANH: return tanhf(x);
     case U_GELU: return gelu_fwd(x);
     case U_GELU_GRAD: return gelu_grad(x);
+    case U_LOG: return full_log(x);
+    case U_SIGMOID: return fast_sigmoid(x);
+    case U_RELU: return fmaxf(x, 0.0f);
+    case U_ABS: return __builtin_fabsf(x);
+    case U_SQRT: return full_sqrt(x);
     default: return x;
   }
 }

@@ -52,6 +52,20 @@ def test_normalize_from_saved_statistics_and_broadcast_outputs(rows, cols, dtype
     note(f"normalise from statistics {rows}x{cols} {dtype}: {worst}")
 
 
+@pytest.mark.parametrize("rows,cols,dtype", [(50, 128, "f32"), (7, 1000, "bf16"), (19, 264, "f16"), (4, 4096, "f32"), (33, 127, "f32"),
+                                             (3, 50257, "f32"), (2, 128256, "bf16")])
+def test_log_sigmoid_relu_abs_sqrt_patterns(rows, cols, dtype):
+    """Log-softmax, a sigmoid gate with a rectified branch, rows scaled by their L2 norm with their L1 norms stored:
+    every launch shape of the generated kernel and of the interpreted program, and the per-op plan."""
+    from workloads import l1_l2_scale_graph, log_softmax_graph, sigmoid_gate_graph
+    if not B.codegen_available() and (cols > 8192 or cols % 4):
+        pytest.skip("rows of this length exist as generated kernels only")
+    for make in (log_softmax_graph, sigmoid_gate_graph, l1_l2_scale_graph):
+        spec = make(rows, cols, dtype)
+        worst, info = _run(spec)
+        note(f"{spec.name}: {info['kernel']}, {info['n_candidates']} shapes, worst {worst}")
+
+
 @pytest.mark.parametrize("rows,cols", [(7, 64), (300, 1024), (2, 4096)])
 def test_outer_product_without_full_input(rows, cols):
     worst, _ = _run(outer_scale_graph(rows, cols))

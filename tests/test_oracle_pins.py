@@ -410,6 +410,42 @@ def test_elementwise_ops_against_python_scalars():
     np.testing.assert_array_equal(O.op_broadcast(b.reshape(1, 3), (2, 3)), [b, b])
 
 
+def test_log_sigmoid_relu_abs_sqrt_closed_forms():
+    x = np.linspace(-6.0, 6.0, 49)
+    pos = np.array([1e-6, 0.25, 1.0, 2.0, 9.0, 1e6])
+    # python scalars, one by one
+    for v in pos:
+        assert O.op_log(np.array([v]))[0] == pytest.approx(math.log(v), rel=1e-15, abs=1e-300)
+        assert O.op_sqrt(np.array([v]))[0] == pytest.approx(math.sqrt(v), rel=1e-15)
+    np.testing.assert_array_equal(O.op_sqrt(np.array([0.0, 4.0, 6.25])), [0.0, 2.0, 2.5])
+    np.testing.assert_array_equal(O.op_log(np.array([1.0])), [0.0])
+    # identities that a wrong sign, a missing term or a swapped definition breaks
+    np.testing.assert_allclose(O.op_log(O.op_exp(x)), x, rtol=0, atol=1e-14)
+    np.testing.assert_allclose(O.op_sigmoid(x) + O.op_sigmoid(-x), 1.0, rtol=0, atol=1e-15)
+    np.testing.assert_allclose(O.op_sigmoid(x), 0.5 * (1.0 + np.tanh(0.5 * x)), rtol=1e-14)
+    assert O.op_sigmoid(np.array([0.0]))[0] == 0.5 and O.op_sigmoid(np.array([math.log(3.0)]))[0] == pytest.approx(0.75, rel=1e-15)
+    np.testing.assert_array_equal(O.op_relu(x) - O.op_relu(-x), x)
+    np.testing.assert_array_equal(O.op_relu(x) + O.op_relu(-x), O.op_abs(x))
+    np.testing.assert_array_equal(O.op_abs(np.array([-1.5, 0.0, 2.0])), [1.5, 0.0, 2.0])
+    np.testing.assert_allclose(O.op_sqrt(pos) ** 2, pos, rtol=1e-15)
+
+
+def test_log_softmax_is_the_logarithm_of_softmax():
+    from workloads import log_softmax_graph, softmax_graph
+    rng = np.random.default_rng(5)
+    x = rng.normal(0.0, 3.0, (7, 33))
+    ls = O.evaluate(log_softmax_graph(7, 33, "f32"), {"x": x.astype(np.float32)})["y"]
+    sm = O.evaluate(softmax_graph(7, 33, "f32"), {"x": x.astype(np.float32)})["y"]
+    np.testing.assert_allclose(np.exp(ls), sm, rtol=1e-13)
+    np.testing.assert_allclose(np.exp(ls).sum(axis=-1), 1.0, rtol=1e-13)
+    # brute force, python loops
+    xr = x.astype(np.float32).astype(np.float64)
+    for r in range(2):
+        m = max(xr[r])
+        want = [v - m - math.log(sum(math.exp(u - m) for u in xr[r])) for v in xr[r]]
+        np.testing.assert_allclose(ls[r], want, rtol=1e-13, atol=1e-13)
+
+
 def test_max_rel_err_metric():
     ref = np.array([1.0, 0.0, -2.0, 1e-9])
     got = np.array([1.001, 0.0, -2.0, 2e-9])

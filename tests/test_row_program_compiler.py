@@ -7,7 +7,7 @@ import pytest
 
 from oracle import oracle as O
 from paper_2009_10924_amd import binding as B
-from workloads import (layernorm_stats_graph, make_inputs, normalize_from_stats_graph, outer_scale_graph,
+from workloads import (l1_l2_scale_graph, log_softmax_graph, sigmoid_gate_graph, layernorm_stats_graph, make_inputs, normalize_from_stats_graph, outer_scale_graph,
                        random_row_pattern, scaled_softmax_colbias_graph, silu_gate_graph)
 
 NP_DT = {0: "f32", 1: "f16", 2: "bf16"}
@@ -132,7 +132,8 @@ def emulate(listing, spec, inputs, anchor_dims):
             r = {"add": lambda: a + b, "sub": lambda: a - b, "rsub": lambda: b - a, "mul": lambda: a * b, "div": lambda: a / b,
                  "rdiv": lambda: b / a, "max": lambda: np.maximum(a, b), "square": lambda: a * a, "exp": lambda: np.exp(a),
                  "rsqrt": lambda: 1.0 / np.sqrt(a), "tanh": lambda: np.tanh(a), "gelu": lambda: _gelu(a),
-                 "gelu_grad": lambda: _gelu_grad(a), "load": lambda: b, "cvt": lambda: _round_through(a, aux)}[op]()
+                 "gelu_grad": lambda: _gelu_grad(a), "log": lambda: np.log(a), "sigmoid": lambda: 1.0 / (1.0 + np.exp(-a)),
+                 "relu": lambda: np.maximum(a, 0.0), "abs": lambda: np.abs(a), "sqrt": lambda: np.sqrt(a), "load": lambda: b, "cvt": lambda: _round_through(a, aux)}[op]()
         r = np.asarray(r, dtype=np.float32)
         if scalar:
             sacc = np.broadcast_to(r, (rows, 1)).copy()
@@ -173,6 +174,9 @@ def _compare(spec, seed=1):
     lambda: scaled_softmax_colbias_graph(13, 40, "f32"),
     lambda: normalize_from_stats_graph(11, 48, "f32"),
     lambda: outer_scale_graph(7, 16),
+    lambda: log_softmax_graph(11, 72, "f32"),
+    lambda: sigmoid_gate_graph(9, 64, "f32"),
+    lambda: l1_l2_scale_graph(13, 40, "f32"),
 ])
 def test_named_patterns_compile_to_correct_programs(make):
     _compare(make())

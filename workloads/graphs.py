@@ -28,7 +28,7 @@ OPCODES = {
     "add": 2, "sub": 2, "mul": 2, "div": 2, "max": 2,
     "scale": 1, "add_scalar": 1,
     "square": 1, "exp": 1, "rsqrt": 1, "tanh": 1,
-    "gelu_tanh": 1, "gelu_tanh_grad": 1,
+    "gelu_tanh": 1, "gelu_tanh_grad": 1, "log": 1, "sigmoid": 1, "relu": 1, "abs": 1, "sqrt": 1,
     "broadcast": 1,
     "reduce_sum": 1, "reduce_max": 1, "reduce_mean": 1,
     "transpose": 1, "convert": 1,
@@ -303,6 +303,31 @@ def silu_gate_graph(rows: int, cols: int, dtype: str = "bf16") -> GraphSpec:
     return GraphSpec(name=f"pattern_silu_gate_{dtype}_{rows}x{cols}",
                      inputs=[TensorSpec("a", dtype, (rows, cols)), TensorSpec("b", dtype, (rows, cols))],
                      ops=ops, outputs=[("out", dtype)])
+
+
+def log_softmax_graph(rows: int, cols: int, dtype: str = "f32") -> GraphSpec:
+    """Row log-softmax: y = (x - max) - log(sum exp(x - max))  (6 ops, two row reductions)."""
+    ops = [_op("m", "reduce_max", "x", axis=1), _op("c", "sub", "x", "m"), _op("e", "exp", "c"),
+           _op("s", "reduce_sum", "e", axis=1), _op("l", "log", "s"), _op("y", "sub", "c", "l")]
+    return GraphSpec(name=f"pattern_log_softmax_{dtype}_{rows}x{cols}", inputs=[TensorSpec("x", dtype, (rows, cols))],
+                     ops=ops, outputs=[("y", dtype)])
+
+
+def sigmoid_gate_graph(rows: int, cols: int, dtype: str = "bf16") -> GraphSpec:
+    """Gated linear unit with a rectified side branch: out = a * sigmoid(b + bias) + relu(a)  (5 ops)."""
+    ops = [_op("z", "add", "b", "bias"), _op("g", "sigmoid", "z"), _op("p", "mul", "a", "g"), _op("r", "relu", "a"),
+           _op("out", "add", "p", "r")]
+    return GraphSpec(name=f"pattern_sigmoid_gate_{dtype}_{rows}x{cols}",
+                     inputs=[TensorSpec("a", dtype, (rows, cols)), TensorSpec("b", dtype, (rows, cols)), TensorSpec("bias", dtype, (cols,))],
+                     ops=ops, outputs=[("out", dtype)])
+
+
+def l1_l2_scale_graph(rows: int, cols: int, dtype: str = "f32", eps: float = 1e-6) -> GraphSpec:
+    """Rows scaled by their L2 norm, and their L1 norms: out = x / sqrt(sum x^2 + eps), l1 = sum |x|  (7 ops)."""
+    ops = [_op("q", "square", "x"), _op("ss", "reduce_sum", "q", axis=1), _op("e", "add_scalar", "ss", value=float(eps)),
+           _op("n", "sqrt", "e"), _op("out", "div", "x", "n"), _op("a", "abs", "x"), _op("l1", "reduce_sum", "a", axis=1)]
+    return GraphSpec(name=f"pattern_l1_l2_scale_{dtype}_{rows}x{cols}", inputs=[TensorSpec("x", dtype, (rows, cols))],
+                     ops=ops, outputs=[("out", dtype), ("l1", "f32")])
 
 
 def scaled_softmax_colbias_graph(rows: int, cols: int, dtype: str = "f32") -> GraphSpec:
