@@ -401,7 +401,7 @@ def main():
         torch.cuda.empty_cache()
         from paper_2009_10924_amd import binding as B
         generic = {}
-        for name in ("G1", "G2", "G3", "G4", "G5", "G6", "G7", "G8", "G9", "G10", "G11"):
+        for name in ("G1", "G2", "G3", "G4", "G5", "G6", "G7", "G8", "G9", "G10", "G11", "G12"):
             spec = GENERIC_CONFIGS[name]()
             generic[name] = measure_config(name, spec, max(50, args.steps // 8), 10)   # AUTO: the kernel generated for the pattern
             with B.codegen(False):                                                      # the interpreted row program beside it

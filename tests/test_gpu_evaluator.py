@@ -48,7 +48,7 @@ def test_auto_pick_is_near_the_measured_best(cfg, steps):
     assert worst[1] > min(r[1] for r in rows)
 
 
-@pytest.mark.parametrize("cfg,steps", [("G1", 300), ("G4", 300), ("G6", 150), ("G9", 100), ("G10", 100), ("G11", 20)])
+@pytest.mark.parametrize("cfg,steps", [("G1", 300), ("G4", 300), ("G6", 150), ("G9", 100), ("G10", 100), ("G11", 20), ("G12", 20)])
 def test_auto_pick_among_generated_shapes_is_near_the_measured_best(cfg, steps):
     """The same judgement for the shapes of a generated kernel (lanes per row, steps per lane, step width, rows per
     lane group, column tiles): what AUTO compiles and runs is within 10 % of the fastest shape."""

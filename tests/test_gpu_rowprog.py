@@ -248,6 +248,17 @@ def test_column_sums_handed_out_in_16_bits(rows, cols, dtype, sum_dtype):
 
 
 @pytest.mark.parametrize("seed", range(24))
+def test_random_row_patterns_with_the_wider_vocabulary(seed):
+    dtype = ("f32", "f16", "bf16")[seed % 3]
+    rows, cols = [(37, 96), (130, 64), (64, 520), (9, 1001), (5, 20000), (300, 256)][seed % 6]
+    spec = random_row_pattern(1500 + seed, rows, cols, dtype, n_ops=6 + seed % 10, more_ops=True, column_sums=(seed % 2) if cols % 4 == 0 and cols < 8192 else 0)
+    if not B.codegen_available() and B.Plan(B.Graph.from_spec(spec), "auto").info["scheme"] == "unfused":
+        pytest.skip("this shape exists as a generated kernel only")
+    worst, info = _run(spec, seed=seed)
+    note(f"random pattern {seed} (wider vocabulary) {rows}x{cols} {dtype}: {info['kernel']}, {info['n_candidates']} shapes, worst {worst}")
+
+
+@pytest.mark.parametrize("seed", range(24))
 def test_random_row_patterns_with_column_sums(seed):
     """Seeded random patterns of which one to three full-shaped values are also summed over all rows: every launch
     shape (rows per lane group, column tiles where no row reduction ties the columns together) and the per-op plan."""

@@ -476,10 +476,12 @@ def rmsnorm_backward_graph(rows: int, cols: int, dtype: str = "bf16") -> GraphSp
                      ops=ops, outputs=[("dx", dtype), ("dgamma", "f32")])
 
 
-def random_row_pattern(seed: int, rows: int, cols: int, dtype: str = "f32", n_ops: int = 12, column_sums: int = 0) -> GraphSpec:
+def random_row_pattern(seed: int, rows: int, cols: int, dtype: str = "f32", n_ops: int = 12, column_sums: int = 0,
+                       more_ops: bool = False) -> GraphSpec:
     """A random connected pattern of element-wise ops and row reductions over [rows, cols] (descriptor only).
     Domains are kept safe by construction: exp only of tanh, division and rsqrt only of 1 + square.
-    column_sums: up to that many full-shaped values of the pattern are also summed over all rows (float32 outputs)."""
+    column_sums: up to that many full-shaped values of the pattern are also summed over all rows (float32 outputs).
+    more_ops: sigmoid, relu, abs, and log / sqrt of 1 + square join the vocabulary."""
     import random
     rnd = random.Random(seed)
     inputs = [TensorSpec("x0", dtype, (rows, cols))]
@@ -515,6 +517,14 @@ def random_row_pattern(seed: int, rows: int, cols: int, dtype: str = "f32", n_op
 
     while len(ops) < n_ops:
         r = rnd.random()
+        if more_ops and rnd.random() < 0.3:
+            a = pick(("full", "rscal"))
+            kind = rnd.choice(["sigmoid", "relu", "abs", "log", "sqrt"])
+            if kind in ("log", "sqrt"):
+                q = add("square", a, kind=kinds[a])
+                a = add("add_scalar", q, kind=kinds[a], value=1.0)
+            add(kind, a, kind=kinds[a])
+            continue
         if r < 0.40:
             a, b = pick(), pick()
             if kinds[a] == "col" and kinds[b] == "col":
@@ -563,7 +573,7 @@ def random_row_pattern(seed: int, rows: int, cols: int, dtype: str = "f32", n_op
         for i, n in enumerate(sorted(summed[:column_sums], key=lambda n: int(n[1:]))):
             ops.append(_op(f"cs{i}", "reduce_sum", n, axis=0))
             outputs.append((f"cs{i}", "f32"))
-    return GraphSpec(name=f"pattern_random{seed}_{dtype}_{rows}x{cols}" + (f"_cs{column_sums}" if column_sums else ""),
+    return GraphSpec(name=f"pattern_random{seed}_{dtype}_{rows}x{cols}" + (f"_cs{column_sums}" if column_sums else "") + ("_more" if more_ops else ""),
                      inputs=inputs, ops=ops, outputs=outputs)
 
 
@@ -768,6 +778,7 @@ GENERIC_CONFIGS = {
     "G10": lambda: rmsnorm_backward_graph(8192, 4096, "bf16"),               # N5's shape
     # a row far beyond one workgroup's registers (probabilities over a vocabulary): chunks, a pass per row reduction
     "G11": lambda: softmax_graph(4096, 128256, "bf16"),
+    "G12": lambda: log_softmax_graph(4096, 128256, "bf16"),                  # the same with a logarithm: what a cross-entropy reads
 }
 
 FULL_CONFIGS = {
