@@ -187,10 +187,15 @@ __device__ __forceinline__ void fold_tile(const float* __restrict__ partials, fl
   }
   sm[g * Q + q] = s;
   __syncthreads();
-  if (g == 0 && col < width) {
-    f32x4 v = sm[q];
+  // the G row groups fold pairwise through LDS (log2 G steps, the same order every run) rather than one thread
+  // walking all G slots: with 64 groups the serial walk took longer than the loads
 #pragma unroll
-    for (int k = 1; k < G; ++k) v += sm[k * Q + q];
+  for (int half = G / 2; half >= 1; half /= 2) {
+    if ((int)g < half) sm[g * Q + q] += sm[(g + half) * Q + q];
+    __syncthreads();
+  }
+  if (g == 0 && col < width) {
+    const f32x4 v = sm[q];
     // the split is a multiple of 4, so a quad never straddles the two outputs; sums handed out in 16 bits are
     // rounded here, once
     float* const base = col < split ? out0 : out1;
