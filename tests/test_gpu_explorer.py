@@ -155,6 +155,36 @@ def test_random_multi_pattern_programs(seed):
          f"({info['n_patterns']} patterns, {info['n_packs']} packs), workspace {info['workspace_bytes']} B, worst {worst:.3f} of the bar")
 
 
+def _side_by_side(name, members):
+    from workloads.graphs import GraphSpec, OpSpec, TensorSpec
+    inputs, ops, outputs = [], [], []
+    for k, m in enumerate(members):
+        ren = lambda n, k=k: f"s{k}_{n}"
+        inputs += [TensorSpec(ren(t.name), t.dtype, t.dims) for t in m.inputs]
+        ops += [OpSpec(ren(o.out), o.opcode, tuple(ren(i) for i in o.inputs), dict(o.attr)) for o in m.ops]
+        outputs += [(ren(n), d) for n, d in m.outputs]
+    return GraphSpec(name, inputs, ops, outputs)
+
+
+def test_folds_of_hand_written_families_join_as_well():
+    """Bias + GELU with its bias gradient (twice) and LayerNorm backward, side by side: three hand-written kernels
+    with a fold launch each; the program issues the three folds as one launch."""
+    from workloads import bias_gelu_dbias_graph, layernorm_backward_graph
+    spec = _side_by_side("pattern_three_family_folds", [bias_gelu_dbias_graph(1000, 512), layernorm_backward_graph(600, 256, "f32"),
+                                                         bias_gelu_dbias_graph(300, 1024)])
+    inp = make_inputs(spec, seed=0)
+    ref = O.evaluate(spec, inp)
+    got, prog = run_program(spec, inp)
+    assert prog.info["n_joint_folds"] == 3 and prog.info["n_kernels"] == 4
+    assert sorted(s["info"]["pattern"] for s in prog.patterns()) == ["bias_gelu_dbias", "bias_gelu_dbias", "layernorm_backward"]
+    apart, p2 = run_program(spec, inp, no_joint_folds=True)
+    assert p2.info["n_kernels"] == 6
+    for name, dt in spec.outputs:
+        assert np.array_equal(got[name], apart[name]), name
+        err = O.max_rel_err(got[name], ref[name].reshape(got[name].shape), O.rms(ref[name]))
+        assert err <= TOL[dt], (name, err)
+
+
 @pytest.mark.parametrize("seed", range(12))
 def test_random_multi_pattern_programs_with_column_sums(seed):
     """Random segments that also sum one or two of their values over all rows: the folds of all segments run as one
