@@ -55,6 +55,7 @@ struct Compiler {
   int32_t colsum_slot[kProgMaxColSums];   // their fs_execute output slots
   int32_t colsum_dt = -1;                 // the dtype they are handed out in (one for all of a pattern's sums)
   std::vector<char> is_colsum;            // per op
+  std::vector<char> sum_chain;            // per op: a sum along one leading axis on the way to a column sum (emits nothing)
   int vec_instr = 0, scal_instr = 0, reg_reads = 0, reg_writes = 0, trans = 0;
   std::vector<int> free_regs, free_sregs;
   int acc_holds = -1, sacc_holds = -1;   // roots
@@ -462,9 +463,25 @@ struct Compiler {
     return true;
   }
 
+  // A sum over all rows of a pattern with several leading axes is written as a chain: reduce_sum along axis 0, then
+  // along axis 1, ... up to the last leading axis, each the only reader of the one before.  Returns the op that ends
+  // the chain which op `i` (a reduce_sum along axis 0) starts, or -1.
+  int column_sum_chain_end(size_t i) const {
+    size_t cur = i;
+    for (int ax = 1; ax <= rank - 2; ++ax) {
+      const Tensor& t = g.tensors[g.ops[cur].out];
+      if (t.output_slot >= 0 || t.consumers.size() != 1) return -1;
+      const Op& next = g.ops[t.consumers[0]];
+      if (next.opcode != FS_REDUCE_SUM || next.axis != ax) return -1;
+      cur = (size_t)t.consumers[0];
+    }
+    return (int)cur;
+  }
+
   bool classify_ops() {
     // aliases and result classes; which ops read which roots
     const size_t n_ops = g.ops.size();
+    sum_chain.assign(n_ops, 0);
     reads.assign(n_ops, {});
     is_alias.assign(n_ops, 0);
     view_fold.assign(n_ops, 0);
@@ -489,13 +506,31 @@ struct Compiler {
           break;
         case FS_REDUCE_SUM: case FS_REDUCE_MAX: case FS_REDUCE_MEAN: {
           const Tensor& src = g.tensors[op.in[0]];
-          if (op.opcode == FS_REDUCE_SUM && op.axis == 0 && src.rank == 2 && rank == 2 && ka == V_FULL && !stretched_rows(src) &&
-              out.output_slot >= 0 && out.consumers.empty() && out.store_as != FS_I32 && cols % 4 == 0 &&
-              (colsum_dt < 0 || colsum_dt == (int32_t)out.store_as)) {
-            // the sum over all rows: every workgroup leaves partial sums, a second launch folds them.  Nothing in the
-            // pattern can read it (that would take a grid-wide wait), so it has to be a graph output.
+          if (sum_chain[i] == 1) {   // inside a chain: stands for the value the chain sums
+            is_alias[i] = 1;
+            val[op.out].kind = V_FULL;
+            break;
+          }
+          if (op.opcode == FS_REDUCE_SUM && op.axis == 0 && src.rank == rank && ka == V_FULL && !stretched_rows(src) && cols % 4 == 0 &&
+              sum_chain[i] == 0) {
+            const int end = column_sum_chain_end(i);
+            const Tensor* last = end >= 0 ? &g.tensors[g.ops[end].out] : nullptr;
+            if (last && last->output_slot >= 0 && last->consumers.empty() && last->store_as != FS_I32 &&
+                (colsum_dt < 0 || colsum_dt == (int32_t)last->store_as)) {
+              // the sum over all rows: every workgroup leaves partial sums, a second launch folds them.  Nothing in the
+              // pattern can read it (that would take a grid-wide wait), so it has to be a graph output.
+              colsum_dt = (int32_t)last->store_as;
+              for (size_t k = i; (int)k != end; k = (size_t)g.tensors[g.ops[k].out].consumers[0]) sum_chain[k] = 1;
+              sum_chain[end] = 2;
+              if ((int)i != end) {
+                is_alias[i] = 1;
+                val[op.out].kind = V_FULL;
+                break;
+              }
+            }
+          }
+          if (sum_chain[i] == 2) {   // the op that completes the sum over all rows
             is_colsum[i] = 1;
-            colsum_dt = (int32_t)out.store_as;
             want = V_COL;
             break;
           }

@@ -235,6 +235,18 @@ def test_rows_in_chunks_with_folded_transposes(dims, dtype):
         note(f"{make.__name__} {dims} {dtype}: {info['kernel']}, {info['n_candidates']} shapes, worst {worst}")
 
 
+@pytest.mark.parametrize("dims,dtype", [((4, 50, 128), "bf16"), ((3, 7, 5, 64), "f32"), ((32, 128, 768), "bf16"), ((2, 2, 300, 256), "f16")])
+def test_bias_gradient_as_a_chain_of_sums_over_the_leading_axes(dims, dtype):
+    """[B,S,H] or [B,S,N,H] activations: the sums along axis 0, 1, ... are one column sum of the pattern's row space."""
+    if not B.codegen_available():
+        pytest.skip("column sums inside a row pattern exist as generated kernels only")
+    from workloads import bias_gradient_chain_graph
+    spec = bias_gradient_chain_graph(dims, dtype)
+    worst, info = _run(spec, repeat=2)
+    assert info["pattern"] == "row_generated" and info["n_kernels"] == 2 and info["scheme"] == "global"
+    note(f"{spec.name}: {info['kernel']}, {info['n_candidates']} shapes, worst {worst}")
+
+
 @pytest.mark.parametrize("rows,cols,dtype,sum_dtype", [(1000, 128, "bf16", "bf16"), (300, 768, "f16", "f16"), (2500, 1024, "f32", "bf16"), (37, 96, "bf16", "f16")])
 def test_column_sums_handed_out_in_16_bits(rows, cols, dtype, sum_dtype):
     """The fold launch rounds the float32 sum once, to the dtype the gradient is wanted in."""

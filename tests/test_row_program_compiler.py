@@ -246,6 +246,25 @@ def test_transposed_views_that_are_outputs_compile_to_load_and_store():
     assert listing.count("rowstrides=15,1,3") == 3 and listing.count(" store ") == 4
 
 
+@pytest.mark.parametrize("dims", [(4, 9, 64), (2, 3, 5, 32), (37, 96)])
+def test_sums_over_several_leading_axes_in_a_chain_are_one_column_sum(dims):
+    from workloads import bias_gradient_chain_graph
+    from workloads.graphs import GraphSpec
+    if not B.codegen_available():
+        pytest.skip("needs the run-time compiler")
+    spec = bias_gradient_chain_graph(dims, "f32")
+    n_instr, info = _compare(spec)
+    assert info["n_kernels"] == 2 and n_instr == 5          # add, gelu', mul, store, colsum: the chain's links emit nothing
+    if len(dims) > 2:
+        # a chain that stops before the last leading axis leaves values that several rows share: no row program
+        short = GraphSpec("pattern_short_chain", spec.inputs, spec.ops[:-1], [("dx", "f32"), (spec.ops[-2].out, "f32")])
+        assert B.Plan(B.Graph.from_spec(short), "auto").info["scheme"] == "unfused"
+        # and one whose link is read elsewhere as well
+        extra = GraphSpec("pattern_read_link", spec.inputs, list(spec.ops) + [type(spec.ops[0])("h", "scale", ("s0",), {"value": 0.5})],
+                          list(spec.outputs) + [("h", "f32")])
+        assert B.Plan(B.Graph.from_spec(extra), "auto").info["scheme"] == "unfused"
+
+
 def test_column_sums_of_one_pattern_share_the_dtype_they_are_handed_out_in():
     from workloads import gelu_backward_graph, layernorm_backward_bias_graph
     from workloads.graphs import GraphSpec

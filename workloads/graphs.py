@@ -438,6 +438,22 @@ def gelu_backward_graph(rows: int, cols: int, dtype: str = "bf16", sum_dtype: st
                      ops=ops, outputs=[("dx", dtype), ("dbias", sum_dtype)])
 
 
+def bias_gradient_chain_graph(dims: Sequence[int], dtype: str = "bf16") -> GraphSpec:
+    """Backward of bias + tanh-GELU over activations with several leading axes ([B,S,H] or [B,S,N,H]): dx, and the bias
+    gradient as a chain of sums, one leading axis after the other, down to one value per column."""
+    dims = tuple(int(d) for d in dims)
+    rank = len(dims)
+    ops = [_op("z", "add", "x", "bias"), _op("d", "gelu_tanh_grad", "z"), _op("dx", "mul", "g", "d")]
+    prev = "dx"
+    for ax in range(rank - 1):
+        name = "dbias" if ax == rank - 2 else f"s{ax}"
+        ops.append(_op(name, "reduce_sum", prev, axis=ax))
+        prev = name
+    return GraphSpec(name=f"pattern_bias_gradient_chain_{dtype}_{'x'.join(map(str, dims))}",
+                     inputs=[TensorSpec("x", dtype, dims), TensorSpec("bias", dtype, dims[-1:]), TensorSpec("g", dtype, dims)],
+                     ops=ops, outputs=[("dx", dtype), ("dbias", "f32")])
+
+
 def layernorm_backward_bias_graph(rows: int, cols: int, dtype: str = "bf16", sum_dtype: str = "f32") -> GraphSpec:
     """LayerNorm backward from saved statistics together with the gradient of the bias that was added in front of the
     LayerNorm: dx (rounded to the storage dtype), dgamma, dbeta and dbias = column sum of the rounded dx.  Two row
