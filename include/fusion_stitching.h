@@ -204,9 +204,10 @@ int64_t fs_plan_describe(const fs_plan *p, char *text, size_t capacity);
  * Generated kernels only: row lengths that are no multiple of 4 elements; rows of more than
  * 2048 128-bit vectors (workgroups of 512 / 1024 threads; beyond 8192 vectors the row is
  * worked through in chunks, one pass per row reduction, the chunks kept in registers where
- * they fit); sums over all rows of a rank-2 pattern (reduce_sum along axis 0, a graph
- * output nothing else reads, float32 or rounded once to a 16-bit dtype; the plan then has
- * fold launches and a workspace); more than 4 full-shaped inputs.
+ * they fit); sums over all rows of a pattern (reduce_sum along axis 0 of a rank-2 value, or
+ * a chain of reduce_sums along each leading axis in turn; a graph output nothing else
+ * reads, float32 or rounded once to a 16-bit dtype; the plan then has fold launches and a
+ * workspace); more than 4 full-shaped inputs.
  * Compilation needs no GPU; the module is loaded on the device that is current at plan
  * creation (or, without one, by the first fs_execute: do that one outside stream capture).
  * If the compiler is not available, compilation fails or the kernel would spill registers,
