@@ -62,13 +62,15 @@ CostResult evaluate(const KernelCost& k, int32_t vgprs_compiled) {
                        (d.n_cu * d.simd_per_cu) / d.clock_hz;
   // every extra round of a kernel that runs in few rounds pays a ramp of its own;
   // so does a wave that has to wait for its index arithmetic before its first load
-  const double t_ramp = std::min(rounds - 1.0, 2.0) * 0.5 * d.mem_latency_s +
+  const double t_ramp = std::min(rounds - 1.0, 2.0) * 0.25 * d.mem_latency_s +
                         k.preamble_instr * d.cycles_valu * simd_share / d.clock_hz;
 
   // The wave-rounds term and the streaming floor overlap only partly: a wave that is
   // computing is not loading, and only the other waves of its SIMD can fill the gap.
-  const double t_stream = std::max(t_hbm + t_cache + t_lds, t_alu);
-  const double t_body = std::max(t_latency, t_stream) + 0.25 * std::min(t_latency, t_stream);
+  // (re-reads that the caches serve share the memory pipeline with the stream but mostly fill its gaps: a quarter
+  // of their own time shows, measured on the patterns with per-column operands)
+  const double t_stream = std::max(t_hbm + 0.25 * t_cache + t_lds, t_alu);
+  const double t_body = std::max(t_latency, t_stream) + 0.10 * std::min(t_latency, t_stream);
   r.seconds = d.launch_s + t_body + t_ramp + k.serial_tail_s;
   return r;
 }

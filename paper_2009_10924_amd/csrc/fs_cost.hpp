@@ -19,7 +19,8 @@ struct DeviceModel {
   double clock_hz = 2.4e9;
   double hbm_peak_Bps = 8.0e12;
   // measured / calibrated on one MI355X
-  double stream_fraction = 0.78;     // plain copy kernel, fraction of hbm_peak
+  double stream_fraction = 0.84;     // one-shot kernels with three or more independent streams, fraction of hbm_peak
+                                     // (the grid-stride copy kernel reaches 0.78)
   double mem_latency_s = 1.2e-6;     // loaded HBM round trip seen by a wave
   double launch_s = 2.2e-6;          // fixed cost of one kernel: dispatch, first load round trip, drain
   double l2_Bps = 20.0e12;           // aggregate cache bandwidth for re-read operands
