@@ -349,6 +349,17 @@ fs_status fs_program_query(const fs_program *p, fs_program_info *out);
  * figures of its plan.  Every out pointer may be null.  Errors: FS_ERR_INVALID_ARG.      */
 fs_status fs_program_pattern(const fs_program *p, int32_t index, int32_t *ops, int32_t capacity, int32_t *n_ops,
                              double *f_us, int32_t *pack, fs_plan_info *info);
+/* Writes a text listing of what fs_program_execute will issue into `text` (HOST buffer of
+ * `capacity` bytes, NUL-terminated, truncated if too small) and returns the size needed
+ * including the NUL, or a negative error.  One line per step in execution order (`step <i>
+ * ops=<graph op indices> pattern=<name> kernel=<name> launches=<issued at the step> f_us=<score>`,
+ * with `pack=<j>` for members of a packed launch, which is issued where its first member
+ * stands), indented under it where each of the plan's inputs and outputs lives (`in<k>` /
+ * `out<k>` of the graph, or `ws+<offset>` in the program's workspace) and the plan's own
+ * scratch (`scratch ws+<offset> <bytes>`); then one line per packed launch (`pack <j>
+ * launches=<n> members=<steps>`) and per joint fold launch (`joint_fold <j> folds=<n>
+ * of_steps=<steps whose column sums it finishes>`).  Errors: FS_ERR_INVALID_ARG.         */
+int64_t fs_program_describe(const fs_program *p, char *text, size_t capacity);
 /* Enqueues the whole program on `hip_stream` and returns without waiting.  inputs /
  * outputs: DEVICE pointers in the graph's declaration order, 16-byte aligned.  `workspace`:
  * DEVICE scratch of at least fs_program_info.workspace_bytes, 256-byte aligned, zero-filled

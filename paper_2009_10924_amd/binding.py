@@ -32,6 +32,7 @@ EXPORTS = [
     "fs_plan_source", "fs_codegen_enable", "fs_codegen_available", "fs_execute", "fs_stream_copy", "fs_last_error", "fs_version",
     "fs_pack_create", "fs_pack_destroy", "fs_pack_query", "fs_pack_execute",
     "fs_explore", "fs_explore_score", "fs_program_destroy", "fs_program_query", "fs_program_pattern", "fs_program_execute",
+    "fs_program_describe",
 ]
 FS_PACK_MAX_MEMBERS = 256
 
@@ -165,6 +166,8 @@ def load() -> C.CDLL:
     lib.fs_plan_candidate.restype = i32
     lib.fs_plan_describe.argtypes = [vp, C.c_char_p, C.c_size_t]
     lib.fs_plan_describe.restype = C.c_int64
+    lib.fs_program_describe.argtypes = [vp, C.c_char_p, C.c_size_t]
+    lib.fs_program_describe.restype = C.c_int64
     lib.fs_plan_source.argtypes = [vp, C.c_char_p, C.c_size_t]
     lib.fs_plan_source.restype = C.c_int64
     lib.fs_codegen_enable.argtypes = [C.c_int32]
@@ -453,6 +456,14 @@ class Program:
             _check(self._lib.fs_program_pattern(self.handle, i, ops, n.value, None, None, None, None))
             out.append({"ops": list(ops)[:n.value], "f_us": f.value, "pack": pack.value, "info": info.as_dict()})
         return out
+
+    def describe(self) -> str:
+        need = self._lib.fs_program_describe(self.handle, None, 0)
+        if need < 0:
+            _check(int(need))
+        buf = C.create_string_buffer(int(need))
+        self._lib.fs_program_describe(self.handle, buf, int(need))
+        return buf.value.decode()
 
     def make_workspace(self, device="cuda"):
         import torch

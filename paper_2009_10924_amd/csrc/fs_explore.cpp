@@ -953,6 +953,55 @@ fs_status fs_program_pattern(const fs_program* p, int32_t index, int32_t* ops, i
   return FS_OK;
 }
 
+int64_t fs_program_describe(const fs_program* p, char* text, size_t capacity) {
+  clear_error();
+  if (!p || (!text && capacity > 0)) return fail(FS_ERR_INVALID_ARG, "fs_program_describe: null argument");
+  std::string s;
+  char line[320];
+  auto where = [](const BufRef& r) {
+    char b[48];
+    if (r.kind == BUF_INPUT) snprintf(b, sizeof b, "in%d", r.slot);
+    else if (r.kind == BUF_OUTPUT) snprintf(b, sizeof b, "out%d", r.slot);
+    else snprintf(b, sizeof b, "ws+%lld", (long long)r.offset);
+    return std::string(b);
+  };
+  snprintf(line, sizeof line, "program steps=%zu launches=%d packs=%zu joint_fold_launches=%zu workspace=%lld\n", p->steps.size(),
+           p->info.n_kernels, p->packs.size(), p->joint_folds.size(), (long long)p->info.workspace_bytes);
+  s += line;
+  for (size_t i = 0; i < p->steps.size(); ++i) {
+    const fs_program::Step& st = p->steps[i];
+    const fs_plan_info& pi = st.plan->candidates[st.plan->chosen].info;
+    std::string ops;
+    for (int o : st.ops) ops += (ops.empty() ? "" : ",") + std::to_string(o);
+    snprintf(line, sizeof line, "step %zu ops=%s pattern=%s kernel=%s launches=%zu f_us=%.3f", i, ops.c_str(), pi.pattern, pi.kernel,
+             st.pack >= 0 ? (size_t)0 : st.own_launches, st.f);
+    s += line;
+    if (st.pack >= 0) s += " pack=" + std::to_string(st.pack);
+    s += "\n";
+    for (size_t k = 0; k < st.in.size(); ++k) s += "  input " + std::to_string(k) + " " + where(st.in[k]) + "\n";
+    for (size_t k = 0; k < st.out.size(); ++k) s += "  output " + std::to_string(k) + " " + where(st.out[k]) + "\n";
+    if (pi.workspace_bytes > 0)
+      s += "  scratch ws+" + std::to_string((long long)st.plan_ws_offset) + " " + std::to_string((long long)pi.workspace_bytes) + "\n";
+  }
+  for (size_t j = 0; j < p->packs.size(); ++j) {
+    std::string members;
+    for (int m : p->packs[j].steps) members += (members.empty() ? "" : ",") + std::to_string(m);
+    s += "pack " + std::to_string(j) + " launches=" + std::to_string(p->packs[j].pack->info.n_kernels) + " members=" + members + "\n";
+  }
+  for (size_t j = 0; j < p->joint_folds.size(); ++j) {
+    std::string of;
+    for (const fs_program::JointFold& f : p->joint_folds[j]) of += (of.empty() ? "" : ",") + std::to_string(f.step);
+    s += "joint_fold " + std::to_string(j) + " folds=" + std::to_string(p->joint_folds[j].size()) + " of_steps=" + of + "\n";
+  }
+  const size_t need = s.size() + 1;
+  if (capacity > 0) {
+    const size_t n = std::min(capacity - 1, s.size());
+    memcpy(text, s.data(), n);
+    text[n] = 0;
+  }
+  return (int64_t)need;
+}
+
 fs_status fs_program_execute(const fs_program* p, const void* const* inputs, void* const* outputs, void* workspace,
                              size_t workspace_bytes, void* hip_stream) {
   clear_error();

@@ -173,6 +173,29 @@ def test_backward_block_folds_its_column_sums_in_one_launch_at_the_end():
     assert len(sums) >= 2 and all(s["info"]["n_kernels"] >= 2 for s in sums)                  # a plan alone keeps its folds
 
 
+def test_program_listing_names_steps_buffers_and_joint_folds():
+    from workloads import transformer_block_backward_graph
+    spec = transformer_block_backward_graph(3, 40, 4, 32, 256, "bf16")
+    prog = B.Program(B.Graph.from_spec(spec))
+    text = prog.describe()
+    lines = text.splitlines()
+    steps = [l for l in lines if l.startswith("step ")]
+    assert lines[0].startswith("program steps=") and len(steps) == len(prog.patterns())
+    for l, st in zip(steps, prog.patterns()):
+        assert f"ops={','.join(map(str, st['ops']))} " in l and f"kernel={st['info']['kernel']} " in l
+    # every graph input and output appears where a step binds it; what crosses steps lives in the workspace
+    assert all(f" in{k}" in text for k in range(len(spec.inputs))) and all(f" out{k}" in text for k in range(len(spec.outputs)))
+    issued = [l for l in lines if l.startswith("step ") or l.startswith("pack ")]
+    assert sum(int(l.split("launches=")[1].split()[0]) for l in issued) + len([l for l in lines if l.startswith("joint_fold ")]) == prog.info["n_kernels"]
+    if prog.info["n_joint_folds"]:
+        assert sum(int(l.split("folds=")[1].split()[0]) for l in lines if l.startswith("joint_fold ")) == prog.info["n_joint_folds"]
+    lib = B.load()
+    assert lib.fs_program_describe(None, None, 0) == -1
+    import ctypes
+    small = ctypes.create_string_buffer(16)
+    assert lib.fs_program_describe(prog.handle, small, 16) == len(text) + 1 and small.value.decode() == text[:15]
+
+
 def test_independent_launch_bound_patterns_share_one_packed_launch():
     from workloads import independent_tiny_patterns_graph
     spec = independent_tiny_patterns_graph()
