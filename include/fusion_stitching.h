@@ -158,6 +158,17 @@ fs_tensor fs_graph_op(fs_graph *g, int32_t opcode, int32_t n_in, const fs_tensor
 fs_status fs_graph_output(fs_graph *g, fs_tensor t, int32_t store_as);
 /* Freezes the graph: at least one output, every op reaches an output.
  * Errors: FS_ERR_INVALID_ARG.                                                    */
+/* Declares that graph input `input` is computed OUTSIDE the graph (by a matrix product,
+ * say) from the op result `from`, which must be declared a graph output before
+ * fs_graph_finalize.  Section 2.1: compute-intensive ops are not fused; they cut the graph
+ * of memory-intensive ops, and this call records the cut.  Consequences: no fusion pattern
+ * holds both the op that makes `from` and an op that reads `input` (nor ops on a path
+ * between two of its members that leads through such a dependence); the steps of an explored
+ * program are grouped into stages (fs_program_execute_stage) between which the caller runs
+ * the external computations.  Call it after the op that makes `from` and before any op
+ * reads `input`.  A graph with such dependences has no single plan: fs_plan_create returns
+ * FS_ERR_UNSUPPORTED_PATTERN; use fs_explore.  Errors: FS_ERR_INVALID_ARG.                */
+fs_status fs_graph_external(fs_graph *g, fs_tensor from, fs_tensor input);
 fs_status fs_graph_finalize(fs_graph *g);
 
 /* ---- plan (Section 4.2: enumerate schedules and launch dimensions, discard
@@ -318,6 +329,8 @@ typedef struct fs_program_info {
   double f_total_us;         /* sum of the chosen patterns' delta-evaluator scores (Eq. 3), remote fusion included */
   double predicted_us;       /* latency-evaluator estimate of one fs_program_execute        */
   double predicted_unfused_us; /* the same ops one kernel each, by the delta-evaluator's per-op term */
+  int32_t n_stages;       /* 1 + the longest chain of external computations (fs_graph_external) between steps */
+  int32_t reserved;
 } fs_program_info;
 
 /* Delta-evaluator (Section 5.4, Eq. 3) for the ops[0..n) of `g` (op index = order of the
@@ -354,7 +367,7 @@ fs_status fs_program_pattern(const fs_program *p, int32_t index, int32_t *ops, i
  * including the NUL, or a negative error.  One line per step in execution order (`step <i>
  * ops=<graph op indices> pattern=<name> kernel=<name> launches=<issued at the step> f_us=<score>`,
  * with `pack=<j>` for members of a packed launch, which is issued where its first member
- * stands), indented under it where each of the plan's inputs and outputs lives (`in<k>` /
+ * stands, and `stage=<k>` when the program has more than one stage), indented under it where each of the plan's inputs and outputs lives (`in<k>` /
  * `out<k>` of the graph, or `ws+<offset>` in the program's workspace) and the plan's own
  * scratch (`scratch ws+<offset> <bytes>`); then one line per packed launch (`pack <j>
  * launches=<n> members=<steps>`) and per joint fold launch (`joint_fold <j> folds=<n>
@@ -369,6 +382,18 @@ int64_t fs_program_describe(const fs_program *p, char *text, size_t capacity);
  * Errors: FS_ERR_INVALID_ARG, FS_ERR_WORKSPACE, FS_ERR_ALIGN, FS_ERR_HIP.               */
 fs_status fs_program_execute(const fs_program *p, const void *const *inputs, void *const *outputs, void *workspace,
                              size_t workspace_bytes, void *hip_stream);
+
+/* The steps of one stage (0 <= stage < fs_program_info.n_stages), same arguments and rules.
+ * A program whose graph declares external computations (fs_graph_external) is run stage by
+ * stage: after stage k the caller runs, on the same stream, the external computations whose
+ * operands are complete (every graph output that feeds one is written by the end of the
+ * stage that makes it) and whose results stage k+1 reads.  fs_program_execute issues all
+ * stages back to back (for timing the program's own kernels with the external results
+ * already in place).  Column sums that nothing reads, external computations included, may
+ * only be complete after the LAST stage (their joint fold launch runs there).
+ * Errors: as fs_program_execute.                                                           */
+fs_status fs_program_execute_stage(const fs_program *p, int32_t stage, const void *const *inputs, void *const *outputs,
+                                   void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Plain streaming copy of `bytes` (multiple of 16) from src to dst, both DEVICE
  * and 16-byte aligned: the measured HBM ceiling every result is reported beside

@@ -63,11 +63,26 @@ class GraphView:
             for name in op.inputs:
                 self.sharing[i].extend(readers[name])
         self.is_output = [op.out in outputs for op in spec.ops]
+        # ops that wait for an op's result through a computation outside the graph (Section 2.1: compute-intensive ops
+        # are not fused): they run after it, and never in the same kernel
+        self.waiting: List[List[int]] = [[] for _ in range(self.n)]
+        for src, dst in getattr(spec, "external", ()):
+            for i in readers.get(dst, []):
+                if i not in self.waiting[producer[src]]:
+                    self.waiting[producer[src]].append(i)
+        # desc: everything that reads an op's result, directly or not (what a pattern grown from the op may hold)
+        # after: the same plus what waits for it through external computations (what decides the order of execution)
         self.desc: List[set] = [set() for _ in range(self.n)]
+        self.after: List[set] = [set() for _ in range(self.n)]
         for i in range(self.n - 1, -1, -1):
             for c in self.consumers[i]:
                 self.desc[i].add(c)
                 self.desc[i] |= self.desc[c]
+                self.after[i].add(c)
+                self.after[i] |= self.after[c]
+            for c in self.waiting[i]:
+                self.after[i].add(c)
+                self.after[i] |= self.after[c]
 
 
 def plan_is_acyclic(view: GraphView, groups: Sequence[Sequence[int]]) -> bool:
@@ -83,7 +98,7 @@ def plan_is_acyclic(view: GraphView, groups: Sequence[Sequence[int]]) -> bool:
     succ: Dict[int, set] = {}
     waiting: Dict[int, int] = {k: 0 for k in set(gid.values())}
     for o in range(view.n):
-        for c in view.consumers[o]:
+        for c in list(view.consumers[o]) + list(view.waiting[o]):
             if gid[c] != gid[o] and gid[c] not in succ.setdefault(gid[o], set()):
                 succ[gid[o]].add(gid[c])
                 waiting[gid[c]] += 1

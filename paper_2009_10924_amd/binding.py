@@ -32,7 +32,7 @@ EXPORTS = [
     "fs_plan_source", "fs_codegen_enable", "fs_codegen_available", "fs_execute", "fs_stream_copy", "fs_last_error", "fs_version",
     "fs_pack_create", "fs_pack_destroy", "fs_pack_query", "fs_pack_execute",
     "fs_explore", "fs_explore_score", "fs_program_destroy", "fs_program_query", "fs_program_pattern", "fs_program_execute",
-    "fs_program_describe",
+    "fs_program_describe", "fs_program_execute_stage", "fs_graph_external",
 ]
 FS_PACK_MAX_MEMBERS = 256
 
@@ -114,6 +114,7 @@ class fs_program_info(C.Structure):
         ("n_kernels", C.c_int32), ("n_packs", C.c_int32), ("beam_plans", C.c_int32), ("n_joint_folds", C.c_int32),
         ("workspace_bytes", C.c_int64), ("bytes_min", C.c_int64), ("bytes_moved_model", C.c_int64),
         ("f_total_us", C.c_double), ("predicted_us", C.c_double), ("predicted_unfused_us", C.c_double),
+        ("n_stages", C.c_int32), ("reserved", C.c_int32),
     ]
 
     def as_dict(self) -> Dict:
@@ -191,6 +192,10 @@ def load() -> C.CDLL:
     lib.fs_program_pattern.restype = i32
     lib.fs_program_execute.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp, C.c_size_t, vp]
     lib.fs_program_execute.restype = i32
+    lib.fs_program_execute_stage.argtypes = [vp, i32, C.POINTER(vp), C.POINTER(vp), vp, C.c_size_t, vp]
+    lib.fs_program_execute_stage.restype = i32
+    lib.fs_graph_external.argtypes = [vp, i32, i32]
+    lib.fs_graph_external.restype = i32
     lib.fs_pack_create.argtypes = [C.POINTER(vp), i32, C.POINTER(vp)]
     lib.fs_pack_create.restype = i32
     lib.fs_pack_destroy.argtypes = [vp]
@@ -264,8 +269,14 @@ class Graph:
         g = cls()
         for t in spec.inputs:
             g.names[t.name] = g.input(t.dtype, t.dims)
+        external = list(getattr(spec, "external", ()))
         for op in spec.ops:
             g.names[op.out] = g.op(op.opcode, [g.names[n] for n in op.inputs], **op.attr)
+            # a dependence through an external computation is declared as soon as its source exists (and before
+            # anything reads the input it leads to)
+            for src, dst in external:
+                if src == op.out:
+                    _check(g._lib.fs_graph_external(g.handle, g.names[src], g.names[dst]))
         for name, dtype in spec.outputs:
             g.output(g.names[name], dtype)
         g.finalize()
@@ -478,6 +489,19 @@ class Program:
 
         def call(_keep=(ins, outs)):
             code = fn(handle, ins, outs, ws, nb, st)
+            if code < 0:
+                _check(code)
+        return call
+
+    def bind_stage(self, stage: int, inputs: Sequence[int], outputs: Sequence[int], workspace: int, workspace_bytes: int, stream: int):
+        """The steps of one stage (programs whose graph declares external computations run stage by stage)."""
+        ins = (C.c_void_p * max(1, len(inputs)))(*inputs)
+        outs = (C.c_void_p * max(1, len(outputs)))(*outputs)
+        ws, nb, st = C.c_void_p(workspace), C.c_size_t(workspace_bytes), C.c_void_p(stream)
+        fn, handle = self._lib.fs_program_execute_stage, self.handle
+
+        def call(_keep=(ins, outs)):
+            code = fn(handle, stage, ins, outs, ws, nb, st)
             if code < 0:
                 _check(code)
         return call

@@ -59,7 +59,9 @@ struct Explorer {
   const fs_graph& g;
   int n;                                     // ops
   std::vector<std::vector<int>> consumers;   // op -> ops that read its result (sorted, distinct)
-  std::vector<std::vector<uint64_t>> desc;   // op -> bitset of its descendants
+  std::vector<std::vector<int>> waiting;     // op -> ops that wait for its result through an external computation
+  std::vector<std::vector<uint64_t>> desc;   // op -> bitset of everything that runs after it because of it
+  std::vector<std::vector<uint64_t>> reads_of;   // op -> bitset of its descendants through tensors of the graph alone
   std::map<OpSet, Scored> memo;
   int top_k = 3, beam_width = 3;
 
@@ -69,13 +71,32 @@ struct Explorer {
       std::set<int> c(g.tensors[g.ops[i].out].consumers.begin(), g.tensors[g.ops[i].out].consumers.end());
       consumers[i].assign(c.begin(), c.end());
     }
+    waiting.resize(n);
+    const std::vector<std::vector<int>> waits_for = g.external_producers();
+    for (int i = 0; i < n; ++i)
+      for (int p : waits_for[i]) waiting[p].push_back(i);
     const int words = (n + 63) / 64;
     desc.assign(n, std::vector<uint64_t>(words, 0));
-    for (int i = n - 1; i >= 0; --i)
+    reads_of.assign(n, std::vector<uint64_t>(words, 0));
+    for (int i = n - 1; i >= 0; --i) {
       for (int c : consumers[i]) {
+        desc[i][c / 64] |= 1ull << (c % 64);
+        reads_of[i][c / 64] |= 1ull << (c % 64);
+        for (int w = 0; w < words; ++w) { desc[i][w] |= desc[c][w]; reads_of[i][w] |= reads_of[c][w]; }
+      }
+      for (int c : waiting[i]) {
         desc[i][c / 64] |= 1ull << (c % 64);
         for (int w = 0; w < words; ++w) desc[i][w] |= desc[c][w];
       }
+    }
+  }
+
+  // An op and an op that waits for its result through an external computation cannot share a kernel.
+  bool holds_external_dependence(const OpSet& p) const {
+    for (int o : p)
+      for (int c : waiting[o])
+        if (std::binary_search(p.begin(), p.end(), c)) return true;
+    return false;
   }
 
   // No path may leave the pattern and come back (Section 5.2, cyclic dependence).
@@ -194,7 +215,7 @@ struct Explorer {
       s.valid = true;
       s.t_fused = s.t_unfused;
       s.f = 0;
-    } else if (!convex(p)) {
+    } else if (holds_external_dependence(p) || !convex(p)) {
       s.why = FS_ERR_CYCLE;
     } else {
       SubGraph sub;
@@ -358,7 +379,7 @@ struct Explorer {
       std::vector<Pat> seeds;
       OpSet cone{v};
       for (int x = v + 1; x < n; ++x)
-        if ((desc[v][x / 64] >> (x % 64)) & 1) cone.push_back(x);
+        if ((reads_of[v][x / 64] >> (x % 64)) & 1) cone.push_back(x);
       if (cone.size() > 1) consider(cone, &seeds);
       // the same cone, but not continued past a graph output: that tensor is written to memory anyway
       OpSet bounded{v};
@@ -404,25 +425,28 @@ struct Explorer {
     for (int o = 0; o < n; ++o)
       if (gid[o] < 0) gid[o] = n_groups++;
     std::vector<std::vector<int>> next(n_groups);
-    std::vector<int> waiting(n_groups, 0);
-    for (int o = 0; o < n; ++o)
+    std::vector<int> pending(n_groups, 0);
+    for (int o = 0; o < n; ++o) {
       for (int c : consumers[o])
         if (gid[c] != gid[o]) next[gid[o]].push_back(gid[c]);
+      for (int c : waiting[o])
+        if (gid[c] != gid[o]) next[gid[o]].push_back(gid[c]);
+    }
     for (int a = 0; a < n_groups; ++a) {
       std::sort(next[a].begin(), next[a].end());
       next[a].erase(std::unique(next[a].begin(), next[a].end()), next[a].end());
-      for (int b : next[a]) ++waiting[b];
+      for (int b : next[a]) ++pending[b];
     }
     std::vector<int> ready;
     for (int a = 0; a < n_groups; ++a)
-      if (waiting[a] == 0) ready.push_back(a);
+      if (pending[a] == 0) ready.push_back(a);
     int done = 0;
     while (!ready.empty()) {
       const int a = ready.back();
       ready.pop_back();
       ++done;
       for (int b : next[a])
-        if (--waiting[b] == 0) ready.push_back(b);
+        if (--pending[b] == 0) ready.push_back(b);
     }
     return done == n_groups;
   }
@@ -537,6 +561,7 @@ struct fs_program {
     int64_t plan_ws_offset = 0;
     int32_t pack = -1;                  // index into packs, -1 = runs on its own
     size_t own_launches = 0;            // launches of the plan issued at the step itself (the rest are joint folds)
+    int32_t stage = 0;                  // external computations that must have run before it (longest chain of them)
   };
   struct JointFold { int step; size_t launch; };   // a K_COLFOLD launch of a step's plan, issued after the last step
   struct Pack {
@@ -648,14 +673,21 @@ bool order_steps(const fs_graph& g, std::vector<fs_program::Step>* steps) {
   std::stable_sort(steps->begin(), steps->end(),
                    [](const fs_program::Step& a, const fs_program::Step& b) { return a.ops.back() < b.ops.back(); });
   const std::vector<int> owner = owners(g, *steps);
+  const std::vector<std::vector<int>> waits_for = g.external_producers();
   const size_t ns = steps->size();
-  std::vector<std::set<int>> deps(ns);
+  std::vector<std::set<int>> deps(ns), across(ns);   // steps it reads from; steps it waits for through external computations
   for (size_t s = 0; s < ns; ++s)
-    for (int o : (*steps)[s].ops)
+    for (int o : (*steps)[s].ops) {
       for (int k = 0; k < g.ops[o].n_in; ++k) {
         const int32_t prod = g.tensors[g.ops[o].in[k]].producer;
         if (prod >= 0 && owner[prod] != (int)s) deps[s].insert(owner[prod]);
       }
+      for (int prod : waits_for[o]) {
+        if (owner[prod] == (int)s) return false;   // cannot happen: such a pattern has no score
+        deps[s].insert(owner[prod]);
+        across[s].insert(owner[prod]);
+      }
+    }
   std::vector<int> order;
   std::vector<char> done(ns, 0);
   while (order.size() < ns) {
@@ -669,6 +701,14 @@ bool order_steps(const fs_graph& g, std::vector<fs_program::Step>* steps) {
     }
     if (!progressed) return false;
   }
+  // stages: a step runs in the stage after the latest one it waits for across an external computation, and never
+  // before a step it reads from; the steps are issued stage by stage
+  for (int s : order) {
+    int32_t stage = 0;
+    for (int d : deps[s]) stage = std::max(stage, (*steps)[d].stage + (across[s].count(d) ? 1 : 0));
+    (*steps)[s].stage = stage;
+  }
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return (*steps)[a].stage < (*steps)[b].stage; });
   std::vector<fs_program::Step> sorted;
   for (int s : order) sorted.push_back(std::move((*steps)[s]));
   steps->swap(sorted);
@@ -688,10 +728,11 @@ void decide_packs(const fs_graph& g, fs_program* prog, std::vector<int>* pos) {
         if (prod >= 0 && owner[prod] != s) level[s] = std::max(level[s], level[owner[prod]] + 1);
       }
   const double tiny_us = 3.0 * device().launch_s * 1e6;   // the launch is a third or more of the pattern's estimated time
-  std::map<int, std::vector<int>> by_level;
+  std::map<std::pair<int, int>, std::vector<int>> by_level;   // (stage, level): members of a pack are issued together
   for (int s = 0; s < ns; ++s) {
     const fs_plan* p = prog->steps[s].plan;
-    if ((p->pack.spec >= 0 || p->generic.valid) && p->candidates[p->chosen].info.predicted_us <= tiny_us) by_level[level[s]].push_back(s);
+    if ((p->pack.spec >= 0 || p->generic.valid) && p->candidates[p->chosen].info.predicted_us <= tiny_us)
+      by_level[{prog->steps[s].stage, level[s]}].push_back(s);
   }
   for (auto& kv : by_level) {
     if (kv.second.size() < 2) continue;
@@ -776,8 +817,11 @@ void join_folds(const fs_graph& g, fs_program* prog) {
       for (int k = 0; k < 3; ++k) {
         const BufRef& r = launches[first - 1].ptr[k];
         if (r.kind != BUF_OUTPUT) continue;
-        const Tensor& T = g.tensors[s.out[r.slot].slot];
+        const int32_t t = s.out[r.slot].slot;
+        const Tensor& T = g.tensors[t];
         if (T.output_slot < 0 || !T.consumers.empty()) free_standing = false;
+        for (const std::pair<int32_t, int32_t>& e : g.external)
+          if (e.first == t) free_standing = false;   // an external computation reads it before the program ends
       }
       if (!free_standing) break;
       --first;
@@ -824,6 +868,8 @@ void fill_info(const Explorer& ex, fs_program* prog, int32_t beam_plans, double 
     I.predicted_us -= (double)(j.size() - 1) * device().launch_s * 1e6;
   }
   I.n_packs = (int32_t)prog->packs.size();
+  I.n_stages = 1;
+  for (const fs_program::Step& s : prog->steps) I.n_stages = std::max(I.n_stages, s.stage + 1);
   for (int o = 0; o < ex.n; ++o) I.predicted_unfused_us += ex.t_single(o) * 1e6;
 }
 
@@ -977,6 +1023,7 @@ int64_t fs_program_describe(const fs_program* p, char* text, size_t capacity) {
              st.pack >= 0 ? (size_t)0 : st.own_launches, st.f);
     s += line;
     if (st.pack >= 0) s += " pack=" + std::to_string(st.pack);
+    if (p->info.n_stages > 1) s += " stage=" + std::to_string(st.stage);
     s += "\n";
     for (size_t k = 0; k < st.in.size(); ++k) s += "  input " + std::to_string(k) + " " + where(st.in[k]) + "\n";
     for (size_t k = 0; k < st.out.size(); ++k) s += "  output " + std::to_string(k) + " " + where(st.out[k]) + "\n";
@@ -1002,9 +1049,11 @@ int64_t fs_program_describe(const fs_program* p, char* text, size_t capacity) {
   return (int64_t)need;
 }
 
-fs_status fs_program_execute(const fs_program* p, const void* const* inputs, void* const* outputs, void* workspace,
-                             size_t workspace_bytes, void* hip_stream) {
-  clear_error();
+}  // extern "C"
+
+// The steps of stages first_stage..last_stage; the joint fold launches go with the program's last stage.
+static fs_status run_program(const fs_program* p, int32_t first_stage, int32_t last_stage, const void* const* inputs,
+                             void* const* outputs, void* workspace, size_t workspace_bytes, void* hip_stream) {
   if (!p || !inputs || !outputs) return fail(FS_ERR_INVALID_ARG, "fs_program_execute: null argument");
   for (int i = 0; i < p->n_inputs; ++i) {
     if (!inputs[i]) return fail(FS_ERR_INVALID_ARG, "fs_program_execute: input %d is null", i);
@@ -1030,6 +1079,7 @@ fs_status fs_program_execute(const fs_program* p, const void* const* inputs, voi
   std::vector<const void*> in;
   std::vector<void*> out;
   for (const fs_program::Step& s : p->steps) {
+    if (s.stage < first_stage || s.stage > last_stage) continue;
     if (s.pack >= 0) {
       if (pack_done[s.pack]) continue;
       pack_done[s.pack] = 1;
@@ -1051,6 +1101,7 @@ fs_status fs_program_execute(const fs_program* p, const void* const* inputs, voi
     const fs_status st = run_launches(s.plan, in.data(), out.data(), need > 0 ? ws + s.plan_ws_offset : nullptr, hip_stream, s.own_launches);
     if (st != FS_OK) return st;
   }
+  if (last_stage < p->info.n_stages - 1) return FS_OK;
   for (const std::vector<fs_program::JointFold>& joint : p->joint_folds) {
     FoldManyP t{};
     uint32_t blocks = 0;
@@ -1081,6 +1132,24 @@ fs_status fs_program_execute(const fs_program* p, const void* const* inputs, voi
     if (err != 0) return fail(FS_ERR_HIP, "fs_program_execute: launching the joint fold failed: %s", hip_error_text(err));
   }
   return FS_OK;
+}
+
+extern "C" {
+
+fs_status fs_program_execute(const fs_program* p, const void* const* inputs, void* const* outputs, void* workspace,
+                             size_t workspace_bytes, void* hip_stream) {
+  clear_error();
+  if (!p) return fail(FS_ERR_INVALID_ARG, "fs_program_execute: null argument");
+  return run_program(p, 0, p->info.n_stages - 1, inputs, outputs, workspace, workspace_bytes, hip_stream);
+}
+
+fs_status fs_program_execute_stage(const fs_program* p, int32_t stage, const void* const* inputs, void* const* outputs,
+                                   void* workspace, size_t workspace_bytes, void* hip_stream) {
+  clear_error();
+  if (!p) return fail(FS_ERR_INVALID_ARG, "fs_program_execute_stage: null argument");
+  if (stage < 0 || stage >= p->info.n_stages)
+    return fail(FS_ERR_INVALID_ARG, "fs_program_execute_stage: stage %d outside 0..%d", stage, p->info.n_stages - 1);
+  return run_program(p, stage, stage, inputs, outputs, workspace, workspace_bytes, hip_stream);
 }
 
 }  // extern "C"

@@ -4,6 +4,8 @@
 // be smaller than the id of the result they feed.
 #include <cstring>
 
+#include <algorithm>
+
 #include "fs_internal.hpp"
 
 namespace fs {
@@ -204,11 +206,29 @@ fs_status fs_graph_output(fs_graph* g, fs_tensor t, int32_t store_as) {
   return FS_OK;
 }
 
+fs_status fs_graph_external(fs_graph* g, fs_tensor from, fs_tensor input) {
+  clear_error();
+  if (!g) return fail(FS_ERR_INVALID_ARG, "fs_graph_external: graph is null");
+  if (g->finalized) return fail(FS_ERR_INVALID_ARG, "fs_graph_external: graph is finalized");
+  const int32_t n = (int32_t)g->tensors.size();
+  if (from < 0 || from >= n || input < 0 || input >= n) return fail(FS_ERR_INVALID_ARG, "fs_graph_external: bad tensor id");
+  if (g->tensors[from].producer < 0) return fail(FS_ERR_INVALID_ARG, "fs_graph_external: tensor %d is not the result of an op", from);
+  if (g->tensors[input].producer >= 0) return fail(FS_ERR_INVALID_ARG, "fs_graph_external: tensor %d is not a graph input", input);
+  // declared before anything reads the input: the order in which ops were added stays an order of execution
+  if (!g->tensors[input].consumers.empty())
+    return fail(FS_ERR_INVALID_ARG, "fs_graph_external: input %d is already read by an op; declare the dependence first", input);
+  g->external.emplace_back(from, input);
+  return FS_OK;
+}
+
 fs_status fs_graph_finalize(fs_graph* g) {
   clear_error();
   if (!g) return fail(FS_ERR_INVALID_ARG, "fs_graph_finalize: graph is null");
   if (g->finalized) return FS_OK;
   if (g->outputs.empty()) return fail(FS_ERR_INVALID_ARG, "fs_graph_finalize: no output declared");
+  for (const std::pair<int32_t, int32_t>& e : g->external)
+    if (g->tensors[e.first].output_slot < 0)
+      return fail(FS_ERR_INVALID_ARG, "fs_graph_finalize: tensor %d feeds an external computation and must be a graph output", e.first);
   // every op must reach an output (no dead code inside a fusion pattern)
   for (const Op& op : g->ops) {
     const Tensor& t = g->tensors[op.out];
@@ -220,3 +240,14 @@ fs_status fs_graph_finalize(fs_graph* g) {
 }
 
 }  // extern "C"
+
+std::vector<std::vector<int>> fs_graph::external_producers() const {
+  std::vector<std::vector<int>> waits(ops.size());
+  for (const std::pair<int32_t, int32_t>& e : external)
+    for (int32_t reader : tensors[e.second].consumers) waits[reader].push_back(tensors[e.first].producer);
+  for (std::vector<int>& w : waits) {
+    std::sort(w.begin(), w.end());
+    w.erase(std::unique(w.begin(), w.end()), w.end());
+  }
+  return waits;
+}

@@ -55,7 +55,12 @@ struct fs_graph {
   std::vector<fs::Op> ops;
   std::vector<int32_t> inputs;   // tensor ids in declaration order
   std::vector<int32_t> outputs;  // tensor ids in declaration order
+  // (from, input): graph input `input` is computed outside the graph (say, by a matrix product) from the graph output
+  // `from`.  Whatever reads `input` runs after `from` is complete, and never in the kernel that makes `from`.
+  std::vector<std::pair<int32_t, int32_t>> external;
   bool finalized = false;
+  // per op: the ops whose results it waits for through external computations (sorted, distinct)
+  std::vector<std::vector<int>> external_producers() const;
 };
 
 namespace fs {

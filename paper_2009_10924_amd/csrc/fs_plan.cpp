@@ -173,6 +173,8 @@ fs_status fs::run_launches(const fs_plan* p, const void* const* inputs, void* co
 fs_status fs::create_plan(const fs_graph* g, int32_t scheme, const fs_plan_opts* opts, bool complete, fs_plan** out) {
   if (!g || !out) return fail(FS_ERR_INVALID_ARG, "fs_plan_create: null argument");
   if (!g->finalized) return fail(FS_ERR_INVALID_ARG, "fs_plan_create: graph is not finalized");
+  if (!g->external.empty())
+    return fail(FS_ERR_UNSUPPORTED_PATTERN, "fs_plan_create: the graph waits for external computations between its ops; no single plan runs it (use fs_explore)");
   if (scheme < FS_SCHEME_AUTO || scheme > FS_SCHEME_GLOBAL) return fail(FS_ERR_INVALID_ARG, "fs_plan_create: bad scheme %d", scheme);
   fs_plan_opts o = {-1, 0, 0, 0};
   if (opts) o = *opts;

@@ -46,6 +46,10 @@ SPECS = {
     "layernorm_stats": lambda: layernorm_stats_graph(64, 256, with_variance=True),
 }
 SPECS.update({f"multi{s}": (lambda s=s: random_multi_pattern(s)) for s in range(16)})
+# graphs with matrix products taken out and declared (patterns may not span them)
+SPECS["block_forward"] = lambda: transformer_block_graph(2, 16, 2, 8, 64, "bf16")
+SPECS["block_forward_biases"] = lambda: transformer_block_graph(2, 16, 2, 8, 64, "bf16", projection_bias=True)
+SPECS["block_backward"] = lambda: __import__("workloads").transformer_block_backward_graph(2, 16, 2, 8, 64, "bf16")
 SPECS.update({f"multi_sums{s}": (lambda s=s: random_multi_pattern(s, rows=64, cols=128, segments=2 + s % 3, column_sums=1 + s % 2)) for s in range(8)})
 SPECS.update({f"multi_big{s}": (lambda s=s: random_multi_pattern(100 + s, rows=512, cols=1024, segments=4)) for s in range(4)})
 
@@ -107,8 +111,14 @@ def test_plan_structure(name):
         seen |= set(ops)
         inside = set(ops)
         # convex: nothing outside lies between two members
-        below = set().union(*(view.desc[o] for o in ops)) - inside
-        assert not any(view.desc[x] & inside for x in below), f"{name}: pattern {ops} has a cyclic dependence"
+        below = set().union(*(view.after[o] for o in ops)) - inside
+        assert not any(view.after[x] & inside for x in below), f"{name}: pattern {ops} has a cyclic dependence"
+        # nothing in a pattern waits for another member through an external computation, and what it waits for has run
+        for o in ops:
+            assert not (set(view.waiting[o]) & inside), f"{name}: pattern {ops} spans an external computation"
+        for p in range(view.n):
+            if set(view.waiting[p]) & inside:
+                assert p in done, f"{name}: {ops} runs before op {p}, whose result it needs through an external computation"
         # execution order: every producer outside the pattern has run
         for o in ops:
             assert all(p in done or p in inside for p in view.producers[o]), f"{name}: {ops} runs before its producers"
@@ -138,22 +148,48 @@ def test_transformer_block_plan_is_the_hand_partition():
     assert order.index(tuple(range(11, 23))) < order.index(tuple(range(25, 37)))
 
 
-def test_transformer_block_plan_with_generated_kernels_goes_beyond_the_hand_partition():
-    """A generated kernel is not bound to a family's operand list: the two LayerNorm neighbourhoods, the second of
-    which reads what the first stored, become one 24-op pattern (one launch less, one read of the stored tensor less)."""
-    if not B.codegen_available():
-        pytest.skip("needs the run-time compiler")
+def test_matrix_products_between_patterns_keep_them_apart():
+    """The block's graph says which input each matrix product computes from which outputs.  Without that knowledge
+    the two LayerNorm neighbourhoods, the second of which reads what the first stored, look like ONE 24-op pattern
+    (and a generated kernel can run it); in the block they are five matrix-product-separated stages apart, and the
+    plan is the hand partition, run stage by stage."""
     spec = transformer_block_graph(32, 128, 12, 64, 3072, "bf16")
     g = B.Graph.from_spec(spec)
-    with B.codegen(True):
-        prog = B.Program(g)
-    with B.codegen(False):
-        hand = B.Program(g)
+    prog = B.Program(g)
     steps = prog.patterns()
-    assert prog.info["n_kernels"] < hand.info["n_kernels"] and prog.info["predicted_us"] < hand.info["predicted_us"]
-    big = max(steps, key=lambda s: len(s["ops"]))
-    assert big["info"]["pattern"] == "row_generated" and tuple(big["ops"]) == tuple(range(11, 23)) + tuple(range(25, 37))
     assert sorted(o for s in steps for o in s["ops"]) == list(range(len(spec.ops)))
+    assert max(len(s["ops"]) for s in steps) == 12 and prog.info["n_kernels"] == 6 and prog.info["n_stages"] == 6
+    text = prog.describe()
+    stages = [int(l.split("stage=")[1].split()[0]) for l in text.splitlines() if l.startswith("step ")]
+    assert stages == sorted(stages) == [0, 1, 2, 3, 4, 5]
+    with pytest.raises(B.FsError) as e:        # no single plan can run a graph that waits for outside work in the middle
+        B.Plan(g, "auto")
+    assert e.value.code == -5 and "external" in e.value.text
+    if B.codegen_available():
+        free = B.Program(B.Graph.from_spec(transformer_block_graph(32, 128, 12, 64, 3072, "bf16", matmul_dependences=False)))
+        big = max(free.patterns(), key=lambda s: len(s["ops"]))
+        assert tuple(big["ops"]) == tuple(range(11, 23)) + tuple(range(25, 37)) and free.info["n_stages"] == 1
+        assert free.info["n_kernels"] < prog.info["n_kernels"]
+
+
+def test_external_dependences_are_checked_when_declared():
+    lib = B.load()
+    g = B.Graph()
+    x = g.input("f32", (8, 16))
+    y = g.input("f32", (8, 16))
+    e = g.op("exp", [x])
+    assert lib.fs_graph_external(g.handle, x, y) == -1          # the source must be an op's result
+    assert lib.fs_graph_external(g.handle, e, e) == -1          # the target must be a graph input
+    assert lib.fs_graph_external(g.handle, e, y) == 0
+    t = g.op("tanh", [y])
+    assert lib.fs_graph_external(g.handle, e, y) == -1          # too late: something reads the input already
+    g.output(t, "f32")
+    assert lib.fs_graph_finalize(g.handle) == -1                # what an external computation reads must be an output
+    assert "must be a graph output" in lib.fs_last_error().decode()
+    g.output(e, "f32")
+    g.finalize()
+    prog = B.Program(g)
+    assert prog.info["n_stages"] == 2 and prog.info["n_kernels"] == 2
 
 
 def test_backward_block_folds_its_column_sums_in_one_launch_at_the_end():

@@ -138,6 +138,46 @@ def test_folds_of_column_sums_that_are_read_again_stay_in_place(rows, cols):
     note(f"three bias gradients {rows}x{cols}: {prog.info['n_kernels']} launches ({apart.info['n_kernels']} with every fold in place), worst {worst:.3f}")
 
 
+@pytest.mark.parametrize("backward", [False, True])
+def test_block_runs_stage_by_stage_between_its_matrix_products(backward):
+    """The block's graph names the matrix products that were taken out; the program has one stage per stretch between
+    them.  Stage by stage, with the caller's work in between (here: re-writing the inputs the next stage reads, as
+    the matrix product would), the outputs are those of the all-at-once run bit for bit."""
+    import torch
+    from workloads import transformer_block_backward_graph
+    spec = (transformer_block_backward_graph if backward else transformer_block_graph)(3, 40, 4, 32, 256, "bf16")
+    inp = make_inputs(spec, seed=3)
+    whole, prog = run_program(spec, inp, repeat=1)
+    assert prog.info["n_stages"] == 6
+    dev_in = [B.to_device(inp[t.name], t.dtype) for t in spec.inputs]
+    late = {dst for _, dst in spec.external}                      # inputs that a matrix product hands over later
+    for t, d in zip(spec.inputs, dev_in):
+        if t.name in late:
+            d.fill_(float("nan"))                                  # not there yet
+    dev_out = B.alloc_outputs(spec)
+    for o in dev_out:
+        o.fill_(float("nan"))                                      # an output counts as made once it holds numbers
+    ws = prog.make_workspace()
+    stream = torch.cuda.current_stream().cuda_stream
+    ins, outs = [t.data_ptr() for t in dev_in], [t.data_ptr() for t in dev_out]
+    produced = set()
+    for stage in range(prog.info["n_stages"]):
+        prog.bind_stage(stage, ins, outs, ws.data_ptr(), ws.numel(), stream)()
+        torch.cuda.synchronize()
+        # the "matrix products" whose operands are complete hand over their results
+        for (name, dt), o in zip(spec.outputs, dev_out):
+            if not torch.isnan(o.float()).any():
+                produced.add(name)
+        for t, d in zip(spec.inputs, dev_in):
+            if t.name in late and all(src in produced for src, dst in spec.external if dst == t.name):
+                d.copy_(B.to_device(inp[t.name], t.dtype))
+    for (name, dt), o in zip(spec.outputs, dev_out):
+        got = O.to_f64(B.to_host(o, dt), dt)
+        assert np.array_equal(got, whole[name]), name
+    with pytest.raises(B.FsError):
+        prog.bind_stage(6, ins, outs, ws.data_ptr(), ws.numel(), stream)()
+
+
 def test_transformer_block_without_packing_and_remote_fusion():
     spec = transformer_block_graph(2, 16, 2, 8, 64, "bf16")
     a, pa = compare(spec, no_packing=True)

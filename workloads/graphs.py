@@ -56,6 +56,8 @@ class GraphSpec:
     inputs: List[TensorSpec]
     ops: List[OpSpec]
     outputs: List[Tuple[str, str]]
+    # (output name, input name): the input is computed outside the graph (by a matrix product, say) from that output
+    external: List[Tuple[str, str]] = field(default_factory=list)
 
     def input_names(self) -> List[str]:
         return [t.name for t in self.inputs]
@@ -607,13 +609,16 @@ def _layernorm_ops(prefix: str, x: str, res: str, bias: str, gamma: str, beta: s
 
 
 def transformer_block_graph(batch: int = 32, seq: int = 128, heads: int = 12, dim: int = 64, ffn: int = 3072,
-                            dtype: str = "bf16", projection_bias: bool = False) -> GraphSpec:
+                            dtype: str = "bf16", projection_bias: bool = False, matmul_dependences: bool = True) -> GraphSpec:
     """The memory-intensive ops of one transformer encoder block, with the matrix products taken out: their
     results come in as graph inputs.  Head split / merge transposes, scale + mask + softmax, output bias +
     residual + LayerNorm, feed-forward bias + GELU, second bias + residual + LayerNorm that reads the first
     one's stored result (37 ops, 8 patterns by hand).  projection_bias: the query / key / value projections come
     without their biases [H,D], which are added (and the sum rounded to the storage dtype) in front of the head
-    split (43 ops, or 46 with the rounding when the storage dtype is not float32)."""
+    split (43 ops, or 46 with the rounding when the storage dtype is not float32).
+    matmul_dependences: the graph says which input each matrix product computes from which outputs (scores from the
+    split q and k, the context from probabilities and v, ...), so that no pattern spans a matrix product; without
+    them every input counts as available from the start."""
     hidden, rows = heads * dim, batch * seq
     t4 = (batch, seq, heads, dim)
     split, bias_inputs = [], []
@@ -647,12 +652,15 @@ def transformer_block_graph(batch: int = 32, seq: int = 128, heads: int = 12, di
     ] + _layernorm_ops("l2_", "ffn2_out", "l1_out", "bias2", "gamma2", "beta2", 1e-5, dtype)
     outputs = [("qt", dtype), ("kt", dtype), ("vt", dtype), ("p_y", dtype), ("ctx_t", dtype), ("l1_out", dtype),
                ("act", dtype), ("l2_out", dtype)]
+    # the matrix products that were taken out: what each one reads and what it hands back
+    external = [("qt", "scores"), ("kt", "scores"), ("p_y", "ctx"), ("vt", "ctx"), ("ctx_t", "attn_out"), ("l1_out", "ffn1_out"),
+                ("act", "ffn2_out")] if matmul_dependences else []
     return GraphSpec(name=f"pattern_transformer_block_{'pb_' if projection_bias else ''}{dtype}_b{batch}_s{seq}", inputs=inputs, ops=ops,
-                     outputs=outputs)
+                     outputs=outputs, external=external)
 
 
 def transformer_block_backward_graph(batch: int = 32, seq: int = 128, heads: int = 12, dim: int = 64, ffn: int = 3072,
-                                     dtype: str = "bf16") -> GraphSpec:
+                                     dtype: str = "bf16", matmul_dependences: bool = True) -> GraphSpec:
     """The memory-intensive ops of the backward pass through one transformer encoder block, matrix products taken out
     (the gradients they produce come in as graph inputs, the gradients they consume go out as graph outputs):
     LayerNorm 2 backward from saved statistics (dx, dgamma, dbeta) and the bias gradient behind it, bias + GELU
@@ -699,7 +707,11 @@ def transformer_block_backward_graph(batch: int = 32, seq: int = 128, heads: int
     outputs = [("l2_dxc", dtype), ("l2_dgamma", "f32"), ("l2_dbeta", "f32"), ("dbias2", "f32"), ("f_dxc", dtype), ("dbias1", "f32"),
                ("l1_dxc", dtype), ("l1_dgamma", "f32"), ("l1_dbeta", "f32"), ("dbias_o", "f32"), ("d_ctx", dtype), ("d_scores", dtype),
                ("d_q", dtype), ("d_k", dtype), ("d_v", dtype)]
-    return GraphSpec(name=f"pattern_transformer_block_backward_{dtype}_b{batch}_s{seq}", inputs=inputs, ops=ops, outputs=outputs)
+    # the backward matrix products that were taken out: the gradient each one computes from which gradient
+    external = [("l2_dxc", "up_act"), ("f_dxc", "up_l1"), ("l1_dxc", "up_ctx"), ("d_ctx", "up_probs"), ("d_ctx", "up_v"),
+                ("d_scores", "up_q"), ("d_scores", "up_k")] if matmul_dependences else []
+    return GraphSpec(name=f"pattern_transformer_block_backward_{dtype}_b{batch}_s{seq}", inputs=inputs, ops=ops, outputs=outputs,
+                     external=external)
 
 
 def random_multi_pattern(seed: int, rows: int = 24, cols: int = 32, segments: int = 3, dtype: str = "f32",
