@@ -266,7 +266,10 @@ def measure_program(name, steps, warmup):
     ws = [prog.make_workspace() for _ in range(n_sets)]
     calls = [prog.bind([t.data_ptr() for t in i], [t.data_ptr() for t in o], w.data_ptr(), w.numel(), stream)
              for i, o, w in zip(inputs, outputs, ws)]
-    unf = B.Plan(g, "unfused")
+    # the per-op baseline of the same ops (one plan has no place for work between its kernels: the declared matrix
+    # products are left out of its graph, as their results are in place for both timings anyway)
+    import dataclasses
+    unf = B.Plan(B.Graph.from_spec(dataclasses.replace(spec, external=[])), "unfused")
     uws = [unf.make_workspace() for _ in range(2)]
     ucalls = [unf.bind([t.data_ptr() for t in inputs[k]], [t.data_ptr() for t in outputs[k]],
                        uws[k].data_ptr() if uws[k] is not None else 0, uws[k].numel() if uws[k] is not None else 0, stream)
@@ -288,7 +291,8 @@ def measure_program(name, steps, warmup):
     t_unf = timed(ucalls, max(5, steps // 8))
     steps_info = prog.patterns()
     return {"workload": spec.name, "ops": info["n_ops"], "patterns": info["n_patterns"], "single_ops": info["n_single_ops"],
-            "launches": info["n_kernels"], "packs": info["n_packs"], "workspace_bytes": info["workspace_bytes"],
+            "launches": info["n_kernels"], "packs": info["n_packs"], "stages": info["n_stages"], "joint_folds": info["n_joint_folds"],
+            "workspace_bytes": info["workspace_bytes"],
             "bytes_min": info["bytes_min"], "us": t_prog, "GBps": info["bytes_min"] / t_prog / 1e3,
             "frac_of_peak": info["bytes_min"] / t_prog / 1e3 / HBM_PEAK_GBPS,
             "unfused_us": t_unf, "unfused_launches": unf.info["n_kernels"], "speedup_vs_unfused": t_unf / t_prog,
