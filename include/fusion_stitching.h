@@ -341,7 +341,8 @@ typedef struct fs_program_info {
  * dependence, also when the call fails with FS_ERR_UNSUPPORTED_PATTERN (the explorer
  * grows such patterns further, in case a larger one is covered by a kernel family).
  * `ops`, `f_us`, `f_optimistic_us` are HOST pointers.  Errors: FS_ERR_INVALID_ARG; FS_ERR_CYCLE (fusing
- * them creates a cyclic dependence, Section 5.2); FS_ERR_UNSUPPORTED_PATTERN (no stitched
+ * them creates a cyclic dependence, Section 5.2, or they hold both ends of an external
+ * computation declared with fs_graph_external); FS_ERR_UNSUPPORTED_PATTERN (no stitched
  * kernel can run them as one pattern); FS_ERR_DTYPE (a graph output stored in another
  * dtype than it was computed in would have to feed ops outside the pattern).            */
 fs_status fs_explore_score(const fs_graph *g, const int32_t *ops, int32_t n, double *f_us, double *f_optimistic_us);
