@@ -47,6 +47,8 @@ SPECS = {
 }
 SPECS.update({f"multi{s}": (lambda s=s: random_multi_pattern(s)) for s in range(16)})
 # graphs with matrix products taken out and declared (patterns may not span them)
+SPECS.update({f"multi_outside{s}": (lambda s=s: random_multi_pattern(s, rows=64, cols=128, segments=2 + s % 3, external_links=True,
+                                                                    column_sums=s % 2)) for s in range(8)})
 SPECS["block_forward"] = lambda: transformer_block_graph(2, 16, 2, 8, 64, "bf16")
 SPECS["block_forward_biases"] = lambda: transformer_block_graph(2, 16, 2, 8, 64, "bf16", projection_bias=True)
 SPECS["block_backward"] = lambda: __import__("workloads").transformer_block_backward_graph(2, 16, 2, 8, 64, "bf16")

@@ -178,6 +178,40 @@ def test_block_runs_stage_by_stage_between_its_matrix_products(backward):
         prog.bind_stage(6, ins, outs, ws.data_ptr(), ws.numel(), stream)()
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_random_programs_with_outside_links_run_stage_by_stage(seed):
+    """Random segments, every other link of the chain a computation outside the graph: the program against the
+    oracle, and stage by stage (the linked inputs filled in only once their source is complete) bit for bit the same."""
+    import torch
+    rows, cols = [(64, 128), (130, 64), (40, 520)][seed % 3]
+    spec = random_multi_pattern(seed, rows=rows, cols=cols, segments=2 + seed % 3, external_links=True, column_sums=seed % 2)
+    worst, prog = compare(spec, seed=seed)
+    assert prog.info["n_stages"] == 1 + len(spec.external)        # the links are in series
+    inp = make_inputs(spec, seed=seed)
+    whole, _ = run_program(spec, inp, repeat=1)
+    dev_in = [B.to_device(inp[t.name], t.dtype) for t in spec.inputs]
+    late = {dst: src for src, dst in spec.external}
+    for t, d in zip(spec.inputs, dev_in):
+        if t.name in late:
+            d.fill_(float("nan"))
+    dev_out = B.alloc_outputs(spec)
+    for o in dev_out:
+        o.fill_(float("nan"))
+    ws = prog.make_workspace()
+    stream = torch.cuda.current_stream().cuda_stream
+    ins, outs = [t.data_ptr() for t in dev_in], [t.data_ptr() for t in dev_out]
+    out_of = {name: o for (name, _), o in zip(spec.outputs, dev_out)}
+    for stage in range(prog.info["n_stages"]):
+        prog.bind_stage(stage, ins, outs, ws.data_ptr(), ws.numel(), stream)()
+        torch.cuda.synchronize()
+        for t, d in zip(spec.inputs, dev_in):
+            if t.name in late and not torch.isnan(out_of[late[t.name]].float()).any() and torch.isnan(d.float()).any():
+                d.copy_(B.to_device(inp[t.name], t.dtype))
+    for (name, dt), o in zip(spec.outputs, dev_out):
+        assert np.array_equal(O.to_f64(B.to_host(o, dt), dt), whole[name]), name
+    note(f"multi pattern {seed} with outside links: {prog.info['n_stages']} stages, {prog.info['n_kernels']} launches, worst {worst:.3f} of the bar")
+
+
 def test_transformer_block_without_packing_and_remote_fusion():
     spec = transformer_block_graph(2, 16, 2, 8, 64, "bf16")
     a, pa = compare(spec, no_packing=True)

@@ -715,21 +715,28 @@ def transformer_block_backward_graph(batch: int = 32, seq: int = 128, heads: int
 
 
 def random_multi_pattern(seed: int, rows: int = 24, cols: int = 32, segments: int = 3, dtype: str = "f32",
-                         seg_ops: Tuple[int, int] = (3, 9), column_sums: int = 0) -> GraphSpec:
+                         seg_ops: Tuple[int, int] = (3, 9), column_sums: int = 0, external_links: bool = False) -> GraphSpec:
     """Several random row patterns chained through transposes (each transpose turns the previous segment's
-    columns into rows, so no single row kernel can span it) plus an independent side pattern."""
+    columns into rows, so no single row kernel can span it) plus an independent side pattern.
+    external_links: every other link of the chain is a computation outside the graph instead (the next segment's
+    first input is declared as computed from the previous segment's main output)."""
     import random
     rnd = random.Random(1000 + seed)
     inputs: List[TensorSpec] = []
     ops: List[OpSpec] = []
     outputs: List[Tuple[str, str]] = []
     carry = None
+    external: List[Tuple[str, str]] = []
+    outside_source = None
     r, c = rows, cols
     for s in range(segments):
         seg = random_row_pattern(seed * 17 + s, r, c, dtype, n_ops=rnd.randint(*seg_ops), column_sums=column_sums)
         ren = {t.name: f"s{s}_{t.name}" for t in seg.inputs}
         ren.update({o.out: f"s{s}_{o.out}" for o in seg.ops})
         seg_inputs = list(seg.inputs)
+        if outside_source is not None:
+            external.append((outside_source, ren[seg_inputs[0].name]))   # this segment's first input comes from outside
+            outside_source = None
         if carry is not None:
             ren[seg_inputs[0].name] = carry                      # the first full input is the transposed carry
             seg_inputs = seg_inputs[1:]
@@ -738,7 +745,11 @@ def random_multi_pattern(seed: int, rows: int = 24, cols: int = 32, segments: in
         main = ren[seg.outputs[0][0]]
         for name, dt in seg.outputs[1:]:
             outputs.append((ren[name], dt))
-        if s + 1 < segments:
+        if s + 1 < segments and external_links and s % 2 == 0:
+            outputs.append((main, dtype))          # what the outside computation reads
+            outside_source = main
+            carry = None
+        elif s + 1 < segments:
             cv = f"s{s}_cv"
             ops.append(_op(cv, "convert", main, dtype=dtype))     # transposes move stored values
             carry = f"s{s}_t"
@@ -746,7 +757,8 @@ def random_multi_pattern(seed: int, rows: int = 24, cols: int = 32, segments: in
             r, c = c, r
         else:
             outputs.append((main, dtype))
-    return GraphSpec(name=f"pattern_multi{seed}_{dtype}_{rows}x{cols}", inputs=inputs, ops=ops, outputs=outputs)
+    return GraphSpec(name=f"pattern_multi{seed}_{dtype}_{rows}x{cols}" + ("_ext" if external_links else ""), inputs=inputs, ops=ops,
+                     outputs=outputs, external=external)
 
 
 def independent_tiny_patterns_graph() -> GraphSpec:
