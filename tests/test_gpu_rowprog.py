@@ -270,6 +270,20 @@ def test_random_row_patterns_with_the_wider_vocabulary(seed):
     note(f"random pattern {seed} (wider vocabulary) {rows}x{cols} {dtype}: {info['kernel']}, {info['n_candidates']} shapes, worst {worst}")
 
 
+@pytest.mark.parametrize("seed", range(9))
+def test_random_row_patterns_on_rows_worked_through_in_chunks(seed):
+    """Seeded random patterns (wider vocabulary, several inputs and outputs, kept values) on rows beyond a workgroup's
+    registers: every chunked shape, with and without chunks kept in registers, and the per-op plan."""
+    if not B.codegen_available():
+        pytest.skip("rows of this length exist as generated kernels only")
+    dtype = ("bf16", "f32", "f16")[seed % 3]
+    rows, cols = [(3, 70000), (2, 40004), (4, 66000)][seed % 3]
+    spec = random_row_pattern(2500 + seed, rows, cols, dtype, n_ops=5 + seed % 7, more_ops=seed % 2 == 1)
+    worst, info = _run(spec, seed=seed)
+    assert "chunks" in info["kernel"], info
+    note(f"random pattern {seed} in chunks {rows}x{cols} {dtype}: {info['kernel']}, {info['n_candidates']} shapes, worst {worst}")
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_random_row_patterns_with_column_sums(seed):
     """Seeded random patterns of which one to three full-shaped values are also summed over all rows: every launch
