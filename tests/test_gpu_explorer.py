@@ -212,6 +212,96 @@ def test_random_programs_with_outside_links_run_stage_by_stage(seed):
     note(f"multi pattern {seed} with outside links: {prog.info['n_stages']} stages, {prog.info['n_kernels']} launches, worst {worst:.3f} of the bar")
 
 
+def test_block_forward_with_its_matrix_products_run_between_the_stages():
+    """One encoder block end to end: the six stages of the explored program with the five groups of matrix products
+    really run between them (torch, bfloat16) from the outputs the graph says they read.  Reference: the same flow in
+    float64 with every stored tensor rounded to bfloat16.  A dependence missing from the graph's declaration would let
+    a stage read an input before its matrix product wrote it (the inputs start out as NaN)."""
+    import torch
+    B_, S, H, Dh, F = 3, 40, 4, 32, 256
+    hidden, rows = H * Dh, B_ * S
+    spec = transformer_block_graph(B_, S, H, Dh, F, "bf16")
+    prog = B.Program(B.Graph.from_spec(spec))
+    assert prog.info["n_stages"] == 6
+    rng = np.random.default_rng(7)
+
+    def bf(a):                                   # float64 values on the bfloat16 grid
+        return O.round_to(np.asarray(a, dtype=np.float64), "bf16")
+
+    def store(v):                                # ... as storage (bit patterns)
+        return (np.ascontiguousarray(v, dtype=np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    x0 = bf(rng.standard_normal((rows, hidden)))
+    W = {n: bf(rng.standard_normal(shape) / np.sqrt(shape[0])) for n, shape in
+         (("q", (hidden, hidden)), ("k", (hidden, hidden)), ("v", (hidden, hidden)), ("o", (hidden, hidden)), ("1", (hidden, F)), ("2", (F, hidden)))}
+    given = make_inputs(spec, seed=7)            # mask, biases, gains: the inputs no matrix product makes
+    late = {dst for _, dst in spec.external} | {"q_lin", "k_lin", "v_lin", "x"}
+
+    # what each matrix product computes, from float64 views of the tensors it reads (graph outputs and the block's input)
+    products = {
+        "q_lin": lambda t: (t["x0"] @ W["q"]).reshape(B_, S, H, Dh), "k_lin": lambda t: (t["x0"] @ W["k"]).reshape(B_, S, H, Dh),
+        "v_lin": lambda t: (t["x0"] @ W["v"]).reshape(B_, S, H, Dh), "x": lambda t: t["x0"],
+        "scores": lambda t: t["qt"] @ np.swapaxes(t["kt"], -1, -2), "ctx": lambda t: t["p_y"] @ t["vt"],
+        "attn_out": lambda t: t["ctx_t"].reshape(rows, hidden) @ W["o"], "ffn1_out": lambda t: t["l1_out"] @ W["1"],
+        "ffn2_out": lambda t: t["act"] @ W["2"],
+    }
+    needs = {"q_lin": [], "k_lin": [], "v_lin": [], "x": []}
+    for src, dst in spec.external:
+        needs.setdefault(dst, []).append(src)
+
+    # reference: float64, one matrix product after the other in the order of the block, stored tensors rounded to
+    # bfloat16.  Inputs that are not there yet are zeros: what does not depend on them is already right.
+    dims = {t.name: t.dims for t in spec.inputs}
+    ref_in = {t.name: (O.to_f64(given[t.name], t.dtype) if t.name not in late else np.zeros(t.dims)) for t in spec.inputs}
+    seen = {"x0": x0}
+    for name in ("q_lin", "k_lin", "v_lin", "x", "scores", "ctx", "attn_out", "ffn1_out", "ffn2_out"):
+        assert all(src in seen for src in needs[name])
+        ref_in[name] = bf(products[name](seen)).reshape(dims[name])
+        out = O.evaluate(spec, {n: store(v) for n, v in ref_in.items()}, round_outputs=True)
+        seen.update({n: out[n] for n, _ in spec.outputs})   # (those a later product reads are complete by then)
+    ref = out
+
+    # GPU: the program's stages with torch's matrix products between them
+    dev_in = {t.name: (B.to_device(given[t.name], t.dtype) if t.name not in late else
+                       torch.full(tuple(t.dims), float("nan"), dtype=torch.bfloat16, device="cuda")) for t in spec.inputs}
+    dev_out = {name: o for (name, _), o in zip(spec.outputs, B.alloc_outputs(spec))}
+    for o in dev_out.values():
+        o.fill_(float("nan"))
+    dW = {n: torch.from_numpy(w).to("cuda", torch.bfloat16) for n, w in W.items()}
+    dx0 = torch.from_numpy(x0).to("cuda", torch.bfloat16)
+    gpu_products = {
+        "q_lin": lambda: (dx0 @ dW["q"]).view(B_, S, H, Dh), "k_lin": lambda: (dx0 @ dW["k"]).view(B_, S, H, Dh),
+        "v_lin": lambda: (dx0 @ dW["v"]).view(B_, S, H, Dh), "x": lambda: dx0,
+        "scores": lambda: dev_out["qt"] @ dev_out["kt"].transpose(-1, -2), "ctx": lambda: dev_out["p_y"] @ dev_out["vt"],
+        "attn_out": lambda: dev_out["ctx_t"].reshape(rows, hidden) @ dW["o"], "ffn1_out": lambda: dev_out["l1_out"] @ dW["1"],
+        "ffn2_out": lambda: dev_out["act"] @ dW["2"],
+    }
+    ws = prog.make_workspace()
+    stream = torch.cuda.current_stream().cuda_stream
+    ins = [dev_in[t.name].data_ptr() for t in spec.inputs]
+    outs = [dev_out[name].data_ptr() for name, _ in spec.outputs]
+    written = set()
+
+    def run_products():
+        for name in sorted(late - written):
+            if all(not torch.isnan(dev_out[s].float()).any() for s in needs[name]):
+                dev_in[name].copy_(gpu_products[name]())
+                written.add(name)
+    run_products()                               # the projections of the block's input
+    for stage in range(prog.info["n_stages"]):
+        prog.bind_stage(stage, ins, outs, ws.data_ptr(), ws.numel(), stream)()
+        torch.cuda.synchronize()
+        run_products()
+    assert written == late
+    for name, dt in spec.outputs:
+        got = O.to_f64(B.to_host(dev_out[name], dt), dt)
+        assert np.isfinite(got).all(), name
+        # bfloat16 matrix products on the GPU accumulate in float32 and round once; the reference rounds float64
+        # sums: a unit in the last place apart now and then, and LayerNorm passes that on
+        err = O.max_rel_err(got, ref[name].reshape(got.shape), O.rms(ref[name]))
+        assert err <= 5e-2, (name, err)
+        note(f"    block forward with matrix products, {name}: max err {err:.2e} of the rms")
+
+
 def test_transformer_block_without_packing_and_remote_fusion():
     spec = transformer_block_graph(2, 16, 2, 8, 64, "bf16")
     a, pa = compare(spec, no_packing=True)
