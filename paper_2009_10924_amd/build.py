@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(PKG_DIR, "libfusion_stitching.so")
 
 SOURCES = [
     "fs_graph.cpp", "fs_unfused.cpp", "fs_match.cpp", "fs_cost.cpp", "fs_stitch.cpp", "fs_family_softmax.cpp", "fs_family_layernorm.cpp", "fs_family_gelu.cpp",
-    "fs_family_transpose.cpp", "fs_family_rows.cpp", "fs_plan.cpp", "fs_pack.cpp", "fs_rowprog.cpp", "fs_explore.cpp", "fs_codegen.cpp",
+    "fs_family_transpose.cpp", "fs_family_rows.cpp", "fs_plan.cpp", "fs_pack.cpp", "fs_rowprog.cpp", "fs_explore.cpp", "fs_program.cpp", "fs_codegen.cpp",
     "kernels/launch.hip", "kernels/unfused.hip", "kernels/softmax.hip", "kernels/layernorm.hip",
     "kernels/gelu.hip", "kernels/tchain.hip", "kernels/rowops.hip", "kernels/pack.hip", "kernels/rowprog.hip",
     "kernels/gen_runtime.hip", "kernels/gen_sample.hip",
