@@ -53,7 +53,7 @@ struct Compiler {
   int n_out = 0, n_rout = 0, n_reductions = 0;
   int n_colsum = 0;                       // column sums over all rows: outputs only, handed out by a fold launch
   int32_t colsum_slot[kProgMaxColSums];   // their fs_execute output slots
-  int32_t colsum_dt = -1;                 // the dtype they are handed out in (one for all of a pattern's sums)
+  int32_t colsum_dt[kProgMaxColSums];     // the dtype each is handed out in (a fold launch rounds its sums to one dtype)
   std::vector<char> is_colsum;            // per op
   std::vector<char> sum_chain;            // per op: a sum along one leading axis on the way to a column sum (emits nothing)
   int vec_instr = 0, scal_instr = 0, reg_reads = 0, reg_writes = 0, trans = 0;
@@ -254,7 +254,11 @@ struct Compiler {
         ProgInstr cs{};
         cs.op = PO_COLSUM;
         cs.b_kind = PK_ACC;
-        if (!planning) { cs.dst = (uint8_t)n_colsum; colsum_slot[n_colsum++] = out.output_slot; }
+        if (!planning) {
+          cs.dst = (uint8_t)n_colsum;
+          colsum_dt[n_colsum] = (int32_t)out.store_as;
+          colsum_slot[n_colsum++] = out.output_slot;
+        }
         if (!push(cs)) return false;
         if (!planning)
           for (int r : reads[i])
@@ -515,11 +519,9 @@ struct Compiler {
               sum_chain[i] == 0) {
             const int end = column_sum_chain_end(i);
             const Tensor* last = end >= 0 ? &g.tensors[g.ops[end].out] : nullptr;
-            if (last && last->output_slot >= 0 && last->consumers.empty() && last->store_as != FS_I32 &&
-                (colsum_dt < 0 || colsum_dt == (int32_t)last->store_as)) {
+            if (last && last->output_slot >= 0 && last->consumers.empty() && last->store_as != FS_I32) {
               // the sum over all rows: every workgroup leaves partial sums, a second launch folds them.  Nothing in the
               // pattern can read it (that would take a grid-wide wait), so it has to be a graph output.
-              colsum_dt = (int32_t)last->store_as;
               for (size_t k = i; (int)k != end; k = (size_t)g.tensors[g.ops[k].out].consumers[0]) sum_chain[k] = 1;
               sum_chain[end] = 2;
               if ((int)i != end) {
@@ -962,13 +964,12 @@ void add_column_sums(const Compiler& c, int vec, const Shape& s, int64_t bytes_m
   ml.ptr[kSlotWs].kind = BUF_WORKSPACE;
   ml.ptr[kSlotWs].offset = 0;
   cand->info.lds_bytes += s.block ? 0 : c.n_colsum * 4 * (int32_t)(s.L * kv) * 4;
-  // a fold launch hands out two sums: sums 0 and 1 by the first, 2 and 3 by a second one over the other half of
-  // the partial rows
-  for (int first = 0; first < c.n_colsum; first += 2) {
-    const int here = std::min(2, c.n_colsum - first);
+  // a fold launch hands out two neighbouring sums of one dtype (or one sum) from its slice of the partial rows
+  for (int first = 0, here = 0; first < c.n_colsum; first += here) {
+    here = (first + 1 < c.n_colsum && c.colsum_dt[first] == c.colsum_dt[first + 1]) ? 2 : 1;
     cand->launches.emplace_back();
     Launch& f = cand->launches.back();
-    make_fold_launch(&f, n_wg, (uint32_t)here * base.cols, base.cols, width, c.colsum_dt);
+    make_fold_launch(&f, n_wg, (uint32_t)here * base.cols, base.cols, width, c.colsum_dt[first]);
     f.ptr[0].kind = BUF_WORKSPACE;
     f.ptr[0].offset = (int64_t)first * base.cols * 4;
     for (int i = 0; i < here; ++i) {

@@ -257,6 +257,12 @@ def test_column_sums_handed_out_in_16_bits(rows, cols, dtype, sum_dtype):
         worst, info = _run(spec, repeat=2)
         assert info["pattern"] == "row_generated" and info["n_kernels"] == launches and info["scheme"] == "global"
         note(f"{spec.name} sums as {sum_dtype}: {info['kernel']}, worst {worst}")
+    # sums of different dtypes side by side: a fold launch each where neighbours differ
+    from workloads.graphs import GraphSpec
+    spec = layernorm_backward_bias_graph(rows, cols, dtype, sum_dtype=sum_dtype)
+    mixed = GraphSpec(spec.name + "_mixed", spec.inputs, spec.ops, [(n, "f32" if n == "dgamma" else d) for n, d in spec.outputs])
+    worst, info = _run(mixed, repeat=2)
+    assert info["pattern"] == "row_generated" and info["n_kernels"] == 4
 
 
 @pytest.mark.parametrize("seed", range(24))

@@ -83,10 +83,12 @@ def emulate(listing, spec, inputs, anchor_dims):
     # column sums leave through the fold launch that follows: its pointer lines name the outputs
     fold = [i for i, l in enumerate(lines) if l[:2] == ["launch", "colfold"]]
     colsum_bind = {}
-    for k, start in enumerate(fold):          # each fold launch hands out two sums, in order
-        for l in lines[start + 1:(fold[k + 1] if k + 1 < len(fold) else len(lines))]:
-            if l and l[0] in ("ptr1", "ptr2"):
-                colsum_bind[2 * k + int(l[0][3:]) - 1] = int(l[1][3:])
+    handed = 0
+    for k, start in enumerate(fold):          # each fold launch hands out one or two sums, in order
+        mine = [l for l in lines[start + 1:(fold[k + 1] if k + 1 < len(fold) else len(lines))] if l and l[0] in ("ptr1", "ptr2")]
+        for l in mine:
+            colsum_bind[handed + int(l[0][3:]) - 1] = int(l[1][3:])
+        handed += len(mine)
     acc = np.zeros((rows, cols), np.float32) if acc0 is None else acc0.copy()
     sacc = np.zeros((rows, 1), np.float32)
     f32 = np.float32
@@ -265,17 +267,20 @@ def test_sums_over_several_leading_axes_in_a_chain_are_one_column_sum(dims):
         assert B.Plan(B.Graph.from_spec(extra), "auto").info["scheme"] == "unfused"
 
 
-def test_column_sums_of_one_pattern_share_the_dtype_they_are_handed_out_in():
+def test_column_sums_of_different_dtypes_get_fold_launches_of_their_own():
+    """A fold launch rounds what it hands out to one dtype: two neighbouring sums of the same dtype share a launch,
+    a sum whose neighbour has another dtype gets its own."""
     from workloads import gelu_backward_graph, layernorm_backward_bias_graph
     from workloads.graphs import GraphSpec
     if not B.codegen_available():
         pytest.skip("needs the run-time compiler")
     plan = B.Plan(B.Graph.from_spec(gelu_backward_graph(64, 128, "bf16", sum_dtype="bf16")), "auto")
     assert plan.info["pattern"] == "row_generated" and plan.info["n_kernels"] == 2
-    spec = layernorm_backward_bias_graph(64, 128, "bf16", sum_dtype="bf16")
+    spec = layernorm_backward_bias_graph(64, 128, "f32", sum_dtype="bf16")          # dbias, dgamma, dbeta all bf16: 2 folds
+    assert B.Plan(B.Graph.from_spec(spec), "auto").info["n_kernels"] == 3
     mixed = GraphSpec(spec.name + "_mixed", spec.inputs, spec.ops, [(n, "f32" if n == "dgamma" else d) for n, d in spec.outputs])
-    assert B.Plan(B.Graph.from_spec(spec), "auto").info["pattern"] == "row_generated"
-    assert B.Plan(B.Graph.from_spec(mixed), "auto").info["scheme"] == "unfused"     # one fold launch rounds to one dtype
+    n_instr, info = _compare(mixed)                                                     # bf16, f32, bf16: a fold each
+    assert info["pattern"] == "row_generated" and info["n_kernels"] == 4
 
 
 @pytest.mark.parametrize("rows,cols", [(37, 96), (50, 128), (9, 1024)])
