@@ -174,6 +174,28 @@ def test_matrix_products_between_patterns_keep_them_apart():
         assert free.info["n_kernels"] < prog.info["n_kernels"]
 
 
+def test_a_stack_of_blocks_is_explored_block_by_block():
+    """Six blocks, 222 ops: six launches per block, one stage per stretch between matrix products, found in seconds."""
+    import time
+    from workloads import transformer_stack_graph
+    spec = transformer_stack_graph(6, 2, 16, 2, 8, 64, "bf16")
+    assert len(spec.ops) == 6 * 37
+    g = B.Graph.from_spec(spec)
+    t0 = time.perf_counter()
+    prog = B.Program(g)
+    assert time.perf_counter() - t0 < 30.0
+    assert prog.info["n_kernels"] == 36 and prog.info["n_stages"] == 36
+    view = X.GraphView(spec)
+    done = set()
+    for st in prog.patterns():
+        inside = set(st["ops"])
+        assert all(p in done or p in inside for o in st["ops"] for p in view.producers[o])
+        assert not any(set(view.waiting[o]) & inside for o in st["ops"])
+        assert all(p in done for p in range(view.n) if set(view.waiting[p]) & inside)
+        done |= inside
+    assert done == set(range(len(spec.ops)))
+
+
 def test_external_dependences_are_checked_when_declared():
     lib = B.load()
     g = B.Graph()

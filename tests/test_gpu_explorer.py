@@ -302,6 +302,16 @@ def test_block_forward_with_its_matrix_products_run_between_the_stages():
         note(f"    block forward with matrix products, {name}: max err {err:.2e} of the rms")
 
 
+def test_a_stack_of_three_blocks_against_the_oracle():
+    """Three blocks chained (a block's residual input is the previous block's output: an edge; its projections are
+    declared matrix products): 111 ops, 18 launches in 18 stages, all at once against the oracle."""
+    from workloads import transformer_stack_graph
+    spec = transformer_stack_graph(3, 2, 16, 2, 8, 64, "bf16")
+    worst, prog = compare(spec)
+    assert prog.info["n_kernels"] == 18 and prog.info["n_stages"] == 18
+    note(f"stack of 3 blocks: {prog.info['n_ops']} ops -> {prog.info['n_kernels']} launches, worst {worst:.3f} of the bar")
+
+
 def test_transformer_block_without_packing_and_remote_fusion():
     spec = transformer_block_graph(2, 16, 2, 8, 64, "bf16")
     a, pa = compare(spec, no_packing=True)

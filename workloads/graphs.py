@@ -659,6 +659,30 @@ def transformer_block_graph(batch: int = 32, seq: int = 128, heads: int = 12, di
                      outputs=outputs, external=external)
 
 
+def transformer_stack_graph(n_blocks: int, batch: int = 32, seq: int = 128, heads: int = 12, dim: int = 64, ffn: int = 3072,
+                            dtype: str = "bf16") -> GraphSpec:
+    """`n_blocks` encoder blocks one after the other: a block's residual input is the previous block's output itself
+    (an edge of the graph), its q / k / v projections are matrix products of that output (declared)."""
+    inputs: List[TensorSpec] = []
+    ops: List[OpSpec] = []
+    outputs: List[Tuple[str, str]] = []
+    external: List[Tuple[str, str]] = []
+    prev_out = None
+    for b in range(n_blocks):
+        blk = transformer_block_graph(batch, seq, heads, dim, ffn, dtype)
+        ren = lambda n, b=b: f"b{b}_{n}"
+        src = lambda n, b=b, prev=prev_out: prev if (n == "x" and prev is not None) else f"b{b}_{n}"
+        inputs += [TensorSpec(ren(t.name), t.dtype, t.dims) for t in blk.inputs if not (t.name == "x" and prev_out is not None)]
+        ops += [OpSpec(ren(o.out), o.opcode, tuple(src(i) for i in o.inputs), dict(o.attr)) for o in blk.ops]
+        outputs += [(ren(n), d) for n, d in blk.outputs]
+        external += [(ren(a), ren(c)) for a, c in blk.external]
+        if prev_out is not None:
+            external += [(prev_out, ren(n)) for n in ("q_lin", "k_lin", "v_lin")]
+        prev_out = ren("l2_out")
+    return GraphSpec(name=f"pattern_transformer_stack{n_blocks}_{dtype}_b{batch}_s{seq}", inputs=inputs, ops=ops, outputs=outputs,
+                     external=external)
+
+
 def transformer_block_backward_graph(batch: int = 32, seq: int = 128, heads: int = 12, dim: int = 64, ffn: int = 3072,
                                      dtype: str = "bf16", matmul_dependences: bool = True) -> GraphSpec:
     """The memory-intensive ops of the backward pass through one transformer encoder block, matrix products taken out
