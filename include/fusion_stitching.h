@@ -199,7 +199,8 @@ fs_status fs_plan_candidate(const fs_plan *p, int32_t index, fs_plan_info *out);
  * flags=<v|s><k|-> aux=<dtype> imm=<value>` (v: acc <- acc op b on full-shaped values,
  * s: the same on per-row values; k: result also kept in register dst).  A pattern with
  * sums over all rows adds `colsums <n> partials <buffer> rows_per_group <r> col_tiles <t>`
- * (and the fold launches after it); a row that is worked through in pieces adds
+ * (and `launch colfold` entries after it, one per fold; folds that follow each other
+ * are issued as ONE kernel launch, which `launches=` counts); a row worked through in pieces adds
  * `chunks <n> of <w> columns[, the first <k> kept in registers]`.
  * Errors: FS_ERR_INVALID_ARG.                                                          */
 int64_t fs_plan_describe(const fs_plan *p, char *text, size_t capacity);
@@ -217,8 +218,8 @@ int64_t fs_plan_describe(const fs_plan *p, char *text, size_t capacity);
  * worked through in chunks, one pass per row reduction, the chunks kept in registers where
  * they fit); sums over all rows of a pattern (reduce_sum along axis 0 of a rank-2 value, or
  * a chain of reduce_sums along each leading axis in turn; a graph output nothing else
- * reads, float32 or rounded once to a 16-bit dtype; the plan then has fold launches and a
- * workspace); more than 4 full-shaped inputs.
+ * reads, float32 or rounded once to a 16-bit dtype; the plan then has a workspace and a
+ * second launch that folds the partial sums); more than 4 full-shaped inputs.
  * Compilation needs no GPU; the module is loaded on the device that is current at plan
  * creation (or, without one, by the first fs_execute: do that one outside stream capture).
  * If the compiler is not available, compilation fails or the kernel would spill registers,

@@ -840,12 +840,14 @@ void fill_info(const Explorer& ex, fs_program* prog, int32_t beam_plans, double 
       ++I.n_steps;
     }
   }
-  for (const std::vector<fs_program::JointFold>& j : prog->joint_folds) {
-    // the estimate keeps the folds' own times and drops the launches they no longer pay for
-    I.n_joint_folds += (int32_t)j.size();
-    I.n_kernels -= (int32_t)j.size() - 1;
-    I.predicted_us -= (double)(j.size() - 1) * device().launch_s * 1e6;
-  }
+  // joint folds: the steps they come from no longer issue a fold launch of their own; the estimate keeps the folds'
+  // own times and drops the launches they no longer pay for
+  int moved_from = 0;
+  for (const fs_program::Step& s : prog->steps)
+    if (s.pack < 0 && s.own_launches < s.plan->candidates[s.plan->chosen].launches.size()) ++moved_from;
+  for (const std::vector<fs_program::JointFold>& j : prog->joint_folds) I.n_joint_folds += (int32_t)j.size();
+  I.n_kernels += (int32_t)prog->joint_folds.size() - moved_from;
+  I.predicted_us -= (double)(moved_from - (int)prog->joint_folds.size()) * device().launch_s * 1e6;
   I.n_packs = (int32_t)prog->packs.size();
   I.n_stages = 1;
   for (const fs_program::Step& s : prog->steps) I.n_stages = std::max(I.n_stages, s.stage + 1);

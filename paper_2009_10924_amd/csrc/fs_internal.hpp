@@ -178,6 +178,8 @@ fs_status create_plan(const fs_graph* g, int32_t scheme, const fs_plan_opts* opt
 // The first `n_launches` launches of the plan's chosen candidate (arguments already validated by the caller).
 fs_status run_launches(const fs_plan* p, const void* const* inputs, void* const* outputs, void* workspace, void* hip_stream,
                        size_t n_launches);
+// How many kernel launches that makes (folds of column partial sums that follow each other go out as one).
+size_t launches_issued(const fs_plan* p, size_t n_launches);
 fs_status complete_plan(fs_plan* p);
 int64_t graph_bytes_min(const fs_graph& g);
 // Multiply-high constants for n / d with n < 2^31 (d == 0 in the result marks "no usable constants").

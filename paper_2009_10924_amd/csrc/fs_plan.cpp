@@ -144,20 +144,60 @@ fs_status complete_plan(fs_plan* p) {
 
 using namespace fs;
 
+size_t fs::launches_issued(const fs_plan* p, size_t n_launches) {
+  const Candidate& c = p->candidates[p->chosen];
+  const size_t end = std::min(n_launches, c.launches.size());
+  size_t issued = 0;
+  for (size_t li = 0; li < end; ++li, ++issued)
+    if (c.launches[li].kernel == K_COLFOLD)
+      for (size_t folds = 1; li + 1 < end && folds < (size_t)kFoldManyMax && c.launches[li + 1].kernel == K_COLFOLD; ++folds) ++li;
+  return issued;
+}
+
 fs_status fs::run_launches(const fs_plan* p, const void* const* inputs, void* const* outputs, void* workspace, void* hip_stream,
                        size_t n_launches) {
   const Candidate& c = p->candidates[p->chosen];
-  for (size_t li = 0; li < n_launches && li < c.launches.size(); ++li) {
-    const Launch& l = c.launches[li];
-    KernelArgs a = l.args;
-    for (int k = 0; k < kMaxPtrs; ++k) {
-      switch (l.ptr[k].kind) {
-        case BUF_INPUT: a.p[k] = const_cast<void*>(inputs[l.ptr[k].slot]); break;
-        case BUF_OUTPUT: a.p[k] = outputs[l.ptr[k].slot]; break;
-        case BUF_WORKSPACE: a.p[k] = static_cast<char*>(workspace) + l.ptr[k].offset; break;
-        default: a.p[k] = nullptr; break;
-      }
+  const size_t end = std::min(n_launches, c.launches.size());
+  auto address = [&](const BufRef& r) -> void* {
+    switch (r.kind) {
+      case BUF_INPUT: return const_cast<void*>(inputs[r.slot]);
+      case BUF_OUTPUT: return outputs[r.slot];
+      case BUF_WORKSPACE: return static_cast<char*>(workspace) + r.offset;
+      default: return nullptr;
     }
+  };
+  for (size_t li = 0; li < end; ++li) {
+    const Launch& l = c.launches[li];
+    // several folds of column partial sums in a row (a pattern with more than two column sums, or sums of different
+    // dtypes) are independent of each other: they go out as one launch
+    size_t folds = 0;
+    while (li + folds < end && folds < (size_t)kFoldManyMax && c.launches[li + folds].kernel == K_COLFOLD) ++folds;
+    if (folds >= 2) {
+      FoldManyP t{};
+      uint32_t blocks = 0;
+      for (int k = 0; k < kFoldManyMax; ++k) t.first_block[k] = 0xffffffffu;
+      for (size_t k = 0; k < folds; ++k) {
+        const Launch& f = c.launches[li + k];
+        const GeluP& fp = f.args.u.gelu;
+        t.partials[k] = static_cast<const float*>(address(f.ptr[0]));
+        t.out0[k] = static_cast<float*>(address(f.ptr[1]));
+        t.out1[k] = static_cast<float*>(address(f.ptr[2]));
+        t.first_block[k] = blocks;
+        t.n[k] = fp.n_row_tiles;
+        t.width[k] = fp.fold_cols;
+        t.stride[k] = fp.cols;
+        t.split[k] = fp.fold_split;
+        t.quads[k] = fp.fold_quads;
+        t.out_dt[k] = fp.dt;
+        blocks += f.shape.grid[0];
+      }
+      const int err = launch_fold_many(t, blocks, hip_stream);
+      if (err != 0) return fail(FS_ERR_HIP, "fs_execute: launching the folds failed: %s", hip_error_text(err));
+      li += folds - 1;
+      continue;
+    }
+    KernelArgs a = l.args;
+    for (int k = 0; k < kMaxPtrs; ++k) a.p[k] = address(l.ptr[k]);
     int err;
     if (l.kernel == K_ROW_GENERATED) {
       if (!l.gen) return fail(FS_ERR_INVALID_ARG, "fs_execute: the plan's generated kernel was never compiled");
@@ -304,7 +344,7 @@ int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) {
     else snprintf(b, sizeof b, "-");
     return std::string(b);
   };
-  snprintf(line, sizeof line, "plan pattern=%s scheme=%s launches=%zu\n", c.info.pattern, scheme_name(c.info.scheme), c.launches.size());
+  snprintf(line, sizeof line, "plan pattern=%s scheme=%s launches=%zu\n", c.info.pattern, scheme_name(c.info.scheme), launches_issued(p, c.launches.size()));
   s += line;
   for (const Launch& l : c.launches) {
     snprintf(line, sizeof line, "launch %s grid=%u block=%u lds=%u\n", kernel_name(l.kernel), l.shape.grid[0] * l.shape.grid[1] * l.shape.grid[2],

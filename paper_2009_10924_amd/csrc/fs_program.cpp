@@ -56,7 +56,7 @@ int64_t fs_program_describe(const fs_program* p, char* text, size_t capacity) {
     std::string ops;
     for (int o : st.ops) ops += (ops.empty() ? "" : ",") + std::to_string(o);
     snprintf(line, sizeof line, "step %zu ops=%s pattern=%s kernel=%s launches=%zu f_us=%.3f", i, ops.c_str(), pi.pattern, pi.kernel,
-             st.pack >= 0 ? (size_t)0 : st.own_launches, st.f);
+             st.pack >= 0 ? (size_t)0 : launches_issued(st.plan, st.own_launches), st.f);
     s += line;
     if (st.pack >= 0) s += " pack=" + std::to_string(st.pack);
     if (p->info.n_stages > 1) s += " stage=" + std::to_string(st.stage);

@@ -978,7 +978,7 @@ void add_column_sums(const Compiler& c, int vec, const Shape& s, int64_t bytes_m
     }
   }
   cand->info.scheme = FS_SCHEME_GLOBAL;
-  cand->info.n_kernels = (int32_t)cand->launches.size();
+  cand->info.n_kernels = 2;   // the pattern's kernel, and its folds as one launch
   cand->info.workspace_bytes = (int64_t)n_wg * width * 4;
   cand->info.bytes_moved_model = bytes_min + 2 * cand->info.workspace_bytes;
   if (s.CT > 1)
@@ -998,7 +998,7 @@ void add_column_sums(const Compiler& c, int vec, const Shape& s, int64_t bytes_m
   }
   gc.lds_bytes_per_block = cand->info.lds_bytes;
   gc.barriers = 1;
-  gc.serial_tail_s += (d.mem_latency_s + 0.5 * d.launch_s + d.mem_latency_s * std::ceil(n_wg / 64.0 / 8.0) * 0.5) * (cand->launches.size() - 1);
+  gc.serial_tail_s += (d.mem_latency_s + 0.5 * d.launch_s + d.mem_latency_s * std::ceil(n_wg / 64.0 / 8.0) * 0.5) * 1.0;
 }
 
 // One candidate: the program in shape `s`, interpreted or generated.  false: the shape does not fit (the
