@@ -964,7 +964,8 @@ void add_column_sums(const Compiler& c, int vec, const Shape& s, int64_t bytes_m
   ml.ptr[kSlotWs].kind = BUF_WORKSPACE;
   ml.ptr[kSlotWs].offset = 0;
   cand->info.lds_bytes += s.block ? 0 : c.n_colsum * 4 * (int32_t)(s.L * kv) * 4;
-  // a fold launch hands out two neighbouring sums of one dtype (or one sum) from its slice of the partial rows
+  // a fold hands out two neighbouring sums of one dtype (or one sum) from its slice of the partial rows; the folds
+  // are kept as one record each and issued together as one launch
   for (int first = 0, here = 0; first < c.n_colsum; first += here) {
     here = (first + 1 < c.n_colsum && c.colsum_dt[first] == c.colsum_dt[first + 1]) ? 2 : 1;
     cand->launches.emplace_back();
