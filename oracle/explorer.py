@@ -25,6 +25,20 @@ What the paper fixes, and how it is read here (each reading is listed in the des
   * Seeds: everything downstream of a vertex, the same stopped at graph outputs, and the connected component a
     vertex starts are offered as candidates too and escape the top-k cut (a kernel family can be runnable as a
     whole while parts of it are not, and the cut favours ever larger patterns).
+
+Four of these go beyond the paper's text: the pairwise joining of the halves' candidates, the tentative patterns,
+the look-ahead in the beam's ranking and the seeds.  `explore` takes a switch for each (tentative patterns arise
+only when the score callback reports "unsupported"), and with all of them off it is the procedure of Section 5.2 /
+5.3 alone.
+
+Pins (tests/test_explorer_pins.py, fixtures tests/golden/explorer_*.txt: tiny graphs with hand-written score
+tables, every expected value derived by hand in the fixture's comments):
+  explore           candidate patterns per vertex and the beam's plans on a chain, a diamond, a vertex with three
+                    consumers and the cyclic-dependence triangle of Section 5.2, additions off; the three-consumer
+                    case also with the halves joined
+  plan_is_acyclic   the cyclic pattern of the triangle / diamond; two patterns that wait for each other
+  remote_fusion     two independent chains and a lone op (hand gains), and a merge that a cycle forbids
+  brute_force_best  hand-enumerated optimum on each fixture
 """
 from __future__ import annotations
 
@@ -63,7 +77,7 @@ class GraphView:
             for name in op.inputs:
                 self.sharing[i].extend(readers[name])
         self.is_output = [op.out in outputs for op in spec.ops]
-        # ops that wait for an op's result through a computation outside the graph (Section 2.1: compute-intensive ops
+        # ops that wait for an op's result through a computation outside the graph (Section 1: compute-intensive ops
         # are not fused): they run after it, and never in the same kernel
         self.waiting: List[List[int]] = [[] for _ in range(self.n)]
         for src, dst in getattr(spec, "external", ()):
@@ -125,8 +139,10 @@ def _key(p: Pat):
     return (-p.f, p.ops)
 
 
-def explore(view: GraphView, score: ScoreFn, top_k: int = 3, beam_width: int = 3, max_tentative_ops: int = 24):
-    """Returns (candidate patterns per vertex, the beam's plans as [(patterns, accumulated score)])."""
+def explore(view: GraphView, score: ScoreFn, top_k: int = 3, beam_width: int = 3, max_tentative_ops: int = 24,
+            join_halves: bool = True, seeds: bool = True, lookahead: bool = True):
+    """Returns (candidate patterns per vertex, the beam's plans as [(patterns, accumulated score)]).
+    join_halves / seeds / lookahead switch the additions to Section 5.2 / 5.3 described in the module header."""
     n = view.n
 
     def reads_own_output(ops: Ops) -> bool:
@@ -134,6 +150,8 @@ def explore(view: GraphView, score: ScoreFn, top_k: int = 3, beam_width: int = 3
         return any(view.is_output[o] and any(c in s for c in view.consumers[o]) for o in ops)
 
     def consider(ops: Ops, out: List[Pat]) -> None:
+        if not plan_is_acyclic(view, [ops]):   # Section 5.2: fusing these ops creates a cyclic dependence
+            return
         status, f, f_opt = score(ops)
         if status == 0:
             if f > 0:
@@ -181,9 +199,10 @@ def explore(view: GraphView, score: ScoreFn, top_k: int = 3, beam_width: int = 3
         a = reduce_group(v, group[:half])
         b = reduce_group(v, group[half:])
         out = a + b
-        for x in a:
-            for y in b:
-                consider(unite(x.ops, y.ops), out)
+        if join_halves:
+            for x in a:
+                for y in b:
+                    consider(unite(x.ops, y.ops), out)
         return keep_top(out)
 
     for v in range(n - 1, -1, -1):
@@ -203,11 +222,11 @@ def explore(view: GraphView, score: ScoreFn, top_k: int = 3, beam_width: int = 3
                 if comp[x] < 0:
                     comp[x] = v
                     stack.append(x)
-    for v in range(n):
-        seeds: List[Pat] = []
+    for v in range(n if seeds else 0):
+        seed_pats: List[Pat] = []
         cone = tuple([v] + sorted(x for x in view.desc[v]))
         if len(cone) > 1:
-            consider(cone, seeds)
+            consider(cone, seed_pats)
         # the same cone, not continued past a graph output
         inside = {v}
         for x in range(v, n):
@@ -215,13 +234,13 @@ def explore(view: GraphView, score: ScoreFn, top_k: int = 3, beam_width: int = 3
                 inside.update(view.consumers[x])
         bounded = tuple(sorted(inside))
         if len(bounded) > 1 and bounded != cone:
-            consider(bounded, seeds)
+            consider(bounded, seed_pats)
         if comp[v] == v:
             whole = tuple(x for x in range(n) if comp[x] == v)
             if len(whole) > 1 and whole != cone and whole != bounded:
-                consider(whole, seeds)
+                consider(whole, seed_pats)
         # seeds escape the top-k cut
-        for sd in seeds:
+        for sd in seed_pats:
             if all(p.ops != sd.ops for p in cand[v]):
                 cand[v].append(sd)
         cand[v].sort(key=_key)
@@ -238,7 +257,7 @@ def explore(view: GraphView, score: ScoreFn, top_k: int = 3, beam_width: int = 3
 
     def rank(covered, f, v):
         r = f
-        for u in range(v + 1, n):
+        for u in range(v + 1, n if lookahead else 0):
             if u not in covered:
                 r += per_op[u]
         return r
