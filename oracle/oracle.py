@@ -8,7 +8,7 @@ of the fusion pattern one after another (Section 7.2 of the paper: results are
 unchanged by fusion).  So the oracle is that plain definition: every op of the
 subgraph is evaluated on its own, in topological (list) order, each
 intermediate materialised as a float64 numpy array.  No blocking, fusion or
-reordering.  Op vocabulary = the memory-intensive ops of Section 2.1 / 4
+reordering.  Op vocabulary = the memory-intensive ops of Section 1 / 3.1 / 4
 (elementwise light and expensive, reduction, broadcast, transpose).
 
 Readings of points the paper leaves open (it states no numerics at all):
@@ -186,15 +186,21 @@ _UNARY = {"square": op_square, "exp": op_exp, "rsqrt": op_rsqrt, "tanh": op_tanh
 
 
 def evaluate(graph, inputs: Mapping[str, np.ndarray], round_outputs: bool = False,
-             keep_all: bool = False) -> Dict[str, np.ndarray]:
+             keep_all: bool = False, stored: Mapping[str, np.ndarray] = None) -> Dict[str, np.ndarray]:
     """Evaluate `graph` op by op in float64.
 
     graph   : object with .inputs (name,dtype,dims), .ops (out,opcode,inputs,attr), .outputs
     inputs  : storage-dtype arrays keyed by input name
+    stored  : {name of a `convert` result that is a graph output: float64 array of the values some implementation
+              stored for it}.  The ops that read such a result then read the stored values instead of the oracle's
+              own rounding, so everything downstream is the exact function of what was stored (an upstream value near
+              a rounding tie may legitimately round either way; the choice must not be charged to what is computed
+              from it).  The value reported for the `convert` result itself stays the oracle's own.
     returns : {output name: float64 array}; with keep_all every intermediate too.
     """
     env: Dict[str, np.ndarray] = {}
     pre_convert: Dict[str, np.ndarray] = {}
+    own: Dict[str, np.ndarray] = {}       # the oracle's own rounding where `stored` replaced it
     for t in graph.inputs:
         a = to_f64(inputs[t.name], t.dtype)
         if tuple(a.shape) != tuple(t.dims):
@@ -227,12 +233,17 @@ def evaluate(graph, inputs: Mapping[str, np.ndarray], round_outputs: bool = Fals
         else:
             raise ValueError(f"unknown opcode {code}")
         env[op.out] = np.asarray(r, dtype=np.float64)
+        if stored is not None and op.out in stored:
+            if code != "convert":
+                raise ValueError(f"stored value given for {op.out}, which is not the result of a convert")
+            own[op.out] = env[op.out]
+            env[op.out] = np.asarray(stored[op.out], dtype=np.float64).reshape(env[op.out].shape)
     if keep_all:
         return env
     out: Dict[str, np.ndarray] = {}
     for name, dtype in graph.outputs:
         if round_outputs:
-            out[name] = round_to(env[name], dtype)
+            out[name] = round_to(own.get(name, env[name]), dtype)
         else:
             out[name] = pre_convert.get(name, env[name])
     return out
