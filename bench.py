@@ -1,16 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark of the stitched hot path on one MI355X.
 
-Headline workload (benchmark configs[1]): residual add + bias + LayerNorm,
-x,res fp32 [8192,768] -> bf16, one stitched kernel per step.  A step is one pass of the
-whole subgraph over one batch.  Inputs are resident in HBM before the timed region;
-the step rotates through enough independent buffer sets that no set is still in the
-256 MB Infinity Cache when its turn comes again (cold-HBM rule).
+Headline workload: the largest of the benchmark's five configurations, C4 = bias + tanh-GELU
+forward fused with the bias-gradient column sum, x, grad bf16 [16384,3072] (302 MB of minimum
+traffic; two launches per step: the stitched kernel and the fold of its column partial sums).
+A step is one pass of the whole subgraph over one batch.  Inputs are resident in HBM before
+the timed region; the step rotates through enough independent buffer sets that no set is still
+in the 256 MB Infinity Cache when its turn comes again (cold-HBM rule).
 
-Prints ONE JSON line: metric/value = achieved GB/s on the subgraph's minimum traffic
-(each input read once + each output written once), plus `roofline`, `cpu_baseline`
-(the float64 per-op oracle timed on this machine's host) and, for context, the other four
-configurations, the per-op GPU baseline and a plain streaming copy.
+Prints ONE JSON line: metric/value = achieved GB/s on the subgraph's minimum traffic (each
+input read once + each output written once) over the whole step, plus `roofline` -- which
+carries `per_config`, the same measurement for all five configurations (C2 and C5 both as the
+evaluator's choice and with the LDS scheme forced), each beside the per-op GPU baseline and
+beside streaming probes of the same bytes and read : write mix -- and `cpu_baseline` (the
+float64 per-op oracle timed on this machine's host).  Further context (backward patterns, packed
+launches, explored programs, generated kernels) follows in extra keys.
 """
 from __future__ import annotations
 
@@ -28,14 +32,17 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 CACHE_BYTES = 256 << 20         # Infinity Cache; rotation footprint must be >= 2x this
 
 
+TRAFFIC_PROFILE = "profiles/stitched_kernels_hbm_traffic_pmc.md"
+
+
 def _profiled_traffic(tag: str):
-    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of
-    known size); the figure is kept with the committed counter summary under profiles/."""
-    path = os.path.join(ROOT, "profiles", "stitched_kernels_hbm_traffic_pmc.md")
+    """HBM bytes per step measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of
+    known size, summed over the step's launches).  NOT measured in this run: read from the committed counter
+    summary, whose lines `TRAFFIC_BYTES_PER_STEP <config> <kernels> <bytes>` were written from such a run."""
     try:
-        for line in open(path):
+        for line in open(os.path.join(ROOT, TRAFFIC_PROFILE)):
             parts = line.split()
-            if len(parts) == 4 and parts[0] == "TRAFFIC_BYTES_PER_LAUNCH" and parts[1] == tag:
+            if len(parts) == 4 and parts[0] == "TRAFFIC_BYTES_PER_STEP" and parts[1] == tag:
                 return float(parts[3])
     except OSError:
         pass
@@ -123,17 +130,50 @@ def copy_ceiling(steps=50, nbytes=1 << 30):
     return 2 * nbytes / sec / 1e9
 
 
-def copy_same_bytes(bytes_min, steps=300):
-    """us of a plain streaming copy that moves the same number of bytes (half read, half written) through
-    rotating cold buffers: the practical ceiling for a kernel of this footprint (launch ramp included)."""
+def time_oracle(spec, host_inputs, min_seconds=10.0, max_repeats=50):
+    """Wall-clock of the float64 per-op oracle on this host (single-threaded numpy kernels): (seconds per pass,
+    passes timed, whether an untimed warm pass came first).  A first pass that already takes `min_seconds` is the
+    sample itself, so that the bounded sample stays at 10-30 s of CPU work."""
+    from oracle import oracle as O
+    t0 = time.perf_counter()
+    O.evaluate(spec, host_inputs)
+    first = time.perf_counter() - t0
+    if first >= min_seconds:
+        return first, 1, False
+    reps, t0 = 0, time.perf_counter()
+    while True:
+        O.evaluate(spec, host_inputs)
+        reps += 1
+        dt = time.perf_counter() - t0
+        if dt >= min_seconds or reps >= max_repeats:
+            return dt / reps, reps, True
+
+
+def stream_mix(spec):
+    """(reads, writes) of equal-sized streams whose ratio is closest to the subgraph's input : output bytes."""
+    from workloads import DTYPE_BYTES
+    import math
+    shapes = None
+    from paper_2009_10924_amd import binding as B
+    shapes = B.output_shapes(spec)
+    bytes_in = sum(math.prod(t.dims) * DTYPE_BYTES[t.dtype] for t in spec.inputs)
+    bytes_out = sum(math.prod(shapes[name]) * DTYPE_BYTES[dt] for name, dt in spec.outputs)
+    ratio = bytes_in / max(1, bytes_out)
+    return min(((1, 1), (2, 1), (3, 1), (4, 1), (3, 2), (1, 2)), key=lambda m: abs(math.log(ratio / (m[0] / m[1]))))
+
+
+def probe_us(total_bytes, reads, writes, vecs_per_lane=2, steps=200):
+    """us of the streaming probe (fs_stream_probe) that moves `total_bytes` as `reads` input and `writes` output
+    streams of equal size through rotating cold buffers: the traffic-only bound for a kernel of this footprint and
+    read : write mix (launch ramp and drain included)."""
     import torch
     from paper_2009_10924_amd import binding as B
-    half = max(16, (bytes_min // 2) // 16 * 16)
-    n_sets = min(_sets_needed(2 * half), 4096)
-    srcs = [torch.empty(half, dtype=torch.uint8, device="cuda").fill_(3) for _ in range(n_sets)]
-    dsts = [torch.empty(half, dtype=torch.uint8, device="cuda") for _ in range(n_sets)]
+    stream_bytes = max(16, (total_bytes // (reads + writes)) // 16 * 16)
+    n_sets = min(_sets_needed((reads + writes) * stream_bytes), 4096)
+    srcs = [torch.empty(max(16, reads * stream_bytes), dtype=torch.uint8, device="cuda").fill_(3) for _ in range(n_sets)]
+    dsts = [torch.empty(max(16, writes * stream_bytes), dtype=torch.uint8, device="cuda") for _ in range(n_sets)]
     stream = torch.cuda.current_stream().cuda_stream
-    calls = [B.bind_copy(d.data_ptr(), s.data_ptr(), half, stream) for d, s in zip(dsts, srcs)]
+    calls = [B.bind_probe(d.data_ptr(), s.data_ptr(), stream_bytes, reads, writes, vecs_per_lane, stream) for d, s in zip(dsts, srcs)]
     for i in range(min(20, n_sets)):
         calls[i]()
     torch.cuda.synchronize()
@@ -146,44 +186,47 @@ def copy_same_bytes(bytes_min, steps=300):
     return e0.elapsed_time(e1) * 1e3 / steps
 
 
-def time_oracle(spec, host_inputs, min_seconds=10.0, max_repeats=50):
-    """Wall-clock of the float64 per-op oracle on this host (single-threaded numpy kernels)."""
-    from oracle import oracle as O
-    O.evaluate(spec, host_inputs)                 # untimed warm pass
-    reps, t0 = 0, time.perf_counter()
-    while True:
-        O.evaluate(spec, host_inputs)
-        reps += 1
-        dt = time.perf_counter() - t0
-        if dt >= min_seconds or reps >= max_repeats:
-            return dt / reps, reps
+def grid_floor_us(workgroups, steps=400):
+    """us of a launch of `workgroups` x 256 threads in which every lane loads one 128-bit vector and stores one
+    (cold buffers): the fixed cost -- launch, first memory round trip, drain -- that a one-shot kernel of that grid
+    pays whatever else it does."""
+    return probe_us(2 * 16 * 256 * max(1, workgroups), 1, 1, vecs_per_lane=1, steps=steps)
 
 
-def measure_config(name, spec, steps, warmup, with_unfused=True):
-    r = Runner(spec, "auto")
+def measure_config(name, spec, steps, warmup, with_unfused=True, scheme="auto", probes=True):
+    r = Runner(spec, scheme)
     wall, ev = r.time_region(steps, warmup)
     sec = ev / steps
     out = {
         "workload": spec.name, "pattern": r.info["pattern"], "scheme": r.info["scheme"], "kernel": r.info["kernel"],
-        "n_kernels": r.info["n_kernels"], "bytes_min": r.info["bytes_min"], "us": sec * 1e6,
+        "n_kernels": r.info["n_kernels"], "grid": r.info["grid"][0], "block": r.info["block"][0], "vgprs": r.info["vgprs"],
+        "lds_bytes": r.info["lds_bytes"], "bytes_min": r.info["bytes_min"], "us": sec * 1e6,
         "GBps": r.info["bytes_min"] / sec / 1e9, "frac_of_peak": r.info["bytes_min"] / sec / 1e9 / HBM_PEAK_GBPS,
-        "predicted_us": r.info["predicted_us"], "buffer_sets": r.n_sets,
+        "predicted_us": r.info["predicted_us"], "buffer_sets": r.n_sets, "launches_timed": steps,
     }
     if r.info["pattern"] == "row_generated":   # the generated kernel's own name, as kernel traces show it
         out["entry"] = [l.split()[1] for l in r.plan.describe().splitlines() if l.strip().startswith("entry ")][0]
+    host = r.host_inputs
+    del r
+    import torch
+    torch.cuda.empty_cache()
     if with_unfused:
-        host = r.host_inputs
-        del r
         u = Runner(spec, "unfused", host_inputs=host, n_sets=2)
         _, evu = u.time_region(max(10, steps // 4), max(3, warmup // 4))
         secu = evu / max(10, steps // 4)
         out.update({"unfused_us": secu * 1e6, "unfused_kernels": u.info["n_kernels"],
                     "unfused_bytes_model": u.info["bytes_moved_model"], "speedup_vs_unfused": secu / sec})
         del u
-    import torch
-    torch.cuda.empty_cache()
-    out["copy_same_bytes_us"] = copy_same_bytes(out["bytes_min"])
-    out["frac_of_copy_same_bytes"] = out["copy_same_bytes_us"] / out["us"]
+        torch.cuda.empty_cache()
+    if probes:
+        reads, writes = stream_mix(spec)
+        best = min(probe_us(out["bytes_min"], reads, writes, k, steps=max(50, min(300, steps))) for k in (1, 2, 4))
+        torch.cuda.empty_cache()
+        out["probe"] = {"mix": f"{reads}r:{writes}w", "us": best, "GBps": out["bytes_min"] / best / 1e3}
+        out["frac_of_probe"] = best / out["us"]
+        if out["grid"] * out["block"] * 32 < out["bytes_min"]:
+            out["grid_floor_us"] = grid_floor_us(out["grid"] * out["block"] // 256)
+            torch.cuda.empty_cache()
     return out
 
 
@@ -301,12 +344,37 @@ def measure_program(name, steps, warmup):
             "buffer_sets": n_sets}
 
 
+HEADLINE = "C4"
+HEADLINE_TEXT = ("C4 bias + tanh-GELU forward + bias-gradient column sum, x, grad bf16 [16384,3072], bias bf16 [3072] -> "
+                 "y bf16, dbias fp32 [3072], seed 0 (the largest of the five configurations; 2 launches per step)")
+# per_config rows: the five configurations as the evaluator runs them, and the two whose BASELINE text names LDS
+# (C2 "reused via LDS", C5 "LDS-tiled") also with the LDS scheme forced
+PER_CONFIG = (("C1", "C1", "auto"), ("C2", "C2", "auto"), ("C2_lds", "C2", "lds"), ("C3", "C3", "auto"), ("C4", "C4", "auto"),
+              ("C5", "C5", "auto"), ("C5_lds", "C5", "lds"))
+
+
+def _row(m, tag):
+    """The compact per_config row kept inside `roofline`."""
+    row = {"kernel": m["kernel"], "scheme": m["scheme"], "launches": m["n_kernels"], "bytes_min": m["bytes_min"],
+           "us": round(m["us"], 3), "GBps": round(m["GBps"], 1), "frac": round(m["frac_of_peak"], 4),
+           "traffic": _profiled_traffic(tag), "unfused_us": round(m["unfused_us"], 2), "unfused_launches": m["unfused_kernels"],
+           "speedup_vs_unfused": round(m["speedup_vs_unfused"], 2), "launches_timed": m["launches_timed"],
+           "grid": m["grid"], "block": m["block"], "vgprs": m["vgprs"], "lds_bytes": m["lds_bytes"]}
+    if "probe" in m:
+        row.update({"ceiling_mix": m["probe"]["mix"], "ceiling_us": round(m["probe"]["us"], 3),
+                    "ceiling_GBps": round(m["probe"]["GBps"], 1), "frac_of_ceiling": round(m["frac_of_probe"], 4)})
+    if "grid_floor_us" in m:
+        row["grid_floor_us"] = round(m["grid_floor_us"], 3)
+    return row
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=100)
-    ap.add_argument("--no-context", action="store_true", help="skip the other configurations, copy ceiling and oracle timing")
+    ap.add_argument("--no-context", action="store_true", help="headline, per_config and ceilings only: skip the oracle timing and the patterns beyond the five configurations")
+    ap.add_argument("--only", default="", help="comma-separated per_config / context names to measure (for profiling runs), e.g. C4,N2,G11")
     ap.add_argument("--oracle-seconds", type=float, default=10.0)
     args = ap.parse_args()
     if args.gpus != 1:
@@ -317,59 +385,66 @@ def main():
         sys.exit("bench.py: no GPU visible; the hot path has no CPU fallback")
     torch.cuda.set_device(0)
     from workloads import FULL_CONFIGS
+    only = set(x for x in args.only.split(",") if x)
 
-    spec = FULL_CONFIGS["C2"]()
+    def wanted(name):
+        return not only or name in only
+
+    spec = FULL_CONFIGS[HEADLINE]()
     r = Runner(spec, "auto")
     bytes_min = r.info["bytes_min"]
     wall, ev = r.time_region(args.steps, args.warmup)
     sec_step = ev / args.steps
-    # one more pass with an event pair around every launch (upper bound of the kernel's own duration)
+    # one more pass with an event pair around every step (upper bound of the step's own duration)
     avg_pair, med_pair, min_pair = r.per_launch_events(min(args.steps, 200))
     achieved = bytes_min / sec_step / 1e9
 
+    roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                "frac": achieved / HBM_PEAK_GBPS, "traffic": _profiled_traffic(HEADLINE),
+                "traffic_source": f"not measured in this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary {TRAFFIC_PROFILE}",
+                "scope": "whole step = stitched kernel + fold launch; algorithmic bytes / (event time of the timed region / steps)",
+                "algorithmic_bytes_per_step": bytes_min, "us_per_step_region": sec_step * 1e6,
+                "us_per_step_event_pair": {"avg": avg_pair * 1e6, "median": med_pair * 1e6, "min": min_pair * 1e6}}
     result = {
         "metric": "achieved HBM GB/s (% of peak) per fused subgraph; speedup vs unfused per-op",
         "value": achieved, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": sec_step * 1e3, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "C2 residual add + bias + LayerNorm, x,res fp32 [8192,768] -> bf16, eps 1e-5, seed 0",
-                   "pattern": r.info["pattern"], "scheme": r.info["scheme"], "kernel": r.info["kernel"],
-                   "block": r.info["block"], "grid": r.info["grid"], "vgprs": r.info["vgprs"],
+        "config": {"workload": HEADLINE_TEXT, "pattern": r.info["pattern"], "scheme": r.info["scheme"], "kernel": r.info["kernel"],
+                   "launches_per_step": r.info["n_kernels"], "block": r.info["block"], "grid": r.info["grid"], "vgprs": r.info["vgprs"],
                    "buffer_sets": r.n_sets, "cold_hbm_rotation_bytes": r.n_sets * bytes_min},
-        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": _profiled_traffic("C2"),
-                     "algorithmic_bytes_per_launch": bytes_min, "us_per_launch_region": sec_step * 1e6,
-                     "us_per_launch_event_pair": {"avg": avg_pair * 1e6, "median": med_pair * 1e6, "min": min_pair * 1e6}},
+        "roofline": roofline,
         "wall_ms_per_step": wall / args.steps * 1e3,
     }
-    host_c2 = r.host_inputs
+    host_head = r.host_inputs
     del r
     torch.cuda.empty_cache()
 
-    if not args.no_context:
-        u = Runner(spec, "unfused", host_inputs=host_c2, n_sets=3)
-        _, evu = u.time_region(max(20, args.steps // 8), 5)
-        secu = evu / max(20, args.steps // 8)
-        result["unfused"] = {"us": secu * 1e6, "n_kernels": u.info["n_kernels"], "bytes_model": u.info["bytes_moved_model"],
-                             "speedup_stitched": secu / sec_step}
-        del u
+    # ---- all five configurations, inside `roofline` ---------------------------------------------------------------
+    n_cfg = max(200, args.steps)
+    per_config, details = {}, {}
+    for tag, cfg, scheme in PER_CONFIG:
+        if not wanted(tag):
+            continue
+        m = measure_config(tag, FULL_CONFIGS[cfg](), n_cfg, max(10, args.warmup), scheme=scheme)
+        details[tag] = m
+        per_config[tag] = _row(m, tag)
         torch.cuda.empty_cache()
-        result["copy_ceiling_GBps"] = copy_ceiling()
+    roofline["per_config"] = per_config
+    if wanted("ceilings"):
+        # what the memory system gives traffic-only kernels on 1 GiB per stream set (cold by size)
+        gib = 1 << 30
+        roofline["ceilings_GBps"] = {
+            "copy_1r1w": gib / min(probe_us(gib, 1, 1, k, steps=30) for k in (1, 2, 4)) / 1e3,
+            "read_only": gib / min(probe_us(gib, 2, 0, k, steps=30) for k in (1, 2, 4)) / 1e3,
+            "write_only": gib / min(probe_us(gib, 0, 1, k, steps=30) for k in (1, 2, 4)) / 1e3,
+            "mix_2r1w": gib / min(probe_us(gib, 2, 1, k, steps=30) for k in (1, 2, 4)) / 1e3,
+            "mix_4r1w": gib / min(probe_us(gib, 4, 1, k, steps=30) for k in (1, 2, 4)) / 1e3,
+            "library_copy_kernel": copy_ceiling(),
+        }
         torch.cuda.empty_cache()
-        result["copy_same_bytes_us"] = copy_same_bytes(bytes_min)
-        torch.cuda.empty_cache()
-        sec_o, reps = time_oracle(spec, host_c2, args.oracle_seconds)
-        threads = 1
-        result["cpu_baseline"] = {"value": bytes_min / sec_o / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
-                                  "sample": f"full C2 batch [8192,768], {reps} repeats after one warm pass, {sec_o:.3f} s each",
-                                  "seconds_per_subgraph": sec_o, "host_cpus": os.cpu_count(),
-                                  "affinity": len(os.sched_getaffinity(0))}
-        others = {}
-        for name in ("C1", "C3", "C4", "C5"):
-            others[name] = measure_config(name, FULL_CONFIGS[name](), max(50, args.steps // 4), max(10, args.warmup // 2))
-            torch.cuda.empty_cache()
-        # C1 is launch-bound (8 ns of traffic at peak): its floor is one launch of a 16-byte copy; the same
-        # kernel on 2^20 rows shows that the kernel itself streams.
+    if "C1" in per_config:
+        # C1 is launch-bound (8 ns of traffic at peak): its floor is one launch of a 16-byte copy
         tiny_src = torch.zeros(16, dtype=torch.uint8, device="cuda")
         tiny_dst = torch.zeros(16, dtype=torch.uint8, device="cuda")
         from paper_2009_10924_amd import binding as B
@@ -383,33 +458,46 @@ def main():
             tiny()
         e1.record()
         torch.cuda.synchronize()
-        others["C1"]["launch_floor_us"] = e0.elapsed_time(e1) * 1e3 / 2000
+        per_config["C1"]["launch_floor_us"] = round(e0.elapsed_time(e1) * 1e3 / 2000, 3)
+
+    if not args.no_context and not only:
+        sec_o, reps, warmed = time_oracle(spec, host_head, args.oracle_seconds, max_repeats=20)
+        result["cpu_baseline"] = {"value": bytes_min / sec_o / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"full C4 batch [16384,3072] (numpy float64, one op at a time), {reps} pass(es) {'after one warm pass' if warmed else 'timed from cold'}, {sec_o:.3f} s each",
+                                  "seconds_per_subgraph": sec_o, "host_cpus": os.cpu_count(),
+                                  "affinity": len(os.sched_getaffinity(0))}
+    del host_head
+    result["per_config_details"] = details
+
+    if not args.no_context:
         from workloads import softmax_graph
-        others["C1_rows_2pow20"] = measure_config("C1_large", softmax_graph(1 << 20, 128, "f32"), 30, 5, with_unfused=False)
-        torch.cuda.empty_cache()
-        result["other_configs"] = others
+        if wanted("C1_rows_2pow20"):
+            # the same kernel as C1 on 2^20 rows shows that the kernel itself streams
+            result["C1_rows_2pow20"] = measure_config("C1_large", softmax_graph(1 << 20, 128, "f32"), 30, 5, with_unfused=False)
+            torch.cuda.empty_cache()
         from workloads import NEXT_CONFIGS
         # patterns beyond the five configurations: softmax / LayerNorm backward, innermost-axis-moving transposes
         result["next_patterns"] = {name: measure_config(name, NEXT_CONFIGS[name](), max(50, args.steps // 4), 20)
-                                   for name in ("N1", "N2", "N3", "N4", "N5", "N6")}
+                                   for name in ("N1", "N2", "N3", "N4", "N5", "N6") if wanted(name)}
         torch.cuda.empty_cache()
-        result["packing"] = measure_pack("P1", max(200, args.steps // 2), 20)
-        torch.cuda.empty_cache()
+        if wanted("P1"):
+            result["packing"] = measure_pack("P1", max(200, args.steps // 2), 20)
+            torch.cuda.empty_cache()
+        for key, name in (("explorer", "T1"), ("explorer_T2", "T2"), ("explorer_T3", "T3")):
+            if wanted(name):
+                result[key] = measure_program(name, max(100, args.steps // 8), 10)
+                torch.cuda.empty_cache()
         # row-local patterns outside the hand-written families: one generated kernel each
         from workloads import GENERIC_CONFIGS
-        result["explorer"] = measure_program("T1", max(100, args.steps // 8), 10)
-        torch.cuda.empty_cache()
-        result["explorer_T2"] = measure_program("T2", max(100, args.steps // 8), 10)
-        torch.cuda.empty_cache()
-        result["explorer_T3"] = measure_program("T3", max(100, args.steps // 8), 10)
-        torch.cuda.empty_cache()
         from paper_2009_10924_amd import binding as B
         generic = {}
         for name in ("G1", "G2", "G3", "G4", "G5", "G6", "G7", "G8", "G9", "G10", "G11", "G12"):
-            spec = GENERIC_CONFIGS[name]()
-            generic[name] = measure_config(name, spec, max(50, args.steps // 8), 10)   # AUTO: the kernel generated for the pattern
-            with B.codegen(False):                                                      # the interpreted row program beside it
-                r = Runner(spec, "auto")
+            if not wanted(name):
+                continue
+            gspec = GENERIC_CONFIGS[name]()
+            generic[name] = measure_config(name, gspec, max(50, args.steps // 8), 10)   # AUTO: the kernel generated for the pattern
+            with B.codegen(False):                                                       # the interpreted row program beside it
+                r = Runner(gspec, "auto")
             if r.info["pattern"] == "row_program":   # patterns with column sums have no interpreted form
                 _, ev = r.time_region(50, 5)
                 generic[name].update({"interpreted_us": ev / 50 * 1e6, "interpreted_kernel": r.info["kernel"]})

@@ -1,5 +1,6 @@
 """Full-size parity: the five benchmark configurations at their real shapes, in the launch
-configuration the benchmark times (scheme AUTO), against the float64 oracle on the same
+configurations the benchmark times (scheme AUTO; for the two configurations whose description
+names LDS, C2 and C5, also with the LDS scheme forced), against the float64 oracle on the same
 seeded inputs; plus the per-op plan at the same size as a second, independent GPU
 implementation."""
 import numpy as np
@@ -81,17 +82,34 @@ def test_full_size_config(cfg):
             got, _, info, _ = run_spec(spec, inp, scheme, repeat=2)
             if cfg.startswith("G") and scheme == "auto":
                 assert info["pattern"] == "row_generated"
-        for name, dt in spec.outputs:
-            floor = O.rms(ref[name]) if name in RMS_FLOOR.get(cfg, ()) else 0.0
-            err = check(got[name], ref[name], dt, floor, f"{cfg}/{info['kernel']}/{name}")
-            strict = O.max_rel_err(got[name], ref[name], 0.0)
-            over = int(np.sum(np.abs(got[name] - ref[name]) > TOL[dt] * np.abs(ref[name])))
-            note(f"    {cfg} {scheme:7s} {info['kernel']:48s} {name}: max rel err {err:.3e} "
-                 f"(strict {strict:.3e}, {over} of {ref[name].size} elements over the strict bar)")
-        if cfg == "C3":
-            assert ((got["y"] == 0) == (ref["y"] == 0)).all()      # masked keys are exact zeros
-        if cfg == "C5":
-            ss = np.sum(got["out"] ** 2, axis=-1)                   # rows are unit vectors up to eps
-            assert np.max(np.abs(ss - 1.0)) < 1e-4
-        if cfg in ("C1", "C3"):
-            assert np.max(np.abs(np.sum(got["y"], axis=-1) - 1.0)) < (1e-5 if cfg == "C1" else 2e-2)
+        _compare(cfg, spec, got, ref, info, scheme)
+
+
+def _compare(cfg, spec, got, ref, info, scheme):
+    for name, dt in spec.outputs:
+        floor = O.rms(ref[name]) if name in RMS_FLOOR.get(cfg, ()) else 0.0
+        err = check(got[name], ref[name], dt, floor, f"{cfg}/{info['kernel']}/{name}")
+        strict = O.max_rel_err(got[name], ref[name], 0.0)
+        over = int(np.sum(np.abs(got[name] - ref[name]) > TOL[dt] * np.abs(ref[name])))
+        note(f"    {cfg} {scheme:7s} {info['kernel']:48s} {name}: max rel err {err:.3e} "
+             f"(strict {strict:.3e}, {over} of {ref[name].size} elements over the strict bar)")
+    if cfg == "C3":
+        assert ((got["y"] == 0) == (ref["y"] == 0)).all()      # masked keys are exact zeros
+    if cfg == "C5":
+        ss = np.sum(got["out"] ** 2, axis=-1)                   # rows are unit vectors up to eps
+        assert np.max(np.abs(ss - 1.0)) < 1e-4
+    if cfg in ("C1", "C3"):
+        assert np.max(np.abs(np.sum(got["y"], axis=-1) - 1.0)) < (1e-5 if cfg == "C1" else 2e-2)
+
+
+@pytest.mark.parametrize("cfg", ["C2", "C5"])
+def test_full_size_forced_lds_scheme(cfg):
+    """Block composition at full size: the row's reduced values (C2) / the normalised slab (C5) go through LDS.
+    These are the plans the benchmark times beside the evaluator's own choice."""
+    spec = ALL[cfg]()
+    note(f"  full-size {cfg} with the LDS scheme forced: generating inputs")
+    inp = make_inputs(spec, seed=0)
+    ref = O.evaluate(spec, inp)
+    got, _, info, _ = run_spec(spec, inp, "lds", repeat=2)
+    assert info["scheme"] == "lds" and info["lds_bytes"] > 0, info
+    _compare(cfg, spec, got, ref, info, "lds")
