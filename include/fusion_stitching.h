@@ -2,13 +2,16 @@
  * fusion_stitching.h -- C ABI of the MI355X (gfx950) stitched-subgraph library.
  *
  * The library executes one *fusion pattern* -- a subgraph of memory-intensive
- * ops (element-wise, broadcast, reduction, transpose; paper Section 2.1 and
- * Section 5.1, "fusion pattern P_i = (V_i, E_i)") -- either as one stitched GPU
- * kernel in which intermediates stay on chip, or as the per-op baseline of one
- * kernel per op.  The calls mirror the paper's code-generation problem
- * statement (Section 4: a fusion pattern goes in, a kernel with a chosen
- * schedule and launch dimension comes out, Section 4.2), with hand-written
- * kernels selected by pattern matching instead of JIT emission.
+ * ops (element-wise, broadcast, reduction, transpose; the op kinds of paper
+ * Section 1 and Section 3.1; Section 5.1, "fusion pattern P_i = (V_i, E_i)") --
+ * either as one stitched GPU kernel in which intermediates stay on chip, or as
+ * the per-op baseline of one kernel per op.  The calls mirror the paper's
+ * code-generation problem statement (Section 4: a fusion pattern goes in, a
+ * kernel with a chosen schedule and launch dimension comes out, Section 4.2).
+ * The kernel is a hand-written one of a pattern family where a family matches
+ * the pattern, otherwise HIP source generated for the pattern and compiled for
+ * gfx950 when the plan is created (or, without the run-time compiler, a fixed
+ * kernel that interprets the pattern's instruction list).
  *
  * Conventions
  *   - All handles are opaque and owned by the library; destroy with the
@@ -54,7 +57,9 @@ enum fs_error {
                                       (Section 4.2: schedules violating data locality are discarded)   */
   FS_ERR_WORKSPACE = -7,           /* workspace null or smaller than fs_plan_info.workspace_bytes      */
   FS_ERR_ALIGN = -8,               /* a device pointer is not 16-byte aligned                          */
-  FS_ERR_HIP = -9                  /* a HIP call failed; text carries hipGetErrorString                */
+  FS_ERR_HIP = -9,                 /* a HIP call failed; text carries hipGetErrorString                */
+  FS_ERR_HOST = -10                /* the host ran out of memory, or an internal error was caught at the
+                                      boundary (nothing is ever thrown across it)                       */
 };
 
 enum fs_dtype { FS_F32 = 0, FS_F16 = 1, FS_BF16 = 2, FS_I32 = 3 };
@@ -101,11 +106,14 @@ enum fs_scheme {
   FS_SCHEME_WAVE = 3, FS_SCHEME_LDS = 4, FS_SCHEME_GLOBAL = 5
 };
 
-/* Optional constraints on the launch shape; a zero / negative field means "any".
- * The cost model picks the cheapest candidate that satisfies all given fields;
- * if none does, fs_plan_create returns FS_ERR_LOCALITY.                          */
+/* Optional constraints on the launch shape; a zero / negative field means "any", so a
+ * zero-initialised struct asks for nothing.  The cost model picks the cheapest candidate
+ * that satisfies all given fields; if none does, fs_plan_create returns FS_ERR_LOCALITY.
+ * `candidate` overrides the choice: with k > 0 the plan is entry k - 1 of the candidate
+ * list, whatever the model and the other fields say.                                  */
 typedef struct fs_plan_opts {
-  int32_t candidate;      /* >= 0: take exactly this entry of the candidate list; -1: choose   */
+  int32_t candidate;      /* k > 0: take exactly entry k - 1 of the candidate list (the index
+                             fs_plan_info.candidate reports, plus one); <= 0: choose           */
   int32_t block_threads;  /* threads per workgroup                                             */
   int32_t lanes_per_row;  /* lanes that share one reduction row (WAVE) / threads per row (LDS) */
   int32_t vecs_per_lane;  /* 128-bit vectors each lane keeps in registers                      */
@@ -156,11 +164,9 @@ fs_tensor fs_graph_op(fs_graph *g, int32_t opcode, int32_t n_in, const fs_tensor
  * `outputs` follow the order of these calls.  A tensor can be marked once.
  * Errors: FS_ERR_INVALID_ARG, FS_ERR_DTYPE (I32 tensors only store as I32).      */
 fs_status fs_graph_output(fs_graph *g, fs_tensor t, int32_t store_as);
-/* Freezes the graph: at least one output, every op reaches an output.
- * Errors: FS_ERR_INVALID_ARG.                                                    */
 /* Declares that graph input `input` is computed OUTSIDE the graph (by a matrix product,
  * say) from the op result `from`, which must be declared a graph output before
- * fs_graph_finalize.  Section 2.1: compute-intensive ops are not fused; they cut the graph
+ * fs_graph_finalize.  Section 1 / Section 5.1: compute-intensive ops are not fused; they cut the graph
  * of memory-intensive ops, and this call records the cut.  Consequences: no fusion pattern
  * holds both the op that makes `from` and an op that reads `input` (nor ops on a path
  * between two of its members that leads through such a dependence); the steps of an explored
@@ -169,6 +175,8 @@ fs_status fs_graph_output(fs_graph *g, fs_tensor t, int32_t store_as);
  * reads `input`.  A graph with such dependences has no single plan: fs_plan_create returns
  * FS_ERR_UNSUPPORTED_PATTERN; use fs_explore.  Errors: FS_ERR_INVALID_ARG.                */
 fs_status fs_graph_external(fs_graph *g, fs_tensor from, fs_tensor input);
+/* Freezes the graph: at least one output, every op reaches an output.
+ * Errors: FS_ERR_INVALID_ARG.                                                    */
 fs_status fs_graph_finalize(fs_graph *g);
 
 /* ---- plan (Section 4.2: enumerate schedules and launch dimensions, discard
@@ -247,18 +255,16 @@ int64_t fs_plan_source(const fs_plan *p, char *text, size_t capacity);
  * default stream) and returns without waiting.  inputs[i] / outputs[j] are
  * DEVICE pointers in declaration order, each 16-byte aligned and sized for its
  * tensor; inputs are never written.  `workspace` is DEVICE scratch of at least
- * fs_plan_info.workspace_bytes (may be null when that is 0); the library leaves
- * it reusable for the next call of the same plan on the same stream (its
- * arrival counters are reset by the kernel that used them) but its first use
- * must see zeros in the first 256 bytes * (number of counters); the simplest
- * rule: zero-fill it once after allocating.  Allocates nothing, never
+ * fs_plan_info.workspace_bytes (may be null when that is 0); its contents on entry
+ * do not matter (every kernel that reads it reads what an earlier kernel of the same
+ * call wrote) and it is reusable afterwards.  Allocates nothing, never
  * synchronizes.  Two calls that share a workspace must be ordered on one stream.
  * Errors: FS_ERR_INVALID_ARG, FS_ERR_WORKSPACE, FS_ERR_ALIGN, FS_ERR_HIP.         */
 fs_status fs_execute(const fs_plan *p, const void *const *inputs, void *const *outputs,
                      void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* ---- packed execution (Section 4.1, kernel packing: ops with no data dependence
- *      share one kernel to cut launches; Section 5.3, remote fusion: patterns that
+ *      share one kernel to cut launches; Section 5.2, remote fusion: patterns that
  *      are not adjacent in the graph may still be packed) -------------------------- */
 
 #define FS_PACK_MAX_MEMBERS 256  /* members of one pack; every 32 of them share one launch */
@@ -377,9 +383,9 @@ fs_status fs_program_pattern(const fs_program *p, int32_t index, int32_t *ops, i
 int64_t fs_program_describe(const fs_program *p, char *text, size_t capacity);
 /* Enqueues the whole program on `hip_stream` and returns without waiting.  inputs /
  * outputs: DEVICE pointers in the graph's declaration order, 16-byte aligned.  `workspace`:
- * DEVICE scratch of at least fs_program_info.workspace_bytes, 256-byte aligned, zero-filled
- * once after allocation (it holds the tensors that cross from one pattern to the next and
- * the patterns' own scratch); calls that share it must be ordered on one stream.
+ * DEVICE scratch of at least fs_program_info.workspace_bytes, 256-byte aligned (it holds the
+ * tensors that cross from one pattern to the next and the patterns' own scratch; its contents
+ * on entry do not matter); calls that share it must be ordered on one stream.
  * Allocates nothing, never synchronizes.
  * Errors: FS_ERR_INVALID_ARG, FS_ERR_WORKSPACE, FS_ERR_ALIGN, FS_ERR_HIP.               */
 fs_status fs_program_execute(const fs_program *p, const void *const *inputs, void *const *outputs, void *workspace,
@@ -399,8 +405,23 @@ fs_status fs_program_execute_stage(const fs_program *p, int32_t stage, const voi
 
 /* Plain streaming copy of `bytes` (multiple of 16) from src to dst, both DEVICE
  * and 16-byte aligned: the measured HBM ceiling every result is reported beside
- * (Section 2.3 names off-chip traffic as the dominant cost).                     */
+ * (Section 2.2 names off-chip traffic as the dominant cost).                     */
 fs_status fs_stream_copy(void *dst, const void *src, size_t bytes, void *hip_stream);
+
+/* Streaming probe: a kernel that only moves data, with a chosen mix of streams, in the
+ * one-shot shape of the stitched row kernels.  Every lane reads `vecs_per_lane` (1, 2 or 4)
+ * 128-bit vectors from each of `reads` (0..4) input streams and writes as many to each of
+ * `writes` (0..2, not both 0) output streams; all loads are issued before the first store.
+ * `src`: DEVICE, reads * stream_bytes (may be null when reads is 0); `dst`: DEVICE,
+ * writes * stream_bytes, at least 16 bytes (a read-only probe stores nothing there unless
+ * the input holds one particular bit pattern, which keeps its loads alive); stream_bytes a
+ * multiple of 16, below 2^35; pointers 16-byte aligned.  What it writes is a function of the
+ * inputs and the element index, of no further meaning.  Its time is the bound a stitched
+ * kernel with the same bytes and the same read : write mix is reported beside (Section
+ * 2.2); with a small stream_bytes it gives the fixed cost of a launch of that many
+ * workgroups.  Errors: FS_ERR_INVALID_ARG, FS_ERR_ALIGN, FS_ERR_SHAPE, FS_ERR_HIP.      */
+fs_status fs_stream_probe(void *dst, const void *src, size_t stream_bytes, int32_t reads, int32_t writes,
+                          int32_t vecs_per_lane, void *hip_stream);
 
 /* Text of the calling thread's most recent error ("" if none); valid until the
  * thread's next library call.                                                    */

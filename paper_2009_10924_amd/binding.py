@@ -24,12 +24,12 @@ SCHEME = {"auto": 0, "unfused": 1, "local": 2, "wave": 3, "lds": 4, "global": 5}
 SCHEME_NAME = {v: k for k, v in SCHEME.items()}
 ERROR_NAME = {0: "FS_OK", -1: "FS_ERR_INVALID_ARG", -2: "FS_ERR_SHAPE", -3: "FS_ERR_DTYPE", -4: "FS_ERR_CYCLE",
               -5: "FS_ERR_UNSUPPORTED_PATTERN", -6: "FS_ERR_LOCALITY", -7: "FS_ERR_WORKSPACE",
-              -8: "FS_ERR_ALIGN", -9: "FS_ERR_HIP"}
+              -8: "FS_ERR_ALIGN", -9: "FS_ERR_HIP", -10: "FS_ERR_HOST"}
 
 EXPORTS = [
     "fs_graph_create", "fs_graph_destroy", "fs_graph_input", "fs_graph_op", "fs_graph_output",
     "fs_graph_finalize", "fs_plan_create", "fs_plan_destroy", "fs_plan_query", "fs_plan_candidate", "fs_plan_describe",
-    "fs_plan_source", "fs_codegen_enable", "fs_codegen_available", "fs_execute", "fs_stream_copy", "fs_last_error", "fs_version",
+    "fs_plan_source", "fs_codegen_enable", "fs_codegen_available", "fs_execute", "fs_stream_copy", "fs_stream_probe", "fs_last_error", "fs_version",
     "fs_pack_create", "fs_pack_destroy", "fs_pack_query", "fs_pack_execute",
     "fs_explore", "fs_explore_score", "fs_program_destroy", "fs_program_query", "fs_program_pattern", "fs_program_execute",
     "fs_program_describe", "fs_program_execute_stage", "fs_graph_external",
@@ -179,6 +179,8 @@ def load() -> C.CDLL:
     lib.fs_execute.restype = i32
     lib.fs_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
     lib.fs_stream_copy.restype = i32
+    lib.fs_stream_probe.argtypes = [vp, vp, C.c_size_t, i32, i32, i32, vp]
+    lib.fs_stream_probe.restype = i32
     lib.fs_explore.argtypes = [vp, C.POINTER(fs_explore_opts), C.POINTER(vp)]
     lib.fs_explore.restype = i32
     lib.fs_explore_score.argtypes = [vp, C.POINTER(i32), i32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -288,7 +290,8 @@ class Plan:
                  lanes_per_row: int = 0, vecs_per_lane: int = 0):
         self._lib = load()
         self._graph = graph
-        opts = fs_plan_opts(candidate, block_threads, lanes_per_row, vecs_per_lane)
+        # `candidate` here is the 0-based index fs_plan_info reports (-1: choose); the C struct counts from 1 (0: choose)
+        opts = fs_plan_opts(candidate + 1 if candidate >= 0 else 0, block_threads, lanes_per_row, vecs_per_lane)
         h = C.c_void_p()
         _check(self._lib.fs_plan_create(graph.handle, SCHEME[scheme], C.byref(opts), C.byref(h)))
         self.handle = h
@@ -522,6 +525,18 @@ def bind_copy(dst_ptr: int, src_ptr: int, nbytes: int, stream: int):
 
     def call():
         code = fn(d, s_, n, st)
+        if code < 0:
+            _check(code)
+    return call
+
+
+def bind_probe(dst_ptr: int, src_ptr: int, stream_bytes: int, reads: int, writes: int, vecs_per_lane: int, stream: int):
+    """Pre-marshalled fs_stream_probe call."""
+    fn = load().fs_stream_probe
+    d, s_, n, st = C.c_void_p(dst_ptr), C.c_void_p(src_ptr), C.c_size_t(stream_bytes), C.c_void_p(stream)
+
+    def call():
+        code = fn(d, s_, n, reads, writes, vecs_per_lane, st)
         if code < 0:
             _check(code)
     return call

@@ -6,7 +6,7 @@
 //   * patterns with a cyclic dependence or that the code generator cannot process are discarded
 //     (Section 5.2) -- "can process" here means: a hand-written kernel family matches it or it
 //     compiles to a row program (a generated kernel, or the interpreter).  Computations outside the
-//     graph that the graph names (Section 2.1: compute-intensive ops are not fused) order execution
+//     graph that the graph names (Section 1: compute-intensive ops go to libraries and are not fused) order execution
 //     like edges and are never inside a pattern;
 //   * score f = T_reduced_mem + T_reduced_calls - T_penalty (Section 5.4, Eq. 3), with constants
 //     measured on MI355X (launch cost, streaming rate) and the penalty from the kernel estimate
@@ -858,7 +858,7 @@ void fill_info(const Explorer& ex, fs_program* prog, int32_t beam_plans, double 
 
 extern "C" {
 
-fs_status fs_explore_score(const fs_graph* g, const int32_t* ops, int32_t n, double* f_us, double* f_optimistic_us) {
+fs_status fs_explore_score(const fs_graph* g, const int32_t* ops, int32_t n, double* f_us, double* f_optimistic_us) try {
   clear_error();
   if (!g || !ops || !f_us) return fail(FS_ERR_INVALID_ARG, "fs_explore_score: null argument");
   if (!g->finalized) return fail(FS_ERR_INVALID_ARG, "fs_explore_score: graph is not finalized");
@@ -878,9 +878,11 @@ fs_status fs_explore_score(const fs_graph* g, const int32_t* ops, int32_t n, dou
   }
   *f_us = s.f;
   return FS_OK;
+} catch (...) {
+  return fs::fail_caught("fs_explore_score");
 }
 
-fs_status fs_explore(const fs_graph* g, const fs_explore_opts* opts, fs_program** out) {
+fs_status fs_explore(const fs_graph* g, const fs_explore_opts* opts, fs_program** out) try {
   clear_error();
   if (!g || !out) return fail(FS_ERR_INVALID_ARG, "fs_explore: null argument");
   if (!g->finalized) return fail(FS_ERR_INVALID_ARG, "fs_explore: graph is not finalized");
@@ -953,6 +955,8 @@ fs_status fs_explore(const fs_graph* g, const fs_explore_opts* opts, fs_program*
   prog->n_outputs = (int32_t)g->outputs.size();
   *out = prog;
   return FS_OK;
+} catch (...) {
+  return fs::fail_caught("fs_explore");
 }
 
 }  // extern "C"

@@ -96,9 +96,8 @@ bool build_gelu(const fs_graph& g, std::vector<Candidate>* out, PackForm* pack) 
   if (!is_input(g, tg) || !same_dims(g.tensors[tg], x) || g.tensors[tg].dtype != p.dt || d.store_as != FS_F32) return true;
   const uint32_t tile_cols = 64 * VEC;
   const uint32_t n_col_tiles = (p.cols + tile_cols - 1) / tile_cols;
-  const int64_t counter_bytes = ((int64_t)n_col_tiles * 4 + 255) / 256 * 256;
   struct Shape { int waves, unroll; };
-  for (int ticket = 0; ticket < 2; ++ticket) {
+  {
     for (Shape sh : {Shape{4, 2}, Shape{4, 4}, Shape{8, 2}, Shape{8, 4}}) {
       const uint32_t tile_rows = sh.waves * sh.unroll;
       const uint32_t max_rb = (p.rows + tile_rows - 1) / tile_rows;
@@ -113,7 +112,6 @@ bool build_gelu(const fs_graph& g, std::vector<Candidate>* out, PackForm* pack) 
         q.n_row_tiles = n_rb;
         q.waves = sh.waves;
         q.unroll = sh.unroll;
-        q.ticket = ticket;
         {
           Launch& l = c.launches.front();
           l.args.u.gelu = q;
@@ -121,21 +119,20 @@ bool build_gelu(const fs_graph& g, std::vector<Candidate>* out, PackForm* pack) 
           l.ptr[1] = in_ref(g, tb);
           l.ptr[2] = in_ref(g, tg);
           l.ptr[3] = out_ref(y.output_slot);
-          l.ptr[4] = out_ref(d.output_slot);
-          l.ptr[5] = ws_ref(counter_bytes);
-          l.ptr[6] = ws_ref(0);
+          l.ptr[4] = ws_ref(0);
           l.shape.block[0] = sh.waves * 64;
           l.shape.grid[0] = n_rb * n_col_tiles;
         }
-        if (!ticket) {
+        {
+          // the global hand-off: a second launch folds the row blocks' partial sums
           c.launches.emplace_back();
           Launch& f = c.launches.back();
           make_fold_launch(&f, n_rb, p.cols, p.cols);
-          f.ptr[0] = ws_ref(counter_bytes);
+          f.ptr[0] = ws_ref(0);
           f.ptr[1] = out_ref(d.output_slot);
           c.info.n_kernels = 2;
         }
-        c.info.workspace_bytes = counter_bytes + (int64_t)n_rb * p.cols * 4;
+        c.info.workspace_bytes = (int64_t)n_rb * p.cols * 4;
         c.info.rows_per_block = (int32_t)tile_rows;
         c.info.vecs_per_lane = sh.unroll;
         c.info.lanes_per_row = 64;
@@ -150,20 +147,14 @@ bool build_gelu(const fs_graph& g, std::vector<Candidate>* out, PackForm* pack) 
         kc.waves = (double)n_rb * n_col_tiles * sh.waves;
         kc.bytes_in_flight_per_lane = 32.0 * sh.unroll;
         kc.vgpr_estimate = 40 + 16 * sh.unroll;
-        kc.barriers = ticket ? 5 : 1;
+        kc.barriers = 1;
         kc.lds_bytes_per_block = c.info.lds_bytes;
         kc.rows_per_wave_loop = std::max(1.0, (double)p.rows / ((double)n_rb * tile_rows));
         kc.dep_phases = 0;   // software pipelined: only the first tile's load latency is exposed (added below)
-        // the fold: a second launch spread over the chip, or one workgroup per column tile
-        // reading n_rb partial rows with (threads / column quads) row groups in parallel
-        if (ticket) {
-          const double groups = std::max(1.0, sh.waves * 64.0 / (tile_cols / 4.0));
-          kc.serial_tail_s = device().mem_latency_s * (3.0 + std::ceil(n_rb / groups / 8.0));
-        } else {
-          kc.serial_tail_s = device().mem_latency_s + 0.5 * device().launch_s + device().mem_latency_s * std::ceil(n_rb / 16.0 / 8.0) * 0.5;
-        }
+        // the fold: a second launch spread over the chip
+        kc.serial_tail_s = device().mem_latency_s + 0.5 * device().launch_s + device().mem_latency_s * std::ceil(n_rb / 16.0 / 8.0) * 0.5;
         char var[48];
-        snprintf(var, sizeof var, "<%s,W%d,U%d,RB%u,%s>", dtype_name(p.dt), sh.waves, sh.unroll, n_rb, ticket ? "ticket" : "fold");
+        snprintf(var, sizeof var, "<%s,W%d,U%d,RB%u,fold>", dtype_name(p.dt), sh.waves, sh.unroll, n_rb);
         finish_candidate(&c, var, kc);
         out->push_back(c);
       }

@@ -5,23 +5,37 @@
 #include <cstring>
 
 #include <algorithm>
+#include <exception>
+#include <new>
 
 #include "fs_internal.hpp"
 
 namespace fs {
 
-static thread_local std::string g_error;
+// fixed storage: reporting an error must not itself need host memory
+static thread_local char g_error[1024];
 
 fs_status fail(fs_status code, const char* fmt, ...) {
-  char buf[512];
   va_list ap;
   va_start(ap, fmt);
-  vsnprintf(buf, sizeof buf, fmt, ap);
+  vsnprintf(g_error, sizeof g_error, fmt, ap);
   va_end(ap);
-  g_error = buf;
   return code;
 }
-void clear_error() { g_error.clear(); }
+void clear_error() { g_error[0] = 0; }
+
+// Called from the catch (...) of every C-ABI function: nothing may be thrown across the boundary.
+fs_status fail_caught(const char* who) {
+  try {
+    throw;
+  } catch (const std::bad_alloc&) {
+    return fail(FS_ERR_HOST, "%s: out of host memory", who);
+  } catch (const std::exception& e) {
+    return fail(FS_ERR_HOST, "%s: internal error: %s", who, e.what());
+  } catch (...) {
+    return fail(FS_ERR_HOST, "%s: internal error", who);
+  }
+}
 
 int dtype_bytes(int32_t dt) { return (dt == FS_F32 || dt == FS_I32) ? 4 : 2; }
 const char* dtype_name(int32_t dt) {
@@ -56,20 +70,22 @@ using namespace fs;
 
 extern "C" {
 
-const char* fs_last_error(void) { return g_error.c_str(); }
+const char* fs_last_error(void) { return g_error; }
 const char* fs_version(void) { return "fusion-stitching-gfx950 0.1"; }
 
-fs_status fs_graph_create(fs_graph** out) {
+fs_status fs_graph_create(fs_graph** out) try {
   clear_error();
   if (!out) return fail(FS_ERR_INVALID_ARG, "fs_graph_create: out is null");
   *out = new (std::nothrow) fs_graph();
   if (!*out) return fail(FS_ERR_INVALID_ARG, "fs_graph_create: out of host memory");
   return FS_OK;
+} catch (...) {
+  return fs::fail_caught("fs_graph_create");
 }
 
 void fs_graph_destroy(fs_graph* g) { delete g; }
 
-fs_tensor fs_graph_input(fs_graph* g, int32_t dtype, int32_t rank, const int64_t* dims) {
+fs_tensor fs_graph_input(fs_graph* g, int32_t dtype, int32_t rank, const int64_t* dims) try {
   clear_error();
   if (!g || !dims) return fail(FS_ERR_INVALID_ARG, "fs_graph_input: null argument");
   if (g->finalized) return fail(FS_ERR_INVALID_ARG, "fs_graph_input: graph is finalized");
@@ -89,9 +105,11 @@ fs_tensor fs_graph_input(fs_graph* g, int32_t dtype, int32_t rank, const int64_t
   g->tensors.push_back(t);
   g->inputs.push_back((int32_t)g->tensors.size() - 1);
   return (fs_tensor)g->tensors.size() - 1;
+} catch (...) {
+  return fs::fail_caught("fs_graph_input");
 }
 
-fs_tensor fs_graph_op(fs_graph* g, int32_t opcode, int32_t n_in, const fs_tensor* in, const void* attr, size_t attr_bytes) {
+fs_tensor fs_graph_op(fs_graph* g, int32_t opcode, int32_t n_in, const fs_tensor* in, const void* attr, size_t attr_bytes) try {
   clear_error();
   if (!g || !in) return fail(FS_ERR_INVALID_ARG, "fs_graph_op: null argument");
   if (g->finalized) return fail(FS_ERR_INVALID_ARG, "fs_graph_op: graph is finalized");
@@ -185,9 +203,11 @@ fs_tensor fs_graph_op(fs_graph* g, int32_t opcode, int32_t n_in, const fs_tensor
   g->tensors.push_back(r);
   g->ops.push_back(op);
   return next_id;
+} catch (...) {
+  return fs::fail_caught("fs_graph_op");
 }
 
-fs_status fs_graph_output(fs_graph* g, fs_tensor t, int32_t store_as) {
+fs_status fs_graph_output(fs_graph* g, fs_tensor t, int32_t store_as) try {
   clear_error();
   if (!g) return fail(FS_ERR_INVALID_ARG, "fs_graph_output: graph is null");
   if (g->finalized) return fail(FS_ERR_INVALID_ARG, "fs_graph_output: graph is finalized");
@@ -204,9 +224,11 @@ fs_status fs_graph_output(fs_graph* g, fs_tensor t, int32_t store_as) {
   x.store_as = store_as;
   g->outputs.push_back(t);
   return FS_OK;
+} catch (...) {
+  return fs::fail_caught("fs_graph_output");
 }
 
-fs_status fs_graph_external(fs_graph* g, fs_tensor from, fs_tensor input) {
+fs_status fs_graph_external(fs_graph* g, fs_tensor from, fs_tensor input) try {
   clear_error();
   if (!g) return fail(FS_ERR_INVALID_ARG, "fs_graph_external: graph is null");
   if (g->finalized) return fail(FS_ERR_INVALID_ARG, "fs_graph_external: graph is finalized");
@@ -219,9 +241,11 @@ fs_status fs_graph_external(fs_graph* g, fs_tensor from, fs_tensor input) {
     return fail(FS_ERR_INVALID_ARG, "fs_graph_external: input %d is already read by an op; declare the dependence first", input);
   g->external.emplace_back(from, input);
   return FS_OK;
+} catch (...) {
+  return fs::fail_caught("fs_graph_external");
 }
 
-fs_status fs_graph_finalize(fs_graph* g) {
+fs_status fs_graph_finalize(fs_graph* g) try {
   clear_error();
   if (!g) return fail(FS_ERR_INVALID_ARG, "fs_graph_finalize: graph is null");
   if (g->finalized) return FS_OK;
@@ -237,6 +261,8 @@ fs_status fs_graph_finalize(fs_graph* g) {
   }
   g->finalized = true;
   return FS_OK;
+} catch (...) {
+  return fs::fail_caught("fs_graph_finalize");
 }
 
 }  // extern "C"

@@ -47,6 +47,8 @@ const char* scheme_name(int32_t s);
 // status + thread-local message
 fs_status fail(fs_status code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 void clear_error();
+// the current exception (call inside a catch block) turned into FS_ERR_HOST with a message
+fs_status fail_caught(const char* who);
 
 }  // namespace fs
 
@@ -178,6 +180,8 @@ fs_status create_plan(const fs_graph* g, int32_t scheme, const fs_plan_opts* opt
 // The first `n_launches` launches of the plan's chosen candidate (arguments already validated by the caller).
 fs_status run_launches(const fs_plan* p, const void* const* inputs, void* const* outputs, void* workspace, void* hip_stream,
                        size_t n_launches);
+// The checks every execute entry point makes on its pointer arrays (null, alignment); `who` names the caller in the message.
+fs_status check_execute_args(const fs_plan* p, const void* const* inputs, void* const* outputs, const char* who);
 // How many kernel launches that makes (folds of column partial sums that follow each other go out as one).
 size_t launches_issued(const fs_plan* p, size_t n_launches);
 fs_status complete_plan(fs_plan* p);

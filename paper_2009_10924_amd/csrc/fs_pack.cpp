@@ -118,7 +118,7 @@ using namespace fs;
 
 extern "C" {
 
-fs_status fs_pack_create(const fs_plan* const* plans, int32_t n, fs_pack** out) {
+fs_status fs_pack_create(const fs_plan* const* plans, int32_t n, fs_pack** out) try {
   clear_error();
   if (!plans || !out) return fail(FS_ERR_INVALID_ARG, "fs_pack_create: null argument");
   if (n < 1 || n > FS_PACK_MAX_MEMBERS) return fail(FS_ERR_INVALID_ARG, "fs_pack_create: %d members, 1..%d allowed", n, FS_PACK_MAX_MEMBERS);
@@ -217,18 +217,22 @@ fs_status fs_pack_create(const fs_plan* const* plans, int32_t n, fs_pack** out) 
   pk->info.vgprs = r.from_device ? r.vgprs : 0;
   *out = pk;
   return FS_OK;
+} catch (...) {
+  return fs::fail_caught("fs_pack_create");
 }
 
 void fs_pack_destroy(fs_pack* p) { delete p; }
 
-fs_status fs_pack_query(const fs_pack* p, fs_pack_info* out) {
+fs_status fs_pack_query(const fs_pack* p, fs_pack_info* out) try {
   clear_error();
   if (!p || !out) return fail(FS_ERR_INVALID_ARG, "fs_pack_query: null argument");
   *out = p->info;
   return FS_OK;
+} catch (...) {
+  return fs::fail_caught("fs_pack_query");
 }
 
-fs_status fs_pack_execute(const fs_pack* p, const void* const* inputs, void* const* outputs, void* hip_stream) {
+fs_status fs_pack_execute(const fs_pack* p, const void* const* inputs, void* const* outputs, void* hip_stream) try {
   clear_error();
   if (!p || !inputs || !outputs) return fail(FS_ERR_INVALID_ARG, "fs_pack_execute: null argument");
   for (int i = 0; i < p->n_inputs; ++i) {
@@ -264,6 +268,8 @@ fs_status fs_pack_execute(const fs_pack* p, const void* const* inputs, void* con
     if (err != 0) return fail(FS_ERR_HIP, "fs_pack_execute: launching the packed kernel failed: %s", hip_error_text(err));
   }
   return FS_OK;
+} catch (...) {
+  return fs::fail_caught("fs_pack_execute");
 }
 
 }  // extern "C"

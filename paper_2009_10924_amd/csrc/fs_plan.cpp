@@ -210,6 +210,19 @@ fs_status fs::run_launches(const fs_plan* p, const void* const* inputs, void* co
   return FS_OK;
 }
 
+fs_status fs::check_execute_args(const fs_plan* p, const void* const* inputs, void* const* outputs, const char* who) {
+  if (!p || !inputs || !outputs) return fail(FS_ERR_INVALID_ARG, "%s: null argument", who);
+  for (int i = 0; i < p->n_inputs; ++i) {
+    if (!inputs[i]) return fail(FS_ERR_INVALID_ARG, "%s: input %d is null", who, i);
+    if ((uintptr_t)inputs[i] & 15u) return fail(FS_ERR_ALIGN, "%s: input %d is not 16-byte aligned", who, i);
+  }
+  for (int i = 0; i < p->n_outputs; ++i) {
+    if (!outputs[i]) return fail(FS_ERR_INVALID_ARG, "%s: output %d is null", who, i);
+    if ((uintptr_t)outputs[i] & 15u) return fail(FS_ERR_ALIGN, "%s: output %d is not 16-byte aligned", who, i);
+  }
+  return FS_OK;
+}
+
 fs_status fs::create_plan(const fs_graph* g, int32_t scheme, const fs_plan_opts* opts, bool complete, fs_plan** out) {
   if (!g || !out) return fail(FS_ERR_INVALID_ARG, "fs_plan_create: null argument");
   if (!g->finalized) return fail(FS_ERR_INVALID_ARG, "fs_plan_create: graph is not finalized");
@@ -217,7 +230,11 @@ fs_status fs::create_plan(const fs_graph* g, int32_t scheme, const fs_plan_opts*
     return fail(FS_ERR_UNSUPPORTED_PATTERN, "fs_plan_create: the graph waits for external computations between its ops; no single plan runs it (use fs_explore)");
   if (scheme < FS_SCHEME_AUTO || scheme > FS_SCHEME_GLOBAL) return fail(FS_ERR_INVALID_ARG, "fs_plan_create: bad scheme %d", scheme);
   fs_plan_opts o = {-1, 0, 0, 0};
-  if (opts) o = *opts;
+  if (opts) {
+    o = *opts;
+    // the public field counts from 1 (0 = choose, so a zero-initialised struct asks for nothing); inside, -1 = choose
+    o.candidate = opts->candidate > 0 ? opts->candidate - 1 : -1;
+  }
 
   std::vector<Candidate> all;
   std::string pattern;
@@ -288,6 +305,7 @@ fs_status fs::create_plan(const fs_graph* g, int32_t scheme, const fs_plan_opts*
       // did not compile, the per-op plan is what remains
       if (scheme == FS_SCHEME_AUTO && o.candidate < 0 && s == FS_ERR_UNSUPPORTED_PATTERN) {
         fs_plan_opts plain = o;
+        plain.candidate = 0;
         return create_plan(g, FS_SCHEME_UNFUSED, &plain, true, out);
       }
       return s;
@@ -299,38 +317,46 @@ fs_status fs::create_plan(const fs_graph* g, int32_t scheme, const fs_plan_opts*
 
 extern "C" {
 
-fs_status fs_plan_create(const fs_graph* g, int32_t scheme, const fs_plan_opts* opts, fs_plan** out) {
+fs_status fs_plan_create(const fs_graph* g, int32_t scheme, const fs_plan_opts* opts, fs_plan** out) try {
   clear_error();
   return create_plan(g, scheme, opts, true, out);
+} catch (...) {
+  return fs::fail_caught("fs_plan_create");
 }
 
-int32_t fs_codegen_enable(int32_t on) {
+int32_t fs_codegen_enable(int32_t on) try {
   const int32_t before = codegen_enabled() ? 1 : 0;
   g_codegen.store(on ? 1 : 0, std::memory_order_relaxed);
   return before;
+} catch (...) {
+  return fs::fail_caught("fs_codegen_enable");
 }
 
 int32_t fs_codegen_available(void) { return gen_available() ? 1 : 0; }
 
 void fs_plan_destroy(fs_plan* p) { delete p; }
 
-fs_status fs_plan_query(const fs_plan* p, fs_plan_info* out) {
+fs_status fs_plan_query(const fs_plan* p, fs_plan_info* out) try {
   clear_error();
   if (!p || !out) return fail(FS_ERR_INVALID_ARG, "fs_plan_query: null argument");
   *out = p->candidates[p->chosen].info;
   return FS_OK;
+} catch (...) {
+  return fs::fail_caught("fs_plan_query");
 }
 
-fs_status fs_plan_candidate(const fs_plan* p, int32_t index, fs_plan_info* out) {
+fs_status fs_plan_candidate(const fs_plan* p, int32_t index, fs_plan_info* out) try {
   clear_error();
   if (!p || !out) return fail(FS_ERR_INVALID_ARG, "fs_plan_candidate: null argument");
   if (index < 0 || index >= (int32_t)p->candidates.size())
     return fail(FS_ERR_INVALID_ARG, "fs_plan_candidate: index %d outside 0..%zu", index, p->candidates.size() - 1);
   *out = p->candidates[index].info;
   return FS_OK;
+} catch (...) {
+  return fs::fail_caught("fs_plan_candidate");
 }
 
-int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) {
+int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) try {
   clear_error();
   if (!p || (!text && capacity > 0)) return fail(FS_ERR_INVALID_ARG, "fs_plan_describe: null argument");
   const Candidate& c = p->candidates[p->chosen];
@@ -400,9 +426,11 @@ int64_t fs_plan_describe(const fs_plan* p, char* text, size_t capacity) {
     text[n] = 0;
   }
   return (int64_t)s.size() + 1;
+} catch (...) {
+  return fs::fail_caught("fs_plan_describe");
 }
 
-int64_t fs_plan_source(const fs_plan* p, char* text, size_t capacity) {
+int64_t fs_plan_source(const fs_plan* p, char* text, size_t capacity) try {
   clear_error();
   if (!p || (!text && capacity > 0)) return fail(FS_ERR_INVALID_ARG, "fs_plan_source: null argument");
   std::string s;
@@ -414,30 +442,27 @@ int64_t fs_plan_source(const fs_plan* p, char* text, size_t capacity) {
     text[n] = 0;
   }
   return (int64_t)s.size() + 1;
+} catch (...) {
+  return fs::fail_caught("fs_plan_source");
 }
 
 fs_status fs_execute(const fs_plan* p, const void* const* inputs, void* const* outputs, void* workspace,
-                     size_t workspace_bytes, void* hip_stream) {
+                     size_t workspace_bytes, void* hip_stream) try {
   clear_error();
-  if (!p || !inputs || !outputs) return fail(FS_ERR_INVALID_ARG, "fs_execute: null argument");
+  const fs_status s = check_execute_args(p, inputs, outputs, "fs_execute");
+  if (s != FS_OK) return s;
   const Candidate& c = p->candidates[p->chosen];
-  for (int i = 0; i < p->n_inputs; ++i) {
-    if (!inputs[i]) return fail(FS_ERR_INVALID_ARG, "fs_execute: input %d is null", i);
-    if ((uintptr_t)inputs[i] & 15u) return fail(FS_ERR_ALIGN, "fs_execute: input %d is not 16-byte aligned", i);
-  }
-  for (int i = 0; i < p->n_outputs; ++i) {
-    if (!outputs[i]) return fail(FS_ERR_INVALID_ARG, "fs_execute: output %d is null", i);
-    if ((uintptr_t)outputs[i] & 15u) return fail(FS_ERR_ALIGN, "fs_execute: output %d is not 16-byte aligned", i);
-  }
   if (c.info.workspace_bytes > 0) {
     if (!workspace || workspace_bytes < (size_t)c.info.workspace_bytes)
       return fail(FS_ERR_WORKSPACE, "fs_execute: workspace of %lld bytes needed, %zu given", (long long)c.info.workspace_bytes, workspace_bytes);
     if ((uintptr_t)workspace & 15u) return fail(FS_ERR_ALIGN, "fs_execute: workspace is not 16-byte aligned");
   }
   return run_launches(p, inputs, outputs, workspace, hip_stream, c.launches.size());
+} catch (...) {
+  return fs::fail_caught("fs_execute");
 }
 
-fs_status fs_stream_copy(void* dst, const void* src, size_t bytes, void* hip_stream) {
+fs_status fs_stream_copy(void* dst, const void* src, size_t bytes, void* hip_stream) try {
   clear_error();
   if (!dst || !src) return fail(FS_ERR_INVALID_ARG, "fs_stream_copy: null pointer");
   if (((uintptr_t)dst | (uintptr_t)src | bytes) & 15u) return fail(FS_ERR_ALIGN, "fs_stream_copy: pointers and size must be multiples of 16");
@@ -454,6 +479,8 @@ fs_status fs_stream_copy(void* dst, const void* src, size_t bytes, void* hip_str
   const int err = launch_kernel(K_COPY, a, s, hip_stream);
   if (err != 0) return fail(FS_ERR_HIP, "fs_stream_copy: %s", hip_error_text(err));
   return FS_OK;
+} catch (...) {
+  return fs::fail_caught("fs_stream_copy");
 }
 
 }  // extern "C"

@@ -12,15 +12,17 @@ fs_status fs_pack_execute(const fs_pack* p, const void* const* inputs, void* con
 
 void fs_program_destroy(fs_program* p) { delete p; }
 
-fs_status fs_program_query(const fs_program* p, fs_program_info* out) {
+fs_status fs_program_query(const fs_program* p, fs_program_info* out) try {
   clear_error();
   if (!p || !out) return fail(FS_ERR_INVALID_ARG, "fs_program_query: null argument");
   *out = p->info;
   return FS_OK;
+} catch (...) {
+  return fs::fail_caught("fs_program_query");
 }
 
 fs_status fs_program_pattern(const fs_program* p, int32_t index, int32_t* ops, int32_t capacity, int32_t* n_ops, double* f_us,
-                             int32_t* pack, fs_plan_info* info) {
+                             int32_t* pack, fs_plan_info* info) try {
   clear_error();
   if (!p) return fail(FS_ERR_INVALID_ARG, "fs_program_pattern: null argument");
   if (index < 0 || index >= (int32_t)p->steps.size())
@@ -33,9 +35,11 @@ fs_status fs_program_pattern(const fs_program* p, int32_t index, int32_t* ops, i
   if (pack) *pack = s.pack;
   if (info) *info = s.plan->candidates[s.plan->chosen].info;
   return FS_OK;
+} catch (...) {
+  return fs::fail_caught("fs_program_pattern");
 }
 
-int64_t fs_program_describe(const fs_program* p, char* text, size_t capacity) {
+int64_t fs_program_describe(const fs_program* p, char* text, size_t capacity) try {
   clear_error();
   if (!p || (!text && capacity > 0)) return fail(FS_ERR_INVALID_ARG, "fs_program_describe: null argument");
   std::string s;
@@ -83,6 +87,8 @@ int64_t fs_program_describe(const fs_program* p, char* text, size_t capacity) {
     text[n] = 0;
   }
   return (int64_t)need;
+} catch (...) {
+  return fs::fail_caught("fs_program_describe");
 }
 
 }  // extern "C"
@@ -173,19 +179,23 @@ static fs_status run_program(const fs_program* p, int32_t first_stage, int32_t l
 extern "C" {
 
 fs_status fs_program_execute(const fs_program* p, const void* const* inputs, void* const* outputs, void* workspace,
-                             size_t workspace_bytes, void* hip_stream) {
+                             size_t workspace_bytes, void* hip_stream) try {
   clear_error();
   if (!p) return fail(FS_ERR_INVALID_ARG, "fs_program_execute: null argument");
   return run_program(p, 0, p->info.n_stages - 1, inputs, outputs, workspace, workspace_bytes, hip_stream);
+} catch (...) {
+  return fs::fail_caught("fs_program_execute");
 }
 
 fs_status fs_program_execute_stage(const fs_program* p, int32_t stage, const void* const* inputs, void* const* outputs,
-                                   void* workspace, size_t workspace_bytes, void* hip_stream) {
+                                   void* workspace, size_t workspace_bytes, void* hip_stream) try {
   clear_error();
   if (!p) return fail(FS_ERR_INVALID_ARG, "fs_program_execute_stage: null argument");
   if (stage < 0 || stage >= p->info.n_stages)
     return fail(FS_ERR_INVALID_ARG, "fs_program_execute_stage: stage %d outside 0..%d", stage, p->info.n_stages - 1);
   return run_program(p, stage, stage, inputs, outputs, workspace, workspace_bytes, hip_stream);
+} catch (...) {
+  return fs::fail_caught("fs_program_execute_stage");
 }
 
 }  // extern "C"

@@ -8,10 +8,12 @@
 // schemes exclude (Section 4.1, last paragraph: no inter-block communication).  Here
 // it is one round trip through device memory: every workgroup leaves its column
 // partials in a [n_row_blocks, cols] float32 workspace, and the partials are folded in
-// row-block order (fixed order: results are bit-identical from run to run) either
-//   * by a second, tiny launch (k_colfold) -- the kernel boundary is the hand-off; or
-//   * inside the same launch by the workgroup that draws the last ticket of its
-//     column tile from a counter in the workspace (the counter is left at zero).
+// row-block order (fixed order: results are bit-identical from run to run) by a second,
+// tiny launch (k_colfold): the kernel boundary is the hand-off.  Folding inside the same
+// launch (the workgroup that arrives last reads the others' partials) needs an agent-scope
+// release per workgroup before it signals its arrival, which on this part writes back the
+// whole L2 of the workgroup's die while that cache is full of freshly stored y: measured
+// at 1.6x the time of the two launches, so that form is not built.
 #include <hip/hip_runtime.h>
 
 #include "device_utils.hpp"
@@ -61,11 +63,10 @@ __device__ __forceinline__ float gelu_and_grad(float z, float g, float& acc) {
 // rows w, w+WAVES, ... of a row tile, so every wave-wide access is one contiguous
 // 1 KB piece, and at any moment the resident workgroups sweep one band of rows
 // (DRAM pages stay open) while each keeps its column sums in registers.
-template <typename T, int WAVES, int UNROLL, bool TICKET>
+template <typename T, int WAVES, int UNROLL>
 __global__ void __launch_bounds__(WAVES * 64) k_bias_gelu_dbias(const T* __restrict__ x, const T* __restrict__ bias,
                                                                 const T* __restrict__ grad, T* __restrict__ y,
-                                                                float* __restrict__ dbias, float* __restrict__ partials,
-                                                                uint32_t* __restrict__ counters, GeluP p) {
+                                                                float* __restrict__ partials, GeluP p) {
   constexpr int VEC = Elem<T>::VEC;
   constexpr int TILE_COLS = 64 * VEC, NT = WAVES * 64, TILE_ROWS = WAVES * UNROLL;
   __shared__ float red[WAVES][TILE_COLS];
@@ -123,43 +124,7 @@ __global__ void __launch_bounds__(WAVES * 64) k_bias_gelu_dbias(const T* __restr
 #pragma unroll
     for (int w = 1; w < WAVES; ++w) s += red[w][c];
     const uint32_t gc = ct * TILE_COLS + c;
-    if (gc < p.cols) {
-      float* dst = partials + (size_t)rb * p.cols + gc;
-      // TICKET: write through to device memory (agent-scope atomic store), so the
-      // folding workgroup, which may sit on another XCD with its own L2, can see it.
-      if (TICKET) __hip_atomic_store(dst, s, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      else *dst = s;
-    }
-  }
-  if constexpr (TICKET) {
-    // global step.  The barrier makes every lane's write-through store complete before
-    // lane 0 takes the ticket, so a full L2 write-back (what a release fence would cost
-    // on this multi-L2 part while the cache is full of freshly written y) is not needed.
-    __shared__ uint32_t ticket;
-    __syncthreads();
-    if (threadIdx.x == 0) ticket = __hip_atomic_fetch_add(&counters[ct], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
-    if (ticket != p.n_row_tiles - 1) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");   // drop stale cached lines before reading the partials
-    constexpr int NQ = TILE_COLS / 4, NG = NT / NQ;      // column quads x row groups; NG <= WAVES
-    const uint32_t quad = threadIdx.x % NQ, g = threadIdx.x / NQ;
-    const uint32_t qc = ct * TILE_COLS + quad * 4;
-    f32x4 s = {0.0f, 0.0f, 0.0f, 0.0f};
-    if (qc < p.cols) {
-      const float* src = partials + qc;
-      for (uint32_t t = g; t < p.n_row_tiles; t += NG) s += *reinterpret_cast<const f32x4*>(src + (size_t)t * p.cols);
-    }
-    __syncthreads();
-    *reinterpret_cast<f32x4*>(&red[g][quad * 4]) = s;
-    __syncthreads();
-    for (uint32_t c = threadIdx.x; c < TILE_COLS; c += NT) {
-      float v = red[0][c];
-#pragma unroll
-      for (int k = 1; k < NG; ++k) v += red[k][c];
-      const uint32_t gc = ct * TILE_COLS + c;
-      if (gc < p.cols) dbias[gc] = v;
-    }
-    if (threadIdx.x == 0) __hip_atomic_store(&counters[ct], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (gc < p.cols) partials[(size_t)rb * p.cols + gc] = s;
   }
 }
 
@@ -247,18 +212,18 @@ namespace fs {
 using namespace fsk;
 
 namespace {
-template <typename T, bool TICKET>
+template <typename T>
 const void* dbias_sym(int waves, int unroll) {
-  if (waves == 4 && unroll == 2) return (const void*)k_bias_gelu_dbias<T, 4, 2, TICKET>;
-  if (waves == 4 && unroll == 4) return (const void*)k_bias_gelu_dbias<T, 4, 4, TICKET>;
-  if (waves == 8 && unroll == 2) return (const void*)k_bias_gelu_dbias<T, 8, 2, TICKET>;
-  if (waves == 8 && unroll == 4) return (const void*)k_bias_gelu_dbias<T, 8, 4, TICKET>;
+  if (waves == 4 && unroll == 2) return (const void*)k_bias_gelu_dbias<T, 4, 2>;
+  if (waves == 4 && unroll == 4) return (const void*)k_bias_gelu_dbias<T, 4, 4>;
+  if (waves == 8 && unroll == 2) return (const void*)k_bias_gelu_dbias<T, 8, 2>;
+  if (waves == 8 && unroll == 4) return (const void*)k_bias_gelu_dbias<T, 8, 4>;
   return nullptr;
 }
 template <typename T>
 const void* gelu_sym(int32_t kernel, const GeluP& p) {
   if (kernel == K_BIAS_GELU) return (const void*)k_bias_gelu<T>;
-  return p.ticket ? dbias_sym<T, true>(p.waves, p.unroll) : dbias_sym<T, false>(p.waves, p.unroll);
+  return dbias_sym<T>(p.waves, p.unroll);
 }
 }  // namespace
 

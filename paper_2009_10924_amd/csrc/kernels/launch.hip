@@ -15,7 +15,7 @@ const KernelDesc kDesc[K_COUNT] = {
     {"unary", 2},          {"binary", 3},          {"reduce_row", 2},     {"reduce_mid", 2},
     {"transpose_rows", 2}, {"transpose_tile", 2},  {"copy", 2},           {"softmax_wave", 3},
     {"softmax_block", 3},  {"layernorm_wave", 8},  {"layernorm_block", 8}, {"bias_gelu", 3},
-    {"bias_gelu_dbias", 7}, {"colfold", 3},        {"tchain_wave", 3},    {"tchain_lds", 3},
+    {"bias_gelu_dbias", 5}, {"colfold", 3},        {"tchain_wave", 3},    {"tchain_lds", 3},
     {"row_wave", 6},       {"row_block", 6},       {"row_program", 0},    {"layernorm_bwd", 7},
     {"row_generated", 0},
 };

@@ -32,7 +32,7 @@ enum KernelId : int32_t {
   K_LAYERNORM_WAVE,    // p0 x, p1 res, p2 bias, p3 gamma, p4 beta, p5 out, p6 row mean out (or null), p7 row rstd out (or null)
   K_LAYERNORM_BLOCK,
   K_BIAS_GELU,         // p0 x, p1 bias, p2 y
-  K_BIAS_GELU_DBIAS,   // p0 x, p1 bias, p2 grad, p3 y, p4 dbias, p5 partials, p6 counters
+  K_BIAS_GELU_DBIAS,   // p0 x, p1 bias, p2 grad, p3 y, p4 partials [n_row_tiles, cols] f32 (folded by K_COLFOLD)
   K_COLFOLD,           // p0 partials [n_row_tiles, fold_cols] f32, p1 out0 (columns < fold_split), p2 out1 (the rest), both of dtype dt
   K_TCHAIN_WAVE,       // p0 x, p1 scale, p2 out
   K_TCHAIN_LDS,
@@ -118,7 +118,6 @@ struct GeluP {
   uint32_t rows, cols;              // K_COLFOLD: cols = floats between two partial rows
   uint32_t n_row_tiles;             // row blocks = rows of the partials workspace
   int32_t waves, unroll;            // workgroup = waves x 64 lanes; a row tile = waves * unroll rows
-  int32_t ticket;                   // 1: fold inside the launch (last ticket), 0: fold by K_COLFOLD
   uint32_t fold_cols, fold_split;   // K_COLFOLD: columns of the partials, first column that goes to the second output
   uint32_t fold_quads;              // K_COLFOLD: column quads per workgroup (16 with 16 row groups, or 4 with 64)
 };

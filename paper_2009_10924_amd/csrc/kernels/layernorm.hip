@@ -1,7 +1,7 @@
 // Stitched residual-add + bias + LayerNorm:
 //     h = x (+ res) (+ bias);  mu = mean(h);  c = h - mu;  v = mean(c^2);
 //     out = c * rsqrt(v + eps) (* gamma + beta)          -- one kernel, 12 ops
-// This is the pattern of the paper's Figure 1 / Section 7.3: two row reductions and
+// This is the pattern of the paper's Figure 1 (Section 2.1) / Section 7.4: two row reductions and
 // one expensive op on the per-row tensor, with every intermediate kept on chip.
 //   * wave variant  (warp composition): an aligned group of L lanes of one wavefront
 //     owns a row in registers; mean and variance are cross-lane all-reduces.

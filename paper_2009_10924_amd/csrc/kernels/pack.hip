@@ -1,5 +1,5 @@
 // Kernel packing (paper Section 4.1) across fusion patterns that have no data dependence
-// on each other (Section 5.3, remote fusion: patterns that are not adjacent in the graph
+// on each other (Section 5.2, remote fusion: patterns that are not adjacent in the graph
 // still share one kernel): up to 32 independent row patterns run as ONE launch.  Each
 // workgroup finds the member it serves from a table carried in the kernel arguments,
 // then runs that member's pattern on the generic row skeleton exactly as a stand-alone

@@ -275,3 +275,29 @@ def test_generated_pack_takes_any_row_local_member(lib):
     with pytest.raises(B.FsError) as e:       # per-op plans carry no pattern
         B.Pack([B.Plan(B.Graph.from_spec(softmax_graph(8, 64)), "unfused")])
     assert e.value.code == -5
+
+
+def test_zero_initialised_plan_opts_ask_for_nothing(lib):
+    # the C idiom `fs_plan_opts o = {0}; o.block_threads = 256;` must leave the choice to the evaluator:
+    # `candidate` counts from 1, zero means "choose"
+    import ctypes as C
+    spec = FULL_CONFIGS["C2"]()
+    g = B.Graph.from_spec(spec)
+    auto = B.Plan(g, "auto").info
+    h = C.c_void_p()
+    opts = B.fs_plan_opts(0, 0, 0, 0)
+    assert lib.fs_plan_create(g.handle, B.SCHEME["auto"], C.byref(opts), C.byref(h)) == 0
+    info = B.fs_plan_info()
+    assert lib.fs_plan_query(h, C.byref(info)) == 0
+    assert info.candidate == auto["candidate"] and info.kernel.decode() == auto["kernel"]
+    lib.fs_plan_destroy(h)
+    # k > 0 takes entry k - 1, whatever the other fields say
+    for k in (1, auto["n_candidates"]):
+        opts = B.fs_plan_opts(k, 0, 0, 0)
+        assert lib.fs_plan_create(g.handle, B.SCHEME["auto"], C.byref(opts), C.byref(h)) == 0
+        assert lib.fs_plan_query(h, C.byref(info)) == 0
+        assert info.candidate == k - 1
+        lib.fs_plan_destroy(h)
+    opts = B.fs_plan_opts(auto["n_candidates"] + 1, 0, 0, 0)
+    assert lib.fs_plan_create(g.handle, B.SCHEME["auto"], C.byref(opts), C.byref(h)) == -1
+
