@@ -179,7 +179,7 @@ def load() -> C.CDLL:
     lib.fs_execute.restype = i32
     lib.fs_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
     lib.fs_stream_copy.restype = i32
-    lib.fs_stream_probe.argtypes = [vp, vp, C.c_size_t, i32, i32, i32, vp]
+    lib.fs_stream_probe.argtypes = [vp, vp, C.c_size_t, C.c_size_t, i32, i32, i32, vp]
     lib.fs_stream_probe.restype = i32
     lib.fs_explore.argtypes = [vp, C.POINTER(fs_explore_opts), C.POINTER(vp)]
     lib.fs_explore.restype = i32
@@ -530,13 +530,15 @@ def bind_copy(dst_ptr: int, src_ptr: int, nbytes: int, stream: int):
     return call
 
 
-def bind_probe(dst_ptr: int, src_ptr: int, stream_bytes: int, reads: int, writes: int, vecs_per_lane: int, stream: int):
+def bind_probe(dst_ptr: int, src_ptr: int, stream_bytes: int, reads: int, writes: int, vecs_per_lane: int, stream: int,
+               pitch_bytes: int = 0):
     """Pre-marshalled fs_stream_probe call."""
     fn = load().fs_stream_probe
     d, s_, n, st = C.c_void_p(dst_ptr), C.c_void_p(src_ptr), C.c_size_t(stream_bytes), C.c_void_p(stream)
+    pitch = C.c_size_t(pitch_bytes)
 
     def call():
-        code = fn(d, s_, n, reads, writes, vecs_per_lane, st)
+        code = fn(d, s_, n, pitch, reads, writes, vecs_per_lane, st)
         if code < 0:
             _check(code)
     return call

@@ -84,5 +84,41 @@ def build(verbose: bool = False, jobs: int | None = None) -> str:
     return LIB_PATH
 
 
+HOST_SAN_LIB = os.path.join(PKG_DIR, "libfusion_stitching_host_san.so")
+
+
+def build_host_sanitized(verbose: bool = False) -> str:
+    """TEST-ONLY: the host core (every .cpp of SOURCES) with csrc/host_stub.cpp in place of the HIP kernels, built by
+    the host compiler with AddressSanitizer and UndefinedBehaviorSanitizer.  Needs no GPU and no ROCm; a process that
+    loads it preloads the compiler's libasan (tests/test_host_sanitizers.py does).  Launches are checked and counted,
+    never run."""
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    _embed_sources()
+    cxx = os.environ.get("CXX", "g++")
+    flags = ["-O1", "-g", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-fsanitize=address,undefined",
+             "-fno-omit-frame-pointer", "-fno-sanitize-recover=undefined"]
+    srcs = [s for s in SOURCES if s.endswith(".cpp")] + ["host_stub.cpp"]
+
+    def compile_one(src: str) -> str:
+        obj = os.path.join(OBJ_DIR, "san_" + src.replace("/", "_") + ".o")
+        cmd = [cxx, *flags, "-c", os.path.join(CSRC, src), "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        r = subprocess.run(cmd, capture_output=True, text=True)
+        if r.returncode != 0:
+            raise RuntimeError(f"sanitizer build of the host core failed: {src}\n{r.stderr}")
+        return obj
+
+    with cf.ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as pool:
+        objs = list(pool.map(compile_one, srcs))
+    r = subprocess.run([cxx, "-shared", "-fsanitize=address,undefined", "-o", HOST_SAN_LIB, *objs], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"sanitizer link of the host core failed\n{r.stderr}")
+    return HOST_SAN_LIB
+
+
 if __name__ == "__main__":
-    print(build(verbose="-v" in sys.argv))
+    if "--host-sanitized" in sys.argv:
+        print(build_host_sanitized(verbose="-v" in sys.argv))
+    else:
+        print(build(verbose="-v" in sys.argv))

@@ -112,6 +112,7 @@ bool build_gelu(const fs_graph& g, std::vector<Candidate>* out, PackForm* pack) 
         q.n_row_tiles = n_rb;
         q.waves = sh.waves;
         q.unroll = sh.unroll;
+        q.fast = (p.rows % (n_rb * tile_rows) == 0 && p.cols % tile_cols == 0) ? 1 : 0;
         {
           Launch& l = c.launches.front();
           l.args.u.gelu = q;

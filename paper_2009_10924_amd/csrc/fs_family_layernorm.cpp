@@ -258,7 +258,7 @@ bool build_layernorm_backward(const fs_graph& g, std::vector<Candidate>* out, Pa
       const uint32_t tile_rows = groups * sh.r;
       const uint32_t n_tiles = (p.rows + tile_rows - 1) / tile_rows;
       uint32_t last = 0;
-      for (uint32_t want : {512u, 1024u, 2048u}) {
+      for (uint32_t want : {256u, 512u, 1024u, 2048u}) {
         const uint32_t n_rb = std::min<uint32_t>(want, n_tiles);
         if (n_rb == last) continue;
         last = n_rb;
@@ -269,6 +269,7 @@ bool build_layernorm_backward(const fs_graph& g, std::vector<Candidate>* out, Pa
         q.vecs_per_lane = K;
         q.waves = sh.waves;
         q.rows_per_group = sh.r;
+        q.fast = ((uint64_t)L * K == nvec && p.rows % tile_rows == 0 && n_tiles % n_rb == 0) ? 1 : 0;
         {
           Launch& l = c.launches.front();
           l.args.u.lnbwd = q;

@@ -104,14 +104,14 @@ bool build_transpose(const fs_graph& g, std::vector<Candidate>* out, PackForm* p
   const bool tile = l.kernel == K_TRANSPOSE_TILE;
   u.info.scheme = tile ? FS_SCHEME_LDS : FS_SCHEME_LOCAL;
   snprintf(u.info.pattern, sizeof u.info.pattern, "transpose");
-  u.info.lds_bytes = !tile ? 0 : l.args.u.transpose.vec > 1 ? 64 * 66 * l.args.u.transpose.elem_bytes : 32 * 33 * l.args.u.transpose.elem_bytes;
+  u.info.lds_bytes = !tile ? 0 : l.args.u.transpose.vec > 1 ? 256 * 16 * l.args.u.transpose.vec : 32 * 33 * l.args.u.transpose.elem_bytes;
   KernelCost kc;
   kc.hbm_bytes = (double)u.info.bytes_min;
   kc.elems = (double)l.args.u.transpose.n;
   kc.valu_per_elem = tile ? 12 : 4;
   kc.waves_per_block = 4;
   kc.waves = (double)l.shape.grid[0] * 4;
-  kc.bytes_in_flight_per_lane = tile ? (l.args.u.transpose.vec > 1 ? 64.0 * l.args.u.transpose.elem_bytes / 4.0 : 4.0 * l.args.u.transpose.elem_bytes)
+  kc.bytes_in_flight_per_lane = tile ? (l.args.u.transpose.vec > 1 ? 16.0 * l.args.u.transpose.vec : 4.0 * l.args.u.transpose.elem_bytes)
                                      : (double)l.args.u.transpose.vec * l.args.u.transpose.elem_bytes;
   kc.vgpr_estimate = 24;
   kc.barriers = tile ? 1 : 0;

@@ -231,8 +231,10 @@ fs_status build_unfused(const fs_graph& g, Candidate* out) {
         // both tile axes multiples of a 128-bit vector: 64x64 tile with vector accesses, else 32x32 scalar
         const uint32_t v128 = 16 / p.elem_bytes;
         p.vec = (p.out_dims[q] % v128 == 0 && p.out_dims[3] % v128 == 0) ? (int32_t)v128 : 1;
-        const int64_t tile = p.vec > 1 ? 64 : 32;
-        int64_t blocks = ((int64_t)p.out_dims[q] + tile - 1) / tile * (((int64_t)p.out_dims[3] + tile - 1) / tile);
+        // vectorised tile: 16 x 16 units of vec x vec elements, or 8 x 32 when the moving axis is short
+        p.tile_uq = p.vec > 1 ? (p.out_dims[q] > 8u * (uint32_t)p.vec ? 16u : 8u) : 0u;
+        const int64_t tile_q = p.vec > 1 ? (int64_t)p.tile_uq * p.vec : 32, tile_3 = p.vec > 1 ? (int64_t)(256 / p.tile_uq) * p.vec : 32;
+        int64_t blocks = ((int64_t)p.out_dims[q] + tile_q - 1) / tile_q * (((int64_t)p.out_dims[3] + tile_3 - 1) / tile_3);
         for (uint32_t k = 0; k < 3; ++k) if (k != q) blocks *= p.out_dims[k];
         if (blocks >= (int64_t(1) << 31)) return fail(FS_ERR_SHAPE, "transpose: too many tiles");
         l.shape.grid[0] = (uint32_t)blocks;

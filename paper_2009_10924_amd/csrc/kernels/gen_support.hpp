@@ -288,8 +288,20 @@ struct GenRow {
   }
 };
 
+// A mid-pattern `convert`: the float32 value rounded to the storage dtype (nearest even) and widened again.  The value
+// is pinned in a register first (an empty asm the compiler cannot see through): otherwise the compiler may fuse the
+// multiplication that produced it with the conversion into one mixed-precision instruction (v_fma_mixlo_f16), which
+// rounds the exact product once -- while another use of the same value (the store) rounds the float32 product.  The
+// two differ by one 16-bit ulp where the float32 product is a tie, and a column sum of the rounded values would no
+// longer be the sum of what is stored.
 template <int DT> __device__ __forceinline__ float gen_round(float v) { return v; }
-template <> __device__ __forceinline__ float gen_round<1>(float v) { return (float)(_Float16)v; }
-template <> __device__ __forceinline__ float gen_round<2>(float v) { return bf16_bits_to_f32(pack_bf16(v, 0.0f) & 0xFFFFu); }
+template <> __device__ __forceinline__ float gen_round<1>(float v) {
+  asm volatile("" : "+v"(v));
+  return (float)(_Float16)v;
+}
+template <> __device__ __forceinline__ float gen_round<2>(float v) {
+  asm volatile("" : "+v"(v));
+  return bf16_bits_to_f32(pack_bf16(v, 0.0f) & 0xFFFFu);
+}
 
 }  // namespace fsk

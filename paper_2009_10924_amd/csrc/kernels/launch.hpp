@@ -89,6 +89,8 @@ struct TransposeP {
   // K_TRANSPOSE_TILE: the two axes of the tile
   uint32_t tile_in_axis_out_pos;  // output position of the input's innermost axis
   uint32_t out_stride[4];
+  uint32_t tile_uq;               // vectorised tile: 16-byte units along the input's innermost axis (16 or 8); the tile is
+                                  // tile_uq * vec elements along it by (256 / tile_uq) * vec along the output's innermost axis
 };
 
 // ---- stitched -----------------------------------------------------------------
@@ -118,6 +120,7 @@ struct GeluP {
   uint32_t rows, cols;              // K_COLFOLD: cols = floats between two partial rows
   uint32_t n_row_tiles;             // row blocks = rows of the partials workspace
   int32_t waves, unroll;            // workgroup = waves x 64 lanes; a row tile = waves * unroll rows
+  int32_t fast;                     // 1: rows fill every workgroup's row tiles and cols fill the column tiles exactly
   uint32_t fold_cols, fold_split;   // K_COLFOLD: columns of the partials, first column that goes to the second output
   uint32_t fold_quads;              // K_COLFOLD: column quads per workgroup (16 with 16 row groups, or 4 with 64)
 };
@@ -137,6 +140,7 @@ struct LnBwdP {
   float inv_cols;
   int32_t lanes_per_row, lanes_log2, vecs_per_lane;
   int32_t waves, rows_per_group;    // workgroup = waves x 64 lanes; rows each lane group loads up front
+  int32_t fast;                     // 1: the row fills the lanes exactly, the tiles fill the workgroups' rounds exactly
 };
 enum RowPattern : int32_t { ROW_SOFTMAX_BWD = 0, ROW_RMSNORM = 1 };
 struct RowP {

@@ -190,20 +190,23 @@ __global__ void __launch_bounds__(256) k_layernorm_block(const TI* __restrict__ 
 // requested before the first is used.  With one tile per workgroup the whole problem
 // runs as a single round of resident wavefronts, like the forward kernel; with more
 // tiles than workgroups the column sums simply keep accumulating.
-template <typename T, int K, int R, int WAVES>
+// FAST: the row fills the lanes exactly and the tiles fill the workgroups' rounds exactly.  Then nothing in the
+// row loop is conditional, the next tile's loads are issued before this tile's arithmetic (software pipeline),
+// and -- because the stores sit in no branch -- the wait for those loads leaves this tile's stores in flight.
+template <typename T, int K, int R, int WAVES, bool FAST>
 __global__ void __launch_bounds__(WAVES * 64) k_layernorm_bwd(const T* __restrict__ h, const T* __restrict__ dy,
                                                               const T* __restrict__ gamma, const float* __restrict__ mu,
                                                               const float* __restrict__ rstd, T* __restrict__ dx,
                                                               float* __restrict__ partials, LnBwdP p) {
   constexpr int VEC = Elem<T>::VEC;
   constexpr uint32_t NT = WAVES * 64;
-  extern __shared__ float lds[];                       // [groups][2][cols]
+  extern __shared__ __align__(16) float lds[];         // [groups][2][cols]
   const uint32_t L = p.lanes_per_row;
   const uint32_t groups = NT >> p.lanes_log2;
   const uint32_t group = threadIdx.x >> p.lanes_log2, lane = threadIdx.x & (L - 1);
   const uint32_t nvec = p.cols / VEC;
-  auto vec_at = [&](int k) { return min(lane + k * L, nvec - 1); };
-  auto valid = [&](int k) { return lane + k * L < nvec; };
+  auto vec_at = [&](int k) { return FAST ? lane + k * L : min(lane + k * L, nvec - 1); };
+  auto valid = [&](int k) { return FAST || lane + k * L < nvec; };
 
   float gam[K][VEC], dg[K][VEC], db[K][VEC];
   {
@@ -219,37 +222,42 @@ __global__ void __launch_bounds__(WAVES * 64) k_layernorm_bwd(const T* __restric
   }
   const uint32_t tile_rows = groups * R;
   const uint32_t n_tiles = (p.rows + tile_rows - 1) / tile_rows;
-  for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-    u32x4 rh[R][K], rd[R][K];
-    float rmu[R], rrs[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-      const uint32_t rc = min(tile * tile_rows + r * groups + group, p.rows - 1);
-      const size_t base = (size_t)rc * p.cols;
-#pragma unroll
-      for (int k = 0; k < K; ++k) {
-        rh[r][k] = load_raw_nt(h + base + vec_at(k) * VEC);
-        rd[r][k] = load_raw_nt(dy + base + vec_at(k) * VEC);
-      }
-      rmu[r] = mu[rc];
-      rrs[r] = rstd[rc];
-    }
+  struct Raw {
+    u32x4 h[R][K], d[R][K];
+    float mu[R], rs[R];
+  };
+  auto issue = [&](uint32_t tile, Raw& w) {
 #pragma unroll
     for (int r = 0; r < R; ++r) {
       const uint32_t row = tile * tile_rows + r * groups + group;
-      const bool row_ok = row < p.rows;
+      const uint32_t rc = FAST ? row : min(row, p.rows - 1);
+      const size_t base = (size_t)rc * p.cols;
+#pragma unroll
+      for (int k = 0; k < K; ++k) {
+        w.h[r][k] = load_raw_nt(h + base + vec_at(k) * VEC);
+        w.d[r][k] = load_raw_nt(dy + base + vec_at(k) * VEC);
+      }
+      w.mu[r] = mu[rc];
+      w.rs[r] = rstd[rc];
+    }
+  };
+  auto compute = [&](uint32_t tile, const Raw& w) {
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+      const uint32_t row = tile * tile_rows + r * groups + group;
+      const bool row_ok = FAST || row < p.rows;
       float xh[K][VEC], g[K][VEC];
       float s1 = 0.0f, s2 = 0.0f;
 #pragma unroll
       for (int k = 0; k < K; ++k) {
         float dv[VEC];
-        unpack(rh[r][k], xh[k], (const T*)nullptr);
-        unpack(rd[r][k], dv, (const T*)nullptr);
+        unpack(w.h[r][k], xh[k], (const T*)nullptr);
+        unpack(w.d[r][k], dv, (const T*)nullptr);
         const bool ok = row_ok && valid(k);
 #pragma unroll
         for (int e = 0; e < VEC; ++e) {
           const float d = ok ? dv[e] : 0.0f;             // padding and past-the-end rows contribute nothing
-          xh[k][e] = (xh[k][e] - rmu[r]) * rrs[r];
+          xh[k][e] = (xh[k][e] - w.mu[r]) * w.rs[r];
           g[k][e] = d * gam[k][e];
           s1 += g[k][e];
           s2 = __builtin_fmaf(g[k][e], xh[k][e], s2);
@@ -259,13 +267,37 @@ __global__ void __launch_bounds__(WAVES * 64) k_layernorm_bwd(const T* __restric
       }
       const float m1 = group_allreduce<OpSum>(s1, (int)L) * p.inv_cols;
       const float m2 = group_allreduce<OpSum>(s2, (int)L) * p.inv_cols;
-      const size_t base = (size_t)min(row, p.rows - 1) * p.cols;
+      const size_t base = (size_t)(FAST ? row : min(row, p.rows - 1)) * p.cols;
 #pragma unroll
       for (int k = 0; k < K; ++k) {
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) g[k][e] = (g[k][e] - m1 - xh[k][e] * m2) * rrs[r];
+        for (int e = 0; e < VEC; ++e) g[k][e] = (g[k][e] - m1 - xh[k][e] * m2) * w.rs[r];
         if (row_ok && valid(k)) store_vec_nt(dx + base + (lane + k * L) * VEC, g[k]);
       }
+    }
+  };
+  if constexpr (FAST) {
+    // n_tiles / gridDim.x rounds for every workgroup; first and last stand outside the loop so that the loop is
+    // entered with the same loads and stores in flight that its own rounds leave behind
+    Raw next;
+    uint32_t tile = blockIdx.x;
+    auto round = [&](uint32_t at) {
+      const Raw cur = next;
+      issue(at + gridDim.x, next);
+      compute(at, cur);
+    };
+    issue(tile, next);
+    if (tile + gridDim.x < n_tiles) {
+      round(tile);
+      tile += gridDim.x;
+      for (; tile + gridDim.x < n_tiles; tile += gridDim.x) round(tile);
+    }
+    compute(tile, next);
+  } else {
+    for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+      Raw w;
+      issue(tile, w);
+      compute(tile, w);
     }
   }
   // regional step: lane groups of the workgroup meet in LDS, folded in group order
@@ -274,7 +306,10 @@ __global__ void __launch_bounds__(WAVES * 64) k_layernorm_bwd(const T* __restric
     if (valid(k)) {
       float* a = lds + (size_t)(group * 2) * p.cols + (lane + k * L) * VEC;
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) { a[e] = dg[k][e]; a[p.cols + e] = db[k][e]; }
+      for (int e = 0; e < VEC; e += 4) {   // 128-bit LDS stores: scalar ones would be VEC floats apart from lane to lane
+        *reinterpret_cast<f32x4*>(a + e) = f32x4{dg[k][e], dg[k][e + 1], dg[k][e + 2], dg[k][e + 3]};
+        *reinterpret_cast<f32x4*>(a + p.cols + e) = f32x4{db[k][e], db[k][e + 1], db[k][e + 2], db[k][e + 3]};
+      }
     }
   }
   __syncthreads();
@@ -292,25 +327,29 @@ namespace fs {
 using namespace fsk;
 
 namespace {
-template <typename T, int R, int WAVES>
+template <typename T, int R, int WAVES, bool FAST>
 const void* ln_bwd_sym_k(int K) {
   switch (K) {
-    case 1: return (const void*)k_layernorm_bwd<T, 1, R, WAVES>;
-    case 2: return (const void*)k_layernorm_bwd<T, 2, R, WAVES>;
-    case 3: return (const void*)k_layernorm_bwd<T, 3, R, WAVES>;
-    case 4: return (const void*)k_layernorm_bwd<T, 4, R, WAVES>;
-    case 6: return (const void*)k_layernorm_bwd<T, 6, R, WAVES>;
+    case 1: return (const void*)k_layernorm_bwd<T, 1, R, WAVES, FAST>;
+    case 2: return (const void*)k_layernorm_bwd<T, 2, R, WAVES, FAST>;
+    case 3: return (const void*)k_layernorm_bwd<T, 3, R, WAVES, FAST>;
+    case 4: return (const void*)k_layernorm_bwd<T, 4, R, WAVES, FAST>;
+    case 6: return (const void*)k_layernorm_bwd<T, 6, R, WAVES, FAST>;
     default: return nullptr;
   }
 }
+template <typename T, bool FAST>
+const void* ln_bwd_sym_f(const LnBwdP& b) {
+  if (b.waves == 4 && b.rows_per_group == 1) return ln_bwd_sym_k<T, 1, 4, FAST>(b.vecs_per_lane);
+  if (b.waves == 4 && b.rows_per_group == 2) return ln_bwd_sym_k<T, 2, 4, FAST>(b.vecs_per_lane);
+  if (b.waves == 4 && b.rows_per_group == 4) return ln_bwd_sym_k<T, 4, 4, FAST>(b.vecs_per_lane);
+  if (b.waves == 8 && b.rows_per_group == 1) return ln_bwd_sym_k<T, 1, 8, FAST>(b.vecs_per_lane);
+  if (b.waves == 8 && b.rows_per_group == 2) return ln_bwd_sym_k<T, 2, 8, FAST>(b.vecs_per_lane);
+  return nullptr;
+}
 template <typename T>
 const void* ln_bwd_sym(const LnBwdP& b) {
-  if (b.waves == 4 && b.rows_per_group == 1) return ln_bwd_sym_k<T, 1, 4>(b.vecs_per_lane);
-  if (b.waves == 4 && b.rows_per_group == 2) return ln_bwd_sym_k<T, 2, 4>(b.vecs_per_lane);
-  if (b.waves == 4 && b.rows_per_group == 4) return ln_bwd_sym_k<T, 4, 4>(b.vecs_per_lane);
-  if (b.waves == 8 && b.rows_per_group == 1) return ln_bwd_sym_k<T, 1, 8>(b.vecs_per_lane);
-  if (b.waves == 8 && b.rows_per_group == 2) return ln_bwd_sym_k<T, 2, 8>(b.vecs_per_lane);
-  return nullptr;
+  return b.fast ? ln_bwd_sym_f<T, true>(b) : ln_bwd_sym_f<T, false>(b);
 }
 template <typename TI, typename TO>
 const void* ln_sym(int32_t kernel, int K, bool fast, bool stats) {

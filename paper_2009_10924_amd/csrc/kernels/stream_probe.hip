@@ -12,14 +12,14 @@
 namespace fsk {
 
 template <int R, int W, int K>
-__global__ void __launch_bounds__(256) k_stream_probe(const u32x4* __restrict__ src, u32x4* __restrict__ dst, uint32_t n_vec) {
+__global__ void __launch_bounds__(256) k_stream_probe(const u32x4* __restrict__ src, u32x4* __restrict__ dst, uint32_t n_vec, uint32_t pitch_vec) {
   const uint32_t base = blockIdx.x * (256u * K) + threadIdx.x;
   u32x4 t[R > 0 ? R : 1][K];
 #pragma unroll
   for (int r = 0; r < R; ++r)
 #pragma unroll
     for (int k = 0; k < K; ++k)
-      t[r][k] = __builtin_nontemporal_load(src + (size_t)r * n_vec + min(base + k * 256u, n_vec - 1u));   // clamped, not branched
+      t[r][k] = __builtin_nontemporal_load(src + (size_t)r * pitch_vec + min(base + k * 256u, n_vec - 1u));   // clamped, not branched
   u32x4 v[K];
 #pragma unroll
   for (int k = 0; k < K; ++k) {
@@ -38,7 +38,7 @@ __global__ void __launch_bounds__(256) k_stream_probe(const u32x4* __restrict__ 
     for (int w = 0; w < W; ++w)
 #pragma unroll
       for (int k = 0; k < K; ++k)
-        if (base + k * 256u < n_vec) __builtin_nontemporal_store(v[k], dst + (size_t)w * n_vec + base + k * 256u);
+        if (base + k * 256u < n_vec) __builtin_nontemporal_store(v[k], dst + (size_t)w * pitch_vec + base + k * 256u);
   }
 }
 
@@ -73,20 +73,23 @@ const void* probe_symbol(int r, int w, int k) {
 
 }  // namespace fsk
 
-extern "C" fs_status fs_stream_probe(void* dst, const void* src, size_t stream_bytes, int32_t reads, int32_t writes,
-                                     int32_t vecs_per_lane, void* hip_stream) {
+extern "C" fs_status fs_stream_probe(void* dst, const void* src, size_t stream_bytes, size_t stream_pitch_bytes, int32_t reads,
+                                     int32_t writes, int32_t vecs_per_lane, void* hip_stream) {
   fs::clear_error();
   if (!dst || (reads > 0 && !src)) return fs::fail(FS_ERR_INVALID_ARG, "fs_stream_probe: null pointer");
   const void* sym = fsk::probe_symbol(reads, writes, vecs_per_lane);
   if (!sym)
     return fs::fail(FS_ERR_INVALID_ARG, "fs_stream_probe: reads 0..4, writes 0..2 (not both 0), vecs_per_lane 1, 2 or 4; got %d, %d, %d", reads, writes,
                     vecs_per_lane);
-  if (((uintptr_t)dst | (uintptr_t)src | stream_bytes) & 15u) return fs::fail(FS_ERR_ALIGN, "fs_stream_probe: pointers and size must be multiples of 16");
+  if (stream_pitch_bytes == 0) stream_pitch_bytes = stream_bytes;
+  if (((uintptr_t)dst | (uintptr_t)src | stream_bytes | stream_pitch_bytes) & 15u)
+    return fs::fail(FS_ERR_ALIGN, "fs_stream_probe: pointers, size and pitch must be multiples of 16");
+  if (stream_pitch_bytes < stream_bytes) return fs::fail(FS_ERR_SHAPE, "fs_stream_probe: the pitch is smaller than a stream");
   if (stream_bytes == 0) return FS_OK;
-  if (stream_bytes / 16 >= (size_t(1) << 31)) return fs::fail(FS_ERR_SHAPE, "fs_stream_probe: too large");
-  uint32_t n_vec = (uint32_t)(stream_bytes / 16);
+  if (stream_pitch_bytes / 16 >= (size_t(1) << 31)) return fs::fail(FS_ERR_SHAPE, "fs_stream_probe: too large");
+  uint32_t n_vec = (uint32_t)(stream_bytes / 16), pitch_vec = (uint32_t)(stream_pitch_bytes / 16);
   const uint32_t per_block = 256u * (uint32_t)vecs_per_lane;
-  void* argv[3] = {&src, &dst, &n_vec};
+  void* argv[4] = {&src, &dst, &n_vec, &pitch_vec};
   const hipError_t e = hipLaunchKernel(sym, dim3((n_vec + per_block - 1) / per_block), dim3(256), argv, 0, static_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fs::fail(FS_ERR_HIP, "fs_stream_probe: %s", hipGetErrorString(e));
   return FS_OK;

@@ -248,21 +248,26 @@ __global__ void __launch_bounds__(256) k_transpose_tile(const T* __restrict__ in
   }
 }
 
-// ---- transpose, innermost axis moves: 64x64 tile, 128-bit global accesses ----------------
-// Same tiling as above with both HBM sides moved as 128-bit vectors: a thread loads
-// VEC contiguous input elements, parks them in LDS un-transposed, and after the barrier
-// gathers VEC elements down a tile column for one 128-bit store along the output's
-// innermost axis.  Tile pitch 64+1 words (64+2 halfwords) keeps both LDS phases at the
-// two-lanes-per-bank minimum of a 64-lane wave.  Needs both tile axes to be multiples
-// of VEC; other shapes use the 32x32 scalar kernel.
-template <typename T>
+// ---- transpose, innermost axis moves: 128-bit accesses on both HBM sides AND both LDS sides ----------------
+// The tile is UQ x U3 units of VEC x VEC elements (UQ * U3 = 256 threads, one unit each; VEC = elements in 16
+// bytes), TQ = UQ * VEC along the input's innermost axis (output axis q) by T3 = U3 * VEC along the output's.
+// A thread loads its unit as VEC rows of 16 bytes (a wave reads runs of UQ * 16 bytes), transposes it in
+// registers (32-bit elements: a renaming; 16-bit elements: one byte-permute per pair), and parks it in LDS as VEC
+// 16-byte pieces, one per tile column, each holding VEC consecutive elements of the OUTPUT's innermost axis.
+// After the barrier a thread reads one 16-byte piece per pass and stores it: a wave writes runs of U3 * 16 bytes
+// (or several full columns).  LDS is [TQ columns][U3 pieces] of 16 bytes, unpadded; piece u of column c sits at
+// position u ^ (c / VEC mod 8): any eight neighbouring lanes -- the lanes one LDS cycle serves for a 128-bit
+// access -- then hit eight different 16-byte bank groups, writing (same row unit, eight column units) and
+// reading (same column, eight neighbouring pieces) alike, where a padded tile with scalar accesses ran at two
+// lanes per bank (measured: conflict cycles half of the LDS-active cycles).
+// Needs both tile axes to be multiples of VEC; other shapes use the 32x32 scalar kernel.
+template <typename T, int UQ>
 __global__ void __launch_bounds__(256) k_transpose_tile64(const T* __restrict__ in, T* __restrict__ out, TransposeP p) {
-  constexpr uint32_t VEC = 16 / sizeof(T), TILE = 64, PITCH = TILE + (sizeof(T) == 4 ? 1 : 2);
-  constexpr uint32_t LANES_PER_ROW = TILE / VEC, ROWS_PER_PASS = 256 / LANES_PER_ROW;
-  __shared__ T tile[TILE][PITCH];
+  constexpr uint32_t VEC = 16 / sizeof(T), U3 = 256 / UQ, TQ = UQ * VEC, T3 = U3 * VEC;
+  __shared__ u32x4 tile[TQ * U3];
   const uint32_t q = p.tile_in_axis_out_pos;
   const uint32_t nq = p.out_dims[q], n3 = p.out_dims[3];
-  const uint32_t tq = (nq + TILE - 1) / TILE, t3 = (n3 + TILE - 1) / TILE;
+  const uint32_t tq = (nq + TQ - 1) / TQ, t3 = (n3 + T3 - 1) / T3;
   uint32_t bid = blockIdx.x;
   const uint32_t b3 = bid % t3; bid /= t3;
   const uint32_t bq = bid % tq; bid /= tq;
@@ -272,32 +277,48 @@ __global__ void __launch_bounds__(256) k_transpose_tile64(const T* __restrict__ 
   const uint32_t cb0 = bid / p.out_dims[ax[1]];
   const uint32_t in_base = cb0 * p.in_stride[ax[0]] + cb1 * p.in_stride[ax[1]];
   const uint32_t out_base = cb0 * p.out_stride[ax[0]] + cb1 * p.out_stride[ax[1]];
-  const uint32_t lr = threadIdx.x % LANES_PER_ROW, rr = threadIdx.x / LANES_PER_ROW;
-  union Pack { u32x4 v; T e[VEC]; };
-  // read: 128-bit along the input's innermost axis (output axis q)
-  Pack buf[TILE / ROWS_PER_PASS];
+  // load: unit (uq, u3) = columns uq*VEC.. of rows u3*VEC..; padding units are clamped to valid addresses (what
+  // they park in LDS is never stored)
+  const uint32_t uq = threadIdx.x % UQ, u3 = threadIdx.x / UQ;
+  const uint32_t cq0 = min(bq * TQ + uq * VEC, nq - VEC), c30 = min(b3 * T3 + u3 * VEC, n3 - VEC);
+  u32x4 row[VEC];
 #pragma unroll
-  for (uint32_t s = 0; s < TILE / ROWS_PER_PASS; ++s) {
-    const uint32_t j = rr + s * ROWS_PER_PASS;
-    const uint32_t cq = min(bq * TILE + lr * VEC, nq - VEC), c3 = min(b3 * TILE + j, n3 - 1);
-    buf[s].v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(in + in_base + cq + c3 * p.in_stride[3]));
+  for (uint32_t s = 0; s < VEC; ++s)
+    row[s] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(in + in_base + cq0 + (size_t)(c30 + s) * p.in_stride[3]));
+  // transpose in registers: col[e] = elements e of rows 0..VEC-1
+  u32x4 col[VEC];
+  if constexpr (sizeof(T) == 4) {
+#pragma unroll
+    for (uint32_t e = 0; e < 4; ++e) col[e] = u32x4{row[0][e], row[1][e], row[2][e], row[3][e]};
+  } else {
+    // 2x2 blocks of 16-bit elements first: for rows (2m, 2m+1) and dword k, lo = [r0.lo16, r1.lo16] is column 2k,
+    // hi = [r0.hi16, r1.hi16] column 2k+1, each holding rows 2m, 2m+1; the rest is a renaming
+#pragma unroll
+    for (uint32_t k = 0; k < 4; ++k) {
+      uint32_t lo[4], hi[4];
+#pragma unroll
+      for (uint32_t m = 0; m < 4; ++m) {
+        lo[m] = __builtin_amdgcn_perm(row[2 * m + 1][k], row[2 * m][k], 0x05040100u);   // [r0.lo, r1.lo]
+        hi[m] = __builtin_amdgcn_perm(row[2 * m + 1][k], row[2 * m][k], 0x07060302u);   // [r0.hi, r1.hi]
+      }
+      col[2 * k] = u32x4{lo[0], lo[1], lo[2], lo[3]};
+      col[2 * k + 1] = u32x4{hi[0], hi[1], hi[2], hi[3]};
+    }
   }
 #pragma unroll
-  for (uint32_t s = 0; s < TILE / ROWS_PER_PASS; ++s) {
-    const uint32_t j = rr + s * ROWS_PER_PASS;
-#pragma unroll
-    for (uint32_t e = 0; e < VEC; ++e) tile[j][lr * VEC + e] = buf[s].e[e];
+  for (uint32_t e = 0; e < VEC; ++e) {
+    const uint32_t c = uq * VEC + e;
+    tile[c * U3 + (u3 ^ (uq & 7u))] = col[e];
   }
   __syncthreads();
-  // write: 128-bit along the output's innermost axis
+  // store: piece u of column c -> 16 bytes of output row (bq*TQ + c) at column b3*T3 + u*VEC
+  const uint32_t u = threadIdx.x % U3, c_first = threadIdx.x / U3;
 #pragma unroll
-  for (uint32_t s = 0; s < TILE / ROWS_PER_PASS; ++s) {
-    const uint32_t i = rr + s * ROWS_PER_PASS;
-    const uint32_t cq = bq * TILE + i, c3 = b3 * TILE + lr * VEC;
-    Pack o;
-#pragma unroll
-    for (uint32_t e = 0; e < VEC; ++e) o.e[e] = tile[lr * VEC + e][i];
-    if (cq < nq && c3 < n3) __builtin_nontemporal_store(o.v, reinterpret_cast<u32x4*>(out + out_base + cq * p.out_stride[q] + c3));
+  for (uint32_t s = 0; s < TQ / UQ; ++s) {
+    const uint32_t c = c_first + s * UQ;
+    const u32x4 v = tile[c * U3 + (u ^ ((c / VEC) & 7u))];
+    const uint32_t cq = bq * TQ + c, c3 = b3 * T3 + u * VEC;
+    if (cq < nq && c3 < n3) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(out + out_base + (size_t)cq * p.out_stride[q] + c3));
   }
 }
 
@@ -334,8 +355,11 @@ const void* unfused_kernel_symbol(int32_t kernel, const KernelArgs& a) {
            : vb == 4 ? (const void*)k_transpose_rows<uint32_t> : (const void*)k_transpose_rows<uint16_t>;
     }
     case K_TRANSPOSE_TILE:
-      if (a.u.transpose.vec > 1)
-        return a.u.transpose.elem_bytes == 4 ? (const void*)k_transpose_tile64<uint32_t> : (const void*)k_transpose_tile64<uint16_t>;
+      if (a.u.transpose.vec > 1) {
+        if (a.u.transpose.tile_uq == 8)
+          return a.u.transpose.elem_bytes == 4 ? (const void*)k_transpose_tile64<uint32_t, 8> : (const void*)k_transpose_tile64<uint16_t, 8>;
+        return a.u.transpose.elem_bytes == 4 ? (const void*)k_transpose_tile64<uint32_t, 16> : (const void*)k_transpose_tile64<uint16_t, 16>;
+      }
       return a.u.transpose.elem_bytes == 4 ? (const void*)k_transpose_tile<uint32_t> : (const void*)k_transpose_tile<uint16_t>;
     case K_COPY:
       return (const void*)k_copy;

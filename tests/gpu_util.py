@@ -32,7 +32,8 @@ def cancelling_outputs(spec, inputs):
     float32 arithmetic gives every computed value a relative error of about 1e-7.  An `add` / `sub` / `add_scalar`
     whose result can be near zero while an operand is a computed (already rounded) value, a `reduce_sum` /
     `reduce_mean` over values of both signs, and a `log` (whose result is near zero for arguments near one) turn
-    that into an error that is small against the operands but unbounded against the result; every op that passes
+    that into an error that is small against the operands but unbounded against the result (the derivative of the
+    tanh-GELU likewise: it changes sign near -0.752, where its two terms cancel); every op that passes
     relative error on (mul, div, scale, max, square, abs, relu, sqrt, rsqrt, tanh, the GELU pair, reduce_max,
     convert, broadcast, transpose) passes the property on.  `exp` and `sigmoid` end it (their relative error is the
     absolute error of the argument), and so do sums of non-negative terms.  Sums of graph inputs are exact to half
@@ -62,10 +63,10 @@ def cancelling_outputs(spec, inputs):
             out = (False, True, False)
         elif code in _NONNEG_OPS:
             out = (False, True, c[0])
-        elif code in ("tanh", "gelu_tanh", "gelu_tanh_grad"):
-            out = (False, False, c[0])
-        elif code == "log":
-            out = (False, False, True)
+        elif code in ("tanh", "gelu_tanh"):
+            out = (False, False, c[0])      # zero only at zero, where they behave like their argument
+        elif code in ("log", "gelu_tanh_grad"):
+            out = (False, False, True)      # zero at a generic argument (1; about -0.752): a sum of terms that cancel there
         elif code in ("reduce_sum", "reduce_mean"):
             out = (False, nn[0], not nn[0])
         elif code == "reduce_max":

@@ -8,17 +8,16 @@ import pytest
 
 from oracle import oracle as O
 from paper_2009_10924_amd import binding as B
-from tests.gpu_util import TOL, check, note, run_spec
+from tests.gpu_util import TOL, cancelling_outputs, check, note, run_spec
 from workloads import FULL_CONFIGS, GENERIC_CONFIGS, NEXT_CONFIGS, make_inputs
 
 pytestmark = pytest.mark.gpu
 
-# output name -> use the rms floor (outputs formed by cancelling sums)
-RMS_FLOOR = {"C2": {"out"}, "C4": {"dbias"}, "N1": {"dx"}, "N2": {"dx", "dgamma", "dbeta"}, "N6": {"out", "mu"},
-             "G1": {"out", "mu"}, "G4": {"out", "topb"},
-             "G8": {"out"},    # gain * ctx + residual cancels
-             "G9": {"dx", "dbias"}, "G10": {"dx", "dgamma"},   # signed column sums; dx of RMSNorm is a difference
-             "G5": {"y"}}     # probabilities down to exp(-60) sit below the smallest fp16 number and are stored as 0
+# output name -> use the rms floor (outputs formed by cancelling sums or differences).  For the five configurations
+# and the backward patterns the names are written out; test_full_size_config checks that the rule which derives them
+# from the descriptor (tests/gpu_util.cancelling_outputs) agrees, and uses the rule for the generic patterns.
+RMS_FLOOR = {"C1": set(), "C2": {"out"}, "C3": set(), "C4": {"dbias"}, "C5": set(), "N1": {"dx"}, "N2": {"dx", "dgamma", "dbeta"},
+             "N5": set(), "N6": {"out", "mu"}}
 ALL = dict(FULL_CONFIGS, **NEXT_CONFIGS, **GENERIC_CONFIGS)
 
 
@@ -58,6 +57,23 @@ def test_full_size_vocabulary_rows_on_sampled_rows(cfg):
         sums = (got["y"] if cfg == "G11" else np.exp(got["y"])).sum(axis=-1)
         # (the stored logarithms are rounded to bfloat16: a relative 2^-9 of about -12 moves each probability by 2 %)
         assert np.max(np.abs(sums - 1.0)) < (2e-2 if cfg == "G11" else 5e-2)
+        # every row, at no oracle cost: the largest output sits where the largest input sits (ties in the rounded
+        # output allowed), and equals what the row's own maximum and sum give: softmax's largest entry is 1 / sum_j
+        # exp(x_j - max), log-softmax's is minus the logarithm of that sum
+        x = O.to_f64(inp["x"], "bf16")
+        top_in = x.max(axis=-1)
+        at = x.argmax(axis=-1)
+        rows_idx = np.arange(rows)
+        assert np.array_equal(got["y"][rows_idx, at], got["y"].max(axis=-1)), f"{cfg} {scheme}: a row's largest output is not at its largest input"
+        z = np.exp(x - top_in[:, None]).sum(axis=-1)
+        want_top = 1.0 / z if cfg == "G11" else -np.log(z)
+        err_top = np.max(np.abs(got["y"][rows_idx, at] - want_top) / np.abs(want_top))
+        assert err_top <= TOL["bf16"], (cfg, scheme, err_top)
+        # and the smallest entry of every row likewise (the other end of the row's range)
+        low = x.argmin(axis=-1)
+        want_low = np.exp(x[rows_idx, low] - top_in) / z if cfg == "G11" else (x[rows_idx, low] - top_in) - np.log(z)
+        err_low = np.max(np.abs(got["y"][rows_idx, low] - want_low) / np.abs(want_low))
+        assert err_low <= TOL["bf16"], (cfg, scheme, err_low)
         note(f"    {cfg} {scheme:7s} {info['kernel']:48s} y: max rel err {worst:.3e} over {len(sample)} sampled rows; row sums within {np.max(np.abs(sums - 1.0)):.1e} of 1")
 
 
@@ -68,6 +84,8 @@ def test_full_size_config(cfg):
     inp = make_inputs(spec, seed=0)
     note("  oracle")
     ref = O.evaluate(spec, inp)
+    floored = cancelling_outputs(spec, inp)
+    assert cfg not in RMS_FLOOR or RMS_FLOOR[cfg] == floored, (cfg, floored)
     # patterns on the generic path run three ways: the generated kernel (AUTO), the interpreted row program
     # (code generation switched off) and per op
     # (column sums inside a row pattern, G9 / G10, exist as generated kernels only)
@@ -82,12 +100,12 @@ def test_full_size_config(cfg):
             got, _, info, _ = run_spec(spec, inp, scheme, repeat=2)
             if cfg.startswith("G") and scheme == "auto":
                 assert info["pattern"] == "row_generated"
-        _compare(cfg, spec, got, ref, info, scheme)
+        _compare(cfg, spec, got, ref, info, scheme, floored)
 
 
-def _compare(cfg, spec, got, ref, info, scheme):
+def _compare(cfg, spec, got, ref, info, scheme, floored):
     for name, dt in spec.outputs:
-        floor = O.rms(ref[name]) if name in RMS_FLOOR.get(cfg, ()) else 0.0
+        floor = O.rms(ref[name]) if name in floored else 0.0
         err = check(got[name], ref[name], dt, floor, f"{cfg}/{info['kernel']}/{name}")
         strict = O.max_rel_err(got[name], ref[name], 0.0)
         over = int(np.sum(np.abs(got[name] - ref[name]) > TOL[dt] * np.abs(ref[name])))
@@ -112,4 +130,4 @@ def test_full_size_forced_lds_scheme(cfg):
     ref = O.evaluate(spec, inp)
     got, _, info, _ = run_spec(spec, inp, "lds", repeat=2)
     assert info["scheme"] == "lds" and info["lds_bytes"] > 0, info
-    _compare(cfg, spec, got, ref, info, "lds")
+    _compare(cfg, spec, got, ref, info, "lds", RMS_FLOOR[cfg])

@@ -6,28 +6,13 @@ import pytest
 
 from oracle import oracle as O
 from paper_2009_10924_amd import binding as B
-from tests.gpu_util import TOL, check, note, run_spec
+from tests.gpu_util import TOL, all_candidates, check, note, run_spec
 from workloads import (add_bias_layernorm_graph, attention_scores_graph, bias_gelu_dbias_graph, bias_gelu_graph,
                        layernorm_backward_graph, make_inputs, rmsnorm_graph, softmax_backward_graph, softmax_graph,
                        transpose_chain_graph, transpose_graph)
 from workloads.graphs import GraphSpec, OpSpec, TensorSpec
 
 pytestmark = pytest.mark.gpu
-
-
-def all_candidates(spec, inputs, ref, floors, repeat=1):
-    """Runs the per-op plan and every stitched candidate; returns the worst error per output."""
-    worst = {}
-    g = B.Graph.from_spec(spec)
-    n = B.Plan(g, "auto").info["n_candidates"]
-    runs = [("unfused", {})] + [("auto", {"candidate": i}) for i in range(n)]
-    for scheme, opts in runs:
-        note(f"  case {spec.name} scheme={scheme} opts={opts}")
-        got, _, info, _ = run_spec(spec, inputs, scheme, repeat=repeat, **opts)
-        for name, dt in spec.outputs:
-            e = check(got[name], ref[name], dt, floors.get(name, 0.0), f"{spec.name}/{info['kernel']}/{name}")
-            worst[name] = max(worst.get(name, 0.0), e)
-    return worst
 
 
 # ------------------------------------------------------------------ C1 softmax
@@ -104,7 +89,7 @@ def test_bias_gelu_dbias(rows, cols, dtype):
     inp = make_inputs(spec, seed=0)
     ref = O.evaluate(spec, inp)
     floors = {"dbias": O.rms(ref["dbias"])}
-    worst = all_candidates(spec, inp, ref, floors, repeat=3)   # repeat: the arrival counters must reset themselves
+    worst = all_candidates(spec, inp, ref, floors, repeat=3)
     note(f"bias_gelu_dbias {rows}x{cols} {dtype}: worst {worst}")
 
 

@@ -26,7 +26,7 @@ def test_rms_floor_goes_to_cancelling_sums_only():
     # backward patterns: differences and signed column sums
     assert _names(softmax_backward_graph(8, 128, "f16")) == {"dx"}
     assert _names(layernorm_backward_graph(8, 64, "f32")) == {"dx", "dgamma", "dbeta"}
-    assert _names(gelu_backward_graph(16, 64, "bf16")) == {"dbias"}            # dx = g * gelu'(x + b) does not cancel
+    assert _names(gelu_backward_graph(16, 64, "bf16")) == {"dx", "dbias"}      # gelu' changes sign near z = -0.752
     assert _names(rmsnorm_backward_graph(8, 64, "bf16")) == {"dx", "dgamma"}
     # sums of squares and what is computed from them are strict; a row mean of signed values is not
     assert _names(rmsnorm_graph(8, 64, dtype="bf16")) == set()
@@ -36,7 +36,7 @@ def test_rms_floor_goes_to_cancelling_sums_only():
     # the transformer block: only the two LayerNorm outputs; softmax probabilities, GELU and the moves are strict
     assert _names(transformer_block_graph(2, 16, 2, 8, 64, "bf16")) == {"l1_out", "l2_out"}
     back = _names(transformer_block_backward_graph(2, 16, 2, 8, 64, "bf16"))
-    assert {"d_ctx", "d_q", "d_k", "d_v", "f_dxc"}.isdisjoint(back) and {"l2_dxc", "dbias1", "l1_dgamma", "d_scores"} <= back
+    assert {"d_ctx", "d_q", "d_k", "d_v"}.isdisjoint(back) and {"l2_dxc", "dbias1", "l1_dgamma", "d_scores"} <= back
 
 
 def test_sign_of_the_inputs_is_read_from_the_data():
