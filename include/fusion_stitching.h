@@ -263,6 +263,22 @@ int64_t fs_plan_source(const fs_plan *p, char *text, size_t capacity);
 fs_status fs_execute(const fs_plan *p, const void *const *inputs, void *const *outputs,
                      void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/* fs_execute for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments and rules, without
+ * the workspace: the plan's scratch (the partial column sums that the workgroups of one
+ * launch hand to the fold launch, or a per-op plan's intermediates) is a fixed array of
+ * FS_STATIC_SCRATCH_BYTES in the library's device image, one copy per GPU, held until the
+ * process ends; the device of `hip_stream` must be the current device.  A plan whose
+ * fs_plan_info.workspace_bytes is larger is refused with FS_ERR_WORKSPACE before anything
+ * is enqueued.  Allocates nothing on the device (no hipMalloc / hipFree, no allocating
+ * library call), never synchronizes; the first call on a GPU looks up the array's address.
+ * Every call on a GPU uses that GPU's one array, so two calls whose kernels may overlap in
+ * time (different streams, or graphs replayed concurrently) race: order them on one stream.
+ * The array keeps the last call's contents; no plan needs it cleared.
+ * Errors: FS_ERR_INVALID_ARG, FS_ERR_WORKSPACE, FS_ERR_ALIGN, FS_ERR_HIP.               */
+#define FS_STATIC_SCRATCH_BYTES (4u << 20)
+fs_status fs_execute_static(const fs_plan *p, const void *const *inputs, void *const *outputs, void *hip_stream);
+
 /* ---- packed execution (Section 4.1, kernel packing: ops with no data dependence
  *      share one kernel to cut launches; Section 5.2, remote fusion: patterns that
  *      are not adjacent in the graph may still be packed) -------------------------- */

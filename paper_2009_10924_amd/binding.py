@@ -29,12 +29,13 @@ ERROR_NAME = {0: "FS_OK", -1: "FS_ERR_INVALID_ARG", -2: "FS_ERR_SHAPE", -3: "FS_
 EXPORTS = [
     "fs_graph_create", "fs_graph_destroy", "fs_graph_input", "fs_graph_op", "fs_graph_output",
     "fs_graph_finalize", "fs_plan_create", "fs_plan_destroy", "fs_plan_query", "fs_plan_candidate", "fs_plan_describe",
-    "fs_plan_source", "fs_codegen_enable", "fs_codegen_available", "fs_execute", "fs_stream_copy", "fs_stream_probe", "fs_last_error", "fs_version",
+    "fs_plan_source", "fs_codegen_enable", "fs_codegen_available", "fs_execute", "fs_execute_static", "fs_stream_copy", "fs_stream_probe", "fs_last_error", "fs_version",
     "fs_pack_create", "fs_pack_destroy", "fs_pack_query", "fs_pack_execute",
     "fs_explore", "fs_explore_score", "fs_program_destroy", "fs_program_query", "fs_program_pattern", "fs_program_execute",
     "fs_program_describe", "fs_program_execute_stage", "fs_graph_external",
 ]
 FS_PACK_MAX_MEMBERS = 256
+FS_STATIC_SCRATCH_BYTES = 4 << 20
 
 
 class FsError(RuntimeError):
@@ -177,6 +178,8 @@ def load() -> C.CDLL:
     lib.fs_codegen_available.restype = C.c_int32
     lib.fs_execute.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp, C.c_size_t, vp]
     lib.fs_execute.restype = i32
+    lib.fs_execute_static.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp]
+    lib.fs_execute_static.restype = i32
     lib.fs_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
     lib.fs_stream_copy.restype = i32
     lib.fs_stream_probe.argtypes = [vp, vp, C.c_size_t, C.c_size_t, i32, i32, i32, vp]
@@ -364,6 +367,12 @@ class Plan:
         import torch
         n = int(self.info["workspace_bytes"])
         return torch.zeros(max(n, 16), dtype=torch.uint8, device=device) if n > 0 else None
+
+    def execute_static_ptrs(self, inputs: Sequence[int], outputs: Sequence[int], stream: int) -> None:
+        """fs_execute_static: the plan's scratch is the library's static device array, nothing is allocated."""
+        ins = (C.c_void_p * max(1, len(inputs)))(*inputs)
+        outs = (C.c_void_p * max(1, len(outputs)))(*outputs)
+        _check(self._lib.fs_execute_static(self.handle, ins, outs, C.c_void_p(stream)))
 
 
 class Pack:

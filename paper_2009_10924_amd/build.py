@@ -19,7 +19,7 @@ SOURCES = [
     "fs_family_transpose.cpp", "fs_family_rows.cpp", "fs_plan.cpp", "fs_pack.cpp", "fs_rowprog.cpp", "fs_explore.cpp", "fs_program.cpp", "fs_codegen.cpp",
     "kernels/launch.hip", "kernels/unfused.hip", "kernels/softmax.hip", "kernels/layernorm.hip",
     "kernels/gelu.hip", "kernels/tchain.hip", "kernels/rowops.hip", "kernels/pack.hip", "kernels/rowprog.hip",
-    "kernels/gen_runtime.hip", "kernels/gen_sample.hip", "kernels/stream_probe.hip",
+    "kernels/gen_runtime.hip", "kernels/gen_sample.hip", "kernels/static_scratch.hip", "kernels/stream_probe.hip",
 ]
 
 # device headers the run-time compiler gets as text in front of a generated kernel: (file, name of the C string)

@@ -77,6 +77,16 @@ int gen_launch(GenKernel* k, const void* args, size_t args_bytes, const LaunchSh
 }  // namespace fs
 
 // the entry points that live in .hip files in the product
+extern "C" fs_status fs_execute_static(const fs_plan* p, const void* const* inputs, void* const* outputs, void* hip_stream) {
+  fs::clear_error();
+  const fs_status s = fs::check_execute_args(p, inputs, outputs, "fs_execute_static");
+  if (s != FS_OK) return s;
+  const fs::Candidate& c = p->candidates[p->chosen];
+  if (c.info.workspace_bytes > (int64_t)FS_STATIC_SCRATCH_BYTES)
+    return fs::fail(FS_ERR_WORKSPACE, "fs_execute_static: the plan needs %lld bytes of scratch, the static array holds %lld",
+                    (long long)c.info.workspace_bytes, (long long)FS_STATIC_SCRATCH_BYTES);
+  return fs::run_launches(p, inputs, outputs, reinterpret_cast<void*>(0x7000000), hip_stream, c.launches.size());
+}
 extern "C" fs_status fs_stream_probe(void*, const void*, size_t, size_t, int32_t, int32_t, int32_t, void*) {
   return fs::fail(FS_ERR_HIP, "fs_stream_probe: not part of the host stub");
 }

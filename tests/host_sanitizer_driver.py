@@ -22,6 +22,8 @@ def run_plan(spec, scheme="auto", **opts):
     plan = B.Plan(B.Graph.from_spec(spec), scheme, **opts)
     ws = plan.info["workspace_bytes"]
     plan.execute_ptrs(fake(len(spec.inputs), 0x10000), fake(len(spec.outputs), 0x1000000), 0x40000000 if ws else 0, ws, 0)
+    if 0 < ws <= B.FS_STATIC_SCRATCH_BYTES:
+        plan.execute_static_ptrs(fake(len(spec.inputs), 0x10000), fake(len(spec.outputs), 0x1000000), 0)
     plan.describe()
     plan.source()
     return plan

@@ -301,3 +301,25 @@ def test_zero_initialised_plan_opts_ask_for_nothing(lib):
     opts = B.fs_plan_opts(auto["n_candidates"] + 1, 0, 0, 0)
     assert lib.fs_plan_create(g.handle, B.SCHEME["auto"], C.byref(opts), C.byref(h)) == -1
 
+
+def test_static_scratch_entry_point_checks_before_touching_the_gpu(lib):
+    # size and pointer checks come before any HIP call, so they can be exercised without a GPU
+    import ctypes as C
+    spec = FULL_CONFIGS["C4"]()
+    g = B.Graph.from_spec(spec)
+    per_op = B.Plan(g, "unfused")
+    assert per_op.info["workspace_bytes"] > B.FS_STATIC_SCRATCH_BYTES
+    with pytest.raises(B.FsError) as e:
+        per_op.execute_static_ptrs([256] * len(spec.inputs), [256] * len(spec.outputs), 0)
+    assert e.value.code == -7 and "static array" in e.value.text
+    stitched = B.Plan(g, "auto")
+    assert 0 < stitched.info["workspace_bytes"] <= B.FS_STATIC_SCRATCH_BYTES
+    with pytest.raises(B.FsError) as e:
+        stitched.execute_static_ptrs([256, 8, 256], [256] * len(spec.outputs), 0)
+    assert e.value.code == -8
+    with pytest.raises(B.FsError) as e:
+        stitched.execute_static_ptrs([256, 0, 256], [256] * len(spec.outputs), 0)
+    assert e.value.code == -1
+    # the header's constant and the binding's agree
+    header = open(os.path.join(ROOT, "include", "fusion_stitching.h")).read()
+    assert "#define FS_STATIC_SCRATCH_BYTES (4u << 20)" in header and B.FS_STATIC_SCRATCH_BYTES == 4 << 20
