@@ -78,6 +78,27 @@ std::string stretched_row(const uint32_t (&ms)[3], const char* pre = "") {
 
 }  // namespace
 
+// online[q] = 1 where reductions q and q + 1 of the program are "rmax; acc - max; exp; rsum" (a chunked row gathers both
+// in one pass); returns the number of such pairs.  `online` may be null.
+int online_reduction_pairs(const RowProgP& p, std::vector<char>* online) {
+  int q = 0, pairs = 0;
+  bool previous = false;
+  for (int i = 0; i < p.n_instr; ++i) {
+    const ProgInstr& in = p.instr[i];
+    if (in.op != PO_RSUM && in.op != PO_RMAX && in.op != PO_RSUMSQ) continue;
+    const bool pair = in.op == PO_RMAX && i + 3 < p.n_instr && p.instr[i + 1].op == PO_SUB && p.instr[i + 1].b_kind == PK_SACC &&
+                      !(p.instr[i + 1].flags & PF_SCALAR) && p.instr[i + 2].op == PO_EXP && !(p.instr[i + 2].flags & PF_SCALAR) &&
+                      p.instr[i + 3].op == PO_RSUM && !previous;
+    if (pair) {
+      ++pairs;
+      if (online && q < (int)online->size()) (*online)[q] = 1;
+    }
+    previous = pair;
+    ++q;
+  }
+  return pairs;
+}
+
 namespace {
 // member = false: an extern "C" kernel `entry(const GenArgs a)`.  member = true: a device function
 // `entry(const GenArgs& a, uint32_t fs_block)` that a packed kernel calls for the member's range of workgroups.
@@ -107,7 +128,17 @@ struct ChunkPass {
   int reduction;      // the reduction this pass is for; the number of reductions = the last pass, with the stores
   bool last_pass, last_chunk;
   bool ended = false; // set when the pass's reduction has been emitted: nothing after it belongs to the pass
+  bool online = false;   // the pass's reduction is a row maximum whose only use is exp(acc - max) summed over the row: one
+                         // pass gathers both, the sum under a running maximum (see chunked_body)
 };
+
+// Ends a chunk's share of a pass: the running values pass through an empty asm statement.  Such statements keep their
+// order, and each chunk's kept registers pass through one before they are unpacked, so no chunk's unpacking starts
+// before the chunk before it is folded into the running values.  Without it the compiler unpacks several chunks ahead
+// to hide latency, and a row kept in registers no longer fits (it spills by hundreds of bytes per lane).
+std::string kChunkOrderPin(const char* a, const char* b) {
+  return b ? fmt("  asm volatile(\"\" : \"+v\"(%s), \"+v\"(%s));\n", a, b) : fmt("  asm volatile(\"\" : \"+v\"(%s));\n", a);
+}
 
 std::string instruction_text(const RowProgP& p, const ProgInstr& in, bool block, int n_waves, int* reduction_no, ChunkPass* cp = nullptr) {
   std::string t;
@@ -119,10 +150,22 @@ std::string instruction_text(const RowProgP& p, const ProgInstr& in, bool block,
       if (q < cp->reduction) {
         t += fmt("  sacc = red%d;\n", q);
         if (keep) t += fmt("  s%d = sacc;\n", in.dst);
+      } else if (cp->online) {
+        // the lane's running maximum m_run and the lane's sum s_run of exp(acc - m_run) over the chunks seen so far: a
+        // new chunk first raises the maximum (the sum so far is rescaled by exp(old - new), one exponential per lane and
+        // chunk), then adds its own exponentials.  Padding lanes hold -huge for the maximum and add nothing to the sum;
+        // the floor keeps the difference of two "nothing yet" maxima at zero instead of inf - inf.
+        t += "  {\n  const float m_new = fmaxf(m_run, fmaxf(row.partial<OpMax, true, false>(acc), -3.0e38f));\n";
+        t += "#pragma unroll\n  for (int j = 0; j < KV; ++j) acc[j] = fast_exp(acc[j] - m_new);\n";
+        t += "  s_run = s_run * fast_exp(m_run - m_new) + row.partial<OpSum, false, false>(acc);\n  m_run = m_new;\n  }\n";
+        t += kChunkOrderPin("m_run", "s_run");
+        ++*reduction_no;   // the sum's turn is taken as well
+        cp->ended = true;
       } else {
         const bool is_max = in.op == PO_RMAX;
         t += fmt("  part = %s::apply(part, row.partial<%s, %s, %s>(acc));\n", is_max ? "OpMax" : "OpSum", is_max ? "OpMax" : "OpSum",
                  is_max ? "true" : "false", in.op == PO_RSUMSQ ? "true" : "false");
+        t += kChunkOrderPin("part", nullptr);
         cp->ended = true;
       }
       return t;
@@ -188,6 +231,12 @@ std::string chunked_body(const RowProgP& p, const char* entry) {
   for (int i = 0; i < p.n_instr; ++i)
     if (p.instr[i].op == PO_RSUM || p.instr[i].op == PO_RMAX || p.instr[i].op == PO_RSUMSQ) is_max.push_back(p.instr[i].op == PO_RMAX);
   const int n_red = (int)is_max.size();
+  // A row maximum that is only there to keep the exponentials in range -- rmax; acc - max; exp; rsum, the core of every
+  // softmax -- does not need a pass of its own: sum_j exp(x_j - M) = sum over chunks of exp(m - M) * sum_j exp(x_j - m)
+  // for any m, so one pass gathers the maximum and the sum together (a running maximum per lane, the sum rescaled when
+  // it rises), and the pattern takes one pass over the row less.  online[q]: reductions q and q + 1 are such a pair.
+  std::vector<char> online(n_red + 1, 0);
+  online_reduction_pairs(p, &online);
   std::string s = "using namespace fsk;\n";
   s += fmt("extern \"C\" __global__ void __launch_bounds__(%u) %s(const GenArgs a) {\n", L, entry);
   s += "  const uint32_t fs_block = blockIdx.x;\n";
@@ -213,13 +262,13 @@ std::string chunked_body(const RowProgP& p, const char* entry) {
     for (int i = 0; i < p.n_full; ++i)
       s += fmt("  %s::Raw<%s> kept%d_%u;\n", c == NC - 1u ? "TailRow" : "Row", storage_type(p.full_dt[i]), i, c);
   // one chunk's share of a pass, for the row object `row` in scope; kept_chunk >= 0: that chunk stays in registers
-  auto piece = [&](int pass, bool last_chunk, int kept_chunk) {
+  auto piece = [&](int pass, bool last_chunk, int kept_chunk, bool preloaded = false) {
     std::string t;
     const bool last_pass = pass == n_red;
     for (int i = 0; i < p.n_full; ++i) {
       const bool stretched = ((p.full_bcast >> i) & 1u) != 0;
       const std::string at = stretched ? stretched_row(p.ms[i]) : std::string("(size_t)row.row_c");
-      if (kept_chunk >= 0 && pass > 0) {
+      if (kept_chunk >= 0 && (pass > 0 || preloaded)) {
         // (the compiler must not carry the unpacked form over from the pass before: that would take the registers twice)
         t += fmt("  kept%d_%d.forget_contents();\n  const auto& raw_full%d = kept%d_%d;\n", i, kept_chunk, i, i, kept_chunk);
         continue;
@@ -247,22 +296,42 @@ std::string chunked_body(const RowProgP& p, const char* entry) {
     }
     for (int i = 0; i < p.n_rscal; ++i) t += fmt("  s%d = in_rscal%d;\n", p.rscal_sreg[i], i);
     ChunkPass cp{pass, last_pass, last_chunk};
+    cp.online = !last_pass && online[pass] != 0;
     int reduction_no = 0;
     for (int i = 0; i < p.n_instr && !cp.ended; ++i) t += instruction_text(p, p.instr[i], true, n_waves, &reduction_no, &cp);
     return t;
   };
-  for (int pass = 0; pass <= n_red; ++pass) {
+  int walk = 0;   // passes emitted so far (a fused pair counts once): every other one walks the row backwards
+  for (int pass = 0; pass <= n_red; ++pass, ++walk) {
+    const bool fused = pass < n_red && online[pass] != 0;
     s += "  {\n";
-    if (pass < n_red) s += fmt("  float part = %s;\n", is_max[pass] ? "-__builtin_huge_valf()" : "0.0f");
+    if (fused) s += "  float m_run = -3.0e38f, s_run = 0.0f;\n";
+    else if (pass < n_red) s += fmt("  float part = %s;\n", is_max[pass] ? "-__builtin_huge_valf()" : "0.0f");
     // the kept chunks, one block each
     std::string in_registers;
+    // A first pass that also exponentiates (a fused maximum + sum) has more live values per chunk than one that only
+    // compares; left to itself the compiler interleaves the chunks' arithmetic and runs out of registers.  So the loads
+    // of all kept chunks are issued first, and the chunks are then worked through one after the other, each behind a
+    // scheduling barrier (a chunk's arithmetic starts when its own loads have landed).
+    const bool preload = fused && pass == 0 && kept > 0;
+    if (preload) {
+      for (uint32_t c = 0; c < kept; ++c)
+        for (int i = 0; i < p.n_full; ++i) {
+          const bool stretched = ((p.full_bcast >> i) & 1u) != 0;
+          const std::string at = stretched ? stretched_row(p.ms[i]) : std::string("(size_t)row.row_c");
+          in_registers += fmt("  {\n  const %s row(fs_block, 0, %uu);\n  kept%d_%u = row.load<%s, %s>(a.full[%d], %s);\n  }\n", c == NC - 1u ? "TailRow" : "Row",
+                              c * chunk, i, c, storage_type(p.full_dt[i]), stretched ? "false" : "true", i, at.c_str());
+        }
+      in_registers += "  __builtin_amdgcn_sched_barrier(0);\n";
+    }
     for (uint32_t c = 0; c < kept; ++c) {
       const bool is_tail = c == NC - 1u;
-      in_registers += fmt("  {\n  const %s row(fs_block, 0, %uu);\n", is_tail ? "TailRow" : "Row", c * chunk) + piece(pass, is_tail, (int)c) + "  }\n";
+      in_registers += fmt("  {\n  const %s row(fs_block, 0, %uu);\n", is_tail ? "TailRow" : "Row", c * chunk) + piece(pass, is_tail, (int)c, preload) + "  }\n";
+      if (preload) in_registers += "  __builtin_amdgcn_sched_barrier(0);\n";
     }
     // the others: whole chunks by a loop, then the row's last chunk.  Every other pass walks them backwards: it
     // starts with the chunks the pass before read last, which the caches are likeliest to hold still
-    const bool backwards = (pass & 1) != 0;
+    const bool backwards = (walk & 1) != 0;
     std::string from_memory_whole, from_memory_last;
     if (kept < NC - 1u)
       from_memory_whole = fmt("#pragma unroll 1\n  for (uint32_t chunk = %uu; chunk < %uu; ++chunk) {\n  const Row row(fs_block, 0, %s * %uu);\n",
@@ -270,7 +339,14 @@ std::string chunked_body(const RowProgP& p, const char* entry) {
                           piece(pass, false, -1) + "  }\n";
     if (kept < NC) from_memory_last = fmt("  {\n  const TailRow row(fs_block, 0, %uu);\n", (NC - 1u) * chunk) + piece(pass, true, -1) + "  }\n";
     s += backwards ? from_memory_last + from_memory_whole + in_registers : in_registers + from_memory_whole + from_memory_last;
-    if (pass < n_red) s += fmt("  red%d = Row::finish<%s>(part, slots + %d);\n", pass, is_max[pass] ? "OpMax" : "OpSum", n_waves * pass);
+    if (fused) {
+      // the lanes' maxima meet first; every lane then brings its sum to the row's maximum before the sums meet
+      s += fmt("  red%d = Row::finish<OpMax>(m_run, slots + %d);\n", pass, n_waves * pass);
+      s += fmt("  red%d = Row::finish<OpSum>(s_run * fast_exp(m_run - red%d), slots + %d);\n", pass + 1, pass, n_waves * (pass + 1));
+      ++pass;   // the sum's pass is done as well
+    } else if (pass < n_red) {
+      s += fmt("  red%d = Row::finish<%s>(part, slots + %d);\n", pass, is_max[pass] ? "OpMax" : "OpSum", n_waves * pass);
+    }
     s += "  }\n";
   }
   s += "}\n";

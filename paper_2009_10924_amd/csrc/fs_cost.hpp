@@ -25,7 +25,7 @@ struct DeviceModel {
   double launch_s = 2.2e-6;          // fixed cost of one kernel: dispatch, first load round trip, drain
   double l2_Bps = 20.0e12;           // aggregate cache bandwidth for re-read operands
   double last_level_cache_bytes = 256.0 * 1024 * 1024;   // memory-side cache in front of HBM
-  double last_level_reread = 0.85;   // time of a re-read that the memory-side cache still holds, relative to HBM (measured)
+  double last_level_reread = 0.45;   // time of a re-read that the memory-side cache still holds, relative to HBM (measured)
   double lds_Bps = 60.0e12;          // aggregate LDS bandwidth
   double barrier_s = 0.15e-6;        // one workgroup barrier incl. the LDS round trip
   double cycles_valu = 4.0;          // issue cycles of one wave-wide VALU op on a 16-lane SIMD

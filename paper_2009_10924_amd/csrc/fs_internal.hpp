@@ -170,6 +170,9 @@ std::string generated_kernel_entry(const RowProgP& p);   // fs_gen_row_<hash of 
 std::string generate_pack_kernel(const std::vector<RowProgP>& members, const std::vector<uint32_t>& blocks,
                                  std::vector<std::vector<int>>* ptr_slots, std::string* entry);
 std::string embedded_prelude();
+// Pairs of row reductions "rmax; acc - max; exp; rsum" that a row worked through in chunks gathers in one pass
+// (online[q] = 1 for the first of each pair; `online` may be null); returns their number.
+int online_reduction_pairs(const RowProgP& p, std::vector<char>* online);
 // Process-wide switch: candidates with generated kernels are offered only while it is on (default: on
 // unless the environment says FS_CODEGEN=0) and the run-time compiler is available.
 bool codegen_enabled();

@@ -942,13 +942,21 @@ void make_generated(const Compiler& c, int vec, const Shape& s, Candidate* cand)
     // outputs passing through): wide workgroups keep fewer rows in flight
     const double wgs_per_cu = std::max(1.0, std::floor(2048.0 / s.L));
     const double rows_in_flight_bytes = d.n_cu * wgs_per_cu * in_bytes / base.rows;
-    const double reread = rows_in_flight_bytes <= 0.6 * d.last_level_cache_bytes ? d.last_level_reread : 1.0;
-    gc.hbm_bytes += in_bytes * c.n_reductions * reread;
-    cand->info.bytes_moved_model += (int64_t)(in_bytes * c.n_reductions);
-    gc.valu_per_elem *= 1.0 + 0.5 * c.n_reductions;
+    // (every other pass walks the row backwards, so even a set of rows larger than the cache finds the chunks read last;
+    // measured on 128256-column rows: a re-read costs 0.35 to 0.5 of a pass from device memory while the rows in flight
+    // fit, 0.55 to 0.65 at two to four times the cache)
+    const double fit = std::min(1.0, 0.6 * d.last_level_cache_bytes / std::max(1.0, rows_in_flight_bytes));
+    const double reread = d.last_level_reread + (0.8 - d.last_level_reread) * (1.0 - fit);
+    // a row maximum that only keeps the exponentials of a sum in range shares its pass with that sum
+    const int extra_passes = c.n_reductions - online_reduction_pairs(base, nullptr);
+    gc.hbm_bytes += in_bytes * extra_passes * reread;
+    cand->info.bytes_moved_model += (int64_t)(in_bytes * extra_passes);
+    gc.valu_per_elem *= 1.0 + 0.5 * extra_passes;
     gc.trans_per_elem *= 1.0 + 0.5 * c.n_reductions;
     gc.lane_utilisation = (double)(base.cols / vec) / ((double)s.L * s.K * s.NC);
     gc.serial_tail_s += d.mem_latency_s * c.n_reductions;
+    // a first pass that gathers maximum and sum together issues the loads of every kept chunk before it works on the first
+    if (s.kept > 0 && extra_passes < c.n_reductions) gc.bytes_in_flight_per_lane *= (double)s.kept;
   }
 }
 
