@@ -429,16 +429,18 @@ fs_status fs_stream_copy(void *dst, const void *src, size_t bytes, void *hip_str
  * 128-bit vectors from each of `reads` (0..4) input streams and writes as many to each of
  * `writes` (0..2, not both 0) output streams; all loads are issued before the first store.
  * Stream r of a side starts stream_pitch_bytes * r behind the side's pointer (0 = stream_bytes:
- * the streams follow each other; a pitch that is no multiple of a large power of two keeps
- * the streams from meeting in the same memory channel at the same time).
+ * the streams follow each other; a larger pitch puts a gap between them, for experiments
+ * with the streams' relative placement -- none measured so far changed the time).
  * `src`: DEVICE, (reads - 1) * pitch + stream_bytes (may be null when reads is 0); `dst`:
  * DEVICE, likewise for writes, at least 16 bytes (a read-only probe stores nothing there unless
  * the input holds one particular bit pattern, which keeps its loads alive); stream_bytes and
  * the pitch multiples of 16, below 2^35; pointers 16-byte aligned.  What it writes is a function of the
- * inputs and the element index, of no further meaning.  Its time is the bound a stitched
+ * inputs and the element index, of no further meaning.  Its time is the reference a stitched
  * kernel with the same bytes and the same read : write mix is reported beside (Section
- * 2.2); with a small stream_bytes it gives the fixed cost of a launch of that many
- * workgroups.  Errors: FS_ERR_INVALID_ARG, FS_ERR_ALIGN, FS_ERR_SHAPE, FS_ERR_HIP.      */
+ * 2.2: traffic is what these ops cost); the read-only and write-only rates on a large
+ * size give a bound (read bytes / read rate + written bytes / write rate); with a small
+ * stream_bytes it gives the fixed cost of a launch of that many workgroups.
+ * Errors: FS_ERR_INVALID_ARG, FS_ERR_ALIGN, FS_ERR_SHAPE, FS_ERR_HIP.                    */
 fs_status fs_stream_probe(void *dst, const void *src, size_t stream_bytes, size_t stream_pitch_bytes, int32_t reads,
                           int32_t writes, int32_t vecs_per_lane, void *hip_stream);
 
