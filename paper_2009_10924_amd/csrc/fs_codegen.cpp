@@ -415,9 +415,13 @@ std::string body_with_entry(const RowProgP& p, const char* entry, bool member) {
     return t;
   };
   if (looped) {
-    // Running column sums live across the rows a lane group works through; the rows' own work is the loop body.
-    // The loop is software-pipelined: the next row's loads are issued before this row's arithmetic starts (in the
-    // last trip they re-read the last row), and the column vectors are loaded once.
+    // Running column sums live across the rows a lane group works through; the rows' own work is one round.
+    // The rounds are software-pipelined: the next row's loads are issued before this row's arithmetic starts, and the
+    // column vectors are loaded once.  The first and the last round stand outside the loop.  The counter a wave waits
+    // on counts loads and stores in issue order; at the head of a loop whose first entry comes from code that issued
+    // loads last and whose back edge comes from a round that issued its store last, the compiler has to wait for
+    // everything, the store included, in every round.  With the first round peeled both ways into the loop look
+    // alike and the wait leaves the stores in flight; the last round has no row to load ahead.
     if (!block) s += fmt("  __shared__ float colred[%d][4 * Row::PADDED_COLS];\n", p.n_colsum);
     for (int i = 0; i < p.n_colsum; ++i)
       s += fmt("  float cs%d[KV];\n#pragma unroll\n  for (int j = 0; j < KV; ++j) cs%d[j] = 0.0f;\n", i, i);
@@ -429,14 +433,16 @@ std::string body_with_entry(const RowProgP& p, const char* entry, bool member) {
     if (needs_lead) s += "  uint32_t nq1, nlead0, nlead1, nlead2;\n" + lead_of("nrow", "n", false);
     s += row_loads("nrow", "n", "auto ", "float ");
     s += col_unpack("nrow");
-    s += fmt("#pragma unroll 1\n  for (uint32_t it = 0; it < %uu; ++it) {\n", R);
+    s += "  auto round = [&](const uint32_t it, auto has_next) {\n";
     s += "  const Row row = nrow;\n";
     if (p.out_perm) s += lead_of("row", "", true);
     for (int i = 0; i < p.n_full; ++i) s += fmt("  const auto raw_full%d = nraw_full%d;\n", i, i);
     for (int i = 0; i < p.n_rscal; ++i) s += fmt("  const float in_rscal%d = nin_rscal%d;\n", i, i);
-    s += fmt("  nrow = Row(min(it + 1u, %uu) * n_row_wgs + row_wg, tile);\n", R - 1u);
+    s += "  if constexpr (decltype(has_next)::value) {\n";
+    s += "  nrow = Row((it + 1u) * n_row_wgs + row_wg, tile);\n";
     if (needs_lead) s += lead_of("nrow", "n", false);
     s += row_loads("nrow", "n", "", "");
+    s += "  }\n";
   } else {
     s += "  const Row row(fs_block);\n";
     // ---- every global load is issued before anything waits
@@ -469,7 +475,10 @@ std::string body_with_entry(const RowProgP& p, const char* entry, bool member) {
   if (looped) {
     // the next row's reductions reuse this row's LDS slots: nobody may still be reading them
     if (block && n_reductions > 0) s += "  __syncthreads();\n";
-    s += "  }\n";
+    s += "  };\n";
+    if (R > 1u) s += "  round(0u, Yes{});\n";
+    if (R > 2u) s += fmt("#pragma unroll 1\n  for (uint32_t it = 1u; it < %uu; ++it) round(it, Yes{});\n", R - 1u);
+    s += fmt("  round(%uu, No{});\n", R - 1u);
     for (int i = 0; i < p.n_colsum; ++i)
       s += fmt("  Row::colsum_flush(cs%d, %s, static_cast<float*>(a.ws) + (size_t)row_wg * %uu + %uu + tile * %uu);\n", i,
                block ? "nullptr" : fmt("colred[%d]", i).c_str(), (uint32_t)p.n_colsum * p.cols, (uint32_t)i * p.cols, p.cols / CT);

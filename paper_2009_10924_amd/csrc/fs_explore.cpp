@@ -751,7 +751,7 @@ int64_t place_buffers(const fs_graph& g, fs_program* prog, const std::vector<int
       auto it = last_read.find(r.slot);
       if (it == last_read.end() || it->second < at) last_read[r.slot] = at;
     }
-  int64_t fixed = 0;   // the plans' own workspaces: never shared, so arrival counters stay as their kernels left them
+  int64_t fixed = 0;   // the plans' own workspaces: never shared, so partial sums wait there untouched until the joint fold at the end
   for (int s = 0; s < ns; ++s) {
     const int64_t need = prog->steps[s].plan->candidates[prog->steps[s].plan->chosen].info.workspace_bytes;
     prog->steps[s].plan_ws_offset = fixed;

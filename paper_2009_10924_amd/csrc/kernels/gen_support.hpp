@@ -22,6 +22,10 @@ struct GenArgs {
   void* ws;   // partial column sums, one row per workgroup (patterns with column sums), else null
 };
 
+// Compile-time switches handed to generic lambdas of a generated kernel (`if constexpr (decltype(tag)::value)`).
+struct Yes { static constexpr bool value = true; };
+struct No { static constexpr bool value = false; };
+
 // value of `v` in lane (own lane ^ mask) of the wavefront
 __device__ __forceinline__ float xor_lane(float v, uint32_t mask) {
   const int addr = (int)(((threadIdx.x ^ mask) & 63u) << 2);
