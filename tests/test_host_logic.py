@@ -323,3 +323,21 @@ def test_static_scratch_entry_point_checks_before_touching_the_gpu(lib):
     # the header's constant and the binding's agree
     header = open(os.path.join(ROOT, "include", "fusion_stitching.h")).read()
     assert "#define FS_STATIC_SCRATCH_BYTES (4u << 20)" in header and B.FS_STATIC_SCRATCH_BYTES == 4 << 20
+
+
+def test_stream_probe_checks_its_arguments_before_touching_the_gpu(lib):
+    # every refusal below is decided on the host, before any launch
+    def code(**kw):
+        a = dict(dst=256, src=256, stream_bytes=4096, reads=2, writes=1, vecs=2, pitch=0)
+        a.update(kw)
+        try:
+            B.bind_probe(a["dst"], a["src"], a["stream_bytes"], a["reads"], a["writes"], a["vecs"], 0, a["pitch"])()
+        except B.FsError as e:
+            return e.code
+        return 0
+    assert code(dst=0) == -1 and code(src=0) == -1                       # null pointers (a source is needed when anything is read)
+    assert code(reads=5) == -1 and code(writes=3) == -1 and code(reads=0, writes=0) == -1
+    assert code(vecs=3) == -1 and code(reads=-1) == -1
+    assert code(dst=264) == -8 and code(stream_bytes=4100) == -8 and code(pitch=4104) == -8   # 16-byte rule
+    assert code(pitch=2048) == -2                                         # FS_ERR_SHAPE: the streams would overlap
+    assert code(stream_bytes=0) == 0                                      # nothing to move: no launch, no error
