@@ -233,12 +233,85 @@ def test_gelu_grad_is_derivative_of_gelu():
     np.testing.assert_allclose(_dgelu(z), fd, rtol=0, atol=1e-8)
 
 
-def test_gelu_scalar_bruteforce():
-    # independent scalar evaluation through math.erf-free route: tanh via exp
-    for v in (-3.5, -1.0, -0.1, 0.3, 1.0, 2.5):
-        u = 0.7978845608028654 * (v + 0.044715 * v ** 3)
-        th = (math.exp(u) - math.exp(-u)) / (math.exp(u) + math.exp(-u))
-        assert float(_gelu(v)) == pytest.approx(0.5 * v * (1 + th), rel=1e-13)
+def _dec_exp(x):
+    """exp by its power series in 50-digit decimal arithmetic (argument halved until small, result squared back):
+    no library routine for any transcendental is involved."""
+    from decimal import Decimal, getcontext
+    getcontext().prec = 50
+    x = Decimal(x)
+    halvings = 0
+    while abs(x) > Decimal("0.125"):
+        x /= 2
+        halvings += 1
+    term, total, n = Decimal(1), Decimal(1), 0
+    while abs(term) > Decimal(10) ** -48:
+        n += 1
+        term = term * x / n
+        total += term
+    for _ in range(halvings):
+        total *= total
+    return total
+
+
+def _dec_tanh(x):
+    from decimal import Decimal
+    e2 = _dec_exp(2 * Decimal(x))
+    return (e2 - 1) / (e2 + 1)
+
+
+def _dec_sqrt_2_over_pi():
+    """sqrt(2/pi) with pi from Machin's formula, the arctangents by their series, the root by Newton's iteration."""
+    from decimal import Decimal, getcontext
+    getcontext().prec = 50
+
+    def arctan_inv(n):
+        x = Decimal(1) / n
+        term, total, k = x, x, 0
+        while abs(term) > Decimal(10) ** -48:
+            k += 1
+            term = -term * x * x
+            total += term / (2 * k + 1)
+        return total
+    pi = 4 * (4 * arctan_inv(5) - arctan_inv(239))
+    r = Decimal(2) / pi
+    y = Decimal("0.8")
+    for _ in range(8):
+        y = (y + r / y) / 2
+    return y
+
+
+def test_series_arithmetic_reproduces_known_constants():
+    # the decimal evaluator itself against constants typed from tables (20 digits)
+    from decimal import Decimal
+    known = {"e": "2.7182818284590452354", "1/e": "0.36787944117144232160", "tanh(1)": "0.76159415595576488812",
+             "tanh(1/2)": "0.46211715726000975850", "sqrt(2/pi)": "0.79788456080286535588"}
+    got = {"e": _dec_exp(1), "1/e": _dec_exp(-1), "tanh(1)": _dec_tanh(1), "tanh(1/2)": _dec_tanh("0.5"), "sqrt(2/pi)": _dec_sqrt_2_over_pi()}
+    for name, text in known.items():
+        assert abs(got[name] - Decimal(text)) < Decimal("1e-19"), name
+
+
+def test_transcendental_ops_against_series_arithmetic():
+    """exp, tanh, sigmoid, log, tanh-GELU and its derivative of the oracle against 50-digit series arithmetic that calls
+    no library transcendental: a wrong constant (sqrt(2/pi), 0.044715), a dropped term of the derivative or a sign
+    error shows at 1e-3 or more; the bar is a few float64 ulps."""
+    from decimal import Decimal
+    c, k = _dec_sqrt_2_over_pi(), Decimal("0.044715")
+    for text in ("-5.5", "-3.5", "-1", "-0.7520", "-0.1", "0", "0.3", "1", "2.5", "6"):
+        z = Decimal(text)
+        zf = np.array([float(text)])
+        u = c * (z + k * z ** 3)
+        t = _dec_tanh(u)
+        gelu = z * (1 + t) / 2
+        grad = (1 + t) / 2 + z * (1 - t * t) / 2 * c * (1 + 3 * k * z * z)
+        # (1 + tanh u) cancels in float64 for very negative z (an ulp of tanh near -1, times |z|): an absolute bar
+        # of 2e-15 covers that, the relative one everything else
+        assert float(O.op_gelu_tanh(zf)[0]) == pytest.approx(float(gelu), rel=2e-14, abs=2e-15)
+        assert float(O.op_gelu_tanh_grad(zf)[0]) == pytest.approx(float(grad), rel=2e-14, abs=2e-15)
+        assert float(O.op_exp(zf)[0]) == pytest.approx(float(_dec_exp(z)), rel=4e-16)
+        assert float(O.op_tanh(zf)[0]) == pytest.approx(float(_dec_tanh(z)), rel=4e-16, abs=1e-300)
+        assert float(O.op_sigmoid(zf)[0]) == pytest.approx(float(1 / (1 + _dec_exp(-z))), rel=4e-16)
+        # log as the inverse of the series exponential: log(exp(z)) = z
+        assert float(O.op_log(np.array([float(_dec_exp(z))]))[0]) == pytest.approx(float(text), rel=4e-16, abs=2e-16)
 
 
 def test_colsum_golden_7x5(golden_dir):
@@ -405,8 +478,8 @@ def test_elementwise_ops_against_python_scalars():
     np.testing.assert_array_equal(O.op_square(a[0]), [2.25, 4.0, 0.0625])
     np.testing.assert_array_equal(O.op_reduce_max(a, 1)[:, 0], [1.5, 16.0])
     np.testing.assert_array_equal(O.op_reduce_mean(a, 0)[0], [2.75, 3.5, 8.125])
-    assert O.op_exp(np.array([1.0]))[0] == pytest.approx(math.e, rel=1e-15)
-    assert O.op_tanh(np.array([0.5]))[0] == pytest.approx(math.tanh(0.5), rel=1e-15)
+    assert O.op_exp(np.array([1.0]))[0] == pytest.approx(2.718281828459045, rel=1e-15)      # e and tanh(1/2) typed from tables
+    assert O.op_tanh(np.array([0.5]))[0] == pytest.approx(0.46211715726000976, rel=1e-15)
     np.testing.assert_array_equal(O.op_broadcast(b.reshape(1, 3), (2, 3)), [b, b])
 
 
