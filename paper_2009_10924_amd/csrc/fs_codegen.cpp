@@ -155,7 +155,7 @@ std::string instruction_text(const RowProgP& p, const ProgInstr& in, bool block,
         // new chunk first raises the maximum (the sum so far is rescaled by exp(old - new), one exponential per lane and
         // chunk), then adds its own exponentials.  Padding lanes hold -huge for the maximum and add nothing to the sum;
         // the floor keeps the difference of two "nothing yet" maxima at zero instead of inf - inf.
-        t += "  {\n  const float m_new = fmaxf(m_run, fmaxf(row.partial<OpMax, true, false>(acc), -3.0e38f));\n";
+        t += "  {\n  const float m_new = fmaxf(m_run, fmaxf(row.partial<OpMax, true, false>(acc), -3.4028234664e38f));\n";
         t += "#pragma unroll\n  for (int j = 0; j < KV; ++j) acc[j] = fast_exp(acc[j] - m_new);\n";
         t += "  s_run = s_run * fast_exp(m_run - m_new) + row.partial<OpSum, false, false>(acc);\n  m_run = m_new;\n  }\n";
         t += kChunkOrderPin("m_run", "s_run");
@@ -305,7 +305,7 @@ std::string chunked_body(const RowProgP& p, const char* entry) {
   for (int pass = 0; pass <= n_red; ++pass, ++walk) {
     const bool fused = pass < n_red && online[pass] != 0;
     s += "  {\n";
-    if (fused) s += "  float m_run = -3.0e38f, s_run = 0.0f;\n";
+    if (fused) s += "  float m_run = -3.4028234664e38f, s_run = 0.0f;\n";
     else if (pass < n_red) s += fmt("  float part = %s;\n", is_max[pass] ? "-__builtin_huge_valf()" : "0.0f");
     // the kept chunks, one block each
     std::string in_registers;

@@ -211,6 +211,35 @@ def test_rows_beyond_a_workgroups_registers_are_worked_through_in_chunks(rows, c
         note(f"{spec.name}: {info['kernel']} on {info['block'][0]} threads, {info['n_candidates']} shapes, worst {worst}")
 
 
+@pytest.mark.parametrize("dtype,cols", [("f32", 50257), ("bf16", 70000)])
+def test_running_maximum_pass_on_rows_built_to_break_it(dtype, cols):
+    """Softmax and log-softmax over rows in chunks gather maximum and sum in one pass under a running maximum.  Rows
+    made to stress exactly that: the maximum rising with every chunk (every chunk rescales the sum so far), falling
+    (never), sitting in the last element, a first third and a last third masked with -10000 (their terms underflow
+    against the later / earlier maximum), a range of +-30 (terms from e^-60 to 1), and a constant row."""
+    if not B.codegen_available():
+        pytest.skip("rows of this length exist as generated kernels only")
+    from workloads import log_softmax_graph, softmax_graph
+    from workloads.inputs import quantise
+    # (float32 carries |x - max| * 6e-8 of relative error into an exponential: the ranges keep that under the 1e-5 bar)
+    ramp = np.linspace(-25.0, 25.0, cols)
+    noise = np.random.default_rng(11).normal(0.0, 1.0, cols)
+    spike, head_masked, tail_masked = noise.copy(), noise.copy(), noise.copy()
+    spike[-1] = 30.0
+    head_masked[:cols // 3] = -10000.0
+    tail_masked[-(cols // 3):] = -10000.0
+    plain = [ramp, ramp[::-1], spike, np.random.default_rng(12).uniform(-30.0, 30.0, cols), np.full(cols, 3.25)]
+    # log-softmax of a masked entry is about -10000, which would set the rms floor of the whole output: masked rows
+    # go through softmax only (there they are exact zeros)
+    for make, rows in ((softmax_graph, plain + [head_masked, tail_masked]), (log_softmax_graph, plain)):
+        spec = make(len(rows), cols, dtype)
+        assert "chunks" in B.Plan(B.Graph.from_spec(spec), "auto").info["kernel"]
+        inp = {spec.inputs[0].name: quantise(np.stack(rows), dtype)}
+        ref = O.evaluate(spec, inp)
+        worst = all_candidates(spec, inp, ref, floors_for(spec, inp, ref), repeat=1, unfused=False)
+        note(f"{spec.name} on adversarial rows: worst {worst}")
+
+
 @pytest.mark.parametrize("seed", range(48))
 def test_random_row_patterns(seed):
     dtype = ("f32", "f16", "bf16")[seed % 3]
