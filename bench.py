@@ -35,14 +35,19 @@ CACHE_BYTES = 256 << 20         # Infinity Cache; rotation footprint must be >= 
 TRAFFIC_PROFILE = "profiles/stitched_kernels_hbm_traffic_pmc.md"
 
 
-def _profiled_traffic(tag: str):
+def _profiled_traffic(tag: str, kernel: str = ""):
     """HBM bytes per step measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of
     known size, summed over the step's launches).  NOT measured in this run: read from the committed counter
-    summary, whose lines `TRAFFIC_BYTES_PER_STEP <config> <kernels> <bytes>` were written from such a run."""
+    summary, whose lines `TRAFFIC_BYTES_PER_STEP <config> <kernels> <bytes>` were written from such a run.
+    None when the summary was taken on another kernel than the one this run times (`kernel`: the plan's name of
+    its stitched kernel, which starts with the profiled kernel's name less its `k_`)."""
     try:
         for line in open(os.path.join(ROOT, TRAFFIC_PROFILE)):
             parts = line.split()
             if len(parts) == 4 and parts[0] == "TRAFFIC_BYTES_PER_STEP" and parts[1] == tag:
+                profiled = parts[2].split("+")[0]
+                if kernel and not kernel.startswith(profiled[2:] if profiled.startswith("k_") else profiled):
+                    return None
                 return float(parts[3])
     except OSError:
         pass
@@ -390,7 +395,7 @@ def _row(m, tag):
     """The compact per_config row kept inside `roofline`."""
     row = {"kernel": m["kernel"], "scheme": m["scheme"], "launches": m["n_kernels"], "bytes_min": m["bytes_min"],
            "us": round(m["us"], 3), "GBps": round(m["GBps"], 1), "frac": round(m["frac_of_peak"], 4),
-           "traffic": _profiled_traffic(tag), "unfused_us": round(m["unfused_us"], 2), "unfused_launches": m["unfused_kernels"],
+           "traffic": _profiled_traffic(tag, m["kernel"]), "unfused_us": round(m["unfused_us"], 2), "unfused_launches": m["unfused_kernels"],
            "speedup_vs_unfused": round(m["speedup_vs_unfused"], 2), "launches_timed": m["launches_timed"],
            "grid": m["grid"], "block": m["block"], "vgprs": m["vgprs"], "lds_bytes": m["lds_bytes"]}
     if "probe" in m:
@@ -436,8 +441,8 @@ def main():
     achieved = bytes_min / sec_step / 1e9
 
     roofline = {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                "frac": achieved / HBM_PEAK_GBPS, "traffic": _profiled_traffic(HEADLINE),
-                "traffic_source": f"not measured in this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary {TRAFFIC_PROFILE}",
+                "frac": achieved / HBM_PEAK_GBPS, "traffic": _profiled_traffic(HEADLINE, r.info["kernel"]),
+                "traffic_source": f"not measured in this run: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE summary {TRAFFIC_PROFILE} (null where that summary was taken on another kernel)",
                 "scope": "whole step = stitched kernel + fold launch; algorithmic bytes / (event time of the timed region / steps)",
                 "algorithmic_bytes_per_step": bytes_min, "us_per_step_region": sec_step * 1e6,
                 "us_per_step_event_pair": {"avg": avg_pair * 1e6, "median": med_pair * 1e6, "min": min_pair * 1e6}}
