@@ -235,3 +235,23 @@ def test_execute_argument_errors():
     assert e.value.code == -8                                 # FS_ERR_ALIGN
     plan.execute(dev_in, dev_out, ws)                         # still works afterwards
     torch.cuda.synchronize()
+
+
+def test_degenerate_extents():
+    """Rows of one or two elements, a single row, a single head: every plan the library offers for such a shape (a
+    family's catch-all kernel, a generated kernel with single-element steps, or the per-op plan) against the oracle.
+    A softmax over one element is 1, a LayerNorm over one element is beta, a column sum over one row is the row."""
+    from tests.gpu_util import floors_for
+    from workloads import layernorm_backward_graph, rmsnorm_graph, softmax_backward_graph
+    cases = [softmax_graph(1, 1, "f32"), softmax_graph(7, 1, "f16"), softmax_graph(1, 2, "f32"), add_bias_layernorm_graph(3, 1),
+             add_bias_layernorm_graph(1, 2), bias_gelu_dbias_graph(1, 8), bias_gelu_dbias_graph(5, 1), bias_gelu_dbias_graph(1, 1),
+             transpose_chain_graph(2, 1, 3, 8), transpose_chain_graph(1, 1, 1, 4), transpose_chain_graph(3, 5, 1, 1),
+             rmsnorm_graph(1, 1), softmax_backward_graph(1, 1, "f32"), layernorm_backward_graph(1, 4), layernorm_backward_graph(2, 1)]
+    for spec in cases:
+        inp = make_inputs(spec, seed=6)
+        ref = O.evaluate(spec, inp)
+        worst = all_candidates(spec, inp, ref, floors_for(spec, inp, ref), repeat=2)
+        note(f"{spec.name}: worst {worst}")
+    one = O.evaluate(softmax_graph(7, 1, "f16"), make_inputs(softmax_graph(7, 1, "f16"), seed=6))["y"]
+    assert np.array_equal(one, np.ones_like(one))
+
