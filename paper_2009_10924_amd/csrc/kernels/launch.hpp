@@ -91,6 +91,8 @@ struct TransposeP {
   uint32_t out_stride[4];
   uint32_t tile_uq;               // vectorised tile: 16-byte units along the input's innermost axis (16 or 8); the tile is
                                   // tile_uq * vec elements along it by (256 / tile_uq) * vec along the output's innermost axis
+  uint32_t order;                 // which index neighbouring workgroups differ in: 0 the tile along the output's innermost
+                                  // axis, 1 the inner one of the two axes outside the tile
 };
 
 // ---- stitched -----------------------------------------------------------------

@@ -269,12 +269,20 @@ __global__ void __launch_bounds__(256) k_transpose_tile64(const T* __restrict__ 
   const uint32_t nq = p.out_dims[q], n3 = p.out_dims[3];
   const uint32_t tq = (nq + TQ - 1) / TQ, t3 = (n3 + T3 - 1) / T3;
   uint32_t bid = blockIdx.x;
-  const uint32_t b3 = bid % t3; bid /= t3;
-  const uint32_t bq = bid % tq; bid /= tq;
   uint32_t ax[2], na = 0;
   for (uint32_t k = 0; k < 3; ++k) if (k != q) ax[na++] = k;
-  const uint32_t cb1 = bid % p.out_dims[ax[1]];
-  const uint32_t cb0 = bid / p.out_dims[ax[1]];
+  uint32_t b3, bq, cb1, cb0;
+  if (p.order == 0) {
+    b3 = bid % t3; bid /= t3;
+    bq = bid % tq; bid /= tq;
+    cb1 = bid % p.out_dims[ax[1]];
+    cb0 = bid / p.out_dims[ax[1]];
+  } else {
+    cb1 = bid % p.out_dims[ax[1]]; bid /= p.out_dims[ax[1]];
+    b3 = bid % t3; bid /= t3;
+    bq = bid % tq;
+    cb0 = bid / tq;
+  }
   const uint32_t in_base = cb0 * p.in_stride[ax[0]] + cb1 * p.in_stride[ax[1]];
   const uint32_t out_base = cb0 * p.out_stride[ax[0]] + cb1 * p.out_stride[ax[1]];
   // load: unit (uq, u3) = columns uq*VEC.. of rows u3*VEC..; padding units are clamped to valid addresses (what
