@@ -41,7 +41,7 @@ fs_status scratch_of_current_device(void** out) {
 
 }  // namespace
 
-extern "C" fs_status fs_execute_static(const fs_plan* p, const void* const* inputs, void* const* outputs, void* hip_stream) {
+extern "C" fs_status fs_execute_static(const fs_plan* p, const void* const* inputs, void* const* outputs, void* hip_stream) try {
   fs::clear_error();
   const fs_status s = fs::check_execute_args(p, inputs, outputs, "fs_execute_static");
   if (s != FS_OK) return s;
@@ -57,4 +57,6 @@ extern "C" fs_status fs_execute_static(const fs_plan* p, const void* const* inpu
   // Nothing has to start at zero: every kernel that reads the scratch reads what a launch of the same call
   // wrote there before it (the fold reads the partial sums of the launch in front of it).
   return fs::run_launches(p, inputs, outputs, ws, hip_stream, c.launches.size());
+} catch (...) {
+  return fs::fail_caught("fs_execute_static");
 }

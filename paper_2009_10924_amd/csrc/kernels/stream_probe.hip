@@ -74,7 +74,7 @@ const void* probe_symbol(int r, int w, int k) {
 }  // namespace fsk
 
 extern "C" fs_status fs_stream_probe(void* dst, const void* src, size_t stream_bytes, size_t stream_pitch_bytes, int32_t reads,
-                                     int32_t writes, int32_t vecs_per_lane, void* hip_stream) {
+                                     int32_t writes, int32_t vecs_per_lane, void* hip_stream) try {
   fs::clear_error();
   if (!dst || (reads > 0 && !src)) return fs::fail(FS_ERR_INVALID_ARG, "fs_stream_probe: null pointer");
   const void* sym = fsk::probe_symbol(reads, writes, vecs_per_lane);
@@ -93,4 +93,6 @@ extern "C" fs_status fs_stream_probe(void* dst, const void* src, size_t stream_b
   const hipError_t e = hipLaunchKernel(sym, dim3((n_vec + per_block - 1) / per_block), dim3(256), argv, 0, static_cast<hipStream_t>(hip_stream));
   if (e != hipSuccess) return fs::fail(FS_ERR_HIP, "fs_stream_probe: %s", hipGetErrorString(e));
   return FS_OK;
+} catch (...) {
+  return fs::fail_caught("fs_stream_probe");
 }
