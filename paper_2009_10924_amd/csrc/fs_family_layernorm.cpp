@@ -162,11 +162,20 @@ bool build_layernorm(const fs_graph& g, std::vector<Candidate>* out, PackForm* p
     finish_candidate(&c, var, kc);
     out->push_back(c);
   }
+  // block shapes: T threads (whole wavefronts) x K vectors per row.  Where some shape fills its lanes exactly, the
+  // padded ones are not offered: their idle lanes still issue (clamped) loads and wait at the barriers (768 floats:
+  // 192 threads x 1 vector measures 13.2 us, 128 threads x 2 vectors with a quarter of the lanes idle 14.9 us)
+  auto block_threads = [&](int K) { return ((nvec + K - 1) / K + 63) / 64 * 64; };
+  bool exact_fill_exists = false;
   for (int K : {1, 2, 3, 4, 6, 8}) {
-    const uint32_t need = (nvec + K - 1) / K;
-    const uint32_t T = (need + 63) / 64 * 64;
+    const uint32_t T = block_threads(K);
+    exact_fill_exists = exact_fill_exists || (T >= 128 && T <= 256 && (uint64_t)T * K == nvec);
+  }
+  for (int K : {1, 2, 3, 4, 6, 8}) {
+    const uint32_t T = block_threads(K);
     if (T > 256 || T < 128) continue;   // a single wave per row is the wave variant's job
     if ((uint64_t)T * K >= 2ull * nvec) continue;
+    if (exact_fill_exists && (uint64_t)T * K != nvec) continue;
     Candidate c = make_candidate(g, "layernorm", FS_SCHEME_LDS, K_LAYERNORM_BLOCK);
     Launch& l = c.launches.front();
     LayerNormP q = p;
@@ -177,7 +186,10 @@ bool build_layernorm(const fs_graph& g, std::vector<Candidate>* out, PackForm* p
     l.args.u.layernorm = q;
     fill_ptrs(l);
     l.shape.block[0] = T;
-    const uint32_t blocks_per_cu = std::max<uint32_t>(1, 2048 / T / 2);   // fill about half the wave slots per CU with one pass
+    // about 18 wavefronts per compute unit in one pass (measured on 8192 x 768 with 192 threads per row, workgroups
+    // per CU -> us: 3 16.6, 4 14.6, 5 12.8, 6 11.9, 8 12.5, 10 13.0): fewer leave the memory pipeline idle between a
+    // workgroup's rows, more only shorten each workgroup's walk
+    const uint32_t blocks_per_cu = std::max<uint32_t>(1, (1152 + T / 2) / T);
     l.shape.grid[0] = std::min<uint32_t>(p.rows, device().n_cu * blocks_per_cu);
     c.info.lanes_per_row = (int32_t)T;
     c.info.vecs_per_lane = K;
