@@ -355,7 +355,7 @@ class Plan:
         return call
 
     def execute(self, inputs, outputs, workspace=None, stream: Optional[int] = None) -> None:
-        """inputs / outputs: torch device tensors in declaration order; workspace: a zero-initialised uint8 tensor."""
+        """inputs / outputs: torch device tensors in declaration order; workspace: a uint8 tensor (its contents on entry do not matter)."""
         import torch
         if stream is None:
             stream = torch.cuda.current_stream().cuda_stream
