@@ -255,3 +255,44 @@ def test_degenerate_extents():
     one = O.evaluate(softmax_graph(7, 1, "f16"), make_inputs(softmax_graph(7, 1, "f16"), seed=6))["y"]
     assert np.array_equal(one, np.ones_like(one))
 
+
+def test_workspace_contents_on_entry_do_not_matter():
+    """A workspace holds no counters and nothing that has to start at zero: the same plan run on a zeroed workspace and
+    on one filled with 0xFF bytes (NaN as float32) gives bit-identical outputs -- column partial sums (the gelu and
+    LayerNorm-backward families, a generated kernel with column sums), a per-op plan's intermediates, an explored
+    program with a joint fold."""
+    import torch
+    from workloads import gelu_backward_graph, transformer_block_backward_graph
+
+    def outputs_with(plan_like, spec, dev_in, fill):
+        dev_out = B.alloc_outputs(spec)
+        for t in dev_out:
+            t.view(torch.uint8).fill_(0xA5)
+        ws = plan_like.make_workspace()
+        if ws is not None:
+            ws.fill_(fill)
+        if isinstance(plan_like, B.Program):
+            stream = torch.cuda.current_stream().cuda_stream
+            plan_like.bind([t.data_ptr() for t in dev_in], [t.data_ptr() for t in dev_out], ws.data_ptr(), ws.numel(), stream)()
+        else:
+            plan_like.execute(dev_in, dev_out, ws)
+        torch.cuda.synchronize()
+        return [t.view(torch.uint8).cpu().numpy().copy() for t in dev_out]
+
+    cases = [(bias_gelu_dbias_graph(300, 1024), "auto"), (layernorm_backward_graph(130, 768, "f32"), "auto"),
+             (gelu_backward_graph(200, 512, "bf16"), "auto"), (add_bias_layernorm_graph(70, 768), "unfused")]
+    for spec, scheme in cases:
+        plan = B.Plan(B.Graph.from_spec(spec), scheme)
+        assert plan.info["workspace_bytes"] > 0, spec.name
+        inp = make_inputs(spec, seed=2)
+        dev_in = [B.to_device(inp[t.name], t.dtype) for t in spec.inputs]
+        a, b = outputs_with(plan, spec, dev_in, 0), outputs_with(plan, spec, dev_in, 0xFF)
+        assert all(np.array_equal(x, y) for x, y in zip(a, b)), (spec.name, plan.info["kernel"])
+    spec = transformer_block_backward_graph(2, 64, 4, 64, 512, "bf16")
+    prog = B.Program(B.Graph.from_spec(spec))
+    assert prog.info["workspace_bytes"] > 0
+    inp = make_inputs(spec, seed=2)
+    dev_in = [B.to_device(inp[t.name], t.dtype) for t in spec.inputs]
+    a, b = outputs_with(prog, spec, dev_in, 0), outputs_with(prog, spec, dev_in, 0xFF)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b)), "explored program"
+
