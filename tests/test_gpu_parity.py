@@ -296,3 +296,27 @@ def test_workspace_contents_on_entry_do_not_matter():
     a, b = outputs_with(prog, spec, dev_in, 0), outputs_with(prog, spec, dev_in, 0xFF)
     assert all(np.array_equal(x, y) for x, y in zip(a, b)), "explored program"
 
+
+def test_two_plans_on_two_streams_at_once():
+    """fs_execute is re-entrant for different plans: two plans with workspaces of their own, issued alternately on two
+    streams (default priority) so that their kernels overlap on the device, give what each gives alone."""
+    import torch
+    specs = [bias_gelu_dbias_graph(2048, 3072), layernorm_backward_graph(2048, 768, "f32")]
+    plans = [B.Plan(B.Graph.from_spec(s), "auto") for s in specs]
+    ins = [[B.to_device(make_inputs(s, seed=4)[t.name], t.dtype) for t in s.inputs] for s in specs]
+    wss = [p.make_workspace() for p in plans]
+
+    def run(on_streams):
+        outs = [B.alloc_outputs(s) for s in specs]
+        streams = [torch.cuda.Stream(), torch.cuda.Stream()] if on_streams else [torch.cuda.current_stream()] * 2
+        torch.cuda.synchronize()
+        for _ in range(25):
+            for k in (0, 1):
+                plans[k].execute(ins[k], outs[k], wss[k], stream=streams[k].cuda_stream)
+        torch.cuda.synchronize()
+        return [[t.view(torch.uint8).cpu().numpy().copy() for t in o] for o in outs]
+
+    alone, together = run(False), run(True)
+    for a, b, s in zip(alone, together, specs):
+        assert all(np.array_equal(x, y) for x, y in zip(a, b)), s.name
+
