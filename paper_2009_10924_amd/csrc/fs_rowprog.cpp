@@ -782,7 +782,10 @@ std::vector<Shape> enumerate_shapes(const Compiler& c, int vec, bool interpretab
   // long rows: a workgroup per row, of 256 threads, or of 512 / 1024 when that takes steps off every lane
   for (uint32_t T : {256u, 512u, 1024u}) {
     const uint32_t KB = (nvec + T - 1) / T;
-    if (KB <= max_k && 64ull * 2 < nvec && (T == 256 || nvec > (uint64_t)T)) shapes.push_back({T, (int)KB, true, true});
+    // (with column sums a workgroup walks many rows, so few workgroups are resident: there a row may also take exactly
+    // one step of 512 or 1024 lanes, which puts more wavefronts on a compute unit)
+    if (KB <= max_k && 64ull * 2 < nvec && (T == 256 || nvec > (uint64_t)T || (c.n_colsum > 0 && nvec == (uint64_t)T)))
+      shapes.push_back({T, (int)KB, true, true});
   }
   // rows beyond 1024 threads x max_k steps: chunks of a workgroup's worth of steps, a pass per row reduction
   // (also offered, on 1024 threads, to shorter rows whose pattern keeps more values than a lane has registers for).
