@@ -374,8 +374,12 @@ std::string body_with_entry(const RowProgP& p, const char* entry, bool member) {
            (uint32_t)p.lanes_per_row, block ? "true" : "false", R, p.cols);
   s += "  constexpr int KV = Row::KV;\n";
   const int n_waves = block ? p.lanes_per_row / 64 : 4;
-  if (block && n_reductions > 0) s += fmt("  __shared__ float slots[%d];\n", n_waves * n_reductions);
   const bool looped = p.n_colsum > 0;
+  // a workgroup that walks several rows alternates between two sets of reduction slots: a wave may write the next
+  // row's partial value while a slower one still reads this row's, and nobody can be two rows ahead (the next row's
+  // own barrier stands in between), so no barrier is needed at a row's end
+  if (block && n_reductions > 0)
+    s += looped ? fmt("  __shared__ float slots_all[%d];\n", 2 * n_waves * n_reductions) : fmt("  __shared__ float slots[%d];\n", n_waves * n_reductions);
   const bool needs_lead = (p.full_bcast | p.rscal_bcast | p.out_perm) != 0;
   // the row's index along the leading axes, for the row object `rv`; names carry the prefix `pre`
   auto lead_of = [&](const char* rv, const char* pre, bool declare) {
@@ -434,6 +438,7 @@ std::string body_with_entry(const RowProgP& p, const char* entry, bool member) {
     s += row_loads("nrow", "n", "auto ", "float ");
     s += col_unpack("nrow");
     s += "  auto round = [&](const uint32_t it, auto has_next) {\n";
+    if (block && n_reductions > 0) s += fmt("  float* const slots = slots_all + (it & 1u) * %du;\n", n_waves * n_reductions);
     s += "  const Row row = nrow;\n";
     if (p.out_perm) s += lead_of("row", "", true);
     for (int i = 0; i < p.n_full; ++i) s += fmt("  const auto raw_full%d = nraw_full%d;\n", i, i);
@@ -473,8 +478,6 @@ std::string body_with_entry(const RowProgP& p, const char* entry, bool member) {
   int reduction_no = 0;
   for (int i = 0; i < p.n_instr; ++i) s += instruction_text(p, p.instr[i], block, n_waves, &reduction_no);
   if (looped) {
-    // the next row's reductions reuse this row's LDS slots: nobody may still be reading them
-    if (block && n_reductions > 0) s += "  __syncthreads();\n";
     s += "  };\n";
     if (R > 1u) s += "  round(0u, Yes{});\n";
     if (R > 2u) s += fmt("#pragma unroll 1\n  for (uint32_t it = 1u; it < %uu; ++it) round(it, Yes{});\n", R - 1u);
